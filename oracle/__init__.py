@@ -1,0 +1,11 @@
+"""CPU oracle for RMSNorm forward: test infrastructure, not part of the product.
+
+Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import
+this package.  It wraps oracle/rmsnorm_oracle.cpp (plain C++17, fp64) through
+ctypes on host numpy arrays and imports nothing from the HIP package.
+"""
+from .binding import (FP32, FP16, BF16, build, decode, encode, hardware_threads,
+                      rmsnorm_oracle, rmsnorm_oracle_rstd)
+
+__all__ = ["FP32", "FP16", "BF16", "build", "decode", "encode", "hardware_threads",
+           "rmsnorm_oracle", "rmsnorm_oracle_rstd"]

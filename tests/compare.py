@@ -1,0 +1,75 @@
+"""Comparators for GPU-vs-oracle parity (numpy only; no method arithmetic).
+
+fp32: relative error against the oracle value, with exact zeros required where
+the oracle is zero.  fp16 / bf16: distance in units in the last place, measured
+on the bit patterns after mapping them to a monotone integer line on which +0
+and -0 coincide.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+FLT_MIN = float(np.finfo(np.float32).tiny)
+
+
+def ordinal16(bits: np.ndarray) -> np.ndarray:
+    """Sign-magnitude 16-bit patterns -> monotone signed integers (+0 == -0 == 0)."""
+    b = np.asarray(bits, dtype=np.uint16).astype(np.int32)
+    mag = b & 0x7FFF
+    return np.where(b & 0x8000, -mag, mag)
+
+
+def _nan_mask16(bits: np.ndarray, dtype: int) -> np.ndarray:
+    b = np.asarray(bits, dtype=np.uint16)
+    if dtype == 1:   # fp16: exponent 0x7C00, mantissa 0x03FF
+        return ((b & 0x7C00) == 0x7C00) & ((b & 0x03FF) != 0)
+    return ((b & 0x7F80) == 0x7F80) & ((b & 0x007F) != 0)
+
+
+def ulp_distance(got: np.ndarray, want: np.ndarray, dtype: int) -> np.ndarray:
+    """Elementwise ulp distance for 16-bit storage; NaNs must sit in the same places."""
+    gn, wn = _nan_mask16(got, dtype), _nan_mask16(want, dtype)
+    if not np.array_equal(gn, wn):
+        raise AssertionError("NaN positions differ between result and oracle")
+    d = np.abs(ordinal16(got) - ordinal16(want))
+    d[gn] = 0
+    return d
+
+
+def max_rel_err_fp32(got: np.ndarray, want: np.ndarray) -> float:
+    g = np.asarray(got, dtype=np.float32).astype(np.float64)
+    o = np.asarray(want, dtype=np.float32).astype(np.float64)
+    gn, on = np.isnan(g), np.isnan(o)
+    if not np.array_equal(gn, on):
+        raise AssertionError("NaN positions differ between result and oracle")
+    zero = (o == 0.0) & ~on
+    if np.any(g[zero] != 0.0):
+        raise AssertionError("result is non-zero where the oracle is exactly zero")
+    ok = ~on & ~zero
+    if not ok.any():
+        return 0.0
+    return float(np.max(np.abs(g[ok] - o[ok]) / np.maximum(np.abs(o[ok]), FLT_MIN)))
+
+
+# Tolerances of the benchmark spec: fp32 max rel err <= 1e-5; bf16 <= 1 ulp
+# after rounding; fp16 <= 2 ulp.
+TOL_FP32_REL = 1e-5
+TOL_ULP = {1: 2, 2: 1}
+
+
+def check_parity(got: np.ndarray, want: np.ndarray, dtype: int, what: str = "") -> dict:
+    """Asserts the stated tolerance; returns the measured error statistics."""
+    got = np.asarray(got)
+    want = np.asarray(want)
+    assert got.shape == want.shape, f"{what}: shape {got.shape} vs {want.shape}"
+    if dtype == 0:
+        err = max_rel_err_fp32(got, want)
+        assert err <= TOL_FP32_REL, f"{what}: fp32 max rel err {err:.3e} > {TOL_FP32_REL}"
+        return {"max_rel_err": err}
+    d = ulp_distance(got, want, dtype)
+    worst = int(d.max()) if d.size else 0
+    frac = float(np.count_nonzero(d)) / max(d.size, 1)
+    assert worst <= TOL_ULP[dtype], (
+        f"{what}: max ulp distance {worst} > {TOL_ULP[dtype]} "
+        f"(first at flat index {int(np.argmax(d))})")
+    return {"max_ulp": worst, "frac_off": frac}
