@@ -1,0 +1,118 @@
+/*
+ * rmsnorm.h - C ABI of the MI355X (gfx950) row-wise RMSNorm forward library.
+ *
+ * The operation is the "rmsnorm" row of the paper's "Supported kernel types"
+ * table (memory-bound, measured in GB/s) and the kernel of its headline result
+ * in Section 7.1 "Kernel Performance": one fused pass that reads each row once,
+ * normalises it by its root mean square and multiplies by the weight in the
+ * epilogue (the fusion Section 7.3 credits for saving a round trip to memory):
+ *
+ *     y[i, j] = x[i, j] * rsqrt( mean_j( x[i, :]^2 ) + eps ) * w[j]
+ *
+ * Inputs are widened exactly to fp32, the sum of squares and both products are
+ * carried in fp32, and the result is rounded once (nearest-even) to the
+ * storage type.  Domain: finite inputs whose row sum of squares stays below
+ * FLT_MAX; NaN and infinity propagate by IEEE rules.
+ *
+ * Conventions for every entry point:
+ *  - All tensor pointers are DEVICE pointers owned by the caller.  The library
+ *    never allocates, frees, copies or synchronises; a call enqueues work on
+ *    `stream` and returns at once.  Buffers must stay alive until that work
+ *    has run.
+ *  - x and y are M x N, row-major, leading dimension N (no stride argument);
+ *    w has N elements.  x, w and y share one storage type `dtype`.
+ *  - Pointers need only the alignment of their element type.  Rows whose
+ *    start is 16-byte aligned (16-byte aligned bases and N * sizeof(dtype) a
+ *    multiple of 16) take the vectorised kernels; anything else takes a slower
+ *    element-wise kernel.  Neither case is an error.
+ *  - y == x (exactly in place) is allowed; any other overlap of y with x or w
+ *    is undefined.
+ *  - Calls return RMSNORM_OK or a negative rmsnorm_status; nothing throws or
+ *    aborts.  On RMSNORM_ERR_INVALID_ARG and RMSNORM_ERR_UNSUPPORTED nothing
+ *    was launched.
+ *  - Results are bit-identical from run to run for a given (shape, dtype,
+ *    alignment, variant): reductions have a fixed order and use no atomics.
+ */
+#ifndef RMSNORM_H_
+#define RMSNORM_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  RMSNORM_DTYPE_FP32 = 0, /* IEEE binary32 */
+  RMSNORM_DTYPE_FP16 = 1, /* IEEE binary16 */
+  RMSNORM_DTYPE_BF16 = 2  /* bfloat16: upper half of a binary32 */
+} rmsnorm_dtype;
+
+typedef enum {
+  RMSNORM_OK = 0,
+  RMSNORM_ERR_INVALID_ARG = -1, /* null pointer, M < 0, N <= 0, bad dtype, eps < 0 or NaN */
+  RMSNORM_ERR_UNSUPPORTED = -2, /* the forced variant cannot run this shape or alignment */
+  RMSNORM_ERR_LAUNCH = -3       /* the HIP runtime refused the launch */
+} rmsnorm_status;
+
+typedef enum {
+  RMSNORM_VARIANT_AUTO = 0,    /* dispatch on (dtype, N, alignment) */
+  RMSNORM_VARIANT_WAVE = 1,    /* one 64-lane wavefront per row, row held in registers */
+  RMSNORM_VARIANT_BLOCK = 2,   /* one workgroup per row, cross-wave reduction in LDS */
+  RMSNORM_VARIANT_GENERIC = 3  /* element-wise, any alignment, any N; reads x twice */
+} rmsnorm_variant;
+
+/*
+ * RMSNorm forward (the "rmsnorm" kernel of the paper's kernel table; formula
+ * above).
+ *   x      device, M*N elements of `dtype`, read once
+ *   w      device, N elements of `dtype`
+ *   y      device, M*N elements of `dtype`, written once
+ *   M, N   rows and row length; M == 0 is a successful no-op; N must be >= 1
+ *   eps    added to the mean of squares inside the root; must be >= 0
+ *   dtype  an rmsnorm_dtype
+ *   stream a hipStream_t passed as void*; NULL is the default stream
+ */
+int rmsnorm_fwd(const void* x, const void* w, void* y, int64_t M, int64_t N,
+                float eps, int dtype, void* stream);
+
+/*
+ * Same operation with the kernel choice forced (tests and benchmarks use this
+ * to run every kernel on every shape it supports).  `variant` is an
+ * rmsnorm_variant.  RMSNORM_ERR_UNSUPPORTED if that kernel cannot take the
+ * shape: WAVE needs 16-byte aligned rows of at most rmsnorm_wave_max_n(dtype)
+ * elements, BLOCK needs 16-byte aligned rows of at most
+ * rmsnorm_block_max_n(dtype) elements, GENERIC takes everything.
+ */
+int rmsnorm_fwd_variant(const void* x, const void* w, void* y, int64_t M, int64_t N,
+                        float eps, int dtype, void* stream, int variant);
+
+/*
+ * Which kernel RMSNORM_VARIANT_AUTO would pick for this call (an
+ * rmsnorm_variant), without launching anything; a negative rmsnorm_status for
+ * arguments rmsnorm_fwd would reject.  Only pointer alignment is inspected.
+ */
+int rmsnorm_select_variant(const void* x, const void* w, const void* y, int64_t M,
+                           int64_t N, int dtype);
+
+/* Largest N the register-resident kernels accept for `dtype`; 0 for a bad dtype. */
+int64_t rmsnorm_wave_max_n(int dtype);
+int64_t rmsnorm_block_max_n(int dtype);
+
+/*
+ * Plain device-to-device streaming copy of `bytes` bytes (a multiple of 16,
+ * both pointers 16-byte aligned) with the same 128-bit access pattern as the
+ * RMSNorm kernels.  A measurement aid: its known traffic calibrates the
+ * FETCH_SIZE / WRITE_SIZE hardware counters and gives the practical bandwidth
+ * ceiling that the roofline fraction is read against.
+ */
+int rmsnorm_calib_copy(const void* src, void* dst, int64_t bytes, void* stream);
+
+/* Static, human-readable text for a status code. */
+const char* rmsnorm_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+
+#endif /* RMSNORM_H_ */

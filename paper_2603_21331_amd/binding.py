@@ -1,0 +1,158 @@
+"""Thin Python binding of the C ABI in include/rmsnorm.h.
+
+Argument marshalling only: tensors become device pointers, the current torch
+stream becomes the hipStream_t, and shapes are checked against what the call
+claims so that a kernel is never launched on buffers smaller than its grid
+assumes.  Every arithmetic step runs in the HIP kernels.  There is no CPU or
+eager fallback: if the library cannot be loaded, or a call fails, this raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+from . import build as _build
+
+RMSNORM_DTYPE_FP32 = 0
+RMSNORM_DTYPE_FP16 = 1
+RMSNORM_DTYPE_BF16 = 2
+
+RMSNORM_OK = 0
+RMSNORM_ERR_INVALID_ARG = -1
+RMSNORM_ERR_UNSUPPORTED = -2
+RMSNORM_ERR_LAUNCH = -3
+
+RMSNORM_VARIANT_AUTO = 0
+RMSNORM_VARIANT_WAVE = 1
+RMSNORM_VARIANT_BLOCK = 2
+RMSNORM_VARIANT_GENERIC = 3
+
+VARIANT_NAMES = {0: "auto", 1: "wave", 2: "block", 3: "generic"}
+
+_lib = None
+
+
+class RmsnormError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"rmsnorm: {text} (status {status})")
+        self.status = status
+
+
+def library_path() -> str:
+    return _build.LIB_PATH
+
+
+def load() -> ctypes.CDLL:
+    """Loads librmsnorm_hip.so, building it first only if no built library exists."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB_PATH):
+        _build.build()
+    lib = ctypes.CDLL(_build.LIB_PATH)
+    vp, i64, i32, f32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_float
+    lib.rmsnorm_fwd.argtypes = [vp, vp, vp, i64, i64, f32, i32, vp]
+    lib.rmsnorm_fwd.restype = i32
+    lib.rmsnorm_fwd_variant.argtypes = [vp, vp, vp, i64, i64, f32, i32, vp, i32]
+    lib.rmsnorm_fwd_variant.restype = i32
+    lib.rmsnorm_select_variant.argtypes = [vp, vp, vp, i64, i64, i32]
+    lib.rmsnorm_select_variant.restype = i32
+    lib.rmsnorm_wave_max_n.argtypes = [i32]
+    lib.rmsnorm_wave_max_n.restype = i64
+    lib.rmsnorm_block_max_n.argtypes = [i32]
+    lib.rmsnorm_block_max_n.restype = i64
+    lib.rmsnorm_calib_copy.argtypes = [vp, vp, i64, vp]
+    lib.rmsnorm_calib_copy.restype = i32
+    lib.rmsnorm_status_string.argtypes = [i32]
+    lib.rmsnorm_status_string.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def rmsnorm_status_string(status: int) -> str:
+    return load().rmsnorm_status_string(int(status)).decode()
+
+
+def _check(status: int) -> None:
+    if status != RMSNORM_OK:
+        raise RmsnormError(status, rmsnorm_status_string(status))
+
+
+def dtype_code(t) -> int:
+    import torch
+    code = {torch.float32: RMSNORM_DTYPE_FP32, torch.float16: RMSNORM_DTYPE_FP16,
+            torch.bfloat16: RMSNORM_DTYPE_BF16}.get(t.dtype)
+    if code is None:
+        raise TypeError(f"rmsnorm: unsupported tensor dtype {t.dtype}")
+    return code
+
+
+def _marshal(x, w, y):
+    """Checks the tensors against the ABI's layout rules; returns (M, N, dtype, stream)."""
+    import torch
+    if x.dim() != 2:
+        raise ValueError(f"rmsnorm: x must be 2-D (M, N), got shape {tuple(x.shape)}")
+    M, N = x.shape
+    for name, t in (("x", x), ("w", w), ("y", y)):
+        if not t.is_cuda:
+            raise ValueError(f"rmsnorm: {name} must live in device memory")
+        if not t.is_contiguous():
+            raise ValueError(f"rmsnorm: {name} must be contiguous (leading dimension N)")
+        if t.dtype != x.dtype or t.device != x.device:
+            raise ValueError(f"rmsnorm: {name} must match x in dtype and device")
+    if tuple(w.shape) != (N,):
+        raise ValueError(f"rmsnorm: w must have shape ({N},), got {tuple(w.shape)}")
+    if tuple(y.shape) != (M, N):
+        raise ValueError(f"rmsnorm: y must have shape {(M, N)}, got {tuple(y.shape)}")
+    stream = torch.cuda.current_stream(x.device).cuda_stream
+    return M, N, dtype_code(x), stream
+
+
+def rmsnorm_fwd(x, w, eps: float, y=None):
+    """y = x * rsqrt(mean(x^2, -1) + eps) * w on the current stream; returns y."""
+    return rmsnorm_fwd_variant(x, w, eps, RMSNORM_VARIANT_AUTO, y)
+
+
+def rmsnorm_fwd_variant(x, w, eps: float, variant: int, y=None):
+    import torch
+    lib = load()
+    if y is None:
+        y = torch.empty_like(x)
+    M, N, code, stream = _marshal(x, w, y)
+    with torch.cuda.device(x.device):
+        if variant == RMSNORM_VARIANT_AUTO:
+            rc = lib.rmsnorm_fwd(x.data_ptr(), w.data_ptr(), y.data_ptr(), M, N, eps, code, stream)
+        else:
+            rc = lib.rmsnorm_fwd_variant(x.data_ptr(), w.data_ptr(), y.data_ptr(), M, N, eps,
+                                         code, stream, int(variant))
+    _check(rc)
+    return y
+
+
+def rmsnorm_select_variant(x, w, y) -> int:
+    M, N, code, _ = _marshal(x, w, y)
+    rc = load().rmsnorm_select_variant(x.data_ptr(), w.data_ptr(), y.data_ptr(), M, N, code)
+    if rc < 0:
+        _check(rc)
+    return rc
+
+
+def rmsnorm_wave_max_n(dtype: int) -> int:
+    return int(load().rmsnorm_wave_max_n(int(dtype)))
+
+
+def rmsnorm_block_max_n(dtype: int) -> int:
+    return int(load().rmsnorm_block_max_n(int(dtype)))
+
+
+def rmsnorm_calib_copy(src, dst) -> None:
+    """dst <- src, byte for byte, with the library's streaming copy kernel."""
+    import torch
+    if not (src.is_cuda and dst.is_cuda and src.is_contiguous() and dst.is_contiguous()):
+        raise ValueError("rmsnorm_calib_copy: contiguous device tensors required")
+    nbytes = src.numel() * src.element_size()
+    if nbytes != dst.numel() * dst.element_size():
+        raise ValueError("rmsnorm_calib_copy: size mismatch")
+    stream = torch.cuda.current_stream(src.device).cuda_stream
+    with torch.cuda.device(src.device):
+        _check(load().rmsnorm_calib_copy(src.data_ptr(), dst.data_ptr(), nbytes, stream))

@@ -1,0 +1,118 @@
+// 128-bit global memory access and storage-type conversion for gfx950.
+//
+// Every row is moved as 16-byte vectors: one global_load_dwordx4 /
+// global_store_dwordx4 per lane per chunk, so a 64-lane wavefront touches one
+// contiguous 1 KiB span per instruction.  The paper's CUDA starters use the
+// same idea at their hardware's width ("vectorized loads (float4, half2)",
+// Section 5); here the unit is the CDNA4 dwordx4 access.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace rms {
+
+enum : int { kFp32 = 0, kFp16 = 1, kBf16 = 2 };
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+// Streaming accesses carry the non-temporal hint: x and y are touched exactly
+// once, so keeping them in L2 / Infinity Cache only evicts the weight vector.
+template <bool NT>
+__device__ __forceinline__ u32x4 load_vec(const u32x4* p) {
+  if constexpr (NT) return __builtin_nontemporal_load(p);
+  else return *p;
+}
+
+template <bool NT>
+__device__ __forceinline__ void store_vec(u32x4* p, u32x4 v) {
+  if constexpr (NT) __builtin_nontemporal_store(v, p);
+  else *p = v;
+}
+
+__device__ __forceinline__ float as_f32(uint32_t u) { return __builtin_bit_cast(float, u); }
+__device__ __forceinline__ uint32_t as_u32(float f) { return __builtin_bit_cast(uint32_t, f); }
+
+// Storage traits.  VEC = elements per 16-byte vector.  unpack widens exactly to
+// fp32; pack rounds to nearest-even with the hardware converters
+// (v_cvt_pk_bf16_f32 / v_cvt_pk_f16_f32 on gfx950), which also give the IEEE
+// results for overflow, subnormals and NaN.
+template <int DT> struct Storage;
+
+template <> struct Storage<kFp32> {
+  static constexpr int kVec = 4;
+  static constexpr int kBytes = 4;
+  __device__ static __forceinline__ void unpack(u32x4 v, float (&f)[4]) {
+    f[0] = as_f32(v.x); f[1] = as_f32(v.y); f[2] = as_f32(v.z); f[3] = as_f32(v.w);
+  }
+  __device__ static __forceinline__ u32x4 pack(const float (&f)[4]) {
+    u32x4 v = {as_u32(f[0]), as_u32(f[1]), as_u32(f[2]), as_u32(f[3])};
+    return v;
+  }
+  __device__ static __forceinline__ float load_one(const void* p, int64_t i) {
+    return static_cast<const float*>(p)[i];
+  }
+  __device__ static __forceinline__ void store_one(void* p, int64_t i, float f) {
+    static_cast<float*>(p)[i] = f;
+  }
+};
+
+template <> struct Storage<kBf16> {
+  static constexpr int kVec = 8;
+  static constexpr int kBytes = 2;
+  __device__ static __forceinline__ void unpack(u32x4 v, float (&f)[8]) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      f[2 * k] = as_f32(v[k] << 16);            // a bf16 is the top half of an fp32
+      f[2 * k + 1] = as_f32(v[k] & 0xFFFF0000u);
+    }
+  }
+  __device__ static __forceinline__ u32x4 pack(const float (&f)[8]) {
+    u32x4 v;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      f32x2 p = {f[2 * k], f[2 * k + 1]};
+      v[k] = __builtin_bit_cast(uint32_t, __builtin_convertvector(p, bf16x2));
+    }
+    return v;
+  }
+  __device__ static __forceinline__ float load_one(const void* p, int64_t i) {
+    return as_f32(static_cast<uint32_t>(static_cast<const uint16_t*>(p)[i]) << 16);
+  }
+  __device__ static __forceinline__ void store_one(void* p, int64_t i, float f) {
+    static_cast<uint16_t*>(p)[i] = __builtin_bit_cast(uint16_t, static_cast<__bf16>(f));
+  }
+};
+
+template <> struct Storage<kFp16> {
+  static constexpr int kVec = 8;
+  static constexpr int kBytes = 2;
+  __device__ static __forceinline__ void unpack(u32x4 v, float (&f)[8]) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      f32x2 p = __builtin_convertvector(__builtin_bit_cast(f16x2, v[k]), f32x2);
+      f[2 * k] = p.x;
+      f[2 * k + 1] = p.y;
+    }
+  }
+  __device__ static __forceinline__ u32x4 pack(const float (&f)[8]) {
+    u32x4 v;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      f32x2 p = {f[2 * k], f[2 * k + 1]};
+      v[k] = __builtin_bit_cast(uint32_t, __builtin_convertvector(p, f16x2));
+    }
+    return v;
+  }
+  __device__ static __forceinline__ float load_one(const void* p, int64_t i) {
+    return static_cast<float>(static_cast<const _Float16*>(p)[i]);
+  }
+  __device__ static __forceinline__ void store_one(void* p, int64_t i, float f) {
+    static_cast<_Float16*>(p)[i] = static_cast<_Float16>(f);
+  }
+};
+
+}  // namespace rms

@@ -1,0 +1,41 @@
+// Sum over the 64 lanes of a wavefront, result in every lane.
+//
+// The paper's starter uses a "warp shuffle cascade" (kernel table, row rmsnorm)
+// built on 32-lane shuffles; the CDNA4 counterpart is the data-parallel
+// primitive (DPP) operand modifier, which lets a v_add_f32 read a neighbouring
+// lane directly, with no LDS traffic.  The order of additions is fixed, and
+// because a + b == b + a bit for bit, both partners of every exchange hold the
+// same value, so all 64 lanes end with one identical total and the result is
+// reproducible from run to run.
+//
+// Must be called with all 64 lanes active.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+namespace rms {
+
+template <int CTRL>
+__device__ __forceinline__ float add_dpp(float v) {
+  const int moved = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL,
+                                                0xF, 0xF, false);
+  return v + __builtin_bit_cast(float, moved);
+}
+
+__device__ __forceinline__ float read_lane(float v, int lane) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+  v = add_dpp<0xB1>(v);   // quad_perm [1,0,3,2]: lane ^ 1
+  v = add_dpp<0x4E>(v);   // quad_perm [2,3,0,1]: lane ^ 2      -> sum of each quad
+  v = add_dpp<0x141>(v);  // row_half_mirror: lane i <-> 7 - i  -> sum of each 8
+  v = add_dpp<0x140>(v);  // row_mirror: lane i <-> 15 - i      -> sum of each 16-lane row
+  const float r0 = read_lane(v, 0);
+  const float r1 = read_lane(v, 16);
+  const float r2 = read_lane(v, 32);
+  const float r3 = read_lane(v, 48);
+  return (r0 + r1) + (r2 + r3);
+}
+
+}  // namespace rms

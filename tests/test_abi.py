@@ -1,0 +1,127 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every
+symbol the header declares, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2603_21331_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "rmsnorm.h")
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(rmsnorm_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_declares_the_expected_entry_points():
+    names = declared_functions()
+    assert "rmsnorm_fwd" in names and "rmsnorm_fwd_variant" in names
+    assert "rmsnorm_status_string" in names
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    lib = binding.load()
+    for name in declared_functions():
+        assert hasattr(lib, name), f"{name} is declared in rmsnorm.h but not exported"
+
+
+def test_binding_has_the_same_names_as_the_header():
+    for name in declared_functions():
+        assert hasattr(binding, name), f"binding lacks {name}"
+
+
+def test_enum_values_match_the_header():
+    text = open(HEADER).read()
+    for name, value in re.findall(r"\b(RMSNORM_[A-Z0-9_]+)\s*=\s*(-?\d+)", text):
+        assert getattr(binding, name) == int(value), name
+
+
+def test_status_strings():
+    assert binding.rmsnorm_status_string(0) == "ok"
+    for s in (-1, -2, -3, 77):
+        assert binding.rmsnorm_status_string(s)
+
+
+def test_limits():
+    assert binding.rmsnorm_wave_max_n(binding.RMSNORM_DTYPE_BF16) == 8192
+    assert binding.rmsnorm_wave_max_n(binding.RMSNORM_DTYPE_FP16) == 8192
+    assert binding.rmsnorm_wave_max_n(binding.RMSNORM_DTYPE_FP32) == 8192
+    assert binding.rmsnorm_block_max_n(binding.RMSNORM_DTYPE_BF16) >= 32768
+    assert binding.rmsnorm_wave_max_n(9) == 0 and binding.rmsnorm_block_max_n(-1) == 0
+
+
+# The calls below never reach the device: argument checks come first, and the
+# pointers are fake addresses that are never dereferenced on the host.
+P = 0x10000
+
+
+@pytest.mark.parametrize("args", [
+    dict(x=0),                       # null x
+    dict(w=0),                       # null w
+    dict(y=0),                       # null y
+    dict(M=-1),
+    dict(N=0),
+    dict(N=-5),
+    dict(dtype=3),
+    dict(dtype=-1),
+    dict(eps=-1e-6),
+    dict(eps=float("nan")),
+    dict(x=P + 1, dtype=1),          # not element-aligned
+    dict(y=P + 2, dtype=0),
+    dict(M=1 << 40, N=1 << 40),      # M * N overflows
+])
+def test_invalid_arguments_are_rejected_without_a_launch(args):
+    lib = binding.load()
+    a = dict(x=P, w=P + 4096, y=P + 8192, M=4, N=8, eps=1e-6, dtype=2)
+    a.update(args)
+    rc = lib.rmsnorm_fwd(a["x"], a["w"], a["y"], a["M"], a["N"], a["eps"], a["dtype"], None)
+    assert rc == binding.RMSNORM_ERR_INVALID_ARG
+    rc = lib.rmsnorm_fwd_variant(a["x"], a["w"], a["y"], a["M"], a["N"], a["eps"], a["dtype"],
+                                 None, binding.RMSNORM_VARIANT_GENERIC)
+    assert rc == binding.RMSNORM_ERR_INVALID_ARG
+
+
+def test_empty_batch_is_a_successful_no_op():
+    lib = binding.load()
+    assert lib.rmsnorm_fwd(None, None, None, 0, 16, 1e-6, 2, None) == binding.RMSNORM_OK
+
+
+def test_unknown_variant_and_unsupported_shapes():
+    lib = binding.load()
+    assert lib.rmsnorm_fwd_variant(P, P + 4096, P + 8192, 4, 8, 1e-6, 2, None, 9) == \
+        binding.RMSNORM_ERR_INVALID_ARG
+    # a row of 7 bf16 elements is not 16-byte aligned: the vector kernels must refuse
+    for v in (binding.RMSNORM_VARIANT_WAVE, binding.RMSNORM_VARIANT_BLOCK):
+        assert lib.rmsnorm_fwd_variant(P, P + 4096, P + 8192, 4, 7, 1e-6, 2, None, v) == \
+            binding.RMSNORM_ERR_UNSUPPORTED
+    # too long for one wavefront's registers
+    assert lib.rmsnorm_fwd_variant(P, P + (1 << 20), P + (2 << 20), 4, 8200, 1e-6, 2, None,
+                                   binding.RMSNORM_VARIANT_WAVE) == binding.RMSNORM_ERR_UNSUPPORTED
+    # misaligned base pointer
+    assert lib.rmsnorm_fwd_variant(P + 2, P + 4096, P + 8192, 4, 8, 1e-6, 2, None,
+                                   binding.RMSNORM_VARIANT_WAVE) == binding.RMSNORM_ERR_UNSUPPORTED
+
+
+def test_dispatch_choice_is_visible_without_a_launch():
+    lib = binding.load()
+    sel = lib.rmsnorm_select_variant
+    assert sel(P, P + 65536, P + 131072, 16, 8192, 2) == binding.RMSNORM_VARIANT_WAVE
+    assert sel(P, P + 65536, P + 131072, 16, 768, 1) == binding.RMSNORM_VARIANT_WAVE
+    assert sel(P, P + 65536, P + 131072, 16, 13824, 1) == binding.RMSNORM_VARIANT_BLOCK
+    assert sel(P, P + 65536, P + 131072, 16, 1023, 1) == binding.RMSNORM_VARIANT_GENERIC
+    assert sel(P + 2, P + 65536, P + 131072, 16, 1024, 1) == binding.RMSNORM_VARIANT_GENERIC
+    assert sel(P, P + 65536, P + 131072, 16, 1 << 20, 2) == binding.RMSNORM_VARIANT_GENERIC
+    assert sel(P, P + 65536, P + 131072, 16, 0, 2) == binding.RMSNORM_ERR_INVALID_ARG
+
+
+def test_calib_copy_argument_checks():
+    lib = binding.load()
+    assert lib.rmsnorm_calib_copy(P, P + 4096, 0, None) == binding.RMSNORM_OK
+    assert lib.rmsnorm_calib_copy(P, P + 4096, 24, None) == binding.RMSNORM_ERR_INVALID_ARG
+    assert lib.rmsnorm_calib_copy(P + 4, P + 4096, 32, None) == binding.RMSNORM_ERR_INVALID_ARG
+    assert lib.rmsnorm_calib_copy(None, P, 32, None) == binding.RMSNORM_ERR_INVALID_ARG
