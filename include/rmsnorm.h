@@ -58,7 +58,8 @@ typedef enum {
 typedef enum {
   RMSNORM_VARIANT_AUTO = 0,    /* dispatch on (dtype, N, alignment) */
   RMSNORM_VARIANT_WAVE = 1,    /* one 64-lane wavefront per row, row held in registers */
-  RMSNORM_VARIANT_BLOCK = 2,   /* one workgroup per row, cross-wave reduction in LDS */
+  RMSNORM_VARIANT_BLOCK = 2,   /* one workgroup of 128..1024 threads per row, row held in
+                                  registers, cross-wave reduction in LDS */
   RMSNORM_VARIANT_GENERIC = 3  /* element-wise, any alignment, any N; reads x twice */
 } rmsnorm_variant;
 
@@ -86,6 +87,29 @@ int rmsnorm_fwd(const void* x, const void* w, void* y, int64_t M, int64_t N,
  */
 int rmsnorm_fwd_variant(const void* x, const void* w, void* y, int64_t M, int64_t N,
                         float eps, int dtype, void* stream, int variant);
+
+/*
+ * Same operation with the number of threads that share one row forced: the
+ * block-size axis that the paper's optimisation playbook sweeps first
+ * (Section 3.3, tier 1; Section 7.3 reports it as the largest single gain for
+ * RMSNorm).  threads_per_row is 64 (one wavefront per row), 128, 256, 512 or
+ * 1024 (one workgroup per row); anything else is RMSNORM_ERR_INVALID_ARG.
+ * Each thread then holds ceil(N * sizeof(dtype) / 16 / threads_per_row)
+ * 16-byte chunks of the row in registers; RMSNORM_ERR_UNSUPPORTED if that
+ * exceeds what is built for the thread count (64: 16 chunks, 32 for fp32;
+ * 128, 256, 512: 8 chunks; 1024: 16 chunks) or if the rows are not 16-byte
+ * aligned.  Tests use it to run every instantiation; tuning sweeps use it to
+ * check the automatic choice.
+ */
+int rmsnorm_fwd_tuned(const void* x, const void* w, void* y, int64_t M, int64_t N,
+                      float eps, int dtype, void* stream, int threads_per_row);
+
+/*
+ * The threads_per_row that RMSNORM_VARIANT_AUTO uses for 16-byte aligned rows
+ * of N elements: 0 if such rows go to the element-wise kernel, a negative
+ * rmsnorm_status for a bad dtype or N <= 0.
+ */
+int rmsnorm_auto_threads_per_row(int64_t N, int dtype);
 
 /*
  * Which kernel RMSNORM_VARIANT_AUTO would pick for this call (an

@@ -55,6 +55,10 @@ def load() -> ctypes.CDLL:
     lib.rmsnorm_fwd.restype = i32
     lib.rmsnorm_fwd_variant.argtypes = [vp, vp, vp, i64, i64, f32, i32, vp, i32]
     lib.rmsnorm_fwd_variant.restype = i32
+    lib.rmsnorm_fwd_tuned.argtypes = [vp, vp, vp, i64, i64, f32, i32, vp, i32]
+    lib.rmsnorm_fwd_tuned.restype = i32
+    lib.rmsnorm_auto_threads_per_row.argtypes = [i64, i32]
+    lib.rmsnorm_auto_threads_per_row.restype = i32
     lib.rmsnorm_select_variant.argtypes = [vp, vp, vp, i64, i64, i32]
     lib.rmsnorm_select_variant.restype = i32
     lib.rmsnorm_wave_max_n.argtypes = [i32]
@@ -129,6 +133,27 @@ def rmsnorm_fwd_variant(x, w, eps: float, variant: int, y=None):
     return y
 
 
+def rmsnorm_fwd_tuned(x, w, eps: float, threads_per_row: int, y=None):
+    """rmsnorm_fwd with the number of threads sharing one row forced (64 .. 1024)."""
+    import torch
+    lib = load()
+    if y is None:
+        y = torch.empty_like(x)
+    M, N, code, stream = _marshal(x, w, y)
+    with torch.cuda.device(x.device):
+        rc = lib.rmsnorm_fwd_tuned(x.data_ptr(), w.data_ptr(), y.data_ptr(), M, N, eps, code,
+                                   stream, int(threads_per_row))
+    _check(rc)
+    return y
+
+
+def rmsnorm_auto_threads_per_row(N: int, dtype: int) -> int:
+    rc = int(load().rmsnorm_auto_threads_per_row(int(N), int(dtype)))
+    if rc < 0:
+        _check(rc)
+    return rc
+
+
 def rmsnorm_select_variant(x, w, y) -> int:
     M, N, code, _ = _marshal(x, w, y)
     rc = load().rmsnorm_select_variant(x.data_ptr(), w.data_ptr(), y.data_ptr(), M, N, code)
@@ -156,3 +181,32 @@ def rmsnorm_calib_copy(src, dst) -> None:
     stream = torch.cuda.current_stream(src.device).cuda_stream
     with torch.cuda.device(src.device):
         _check(load().rmsnorm_calib_copy(src.data_ptr(), dst.data_ptr(), nbytes, stream))
+
+
+def bind_rmsnorm_fwd(x, w, y, eps: float, variant: int = RMSNORM_VARIANT_AUTO,
+                     threads_per_row: int = 0):
+    """Marshals one call once and returns a zero-argument launcher for it.
+
+    For launch loops (benchmarks, serving steps) where the per-call tensor checks
+    of rmsnorm_fwd would dominate the host side.  The launcher enqueues on the
+    stream that was current when it was bound and raises on a non-zero status.
+    The tensors must outlive every use of the launcher.
+    """
+    import torch
+    lib = load()
+    M, N, code, stream = _marshal(x, w, y)
+    xp, wp, yp = x.data_ptr(), w.data_ptr(), y.data_ptr()
+    eps_c = ctypes.c_float(eps)
+    if threads_per_row:
+        fn, last = lib.rmsnorm_fwd_tuned, int(threads_per_row)
+    else:
+        fn, last = lib.rmsnorm_fwd_variant, int(variant)
+    if torch.cuda.current_device() != x.device.index:
+        raise ValueError("bind_rmsnorm_fwd: make the tensors' device current before binding")
+
+    def launch():
+        rc = fn(xp, wp, yp, M, N, eps_c, code, stream, last)
+        if rc != RMSNORM_OK:
+            _check(rc)
+
+    return launch

@@ -10,11 +10,17 @@ namespace {
 
 using rms::u32x4;
 
-constexpr int kWaveMaxChunks16 = 16;   // 16-bit types: 16 chunks * 64 lanes * 8 = 8192 elements
-constexpr int kWaveMaxChunks32 = 32;   // fp32:         32 chunks * 64 lanes * 4 = 8192 elements
+// Instantiated (threads per row : chunks per thread) combinations.  A chunk is
+// one 16-byte vector per thread.
+//   64   : 1..16 (fp32: 1..32)   one wavefront per row, N <= 8192
+//   128, 256, 512 : 1..8
+//   1024 : 1..16                 N <= 131072 (16-bit) / 65536 (fp32)
+constexpr int kWaveMaxChunks16 = 16;
+constexpr int kWaveMaxChunks32 = 32;
+constexpr int kMidMaxChunks = 8;
 constexpr int kBlockMaxChunks = 16;
 constexpr int kBlockMaxThreads = 1024;
-constexpr int kWavesPerBlock = 4;
+constexpr int kTargetChunks = 4;       // automatic choice aims at <= 4 chunks per thread
 constexpr int kGenericThreads = 256;
 constexpr int64_t kMaxGrid = 1 << 20;  // beyond this the kernels stride over rows
 
@@ -51,20 +57,36 @@ bool rows_vectorisable(const void* x, const void* w, const void* y, int64_t N, i
 
 int64_t vectors_per_row(int64_t N, int dtype) { return N * elem_bytes(dtype) / 16; }
 
-bool wave_can(int64_t nvec, int dtype) {
-  return nvec >= 1 && nvec <= (int64_t)rms::kWave * wave_max_chunks(dtype);
+int max_chunks_for(int threads, int dtype) {
+  switch (threads) {
+    case 64: return wave_max_chunks(dtype);
+    case 128: case 256: case 512: return kMidMaxChunks;
+    case 1024: return kBlockMaxChunks;
+    default: return 0;
+  }
 }
 
-bool block_can(int64_t nvec) {
-  return nvec >= 1 && nvec <= (int64_t)kBlockMaxThreads * kBlockMaxChunks;
+bool threads_can(int threads, int64_t nvec, int dtype) {
+  const int mc = max_chunks_for(threads, dtype);
+  return mc > 0 && nvec >= 1 && (nvec + threads - 1) / threads <= mc;
+}
+
+bool wave_can(int64_t nvec, int dtype) { return threads_can(64, nvec, dtype); }
+
+// Threads per row: the smallest power of two from min_threads up that keeps the
+// row within kTargetChunks chunks per thread; rows longer than 1024 * 4 vectors
+// take 1024 threads with up to 16 chunks.  0 if the row does not fit at all.
+int pick_threads(int64_t nvec, int min_threads, int dtype) {
+  for (int g = min_threads; g <= kBlockMaxThreads; g *= 2)
+    if ((nvec + g - 1) / g <= kTargetChunks && threads_can(g, nvec, dtype)) return g;
+  return threads_can(kBlockMaxThreads, nvec, dtype) ? kBlockMaxThreads : 0;
 }
 
 int choose(const void* x, const void* w, const void* y, int64_t N, int dtype) {
   if (!rows_vectorisable(x, w, y, N, dtype)) return RMSNORM_VARIANT_GENERIC;
-  const int64_t nvec = vectors_per_row(N, dtype);
-  if (wave_can(nvec, dtype)) return RMSNORM_VARIANT_WAVE;
-  if (block_can(nvec)) return RMSNORM_VARIANT_BLOCK;
-  return RMSNORM_VARIANT_GENERIC;
+  const int g = pick_threads(vectors_per_row(N, dtype), 64, dtype);
+  if (g == 0) return RMSNORM_VARIANT_GENERIC;
+  return g == 64 ? RMSNORM_VARIANT_WAVE : RMSNORM_VARIANT_BLOCK;
 }
 
 struct Args {
@@ -78,21 +100,11 @@ struct Args {
   hipStream_t stream;
 };
 
-template <int DT, int CHUNKS>
-void launch_wave(const Args& a) {
-  int64_t blocks = (a.M + kWavesPerBlock - 1) / kWavesPerBlock;
-  if (blocks > kMaxGrid) blocks = kMaxGrid;
-  hipLaunchKernelGGL((rms::rmsnorm_wave_kernel<DT, CHUNKS, kWavesPerBlock, true>),
-                     dim3((unsigned)blocks), dim3(kWavesPerBlock * rms::kWave), 0, a.stream,
-                     (const u32x4*)a.x, (const u32x4*)a.w, (u32x4*)a.y, a.M, a.nvec,
-                     (float)a.N, a.eps);
-}
-
-template <int DT, int CHUNKS, int T>
-void launch_block(const Args& a) {
+template <int DT, int CHUNKS, int G>
+void launch_row(const Args& a) {
   const int64_t blocks = a.M < kMaxGrid ? a.M : kMaxGrid;
-  hipLaunchKernelGGL((rms::rmsnorm_block_kernel<DT, CHUNKS, T, true>),
-                     dim3((unsigned)blocks), dim3(T), 0, a.stream,
+  hipLaunchKernelGGL((rms::rmsnorm_row_kernel<DT, CHUNKS, G, true>),
+                     dim3((unsigned)blocks), dim3(G), 0, a.stream,
                      (const u32x4*)a.x, (const u32x4*)a.w, (u32x4*)a.y, a.M, a.nvec,
                      (float)a.N, a.eps);
 }
@@ -106,9 +118,10 @@ void launch_generic(const Args& a) {
 }
 
 #define RMS_CASE(n, call) case n: call; break;
-#define RMS_CASES_1_16(M_)                                                            \
+#define RMS_CASES_1_8(M_)                                                             \
   RMS_CASE(1, M_(1)) RMS_CASE(2, M_(2)) RMS_CASE(3, M_(3)) RMS_CASE(4, M_(4))         \
-  RMS_CASE(5, M_(5)) RMS_CASE(6, M_(6)) RMS_CASE(7, M_(7)) RMS_CASE(8, M_(8))         \
+  RMS_CASE(5, M_(5)) RMS_CASE(6, M_(6)) RMS_CASE(7, M_(7)) RMS_CASE(8, M_(8))
+#define RMS_CASES_9_16(M_)                                                            \
   RMS_CASE(9, M_(9)) RMS_CASE(10, M_(10)) RMS_CASE(11, M_(11)) RMS_CASE(12, M_(12))   \
   RMS_CASE(13, M_(13)) RMS_CASE(14, M_(14)) RMS_CASE(15, M_(15)) RMS_CASE(16, M_(16))
 #define RMS_CASES_17_32(M_)                                                           \
@@ -117,91 +130,100 @@ void launch_generic(const Args& a) {
   RMS_CASE(25, M_(25)) RMS_CASE(26, M_(26)) RMS_CASE(27, M_(27)) RMS_CASE(28, M_(28)) \
   RMS_CASE(29, M_(29)) RMS_CASE(30, M_(30)) RMS_CASE(31, M_(31)) RMS_CASE(32, M_(32))
 
+// Launches the row kernel with `threads` threads per row.  The caller has
+// checked threads_can(threads, nvec, DT).
 template <int DT>
-int dispatch_wave(const Args& a) {
-  const int chunks = (a.nvec + rms::kWave - 1) / rms::kWave;
-#define RMS_W(c) launch_wave<DT, c>(a)
-  if constexpr (DT == rms::kFp32) {
-    switch (chunks) {
-      RMS_CASES_1_16(RMS_W)
-      RMS_CASES_17_32(RMS_W)
-      default: return RMSNORM_ERR_UNSUPPORTED;
-    }
-  } else {
-    switch (chunks) {
-      RMS_CASES_1_16(RMS_W)
-      default: return RMSNORM_ERR_UNSUPPORTED;
-    }
+int dispatch_row(const Args& a, int threads) {
+  const int chunks = (a.nvec + threads - 1) / threads;
+  switch (threads) {
+    case 64:
+#define RMS_L(c) launch_row<DT, c, 64>(a)
+      if constexpr (DT == rms::kFp32) {
+        switch (chunks) {
+          RMS_CASES_1_8(RMS_L) RMS_CASES_9_16(RMS_L) RMS_CASES_17_32(RMS_L)
+          default: return RMSNORM_ERR_UNSUPPORTED;
+        }
+      } else {
+        switch (chunks) {
+          RMS_CASES_1_8(RMS_L) RMS_CASES_9_16(RMS_L)
+          default: return RMSNORM_ERR_UNSUPPORTED;
+        }
+      }
+#undef RMS_L
+      break;
+    case 128:
+#define RMS_L(c) launch_row<DT, c, 128>(a)
+      switch (chunks) { RMS_CASES_1_8(RMS_L) default: return RMSNORM_ERR_UNSUPPORTED; }
+#undef RMS_L
+      break;
+    case 256:
+#define RMS_L(c) launch_row<DT, c, 256>(a)
+      switch (chunks) { RMS_CASES_1_8(RMS_L) default: return RMSNORM_ERR_UNSUPPORTED; }
+#undef RMS_L
+      break;
+    case 512:
+#define RMS_L(c) launch_row<DT, c, 512>(a)
+      switch (chunks) { RMS_CASES_1_8(RMS_L) default: return RMSNORM_ERR_UNSUPPORTED; }
+#undef RMS_L
+      break;
+    case 1024:
+#define RMS_L(c) launch_row<DT, c, 1024>(a)
+      switch (chunks) {
+        RMS_CASES_1_8(RMS_L) RMS_CASES_9_16(RMS_L)
+        default: return RMSNORM_ERR_UNSUPPORTED;
+      }
+#undef RMS_L
+      break;
+    default:
+      return RMSNORM_ERR_UNSUPPORTED;
   }
-#undef RMS_W
   return RMSNORM_OK;
 }
 
-// Threads per row for the block kernel: the smallest workgroup that keeps the
-// row within 16 chunks per thread, so short rows do not pay for idle waves.
+// threads == 0 means the element-wise kernel.
 template <int DT>
-int dispatch_block(const Args& a) {
-  if (a.nvec <= 256 * kBlockMaxChunks) {
-    const int chunks = (a.nvec + 255) / 256;
-#define RMS_B(c) launch_block<DT, c, 256>(a)
-    switch (chunks) { RMS_CASES_1_16(RMS_B) default: return RMSNORM_ERR_UNSUPPORTED; }
-#undef RMS_B
-  } else if (a.nvec <= 512 * kBlockMaxChunks) {
-    const int chunks = (a.nvec + 511) / 512;
-#define RMS_B(c) launch_block<DT, c, 512>(a)
-    switch (chunks) {
-      RMS_CASE(9, RMS_B(9)) RMS_CASE(10, RMS_B(10)) RMS_CASE(11, RMS_B(11)) RMS_CASE(12, RMS_B(12))
-      RMS_CASE(13, RMS_B(13)) RMS_CASE(14, RMS_B(14)) RMS_CASE(15, RMS_B(15)) RMS_CASE(16, RMS_B(16))
-      default: return RMSNORM_ERR_UNSUPPORTED;
-    }
-#undef RMS_B
-  } else {
-    const int chunks = (a.nvec + 1023) / 1024;
-#define RMS_B(c) launch_block<DT, c, 1024>(a)
-    switch (chunks) {
-      RMS_CASE(9, RMS_B(9)) RMS_CASE(10, RMS_B(10)) RMS_CASE(11, RMS_B(11)) RMS_CASE(12, RMS_B(12))
-      RMS_CASE(13, RMS_B(13)) RMS_CASE(14, RMS_B(14)) RMS_CASE(15, RMS_B(15)) RMS_CASE(16, RMS_B(16))
-      default: return RMSNORM_ERR_UNSUPPORTED;
-    }
-#undef RMS_B
-  }
-  return RMSNORM_OK;
-}
-
-template <int DT>
-int run_typed(const Args& a, int variant) {
+int run_typed(const Args& a, int threads) {
   int rc = RMSNORM_OK;
-  switch (variant) {
-    case RMSNORM_VARIANT_WAVE: rc = dispatch_wave<DT>(a); break;
-    case RMSNORM_VARIANT_BLOCK: rc = dispatch_block<DT>(a); break;
-    case RMSNORM_VARIANT_GENERIC: launch_generic<DT>(a); break;
-    default: return RMSNORM_ERR_INVALID_ARG;
-  }
+  if (threads == 0) launch_generic<DT>(a);
+  else rc = dispatch_row<DT>(a, threads);
   if (rc != RMSNORM_OK) return rc;
   return hipGetLastError() == hipSuccess ? RMSNORM_OK : RMSNORM_ERR_LAUNCH;
 }
 
+// variant: an rmsnorm_variant, or -1 with `threads` forced by the caller.
 int run(const void* x, const void* w, void* y, int64_t M, int64_t N, float eps, int dtype,
-        void* stream, int variant) {
+        void* stream, int variant, int threads) {
   int rc = check_args(x, w, y, M, N, eps, dtype);
   if (rc != RMSNORM_OK) return rc;
-  if (variant < RMSNORM_VARIANT_AUTO || variant > RMSNORM_VARIANT_GENERIC)
-    return RMSNORM_ERR_INVALID_ARG;
+  if (variant < -1 || variant > RMSNORM_VARIANT_GENERIC) return RMSNORM_ERR_INVALID_ARG;
+  if (variant == -1 && max_chunks_for(threads, dtype) == 0) return RMSNORM_ERR_INVALID_ARG;
   if (M == 0) return RMSNORM_OK;
 
   const bool vec_ok = rows_vectorisable(x, w, y, N, dtype);
   const int64_t nvec = vec_ok ? vectors_per_row(N, dtype) : 0;
   if (variant == RMSNORM_VARIANT_AUTO) variant = choose(x, w, y, N, dtype);
-  if (variant == RMSNORM_VARIANT_WAVE && !(vec_ok && wave_can(nvec, dtype)))
-    return RMSNORM_ERR_UNSUPPORTED;
-  if (variant == RMSNORM_VARIANT_BLOCK && !(vec_ok && block_can(nvec)))
-    return RMSNORM_ERR_UNSUPPORTED;
+  switch (variant) {
+    case -1:
+      if (!(vec_ok && threads_can(threads, nvec, dtype))) return RMSNORM_ERR_UNSUPPORTED;
+      break;
+    case RMSNORM_VARIANT_WAVE:
+      if (!(vec_ok && wave_can(nvec, dtype))) return RMSNORM_ERR_UNSUPPORTED;
+      threads = 64;
+      break;
+    case RMSNORM_VARIANT_BLOCK:
+      threads = vec_ok ? pick_threads(nvec, 128, dtype) : 0;
+      if (threads == 0) return RMSNORM_ERR_UNSUPPORTED;
+      break;
+    default:
+      threads = 0;
+      break;
+  }
 
   Args a{x, w, y, M, N, (int)nvec, eps, static_cast<hipStream_t>(stream)};
   switch (dtype) {
-    case RMSNORM_DTYPE_FP32: return run_typed<rms::kFp32>(a, variant);
-    case RMSNORM_DTYPE_FP16: return run_typed<rms::kFp16>(a, variant);
-    case RMSNORM_DTYPE_BF16: return run_typed<rms::kBf16>(a, variant);
+    case RMSNORM_DTYPE_FP32: return run_typed<rms::kFp32>(a, threads);
+    case RMSNORM_DTYPE_FP16: return run_typed<rms::kFp16>(a, threads);
+    case RMSNORM_DTYPE_BF16: return run_typed<rms::kBf16>(a, threads);
     default: return RMSNORM_ERR_INVALID_ARG;
   }
 }
@@ -212,12 +234,25 @@ extern "C" {
 
 int rmsnorm_fwd(const void* x, const void* w, void* y, int64_t M, int64_t N, float eps,
                 int dtype, void* stream) {
-  return run(x, w, y, M, N, eps, dtype, stream, RMSNORM_VARIANT_AUTO);
+  return run(x, w, y, M, N, eps, dtype, stream, RMSNORM_VARIANT_AUTO, 0);
 }
 
 int rmsnorm_fwd_variant(const void* x, const void* w, void* y, int64_t M, int64_t N, float eps,
                         int dtype, void* stream, int variant) {
-  return run(x, w, y, M, N, eps, dtype, stream, variant);
+  if (variant < RMSNORM_VARIANT_AUTO) return RMSNORM_ERR_INVALID_ARG;
+  return run(x, w, y, M, N, eps, dtype, stream, variant, 0);
+}
+
+int rmsnorm_fwd_tuned(const void* x, const void* w, void* y, int64_t M, int64_t N, float eps,
+                      int dtype, void* stream, int threads_per_row) {
+  return run(x, w, y, M, N, eps, dtype, stream, -1, threads_per_row);
+}
+
+int rmsnorm_auto_threads_per_row(int64_t N, int dtype) {
+  const int b = elem_bytes(dtype);
+  if (b == 0 || N <= 0) return RMSNORM_ERR_INVALID_ARG;
+  if ((N * b) % 16 != 0) return 0;
+  return pick_threads(vectors_per_row(N, dtype), 64, dtype);
 }
 
 int rmsnorm_select_variant(const void* x, const void* w, const void* y, int64_t M, int64_t N,

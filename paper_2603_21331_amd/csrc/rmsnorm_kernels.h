@@ -11,11 +11,13 @@
 // additionally stays in registers between the reduce and the scale, so the
 // second pass costs no memory traffic at all.
 //
-//  * rmsnorm_wave_kernel  : one 64-lane wavefront per row.  No LDS, no barrier.
-//  * rmsnorm_block_kernel : one workgroup per row, per-wave partial sums
-//                           combined through LDS in wave order.
-//  * rmsnorm_generic_kernel: element-wise two-pass fallback for rows that are
-//                           not 16-byte aligned or too long for registers.
+//  * rmsnorm_row_kernel<.., G = 64>  : one 64-lane wavefront per row.  No LDS,
+//                                      no barrier.
+//  * rmsnorm_row_kernel<.., G > 64>  : one workgroup per row, per-wave partial
+//                                      sums combined through LDS in wave order.
+//  * rmsnorm_generic_kernel          : element-wise two-pass fallback for rows
+//                                      that are not 16-byte aligned or too long
+//                                      for registers.
 //
 // All sums are fp32, in an order fixed by (kernel, shape) alone: no atomics,
 // so repeated runs give identical bits.
@@ -63,95 +65,69 @@ __device__ __forceinline__ u32x4 scale_vec(u32x4 xv, u32x4 wv, float rstd) {
 }
 
 // ---------------------------------------------------------------------------
-// One wavefront per row.  Vector c * 64 + lane of the row goes to lane `lane`,
-// chunk c, so each load instruction covers 1 KiB of contiguous memory.
-// CHUNKS = ceil(nvec / 64): only the last chunk can be ragged.  All CHUNKS
-// loads are issued before the first use.  The grid may be smaller than the
-// number of rows; each wavefront then strides over rows.
+// Register-resident row kernel: G threads (G/64 wavefronts) share one row, one
+// row per workgroup.  Vector c * G + t of the row goes to thread t, chunk c, so
+// every load instruction of a wavefront covers 1 KiB of contiguous memory.
+// CHUNKS = ceil(nvec / G): only the last chunk can be ragged.  All loads of x
+// and w are issued before the first use; x is then held in registers across
+// the reduction, so the scale pass reads nothing from memory.
+//
+//  G == 64 : one wavefront per row.  DPP reduction only; no LDS, no barrier.
+//  G  > 64 : one workgroup per row.  Each wavefront reduces its lanes with DPP,
+//            lane 0 parks the partial in LDS, and after one barrier every
+//            thread adds the G/64 partials in wave order.  Two LDS slots
+//            alternate between consecutive rows of a striding workgroup, so
+//            one barrier per row is enough.
+//
+// Short per-thread work wins on MI355X: at N = 8192 (bf16) four 16-byte chunks
+// per thread with 256 threads per row sustain about 10 % more bandwidth than
+// sixteen chunks in one wavefront, because load, reduce and store phases of
+// the many small wavefronts interleave more finely.  The grid is flat (one
+// workgroup per row); it only strides when M exceeds the grid limit.
 // ---------------------------------------------------------------------------
-template <int DT, int CHUNKS, int WAVES_PER_BLOCK, bool NT>
-__global__ void __launch_bounds__(WAVES_PER_BLOCK* kWave)
-rmsnorm_wave_kernel(const u32x4* x, const u32x4* __restrict__ w, u32x4* y,
-                    int64_t M, int nvec, float n, float eps) {
-  const int lane = threadIdx.x & (kWave - 1);
-  const int wave = threadIdx.x / kWave;
-  const int64_t row_stride = (int64_t)gridDim.x * WAVES_PER_BLOCK;
-  const int last = (CHUNKS - 1) * kWave + lane;
-  const bool last_ok = last < nvec;
-
-  for (int64_t row = (int64_t)blockIdx.x * WAVES_PER_BLOCK + wave; row < M; row += row_stride) {
-    const u32x4* xr = x + row * nvec;
-    u32x4* yr = y + row * nvec;
-
-    u32x4 v[CHUNKS];
-#pragma unroll
-    for (int c = 0; c < CHUNKS - 1; ++c) v[c] = load_vec<NT>(xr + c * kWave + lane);
-    {
-      const u32x4 zero = {0u, 0u, 0u, 0u};
-      v[CHUNKS - 1] = zero;
-      if (last_ok) v[CHUNKS - 1] = load_vec<NT>(xr + last);
-    }
-
-    const float total = wave_sum(lane_sum_sq<DT, CHUNKS>(v));
-    const float rstd = row_rstd(total, n, eps);
-
-#pragma unroll
-    for (int c = 0; c < CHUNKS - 1; ++c) {
-      const int idx = c * kWave + lane;
-      store_vec<NT>(yr + idx, scale_vec<DT>(v[c], w[idx], rstd));
-    }
-    if (last_ok) store_vec<NT>(yr + last, scale_vec<DT>(v[CHUNKS - 1], w[last], rstd));
-  }
-}
-
-// ---------------------------------------------------------------------------
-// One workgroup of T threads per row, for rows too long for one wavefront's
-// registers.  Vector c * T + tid goes to thread tid, chunk c.  Each wavefront
-// reduces its own lanes with DPP, lane 0 parks the partial in LDS, and after
-// one barrier every thread adds the T/64 partials in wave order.  Two LDS
-// slots alternate between consecutive rows, so one barrier per row is enough.
-// ---------------------------------------------------------------------------
-template <int DT, int CHUNKS, int T, bool NT>
-__global__ void __launch_bounds__(T)
-rmsnorm_block_kernel(const u32x4* x, const u32x4* __restrict__ w, u32x4* y,
-                     int64_t M, int nvec, float n, float eps) {
-  constexpr int WAVES = T / kWave;
+template <int DT, int CHUNKS, int G, bool NT>
+__global__ void __launch_bounds__(G)
+rmsnorm_row_kernel(const u32x4* x, const u32x4* __restrict__ w, u32x4* y,
+                   int64_t M, int nvec, float n, float eps) {
+  constexpr int WAVES = G / kWave;
   __shared__ float partial[2][WAVES];
-  const int tid = threadIdx.x;
-  const int lane = tid & (kWave - 1);
-  const int wave = tid / kWave;
-  const int last = (CHUNKS - 1) * T + tid;
+  const int t = threadIdx.x;
+  const int lane = t & (kWave - 1);
+  const int wave = t / kWave;
+  const int last = (CHUNKS - 1) * G + t;
   const bool last_ok = last < nvec;
+  const u32x4 zero = {0u, 0u, 0u, 0u};
   int slot = 0;
 
   for (int64_t row = blockIdx.x; row < M; row += gridDim.x) {
     const u32x4* xr = x + row * nvec;
     u32x4* yr = y + row * nvec;
 
-    u32x4 v[CHUNKS];
+    u32x4 v[CHUNKS], wv[CHUNKS];
 #pragma unroll
-    for (int c = 0; c < CHUNKS - 1; ++c) v[c] = load_vec<NT>(xr + c * T + tid);
-    {
-      const u32x4 zero = {0u, 0u, 0u, 0u};
-      v[CHUNKS - 1] = zero;
-      if (last_ok) v[CHUNKS - 1] = load_vec<NT>(xr + last);
-    }
+    for (int c = 0; c < CHUNKS - 1; ++c) v[c] = load_vec<NT>(xr + c * G + t);
+    v[CHUNKS - 1] = zero;
+    if (last_ok) v[CHUNKS - 1] = load_vec<NT>(xr + last);
+#pragma unroll
+    for (int c = 0; c < CHUNKS - 1; ++c) wv[c] = w[c * G + t];
+    wv[CHUNKS - 1] = zero;
+    if (last_ok) wv[CHUNKS - 1] = w[last];
 
-    const float wsum = wave_sum(lane_sum_sq<DT, CHUNKS>(v));
-    if (lane == 0) partial[slot][wave] = wsum;
-    __syncthreads();
-    float total = partial[slot][0];
+    float total = wave_sum(lane_sum_sq<DT, CHUNKS>(v));
+    if constexpr (WAVES > 1) {
+      if (lane == 0) partial[slot][wave] = total;
+      __syncthreads();
+      total = partial[slot][0];
 #pragma unroll
-    for (int k = 1; k < WAVES; ++k) total += partial[slot][k];
-    slot ^= 1;
+      for (int k = 1; k < WAVES; ++k) total += partial[slot][k];
+      slot ^= 1;
+    }
     const float rstd = row_rstd(total, n, eps);
 
 #pragma unroll
-    for (int c = 0; c < CHUNKS - 1; ++c) {
-      const int idx = c * T + tid;
-      store_vec<NT>(yr + idx, scale_vec<DT>(v[c], w[idx], rstd));
-    }
-    if (last_ok) store_vec<NT>(yr + last, scale_vec<DT>(v[CHUNKS - 1], w[last], rstd));
+    for (int c = 0; c < CHUNKS - 1; ++c)
+      store_vec<NT>(yr + c * G + t, scale_vec<DT>(v[c], wv[c], rstd));
+    if (last_ok) store_vec<NT>(yr + last, scale_vec<DT>(v[CHUNKS - 1], wv[CHUNKS - 1], rstd));
   }
 }
 

@@ -66,8 +66,9 @@ template <> struct Storage<kBf16> {
   __device__ static __forceinline__ void unpack(u32x4 v, float (&f)[8]) {
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-      f[2 * k] = as_f32(v[k] << 16);            // a bf16 is the top half of an fp32
-      f[2 * k + 1] = as_f32(v[k] & 0xFFFF0000u);
+      const uint32_t d = v[k];
+      f[2 * k] = as_f32(d << 16);               // a bf16 is the top half of an fp32
+      f[2 * k + 1] = as_f32(d & 0xFFFF0000u);
     }
   }
   __device__ static __forceinline__ u32x4 pack(const float (&f)[8]) {
@@ -93,7 +94,10 @@ template <> struct Storage<kFp16> {
   __device__ static __forceinline__ void unpack(u32x4 v, float (&f)[8]) {
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-      f32x2 p = __builtin_convertvector(__builtin_bit_cast(f16x2, v[k]), f32x2);
+      // The element is copied to a scalar first: a bit_cast applied directly to
+      // a vector-element expression reads element 0 whatever k is.
+      const uint32_t d = v[k];
+      f32x2 p = __builtin_convertvector(__builtin_bit_cast(f16x2, d), f32x2);
       f[2 * k] = p.x;
       f[2 * k + 1] = p.y;
     }

@@ -17,6 +17,22 @@ from paper_2603_21331_amd import binding, inputs
 GUARD = 64            # guard elements on each side of y (a multiple of 16 bytes)
 VARIANTS = (binding.RMSNORM_VARIANT_AUTO, binding.RMSNORM_VARIANT_WAVE,
             binding.RMSNORM_VARIANT_BLOCK, binding.RMSNORM_VARIANT_GENERIC)
+THREADS = (64, 128, 256, 512, 1024)
+# A mode is a variant code (0..3) or ("threads", G): every way the ABI can be told to run.
+ALL_MODES = VARIANTS + tuple(("threads", g) for g in THREADS)
+
+
+def mode_name(mode) -> str:
+    if isinstance(mode, tuple):
+        return f"threads{mode[1]}"
+    return binding.VARIANT_NAMES[mode]
+
+
+def launch_mode(x_dev, w_dev, eps: float, mode, y):
+    """One call through the binding in the given mode; raises RmsnormError on a status."""
+    if isinstance(mode, tuple):
+        return binding.rmsnorm_fwd_tuned(x_dev, w_dev, eps, mode[1], y)
+    return binding.rmsnorm_fwd_variant(x_dev, w_dev, eps, mode, y)
 
 
 def say(msg: str) -> None:
@@ -76,16 +92,16 @@ def guards_intact(whole, M: int, N: int, dtype: int, offset_elems: int = 0) -> b
     return bool((head == s).all().item() and (tail == s).all().item())
 
 
-def run_variant(x_dev, w_dev, eps: float, dtype: int, variant: int, what: str):
-    """Runs one kernel variant into a guarded buffer; None if it does not support the shape."""
+def run_variant(x_dev, w_dev, eps: float, dtype: int, mode, what: str):
+    """Runs one mode into a guarded buffer; None if that kernel does not support the shape."""
     import torch
     M, N = x_dev.shape
     whole, y = alloc_guarded(M, N, dtype, x_dev.device)
-    say(f"{what}: {inputs.DTYPE_NAMES[dtype]} {M}x{N} eps={eps} variant={binding.VARIANT_NAMES[variant]}")
+    say(f"{what}: {inputs.DTYPE_NAMES[dtype]} {M}x{N} eps={eps} mode={mode_name(mode)}")
     try:
-        binding.rmsnorm_fwd_variant(x_dev, w_dev, eps, variant, y)
+        launch_mode(x_dev, w_dev, eps, mode, y)
     except binding.RmsnormError as e:
-        if e.status == binding.RMSNORM_ERR_UNSUPPORTED and variant != binding.RMSNORM_VARIANT_AUTO:
+        if e.status == binding.RMSNORM_ERR_UNSUPPORTED and mode != binding.RMSNORM_VARIANT_AUTO:
             return None
         raise
     torch.cuda.synchronize()
@@ -93,8 +109,8 @@ def run_variant(x_dev, w_dev, eps: float, dtype: int, variant: int, what: str):
     return to_host(y, dtype)
 
 
-def check_case(case: dict, device, variants=VARIANTS, nthreads: int = 0, want=None) -> dict:
-    """Runs every requested variant on one input case and compares with the oracle."""
+def check_case(case: dict, device, variants=ALL_MODES, nthreads: int = 0, want=None) -> dict:
+    """Runs every requested mode on one input case and compares with the oracle."""
     dtype, eps = case["dtype"], case["eps"]
     if want is None:
         want = oracle.rmsnorm_oracle(case["x"], case["w"], eps, dtype, nthreads)
@@ -107,7 +123,7 @@ def check_case(case: dict, device, variants=VARIANTS, nthreads: int = 0, want=No
         if got is None:
             continue
         ran += 1
-        stats[binding.VARIANT_NAMES[v]] = compare.check_parity(
-            got, want, dtype, f"{case['name']} [{binding.VARIANT_NAMES[v]}]")
+        stats[mode_name(v)] = compare.check_parity(
+            got, want, dtype, f"{case['name']} [{mode_name(v)}]")
     assert ran >= 1, f"{case['name']}: no variant ran"
     return stats

@@ -107,10 +107,43 @@ def test_unknown_variant_and_unsupported_shapes():
                                    binding.RMSNORM_VARIANT_WAVE) == binding.RMSNORM_ERR_UNSUPPORTED
 
 
+def test_tuned_entry_argument_checks():
+    lib = binding.load()
+    f = lib.rmsnorm_fwd_tuned
+    big = 1 << 22
+    for bad in (0, 32, 96, 2048, -64):
+        assert f(P, P + big, P + 2 * big, 4, 4096, 1e-6, 2, None, bad) == binding.RMSNORM_ERR_INVALID_ARG
+    # 4096 bf16 = 512 vectors: 64 threads -> 8 chunks (ok); 16384 bf16 with 64 threads -> 32 (too many)
+    assert f(P, P + big, P + 2 * big, 4, 16384, 1e-6, 2, None, 64) == binding.RMSNORM_ERR_UNSUPPORTED
+    assert f(P, P + big, P + 2 * big, 4, 16384, 1e-6, 2, None, 128) == binding.RMSNORM_ERR_UNSUPPORTED
+    assert f(P, P + big, P + 2 * big, 4, 1023, 1e-6, 2, None, 256) == binding.RMSNORM_ERR_UNSUPPORTED
+    assert f(P, P + big, P + 2 * big, 0, 4096, 1e-6, 2, None, 256) == binding.RMSNORM_OK
+    assert f(0, P + big, P + 2 * big, 4, 4096, 1e-6, 2, None, 256) == binding.RMSNORM_ERR_INVALID_ARG
+
+
+def test_automatic_threads_per_row():
+    auto = binding.rmsnorm_auto_threads_per_row
+    bf16, fp16, fp32 = binding.RMSNORM_DTYPE_BF16, binding.RMSNORM_DTYPE_FP16, binding.RMSNORM_DTYPE_FP32
+    assert auto(8192, bf16) == 256          # headline shape: 4 chunks per thread
+    assert auto(4096, bf16) == 128
+    assert auto(1024, fp32) == 64
+    assert auto(768, fp16) == 64
+    assert auto(5120, fp16) == 256
+    assert auto(13824, fp16) == 512
+    assert auto(8192, fp32) == 512
+    assert auto(131072, bf16) == 1024
+    assert auto(131080, bf16) == 0          # too long for registers
+    assert auto(1023, bf16) == 0            # rows not 16-byte aligned
+    with pytest.raises(binding.RmsnormError):
+        auto(0, bf16)
+    with pytest.raises(binding.RmsnormError):
+        auto(64, 7)
+
+
 def test_dispatch_choice_is_visible_without_a_launch():
     lib = binding.load()
     sel = lib.rmsnorm_select_variant
-    assert sel(P, P + 65536, P + 131072, 16, 8192, 2) == binding.RMSNORM_VARIANT_WAVE
+    assert sel(P, P + 65536, P + 131072, 16, 8192, 2) == binding.RMSNORM_VARIANT_BLOCK
     assert sel(P, P + 65536, P + 131072, 16, 768, 1) == binding.RMSNORM_VARIANT_WAVE
     assert sel(P, P + 65536, P + 131072, 16, 13824, 1) == binding.RMSNORM_VARIANT_BLOCK
     assert sel(P, P + 65536, P + 131072, 16, 1023, 1) == binding.RMSNORM_VARIANT_GENERIC

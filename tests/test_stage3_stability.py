@@ -92,7 +92,7 @@ def test_nan_and_inf_propagate(gpu_device):
     want = oracle.rmsnorm_oracle(x, case["w"], 1e-6, inputs.FP32)
     xd = H.to_device(x, inputs.FP32, gpu_device)
     wd = H.to_device(case["w"], inputs.FP32, gpu_device)
-    for v in H.VARIANTS:
+    for v in H.ALL_MODES:
         got = H.run_variant(xd, wd, 1e-6, inputs.FP32, v, "nan_inf")
         if got is None:
             continue

@@ -19,11 +19,11 @@ def _repeat(case, device):
     dtype, eps = case["dtype"], case["eps"]
     xd = H.to_device(case["x"], dtype, device)
     wd = H.to_device(case["w"], dtype, device)
-    for v in H.VARIANTS:
-        H.say(f"determinism {case['name']} variant={binding.VARIANT_NAMES[v]}")
+    for v in H.ALL_MODES:
+        H.say(f"determinism {case['name']} mode={H.mode_name(v)}")
         y = torch.empty_like(xd)
         try:
-            binding.rmsnorm_fwd_variant(xd, wd, eps, v, y)
+            H.launch_mode(xd, wd, eps, v, y)
         except binding.RmsnormError as e:
             if e.status == binding.RMSNORM_ERR_UNSUPPORTED:
                 continue
@@ -31,12 +31,12 @@ def _repeat(case, device):
         torch.cuda.synchronize()
         first = _bits(y, dtype)
         for _ in range(2):
-            binding.rmsnorm_fwd_variant(xd, wd, eps, v, y)
+            H.launch_mode(xd, wd, eps, v, y)
             torch.cuda.synchronize()
             assert np.array_equal(_bits(y, dtype), first)
         for _ in range(2):
             fresh = torch.empty_like(xd)
-            binding.rmsnorm_fwd_variant(xd, wd, eps, v, fresh)
+            H.launch_mode(xd, wd, eps, v, fresh)
             torch.cuda.synchronize()
             assert np.array_equal(_bits(fresh, dtype), first)
 
@@ -56,10 +56,9 @@ def test_rows_do_not_depend_on_their_neighbours(gpu_device):
     case = inputs.random_case(4, 710, 300, 4096, inputs.BF16, 1e-6)
     xd = H.to_device(case["x"], inputs.BF16, gpu_device)
     wd = H.to_device(case["w"], inputs.BF16, gpu_device)
-    for v in (binding.RMSNORM_VARIANT_WAVE, binding.RMSNORM_VARIANT_BLOCK,
-              binding.RMSNORM_VARIANT_GENERIC):
-        H.say(f"row independence variant={binding.VARIANT_NAMES[v]}")
-        full = H.to_host(binding.rmsnorm_fwd_variant(xd, wd, 1e-6, v), inputs.BF16)
+    for v in H.ALL_MODES[1:]:
+        H.say(f"row independence mode={H.mode_name(v)}")
+        full = H.to_host(H.launch_mode(xd, wd, 1e-6, v, None), inputs.BF16)
         for i in (0, 3, 157, 299):
-            one = H.to_host(binding.rmsnorm_fwd_variant(xd[i:i + 1], wd, 1e-6, v), inputs.BF16)
+            one = H.to_host(H.launch_mode(xd[i:i + 1], wd, 1e-6, v, None), inputs.BF16)
             assert np.array_equal(one[0], full[i])

@@ -44,11 +44,11 @@ def test_in_place(gpu_device, dtype, N):
     case = inputs.random_case(5, 840 + 2 * dtype, 97, N, dtype, 1e-6)
     want = oracle.rmsnorm_oracle(case["x"], case["w"], 1e-6, dtype)
     wd = H.to_device(case["w"], dtype, gpu_device)
-    for v in H.VARIANTS:
+    for v in H.ALL_MODES:
         xd = H.to_device(case["x"], dtype, gpu_device)
-        H.say(f"in place {case['name']} variant={binding.VARIANT_NAMES[v]}")
+        H.say(f"in place {case['name']} mode={H.mode_name(v)}")
         try:
-            binding.rmsnorm_fwd_variant(xd, wd, 1e-6, v, xd)
+            H.launch_mode(xd, wd, 1e-6, v, xd)
         except binding.RmsnormError as e:
             if e.status == binding.RMSNORM_ERR_UNSUPPORTED:
                 continue
@@ -78,9 +78,9 @@ def test_misaligned_base_pointers(gpu_device, dtype):
     torch.cuda.synchronize()
     assert H.guards_intact(whole, M, N, dtype, offset_elems=1)
     compare.check_parity(H.to_host(y, dtype), want, dtype, "misaligned bases")
-    for v in (binding.RMSNORM_VARIANT_WAVE, binding.RMSNORM_VARIANT_BLOCK):
+    for v in H.ALL_MODES[1:3] + H.ALL_MODES[4:]:
         with pytest.raises(binding.RmsnormError) as e:
-            binding.rmsnorm_fwd_variant(xd, wd, 1e-6, v, y)
+            H.launch_mode(xd, wd, 1e-6, v, y)
         assert e.value.status == binding.RMSNORM_ERR_UNSUPPORTED
 
 
