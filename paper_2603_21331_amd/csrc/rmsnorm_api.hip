@@ -20,7 +20,7 @@ constexpr int kWaveMaxChunks32 = 32;
 constexpr int kMidMaxChunks = 8;
 constexpr int kBlockMaxChunks = 16;
 constexpr int kBlockMaxThreads = 1024;
-constexpr int kTargetChunks = 4;       // automatic choice aims at <= 4 chunks per thread
+constexpr int kSmallRowVectors = 256;  // rows up to this many vectors: one wavefront per row
 constexpr int kGenericThreads = 256;
 constexpr int64_t kMaxGrid = 1 << 20;  // beyond this the kernels stride over rows
 
@@ -73,12 +73,19 @@ bool threads_can(int threads, int64_t nvec, int dtype) {
 
 bool wave_can(int64_t nvec, int dtype) { return threads_can(64, nvec, dtype); }
 
-// Threads per row: the smallest power of two from min_threads up that keeps the
-// row within kTargetChunks chunks per thread; rows longer than 1024 * 4 vectors
-// take 1024 threads with up to 16 chunks.  0 if the row does not fit at all.
+// Threads per row for the automatic path, from timing sweeps on MI355X over
+// N = 128 .. 131072 in all three dtypes: rows of up to 256 vectors (4 KiB) run
+// fastest with one wavefront per row; longer rows with 256 threads until a
+// thread would hold more than 8 chunks, then 512, then 1024.  Within those
+// bands the neighbouring choices are within about 2 % of each other.
+// min_threads > 64 restricts the choice to the workgroup-per-row kernels.
+// Returns 0 if the row does not fit in registers at all.
 int pick_threads(int64_t nvec, int min_threads, int dtype) {
-  for (int g = min_threads; g <= kBlockMaxThreads; g *= 2)
-    if ((nvec + g - 1) / g <= kTargetChunks && threads_can(g, nvec, dtype)) return g;
+  if (min_threads <= 64 && nvec <= kSmallRowVectors && threads_can(64, nvec, dtype)) return 64;
+  for (int g = 256; g <= kBlockMaxThreads; g *= 2)
+    if (g >= min_threads && threads_can(g, nvec, dtype) &&
+        (nvec + g - 1) / g <= kMidMaxChunks)
+      return g;
   return threads_can(kBlockMaxThreads, nvec, dtype) ? kBlockMaxThreads : 0;
 }
 
@@ -276,13 +283,11 @@ int rmsnorm_calib_copy(const void* src, void* dst, int64_t bytes, void* stream) 
   if (bytes < 0 || bytes % 16 != 0) return RMSNORM_ERR_INVALID_ARG;
   if (bytes == 0) return RMSNORM_OK;
   if (!src || !dst || !aligned16(src) || !aligned16(dst)) return RMSNORM_ERR_INVALID_ARG;
-  constexpr int kUnroll = 8, kThreads = 256;
   const int64_t nvec = bytes / 16;
-  int64_t blocks = (nvec + kUnroll * kThreads - 1) / (kUnroll * kThreads);
-  if (blocks > kMaxGrid) blocks = kMaxGrid;
-  hipLaunchKernelGGL((rms::calib_copy_kernel<kUnroll, kThreads>), dim3((unsigned)blocks),
-                     dim3(kThreads), 0, static_cast<hipStream_t>(stream),
-                     (const u32x4*)src, (u32x4*)dst, nvec);
+  int64_t blocks = (nvec + rms::kWave - 1) / rms::kWave;
+  if (blocks > (int64_t)1 << 24) blocks = (int64_t)1 << 24;
+  hipLaunchKernelGGL(rms::calib_copy_kernel, dim3((unsigned)blocks), dim3(rms::kWave), 0,
+                     static_cast<hipStream_t>(stream), (const u32x4*)src, (u32x4*)dst, nvec);
   return hipGetLastError() == hipSuccess ? RMSNORM_OK : RMSNORM_ERR_LAUNCH;
 }
 

@@ -45,6 +45,16 @@ __device__ __forceinline__ float lane_sum_sq(const u32x4 (&v)[CHUNKS]) {
   return (acc[0] + acc[1]) + (acc[2] + acc[3]);
 }
 
+// Makes the compiler treat the packed row as new values.  Without it the fp32
+// forms unpacked for the sum of squares are kept alive for the scale pass,
+// which multiplies the register footprint of the row by two (16-bit types) and
+// spills long rows; widening again costs one ALU operation per element.
+template <int CHUNKS>
+__device__ __forceinline__ void forget_unpacked(u32x4 (&v)[CHUNKS]) {
+#pragma unroll
+  for (int c = 0; c < CHUNKS; ++c) asm volatile("" : "+v"(v[c]));
+}
+
 // rstd = 1 / sqrt(sum / n + eps), with correctly rounded divide and root: it
 // runs once per row, so the "fast rsqrt" of the paper's starter would buy
 // nothing here and would cost accuracy on subnormal sums.
@@ -90,6 +100,10 @@ __global__ void __launch_bounds__(G)
 rmsnorm_row_kernel(const u32x4* x, const u32x4* __restrict__ w, u32x4* y,
                    int64_t M, int nvec, float n, float eps) {
   constexpr int WAVES = G / kWave;
+  // The weight chunks are fetched together with the row when the register
+  // budget allows (the launch bound caps a 1024-thread workgroup at 128 VGPRs),
+  // otherwise one by one in the epilogue.
+  constexpr bool W_EARLY = CHUNKS <= 8 || (G == kWave && CHUNKS <= 16);
   __shared__ float partial[2][WAVES];
   const int t = threadIdx.x;
   const int lane = t & (kWave - 1);
@@ -103,17 +117,22 @@ rmsnorm_row_kernel(const u32x4* x, const u32x4* __restrict__ w, u32x4* y,
     const u32x4* xr = x + row * nvec;
     u32x4* yr = y + row * nvec;
 
-    u32x4 v[CHUNKS], wv[CHUNKS];
+    u32x4 v[CHUNKS];
 #pragma unroll
     for (int c = 0; c < CHUNKS - 1; ++c) v[c] = load_vec<NT>(xr + c * G + t);
     v[CHUNKS - 1] = zero;
     if (last_ok) v[CHUNKS - 1] = load_vec<NT>(xr + last);
+
+    u32x4 wv[W_EARLY ? CHUNKS : 1];
+    if constexpr (W_EARLY) {
 #pragma unroll
-    for (int c = 0; c < CHUNKS - 1; ++c) wv[c] = w[c * G + t];
-    wv[CHUNKS - 1] = zero;
-    if (last_ok) wv[CHUNKS - 1] = w[last];
+      for (int c = 0; c < CHUNKS - 1; ++c) wv[c] = w[c * G + t];
+      wv[CHUNKS - 1] = zero;
+      if (last_ok) wv[CHUNKS - 1] = w[last];
+    }
 
     float total = wave_sum(lane_sum_sq<DT, CHUNKS>(v));
+    forget_unpacked<CHUNKS>(v);
     if constexpr (WAVES > 1) {
       if (lane == 0) partial[slot][wave] = total;
       __syncthreads();
@@ -125,9 +144,15 @@ rmsnorm_row_kernel(const u32x4* x, const u32x4* __restrict__ w, u32x4* y,
     const float rstd = row_rstd(total, n, eps);
 
 #pragma unroll
-    for (int c = 0; c < CHUNKS - 1; ++c)
-      store_vec<NT>(yr + c * G + t, scale_vec<DT>(v[c], wv[c], rstd));
-    if (last_ok) store_vec<NT>(yr + last, scale_vec<DT>(v[CHUNKS - 1], wv[CHUNKS - 1], rstd));
+    for (int c = 0; c < CHUNKS - 1; ++c) {
+      const int idx = c * G + t;
+      const u32x4 wc = W_EARLY ? wv[W_EARLY ? c : 0] : w[idx];
+      store_vec<NT>(yr + idx, scale_vec<DT>(v[c], wc, rstd));
+    }
+    if (last_ok) {
+      const u32x4 wc = W_EARLY ? wv[W_EARLY ? CHUNKS - 1 : 0] : w[last];
+      store_vec<NT>(yr + last, scale_vec<DT>(v[CHUNKS - 1], wc, rstd));
+    }
   }
 }
 
@@ -173,24 +198,15 @@ rmsnorm_generic_kernel(const void* x, const void* __restrict__ w, void* y,
   }
 }
 
-// Streaming copy with the kernels' access pattern (measurement aid).
-template <int UNROLL, int T>
-__global__ void __launch_bounds__(T)
+// Streaming copy (measurement aid): one 16-byte vector per thread, one wavefront
+// per workgroup.  Of the copy shapes tried on MI355X this finest one is the
+// fastest, so its rate serves as the practical ceiling for a stream that is half
+// reads and half writes.
+__global__ void __launch_bounds__(kWave)
 calib_copy_kernel(const u32x4* src, u32x4* dst, int64_t nvec) {
-  const int64_t tile = (int64_t)UNROLL * T;
-  for (int64_t base = (int64_t)blockIdx.x * tile; base < nvec; base += (int64_t)gridDim.x * tile) {
-    u32x4 v[UNROLL];
-#pragma unroll
-    for (int u = 0; u < UNROLL; ++u) {
-      const int64_t i = base + (int64_t)u * T + threadIdx.x;
-      if (i < nvec) v[u] = load_vec<true>(src + i);
-    }
-#pragma unroll
-    for (int u = 0; u < UNROLL; ++u) {
-      const int64_t i = base + (int64_t)u * T + threadIdx.x;
-      if (i < nvec) store_vec<true>(dst + i, v[u]);
-    }
-  }
+  const int64_t stride = (int64_t)gridDim.x * kWave;
+  for (int64_t i = (int64_t)blockIdx.x * kWave + threadIdx.x; i < nvec; i += stride)
+    store_vec<true>(dst + i, load_vec<true>(src + i));
 }
 
 }  // namespace rms

@@ -125,12 +125,15 @@ def test_automatic_threads_per_row():
     auto = binding.rmsnorm_auto_threads_per_row
     bf16, fp16, fp32 = binding.RMSNORM_DTYPE_BF16, binding.RMSNORM_DTYPE_FP16, binding.RMSNORM_DTYPE_FP32
     assert auto(8192, bf16) == 256          # headline shape: 4 chunks per thread
-    assert auto(4096, bf16) == 128
+    assert auto(4096, bf16) == 256
+    assert auto(2048, bf16) == 64
     assert auto(1024, fp32) == 64
     assert auto(768, fp16) == 64
     assert auto(5120, fp16) == 256
-    assert auto(13824, fp16) == 512
-    assert auto(8192, fp32) == 512
+    assert auto(13824, fp16) == 256
+    assert auto(8192, fp32) == 256
+    assert auto(32768, bf16) == 512
+    assert auto(65536, fp16) == 1024
     assert auto(131072, bf16) == 1024
     assert auto(131080, bf16) == 0          # too long for registers
     assert auto(1023, bf16) == 0            # rows not 16-byte aligned
@@ -146,6 +149,7 @@ def test_dispatch_choice_is_visible_without_a_launch():
     assert sel(P, P + 65536, P + 131072, 16, 8192, 2) == binding.RMSNORM_VARIANT_BLOCK
     assert sel(P, P + 65536, P + 131072, 16, 768, 1) == binding.RMSNORM_VARIANT_WAVE
     assert sel(P, P + 65536, P + 131072, 16, 13824, 1) == binding.RMSNORM_VARIANT_BLOCK
+    assert sel(P, P + 65536, P + 131072, 16, 2048, 2) == binding.RMSNORM_VARIANT_WAVE
     assert sel(P, P + 65536, P + 131072, 16, 1023, 1) == binding.RMSNORM_VARIANT_GENERIC
     assert sel(P + 2, P + 65536, P + 131072, 16, 1024, 1) == binding.RMSNORM_VARIANT_GENERIC
     assert sel(P, P + 65536, P + 131072, 16, 1 << 20, 2) == binding.RMSNORM_VARIANT_GENERIC
