@@ -23,8 +23,10 @@
  *    w has N elements.  x, w and y share one storage type `dtype`.
  *  - Pointers need only the alignment of their element type.  Rows whose
  *    start is 16-byte aligned (16-byte aligned bases and N * sizeof(dtype) a
- *    multiple of 16) take the vectorised kernels; anything else takes a slower
- *    element-wise kernel.  Neither case is an error.
+ *    multiple of 16) take the aligned kernels; other rows take the same
+ *    register-resident kernel with element-aligned 128-bit accesses; rows too
+ *    long for registers take a slower element-wise kernel that reads x twice.
+ *    None of these is an error.
  *  - y == x (exactly in place) is allowed; any other overlap of y with x or w
  *    is undefined.
  *  - Calls return RMSNORM_OK or a negative rmsnorm_status; nothing throws or
@@ -60,7 +62,11 @@ typedef enum {
   RMSNORM_VARIANT_WAVE = 1,    /* one 64-lane wavefront per row, row held in registers */
   RMSNORM_VARIANT_BLOCK = 2,   /* one workgroup of 128..1024 threads per row, row held in
                                   registers, cross-wave reduction in LDS */
-  RMSNORM_VARIANT_GENERIC = 3  /* element-wise, any alignment, any N; reads x twice */
+  RMSNORM_VARIANT_GENERIC = 3, /* element-wise, any alignment, any N; reads x twice */
+  RMSNORM_VARIANT_UNALIGNED = 4 /* row held in registers like WAVE / BLOCK, but addressed in
+                                   elements: 128-bit accesses that are only element-aligned
+                                   plus a scalar tail; any alignment, N up to
+                                   rmsnorm_unaligned_max_n(dtype) */
 } rmsnorm_variant;
 
 /*
@@ -83,7 +89,8 @@ int rmsnorm_fwd(const void* x, const void* w, void* y, int64_t M, int64_t N,
  * rmsnorm_variant.  RMSNORM_ERR_UNSUPPORTED if that kernel cannot take the
  * shape: WAVE needs 16-byte aligned rows of at most rmsnorm_wave_max_n(dtype)
  * elements, BLOCK needs 16-byte aligned rows of at most
- * rmsnorm_block_max_n(dtype) elements, GENERIC takes everything.
+ * rmsnorm_block_max_n(dtype) elements, UNALIGNED takes any alignment up to
+ * rmsnorm_unaligned_max_n(dtype) elements, GENERIC takes everything.
  */
 int rmsnorm_fwd_variant(const void* x, const void* w, void* y, int64_t M, int64_t N,
                         float eps, int dtype, void* stream, int variant);
@@ -122,6 +129,7 @@ int rmsnorm_select_variant(const void* x, const void* w, const void* y, int64_t 
 /* Largest N the register-resident kernels accept for `dtype`; 0 for a bad dtype. */
 int64_t rmsnorm_wave_max_n(int dtype);
 int64_t rmsnorm_block_max_n(int dtype);
+int64_t rmsnorm_unaligned_max_n(int dtype);
 
 /*
  * Plain device-to-device streaming copy of `bytes` bytes (a multiple of 16,

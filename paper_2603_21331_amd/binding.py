@@ -26,8 +26,9 @@ RMSNORM_VARIANT_AUTO = 0
 RMSNORM_VARIANT_WAVE = 1
 RMSNORM_VARIANT_BLOCK = 2
 RMSNORM_VARIANT_GENERIC = 3
+RMSNORM_VARIANT_UNALIGNED = 4
 
-VARIANT_NAMES = {0: "auto", 1: "wave", 2: "block", 3: "generic"}
+VARIANT_NAMES = {0: "auto", 1: "wave", 2: "block", 3: "generic", 4: "unaligned"}
 
 _lib = None
 
@@ -65,6 +66,8 @@ def load() -> ctypes.CDLL:
     lib.rmsnorm_wave_max_n.restype = i64
     lib.rmsnorm_block_max_n.argtypes = [i32]
     lib.rmsnorm_block_max_n.restype = i64
+    lib.rmsnorm_unaligned_max_n.argtypes = [i32]
+    lib.rmsnorm_unaligned_max_n.restype = i64
     lib.rmsnorm_calib_copy.argtypes = [vp, vp, i64, vp]
     lib.rmsnorm_calib_copy.restype = i32
     lib.rmsnorm_status_string.argtypes = [i32]
@@ -168,6 +171,10 @@ def rmsnorm_wave_max_n(dtype: int) -> int:
 
 def rmsnorm_block_max_n(dtype: int) -> int:
     return int(load().rmsnorm_block_max_n(int(dtype)))
+
+
+def rmsnorm_unaligned_max_n(dtype: int) -> int:
+    return int(load().rmsnorm_unaligned_max_n(int(dtype)))
 
 
 def rmsnorm_calib_copy(src, dst) -> None:

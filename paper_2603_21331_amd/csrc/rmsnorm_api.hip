@@ -89,8 +89,24 @@ int pick_threads(int64_t nvec, int min_threads, int dtype) {
   return threads_can(kBlockMaxThreads, nvec, dtype) ? kBlockMaxThreads : 0;
 }
 
+// Threads per row for the element-aligned kernel (fewer instantiations: 64
+// threads up to 4 chunks, 256 and 512 up to 8, 1024 up to 16); 0 if the row
+// does not fit in registers.
+int pick_threads_unaligned(int64_t nfull) {
+  if (nfull <= kSmallRowVectors) return 64;
+  if (nfull <= 256 * kMidMaxChunks) return 256;
+  if (nfull <= 512 * kMidMaxChunks) return 512;
+  if (nfull <= (int64_t)kBlockMaxThreads * kBlockMaxChunks) return 1024;
+  return 0;
+}
+
+int64_t full_groups_per_row(int64_t N, int dtype) { return N / (16 / elem_bytes(dtype)); }
+
 int choose(const void* x, const void* w, const void* y, int64_t N, int dtype) {
-  if (!rows_vectorisable(x, w, y, N, dtype)) return RMSNORM_VARIANT_GENERIC;
+  if (!rows_vectorisable(x, w, y, N, dtype)) {
+    return pick_threads_unaligned(full_groups_per_row(N, dtype)) ? RMSNORM_VARIANT_UNALIGNED
+                                                                  : RMSNORM_VARIANT_GENERIC;
+  }
   const int g = pick_threads(vectors_per_row(N, dtype), 64, dtype);
   if (g == 0) return RMSNORM_VARIANT_GENERIC;
   return g == 64 ? RMSNORM_VARIANT_WAVE : RMSNORM_VARIANT_BLOCK;
@@ -114,6 +130,14 @@ void launch_row(const Args& a) {
                      dim3((unsigned)blocks), dim3(G), 0, a.stream,
                      (const u32x4*)a.x, (const u32x4*)a.w, (u32x4*)a.y, a.M, a.nvec,
                      (float)a.N, a.eps);
+}
+
+template <int DT, int CHUNKS, int G>
+void launch_row_unaligned(const Args& a, int nfull) {
+  const int64_t blocks = a.M < kMaxGrid ? a.M : kMaxGrid;
+  hipLaunchKernelGGL((rms::rmsnorm_row_unaligned_kernel<DT, CHUNKS, G, true>),
+                     dim3((unsigned)blocks), dim3(G), 0, a.stream,
+                     a.x, a.w, a.y, a.M, a.N, nfull, (float)a.N, a.eps);
 }
 
 template <int DT>
@@ -187,11 +211,52 @@ int dispatch_row(const Args& a, int threads) {
   return RMSNORM_OK;
 }
 
-// threads == 0 means the element-wise kernel.
+// Launches the element-aligned row kernel.  The caller has checked that the row fits.
+template <int DT>
+int dispatch_row_unaligned(const Args& a) {
+  const int nfull = (int)full_groups_per_row(a.N, DT == rms::kFp32 ? RMSNORM_DTYPE_FP32 : RMSNORM_DTYPE_FP16);
+  const int threads = pick_threads_unaligned(nfull);
+  int chunks = (nfull + threads - 1) / threads;
+  if (chunks < 1) chunks = 1;
+  switch (threads) {
+    case 64:
+#define RMS_L(c) launch_row_unaligned<DT, c, 64>(a, nfull)
+      switch (chunks) {
+        RMS_CASE(1, RMS_L(1)) RMS_CASE(2, RMS_L(2)) RMS_CASE(3, RMS_L(3)) RMS_CASE(4, RMS_L(4))
+        default: return RMSNORM_ERR_UNSUPPORTED;
+      }
+#undef RMS_L
+      break;
+    case 256:
+#define RMS_L(c) launch_row_unaligned<DT, c, 256>(a, nfull)
+      switch (chunks) { RMS_CASES_1_8(RMS_L) default: return RMSNORM_ERR_UNSUPPORTED; }
+#undef RMS_L
+      break;
+    case 512:
+#define RMS_L(c) launch_row_unaligned<DT, c, 512>(a, nfull)
+      switch (chunks) { RMS_CASES_1_8(RMS_L) default: return RMSNORM_ERR_UNSUPPORTED; }
+#undef RMS_L
+      break;
+    case 1024:
+#define RMS_L(c) launch_row_unaligned<DT, c, 1024>(a, nfull)
+      switch (chunks) {
+        RMS_CASES_1_8(RMS_L) RMS_CASES_9_16(RMS_L)
+        default: return RMSNORM_ERR_UNSUPPORTED;
+      }
+#undef RMS_L
+      break;
+    default:
+      return RMSNORM_ERR_UNSUPPORTED;
+  }
+  return RMSNORM_OK;
+}
+
+// threads == 0 means the element-wise kernel, threads == -1 the element-aligned row kernel.
 template <int DT>
 int run_typed(const Args& a, int threads) {
   int rc = RMSNORM_OK;
   if (threads == 0) launch_generic<DT>(a);
+  else if (threads == -1) rc = dispatch_row_unaligned<DT>(a);
   else rc = dispatch_row<DT>(a, threads);
   if (rc != RMSNORM_OK) return rc;
   return hipGetLastError() == hipSuccess ? RMSNORM_OK : RMSNORM_ERR_LAUNCH;
@@ -202,7 +267,7 @@ int run(const void* x, const void* w, void* y, int64_t M, int64_t N, float eps, 
         void* stream, int variant, int threads) {
   int rc = check_args(x, w, y, M, N, eps, dtype);
   if (rc != RMSNORM_OK) return rc;
-  if (variant < -1 || variant > RMSNORM_VARIANT_GENERIC) return RMSNORM_ERR_INVALID_ARG;
+  if (variant < -1 || variant > RMSNORM_VARIANT_UNALIGNED) return RMSNORM_ERR_INVALID_ARG;
   if (variant == -1 && max_chunks_for(threads, dtype) == 0) return RMSNORM_ERR_INVALID_ARG;
   if (M == 0) return RMSNORM_OK;
 
@@ -220,6 +285,10 @@ int run(const void* x, const void* w, void* y, int64_t M, int64_t N, float eps, 
     case RMSNORM_VARIANT_BLOCK:
       threads = vec_ok ? pick_threads(nvec, 128, dtype) : 0;
       if (threads == 0) return RMSNORM_ERR_UNSUPPORTED;
+      break;
+    case RMSNORM_VARIANT_UNALIGNED:
+      if (pick_threads_unaligned(full_groups_per_row(N, dtype)) == 0) return RMSNORM_ERR_UNSUPPORTED;
+      threads = -1;
       break;
     default:
       threads = 0;
@@ -277,6 +346,11 @@ int64_t rmsnorm_wave_max_n(int dtype) {
 int64_t rmsnorm_block_max_n(int dtype) {
   const int b = elem_bytes(dtype);
   return b ? (int64_t)kBlockMaxThreads * kBlockMaxChunks * (16 / b) : 0;
+}
+
+int64_t rmsnorm_unaligned_max_n(int dtype) {
+  const int b = elem_bytes(dtype);
+  return b ? (int64_t)kBlockMaxThreads * kBlockMaxChunks * (16 / b) + (16 / b - 1) : 0;
 }
 
 int rmsnorm_calib_copy(const void* src, void* dst, int64_t bytes, void* stream) {

@@ -15,9 +15,11 @@
 //                                      no barrier.
 //  * rmsnorm_row_kernel<.., G > 64>  : one workgroup per row, per-wave partial
 //                                      sums combined through LDS in wave order.
+//  * rmsnorm_row_unaligned_kernel    : the same, for rows that are not 16-byte
+//                                      aligned (element-aligned 128-bit accesses
+//                                      plus a scalar tail).
 //  * rmsnorm_generic_kernel          : element-wise two-pass fallback for rows
-//                                      that are not 16-byte aligned or too long
-//                                      for registers.
+//                                      too long for registers.
 //
 // All sums are fp32, in an order fixed by (kernel, shape) alone: no atomics,
 // so repeated runs give identical bits.
@@ -153,6 +155,79 @@ rmsnorm_row_kernel(const u32x4* x, const u32x4* __restrict__ w, u32x4* y,
       const u32x4 wc = W_EARLY ? wv[W_EARLY ? CHUNKS - 1 : 0] : w[last];
       store_vec<NT>(yr + last, scale_vec<DT>(v[CHUNKS - 1], wc, rstd));
     }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// The same register-resident kernel for rows that are NOT 16-byte aligned (odd
+// N such as 1023 or 4097, or base pointers off a 16-byte boundary).  Rows are
+// addressed in elements: thread t holds the 16-byte groups c * G + t of the
+// row's floor(N / VEC) full groups, read and written with element-aligned
+// 128-bit accesses, and threads 0 .. N % VEC - 1 each take one of the leftover
+// elements at the end of the row.  x is still read exactly once.
+// ---------------------------------------------------------------------------
+template <int DT, int CHUNKS, int G, bool NT>
+__global__ void __launch_bounds__(G)
+rmsnorm_row_unaligned_kernel(const void* x, const void* __restrict__ w, void* y,
+                             int64_t M, int64_t N, int nfull, float n, float eps) {
+  using S = Storage<DT>;
+  constexpr int WAVES = G / kWave;
+  constexpr int VEC = S::kVec;
+  constexpr int kGroupBytes = 16;
+  __shared__ float partial[2][WAVES];
+  const int t = threadIdx.x;
+  const int lane = t & (kWave - 1);
+  const int wave = t / kWave;
+  const int last = (CHUNKS - 1) * G + t;
+  const bool last_ok = last < nfull;
+  const int rem = (int)(N - (int64_t)nfull * VEC);
+  const bool tail_ok = t < rem;
+  const int64_t tail_col = (int64_t)nfull * VEC + t;
+  const u32x4 zero = {0u, 0u, 0u, 0u};
+  const char* wb = static_cast<const char*>(w);
+  int slot = 0;
+
+  for (int64_t row = blockIdx.x; row < M; row += gridDim.x) {
+    const char* xr = static_cast<const char*>(x) + row * N * S::kBytes;
+    char* yr = static_cast<char*>(y) + row * N * S::kBytes;
+
+    u32x4 v[CHUNKS], wv[CHUNKS];
+#pragma unroll
+    for (int c = 0; c < CHUNKS - 1; ++c)
+      v[c] = load_vec_unaligned<NT>(xr + (int64_t)(c * G + t) * kGroupBytes);
+    v[CHUNKS - 1] = zero;
+    if (last_ok) v[CHUNKS - 1] = load_vec_unaligned<NT>(xr + (int64_t)last * kGroupBytes);
+    float tail_x = 0.f, tail_w = 0.f;
+    if (tail_ok) {
+      tail_x = S::load_one(x, row * N + tail_col);
+      tail_w = S::load_one(w, tail_col);
+    }
+#pragma unroll
+    for (int c = 0; c < CHUNKS - 1; ++c)
+      wv[c] = load_vec_unaligned<false>(wb + (int64_t)(c * G + t) * kGroupBytes);
+    wv[CHUNKS - 1] = zero;
+    if (last_ok) wv[CHUNKS - 1] = load_vec_unaligned<false>(wb + (int64_t)last * kGroupBytes);
+
+    float total = wave_sum(__builtin_fmaf(tail_x, tail_x, lane_sum_sq<DT, CHUNKS>(v)));
+    forget_unpacked<CHUNKS>(v);
+    if constexpr (WAVES > 1) {
+      if (lane == 0) partial[slot][wave] = total;
+      __syncthreads();
+      total = partial[slot][0];
+#pragma unroll
+      for (int k = 1; k < WAVES; ++k) total += partial[slot][k];
+      slot ^= 1;
+    }
+    const float rstd = row_rstd(total, n, eps);
+
+#pragma unroll
+    for (int c = 0; c < CHUNKS - 1; ++c)
+      store_vec_unaligned<NT>(yr + (int64_t)(c * G + t) * kGroupBytes,
+                              scale_vec<DT>(v[c], wv[c], rstd));
+    if (last_ok)
+      store_vec_unaligned<NT>(yr + (int64_t)last * kGroupBytes,
+                              scale_vec<DT>(v[CHUNKS - 1], wv[CHUNKS - 1], rstd));
+    if (tail_ok) S::store_one(y, row * N + tail_col, (tail_x * rstd) * tail_w);
   }
 }
 

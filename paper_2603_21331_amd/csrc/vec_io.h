@@ -33,6 +33,23 @@ __device__ __forceinline__ void store_vec(u32x4* p, u32x4 v) {
   else *p = v;
 }
 
+// The same 16-byte access through a pointer that is only element-aligned.  The
+// amdhsa ABI runs the memory pipeline in unaligned-access mode, and the compiler
+// knows it: these still compile to single global_load/store_dwordx4 instructions.
+typedef u32x4 u32x4_unaligned __attribute__((aligned(2)));
+
+template <bool NT>
+__device__ __forceinline__ u32x4 load_vec_unaligned(const void* p) {
+  if constexpr (NT) return __builtin_nontemporal_load(static_cast<const u32x4_unaligned*>(p));
+  else return *static_cast<const u32x4_unaligned*>(p);
+}
+
+template <bool NT>
+__device__ __forceinline__ void store_vec_unaligned(void* p, u32x4 v) {
+  if constexpr (NT) __builtin_nontemporal_store(v, static_cast<u32x4_unaligned*>(p));
+  else *static_cast<u32x4_unaligned*>(p) = v;
+}
+
 __device__ __forceinline__ float as_f32(uint32_t u) { return __builtin_bit_cast(float, u); }
 __device__ __forceinline__ uint32_t as_u32(float f) { return __builtin_bit_cast(uint32_t, f); }
 

@@ -52,7 +52,10 @@ def test_limits():
     assert binding.rmsnorm_wave_max_n(binding.RMSNORM_DTYPE_FP16) == 8192
     assert binding.rmsnorm_wave_max_n(binding.RMSNORM_DTYPE_FP32) == 8192
     assert binding.rmsnorm_block_max_n(binding.RMSNORM_DTYPE_BF16) >= 32768
+    assert binding.rmsnorm_unaligned_max_n(binding.RMSNORM_DTYPE_BF16) == 131079
+    assert binding.rmsnorm_unaligned_max_n(binding.RMSNORM_DTYPE_FP32) == 65539
     assert binding.rmsnorm_wave_max_n(9) == 0 and binding.rmsnorm_block_max_n(-1) == 0
+    assert binding.rmsnorm_unaligned_max_n(5) == 0
 
 
 # The calls below never reach the device: argument checks come first, and the
@@ -95,6 +98,11 @@ def test_unknown_variant_and_unsupported_shapes():
     lib = binding.load()
     assert lib.rmsnorm_fwd_variant(P, P + 4096, P + 8192, 4, 8, 1e-6, 2, None, 9) == \
         binding.RMSNORM_ERR_INVALID_ARG
+    assert lib.rmsnorm_fwd_variant(P, P + 4096, P + 8192, 4, 8, 1e-6, 2, None, -1) == \
+        binding.RMSNORM_ERR_INVALID_ARG
+    # too long for the element-aligned register kernel
+    assert lib.rmsnorm_fwd_variant(P, P + (1 << 22), P + (2 << 22), 1, 131081, 1e-6, 2, None,
+                                   binding.RMSNORM_VARIANT_UNALIGNED) == binding.RMSNORM_ERR_UNSUPPORTED
     # a row of 7 bf16 elements is not 16-byte aligned: the vector kernels must refuse
     for v in (binding.RMSNORM_VARIANT_WAVE, binding.RMSNORM_VARIANT_BLOCK):
         assert lib.rmsnorm_fwd_variant(P, P + 4096, P + 8192, 4, 7, 1e-6, 2, None, v) == \
@@ -150,8 +158,11 @@ def test_dispatch_choice_is_visible_without_a_launch():
     assert sel(P, P + 65536, P + 131072, 16, 768, 1) == binding.RMSNORM_VARIANT_WAVE
     assert sel(P, P + 65536, P + 131072, 16, 13824, 1) == binding.RMSNORM_VARIANT_BLOCK
     assert sel(P, P + 65536, P + 131072, 16, 2048, 2) == binding.RMSNORM_VARIANT_WAVE
-    assert sel(P, P + 65536, P + 131072, 16, 1023, 1) == binding.RMSNORM_VARIANT_GENERIC
-    assert sel(P + 2, P + 65536, P + 131072, 16, 1024, 1) == binding.RMSNORM_VARIANT_GENERIC
+    assert sel(P, P + 65536, P + 131072, 16, 1023, 1) == binding.RMSNORM_VARIANT_UNALIGNED
+    assert sel(P + 2, P + 65536, P + 131072, 16, 1024, 1) == binding.RMSNORM_VARIANT_UNALIGNED
+    assert sel(P, P + 65536, P + 131072, 16, 3, 0) == binding.RMSNORM_VARIANT_UNALIGNED
+    assert sel(P, P + 65536, P + 131072, 16, 131079, 2) == binding.RMSNORM_VARIANT_UNALIGNED
+    assert sel(P, P + 65536, P + 131072, 16, 131081, 2) == binding.RMSNORM_VARIANT_GENERIC
     assert sel(P, P + 65536, P + 131072, 16, 1 << 20, 2) == binding.RMSNORM_VARIANT_GENERIC
     assert sel(P, P + 65536, P + 131072, 16, 0, 2) == binding.RMSNORM_ERR_INVALID_ARG
 

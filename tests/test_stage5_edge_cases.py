@@ -18,7 +18,8 @@ DTYPES = [inputs.FP32, inputs.FP16, inputs.BF16]
 
 @pytest.mark.parametrize("dtype", DTYPES)
 @pytest.mark.parametrize("M,N", [(1023, 1023), (33, 4097), (129, 1537), (4097, 24), (1537, 1023),
-                                 (5, 8193), (3, 40001)])
+                                 (5, 8193), (3, 40001), (65, 2049), (9, 16391), (7, 33001),
+                                 (3, 131079), (2, 131080), (6, 7), (6, 9), (11, 3)])
 def test_paper_edge_dims(gpu_device, M, N, dtype):
     H.check_case(inputs.random_case(5, 800 + 2 * dtype, M, N, dtype, 1e-6), gpu_device)
 
@@ -60,7 +61,8 @@ def test_in_place(gpu_device, dtype, N):
 @pytest.mark.parametrize("dtype", DTYPES)
 def test_misaligned_base_pointers(gpu_device, dtype):
     """An aligned N with bases one element off a 16-byte boundary: dispatch must fall back
-    to the element-wise kernel, stay inside the buffers and match the oracle."""
+    to the element-aligned kernel, stay inside the buffers and match the oracle; so must
+    the element-wise kernel."""
     M, N = 41, 2048
     case = inputs.random_case(5, 860 + 2 * dtype, M, N, dtype, 1e-6)
     want = oracle.rmsnorm_oracle(case["x"], case["w"], 1e-6, dtype)
@@ -72,13 +74,19 @@ def test_misaligned_base_pointers(gpu_device, dtype):
     xd.copy_(H.to_device(case["x"], dtype, gpu_device))
     wd.copy_(H.to_device(case["w"], dtype, gpu_device))
     whole, y = H.alloc_guarded(M, N, dtype, gpu_device, offset_elems=1)
-    assert binding.rmsnorm_select_variant(xd, wd, y) == binding.RMSNORM_VARIANT_GENERIC
+    assert binding.rmsnorm_select_variant(xd, wd, y) == binding.RMSNORM_VARIANT_UNALIGNED
     H.say(f"misaligned bases {inputs.DTYPE_NAMES[dtype]}")
     binding.rmsnorm_fwd(xd, wd, 1e-6, y)
     torch.cuda.synchronize()
     assert H.guards_intact(whole, M, N, dtype, offset_elems=1)
     compare.check_parity(H.to_host(y, dtype), want, dtype, "misaligned bases")
-    for v in H.ALL_MODES[1:3] + H.ALL_MODES[4:]:
+    whole2, y2 = H.alloc_guarded(M, N, dtype, gpu_device, offset_elems=3)
+    binding.rmsnorm_fwd_variant(xd, wd, 1e-6, binding.RMSNORM_VARIANT_GENERIC, y2)
+    torch.cuda.synchronize()
+    assert H.guards_intact(whole2, M, N, dtype, offset_elems=3)
+    compare.check_parity(H.to_host(y2, dtype), want, dtype, "misaligned bases, element-wise")
+    for v in (binding.RMSNORM_VARIANT_WAVE, binding.RMSNORM_VARIANT_BLOCK) + \
+            tuple(("threads", g) for g in H.THREADS):
         with pytest.raises(binding.RmsnormError) as e:
             H.launch_mode(xd, wd, 1e-6, v, y)
         assert e.value.status == binding.RMSNORM_ERR_UNSUPPORTED
