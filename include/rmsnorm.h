@@ -63,10 +63,12 @@ typedef enum {
   RMSNORM_VARIANT_BLOCK = 2,   /* one workgroup of 128..1024 threads per row, row held in
                                   registers, cross-wave reduction in LDS */
   RMSNORM_VARIANT_GENERIC = 3, /* element-wise, any alignment, any N; reads x twice */
-  RMSNORM_VARIANT_UNALIGNED = 4 /* row held in registers like WAVE / BLOCK, but addressed in
+  RMSNORM_VARIANT_UNALIGNED = 4, /* row held in registers like WAVE / BLOCK, but addressed in
                                    elements: 128-bit accesses that are only element-aligned
                                    plus a scalar tail; any alignment, N up to
                                    rmsnorm_unaligned_max_n(dtype) */
+  RMSNORM_VARIANT_SUBWAVE = 5   /* 8, 16 or 32 lanes per row, several rows per wavefront;
+                                   16-byte aligned rows of at most 1 KiB */
 } rmsnorm_variant;
 
 /*
@@ -87,8 +89,8 @@ int rmsnorm_fwd(const void* x, const void* w, void* y, int64_t M, int64_t N,
  * Same operation with the kernel choice forced (tests and benchmarks use this
  * to run every kernel on every shape it supports).  `variant` is an
  * rmsnorm_variant.  RMSNORM_ERR_UNSUPPORTED if that kernel cannot take the
- * shape: WAVE needs 16-byte aligned rows of at most rmsnorm_wave_max_n(dtype)
- * elements, BLOCK needs 16-byte aligned rows of at most
+ * shape: SUBWAVE needs 16-byte aligned rows of at most 1 KiB, WAVE needs
+ * 16-byte aligned rows of at most rmsnorm_wave_max_n(dtype) elements, BLOCK needs 16-byte aligned rows of at most
  * rmsnorm_block_max_n(dtype) elements, UNALIGNED takes any alignment up to
  * rmsnorm_unaligned_max_n(dtype) elements, GENERIC takes everything.
  */
@@ -99,13 +101,13 @@ int rmsnorm_fwd_variant(const void* x, const void* w, void* y, int64_t M, int64_
  * Same operation with the number of threads that share one row forced: the
  * block-size axis that the paper's optimisation playbook sweeps first
  * (Section 3.3, tier 1; Section 7.3 reports it as the largest single gain for
- * RMSNorm).  threads_per_row is 64 (one wavefront per row), 128, 256, 512 or
- * 1024 (one workgroup per row); anything else is RMSNORM_ERR_INVALID_ARG.
- * Each thread then holds ceil(N * sizeof(dtype) / 16 / threads_per_row)
- * 16-byte chunks of the row in registers; RMSNORM_ERR_UNSUPPORTED if that
- * exceeds what is built for the thread count (64: 16 chunks, 32 for fp32;
- * 128, 256, 512: 8 chunks; 1024: 16 chunks) or if the rows are not 16-byte
- * aligned.  Tests use it to run every instantiation; tuning sweeps use it to
+ * RMSNorm).  threads_per_row is 8, 16 or 32 (several rows per wavefront), 64
+ * (one wavefront per row), 128, 256, 512 or 1024 (one workgroup per row);
+ * anything else is RMSNORM_ERR_INVALID_ARG.  Each thread then holds
+ * ceil(N * sizeof(dtype) / 16 / threads_per_row) 16-byte chunks of the row in
+ * registers; RMSNORM_ERR_UNSUPPORTED if that exceeds what is built for the
+ * thread count (8, 16, 32: 2 chunks; 64: 16 chunks, 32 for fp32; 128, 256,
+ * 512: 8 chunks; 1024: 16 chunks) or if the rows are not 16-byte aligned.  Tests use it to run every instantiation; tuning sweeps use it to
  * check the automatic choice.
  */
 int rmsnorm_fwd_tuned(const void* x, const void* w, void* y, int64_t M, int64_t N,

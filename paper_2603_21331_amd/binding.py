@@ -27,8 +27,9 @@ RMSNORM_VARIANT_WAVE = 1
 RMSNORM_VARIANT_BLOCK = 2
 RMSNORM_VARIANT_GENERIC = 3
 RMSNORM_VARIANT_UNALIGNED = 4
+RMSNORM_VARIANT_SUBWAVE = 5
 
-VARIANT_NAMES = {0: "auto", 1: "wave", 2: "block", 3: "generic", 4: "unaligned"}
+VARIANT_NAMES = {0: "auto", 1: "wave", 2: "block", 3: "generic", 4: "unaligned", 5: "subwave"}
 
 _lib = None
 

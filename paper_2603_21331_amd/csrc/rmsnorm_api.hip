@@ -12,6 +12,7 @@ using rms::u32x4;
 
 // Instantiated (threads per row : chunks per thread) combinations.  A chunk is
 // one 16-byte vector per thread.
+//   8, 16, 32 : 1..2             several rows per wavefront, rows up to 1 KiB
 //   64   : 1..16 (fp32: 1..32)   one wavefront per row, N <= 8192
 //   128, 256, 512 : 1..8
 //   1024 : 1..16                 N <= 131072 (16-bit) / 65536 (fp32)
@@ -57,8 +58,11 @@ bool rows_vectorisable(const void* x, const void* w, const void* y, int64_t N, i
 
 int64_t vectors_per_row(int64_t N, int dtype) { return N * elem_bytes(dtype) / 16; }
 
+constexpr int kSubwaveMaxChunks = 2;
+
 int max_chunks_for(int threads, int dtype) {
   switch (threads) {
+    case 8: case 16: case 32: return kSubwaveMaxChunks;
     case 64: return wave_max_chunks(dtype);
     case 128: case 256: case 512: return kMidMaxChunks;
     case 1024: return kBlockMaxChunks;
@@ -81,6 +85,10 @@ bool wave_can(int64_t nvec, int dtype) { return threads_can(64, nvec, dtype); }
 // min_threads > 64 restricts the choice to the workgroup-per-row kernels.
 // Returns 0 if the row does not fit in registers at all.
 int pick_threads(int64_t nvec, int min_threads, int dtype) {
+  if (min_threads <= 8) {
+    for (int l = 8; l <= 32; l *= 2)
+      if (nvec <= l) return l;
+  }
   if (min_threads <= 64 && nvec <= kSmallRowVectors && threads_can(64, nvec, dtype)) return 64;
   for (int g = 256; g <= kBlockMaxThreads; g *= 2)
     if (g >= min_threads && threads_can(g, nvec, dtype) &&
@@ -107,8 +115,9 @@ int choose(const void* x, const void* w, const void* y, int64_t N, int dtype) {
     return pick_threads_unaligned(full_groups_per_row(N, dtype)) ? RMSNORM_VARIANT_UNALIGNED
                                                                   : RMSNORM_VARIANT_GENERIC;
   }
-  const int g = pick_threads(vectors_per_row(N, dtype), 64, dtype);
+  const int g = pick_threads(vectors_per_row(N, dtype), 8, dtype);
   if (g == 0) return RMSNORM_VARIANT_GENERIC;
+  if (g < 64) return RMSNORM_VARIANT_SUBWAVE;
   return g == 64 ? RMSNORM_VARIANT_WAVE : RMSNORM_VARIANT_BLOCK;
 }
 
@@ -128,6 +137,17 @@ void launch_row(const Args& a) {
   const int64_t blocks = a.M < kMaxGrid ? a.M : kMaxGrid;
   hipLaunchKernelGGL((rms::rmsnorm_row_kernel<DT, CHUNKS, G, true>),
                      dim3((unsigned)blocks), dim3(G), 0, a.stream,
+                     (const u32x4*)a.x, (const u32x4*)a.w, (u32x4*)a.y, a.M, a.nvec,
+                     (float)a.N, a.eps);
+}
+
+template <int DT, int CHUNKS, int L>
+void launch_subwave(const Args& a) {
+  constexpr int kRows = rms::kWave / L;
+  int64_t blocks = (a.M + kRows - 1) / kRows;
+  if (blocks > ((int64_t)1 << 24)) blocks = (int64_t)1 << 24;
+  hipLaunchKernelGGL((rms::rmsnorm_subwave_kernel<DT, CHUNKS, L, true>),
+                     dim3((unsigned)blocks), dim3(rms::kWave), 0, a.stream,
                      (const u32x4*)a.x, (const u32x4*)a.w, (u32x4*)a.y, a.M, a.nvec,
                      (float)a.N, a.eps);
 }
@@ -167,6 +187,15 @@ template <int DT>
 int dispatch_row(const Args& a, int threads) {
   const int chunks = (a.nvec + threads - 1) / threads;
   switch (threads) {
+    case 8:
+      if (chunks == 1) launch_subwave<DT, 1, 8>(a); else launch_subwave<DT, 2, 8>(a);
+      break;
+    case 16:
+      if (chunks == 1) launch_subwave<DT, 1, 16>(a); else launch_subwave<DT, 2, 16>(a);
+      break;
+    case 32:
+      if (chunks == 1) launch_subwave<DT, 1, 32>(a); else launch_subwave<DT, 2, 32>(a);
+      break;
     case 64:
 #define RMS_L(c) launch_row<DT, c, 64>(a)
       if constexpr (DT == rms::kFp32) {
@@ -267,7 +296,7 @@ int run(const void* x, const void* w, void* y, int64_t M, int64_t N, float eps, 
         void* stream, int variant, int threads) {
   int rc = check_args(x, w, y, M, N, eps, dtype);
   if (rc != RMSNORM_OK) return rc;
-  if (variant < -1 || variant > RMSNORM_VARIANT_UNALIGNED) return RMSNORM_ERR_INVALID_ARG;
+  if (variant < -1 || variant > RMSNORM_VARIANT_SUBWAVE) return RMSNORM_ERR_INVALID_ARG;
   if (variant == -1 && max_chunks_for(threads, dtype) == 0) return RMSNORM_ERR_INVALID_ARG;
   if (M == 0) return RMSNORM_OK;
 
@@ -281,6 +310,11 @@ int run(const void* x, const void* w, void* y, int64_t M, int64_t N, float eps, 
     case RMSNORM_VARIANT_WAVE:
       if (!(vec_ok && wave_can(nvec, dtype))) return RMSNORM_ERR_UNSUPPORTED;
       threads = 64;
+      break;
+    case RMSNORM_VARIANT_SUBWAVE:
+      if (!vec_ok) return RMSNORM_ERR_UNSUPPORTED;
+      threads = nvec <= 8 ? 8 : nvec <= 16 ? 16 : 32;
+      if (!threads_can(threads, nvec, dtype)) return RMSNORM_ERR_UNSUPPORTED;
       break;
     case RMSNORM_VARIANT_BLOCK:
       threads = vec_ok ? pick_threads(nvec, 128, dtype) : 0;
@@ -328,7 +362,7 @@ int rmsnorm_auto_threads_per_row(int64_t N, int dtype) {
   const int b = elem_bytes(dtype);
   if (b == 0 || N <= 0) return RMSNORM_ERR_INVALID_ARG;
   if ((N * b) % 16 != 0) return 0;
-  return pick_threads(vectors_per_row(N, dtype), 64, dtype);
+  return pick_threads(vectors_per_row(N, dtype), 8, dtype);
 }
 
 int rmsnorm_select_variant(const void* x, const void* w, const void* y, int64_t M, int64_t N,

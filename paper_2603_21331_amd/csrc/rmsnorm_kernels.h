@@ -15,6 +15,8 @@
 //                                      no barrier.
 //  * rmsnorm_row_kernel<.., G > 64>  : one workgroup per row, per-wave partial
 //                                      sums combined through LDS in wave order.
+//  * rmsnorm_subwave_kernel          : 8, 16 or 32 lanes per row, several rows per
+//                                      wavefront, for rows of at most 1 KiB.
 //  * rmsnorm_row_unaligned_kernel    : the same, for rows that are not 16-byte
 //                                      aligned (element-aligned 128-bit accesses
 //                                      plus a scalar tail).
@@ -154,6 +156,56 @@ rmsnorm_row_kernel(const u32x4* x, const u32x4* __restrict__ w, u32x4* y,
     if (last_ok) {
       const u32x4 wc = W_EARLY ? wv[W_EARLY ? CHUNKS - 1 : 0] : w[last];
       store_vec<NT>(yr + last, scale_vec<DT>(v[CHUNKS - 1], wc, rstd));
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Short rows (at most 32 * CHUNKS vectors, e.g. the 128-element rows of a
+// per-head normalisation): one wavefront would leave most of its lanes idle on
+// a row of 256 bytes, so L = 8, 16 or 32 lanes share a row and a wavefront
+// takes 64 / L consecutive rows at once.  When the row fills its lanes exactly
+// the wavefront's loads are still one contiguous kilobyte.  The reduction stays
+// inside the lane group (DPP, plus one swizzle for L = 32); no LDS storage, no
+// barrier.  Lanes whose row lies past M keep running with zeros so that the
+// cross-lane steps see all 64 lanes active; only their loads and stores are
+// predicated off.
+// ---------------------------------------------------------------------------
+template <int DT, int CHUNKS, int L, bool NT>
+__global__ void __launch_bounds__(kWave)
+rmsnorm_subwave_kernel(const u32x4* x, const u32x4* __restrict__ w, u32x4* y,
+                       int64_t M, int nvec, float n, float eps) {
+  constexpr int ROWS = kWave / L;
+  const int lane = threadIdx.x;
+  const int s = lane % L;
+  const int r = lane / L;
+  const u32x4 zero = {0u, 0u, 0u, 0u};
+
+  for (int64_t base = (int64_t)blockIdx.x * ROWS; base < M; base += (int64_t)gridDim.x * ROWS) {
+    const int64_t row = base + r;
+    const bool row_ok = row < M;
+    const u32x4* xr = x + row * nvec;
+    u32x4* yr = y + row * nvec;
+
+    u32x4 v[CHUNKS], wv[CHUNKS];
+#pragma unroll
+    for (int c = 0; c < CHUNKS; ++c) {
+      const int idx = c * L + s;
+      const bool ok = row_ok && idx < nvec;
+      v[c] = zero;
+      wv[c] = zero;
+      if (ok) {
+        v[c] = load_vec<NT>(xr + idx);
+        wv[c] = w[idx];
+      }
+    }
+    const float total = subwave_sum<L>(lane_sum_sq<DT, CHUNKS>(v));
+    forget_unpacked<CHUNKS>(v);
+    const float rstd = row_rstd(total, n, eps);
+#pragma unroll
+    for (int c = 0; c < CHUNKS; ++c) {
+      const int idx = c * L + s;
+      if (row_ok && idx < nvec) store_vec<NT>(yr + idx, scale_vec<DT>(v[c], wv[c], rstd));
     }
   }
 }

@@ -38,4 +38,23 @@ __device__ __forceinline__ float wave_sum(float v) {
   return (r0 + r1) + (r2 + r3);
 }
 
+// Sum over aligned groups of L = 8, 16 or 32 lanes, result in every lane of the
+// group: the first three or four DPP steps of wave_sum, then for L = 32 one
+// ds_swizzle that swaps neighbouring 16-lane rows (a cross-lane move in the LDS
+// crossbar; no memory is touched).  Must be called with all 64 lanes active.
+template <int L>
+__device__ __forceinline__ float subwave_sum(float v) {
+  static_assert(L == 8 || L == 16 || L == 32, "group size");
+  v = add_dpp<0xB1>(v);
+  v = add_dpp<0x4E>(v);
+  v = add_dpp<0x141>(v);
+  if constexpr (L >= 16) v = add_dpp<0x140>(v);
+  if constexpr (L == 32) {
+    // BitMode swizzle: and_mask 0x1F, or_mask 0, xor_mask 0x10 -> lane ^ 16
+    const int other = __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v), 0x401F);
+    v = v + __builtin_bit_cast(float, other);
+  }
+  return v;
+}
+
 }  // namespace rms

@@ -107,6 +107,9 @@ def test_unknown_variant_and_unsupported_shapes():
     for v in (binding.RMSNORM_VARIANT_WAVE, binding.RMSNORM_VARIANT_BLOCK):
         assert lib.rmsnorm_fwd_variant(P, P + 4096, P + 8192, 4, 7, 1e-6, 2, None, v) == \
             binding.RMSNORM_ERR_UNSUPPORTED
+    # more than 1 KiB per row is too long for the several-rows-per-wavefront kernel
+    assert lib.rmsnorm_fwd_variant(P, P + (1 << 20), P + (2 << 20), 4, 1024, 1e-6, 2, None,
+                                   binding.RMSNORM_VARIANT_SUBWAVE) == binding.RMSNORM_ERR_UNSUPPORTED
     # too long for one wavefront's registers
     assert lib.rmsnorm_fwd_variant(P, P + (1 << 20), P + (2 << 20), 4, 8200, 1e-6, 2, None,
                                    binding.RMSNORM_VARIANT_WAVE) == binding.RMSNORM_ERR_UNSUPPORTED
@@ -119,7 +122,7 @@ def test_tuned_entry_argument_checks():
     lib = binding.load()
     f = lib.rmsnorm_fwd_tuned
     big = 1 << 22
-    for bad in (0, 32, 96, 2048, -64):
+    for bad in (0, 4, 48, 96, 2048, -64):
         assert f(P, P + big, P + 2 * big, 4, 4096, 1e-6, 2, None, bad) == binding.RMSNORM_ERR_INVALID_ARG
     # 4096 bf16 = 512 vectors: 64 threads -> 8 chunks (ok); 16384 bf16 with 64 threads -> 32 (too many)
     assert f(P, P + big, P + 2 * big, 4, 16384, 1e-6, 2, None, 64) == binding.RMSNORM_ERR_UNSUPPORTED
@@ -135,6 +138,13 @@ def test_automatic_threads_per_row():
     assert auto(8192, bf16) == 256          # headline shape: 4 chunks per thread
     assert auto(4096, bf16) == 256
     assert auto(2048, bf16) == 64
+    assert auto(512, bf16) == 64
+    assert auto(256, bf16) == 32
+    assert auto(128, bf16) == 16
+    assert auto(64, fp16) == 8
+    assert auto(8, fp16) == 8
+    assert auto(128, fp32) == 32
+    assert auto(200, bf16) == 32
     assert auto(1024, fp32) == 64
     assert auto(768, fp16) == 64
     assert auto(5120, fp16) == 256
@@ -158,6 +168,7 @@ def test_dispatch_choice_is_visible_without_a_launch():
     assert sel(P, P + 65536, P + 131072, 16, 768, 1) == binding.RMSNORM_VARIANT_WAVE
     assert sel(P, P + 65536, P + 131072, 16, 13824, 1) == binding.RMSNORM_VARIANT_BLOCK
     assert sel(P, P + 65536, P + 131072, 16, 2048, 2) == binding.RMSNORM_VARIANT_WAVE
+    assert sel(P, P + 65536, P + 131072, 16, 128, 2) == binding.RMSNORM_VARIANT_SUBWAVE
     assert sel(P, P + 65536, P + 131072, 16, 1023, 1) == binding.RMSNORM_VARIANT_UNALIGNED
     assert sel(P + 2, P + 65536, P + 131072, 16, 1024, 1) == binding.RMSNORM_VARIANT_UNALIGNED
     assert sel(P, P + 65536, P + 131072, 16, 3, 0) == binding.RMSNORM_VARIANT_UNALIGNED

@@ -14,6 +14,10 @@ pytestmark = pytest.mark.gpu
 SWEEP = [
     ("tiny", 128, 128),
     ("one_vector", 70, 8),
+    ("head_dim_64", 1031, 64),
+    ("head_dim_128", 4099, 128),
+    ("head_dim_256", 515, 256),
+    ("short_ragged", 333, 200),
     ("small", 512, 512),
     ("ragged_last_chunk", 301, 1000),
     ("standard", 1024, 4096),

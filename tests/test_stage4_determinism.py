@@ -50,15 +50,24 @@ def test_determinism_other_dtypes(gpu_device, dtype):
     _repeat(inputs.random_case(4, 700 + 2 * dtype, 777, 5120, dtype, 1e-5), gpu_device)
 
 
-def test_rows_do_not_depend_on_their_neighbours(gpu_device):
+@pytest.mark.parametrize("N", [4096, 128])
+def test_rows_do_not_depend_on_their_neighbours(gpu_device, N):
     """Row i of a large call equals the one-row call on that row, bit for bit, within a
     variant: the grid shape must not leak into the arithmetic."""
-    case = inputs.random_case(4, 710, 300, 4096, inputs.BF16, 1e-6)
+    case = inputs.random_case(4, 710, 300, N, inputs.BF16, 1e-6)
     xd = H.to_device(case["x"], inputs.BF16, gpu_device)
     wd = H.to_device(case["w"], inputs.BF16, gpu_device)
+    ran = 0
     for v in H.ALL_MODES[1:]:
-        H.say(f"row independence mode={H.mode_name(v)}")
-        full = H.to_host(H.launch_mode(xd, wd, 1e-6, v, None), inputs.BF16)
+        H.say(f"row independence N={N} mode={H.mode_name(v)}")
+        try:
+            full = H.to_host(H.launch_mode(xd, wd, 1e-6, v, None), inputs.BF16)
+        except binding.RmsnormError as e:
+            if e.status == binding.RMSNORM_ERR_UNSUPPORTED:
+                continue
+            raise
+        ran += 1
         for i in (0, 3, 157, 299):
             one = H.to_host(H.launch_mode(xd[i:i + 1], wd, 1e-6, v, None), inputs.BF16)
             assert np.array_equal(one[0], full[i])
+    assert ran >= 4

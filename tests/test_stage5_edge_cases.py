@@ -85,7 +85,8 @@ def test_misaligned_base_pointers(gpu_device, dtype):
     torch.cuda.synchronize()
     assert H.guards_intact(whole2, M, N, dtype, offset_elems=3)
     compare.check_parity(H.to_host(y2, dtype), want, dtype, "misaligned bases, element-wise")
-    for v in (binding.RMSNORM_VARIANT_WAVE, binding.RMSNORM_VARIANT_BLOCK) + \
+    for v in (binding.RMSNORM_VARIANT_WAVE, binding.RMSNORM_VARIANT_BLOCK,
+              binding.RMSNORM_VARIANT_SUBWAVE) + \
             tuple(("threads", g) for g in H.THREADS):
         with pytest.raises(binding.RmsnormError) as e:
             H.launch_mode(xd, wd, 1e-6, v, y)
