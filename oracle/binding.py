@@ -27,7 +27,9 @@ def build(force: bool = True) -> str:
 def _load():
     global _lib
     if _lib is None:
-        lib = ctypes.CDLL(build(force=False))
+        # RMSNORM_ORACLE_LIB lets the mutation test (tests/test_oracle_mutants.py) point the
+        # pins at a deliberately broken build of the oracle; nothing else sets it.
+        lib = ctypes.CDLL(os.environ.get("RMSNORM_ORACLE_LIB") or build(force=False))
         vp, i64, dbl, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_double, ctypes.c_int
         lib.rmsnorm_oracle.argtypes = [vp, vp, vp, i64, i64, dbl, i32, i32]
         lib.rmsnorm_oracle.restype = i32

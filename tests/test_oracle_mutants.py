@@ -1,0 +1,78 @@
+"""Do the oracle's pins have teeth?  Each case below plants one plausible mistake in a
+copy of the oracle's source (on the CPU; no GPU is involved), builds it, and runs the pin
+tests against that build: they must fail.  The unmodified source must pass the same way.
+"""
+import os
+import subprocess
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+SRC = os.path.join(ROOT, "oracle", "rmsnorm_oracle.cpp")
+PINS = os.path.join(ROOT, "tests", "test_oracle_pins.py")
+
+MUTANTS = {
+    "mean_over_n_minus_1": ("const double ms = ss / (double)N;",
+                            "const double ms = ss / (double)(N > 1 ? N - 1 : 1);"),
+    "eps_outside_the_root": ("1.0 / std::sqrt(ms + eps)", "1.0 / (std::sqrt(ms) + eps)"),
+    "missing_root": ("1.0 / std::sqrt(ms + eps)", "1.0 / (ms + eps)"),
+    "first_element_dropped": ("double ss = 0.0;\n    for (int64_t j = 0; j < N; ++j) {",
+                              "double ss = 0.0;\n    for (int64_t j = 1; j < N; ++j) {"),
+    "last_element_dropped": ("double ss = 0.0;\n    for (int64_t j = 0; j < N; ++j) {",
+                             "double ss = 0.0;\n    for (int64_t j = 0; j + 1 < N || j == 0; ++j) {"),
+    "sum_of_abs_not_squares": ("ss += xv * xv;", "ss += std::fabs(xv);"),
+    "weight_shifted_by_one": ("const double v = xv * r * wd[(size_t)j];",
+                              "const double v = xv * r * wd[(size_t)((j + 1) % N)];"),
+    "weight_indexed_by_row": ("const double v = xv * r * wd[(size_t)j];",
+                              "const double v = xv * r * wd[(size_t)(i % N)];"),
+    "weight_forgotten": ("const double v = xv * r * wd[(size_t)j];", "const double v = xv * r;"),
+    "x_read_transposed": ("const double xv = decode_bits(load_bits(x, i * N + j, dtype), f);\n      const double v",
+                          "const double xv = decode_bits(load_bits(x, (i * N + j) % (N * ((i * N + j) / N + 1)) == 0 ? 0 : i * N + (N - 1 - j), dtype), f);\n      const double v"),
+    "rounds_through_fp32_first": ("encode_bits(round_to_format(v, f), f)",
+                                  "encode_bits(round_to_format((double)(float)v, f), f)"),
+    "encode_rounds_through_fp32_first": ("encode_bits(round_to_format(src[k], *f), *f)",
+                                         "encode_bits(round_to_format((double)(float)src[k], *f), *f)"),
+    "ties_away_from_zero": ("std::nearbyint(std::ldexp(a, f.p - 1 - e))",
+                            "std::round(std::ldexp(a, f.p - 1 - e))"),
+    "truncates": ("std::nearbyint(std::ldexp(a, f.p - 1 - e))", "std::floor(std::ldexp(a, f.p - 1 - e))"),
+    "subnormals_flushed": ("if (e < f.emin) e = f.emin;", "if (e < f.emin) return std::copysign(0.0, v);"),
+    "no_overflow_to_infinity": ("if (r > max_finite) return std::copysign(INFINITY, v);",
+                                "if (r > max_finite) return std::copysign(max_finite, v);"),
+    "fp16_bias_off_by_one": ("constexpr Format kFp16{11, -14, 15, 5};", "constexpr Format kFp16{11, -14, 16, 5};"),
+    "bf16_mantissa_width": ("constexpr Format kBf16{8, -126, 127, 8};", "constexpr Format kBf16{7, -126, 127, 8};"),
+    "sign_lost": ("return neg ? -v : v;", "return v;"),
+    "rstd_squared_input": ("const double r = 1.0 / std::sqrt(ms + eps);",
+                           "const double r = 1.0 / std::sqrt(ms * ms + eps);"),
+}
+
+
+def _build(source_text: str, out_dir, name: str) -> str:
+    cpp = os.path.join(out_dir, f"{name}.cpp")
+    so = os.path.join(out_dir, f"{name}.so")
+    with open(cpp, "w") as f:
+        f.write(source_text)
+    subprocess.run(["g++", "-O1", "-std=c++17", "-shared", "-fPIC", "-pthread", "-o", so, cpp],
+                   check=True)
+    return so
+
+
+def _run_pins(lib_path: str) -> int:
+    env = dict(os.environ, RMSNORM_ORACLE_LIB=lib_path)
+    proc = subprocess.run([sys.executable, "-m", "pytest", PINS, "-x", "-q", "-p", "no:cacheprovider"],
+                          cwd=ROOT, env=env, capture_output=True, text=True)
+    return proc.returncode
+
+
+def test_unmodified_oracle_passes_its_pins_through_the_same_route(tmp_path):
+    so = _build(open(SRC).read(), str(tmp_path), "pristine")
+    assert _run_pins(so) == 0
+
+
+@pytest.mark.parametrize("name", sorted(MUTANTS))
+def test_planted_mistake_is_caught(tmp_path, name):
+    old, new = MUTANTS[name]
+    text = open(SRC).read()
+    assert text.count(old) >= 1, f"mutation site for {name} not found; update the test"
+    so = _build(text.replace(old, new), str(tmp_path), name)
+    assert _run_pins(so) != 0, f"no pin noticed the planted mistake '{name}'"

@@ -167,6 +167,32 @@ def test_adversarial_magnitudes_against_exact_arithmetic():
     assert np.all((got[3] & 0x7FFF) == 0)
 
 
+@pytest.mark.parametrize("dtype", [FP16, BF16])
+def test_outputs_near_a_rounding_tie_are_rounded_once(dtype):
+    """Outputs whose exact value lies within an fp32 half-ulp of a 16-bit rounding tie would come
+    out one ulp off if the product were rounded to fp32 first.  numpy only LOCATES such
+    elements in a million-element input; exact rational arithmetic then decides what the
+    right bits are for the rows that hold them."""
+    M, N, eps = 1 << 16, 16, 1e-6
+    c = inputs.random_case(12, 260 + 2 * dtype, M, N, dtype, eps)
+    got = bits_of(oracle.rmsnorm_oracle(c["x"], c["w"], eps, dtype), dtype)
+    xd = inputs.storage_to_f64(c["x"], dtype)
+    wd = inputs.storage_to_f64(c["w"], dtype)
+    v = np.abs(xd / np.sqrt((xd * xd).mean(axis=1, keepdims=True) + float(np.float32(eps))) * wd)
+    p = exact.FORMATS[dtype][0]
+    emin = exact.FORMATS[dtype][1]
+    with np.errstate(divide="ignore"):
+        e = np.maximum(np.floor(np.log2(np.where(v > 0, v, 1.0))), emin)
+    frac = np.mod(v / np.exp2(e - (p - 1)), 1.0)
+    window = 2.0 ** -(24 - p)          # an fp32 half-ulp, in units of the 16-bit ulp
+    near = (np.abs(frac - 0.5) < window) & (frac != 0.5) & (v > 0)
+    rows = np.unique(np.nonzero(near)[0])
+    assert len(rows) >= 5, "the input must contain elements in the double-rounding window"
+    rows = rows[:40]
+    want = exact.rmsnorm_exact_bits(bits_of(c["x"], dtype)[rows], bits_of(c["w"], dtype), eps, dtype)
+    assert np.array_equal(got[rows], want)
+
+
 # ------------------------------------------------------------------ closed forms
 
 def _closed_form_bits(num: Fraction, under_root: Fraction, dtype):
