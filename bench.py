@@ -66,6 +66,9 @@ def main() -> int:
                     help="force the block size through rmsnorm_fwd_tuned (0 = automatic dispatch)")
     ap.add_argument("--rows", type=int, default=16384, help="M (the headline workload is 16384)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--all-configs", action="store_true",
+                    help="after the headline measurement, also time the other four workloads "
+                         "(GPU and oracle) and add them to the JSON line under other_configs")
     ap.add_argument("--profile-only", action="store_true",
                     help="warm-up plus --steps launches and nothing else (for rocprofv3 runs)")
     ap.add_argument("--calib-copy", action="store_true",
@@ -249,8 +252,78 @@ def main() -> int:
         stats = compare.check_parity(got, y_ref, dtype, "bench output vs oracle")
         result["parity"] = {"checked": "every element of one output buffer", **stats}
 
+    if args.all_configs:
+        del xs, ys, launchers
+        torch.cuda.empty_cache()
+        result["other_configs"] = other_configs(dev, K)
+
     print(json.dumps(result), flush=True)
     return 0
+
+
+def other_configs(dev, iters: int):
+    """GPU time (rotating buffers, per-launch events, 10 % trimmed mean) and oracle time
+    (single thread and all threads, best of 3) for the workloads other than the headline."""
+    import numpy as np
+    import torch
+    import oracle
+    from paper_2603_21331_amd import binding, inputs
+
+    cases = [inputs.config1(), inputs.config2()] + [inputs.config4(n) for n in inputs.CONFIG4_N] \
+        + [inputs.config5()]
+    tdt = {inputs.FP32: torch.float32, inputs.FP16: torch.float16, inputs.BF16: torch.bfloat16}
+    cores = oracle.hardware_threads()
+    out = []
+    for case in cases:
+        M, N, dtype, eps = case["M"], case["N"], case["dtype"], case["eps"]
+        nbytes = inputs.algorithmic_bytes(M, N, dtype)
+        sets = max(2, min(8, (1 << 30) // max(nbytes, 1) + 1))
+        if dtype == inputs.FP32:
+            x0 = torch.from_numpy(case["x"]).to(dev)
+            w = torch.from_numpy(case["w"]).to(dev)
+        else:
+            x0 = torch.from_numpy(case["x"].view(np.int16)).to(dev).view(tdt[dtype])
+            w = torch.from_numpy(case["w"].view(np.int16)).to(dev).view(tdt[dtype])
+        xs = [x0] + [x0.clone() for _ in range(sets - 1)]
+        ys = [torch.empty_like(x0) for _ in range(sets)]
+        fns = [binding.bind_rmsnorm_fwd(xs[i], w, ys[i], eps) for i in range(sets)]
+        for i in range(10):
+            fns[i % sets]()
+        torch.cuda.synchronize()
+        pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+                 for _ in range(iters)]
+        for i, (a, b) in enumerate(pairs):
+            a.record()
+            fns[i % sets]()
+            b.record()
+        torch.cuda.synchronize()
+        us = trimmed_mean([a.elapsed_time(b) * 1e3 for a, b in pairs])
+        t_all = min(_timed(lambda: oracle.rmsnorm_oracle(case["x"], case["w"], eps, dtype, cores))
+                    for _ in range(3))
+        rows1 = min(M, 512)
+        t_one = min(_timed(lambda: oracle.rmsnorm_oracle(case["x"][:rows1], case["w"], eps, dtype, 1))
+                    for _ in range(3)) * (M / rows1)
+        entry = {
+            "workload": case["name"], "bytes": nbytes, "buffer_sets": sets,
+            "threads_per_row": binding.rmsnorm_auto_threads_per_row(N, dtype),
+            "gpu_us": round(us, 2), "gpu_gbps": round(nbytes / us / 1e3, 1),
+            "gpu_rows_per_s": round(M / us * 1e6, 1),
+            "pct_of_peak": round(nbytes / us / 1e3 / PEAK_HBM_GBPS * 100, 2),
+            "oracle_all_threads_s": round(t_all, 5), "oracle_threads": cores,
+            "oracle_all_threads_gbps": round(nbytes / t_all / 1e9, 3),
+            "oracle_one_thread_s_extrapolated": round(t_one, 4),
+        }
+        log(f"{entry}")
+        out.append(entry)
+        del xs, ys, fns
+        torch.cuda.empty_cache()
+    return out
+
+
+def _timed(fn) -> float:
+    t = time.perf_counter()
+    fn()
+    return time.perf_counter() - t
 
 
 if __name__ == "__main__":
