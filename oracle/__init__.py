@@ -1,11 +1,12 @@
-"""CPU oracle for RMSNorm forward: test infrastructure, not part of the product.
+"""CPU oracles (RMSNorm forward, row softmax): test infrastructure, not part of the product.
 
 Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import
-this package.  It wraps oracle/rmsnorm_oracle.cpp (plain C++17, fp64) through
-ctypes on host numpy arrays and imports nothing from the HIP package.
+this package.  It wraps oracle/rmsnorm_oracle.cpp and oracle/softmax_oracle.cpp
+(plain C++17, fp64; each file stands alone) through ctypes on host numpy arrays
+and imports nothing from the HIP package.
 """
 from .binding import (FP32, FP16, BF16, build, decode, encode, hardware_threads,
-                      rmsnorm_oracle, rmsnorm_oracle_rstd)
+                      rmsnorm_oracle, rmsnorm_oracle_rstd, softmax_oracle)
 
 __all__ = ["FP32", "FP16", "BF16", "build", "decode", "encode", "hardware_threads",
-           "rmsnorm_oracle", "rmsnorm_oracle_rstd"]
+           "rmsnorm_oracle", "rmsnorm_oracle_rstd", "softmax_oracle"]

@@ -12,16 +12,24 @@ FP32, FP16, BF16 = 0, 1, 2
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "rmsnorm_oracle.cpp")
 _LIB = os.path.join(_HERE, "librmsnorm_oracle.so")
+_SOFTMAX_SRC = os.path.join(_HERE, "softmax_oracle.cpp")
+_SOFTMAX_LIB = os.path.join(_HERE, "libsoftmax_oracle.so")
 _lib = None
+_softmax_lib = None
+
+
+def _compile(src: str, lib: str, force: bool) -> str:
+    if force or not os.path.exists(lib) or os.path.getmtime(lib) < os.path.getmtime(src):
+        cmd = ["g++", "-O2", "-std=c++17", "-shared", "-fPIC", "-pthread",
+               "-Wall", "-Wextra", "-o", lib, src]
+        subprocess.run(cmd, check=True)
+    return lib
 
 
 def build(force: bool = True) -> str:
-    """Compiles the oracle with the host compiler.  No GPU toolchain involved."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        cmd = ["g++", "-O2", "-std=c++17", "-shared", "-fPIC", "-pthread",
-               "-Wall", "-Wextra", "-o", _LIB, _SRC]
-        subprocess.run(cmd, check=True)
-    return _LIB
+    """Compiles the oracles with the host compiler.  No GPU toolchain involved."""
+    _compile(_SOFTMAX_SRC, _SOFTMAX_LIB, force)
+    return _compile(_SRC, _LIB, force)
 
 
 def _load():
@@ -29,7 +37,7 @@ def _load():
     if _lib is None:
         # RMSNORM_ORACLE_LIB lets the mutation test (tests/test_oracle_mutants.py) point the
         # pins at a deliberately broken build of the oracle; nothing else sets it.
-        lib = ctypes.CDLL(os.environ.get("RMSNORM_ORACLE_LIB") or build(force=False))
+        lib = ctypes.CDLL(os.environ.get("RMSNORM_ORACLE_LIB") or _compile(_SRC, _LIB, False))
         vp, i64, dbl, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_double, ctypes.c_int
         lib.rmsnorm_oracle.argtypes = [vp, vp, vp, i64, i64, dbl, i32, i32]
         lib.rmsnorm_oracle.restype = i32
@@ -112,3 +120,31 @@ def encode(values, dtype: int) -> np.ndarray:
 
 def hardware_threads() -> int:
     return int(_load().rmsnorm_oracle_hardware_threads())
+
+
+# ------------------------------------------------------------------ row softmax
+
+def _load_softmax():
+    global _softmax_lib
+    if _softmax_lib is None:
+        # SOFTMAX_ORACLE_LIB: same hook as RMSNORM_ORACLE_LIB, for the softmax mutation test.
+        lib = ctypes.CDLL(os.environ.get("SOFTMAX_ORACLE_LIB")
+                          or _compile(_SOFTMAX_SRC, _SOFTMAX_LIB, False))
+        vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
+        lib.softmax_oracle.argtypes = [vp, vp, i64, i64, i32, i32]
+        lib.softmax_oracle.restype = i32
+        _softmax_lib = lib
+    return _softmax_lib
+
+
+def softmax_oracle(x, dtype: int, nthreads: int = 0) -> np.ndarray:
+    """Row softmax of an (M, N) x in storage form; returns storage form."""
+    x = _as_storage(x, dtype)
+    if x.ndim != 2:
+        raise ValueError(f"x must be 2-D, got shape {x.shape}")
+    M, N = x.shape
+    y = np.empty_like(x)
+    rc = _load_softmax().softmax_oracle(x.ctypes.data, y.ctypes.data, M, N, dtype, nthreads)
+    if rc != 0:
+        raise ValueError(f"softmax_oracle rejected its arguments (rc={rc})")
+    return y

@@ -47,6 +47,27 @@ MUTANTS = {
 }
 
 
+SOFTMAX_SRC = os.path.join(ROOT, "oracle", "softmax_oracle.cpp")
+SOFTMAX_PINS = os.path.join(ROOT, "tests", "test_softmax_oracle_pins.py")
+
+SOFTMAX_MUTANTS = {
+    "no_max_subtraction": ("std::exp(v - m); ", "std::exp(v); "),
+    "base_two_exponential": ("std::exp(v - m); ", "std::exp2(v - m); "),
+    "first_term_missing_from_the_sum": ("s += e[(size_t)j];", "if (j > 0 || N == 1) s += e[(size_t)j];"),
+    "divides_by_the_mean": ("e[(size_t)j] / s;", "e[(size_t)j] / (s / (double)N);"),
+    "max_of_absolute_values": ("else if (v > m) m = v;", "else if (std::fabs(v) > m) m = std::fabs(v);"),
+    # (no ties-away-from-zero case here: a quotient exp(.)/sum computed in fp64 never lands
+    #  exactly on a 16-bit or fp32 tie except for dyadic 1/2^k, which is representable)
+    "truncates": ("std::nearbyint(std::ldexp(a, mbits - e))", "std::floor(std::ldexp(a, mbits - e))"),
+    "rounds_up": ("std::nearbyint(std::ldexp(a, mbits - e))", "std::ceil(std::ldexp(a, mbits - e))"),
+    "subnormals_flushed": ("if (e < f.emin) e = f.emin;", "if (e < f.emin) return sign;"),
+    "rounds_through_fp32_first": ("store_bits(y, i * N + j, dtype, narrow(out, f));",
+                                  "store_bits(y, i * N + j, dtype, narrow((double)(float)out, f));"),
+    "nan_row_not_propagated": ("const double out = has_nan ? std::nan(\"\") : e[(size_t)j] / s;",
+                               "const double out = std::isnan(e[(size_t)j]) ? 0.0 : e[(size_t)j] / (std::isnan(s) ? 1.0 : s);"),
+}
+
+
 def _build(source_text: str, out_dir, name: str) -> str:
     cpp = os.path.join(out_dir, f"{name}.cpp")
     so = os.path.join(out_dir, f"{name}.so")
@@ -57,9 +78,10 @@ def _build(source_text: str, out_dir, name: str) -> str:
     return so
 
 
-def _run_pins(lib_path: str) -> int:
-    env = dict(os.environ, RMSNORM_ORACLE_LIB=lib_path)
-    proc = subprocess.run([sys.executable, "-m", "pytest", PINS, "-x", "-q", "-p", "no:cacheprovider"],
+def _run_pins(lib_path: str, var: str = "RMSNORM_ORACLE_LIB", pins: str = PINS) -> int:
+    env = dict(os.environ)
+    env[var] = lib_path
+    proc = subprocess.run([sys.executable, "-m", "pytest", pins, "-x", "-q", "-p", "no:cacheprovider"],
                           cwd=ROOT, env=env, capture_output=True, text=True)
     return proc.returncode
 
@@ -76,3 +98,18 @@ def test_planted_mistake_is_caught(tmp_path, name):
     assert text.count(old) >= 1, f"mutation site for {name} not found; update the test"
     so = _build(text.replace(old, new), str(tmp_path), name)
     assert _run_pins(so) != 0, f"no pin noticed the planted mistake '{name}'"
+
+
+def test_unmodified_softmax_oracle_passes_its_pins_through_the_same_route(tmp_path):
+    so = _build(open(SOFTMAX_SRC).read(), str(tmp_path), "pristine_softmax")
+    assert _run_pins(so, "SOFTMAX_ORACLE_LIB", SOFTMAX_PINS) == 0
+
+
+@pytest.mark.parametrize("name", sorted(SOFTMAX_MUTANTS))
+def test_planted_softmax_mistake_is_caught(tmp_path, name):
+    old, new = SOFTMAX_MUTANTS[name]
+    text = open(SOFTMAX_SRC).read()
+    assert text.count(old) >= 1, f"mutation site for {name} not found; update the test"
+    so = _build(text.replace(old, new), str(tmp_path), name)
+    assert _run_pins(so, "SOFTMAX_ORACLE_LIB", SOFTMAX_PINS) != 0, \
+        f"no pin noticed the planted mistake '{name}'"
