@@ -69,6 +69,9 @@ def main() -> int:
     ap.add_argument("--all-configs", action="store_true",
                     help="after the headline measurement, also time the other four workloads "
                          "(GPU and oracle) and add them to the JSON line under other_configs")
+    ap.add_argument("--op", choices=["rmsnorm", "softmax"], default="rmsnorm",
+                    help="rmsnorm (default): the headline benchmark.  softmax: the same protocol on "
+                         "row softmax at the paper's largest softmax shape (fp16, 8192 x 8192)")
     ap.add_argument("--profile-only", action="store_true",
                     help="warm-up plus --steps launches and nothing else (for rocprofv3 runs)")
     ap.add_argument("--calib-copy", action="store_true",
@@ -94,6 +97,8 @@ def main() -> int:
     binding.load()
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.op == "softmax":
+        return bench_softmax(args, dev)
 
     M, K, W, S = args.rows, args.steps, args.warmup, max(1, args.buffer_sets)
     t0 = time.time()
@@ -257,6 +262,93 @@ def main() -> int:
         torch.cuda.empty_cache()
         result["other_configs"] = other_configs(dev, K)
 
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+def bench_softmax(args, dev) -> int:
+    """Row softmax, fp16, 8192 x 8192 (the largest softmax row of the paper's performance
+    table: 95.9 us, 2800 GB/s on H100), same protocol as the headline benchmark."""
+    import numpy as np
+    import torch
+    from paper_2603_21331_amd import inputs, softmax
+
+    softmax.load()
+    n, K, W, S = 8192, args.steps, args.warmup, max(1, args.buffer_sets)
+    t0 = time.time()
+    case = inputs.softmax_paper_shape(n)
+    log(f"generated {case['name']} in {time.time() - t0:.1f} s")
+    nbytes = inputs.softmax_bytes(n, n, inputs.FP16)
+    x_host = torch.from_numpy(case["x"].view(np.int16))
+    xs = [x_host.to(dev).view(torch.float16) for _ in range(S)]
+    ys = [torch.empty((n, n), dtype=torch.float16, device=dev) for _ in range(S)]
+    fns = [softmax.bind_softmax_fwd(xs[i], ys[i], threads_per_row=args.threads_per_row)
+           for i in range(S)]
+    for i in range(W):
+        fns[i % S]()
+    torch.cuda.synchronize()
+    if args.profile_only:
+        for i in range(K):
+            fns[i % S]()
+        torch.cuda.synchronize()
+        log("profile-only run done")
+        return 0
+
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    start.record()
+    for i in range(K):
+        fns[i % S]()
+    stop.record()
+    torch.cuda.synchronize()
+    ms_per_step = start.elapsed_time(stop) / K
+    value = nbytes / (ms_per_step * 1e-3) / 1e9
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+             for _ in range(K)]
+    for i, (a, b) in enumerate(pairs):
+        a.record()
+        fns[i % S]()
+        b.record()
+    torch.cuda.synchronize()
+    durs = [a.elapsed_time(b) * 1e3 for a, b in pairs]
+    mean_us = sum(durs) / len(durs)
+    result = {
+        "metric": "Softmax fwd achieved HBM GB/s and % of MI355X peak (fp16, 8192x8192)",
+        "value": round(value, 1), "unit": "GB/s",
+        "pct_of_peak": round(100.0 * value / PEAK_HBM_GBPS, 2),
+        "rows_per_s": round(n / (ms_per_step * 1e-3), 1),
+        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(ms_per_step, 6),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"softmax_fwd fp16 M={n} N={n}", "storage_dtype": "fp16",
+                   "threads_per_row": args.threads_per_row
+                   or softmax.softmax_auto_threads_per_row(n, inputs.FP16),
+                   "buffer_sets": S, "bytes_per_step": nbytes},
+        "roofline": {"bound": "hbm", "achieved": round(nbytes / (mean_us * 1e-6) / 1e9, 1),
+                     "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                     "frac": round(nbytes / (mean_us * 1e-6) / 1e9 / PEAK_HBM_GBPS, 4),
+                     "traffic": None, "kernel_mean_us": round(mean_us, 3),
+                     "kernel_trimmed_mean_us": round(trimmed_mean(durs), 3),
+                     "kernel_min_us": round(min(durs), 3)},
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        sys.path.insert(0, os.path.join(ROOT, "tests"))
+        import compare
+        cores = oracle.hardware_threads()
+        best, y_ref = None, None
+        for _ in range(3):
+            t = time.perf_counter()
+            y_ref = oracle.softmax_oracle(case["x"], inputs.FP16, nthreads=cores)
+            dt = time.perf_counter() - t
+            best = dt if best is None else min(best, dt)
+        result["cpu_baseline"] = {"value": round(nbytes / best / 1e9, 3), "unit": "GB/s",
+                                  "cores": cores, "kind": "oracle",
+                                  "sample": f"the whole workload ({n} x {n}), best of 3 runs, "
+                                            f"{best:.3f} s each"}
+        got = ys[0].view(torch.int16).cpu().numpy().view(np.uint16)
+        result["parity"] = {"checked": "every element of one output buffer",
+                            **compare.check_softmax_parity(got, y_ref, inputs.FP16, "bench softmax")}
     print(json.dumps(result), flush=True)
     return 0
 

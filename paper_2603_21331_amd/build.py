@@ -8,9 +8,12 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
 LIB_PATH = os.path.join(_HERE, "librmsnorm_hip.so")
+SOFTMAX_LIB_PATH = os.path.join(_HERE, "libsoftmax_hip.so")
 
 SOURCES = ["rmsnorm_api.hip"]
 HEADERS = ["rmsnorm_kernels.h", "vec_io.h", "wave_reduce.h"]
+SOFTMAX_SOURCES = ["softmax_api.hip"]
+SOFTMAX_HEADERS = ["softmax_kernels.h", "vec_io.h", "wave_reduce.h"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC", "-Wall",
@@ -26,10 +29,9 @@ def hipcc() -> str:
     return "hipcc"
 
 
-def build(verbose: bool = False) -> str:
-    """Compiles csrc/ into librmsnorm_hip.so next to this file and returns its path."""
-    cmd = [hipcc(), *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-o", LIB_PATH,
-           *[os.path.join(CSRC, s) for s in SOURCES]]
+def _compile(sources, lib_path: str, verbose: bool) -> str:
+    cmd = [hipcc(), *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-o", lib_path,
+           *[os.path.join(CSRC, s) for s in sources]]
     if verbose:
         print(" ".join(cmd), flush=True)
     proc = subprocess.run(cmd, capture_output=True, text=True)
@@ -39,7 +41,18 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError(f"hipcc failed ({proc.returncode}):\n{err}")
     if verbose and err.strip():
         print(err)
-    return LIB_PATH
+    return lib_path
+
+
+def build(verbose: bool = False) -> str:
+    """Compiles csrc/ into librmsnorm_hip.so and libsoftmax_hip.so next to this file;
+    returns the path of the RMSNorm library."""
+    _compile(SOFTMAX_SOURCES, SOFTMAX_LIB_PATH, verbose)
+    return _compile(SOURCES, LIB_PATH, verbose)
+
+
+def build_softmax(verbose: bool = False) -> str:
+    return _compile(SOFTMAX_SOURCES, SOFTMAX_LIB_PATH, verbose)
 
 
 def is_stale() -> bool:

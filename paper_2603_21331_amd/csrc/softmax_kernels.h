@@ -1,0 +1,250 @@
+// Row softmax forward kernels for gfx950 (MI355X).
+//
+//   y[i, j] = exp(x[i, j] - max_j x[i, :]) / sum_j exp(x[i, j] - max_j x[i, :])
+//
+// The paper lists the kernel next to RMSNorm in its "Supported kernel types"
+// table (regime Memory, metric GB/s, "warp-shuffle reductions, half2 loads") and
+// it has the same reduce-then-scale shape, so it reuses the RMSNorm design: each
+// row is read from HBM once with 16-byte non-temporal loads, held in registers
+// across both reductions, and written once.  What is held differs: after the
+// maximum is known the row is kept as fp32 exponentials (8 registers per 16-byte
+// chunk of a 16-bit type instead of 4), because computing exp a second time for
+// the scale pass would make the kernel ALU-bound (v_exp_f32 issues at a quarter
+// of the FMA rate).
+//
+//  * softmax_row_kernel<.., G = 64> : one wavefront per row (DPP max and sum).
+//  * softmax_row_kernel<.., G > 64> : one workgroup per row, cross-wave max and
+//                                     sum through LDS, two barriers per row.
+//  * softmax_subwave_kernel        : 8, 16 or 32 lanes per row for rows <= 1 KiB
+//                                     (attention scores over short contexts).
+//  * softmax_generic_kernel        : element-wise three-pass fallback, any
+//                                     alignment, any N.
+//
+// Reductions have a fixed order and use no atomics: results are bit-identical
+// from run to run.
+#pragma once
+
+#include "vec_io.h"
+#include "wave_reduce.h"
+
+namespace rms {
+
+constexpr int kWaveSize = 64;
+constexpr float kNegInf = -__builtin_inff();
+
+// exp(d) for d <= 0 as 2^(d * log2 e), to the accuracy each output type needs.
+//  - fp32 outputs: the product d * log2 e is carried in two floats (t + lo); a
+//    single rounded product would put up to 1e-5 relative error into the result
+//    for |d| ~ 100.  e == 0 is returned as is so that d = -inf (lo is NaN then)
+//    gives 0; a NaN d still gives NaN.
+//  - bf16 outputs share the fp32 exponent range and can be subnormal, so they
+//    take __builtin_exp2f, which keeps subnormal results; the single product is
+//    accurate enough for 8 significand bits.
+//  - fp16 outputs underflow to zero long before fp32 does: raw v_exp_f32.
+template <int DT>
+__device__ __forceinline__ float exp_neg(float d) {
+  constexpr float kLog2eHi = 1.44269502162933349609375f;      // fp32(log2 e)
+  constexpr float kLog2eLo = 1.92596299112661746704e-8f;      // log2 e - fp32(log2 e)
+  constexpr float kLn2 = 0.693147182464599609375f;
+  const float t = d * kLog2eHi;
+  if constexpr (DT == kFp16) {
+    return __builtin_amdgcn_exp2f(t);
+  } else if constexpr (DT == kBf16) {
+    return __builtin_exp2f(t);
+  } else {
+    const float lo = __builtin_fmaf(d, kLog2eHi, -t) + d * kLog2eLo;
+    const float e = __builtin_exp2f(t);
+    return e == 0.f ? 0.f : __builtin_fmaf(e, lo * kLn2, e);   // 2^(t+lo) = 2^t (1 + lo ln 2 + ..)
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Register-resident row kernel: G threads share one row, one row per workgroup.
+// Same data layout as the RMSNorm row kernel: vector c * G + t goes to thread t,
+// chunk c; only the last chunk can be ragged, and its missing elements are
+// filled with -inf so that they take no part in the maximum and add exp(-inf)
+// = 0 to the sum.
+// ---------------------------------------------------------------------------
+template <int DT, int CHUNKS, int G, bool NT>
+__global__ void __launch_bounds__(G)
+softmax_row_kernel(const u32x4* x, u32x4* y, int64_t M, int nvec) {
+  using S = Storage<DT>;
+  constexpr int VEC = S::kVec;
+  constexpr int WAVES = G / kWaveSize;
+  __shared__ float part_max[2][WAVES];
+  __shared__ float part_sum[2][WAVES];
+  const int t = threadIdx.x;
+  const int lane = t & (kWaveSize - 1);
+  const int wave = t / kWaveSize;
+  const int last = (CHUNKS - 1) * G + t;
+  const bool last_ok = last < nvec;
+  int slot = 0;
+
+  for (int64_t row = blockIdx.x; row < M; row += gridDim.x) {
+    const u32x4* xr = x + row * nvec;
+    u32x4* yr = y + row * nvec;
+
+    u32x4 v[CHUNKS];
+#pragma unroll
+    for (int c = 0; c < CHUNKS - 1; ++c) v[c] = load_vec<NT>(xr + c * G + t);
+    {
+      const u32x4 zero = {0u, 0u, 0u, 0u};
+      v[CHUNKS - 1] = zero;
+      if (last_ok) v[CHUNKS - 1] = load_vec<NT>(xr + last);
+    }
+
+    float f[CHUNKS][VEC];
+    float m = kNegInf;
+#pragma unroll
+    for (int c = 0; c < CHUNKS; ++c) {
+      S::unpack(v[c], f[c]);
+      if (c == CHUNKS - 1 && !last_ok) {
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) f[c][k] = kNegInf;
+      }
+#pragma unroll
+      for (int k = 0; k < VEC; ++k) m = __builtin_fmaxf(m, f[c][k]);
+    }
+    m = wave_max(m);
+    if constexpr (WAVES > 1) {
+      if (lane == 0) part_max[slot][wave] = m;
+      __syncthreads();
+      m = part_max[slot][0];
+#pragma unroll
+      for (int k = 1; k < WAVES; ++k) m = __builtin_fmaxf(m, part_max[slot][k]);
+    }
+
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int c = 0; c < CHUNKS; ++c) {
+#pragma unroll
+      for (int k = 0; k < VEC; ++k) {
+        f[c][k] = exp_neg<DT>(f[c][k] - m);
+        acc[k & 3] += f[c][k];
+      }
+    }
+    float s = wave_sum((acc[0] + acc[1]) + (acc[2] + acc[3]));
+    if constexpr (WAVES > 1) {
+      if (lane == 0) part_sum[slot][wave] = s;
+      __syncthreads();
+      s = part_sum[slot][0];
+#pragma unroll
+      for (int k = 1; k < WAVES; ++k) s += part_sum[slot][k];
+      slot ^= 1;
+    }
+    const float inv = 1.0f / s;
+
+#pragma unroll
+    for (int c = 0; c < CHUNKS; ++c) {
+#pragma unroll
+      for (int k = 0; k < VEC; ++k) f[c][k] *= inv;
+      const int idx = c * G + t;
+      if (c < CHUNKS - 1 || last_ok) store_vec<NT>(yr + idx, S::pack(f[c]));
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Short rows: L = 8, 16 or 32 lanes per row, 64 / L consecutive rows per
+// wavefront; reductions stay inside the lane group.  Lanes whose row lies past
+// M run on -inf so that the cross-lane steps always see 64 active lanes; their
+// result (NaN) is never stored.
+// ---------------------------------------------------------------------------
+template <int DT, int CHUNKS, int L, bool NT>
+__global__ void __launch_bounds__(kWaveSize)
+softmax_subwave_kernel(const u32x4* x, u32x4* y, int64_t M, int nvec) {
+  using S = Storage<DT>;
+  constexpr int VEC = S::kVec;
+  constexpr int ROWS = kWaveSize / L;
+  const int lane = threadIdx.x;
+  const int sub = lane % L;
+  const int r = lane / L;
+
+  for (int64_t base = (int64_t)blockIdx.x * ROWS; base < M; base += (int64_t)gridDim.x * ROWS) {
+    const int64_t row = base + r;
+    const bool row_ok = row < M;
+    const u32x4* xr = x + row * nvec;
+    u32x4* yr = y + row * nvec;
+
+    float f[CHUNKS][VEC];
+    float m = kNegInf;
+#pragma unroll
+    for (int c = 0; c < CHUNKS; ++c) {
+      const int idx = c * L + sub;
+      if (row_ok && idx < nvec) {
+        S::unpack(load_vec<NT>(xr + idx), f[c]);
+      } else {
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) f[c][k] = kNegInf;
+      }
+#pragma unroll
+      for (int k = 0; k < VEC; ++k) m = __builtin_fmaxf(m, f[c][k]);
+    }
+    m = subwave_max<L>(m);
+    float acc = 0.f;
+#pragma unroll
+    for (int c = 0; c < CHUNKS; ++c) {
+#pragma unroll
+      for (int k = 0; k < VEC; ++k) {
+        f[c][k] = exp_neg<DT>(f[c][k] - m);
+        acc += f[c][k];
+      }
+    }
+    const float inv = 1.0f / subwave_sum<L>(acc);
+#pragma unroll
+    for (int c = 0; c < CHUNKS; ++c) {
+      const int idx = c * L + sub;
+#pragma unroll
+      for (int k = 0; k < VEC; ++k) f[c][k] *= inv;
+      if (row_ok && idx < nvec) store_vec<NT>(yr + idx, S::pack(f[c]));
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Element-wise fallback: any element alignment, any N; three passes over the
+// row (maximum, sum of exponentials, scaled write), the second and third mostly
+// from cache.  In-place safe: every read of passes one and two precedes, by a
+// barrier, every write of pass three, and in pass three a thread reads an
+// element before it overwrites it.
+// ---------------------------------------------------------------------------
+template <int DT, int T>
+__global__ void __launch_bounds__(T)
+softmax_generic_kernel(const void* x, void* y, int64_t M, int64_t N) {
+  using S = Storage<DT>;
+  constexpr int WAVES = T / kWaveSize;
+  __shared__ float part_max[2][WAVES];
+  __shared__ float part_sum[2][WAVES];
+  const int tid = threadIdx.x;
+  const int lane = tid & (kWaveSize - 1);
+  const int wave = tid / kWaveSize;
+  int slot = 0;
+
+  for (int64_t row = blockIdx.x; row < M; row += gridDim.x) {
+    const int64_t base = row * N;
+    float m = kNegInf;
+    for (int64_t j = tid; j < N; j += T) m = __builtin_fmaxf(m, S::load_one(x, base + j));
+    m = wave_max(m);
+    if (lane == 0) part_max[slot][wave] = m;
+    __syncthreads();
+    m = part_max[slot][0];
+#pragma unroll
+    for (int k = 1; k < WAVES; ++k) m = __builtin_fmaxf(m, part_max[slot][k]);
+
+    float acc = 0.f;
+    for (int64_t j = tid; j < N; j += T) acc += exp_neg<DT>(S::load_one(x, base + j) - m);
+    float s = wave_sum(acc);
+    if (lane == 0) part_sum[slot][wave] = s;
+    __syncthreads();
+    s = part_sum[slot][0];
+#pragma unroll
+    for (int k = 1; k < WAVES; ++k) s += part_sum[slot][k];
+    slot ^= 1;
+    const float inv = 1.0f / s;
+
+    for (int64_t j = tid; j < N; j += T)
+      S::store_one(y, base + j, exp_neg<DT>(S::load_one(x, base + j) - m) * inv);
+  }
+}
+
+}  // namespace rms

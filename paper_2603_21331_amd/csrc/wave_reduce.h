@@ -38,6 +38,41 @@ __device__ __forceinline__ float wave_sum(float v) {
   return (r0 + r1) + (r2 + r3);
 }
 
+// Maximum over the 64 lanes, result in every lane; same exchanges as wave_sum.
+// fmaxf returns the other operand when one is NaN, so NaNs do not take part.
+template <int CTRL>
+__device__ __forceinline__ float max_dpp(float v) {
+  const int moved = __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, v),
+                                                __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, false);
+  return __builtin_fmaxf(v, __builtin_bit_cast(float, moved));
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+  v = max_dpp<0xB1>(v);
+  v = max_dpp<0x4E>(v);
+  v = max_dpp<0x141>(v);
+  v = max_dpp<0x140>(v);
+  const float r0 = read_lane(v, 0);
+  const float r1 = read_lane(v, 16);
+  const float r2 = read_lane(v, 32);
+  const float r3 = read_lane(v, 48);
+  return __builtin_fmaxf(__builtin_fmaxf(r0, r1), __builtin_fmaxf(r2, r3));
+}
+
+template <int L>
+__device__ __forceinline__ float subwave_max(float v) {
+  static_assert(L == 8 || L == 16 || L == 32, "group size");
+  v = max_dpp<0xB1>(v);
+  v = max_dpp<0x4E>(v);
+  v = max_dpp<0x141>(v);
+  if constexpr (L >= 16) v = max_dpp<0x140>(v);
+  if constexpr (L == 32) {
+    const int other = __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v), 0x401F);
+    v = __builtin_fmaxf(v, __builtin_bit_cast(float, other));
+  }
+  return v;
+}
+
 // Sum over aligned groups of L = 8, 16 or 32 lanes, result in every lane of the
 // group: the first three or four DPP steps of wave_sum, then for L = 32 one
 // ds_swizzle that swaps neighbouring 16-lane rows (a cross-lane move in the LDS

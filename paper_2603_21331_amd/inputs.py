@@ -212,3 +212,23 @@ def algorithmic_bytes(M: int, N: int, dtype: int) -> int:
     """
     s = DTYPE_BYTES[dtype]
     return 2 * M * N * s + N * s
+
+
+# ----------------------------------------------------------------------------
+# Row softmax workloads (the paper's table lists 4096 x 4096 and 8192 x 8192, FP16)
+# ----------------------------------------------------------------------------
+
+def softmax_case(seed: int, stream: int, M: int, N: int, dtype: int, std: float = 1.0):
+    """Logits x ~ N(0, std) at any shape."""
+    return dict(name=f"softmax_{DTYPE_NAMES[dtype]}_{M}x{N}_std{std:g}", dtype=dtype, M=M, N=N,
+                x=normal_matrix(seed, stream, M, N, dtype, 0.0, std))
+
+
+def softmax_paper_shape(n: int, seed: int = 0):
+    """FP16 n x n logits, N(0, 1): the two softmax rows of the paper's performance table."""
+    return softmax_case(seed, 96 + (0 if n == 4096 else 2), n, n, FP16)
+
+
+def softmax_bytes(M: int, N: int, dtype: int) -> int:
+    """Read x once, write y once (the model behind the paper's GB/s column for softmax)."""
+    return 2 * M * N * DTYPE_BYTES[dtype]

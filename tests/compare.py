@@ -73,3 +73,34 @@ def check_parity(got: np.ndarray, want: np.ndarray, dtype: int, what: str = "") 
         f"{what}: max ulp distance {worst} > {TOL_ULP[dtype]} "
         f"(first at flat index {int(np.argmax(d))})")
     return {"max_ulp": worst, "frac_off": frac}
+
+
+# ---- row softmax ---------------------------------------------------------------------------
+# Tolerances (derived in the design doc): bf16 <= 1 ulp, fp16 <= 2 ulp against the oracle after its
+# single rounding; fp32 |g - o| <= 1e-5 |o| + 2 subnormal quanta (outputs below FLT_MIN have
+# fewer than 24 significant bits, so a purely relative bound cannot hold there).
+SOFTMAX_FP32_ABS_FLOOR = 2.0 * 2.0 ** -149
+
+
+def check_softmax_parity(got: np.ndarray, want: np.ndarray, dtype: int, what: str = "") -> dict:
+    got = np.asarray(got)
+    want = np.asarray(want)
+    assert got.shape == want.shape, f"{what}: shape {got.shape} vs {want.shape}"
+    if dtype == 0:
+        g = got.astype(np.float64)
+        o = want.astype(np.float64)
+        gn, on = np.isnan(g), np.isnan(o)
+        assert np.array_equal(gn, on), f"{what}: NaN positions differ"
+        ok = ~on
+        if not ok.any():
+            return {"max_rel_err": 0.0}
+        excess = np.abs(g[ok] - o[ok]) - SOFTMAX_FP32_ABS_FLOOR
+        rel = np.maximum(excess, 0.0) / np.maximum(np.abs(o[ok]), FLT_MIN)
+        err = float(rel.max())
+        assert err <= TOL_FP32_REL, f"{what}: fp32 max rel err {err:.3e} > {TOL_FP32_REL}"
+        return {"max_rel_err": err}
+    d = ulp_distance(got, want, dtype)
+    worst = int(d.max()) if d.size else 0
+    assert worst <= TOL_ULP[dtype], (
+        f"{what}: max ulp distance {worst} > {TOL_ULP[dtype]} (first at flat index {int(np.argmax(d))})")
+    return {"max_ulp": worst, "frac_off": float(np.count_nonzero(d)) / max(d.size, 1)}
