@@ -14,8 +14,11 @@ _SRC = os.path.join(_HERE, "rmsnorm_oracle.cpp")
 _LIB = os.path.join(_HERE, "librmsnorm_oracle.so")
 _SOFTMAX_SRC = os.path.join(_HERE, "softmax_oracle.cpp")
 _SOFTMAX_LIB = os.path.join(_HERE, "libsoftmax_oracle.so")
+_LAYERNORM_SRC = os.path.join(_HERE, "layernorm_oracle.cpp")
+_LAYERNORM_LIB = os.path.join(_HERE, "liblayernorm_oracle.so")
 _lib = None
 _softmax_lib = None
+_layernorm_lib = None
 
 
 def _compile(src: str, lib: str, force: bool) -> str:
@@ -29,6 +32,7 @@ def _compile(src: str, lib: str, force: bool) -> str:
 def build(force: bool = True) -> str:
     """Compiles the oracles with the host compiler.  No GPU toolchain involved."""
     _compile(_SOFTMAX_SRC, _SOFTMAX_LIB, force)
+    _compile(_LAYERNORM_SRC, _LAYERNORM_LIB, force)
     return _compile(_SRC, _LIB, force)
 
 
@@ -148,3 +152,41 @@ def softmax_oracle(x, dtype: int, nthreads: int = 0) -> np.ndarray:
     if rc != 0:
         raise ValueError(f"softmax_oracle rejected its arguments (rc={rc})")
     return y
+
+
+# ------------------------------------------------------------------ row LayerNorm
+
+def _load_layernorm():
+    global _layernorm_lib
+    if _layernorm_lib is None:
+        # LAYERNORM_ORACLE_LIB: the mutation test's hook, as for the other oracles.
+        lib = ctypes.CDLL(os.environ.get("LAYERNORM_ORACLE_LIB")
+                          or _compile(_LAYERNORM_SRC, _LAYERNORM_LIB, False))
+        vp, i64, i32, dbl = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_double
+        lib.layernorm_oracle.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, dbl, i32, i32]
+        lib.layernorm_oracle.restype = i32
+        _layernorm_lib = lib
+    return _layernorm_lib
+
+
+def layernorm_oracle(x, w, b, eps: float, dtype: int, nthreads: int = 0, stats: bool = False):
+    """LayerNorm of an (M, N) x with (N,) w and optional (N,) b (None = no bias), storage form.
+
+    Returns y, or (y, mean, rstd) with the fp64 row statistics when stats is true."""
+    x = _as_storage(x, dtype)
+    w = _as_storage(w, dtype)
+    if b is not None:
+        b = _as_storage(b, dtype)
+    if x.ndim != 2 or w.shape != (x.shape[1],) or (b is not None and b.shape != w.shape):
+        raise ValueError(f"shape mismatch: x {x.shape}, w {w.shape}, b {None if b is None else b.shape}")
+    M, N = x.shape
+    y = np.empty_like(x)
+    mean = np.empty(M, dtype=np.float64) if stats else None
+    rstd = np.empty(M, dtype=np.float64) if stats else None
+    rc = _load_layernorm().layernorm_oracle(
+        x.ctypes.data, w.ctypes.data, None if b is None else b.ctypes.data, y.ctypes.data,
+        None if mean is None else mean.ctypes.data, None if rstd is None else rstd.ctypes.data,
+        M, N, eps_as_passed(eps), dtype, nthreads)
+    if rc != 0:
+        raise ValueError(f"layernorm_oracle rejected its arguments (rc={rc})")
+    return (y, mean, rstd) if stats else y

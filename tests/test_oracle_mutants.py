@@ -68,6 +68,33 @@ SOFTMAX_MUTANTS = {
 }
 
 
+LAYERNORM_SRC = os.path.join(ROOT, "oracle", "layernorm_oracle.cpp")
+LAYERNORM_PINS = os.path.join(ROOT, "tests", "test_layernorm_oracle_pins.py")
+
+LAYERNORM_MUTANTS = {
+    "unbiased_variance": ("const double var = spread / static_cast<double>(N);",
+                          "const double var = spread / static_cast<double>(N > 1 ? N - 1 : 1);"),
+    "second_moment_not_centred": ("      spread += c * c;\n", "      spread += (c + mu) * (c + mu);\n"),
+    "mean_not_subtracted_in_output": ("      const double out = c * rstd *", "      const double out = (c + mu) * rstd *"),
+    "eps_outside_the_root": ("1.0 / std::sqrt(var + eps)", "1.0 / (std::sqrt(var) + eps)"),
+    "missing_root": ("1.0 / std::sqrt(var + eps)", "1.0 / (var + eps)"),
+    "mean_over_n_minus_1": ("const double mu = total / static_cast<double>(N);",
+                            "const double mu = total / static_cast<double>(N > 1 ? N - 1 : 1);"),
+    "bias_forgotten": ("+ bv[static_cast<size_t>(j)];", "+ 0.0 * bv[static_cast<size_t>(j)];"),
+    "bias_scaled_by_weight": ("const double out = c * rstd * wv[static_cast<size_t>(j)] + bv[static_cast<size_t>(j)];",
+                              "const double out = (c * rstd + bv[static_cast<size_t>(j)]) * wv[static_cast<size_t>(j)];"),
+    "weight_shifted_by_one": ("c * rstd * wv[static_cast<size_t>(j)]", "c * rstd * wv[static_cast<size_t>((j + 1) % N)]"),
+    "bias_indexed_by_row": ("+ bv[static_cast<size_t>(j)];", "+ bv[static_cast<size_t>(i % N)];"),
+    "first_element_missing_from_the_mean": ("    double total = 0.0;\n    for (int64_t j = 0; j < N; ++j) total",
+                                            "    double total = 0.0;\n    for (int64_t j = (N > 1 ? 1 : 0); j < N; ++j) total"),
+    "rounds_through_fp32_first": ("put_bits(y, i * N + j, dtype, from_double(out, L));",
+                                  "put_bits(y, i * N + j, dtype, from_double((double)(float)out, L));"),
+    "ties_away_from_zero": ("std::nearbyint(std::ldexp(a, frac_bits - e))", "std::round(std::ldexp(a, frac_bits - e))"),
+    "truncates": ("std::nearbyint(std::ldexp(a, frac_bits - e))", "std::floor(std::ldexp(a, frac_bits - e))"),
+    "sign_lost": ("return minus ? -v : v;", "return v;"),
+}
+
+
 def _build(source_text: str, out_dir, name: str) -> str:
     cpp = os.path.join(out_dir, f"{name}.cpp")
     so = os.path.join(out_dir, f"{name}.so")
@@ -112,4 +139,19 @@ def test_planted_softmax_mistake_is_caught(tmp_path, name):
     assert text.count(old) >= 1, f"mutation site for {name} not found; update the test"
     so = _build(text.replace(old, new), str(tmp_path), name)
     assert _run_pins(so, "SOFTMAX_ORACLE_LIB", SOFTMAX_PINS) != 0, \
+        f"no pin noticed the planted mistake '{name}'"
+
+
+def test_unmodified_layernorm_oracle_passes_its_pins_through_the_same_route(tmp_path):
+    so = _build(open(LAYERNORM_SRC).read(), str(tmp_path), "pristine_layernorm")
+    assert _run_pins(so, "LAYERNORM_ORACLE_LIB", LAYERNORM_PINS) == 0
+
+
+@pytest.mark.parametrize("name", sorted(LAYERNORM_MUTANTS))
+def test_planted_layernorm_mistake_is_caught(tmp_path, name):
+    old, new = LAYERNORM_MUTANTS[name]
+    text = open(LAYERNORM_SRC).read()
+    assert text.count(old) >= 1, f"mutation site for {name} not found; update the test"
+    so = _build(text.replace(old, new), str(tmp_path), name)
+    assert _run_pins(so, "LAYERNORM_ORACLE_LIB", LAYERNORM_PINS) != 0, \
         f"no pin noticed the planted mistake '{name}'"
