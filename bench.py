@@ -69,9 +69,10 @@ def main() -> int:
     ap.add_argument("--all-configs", action="store_true",
                     help="after the headline measurement, also time the other four workloads "
                          "(GPU and oracle) and add them to the JSON line under other_configs")
-    ap.add_argument("--op", choices=["rmsnorm", "softmax"], default="rmsnorm",
-                    help="rmsnorm (default): the headline benchmark.  softmax: the same protocol on "
-                         "row softmax at the paper's largest softmax shape (fp16, 8192 x 8192)")
+    ap.add_argument("--op", choices=["rmsnorm", "softmax", "layernorm"], default="rmsnorm",
+                    help="rmsnorm (default): the headline benchmark.  softmax / layernorm: the same "
+                         "protocol on the next kernels at the paper's largest shape for each "
+                         "(fp16 8192 x 8192; fp16 8192 x 4096)")
     ap.add_argument("--profile-only", action="store_true",
                     help="warm-up plus --steps launches and nothing else (for rocprofv3 runs)")
     ap.add_argument("--calib-copy", action="store_true",
@@ -99,6 +100,8 @@ def main() -> int:
     torch.cuda.set_device(dev)
     if args.op == "softmax":
         return bench_softmax(args, dev)
+    if args.op == "layernorm":
+        return bench_layernorm(args, dev)
 
     M, K, W, S = args.rows, args.steps, args.warmup, max(1, args.buffer_sets)
     t0 = time.time()
@@ -349,6 +352,98 @@ def bench_softmax(args, dev) -> int:
         got = ys[0].view(torch.int16).cpu().numpy().view(np.uint16)
         result["parity"] = {"checked": "every element of one output buffer",
                             **compare.check_softmax_parity(got, y_ref, inputs.FP16, "bench softmax")}
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+def bench_layernorm(args, dev) -> int:
+    """LayerNorm forward, fp16, 8192 x 4096 (the larger LayerNorm row of the paper's performance
+    table: 51.9 us, 2586 GB/s on H100), same protocol as the headline benchmark."""
+    import numpy as np
+    import torch
+    from paper_2603_21331_amd import inputs, layernorm
+
+    layernorm.load()
+    K, W = args.steps, args.warmup
+    case = inputs.layernorm_paper_shape(1)
+    M, N, eps = case["M"], case["N"], case["eps"]
+    nbytes = inputs.layernorm_bytes(M, N, inputs.FP16)
+    S = max(args.buffer_sets, 8)               # 8 x 128 MiB: well past the Infinity Cache
+    as_dev = lambda a: torch.from_numpy(a.view(np.int16)).to(dev).view(torch.float16)
+    x0, wd, bd = as_dev(case["x"]), as_dev(case["w"]), as_dev(case["b"])
+    xs = [x0] + [x0.clone() for _ in range(S - 1)]
+    ys = [torch.empty_like(x0) for _ in range(S)]
+    fns = [layernorm.bind_layernorm_fwd(xs[i], wd, bd, ys[i], eps,
+                                        threads_per_row=args.threads_per_row) for i in range(S)]
+    for i in range(W):
+        fns[i % S]()
+    torch.cuda.synchronize()
+    if args.profile_only:
+        for i in range(K):
+            fns[i % S]()
+        torch.cuda.synchronize()
+        log("profile-only run done")
+        return 0
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    start.record()
+    for i in range(K):
+        fns[i % S]()
+    stop.record()
+    torch.cuda.synchronize()
+    ms_per_step = start.elapsed_time(stop) / K
+    value = nbytes / (ms_per_step * 1e-3) / 1e9
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+             for _ in range(K)]
+    for i, (a, b) in enumerate(pairs):
+        a.record()
+        fns[i % S]()
+        b.record()
+    torch.cuda.synchronize()
+    durs = [a.elapsed_time(b) * 1e3 for a, b in pairs]
+    mean_us = sum(durs) / len(durs)
+    result = {
+        "metric": "LayerNorm fwd achieved HBM GB/s and % of MI355X peak (fp16, 8192x4096)",
+        "value": round(value, 1), "unit": "GB/s",
+        "pct_of_peak": round(100.0 * value / PEAK_HBM_GBPS, 2),
+        "rows_per_s": round(M / (ms_per_step * 1e-3), 1),
+        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(ms_per_step, 6),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"layernorm_fwd fp16 M={M} N={N} eps={eps} with bias",
+                   "storage_dtype": "fp16",
+                   "threads_per_row": args.threads_per_row
+                   or layernorm.layernorm_auto_threads_per_row(N, inputs.FP16),
+                   "buffer_sets": S, "bytes_per_step": nbytes},
+        "roofline": {"bound": "hbm", "achieved": round(nbytes / (mean_us * 1e-6) / 1e9, 1),
+                     "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                     "frac": round(nbytes / (mean_us * 1e-6) / 1e9 / PEAK_HBM_GBPS, 4),
+                     "traffic": None, "kernel_mean_us": round(mean_us, 3),
+                     "kernel_trimmed_mean_us": round(trimmed_mean(durs), 3),
+                     "kernel_min_us": round(min(durs), 3)},
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        sys.path.insert(0, os.path.join(ROOT, "tests"))
+        import compare
+        cores = oracle.hardware_threads()
+        best = None
+        for _ in range(3):
+            t = time.perf_counter()
+            y_ref, mean, rstd = oracle.layernorm_oracle(case["x"], case["w"], case["b"], eps,
+                                                        inputs.FP16, nthreads=cores, stats=True)
+            dt = time.perf_counter() - t
+            best = dt if best is None else min(best, dt)
+        result["cpu_baseline"] = {"value": round(nbytes / best / 1e9, 3), "unit": "GB/s",
+                                  "cores": cores, "kind": "oracle",
+                                  "sample": f"the whole workload ({M} x {N}), best of 3 runs, "
+                                            f"{best:.3f} s each"}
+        f64 = lambda a: inputs.storage_to_f64(a, inputs.FP16)
+        scale = compare.layernorm_scale(f64(case["x"]), f64(case["w"]), f64(case["b"]), mean, rstd)
+        got = ys[0].view(torch.int16).cpu().numpy().view(np.uint16)
+        result["parity"] = {"checked": "every element of one output buffer",
+                            **compare.check_layernorm_parity(got, y_ref, scale, inputs.FP16,
+                                                             "bench layernorm")}
     print(json.dumps(result), flush=True)
     return 0
 

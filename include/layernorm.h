@@ -1,0 +1,102 @@
+/*
+ * layernorm.h - C ABI of the MI355X (gfx950) row-wise LayerNorm forward library.
+ *
+ * The operation is the "layernorm" row of the paper's "Supported kernel types"
+ * table (memory-bound, measured in GB/s, "Welford single-pass, float4 loads";
+ * results in the table "Kernel performance on H100", Section 7.1):
+ *
+ *     mean_i = (1/N) sum_j x[i, j]
+ *     var_i  = (1/N) sum_j (x[i, j] - mean_i)^2          (biased)
+ *     y[i, j] = (x[i, j] - mean_i) * rsqrt(var_i + eps) * w[j] + b[j]
+ *
+ * Inputs are widened exactly to fp32, both moments, the products and the bias
+ * add are carried in fp32, and the result is rounded once (nearest-even) to the
+ * storage type.  The moments are taken in two passes over the register-resident
+ * row after shifting it by its first element, so rows whose mean is large
+ * against their spread keep their accuracy.  Domain: finite inputs whose row sum
+ * of squared deviations stays below FLT_MAX.
+ *
+ * Conventions are those of rmsnorm.h: device pointers owned by the caller; the
+ * library never allocates, copies or synchronises; work is enqueued on `stream`;
+ * x and y are M x N row-major with leading dimension N, w and b have N elements,
+ * all of one storage type; b may be NULL (no bias); pointers need only element
+ * alignment (rows that are not 16-byte aligned, or too long for registers, take
+ * a slower element-wise kernel); y == x exactly is allowed, any other overlap is
+ * undefined; a call returns LAYERNORM_OK or a negative layernorm_status and
+ * launches nothing on INVALID_ARG / UNSUPPORTED; results are bit-identical from
+ * run to run.
+ */
+#ifndef LAYERNORM_H_
+#define LAYERNORM_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  LAYERNORM_DTYPE_FP32 = 0,
+  LAYERNORM_DTYPE_FP16 = 1,
+  LAYERNORM_DTYPE_BF16 = 2
+} layernorm_dtype;
+
+typedef enum {
+  LAYERNORM_OK = 0,
+  LAYERNORM_ERR_INVALID_ARG = -1, /* null x/w/y, M < 0, N <= 0, bad dtype, eps < 0 or NaN */
+  LAYERNORM_ERR_UNSUPPORTED = -2, /* the forced kernel cannot run this shape or alignment */
+  LAYERNORM_ERR_LAUNCH = -3       /* the HIP runtime refused the launch */
+} layernorm_status;
+
+typedef enum {
+  LAYERNORM_VARIANT_AUTO = 0,    /* dispatch on (dtype, N, alignment) */
+  LAYERNORM_VARIANT_WAVE = 1,    /* one wavefront per row */
+  LAYERNORM_VARIANT_BLOCK = 2,   /* one workgroup of 256..1024 threads per row */
+  LAYERNORM_VARIANT_GENERIC = 3, /* element-wise, three passes, any alignment, any N */
+  LAYERNORM_VARIANT_SUBWAVE = 4  /* 8, 16 or 32 lanes per row; 16-byte aligned rows <= 1 KiB */
+} layernorm_variant;
+
+/*
+ * LayerNorm over the last dimension (formula above).
+ *   x      device, M*N elements of `dtype`, read once
+ *   w      device, N elements (scale)
+ *   b      device, N elements (shift), or NULL for no bias
+ *   y      device, M*N elements, written once
+ *   M, N   rows and row length; M == 0 is a successful no-op; N must be >= 1
+ *   eps    added to the variance inside the root; must be >= 0
+ *   dtype  a layernorm_dtype
+ *   stream a hipStream_t passed as void*; NULL is the default stream
+ */
+int layernorm_fwd(const void* x, const void* w, const void* b, void* y, int64_t M, int64_t N,
+                  float eps, int dtype, void* stream);
+
+/* Same, with the kernel family forced (a layernorm_variant); LAYERNORM_ERR_UNSUPPORTED
+ * if that family cannot take the shape or alignment. */
+int layernorm_fwd_variant(const void* x, const void* w, const void* b, void* y, int64_t M,
+                          int64_t N, float eps, int dtype, void* stream, int variant);
+
+/*
+ * Same, with the number of threads sharing one row forced: 8, 16, 32 (several
+ * rows per wavefront, up to 2 chunks per thread), 64 (up to 4 chunks), 256, 512
+ * or 1024 (up to 8 chunks); a chunk is 16 bytes of the row.  Other values:
+ * LAYERNORM_ERR_INVALID_ARG; a row that needs more chunks, or is not 16-byte
+ * aligned: LAYERNORM_ERR_UNSUPPORTED.
+ */
+int layernorm_fwd_tuned(const void* x, const void* w, const void* b, void* y, int64_t M,
+                        int64_t N, float eps, int dtype, void* stream, int threads_per_row);
+
+/* threads_per_row of the automatic path for 16-byte aligned rows of N elements; 0 if
+ * such rows go to the element-wise kernel; a negative layernorm_status for bad arguments. */
+int layernorm_auto_threads_per_row(int64_t N, int dtype);
+
+/* Largest N the register-resident kernels accept for `dtype`; 0 for a bad dtype. */
+int64_t layernorm_register_max_n(int dtype);
+
+/* Static, human-readable text for a status code. */
+const char* layernorm_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+
+#endif /* LAYERNORM_H_ */

@@ -12,6 +12,9 @@ SOFTMAX_LIB_PATH = os.path.join(_HERE, "libsoftmax_hip.so")
 
 SOURCES = ["rmsnorm_api.hip"]
 HEADERS = ["rmsnorm_kernels.h", "vec_io.h", "wave_reduce.h"]
+LAYERNORM_LIB_PATH = os.path.join(_HERE, "liblayernorm_hip.so")
+LAYERNORM_SOURCES = ["layernorm_api.hip"]
+LAYERNORM_HEADERS = ["layernorm_kernels.h", "vec_io.h", "wave_reduce.h"]
 SOFTMAX_SOURCES = ["softmax_api.hip"]
 SOFTMAX_HEADERS = ["softmax_kernels.h", "vec_io.h", "wave_reduce.h"]
 
@@ -45,14 +48,19 @@ def _compile(sources, lib_path: str, verbose: bool) -> str:
 
 
 def build(verbose: bool = False) -> str:
-    """Compiles csrc/ into librmsnorm_hip.so and libsoftmax_hip.so next to this file;
-    returns the path of the RMSNorm library."""
+    """Compiles csrc/ into librmsnorm_hip.so, libsoftmax_hip.so and liblayernorm_hip.so next
+    to this file; returns the path of the RMSNorm library."""
     _compile(SOFTMAX_SOURCES, SOFTMAX_LIB_PATH, verbose)
+    _compile(LAYERNORM_SOURCES, LAYERNORM_LIB_PATH, verbose)
     return _compile(SOURCES, LIB_PATH, verbose)
 
 
 def build_softmax(verbose: bool = False) -> str:
     return _compile(SOFTMAX_SOURCES, SOFTMAX_LIB_PATH, verbose)
+
+
+def build_layernorm(verbose: bool = False) -> str:
+    return _compile(LAYERNORM_SOURCES, LAYERNORM_LIB_PATH, verbose)
 
 
 def is_stale() -> bool:

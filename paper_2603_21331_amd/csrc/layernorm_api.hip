@@ -1,0 +1,261 @@
+// C ABI of the row LayerNorm library: argument checks, kernel choice, launch.
+// Declarations and the full contract are in include/layernorm.h.
+#include "../../include/layernorm.h"
+
+#include <hip/hip_runtime.h>
+
+#include "layernorm_kernels.h"
+
+namespace {
+
+using rms::u32x4;
+
+// Instantiated (threads per row : chunks per thread); a chunk is one 16-byte vector.
+//   8, 16, 32 : 1..2     64 : 1..4     256, 512, 1024 : 1..8
+constexpr int kSubwaveMaxChunks = 2;
+constexpr int kWaveMaxChunks = 4;
+constexpr int kBlockMaxChunks = 8;
+constexpr int kMaxThreads = 1024;
+constexpr int kSmallRowVectors = 256;
+constexpr int kGenericThreads = 256;
+constexpr int64_t kMaxGrid = 1 << 20;
+
+int elem_bytes(int dtype) {
+  switch (dtype) {
+    case LAYERNORM_DTYPE_FP32: return 4;
+    case LAYERNORM_DTYPE_FP16: return 2;
+    case LAYERNORM_DTYPE_BF16: return 2;
+    default: return 0;
+  }
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// b may be null (no bias); everything else is required when M > 0.
+int check_args(const void* x, const void* w, const void* b, const void* y, int64_t M, int64_t N,
+               float eps, int dtype) {
+  if (elem_bytes(dtype) == 0) return LAYERNORM_ERR_INVALID_ARG;
+  if (M < 0 || N <= 0) return LAYERNORM_ERR_INVALID_ARG;
+  if (!(eps >= 0.0f)) return LAYERNORM_ERR_INVALID_ARG;
+  if (M > 0 && (!x || !w || !y)) return LAYERNORM_ERR_INVALID_ARG;
+  if (M > INT64_MAX / N) return LAYERNORM_ERR_INVALID_ARG;
+  const uintptr_t mask = (uintptr_t)elem_bytes(dtype) - 1;
+  if (M > 0 && (((uintptr_t)x | (uintptr_t)w | (uintptr_t)b | (uintptr_t)y) & mask))
+    return LAYERNORM_ERR_INVALID_ARG;
+  return LAYERNORM_OK;
+}
+
+bool rows_vectorisable(const void* x, const void* w, const void* b, const void* y, int64_t N,
+                       int dtype) {
+  return aligned16(x) && aligned16(w) && aligned16(b) && aligned16(y) &&
+         (N * elem_bytes(dtype)) % 16 == 0;
+}
+
+int max_chunks_for(int threads) {
+  switch (threads) {
+    case 8: case 16: case 32: return kSubwaveMaxChunks;
+    case 64: return kWaveMaxChunks;
+    case 256: case 512: case 1024: return kBlockMaxChunks;
+    default: return 0;
+  }
+}
+
+bool threads_can(int threads, int64_t nvec) {
+  const int mc = max_chunks_for(threads);
+  return mc > 0 && nvec >= 1 && (nvec + threads - 1) / threads <= mc;
+}
+
+// Same bands as the RMSNorm dispatch, which the same sweeps support: lane groups
+// for rows up to 32 vectors, one wavefront up to 256 vectors, then 256, 512 and
+// 1024 threads while a thread holds at most 8 chunks.  0: does not fit.
+int pick_threads(int64_t nvec, int min_threads) {
+  if (min_threads <= 8)
+    for (int l = 8; l <= 32; l *= 2)
+      if (nvec <= l) return l;
+  if (min_threads <= 64 && nvec <= kSmallRowVectors) return 64;
+  for (int g = 256; g <= kMaxThreads; g *= 2)
+    if (g >= min_threads && threads_can(g, nvec)) return g;
+  return 0;
+}
+
+struct Args {
+  const void* x;
+  const void* w;
+  const void* b;
+  void* y;
+  int64_t M;
+  int64_t N;
+  int nvec;
+  float eps;
+  hipStream_t stream;
+};
+
+template <int DT, int CHUNKS, int G>
+void launch_row(const Args& a) {
+  const int64_t blocks = a.M < kMaxGrid ? a.M : kMaxGrid;
+  hipLaunchKernelGGL((rms::layernorm_row_kernel<DT, CHUNKS, G, true>), dim3((unsigned)blocks),
+                     dim3(G), 0, a.stream, (const u32x4*)a.x, (const u32x4*)a.w,
+                     (const u32x4*)a.b, (u32x4*)a.y, a.M, a.nvec, (float)a.N, a.eps);
+}
+
+template <int DT, int CHUNKS, int L>
+void launch_subwave(const Args& a) {
+  constexpr int kRows = rms::kLnWave / L;
+  int64_t blocks = (a.M + kRows - 1) / kRows;
+  if (blocks > ((int64_t)1 << 24)) blocks = (int64_t)1 << 24;
+  hipLaunchKernelGGL((rms::layernorm_subwave_kernel<DT, CHUNKS, L, true>), dim3((unsigned)blocks),
+                     dim3(rms::kLnWave), 0, a.stream, (const u32x4*)a.x, (const u32x4*)a.w,
+                     (const u32x4*)a.b, (u32x4*)a.y, a.M, a.nvec, (float)a.N, a.eps);
+}
+
+template <int DT>
+void launch_generic(const Args& a) {
+  const int64_t blocks = a.M < kMaxGrid ? a.M : kMaxGrid;
+  hipLaunchKernelGGL((rms::layernorm_generic_kernel<DT, kGenericThreads>), dim3((unsigned)blocks),
+                     dim3(kGenericThreads), 0, a.stream, a.x, a.w, a.b, a.y, a.M, a.N, (float)a.N,
+                     a.eps);
+}
+
+#define LN_CASE(n, call) case n: call; break;
+#define LN_CASES_1_8(M_)                                                          \
+  LN_CASE(1, M_(1)) LN_CASE(2, M_(2)) LN_CASE(3, M_(3)) LN_CASE(4, M_(4))         \
+  LN_CASE(5, M_(5)) LN_CASE(6, M_(6)) LN_CASE(7, M_(7)) LN_CASE(8, M_(8))
+
+template <int DT>
+int dispatch(const Args& a, int threads) {
+  const int chunks = (a.nvec + threads - 1) / threads;
+  switch (threads) {
+    case 8:
+      if (chunks == 1) launch_subwave<DT, 1, 8>(a); else launch_subwave<DT, 2, 8>(a);
+      break;
+    case 16:
+      if (chunks == 1) launch_subwave<DT, 1, 16>(a); else launch_subwave<DT, 2, 16>(a);
+      break;
+    case 32:
+      if (chunks == 1) launch_subwave<DT, 1, 32>(a); else launch_subwave<DT, 2, 32>(a);
+      break;
+    case 64:
+#define LN_L(c) launch_row<DT, c, 64>(a)
+      switch (chunks) {
+        LN_CASE(1, LN_L(1)) LN_CASE(2, LN_L(2)) LN_CASE(3, LN_L(3)) LN_CASE(4, LN_L(4))
+        default: return LAYERNORM_ERR_UNSUPPORTED;
+      }
+#undef LN_L
+      break;
+    case 256:
+#define LN_L(c) launch_row<DT, c, 256>(a)
+      switch (chunks) { LN_CASES_1_8(LN_L) default: return LAYERNORM_ERR_UNSUPPORTED; }
+#undef LN_L
+      break;
+    case 512:
+#define LN_L(c) launch_row<DT, c, 512>(a)
+      switch (chunks) { LN_CASES_1_8(LN_L) default: return LAYERNORM_ERR_UNSUPPORTED; }
+#undef LN_L
+      break;
+    case 1024:
+#define LN_L(c) launch_row<DT, c, 1024>(a)
+      switch (chunks) { LN_CASES_1_8(LN_L) default: return LAYERNORM_ERR_UNSUPPORTED; }
+#undef LN_L
+      break;
+    default:
+      return LAYERNORM_ERR_UNSUPPORTED;
+  }
+  return LAYERNORM_OK;
+}
+
+template <int DT>
+int run_typed(const Args& a, int threads) {
+  int rc = LAYERNORM_OK;
+  if (threads == 0) launch_generic<DT>(a);
+  else rc = dispatch<DT>(a, threads);
+  if (rc != LAYERNORM_OK) return rc;
+  return hipGetLastError() == hipSuccess ? LAYERNORM_OK : LAYERNORM_ERR_LAUNCH;
+}
+
+// variant: a layernorm_variant, or -1 with `threads` forced by the caller.
+int run(const void* x, const void* w, const void* b, void* y, int64_t M, int64_t N, float eps,
+        int dtype, void* stream, int variant, int threads) {
+  int rc = check_args(x, w, b, y, M, N, eps, dtype);
+  if (rc != LAYERNORM_OK) return rc;
+  if (variant < -1 || variant > LAYERNORM_VARIANT_SUBWAVE) return LAYERNORM_ERR_INVALID_ARG;
+  if (variant == -1 && max_chunks_for(threads) == 0) return LAYERNORM_ERR_INVALID_ARG;
+  if (M == 0) return LAYERNORM_OK;
+
+  const bool vec_ok = rows_vectorisable(x, w, b, y, N, dtype);
+  const int64_t nvec = vec_ok ? N * elem_bytes(dtype) / 16 : 0;
+  switch (variant) {
+    case LAYERNORM_VARIANT_AUTO:
+      threads = vec_ok ? pick_threads(nvec, 8) : 0;
+      break;
+    case -1:
+      if (!(vec_ok && threads_can(threads, nvec))) return LAYERNORM_ERR_UNSUPPORTED;
+      break;
+    case LAYERNORM_VARIANT_SUBWAVE:
+      threads = nvec <= 8 ? 8 : nvec <= 16 ? 16 : 32;
+      if (!(vec_ok && threads_can(threads, nvec))) return LAYERNORM_ERR_UNSUPPORTED;
+      break;
+    case LAYERNORM_VARIANT_WAVE:
+      if (!(vec_ok && threads_can(64, nvec))) return LAYERNORM_ERR_UNSUPPORTED;
+      threads = 64;
+      break;
+    case LAYERNORM_VARIANT_BLOCK:
+      threads = vec_ok ? pick_threads(nvec, 256) : 0;
+      if (threads == 0) return LAYERNORM_ERR_UNSUPPORTED;
+      break;
+    default:
+      threads = 0;
+      break;
+  }
+
+  Args a{x, w, b, y, M, N, (int)nvec, eps, static_cast<hipStream_t>(stream)};
+  switch (dtype) {
+    case LAYERNORM_DTYPE_FP32: return run_typed<rms::kFp32>(a, threads);
+    case LAYERNORM_DTYPE_FP16: return run_typed<rms::kFp16>(a, threads);
+    case LAYERNORM_DTYPE_BF16: return run_typed<rms::kBf16>(a, threads);
+    default: return LAYERNORM_ERR_INVALID_ARG;
+  }
+}
+
+}  // namespace
+
+extern "C" {
+
+int layernorm_fwd(const void* x, const void* w, const void* b, void* y, int64_t M, int64_t N,
+                  float eps, int dtype, void* stream) {
+  return run(x, w, b, y, M, N, eps, dtype, stream, LAYERNORM_VARIANT_AUTO, 0);
+}
+
+int layernorm_fwd_variant(const void* x, const void* w, const void* b, void* y, int64_t M,
+                          int64_t N, float eps, int dtype, void* stream, int variant) {
+  if (variant < LAYERNORM_VARIANT_AUTO) return LAYERNORM_ERR_INVALID_ARG;
+  return run(x, w, b, y, M, N, eps, dtype, stream, variant, 0);
+}
+
+int layernorm_fwd_tuned(const void* x, const void* w, const void* b, void* y, int64_t M,
+                        int64_t N, float eps, int dtype, void* stream, int threads_per_row) {
+  return run(x, w, b, y, M, N, eps, dtype, stream, -1, threads_per_row);
+}
+
+int layernorm_auto_threads_per_row(int64_t N, int dtype) {
+  const int b = elem_bytes(dtype);
+  if (b == 0 || N <= 0) return LAYERNORM_ERR_INVALID_ARG;
+  if ((N * b) % 16 != 0) return 0;
+  return pick_threads(N * b / 16, 8);
+}
+
+int64_t layernorm_register_max_n(int dtype) {
+  const int b = elem_bytes(dtype);
+  return b ? (int64_t)kMaxThreads * kBlockMaxChunks * (16 / b) : 0;
+}
+
+const char* layernorm_status_string(int status) {
+  switch (status) {
+    case LAYERNORM_OK: return "ok";
+    case LAYERNORM_ERR_INVALID_ARG: return "invalid argument";
+    case LAYERNORM_ERR_UNSUPPORTED: return "kernel does not support this shape or alignment";
+    case LAYERNORM_ERR_LAUNCH: return "kernel launch failed";
+    default: return "unknown status";
+  }
+}
+
+}  // extern "C"

@@ -232,3 +232,27 @@ def softmax_paper_shape(n: int, seed: int = 0):
 def softmax_bytes(M: int, N: int, dtype: int) -> int:
     """Read x once, write y once (the model behind the paper's GB/s column for softmax)."""
     return 2 * M * N * DTYPE_BYTES[dtype]
+
+
+# ----------------------------------------------------------------------------
+# LayerNorm workloads (the paper's table lists 4096 x 5120 and 8192 x 4096, FP16)
+# ----------------------------------------------------------------------------
+
+def layernorm_case(seed: int, stream: int, M: int, N: int, dtype: int, eps: float = 1e-5,
+                   mean: float = 0.0, std: float = 1.0, bias: bool = True):
+    """x ~ N(mean, std), w ~ N(1, 0.1), b ~ N(0, 0.1) (or no bias) at any shape."""
+    return dict(name=f"layernorm_{DTYPE_NAMES[dtype]}_{M}x{N}", dtype=dtype, M=M, N=N, eps=eps,
+                x=normal_matrix(seed, stream, M, N, dtype, mean, std),
+                w=normal_matrix(seed, stream + 1, 1, N, dtype, 1.0, 0.1)[0],
+                b=normal_matrix(seed, stream + 2, 1, N, dtype, 0.0, 0.1)[0] if bias else None)
+
+
+def layernorm_paper_shape(which: int, seed: int = 0):
+    """FP16 4096 x 5120 (which = 0) or 8192 x 4096 (which = 1): the paper's two LayerNorm rows."""
+    M, N = ((4096, 5120), (8192, 4096))[which]
+    return layernorm_case(seed, 112 + 4 * which, M, N, FP16)
+
+
+def layernorm_bytes(M: int, N: int, dtype: int) -> int:
+    """Read x once, write y once, read w and b once."""
+    return (2 * M * N + 2 * N) * DTYPE_BYTES[dtype]

@@ -104,3 +104,61 @@ def check_softmax_parity(got: np.ndarray, want: np.ndarray, dtype: int, what: st
     assert worst <= TOL_ULP[dtype], (
         f"{what}: max ulp distance {worst} > {TOL_ULP[dtype]} (first at flat index {int(np.argmax(d))})")
     return {"max_ulp": worst, "frac_off": float(np.count_nonzero(d)) / max(d.size, 1)}
+
+
+# ---- LayerNorm -----------------------------------------------------------------------------
+# LayerNorm subtracts (the mean from x, possibly the bias against the scaled value), so any
+# fp32 implementation carries an ABSOLUTE error of a few fp32 ulps of the row's scale, which
+# is not small relative to an output that happens to land near zero.  An element passes if
+# it meets the relative bound of the other kernels (fp32 1e-5; bf16 1 ulp; fp16 2 ulp against
+# the oracle after its rounding) OR lies within 2^-20 of the element's scale
+# |w_j| * max_j |z_i| + |b_j|, where z_i is the normalised row (from the oracle's fp64 mean
+# and rstd).
+LAYERNORM_ABS = 2.0 ** -20
+
+
+def check_layernorm_parity(got, want, scale, dtype: int, what: str = "") -> dict:
+    """scale: (M, N) fp64 array of |w_j| * max|z_i| + |b_j| (see layernorm_scale)."""
+    got = np.asarray(got)
+    want = np.asarray(want)
+    assert got.shape == want.shape, f"{what}: shape {got.shape} vs {want.shape}"
+    if dtype == 0:
+        g = got.astype(np.float64)
+        o = want.astype(np.float64)
+        assert np.array_equal(np.isnan(g), np.isnan(o)), f"{what}: NaN positions differ"
+        ok = ~np.isnan(o)
+        diff = np.abs(g - o)
+        rel_ok = diff <= TOL_FP32_REL * np.abs(o)
+        abs_ok = diff <= LAYERNORM_ABS * scale
+        bad = ok & ~(rel_ok | abs_ok)
+        assert not bad.any(), (f"{what}: {int(bad.sum())} fp32 elements outside both bounds; first at "
+                               f"{tuple(np.argwhere(bad)[0])}: got {g[bad][0]!r} want {o[bad][0]!r}")
+        worst = float((diff / np.maximum(scale, FLT_MIN))[ok].max()) if ok.any() else 0.0
+        return {"max_err_over_scale": worst, "frac_abs_only": float((ok & ~rel_ok).mean())}
+    from_bits = _f64_from_16
+    d = ulp_distance(got, want, dtype)
+    ulp_ok = d <= TOL_ULP[dtype]
+    diff = np.abs(from_bits(got, dtype) - from_bits(want, dtype))
+    with np.errstate(invalid="ignore"):
+        abs_ok = diff <= LAYERNORM_ABS * scale
+    bad = ~(ulp_ok | abs_ok)
+    assert not bad.any(), (f"{what}: {int(bad.sum())} elements outside both bounds; first at "
+                           f"{tuple(np.argwhere(bad)[0])}, ulp distance {int(d[bad][0])}")
+    return {"max_ulp_where_relative": int(d[ulp_ok].max()) if ulp_ok.any() else 0,
+            "frac_off": float(np.count_nonzero(d)) / max(d.size, 1),
+            "frac_abs_only": float((~ulp_ok).mean())}
+
+
+def _f64_from_16(bits, dtype: int) -> np.ndarray:
+    b = np.asarray(bits, dtype=np.uint16)
+    if dtype == 1:
+        return b.view(np.float16).astype(np.float64)
+    return (b.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+
+
+def layernorm_scale(x_f64, w_f64, b_f64, mean, rstd) -> np.ndarray:
+    zmax = (np.abs(x_f64 - mean[:, None]) * rstd[:, None]).max(axis=1)
+    s = np.abs(w_f64)[None, :] * zmax[:, None]
+    if b_f64 is not None:
+        s = s + np.abs(b_f64)[None, :]
+    return s

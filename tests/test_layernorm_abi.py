@@ -1,0 +1,74 @@
+"""Host-side checks of the layernorm C ABI that need no GPU."""
+import os
+import re
+
+import pytest
+
+from paper_2603_21331_amd import layernorm
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "layernorm.h")
+P = 0x10000
+BIG = 1 << 24
+
+
+def declared_functions():
+    text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
+    return sorted(set(re.findall(r"\b(layernorm_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    lib = layernorm.load()
+    names = declared_functions()
+    assert "layernorm_fwd" in names and "layernorm_fwd_tuned" in names
+    for name in names:
+        assert hasattr(lib, name), f"{name} is declared in layernorm.h but not exported"
+        assert hasattr(layernorm, name), f"binding lacks {name}"
+
+
+def test_enum_values_match_the_header():
+    for name, value in re.findall(r"\b(LAYERNORM_[A-Z0-9_]+)\s*=\s*(-?\d+)", open(HEADER).read()):
+        assert getattr(layernorm, name) == int(value), name
+
+
+@pytest.mark.parametrize("args", [dict(x=0), dict(y=0), dict(w=0), dict(eps=-1.0), dict(eps=float("nan")),
+                                  dict(b=P + 3 * BIG + 1, dtype=1), dict(M=-1), dict(N=0), dict(dtype=3),
+                                  dict(dtype=-1), dict(x=P + 1, dtype=1), dict(M=1 << 40, N=1 << 40)])
+def test_invalid_arguments_are_rejected_without_a_launch(args):
+    lib = layernorm.load()
+    a = dict(x=P, w=P + 2 * BIG, b=P + 3 * BIG, y=P + BIG, M=4, N=8, eps=1e-5, dtype=2)
+    a.update(args)
+    assert lib.layernorm_fwd(a["x"], a["w"], a["b"], a["y"], a["M"], a["N"], a["eps"], a["dtype"], None) == \
+        layernorm.LAYERNORM_ERR_INVALID_ARG
+    assert lib.layernorm_fwd_variant(a["x"], a["w"], a["b"], a["y"], a["M"], a["N"], a["eps"], a["dtype"],
+                                     None, 3) == layernorm.LAYERNORM_ERR_INVALID_ARG
+
+
+def test_empty_batch_unknown_variant_and_unsupported_shapes():
+    lib = layernorm.load()
+    W, B, Y = P + 2 * BIG, P + 3 * BIG, P + BIG
+    assert lib.layernorm_fwd(None, None, None, None, 0, 16, 1e-5, 2, None) == layernorm.LAYERNORM_OK
+    assert lib.layernorm_fwd_variant(P, W, B, Y, 4, 8, 1e-5, 2, None, 9) == layernorm.LAYERNORM_ERR_INVALID_ARG
+    assert lib.layernorm_fwd_variant(P, W, B, Y, 4, 8, 1e-5, 2, None, -1) == layernorm.LAYERNORM_ERR_INVALID_ARG
+    for bad in (0, 4, 128, 2048):
+        assert lib.layernorm_fwd_tuned(P, W, B, Y, 4, 4096, 1e-5, 2, None, bad) == layernorm.LAYERNORM_ERR_INVALID_ARG
+    for v in (1, 2, 4):
+        assert lib.layernorm_fwd_variant(P, W, B, Y, 4, 7, 1e-5, 2, None, v) == layernorm.LAYERNORM_ERR_UNSUPPORTED
+        # a misaligned bias pointer alone also rules the vector kernels out
+        assert lib.layernorm_fwd_variant(P, W, B + 2, Y, 4, 64, 1e-5, 2, None, v) == layernorm.LAYERNORM_ERR_UNSUPPORTED
+    assert lib.layernorm_fwd_variant(P, W, B, Y, 4, 4096, 1e-5, 2, None, 1) == layernorm.LAYERNORM_ERR_UNSUPPORTED
+    assert lib.layernorm_fwd_variant(P, W, None, Y, 4, 1024, 1e-5, 2, None, 4) == layernorm.LAYERNORM_ERR_UNSUPPORTED
+    assert lib.layernorm_fwd_tuned(P, W, B, Y, 1, 65544, 1e-5, 2, None, 1024) == layernorm.LAYERNORM_ERR_UNSUPPORTED
+
+
+def test_automatic_threads_per_row():
+    auto = layernorm.layernorm_auto_threads_per_row
+    assert auto(64, 1) == 8 and auto(128, 2) == 16 and auto(256, 1) == 32 and auto(512, 1) == 64
+    assert auto(2048, 2) == 64 and auto(4096, 1) == 256 and auto(8192, 1) == 256
+    assert auto(16384, 2) == 256 and auto(32768, 1) == 512 and auto(65536, 2) == 1024
+    assert auto(65544, 2) == 0 and auto(1023, 1) == 0
+    assert auto(8192, 0) == 256 and auto(32768, 0) == 1024 and auto(32772, 0) == 0
+    assert layernorm.layernorm_register_max_n(1) == 65536 and layernorm.layernorm_register_max_n(0) == 32768
+    with pytest.raises(layernorm.LayerNormError):
+        auto(0, 1)
+    assert layernorm.layernorm_status_string(0) == "ok" and layernorm.layernorm_status_string(-2)
