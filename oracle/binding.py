@@ -16,9 +16,12 @@ _SOFTMAX_SRC = os.path.join(_HERE, "softmax_oracle.cpp")
 _SOFTMAX_LIB = os.path.join(_HERE, "libsoftmax_oracle.so")
 _LAYERNORM_SRC = os.path.join(_HERE, "layernorm_oracle.cpp")
 _LAYERNORM_LIB = os.path.join(_HERE, "liblayernorm_oracle.so")
+_CE_SRC = os.path.join(_HERE, "crossentropy_oracle.cpp")
+_CE_LIB = os.path.join(_HERE, "libcrossentropy_oracle.so")
 _lib = None
 _softmax_lib = None
 _layernorm_lib = None
+_ce_lib = None
 
 
 def _compile(src: str, lib: str, force: bool) -> str:
@@ -33,6 +36,7 @@ def build(force: bool = True) -> str:
     """Compiles the oracles with the host compiler.  No GPU toolchain involved."""
     _compile(_SOFTMAX_SRC, _SOFTMAX_LIB, force)
     _compile(_LAYERNORM_SRC, _LAYERNORM_LIB, force)
+    _compile(_CE_SRC, _CE_LIB, force)
     return _compile(_SRC, _LIB, force)
 
 
@@ -190,3 +194,38 @@ def layernorm_oracle(x, w, b, eps: float, dtype: int, nthreads: int = 0, stats: 
     if rc != 0:
         raise ValueError(f"layernorm_oracle rejected its arguments (rc={rc})")
     return (y, mean, rstd) if stats else y
+
+
+# ------------------------------------------------------------------ row cross-entropy
+
+def _load_crossentropy():
+    global _ce_lib
+    if _ce_lib is None:
+        # CROSSENTROPY_ORACLE_LIB: the mutation test's hook, as for the other oracles.
+        lib = ctypes.CDLL(os.environ.get("CROSSENTROPY_ORACLE_LIB") or _compile(_CE_SRC, _CE_LIB, False))
+        vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
+        lib.crossentropy_oracle.argtypes = [vp, vp, vp, vp, i64, i64, i32, i32]
+        lib.crossentropy_oracle.restype = i32
+        _ce_lib = lib
+    return _ce_lib
+
+
+def crossentropy_oracle(x, target, dtype: int, nthreads: int = 0, with_lse: bool = False):
+    """Per-row loss (float32, M entries) of (M, N) logits in storage form and int64 targets.
+
+    Returns loss, or (loss, lse) with the fp64 log-sum-exp of each row when with_lse is true."""
+    x = _as_storage(x, dtype)
+    target = np.ascontiguousarray(np.asarray(target))
+    if target.dtype != np.int64:
+        raise TypeError(f"targets must be int64, got {target.dtype}")
+    if x.ndim != 2 or target.shape != (x.shape[0],):
+        raise ValueError(f"shape mismatch: x {x.shape}, target {target.shape}")
+    M, N = x.shape
+    loss = np.empty(M, dtype=np.float32)
+    lse = np.empty(M, dtype=np.float64) if with_lse else None
+    rc = _load_crossentropy().crossentropy_oracle(
+        x.ctypes.data, target.ctypes.data, loss.ctypes.data,
+        None if lse is None else lse.ctypes.data, M, N, dtype, nthreads)
+    if rc != 0:
+        raise ValueError(f"crossentropy_oracle rejected its arguments (rc={rc})")
+    return (loss, lse) if with_lse else loss

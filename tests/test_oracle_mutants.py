@@ -95,6 +95,29 @@ LAYERNORM_MUTANTS = {
 }
 
 
+CE_SRC = os.path.join(ROOT, "oracle", "crossentropy_oracle.cpp")
+CE_PINS = os.path.join(ROOT, "tests", "test_crossentropy_oracle_pins.py")
+
+CE_MUTANTS = {
+    "no_max_subtraction": ("s += std::exp(logit(x, i * N + j, dtype) - m);", "s += std::exp(logit(x, i * N + j, dtype));"),
+    "base_two_exponential": ("s += std::exp(logit(", "s += std::exp2(logit("),
+    "log_base_two": ("static_cast<float>(std::log(s) -", "static_cast<float>(std::log2(s) -"),
+    "first_term_missing": ("    for (int64_t j = 0; j < N; ++j) s +=", "    for (int64_t j = (N > 1 ? 1 : 0); j < N; ++j) s +="),
+    "mean_instead_of_sum": ("static_cast<float>(std::log(s) -", "static_cast<float>(std::log(s / (double)N) -"),
+    "sign_of_the_picked_logit": ("- (logit(x, i * N + t, dtype) - m));", "+ (logit(x, i * N + t, dtype) - m));"),
+    "target_of_the_wrong_row": ("- (logit(x, i * N + t, dtype) - m));", "- (logit(x, ((i + 1) % (r1 > 1 ? r1 : 1)) * N + t, dtype) - m));"),
+    "target_off_by_one": ("- (logit(x, i * N + t, dtype) - m));", "- (logit(x, i * N + (t + 1) % N, dtype) - m));"),
+    "max_not_added_back_to_lse_but_loss_uses_lse": ("static_cast<float>(std::log(s) - (logit(x, i * N + t, dtype) - m));",
+                                                    "static_cast<float>(std::log(s) - logit(x, i * N + t, dtype));"),
+    "ignored_rows_not_zero": ("      loss[i] = 0.0f;                         // ignored row", "      loss[i] = static_cast<float>(lse);"),
+    "ignore_only_negative": ("if (t < 0 || t >= N) {", "if (t < 0) { loss[i] = 0.0f; } else if (t >= N) { loss[i] = 1.0f; } else if (false) {"),
+    "rounds_through_bf16_width": ("static_cast<float>(std::log(s) - (logit(x, i * N + t, dtype) - m));",
+                                  "static_cast<float>(std::ldexp(std::nearbyint(std::ldexp(std::log(s) - (logit(x, i * N + t, dtype) - m), 20)), -20));"),
+    "half_decoded_with_wrong_bias": ("v = std::ldexp(static_cast<double>(frac + 1024), ex - 25);", "v = std::ldexp(static_cast<double>(frac + 1024), ex - 24);"),
+    "bf16_shift": ("static_cast<uint32_t>(h) << 16;", "static_cast<uint32_t>(h) << 15;"),
+}
+
+
 def _build(source_text: str, out_dir, name: str) -> str:
     cpp = os.path.join(out_dir, f"{name}.cpp")
     so = os.path.join(out_dir, f"{name}.so")
@@ -154,4 +177,19 @@ def test_planted_layernorm_mistake_is_caught(tmp_path, name):
     assert text.count(old) >= 1, f"mutation site for {name} not found; update the test"
     so = _build(text.replace(old, new), str(tmp_path), name)
     assert _run_pins(so, "LAYERNORM_ORACLE_LIB", LAYERNORM_PINS) != 0, \
+        f"no pin noticed the planted mistake '{name}'"
+
+
+def test_unmodified_crossentropy_oracle_passes_its_pins_through_the_same_route(tmp_path):
+    so = _build(open(CE_SRC).read(), str(tmp_path), "pristine_ce")
+    assert _run_pins(so, "CROSSENTROPY_ORACLE_LIB", CE_PINS) == 0
+
+
+@pytest.mark.parametrize("name", sorted(CE_MUTANTS))
+def test_planted_crossentropy_mistake_is_caught(tmp_path, name):
+    old, new = CE_MUTANTS[name]
+    text = open(CE_SRC).read()
+    assert text.count(old) >= 1, f"mutation site for {name} not found; update the test"
+    so = _build(text.replace(old, new), str(tmp_path), name)
+    assert _run_pins(so, "CROSSENTROPY_ORACLE_LIB", CE_PINS) != 0, \
         f"no pin noticed the planted mistake '{name}'"
