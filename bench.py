@@ -69,10 +69,11 @@ def main() -> int:
     ap.add_argument("--all-configs", action="store_true",
                     help="after the headline measurement, also time the other four workloads "
                          "(GPU and oracle) and add them to the JSON line under other_configs")
-    ap.add_argument("--op", choices=["rmsnorm", "softmax", "layernorm"], default="rmsnorm",
-                    help="rmsnorm (default): the headline benchmark.  softmax / layernorm: the same "
-                         "protocol on the next kernels at the paper's largest shape for each "
-                         "(fp16 8192 x 8192; fp16 8192 x 4096)")
+    ap.add_argument("--op", choices=["rmsnorm", "softmax", "layernorm", "crossentropy"],
+                    default="rmsnorm",
+                    help="rmsnorm (default): the headline benchmark.  softmax / layernorm / "
+                         "crossentropy: the same protocol on the next kernels at the paper's largest "
+                         "shape for each (fp16 8192 x 8192; fp16 8192 x 4096; fp16 8192 x 32000)")
     ap.add_argument("--profile-only", action="store_true",
                     help="warm-up plus --steps launches and nothing else (for rocprofv3 runs)")
     ap.add_argument("--calib-copy", action="store_true",
@@ -102,6 +103,8 @@ def main() -> int:
         return bench_softmax(args, dev)
     if args.op == "layernorm":
         return bench_layernorm(args, dev)
+    if args.op == "crossentropy":
+        return bench_crossentropy(args, dev)
 
     M, K, W, S = args.rows, args.steps, args.warmup, max(1, args.buffer_sets)
     t0 = time.time()
@@ -444,6 +447,95 @@ def bench_layernorm(args, dev) -> int:
         result["parity"] = {"checked": "every element of one output buffer",
                             **compare.check_layernorm_parity(got, y_ref, scale, inputs.FP16,
                                                              "bench layernorm")}
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+def bench_crossentropy(args, dev) -> int:
+    """Cross-entropy forward, fp16, 8192 x 32000 (the larger cross_ent row of the paper's
+    performance table: 253.3 us, 2070 GB/s on H100), same protocol as the headline benchmark."""
+    import numpy as np
+    import torch
+    from paper_2603_21331_amd import crossentropy, inputs
+
+    crossentropy.load()
+    K, W, S = args.steps, args.warmup, max(1, args.buffer_sets)
+    t0 = time.time()
+    case = inputs.crossentropy_paper_shape(1)
+    M, N = case["M"], case["N"]
+    log(f"generated {case['name']} in {time.time() - t0:.1f} s")
+    nbytes = inputs.crossentropy_bytes(M, N, inputs.FP16)
+    x0 = torch.from_numpy(case["x"].view(np.int16)).to(dev).view(torch.float16)
+    td = torch.from_numpy(case["target"]).to(dev)
+    xs = [x0] + [x0.clone() for _ in range(S - 1)]          # 4 x 500 MiB: past the Infinity Cache
+    losses = [torch.empty(M, dtype=torch.float32, device=dev) for _ in range(S)]
+    fns = [crossentropy.bind_crossentropy_fwd(xs[i], td, losses[i], None,
+                                              threads_per_row=args.threads_per_row) for i in range(S)]
+    for i in range(W):
+        fns[i % S]()
+    torch.cuda.synchronize()
+    if args.profile_only:
+        for i in range(K):
+            fns[i % S]()
+        torch.cuda.synchronize()
+        log("profile-only run done")
+        return 0
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    start.record()
+    for i in range(K):
+        fns[i % S]()
+    stop.record()
+    torch.cuda.synchronize()
+    ms_per_step = start.elapsed_time(stop) / K
+    value = nbytes / (ms_per_step * 1e-3) / 1e9
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+             for _ in range(K)]
+    for i, (a, b) in enumerate(pairs):
+        a.record()
+        fns[i % S]()
+        b.record()
+    torch.cuda.synchronize()
+    durs = [a.elapsed_time(b) * 1e3 for a, b in pairs]
+    mean_us = sum(durs) / len(durs)
+    result = {
+        "metric": "Cross-entropy fwd achieved HBM GB/s and % of MI355X peak (fp16, 8192x32000)",
+        "value": round(value, 1), "unit": "GB/s",
+        "pct_of_peak": round(100.0 * value / PEAK_HBM_GBPS, 2),
+        "rows_per_s": round(M / (ms_per_step * 1e-3), 1),
+        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(ms_per_step, 6),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"crossentropy_fwd fp16 M={M} N={N}, int64 targets, fp32 loss per row",
+                   "storage_dtype": "fp16",
+                   "threads_per_row": args.threads_per_row
+                   or crossentropy.crossentropy_auto_threads_per_row(N, inputs.FP16),
+                   "buffer_sets": S, "bytes_per_step": nbytes},
+        "roofline": {"bound": "hbm", "achieved": round(nbytes / (mean_us * 1e-6) / 1e9, 1),
+                     "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                     "frac": round(nbytes / (mean_us * 1e-6) / 1e9 / PEAK_HBM_GBPS, 4),
+                     "traffic": None, "kernel_mean_us": round(mean_us, 3),
+                     "kernel_trimmed_mean_us": round(trimmed_mean(durs), 3),
+                     "kernel_min_us": round(min(durs), 3)},
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        sys.path.insert(0, os.path.join(ROOT, "tests"))
+        import compare
+        cores = oracle.hardware_threads()
+        best, ref = None, None
+        for _ in range(2):
+            t = time.perf_counter()
+            ref = oracle.crossentropy_oracle(case["x"], case["target"], inputs.FP16, nthreads=cores)
+            dt = time.perf_counter() - t
+            best = dt if best is None else min(best, dt)
+        result["cpu_baseline"] = {"value": round(nbytes / best / 1e9, 3), "unit": "GB/s",
+                                  "cores": cores, "kind": "oracle",
+                                  "sample": f"the whole workload ({M} x {N}), best of 2 runs, "
+                                            f"{best:.3f} s each"}
+        got = losses[0].cpu().numpy()
+        result["parity"] = {"checked": "every loss of one output buffer",
+                            **compare.check_crossentropy_parity(got, ref, "bench crossentropy")}
     print(json.dumps(result), flush=True)
     return 0
 

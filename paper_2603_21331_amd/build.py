@@ -15,6 +15,9 @@ HEADERS = ["rmsnorm_kernels.h", "vec_io.h", "wave_reduce.h"]
 LAYERNORM_LIB_PATH = os.path.join(_HERE, "liblayernorm_hip.so")
 LAYERNORM_SOURCES = ["layernorm_api.hip"]
 LAYERNORM_HEADERS = ["layernorm_kernels.h", "vec_io.h", "wave_reduce.h"]
+CROSSENTROPY_LIB_PATH = os.path.join(_HERE, "libcrossentropy_hip.so")
+CROSSENTROPY_SOURCES = ["crossentropy_api.hip"]
+CROSSENTROPY_HEADERS = ["crossentropy_kernels.h", "vec_io.h", "wave_reduce.h"]
 SOFTMAX_SOURCES = ["softmax_api.hip"]
 SOFTMAX_HEADERS = ["softmax_kernels.h", "vec_io.h", "wave_reduce.h"]
 
@@ -48,10 +51,11 @@ def _compile(sources, lib_path: str, verbose: bool) -> str:
 
 
 def build(verbose: bool = False) -> str:
-    """Compiles csrc/ into librmsnorm_hip.so, libsoftmax_hip.so and liblayernorm_hip.so next
-    to this file; returns the path of the RMSNorm library."""
+    """Compiles csrc/ into librmsnorm_hip.so, libsoftmax_hip.so, liblayernorm_hip.so and
+    libcrossentropy_hip.so next to this file; returns the path of the RMSNorm library."""
     _compile(SOFTMAX_SOURCES, SOFTMAX_LIB_PATH, verbose)
     _compile(LAYERNORM_SOURCES, LAYERNORM_LIB_PATH, verbose)
+    _compile(CROSSENTROPY_SOURCES, CROSSENTROPY_LIB_PATH, verbose)
     return _compile(SOURCES, LIB_PATH, verbose)
 
 
@@ -70,6 +74,12 @@ def is_stale() -> bool:
     deps = [os.path.join(CSRC, f) for f in SOURCES + HEADERS]
     deps.append(os.path.join(ROOT, "include", "rmsnorm.h"))
     return any(os.path.getmtime(d) > built for d in deps)
+
+
+
+
+def build_crossentropy(verbose: bool = False) -> str:
+    return _compile(CROSSENTROPY_SOURCES, CROSSENTROPY_LIB_PATH, verbose)
 
 
 if __name__ == "__main__":

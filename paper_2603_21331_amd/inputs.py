@@ -256,3 +256,34 @@ def layernorm_paper_shape(which: int, seed: int = 0):
 def layernorm_bytes(M: int, N: int, dtype: int) -> int:
     """Read x once, write y once, read w and b once."""
     return (2 * M * N + 2 * N) * DTYPE_BYTES[dtype]
+
+
+# ----------------------------------------------------------------------------
+# Cross-entropy workloads (the paper's table lists 4096 x 32k and 8192 x 32k, FP16; its
+# throughput column fixes "32k" as 32000 classes and the bytes as one read of the logits)
+# ----------------------------------------------------------------------------
+
+IGNORED_TARGET = -100
+
+
+def crossentropy_case(seed: int, stream: int, M: int, N: int, dtype: int, std: float = 1.0,
+                      ignore_every: int = 0):
+    """Logits x ~ N(0, std), targets uniform over the N classes (stream + 1); with
+    ignore_every = k, rows 0, k, 2k, ... carry the out-of-range target that marks an ignored row."""
+    target = (raw_u64(seed, stream + 1, 0, M) % np.uint64(N)).astype(np.int64)
+    if ignore_every:
+        target[::ignore_every] = IGNORED_TARGET
+    return dict(name=f"crossentropy_{DTYPE_NAMES[dtype]}_{M}x{N}_std{std:g}", dtype=dtype, M=M, N=N,
+                x=normal_matrix(seed, stream, M, N, dtype, 0.0, std), target=target)
+
+
+def crossentropy_paper_shape(which: int, seed: int = 0):
+    """FP16 4096 x 32000 (which = 0) or 8192 x 32000 (which = 1): the paper's two cross_ent rows."""
+    M = (4096, 8192)[which]
+    return crossentropy_case(seed, 128 + 4 * which, M, 32000, FP16)
+
+
+def crossentropy_bytes(M: int, N: int, dtype: int) -> int:
+    """Read the logits once (the model behind the paper's GB/s column for cross_ent; the M
+    targets and M losses, 12 bytes per row, are left out as the paper leaves them out)."""
+    return M * N * DTYPE_BYTES[dtype]

@@ -162,3 +162,38 @@ def layernorm_scale(x_f64, w_f64, b_f64, mean, rstd) -> np.ndarray:
     if b_f64 is not None:
         s = s + np.abs(b_f64)[None, :]
     return s
+
+
+# ---- row cross-entropy ---------------------------------------------------------------------
+# loss = log(s) - (x_t - m) in fp32.  The sum s >= 1 is an fp32 sum of N rounded exponentials
+# (chains of at most ~100 additions per thread plus the fixed reduction tree, each rounding
+# 2^-24 of s), so log(s), and with it the loss, carries an ABSOLUTE error of up to ~100 * 2^-24
+# in the worst case (a few 1e-7 in practice) whatever the size of the loss; d_t = x_t - m and
+# the final subtraction add 2^-24 relative each.  Bound: 1e-5 relative (the fp32 tolerance of
+# the other kernels) plus 2^-17 absolute.  NaN and infinite results must agree exactly, and an
+# ignored row must be exactly 0.
+CROSSENTROPY_ABS = 2.0 ** -17
+
+
+def check_crossentropy_parity(got, want, what: str = "", exact_zero=None) -> dict:
+    """got: fp32 from the GPU; want: the oracle's values (fp32 losses or fp64 log-sum-exps).
+    exact_zero: optional boolean mask of rows whose result must be exactly 0."""
+    g = np.asarray(got).astype(np.float64)
+    o = np.asarray(want).astype(np.float64)
+    assert g.shape == o.shape, f"{what}: shape {g.shape} vs {o.shape}"
+    assert np.array_equal(np.isnan(g), np.isnan(o)), f"{what}: NaN positions differ"
+    inf = np.isinf(o)
+    assert np.array_equal(g[inf], o[inf]) and not np.isinf(g[~inf & ~np.isnan(o)]).any(), \
+        f"{what}: infinities differ"
+    if exact_zero is not None:
+        assert np.all(g[exact_zero] == 0.0), f"{what}: an ignored row is not exactly 0"
+    ok = np.isfinite(o)
+    if not ok.any():
+        return {"max_abs_err": 0.0, "max_excess_rel": 0.0}
+    diff = np.abs(g[ok] - o[ok])
+    bound = TOL_FP32_REL * np.abs(o[ok]) + CROSSENTROPY_ABS
+    worst = int(np.argmax(diff - bound))
+    assert np.all(diff <= bound), (f"{what}: |{g[ok][worst]!r} - {o[ok][worst]!r}| = {diff[worst]:.3e} "
+                                   f"> {bound[worst]:.3e}")
+    return {"max_abs_err": float(diff.max()),
+            "max_rel_err": float((diff / np.maximum(np.abs(o[ok]), 1.0)).max())}

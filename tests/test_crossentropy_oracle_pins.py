@@ -153,3 +153,29 @@ def test_oracle_rejects_bad_arguments():
     with pytest.raises(TypeError):
         oracle.crossentropy_oracle(x, np.array([0, 1]), BF16)
     assert oracle.crossentropy_oracle(np.zeros((0, 4), dtype=np.float32), np.zeros(0, dtype=np.int64), FP32).shape == (0,)
+
+
+def test_bytes_model_reproduces_the_papers_throughput_column():
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "paper_crossentropy_throughput.txt")
+    with open(path) as f:
+        rows = [ln.split() for ln in f if ln.strip() and not ln.startswith("#")]
+    assert len(rows) == 2
+    for M, N, us, gbps in rows:
+        M, N, us, gbps = int(M), int(N), float(us), float(gbps)
+        mine = inputs.crossentropy_bytes(M, N, FP16) / (us * 1e-6) / 1e9
+        assert abs(mine - gbps) / gbps < 1e-3, (M, N, mine, gbps)
+        other = inputs.crossentropy_bytes(M, 32768, FP16) / (us * 1e-6) / 1e9
+        assert abs(other - gbps) / gbps > 2e-2
+    case = inputs.crossentropy_paper_shape(0)
+    assert case["x"].shape == (4096, 32000) and case["target"].min() >= 0 and case["target"].max() < 32000
+
+
+def test_comparator_rejects_what_it_should():
+    import compare
+    compare.check_crossentropy_parity(np.float32([10.00005, 0.0, np.inf]), np.float32([10.0, 0.0, np.inf]))
+    for g, o in (([10.0002], [10.0]), ([1e-4], [0.0]), ([np.nan], [1.0]), ([1.0], [np.inf]), ([np.inf], [1.0])):
+        with pytest.raises(AssertionError):
+            compare.check_crossentropy_parity(np.float32(g), np.float32(o))
+    with pytest.raises(AssertionError):
+        compare.check_crossentropy_parity(np.float32([1e-7]), np.float32([0.0]), exact_zero=np.array([True]))
