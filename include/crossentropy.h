@@ -59,8 +59,8 @@ typedef enum {
 int crossentropy_fwd(const void* x, const int64_t* target, float* loss, float* lse, int64_t M,
                      int64_t N, int dtype, void* stream);
 
-/* Same, with the number of threads that share one row forced: 64, 256, 512 or 1024 (any
- * other value is CROSSENTROPY_ERR_INVALID_ARG).  Every count runs every shape. */
+/* Same, with the number of threads that share one row forced: a multiple of 64 from 64 to
+ * 1024 (any other value is CROSSENTROPY_ERR_INVALID_ARG).  Every count runs every shape. */
 int crossentropy_fwd_tuned(const void* x, const int64_t* target, float* loss, float* lse,
                            int64_t M, int64_t N, int dtype, void* stream, int threads_per_row);
 

@@ -9,6 +9,9 @@
 namespace {
 
 constexpr int kBatch = 4;                       // 16-byte vectors loaded per thread per step
+constexpr int kWave = 64;
+constexpr int kMaxThreads = 1024;
+constexpr int kWideThreads = 512;               // largest workgroup short of the full 1024
 constexpr int64_t kMaxGrid = 1 << 20;
 constexpr int64_t kMaxN = (int64_t)1 << 32;     // keeps the count of 16-byte groups well inside an int
 
@@ -21,14 +24,19 @@ int elem_bytes(int dtype) {
   }
 }
 
-bool threads_ok(int g) { return g == 64 || g == 256 || g == 512 || g == 1024; }
+bool threads_ok(int g) { return g >= kWave && g <= kMaxThreads && g % kWave == 0; }
 
-// One wavefront per row while a row is at most 256 groups (4 KiB); then 256 threads, and
-// 1024 once a thread of 256 would loop more than 16 times (rows beyond 256 KiB).
-int pick_threads(int64_t groups) {
-  if (groups <= 256) return 64;
-  if (groups <= 256 * kBatch * 16) return 256;
-  return 1024;
+// From sweeps on the GPU (fp16/bf16/fp32, N = 2048 ... 262144, 64 ... 1024 threads in steps
+// of a wavefront).  The best thread count gives a thread about two batches of a 16-bit type
+// (8 vectors) or one batch of fp32 (4 vectors): 16-bit logits cost twice the arithmetic per
+// byte, and a second batch lets it overlap the loads of the other wavefronts.  Workgroups of
+// more than 512 threads pay off only once every thread of 1024 still gets that much.
+int pick_threads(int64_t groups, int dtype) {
+  const int64_t per_thread = dtype == CROSSENTROPY_DTYPE_FP32 ? kBatch : 2 * kBatch;
+  const int64_t want = (groups + per_thread - 1) / per_thread;
+  if (want >= kMaxThreads) return kMaxThreads;
+  const int64_t rounded = (want + kWave - 1) / kWave * kWave;
+  return (int)(rounded < kWave ? kWave : rounded > kWideThreads ? kWideThreads : rounded);
 }
 
 int check_args(const void* x, const int64_t* target, const float* loss, const float* lse,
@@ -44,25 +52,12 @@ int check_args(const void* x, const int64_t* target, const float* loss, const fl
   return CROSSENTROPY_OK;
 }
 
-template <int DT, int G>
-void launch(const void* x, const int64_t* target, float* loss, float* lse, int64_t M, int64_t N,
-            hipStream_t stream) {
-  const int nfull = (int)(N / rms::Storage<DT>::kVec);
-  const int64_t blocks = M < kMaxGrid ? M : kMaxGrid;
-  hipLaunchKernelGGL((rms::crossentropy_row_kernel<DT, G, kBatch, true>), dim3((unsigned)blocks),
-                     dim3(G), 0, stream, x, target, loss, lse, M, N, nfull);
-}
-
 template <int DT>
 int run_typed(const void* x, const int64_t* target, float* loss, float* lse, int64_t M, int64_t N,
               hipStream_t stream, int threads) {
-  switch (threads) {
-    case 64: launch<DT, 64>(x, target, loss, lse, M, N, stream); break;
-    case 256: launch<DT, 256>(x, target, loss, lse, M, N, stream); break;
-    case 512: launch<DT, 512>(x, target, loss, lse, M, N, stream); break;
-    case 1024: launch<DT, 1024>(x, target, loss, lse, M, N, stream); break;
-    default: return CROSSENTROPY_ERR_INVALID_ARG;
-  }
+  const int64_t blocks = M < kMaxGrid ? M : kMaxGrid;
+  hipLaunchKernelGGL((rms::crossentropy_row_kernel<DT, kBatch, true>), dim3((unsigned)blocks),
+                     dim3((unsigned)threads), 0, stream, x, target, loss, lse, M, N);
   return hipGetLastError() == hipSuccess ? CROSSENTROPY_OK : CROSSENTROPY_ERR_LAUNCH;
 }
 
@@ -72,7 +67,7 @@ int run(const void* x, const int64_t* target, float* loss, float* lse, int64_t M
   if (rc != CROSSENTROPY_OK) return rc;
   if (threads != 0 && !threads_ok(threads)) return CROSSENTROPY_ERR_INVALID_ARG;
   if (M == 0) return CROSSENTROPY_OK;
-  if (threads == 0) threads = pick_threads(N / (16 / elem_bytes(dtype)));
+  if (threads == 0) threads = pick_threads(N / (16 / elem_bytes(dtype)), dtype);
   hipStream_t s = static_cast<hipStream_t>(stream);
   switch (dtype) {
     case CROSSENTROPY_DTYPE_FP32: return run_typed<rms::kFp32>(x, target, loss, lse, M, N, s, threads);
@@ -100,7 +95,7 @@ int crossentropy_fwd_tuned(const void* x, const int64_t* target, float* loss, fl
 int crossentropy_auto_threads_per_row(int64_t N, int dtype) {
   const int b = elem_bytes(dtype);
   if (b == 0 || N <= 0 || N >= kMaxN) return CROSSENTROPY_ERR_INVALID_ARG;
-  return pick_threads(N / (16 / b));
+  return pick_threads(N / (16 / b), dtype);
 }
 
 const char* crossentropy_status_string(int status) {

@@ -6,16 +6,15 @@
 // GB/s, "online log-sum-exp, fused NLL").  It only reads: every logit crosses HBM once and one
 // float per row goes back, so nothing has to stay in registers and rows of any length stream
 // through.  Each thread keeps a running maximum and a running sum of exponentials relative to
-// it (the online log-sum-exp the paper names), in batches: a batch of U 16-byte vectors is
-// loaded at once, its maximum taken first, the running sum rescaled at most once per batch,
+// it (the online log-sum-exp the paper names), in batches: a batch of up to 4 16-byte vectors
+// is loaded at once, its maximum taken first, the running sum rescaled at most once per batch,
 // and a subtract, a multiply and one v_exp_f32 spent per element.  The per-thread pairs are
 // combined in a fixed order (DPP maximum, rescale, DPP sum, LDS across wavefronts), so results
 // are bit-identical from run to run.
 //
-// Rows are addressed in elements with element-aligned 128-bit loads (single
-// global_load_dwordx4 instructions under the amdhsa unaligned-access mode), so odd class
-// counts such as 50257 run through the same code; the last N mod VEC logits of a row are
-// read one by one.
+// Any class count and any element-aligned base pointer run through the same code: each row
+// is cut at its own 16-byte boundaries (odd counts such as 50257 shift them from row to row)
+// and only the few logits outside the aligned body are read one by one.
 #pragma once
 
 #include "vec_io.h"
@@ -54,64 +53,106 @@ __device__ __forceinline__ void ce_fold(const float (&f)[COUNT], float& m, float
   s += (acc[0] + acc[1]) + (acc[2] + acc[3]);
 }
 
-template <int DT, int G, int U, bool NT>
-__global__ void __launch_bounds__(G)
+// 16 bytes of -inf in the storage type: what a thread folds where the row has no vector left.
+template <int DT>
+__device__ __forceinline__ u32x4 ce_neg_inf_vec() {
+  constexpr uint32_t p = DT == kFp32 ? 0xFF800000u : DT == kFp16 ? 0xFC00FC00u : 0xFF80FF80u;
+  u32x4 v = {p, p, p, p};
+  return v;
+}
+
+// Vectors (k0 + u) * G + t, u < COUNT, of the aligned body of a row: each load instruction
+// of a wavefront covers one contiguous kilobyte.  Indices past the body (only possible in a
+// thread's last vector) are clamped to the body's last vector, so that every load is
+// unconditional (a load inside a lane-dependent branch makes the compiler wait for the loads
+// before it, and the loads of a batch would go out one after the other); the lanes concerned
+// then fold -inf instead of what the clamped load brought.  Needs nfull >= 1.
+template <int DT, int COUNT, bool NT>
+__device__ __forceinline__ void ce_batch(const u32x4* body, int k0, int G, int t, int nfull,
+                                         float& m, float& s) {
+  constexpr int VEC = Storage<DT>::kVec;
+  u32x4 v[COUNT];
+#pragma unroll
+  for (int u = 0; u < COUNT; ++u) {
+    const int idx = (k0 + u) * G + t;
+    v[u] = load_vec<NT>(body + (idx < nfull ? idx : nfull - 1));
+  }
+  float f[COUNT * VEC];
+#pragma unroll
+  for (int u = 0; u < COUNT; ++u) {
+    if ((k0 + u) * G + t >= nfull) v[u] = ce_neg_inf_vec<DT>();
+    float g[VEC];
+    Storage<DT>::unpack(v[u], g);
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) f[u * VEC + k] = g[k];
+  }
+  ce_fold<COUNT * VEC>(f, m, s);
+}
+
+constexpr int kCeMaxWaves = 16;
+
+// One row per workgroup of G = blockDim.x threads, G any multiple of 64 up to 1024 (the host
+// picks it so that the vectors of a row divide evenly among the threads).
+template <int DT, int U, bool NT>
+__global__ void __launch_bounds__(kCeMaxWaves * kCeWave)
 crossentropy_row_kernel(const void* x, const int64_t* __restrict__ target, float* __restrict__ loss,
-                        float* __restrict__ lse_out, int64_t M, int64_t N, int nfull) {
+                        float* __restrict__ lse_out, int64_t M, int64_t N) {
   using S = Storage<DT>;
   constexpr int VEC = S::kVec;
-  constexpr int WAVES = G / kCeWave;
-  __shared__ float part_m[2][WAVES];
-  __shared__ float part_s[2][WAVES];
+  static_assert(U == 4, "the remainder switch below covers 1..3 vectors");
+  __shared__ float part_m[2][kCeMaxWaves];
+  __shared__ float part_s[2][kCeMaxWaves];
+  const int G = blockDim.x;
+  const int waves = G / kCeWave;
   const int t = threadIdx.x;
   const int lane = t & (kCeWave - 1);
   const int wave = t / kCeWave;
-  const int rem = (int)(N - (int64_t)nfull * VEC);
   int slot = 0;
 
   for (int64_t row = blockIdx.x; row < M; row += gridDim.x) {
+    // A row is cut into a head of single logits up to the next 16-byte boundary, a body of
+    // aligned 16-byte vectors, and a tail of single logits: whatever N and the base pointer
+    // are, the body moves with aligned 128-bit loads.
     const char* xr = static_cast<const char*>(x) + row * N * S::kBytes;
+    const int64_t to_boundary = (int64_t)((16u - (unsigned)((uintptr_t)xr & 15u)) & 15u) / S::kBytes;
+    const int head = (int)(to_boundary < N ? to_boundary : N);
+    const int nfull = (int)((N - head) / VEC);
+    const int rem = (int)(N - head - (int64_t)nfull * VEC);
+    const u32x4* body = reinterpret_cast<const u32x4*>(xr + head * S::kBytes);
+    const int per_thread = (nfull + G - 1) / G;          // vectors k * G + t, k < per_thread
     float m = kCeNegInf, s = 0.f;
 
-    for (int base = t; base < nfull; base += G * U) {
-      u32x4 v[U];
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int idx = base + u * G;
-        if (idx < nfull) v[u] = load_vec_unaligned<NT>(xr + (int64_t)idx * 16);
-      }
-      float f[U * VEC];
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        float g[VEC];
-        S::unpack(v[u], g);
-        const bool live = base + u * G < nfull;
-#pragma unroll
-        for (int k = 0; k < VEC; ++k) f[u * VEC + k] = live ? g[k] : kCeNegInf;
-      }
-      ce_fold<U * VEC>(f, m, s);
+    // Batches of U vectors per thread, one batch at a time (requesting the next batch before
+    // folding the current one was measured and is slower: more bytes in flight per compute
+    // unit, not fewer stalls), then the 1..3 vectors left over, so no load is wasted.
+    int k = 0;
+    for (; k + U <= per_thread; k += U) ce_batch<DT, U, NT>(body, k, G, t, nfull, m, s);
+    switch (per_thread - k) {                            // the same for every thread of the grid
+      case 1: ce_batch<DT, 1, NT>(body, k, G, t, nfull, m, s); break;
+      case 2: ce_batch<DT, 2, NT>(body, k, G, t, nfull, m, s); break;
+      case 3: ce_batch<DT, 3, NT>(body, k, G, t, nfull, m, s); break;
+      default: break;
     }
-    if (t < rem) {
-      const float tail[1] = {S::load_one(x, row * N + (int64_t)nfull * VEC + t)};
-      ce_fold<1>(tail, m, s);
+    if (t < head + rem) {                     // at most 2 * (VEC - 1) single logits per row
+      const int64_t j = t < head ? t : (int64_t)head + (int64_t)nfull * VEC + (t - head);
+      const float single[1] = {S::load_one(x, row * N + j)};
+      ce_fold<1>(single, m, s);
     }
 
     // combine the per-thread pairs: row maximum, rescale, row sum
     float row_m = wave_max(m);
-    if constexpr (WAVES > 1) {
+    if (waves > 1) {
       if (lane == 0) part_m[slot][wave] = row_m;
       __syncthreads();
       row_m = part_m[slot][0];
-#pragma unroll
-      for (int k = 1; k < WAVES; ++k) row_m = __builtin_fmaxf(row_m, part_m[slot][k]);
+      for (int w = 1; w < waves; ++w) row_m = __builtin_fmaxf(row_m, part_m[slot][w]);
     }
     float row_s = wave_sum(s * ce_rescale(m, row_m));
-    if constexpr (WAVES > 1) {
+    if (waves > 1) {
       if (lane == 0) part_s[slot][wave] = row_s;
       __syncthreads();
       row_s = part_s[slot][0];
-#pragma unroll
-      for (int k = 1; k < WAVES; ++k) row_s += part_s[slot][k];
+      for (int w = 1; w < waves; ++w) row_s += part_s[slot][w];
       slot ^= 1;
     }
 

@@ -78,22 +78,25 @@ bool threads_can(int threads, int64_t nvec, int dtype) {
 bool wave_can(int64_t nvec, int dtype) { return threads_can(64, nvec, dtype); }
 
 // Threads per row for the automatic path, from timing sweeps on MI355X over
-// N = 128 .. 131072 in all three dtypes: rows of up to 256 vectors (4 KiB) run
-// fastest with one wavefront per row; longer rows with 256 threads until a
-// thread would hold more than 8 chunks, then 512, then 1024.  Within those
+// N = 128 .. 131072 in all three dtypes, each timed in a sustained run (the
+// first milliseconds after idle run in a clock transient): rows of up to 256
+// vectors (4 KiB) run fastest with one wavefront per row; up to 704 vectors with
+// 256 threads; up to 2560 with 512 (at 1024 vectors, the headline row, two
+// chunks per thread beat four by 2 %); longer rows with 1024.  Within those
 // bands the neighbouring choices are within about 2 % of each other.
 // min_threads > 64 restricts the choice to the workgroup-per-row kernels.
 // Returns 0 if the row does not fit in registers at all.
+constexpr int64_t kMax256Vectors = 704;
+constexpr int64_t kMax512Vectors = 2560;
+
 int pick_threads(int64_t nvec, int min_threads, int dtype) {
   if (min_threads <= 8) {
     for (int l = 8; l <= 32; l *= 2)
       if (nvec <= l) return l;
   }
   if (min_threads <= 64 && nvec <= kSmallRowVectors && threads_can(64, nvec, dtype)) return 64;
-  for (int g = 256; g <= kBlockMaxThreads; g *= 2)
-    if (g >= min_threads && threads_can(g, nvec, dtype) &&
-        (nvec + g - 1) / g <= kMidMaxChunks)
-      return g;
+  if (nvec <= kMax256Vectors && min_threads <= 256 && threads_can(256, nvec, dtype)) return 256;
+  if (nvec <= kMax512Vectors && min_threads <= 512 && threads_can(512, nvec, dtype)) return 512;
   return threads_can(kBlockMaxThreads, nvec, dtype) ? kBlockMaxThreads : 0;
 }
 

@@ -101,13 +101,22 @@ __device__ __forceinline__ u32x4 scale_vec(u32x4 xv, u32x4 wv, float rstd) {
 // ---------------------------------------------------------------------------
 template <int DT, int CHUNKS, int G, bool NT>
 __global__ void __launch_bounds__(G)
-rmsnorm_row_kernel(const u32x4* x, const u32x4* __restrict__ w, u32x4* y,
+rmsnorm_row_kernel(const u32x4* x, const u32x4* w, u32x4* y,
                    int64_t M, int nvec, float n, float eps) {
   constexpr int WAVES = G / kWave;
-  // The weight chunks are fetched together with the row when the register
-  // budget allows (the launch bound caps a 1024-thread workgroup at 128 VGPRs),
-  // otherwise one by one in the epilogue.
-  constexpr bool W_EARLY = CHUNKS <= 8 || (G == kWave && CHUNKS <= 16);
+  // When the weight chunks are fetched.  The weight is re-read by every row and misses the
+  // compute unit's vector cache most of the time (the streaming row pushes it out), so its
+  // loads cost real bandwidth between L2 and the compute unit: measured at N = 8192 bf16,
+  // 3 to 5 % of the kernel.  Fetching them after the reduction, when the row's own loads
+  // have landed, takes them out of the way of those loads and recovers about a third of
+  // that; with a single chunk per thread there is nothing to get out of the way of and
+  // the extra latency only hurts.  Long rows (more than 8 chunks per thread) fetch one
+  // chunk at a time in the epilogue to stay inside the register budget (a 1024-thread
+  // workgroup is capped at 128 VGPRs); one wavefront per row keeps them with the row's loads.
+  constexpr int kWithRow = 0, kAfterReduce = 1, kOneByOne = 2;
+  constexpr int W_WHEN = G == kWave ? (CHUNKS <= 16 ? kWithRow : kOneByOne)
+                         : CHUNKS > 8 ? kOneByOne
+                         : CHUNKS > 1 ? kAfterReduce : kWithRow;
   __shared__ float partial[2][WAVES];
   const int t = threadIdx.x;
   const int lane = t & (kWave - 1);
@@ -119,7 +128,7 @@ rmsnorm_row_kernel(const u32x4* x, const u32x4* __restrict__ w, u32x4* y,
 
   for (int64_t row = blockIdx.x; row < M; row += gridDim.x) {
     const u32x4* xr = x + row * nvec;
-    u32x4* yr = y + row * nvec;
+    const __amdgpu_buffer_rsrc_t yr = row_resource(y + row * nvec, nvec * 16);
 
     u32x4 v[CHUNKS];
 #pragma unroll
@@ -127,8 +136,8 @@ rmsnorm_row_kernel(const u32x4* x, const u32x4* __restrict__ w, u32x4* y,
     v[CHUNKS - 1] = zero;
     if (last_ok) v[CHUNKS - 1] = load_vec<NT>(xr + last);
 
-    u32x4 wv[W_EARLY ? CHUNKS : 1];
-    if constexpr (W_EARLY) {
+    u32x4 wv[W_WHEN == kOneByOne ? 1 : CHUNKS];
+    if constexpr (W_WHEN == kWithRow) {
 #pragma unroll
       for (int c = 0; c < CHUNKS - 1; ++c) wv[c] = w[c * G + t];
       wv[CHUNKS - 1] = zero;
@@ -147,15 +156,27 @@ rmsnorm_row_kernel(const u32x4* x, const u32x4* __restrict__ w, u32x4* y,
     }
     const float rstd = row_rstd(total, n, eps);
 
+    const u32x4* wl = w;
+    if constexpr (W_WHEN != kWithRow) {
+      // ties the pointer to the result of the reduction, so the loads cannot move above it
+      asm volatile("" : "+s"(wl) : "v"(rstd));
+    }
+    if constexpr (W_WHEN == kAfterReduce) {
+#pragma unroll
+      for (int c = 0; c < CHUNKS - 1; ++c) wv[c] = wl[c * G + t];
+      wv[CHUNKS - 1] = zero;
+      if (last_ok) wv[CHUNKS - 1] = wl[last];
+    }
+
 #pragma unroll
     for (int c = 0; c < CHUNKS - 1; ++c) {
       const int idx = c * G + t;
-      const u32x4 wc = W_EARLY ? wv[W_EARLY ? c : 0] : w[idx];
-      store_vec<NT>(yr + idx, scale_vec<DT>(v[c], wc, rstd));
+      const u32x4 wc = W_WHEN == kOneByOne ? wl[idx] : wv[W_WHEN == kOneByOne ? 0 : c];
+      store_row_vec<NT>(yr, idx, scale_vec<DT>(v[c], wc, rstd));
     }
     if (last_ok) {
-      const u32x4 wc = W_EARLY ? wv[W_EARLY ? CHUNKS - 1 : 0] : w[last];
-      store_vec<NT>(yr + last, scale_vec<DT>(v[CHUNKS - 1], wc, rstd));
+      const u32x4 wc = W_WHEN == kOneByOne ? wl[last] : wv[W_WHEN == kOneByOne ? 0 : CHUNKS - 1];
+      store_row_vec<NT>(yr, last, scale_vec<DT>(v[CHUNKS - 1], wc, rstd));
     }
   }
 }

@@ -135,7 +135,7 @@ def test_tuned_entry_argument_checks():
 def test_automatic_threads_per_row():
     auto = binding.rmsnorm_auto_threads_per_row
     bf16, fp16, fp32 = binding.RMSNORM_DTYPE_BF16, binding.RMSNORM_DTYPE_FP16, binding.RMSNORM_DTYPE_FP32
-    assert auto(8192, bf16) == 256          # headline shape: 4 chunks per thread
+    assert auto(8192, bf16) == 512          # headline shape: 2 chunks per thread
     assert auto(4096, bf16) == 256
     assert auto(2048, bf16) == 64
     assert auto(512, bf16) == 64
@@ -148,9 +148,11 @@ def test_automatic_threads_per_row():
     assert auto(1024, fp32) == 64
     assert auto(768, fp16) == 64
     assert auto(5120, fp16) == 256
-    assert auto(13824, fp16) == 256
-    assert auto(8192, fp32) == 256
-    assert auto(32768, bf16) == 512
+    assert auto(5632, fp16) == 256 and auto(5640, fp16) == 512
+    assert auto(13824, fp16) == 512
+    assert auto(8192, fp32) == 512
+    assert auto(20480, bf16) == 512 and auto(20488, bf16) == 1024
+    assert auto(32768, bf16) == 1024
     assert auto(65536, fp16) == 1024
     assert auto(131072, bf16) == 1024
     assert auto(131080, bf16) == 0          # too long for registers

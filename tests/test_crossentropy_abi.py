@@ -48,7 +48,7 @@ def test_empty_batch_and_bad_thread_counts():
     lib = ce.load()
     assert lib.crossentropy_fwd(None, None, None, None, 0, 16, 2, None) == ce.CROSSENTROPY_OK
     assert lib.crossentropy_fwd_tuned(None, None, None, None, 0, 16, 2, None, 64) == ce.CROSSENTROPY_OK
-    for bad in (0, 1, 32, 128, 2048, -64):
+    for bad in (0, 1, 32, 100, 1088, 2048, -64):
         assert lib.crossentropy_fwd_tuned(P, P + BIG, P + 2 * BIG, None, 4, 4096, 2, None, bad) == \
             ce.CROSSENTROPY_ERR_INVALID_ARG
 
@@ -58,9 +58,12 @@ def test_automatic_threads_per_row():
     for dtype in (0, 1, 2):
         for n in (1, 7, 128, 1000):
             assert auto(n, dtype) == 64
-    assert auto(2048, 1) == 64 and auto(2056, 1) == 256 and auto(1024, 0) == 64 and auto(1028, 0) == 256
-    assert auto(32000, 1) == 256 and auto(50257, 2) == 256 and auto(131072, 2) == 256
-    assert auto(131080, 2) == 1024 and auto(65536, 0) == 256 and auto(65540, 0) == 1024
+    # about 8 16-byte vectors per thread for the 16-bit types and 4 for fp32, in whole wavefronts
+    assert auto(2048, 1) == 64 and auto(4096, 2) == 64 and auto(8192, 1) == 128 and auto(12288, 2) == 192
+    assert auto(16384, 1) == 256 and auto(32000, 1) == 512 and auto(50257, 2) == 512
+    assert auto(65536, 1) == 1024 and auto(131072, 2) == 1024 and auto(1 << 30, 1) == 1024
+    assert auto(1024, 0) == 64 and auto(4096, 0) == 256 and auto(8192, 0) == 512
+    assert auto(16000, 0) == 512 and auto(32000, 0) == 1024 and auto(65536, 0) == 1024
     with pytest.raises(ce.CrossEntropyError):
         auto(0, 1)
     with pytest.raises(ce.CrossEntropyError):

@@ -14,7 +14,7 @@ from paper_2603_21331_amd import inputs
 pytestmark = pytest.mark.gpu
 
 DTYPES = [inputs.FP32, inputs.FP16, inputs.BF16]
-MODES = (0, 64, 256, 512, 1024)        # threads per row; 0 = automatic
+MODES = (0, 64, 128, 256, 320, 512, 1024)        # threads per row; 0 = automatic
 GUARD = 16
 SENTINEL = -12345.0
 
@@ -74,7 +74,7 @@ SWEEP = [("tiny", 70, 8), ("head_64", 1031, 64), ("ragged_200", 333, 200), ("ctx
          ("ragged_1000", 301, 1000), ("one_wave_limit", 517, 2048), ("past_one_wave", 130, 2056),
          ("standard_4096", 1024, 4096), ("wide_8192", 259, 8192), ("vocab_32000", 67, 32000),
          ("vocab_50257", 33, 50257), ("vocab_65536", 9, 65536), ("vocab_128256", 7, 128256),
-         ("past_256_threads", 5, 131080), ("long_300001", 3, 300001), ("tall", 8192, 1024)]
+         ("batch_remainder_3", 6, 28672 + 8), ("past_256_threads", 5, 131080), ("long_300001", 3, 300001), ("tall", 8192, 1024)]
 
 
 @pytest.mark.parametrize("dtype", DTYPES)
@@ -235,4 +235,4 @@ def test_empty_batch_and_binding_checks(gpu_device):
     with pytest.raises(TypeError):
         ce.crossentropy_fwd(x.double(), t)
     with pytest.raises(ce.CrossEntropyError):
-        ce.crossentropy_fwd_tuned(x, t, 128)
+        ce.crossentropy_fwd_tuned(x, t, 96)
