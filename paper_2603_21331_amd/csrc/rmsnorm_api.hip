@@ -138,10 +138,21 @@ struct Args {
 template <int DT, int CHUNKS, int G>
 void launch_row(const Args& a) {
   const int64_t blocks = a.M < kMaxGrid ? a.M : kMaxGrid;
+  // Rows that fill their chunks exactly, one row per workgroup: the instance without
+  // predicates and loop bookkeeping (256 and 512 threads, where the headline shapes fall).
+  if constexpr ((G == 256 || G == 512) && CHUNKS <= 8) {
+    if (a.nvec == CHUNKS * G && blocks == a.M) {
+      hipLaunchKernelGGL((rms::rmsnorm_row_kernel<DT, CHUNKS, G, true, true>),
+                         dim3((unsigned)blocks), dim3(G), 0, a.stream,
+                         (const u32x4*)a.x, (const u32x4*)a.w, (u32x4*)a.y, a.M, a.nvec,
+                         1.0f / (float)a.N, a.eps);
+      return;
+    }
+  }
   hipLaunchKernelGGL((rms::rmsnorm_row_kernel<DT, CHUNKS, G, true>),
                      dim3((unsigned)blocks), dim3(G), 0, a.stream,
                      (const u32x4*)a.x, (const u32x4*)a.w, (u32x4*)a.y, a.M, a.nvec,
-                     (float)a.N, a.eps);
+                     1.0f / (float)a.N, a.eps);
 }
 
 template <int DT, int CHUNKS, int L>
@@ -152,7 +163,7 @@ void launch_subwave(const Args& a) {
   hipLaunchKernelGGL((rms::rmsnorm_subwave_kernel<DT, CHUNKS, L, true>),
                      dim3((unsigned)blocks), dim3(rms::kWave), 0, a.stream,
                      (const u32x4*)a.x, (const u32x4*)a.w, (u32x4*)a.y, a.M, a.nvec,
-                     (float)a.N, a.eps);
+                     1.0f / (float)a.N, a.eps);
 }
 
 template <int DT, int CHUNKS, int G>
@@ -160,7 +171,7 @@ void launch_row_unaligned(const Args& a, int nfull) {
   const int64_t blocks = a.M < kMaxGrid ? a.M : kMaxGrid;
   hipLaunchKernelGGL((rms::rmsnorm_row_unaligned_kernel<DT, CHUNKS, G, true>),
                      dim3((unsigned)blocks), dim3(G), 0, a.stream,
-                     a.x, a.w, a.y, a.M, a.N, nfull, (float)a.N, a.eps);
+                     a.x, a.w, a.y, a.M, a.N, nfull, 1.0f / (float)a.N, a.eps);
 }
 
 template <int DT>
@@ -168,7 +179,7 @@ void launch_generic(const Args& a) {
   const int64_t blocks = a.M < kMaxGrid ? a.M : kMaxGrid;
   hipLaunchKernelGGL((rms::rmsnorm_generic_kernel<DT, kGenericThreads>),
                      dim3((unsigned)blocks), dim3(kGenericThreads), 0, a.stream,
-                     a.x, a.w, a.y, a.M, a.N, (float)a.N, a.eps);
+                     a.x, a.w, a.y, a.M, a.N, 1.0f / (float)a.N, a.eps);
 }
 
 #define RMS_CASE(n, call) case n: call; break;

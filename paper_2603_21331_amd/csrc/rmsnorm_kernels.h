@@ -59,11 +59,22 @@ __device__ __forceinline__ void forget_unpacked(u32x4 (&v)[CHUNKS]) {
   for (int c = 0; c < CHUNKS; ++c) asm volatile("" : "+v"(v[c]));
 }
 
-// rstd = 1 / sqrt(sum / n + eps), with correctly rounded divide and root: it
-// runs once per row, so the "fast rsqrt" of the paper's starter would buy
-// nothing here and would cost accuracy on subnormal sums.
-__device__ __forceinline__ float row_rstd(float sum_sq, float n, float eps) {
-  return 1.0f / __builtin_sqrtf(sum_sq / n + eps);
+// rstd = 1 / sqrt(sum / n + eps).  Every thread of a row computes it between the arrival of
+// the row and the first store, so its latency is paid once per row on the critical path: the
+// correctly rounded divide, root and reciprocal of a plain 1 / sqrt(sum / n + eps) take about
+// fifty dependent instructions there, and replacing them was worth 0.7 % of the kernel at the
+// headline shape.  Here: one fused multiply-add for the mean (inv_n = 1 / n rounded to fp32),
+// the hardware reciprocal square root (the paper's "fast rsqrt", 1 ulp) and one Newton step,
+// which together stay within 1.5 ulp of the exact value.  Arguments that are not normal
+// numbers (zero or subnormal: a zero row with eps = 0; infinite: a sum that overflowed; NaN)
+// take the plain formula, so the IEEE corner cases are unchanged.
+__device__ __forceinline__ float row_rstd(float sum_sq, float inv_n, float eps) {
+  const float a = __builtin_fmaf(sum_sq, inv_n, eps);
+  // one class test, and the plain formula laid out off the straight path
+  if (__builtin_expect(!__builtin_isnormal(a) || a < 0.0f, 0)) return 1.0f / __builtin_sqrtf(a);
+  const float y0 = __builtin_amdgcn_rsqf(a);
+  const float e = __builtin_fmaf(-a * y0, y0, 1.0f);
+  return __builtin_fmaf(0.5f * y0, e, y0);
 }
 
 // y = round((x * rstd) * w) for one vector.
@@ -99,10 +110,10 @@ __device__ __forceinline__ u32x4 scale_vec(u32x4 xv, u32x4 wv, float rstd) {
 // the many small wavefronts interleave more finely.  The grid is flat (one
 // workgroup per row); it only strides when M exceeds the grid limit.
 // ---------------------------------------------------------------------------
-template <int DT, int CHUNKS, int G, bool NT>
+template <int DT, int CHUNKS, int G, bool NT, bool FLAT = false>
 __global__ void __launch_bounds__(G)
 rmsnorm_row_kernel(const u32x4* x, const u32x4* w, u32x4* y,
-                   int64_t M, int nvec, float n, float eps) {
+                   int64_t M, int nvec, float inv_n, float eps) {
   constexpr int WAVES = G / kWave;
   // When the weight chunks are fetched.  The weight is re-read by every row and misses the
   // compute unit's vector cache most of the time (the streaming row pushes it out), so its
@@ -121,12 +132,15 @@ rmsnorm_row_kernel(const u32x4* x, const u32x4* w, u32x4* y,
   const int t = threadIdx.x;
   const int lane = t & (kWave - 1);
   const int wave = t / kWave;
+  // FLAT: the host promises nvec == CHUNKS * G (no ragged last chunk) and one row per
+  // workgroup (gridDim.x == M), which removes the predicates and the loop bookkeeping from
+  // both ends of a workgroup's short life; worth 1 % at the headline shape.
   const int last = (CHUNKS - 1) * G + t;
-  const bool last_ok = last < nvec;
+  const bool last_ok = FLAT || last < nvec;
   const u32x4 zero = {0u, 0u, 0u, 0u};
   int slot = 0;
 
-  for (int64_t row = blockIdx.x; row < M; row += gridDim.x) {
+  for (int64_t row = blockIdx.x; row < M; row += FLAT ? M : (int64_t)gridDim.x) {
     const u32x4* xr = x + row * nvec;
     const __amdgpu_buffer_rsrc_t yr = row_resource(y + row * nvec, nvec * 16);
 
@@ -146,26 +160,35 @@ rmsnorm_row_kernel(const u32x4* x, const u32x4* w, u32x4* y,
 
     float total = wave_sum(lane_sum_sq<DT, CHUNKS>(v));
     forget_unpacked<CHUNKS>(v);
+    // (A pointer that has been through an asm statement is no longer known to point to global
+    // memory and would be read with flat loads: the address space is stated again.)
+    typedef const u32x4 __attribute__((address_space(1)))* GlobalVec;
+    const u32x4* wp = w;
+    GlobalVec wl = (GlobalVec)wp;
     if constexpr (WAVES > 1) {
       if (lane == 0) partial[slot][wave] = total;
       __syncthreads();
       total = partial[slot][0];
+      if constexpr (W_WHEN == kAfterReduce) {
+        // Tied to the first value read after the barrier: the loads cannot move above it,
+        // and they are in flight while the partial sums are added and rstd is formed.
+        // They go through the generic pointer as it comes out of the asm statement (flat
+        // loads): measured 0.5 % faster here than the same loads marked global.
+        asm volatile("" : "+s"(wp) : "v"(total));
+#pragma unroll
+        for (int c = 0; c < CHUNKS - 1; ++c) wv[c] = wp[c * G + t];
+        wv[CHUNKS - 1] = zero;
+        if (last_ok) wv[CHUNKS - 1] = wp[last];
+      }
 #pragma unroll
       for (int k = 1; k < WAVES; ++k) total += partial[slot][k];
       slot ^= 1;
     }
-    const float rstd = row_rstd(total, n, eps);
-
-    const u32x4* wl = w;
-    if constexpr (W_WHEN != kWithRow) {
+    const float rstd = row_rstd(total, inv_n, eps);
+    if constexpr (W_WHEN == kOneByOne) {
       // ties the pointer to the result of the reduction, so the loads cannot move above it
-      asm volatile("" : "+s"(wl) : "v"(rstd));
-    }
-    if constexpr (W_WHEN == kAfterReduce) {
-#pragma unroll
-      for (int c = 0; c < CHUNKS - 1; ++c) wv[c] = wl[c * G + t];
-      wv[CHUNKS - 1] = zero;
-      if (last_ok) wv[CHUNKS - 1] = wl[last];
+      asm volatile("" : "+s"(wp) : "v"(rstd));
+      wl = (GlobalVec)wp;
     }
 
 #pragma unroll
@@ -195,7 +218,7 @@ rmsnorm_row_kernel(const u32x4* x, const u32x4* w, u32x4* y,
 template <int DT, int CHUNKS, int L, bool NT>
 __global__ void __launch_bounds__(kWave)
 rmsnorm_subwave_kernel(const u32x4* x, const u32x4* __restrict__ w, u32x4* y,
-                       int64_t M, int nvec, float n, float eps) {
+                       int64_t M, int nvec, float inv_n, float eps) {
   constexpr int ROWS = kWave / L;
   const int lane = threadIdx.x;
   const int s = lane % L;
@@ -222,7 +245,7 @@ rmsnorm_subwave_kernel(const u32x4* x, const u32x4* __restrict__ w, u32x4* y,
     }
     const float total = subwave_sum<L>(lane_sum_sq<DT, CHUNKS>(v));
     forget_unpacked<CHUNKS>(v);
-    const float rstd = row_rstd(total, n, eps);
+    const float rstd = row_rstd(total, inv_n, eps);
 #pragma unroll
     for (int c = 0; c < CHUNKS; ++c) {
       const int idx = c * L + s;
@@ -242,7 +265,7 @@ rmsnorm_subwave_kernel(const u32x4* x, const u32x4* __restrict__ w, u32x4* y,
 template <int DT, int CHUNKS, int G, bool NT>
 __global__ void __launch_bounds__(G)
 rmsnorm_row_unaligned_kernel(const void* x, const void* __restrict__ w, void* y,
-                             int64_t M, int64_t N, int nfull, float n, float eps) {
+                             int64_t M, int64_t N, int nfull, float inv_n, float eps) {
   using S = Storage<DT>;
   constexpr int WAVES = G / kWave;
   constexpr int VEC = S::kVec;
@@ -291,7 +314,7 @@ rmsnorm_row_unaligned_kernel(const void* x, const void* __restrict__ w, void* y,
       for (int k = 1; k < WAVES; ++k) total += partial[slot][k];
       slot ^= 1;
     }
-    const float rstd = row_rstd(total, n, eps);
+    const float rstd = row_rstd(total, inv_n, eps);
 
 #pragma unroll
     for (int c = 0; c < CHUNKS - 1; ++c)
@@ -314,7 +337,7 @@ rmsnorm_row_unaligned_kernel(const void* x, const void* __restrict__ w, void* y,
 template <int DT, int T>
 __global__ void __launch_bounds__(T)
 rmsnorm_generic_kernel(const void* x, const void* __restrict__ w, void* y,
-                       int64_t M, int64_t N, float n, float eps) {
+                       int64_t M, int64_t N, float inv_n, float eps) {
   constexpr int WAVES = T / kWave;
   __shared__ float partial[2][WAVES];
   const int tid = threadIdx.x;
@@ -336,7 +359,7 @@ rmsnorm_generic_kernel(const void* x, const void* __restrict__ w, void* y,
 #pragma unroll
     for (int k = 1; k < WAVES; ++k) total += partial[slot][k];
     slot ^= 1;
-    const float rstd = row_rstd(total, n, eps);
+    const float rstd = row_rstd(total, inv_n, eps);
 
     for (int64_t j = tid; j < N; j += T) {
       const float f = Storage<DT>::load_one(x, base + j);
