@@ -18,7 +18,10 @@ _LAYERNORM_SRC = os.path.join(_HERE, "layernorm_oracle.cpp")
 _LAYERNORM_LIB = os.path.join(_HERE, "liblayernorm_oracle.so")
 _CE_SRC = os.path.join(_HERE, "crossentropy_oracle.cpp")
 _CE_LIB = os.path.join(_HERE, "libcrossentropy_oracle.so")
+_ROWSUM_SRC = os.path.join(_HERE, "rowsum_oracle.cpp")
+_ROWSUM_LIB = os.path.join(_HERE, "librowsum_oracle.so")
 _lib = None
+_rowsum_lib = None
 _softmax_lib = None
 _layernorm_lib = None
 _ce_lib = None
@@ -37,6 +40,7 @@ def build(force: bool = True) -> str:
     _compile(_SOFTMAX_SRC, _SOFTMAX_LIB, force)
     _compile(_LAYERNORM_SRC, _LAYERNORM_LIB, force)
     _compile(_CE_SRC, _CE_LIB, force)
+    _compile(_ROWSUM_SRC, _ROWSUM_LIB, force)
     return _compile(_SRC, _LIB, force)
 
 
@@ -229,3 +233,34 @@ def crossentropy_oracle(x, target, dtype: int, nthreads: int = 0, with_lse: bool
     if rc != 0:
         raise ValueError(f"crossentropy_oracle rejected its arguments (rc={rc})")
     return (loss, lse) if with_lse else loss
+
+
+# ------------------------------------------------------------------ row sum
+
+def _load_rowsum():
+    global _rowsum_lib
+    if _rowsum_lib is None:
+        # ROWSUM_ORACLE_LIB: the mutation test's hook, as for the other oracles.
+        lib = ctypes.CDLL(os.environ.get("ROWSUM_ORACLE_LIB") or _compile(_ROWSUM_SRC, _ROWSUM_LIB, False))
+        vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
+        lib.rowsum_oracle.argtypes = [vp, vp, vp, i64, i64, i32, i32]
+        lib.rowsum_oracle.restype = i32
+        _rowsum_lib = lib
+    return _rowsum_lib
+
+
+def rowsum_oracle(x, dtype: int, nthreads: int = 0, with_abs: bool = False):
+    """Sum over the last dimension of an (M, N) x in storage form: float32, M entries.
+
+    Returns y, or (y, abs_sum) with the fp64 sums of absolute values when with_abs is true."""
+    x = _as_storage(x, dtype)
+    if x.ndim != 2:
+        raise ValueError(f"x must be 2-D, got shape {x.shape}")
+    M, N = x.shape
+    y = np.empty(M, dtype=np.float32)
+    a = np.empty(M, dtype=np.float64) if with_abs else None
+    rc = _load_rowsum().rowsum_oracle(x.ctypes.data, y.ctypes.data,
+                                      None if a is None else a.ctypes.data, M, N, dtype, nthreads)
+    if rc != 0:
+        raise ValueError(f"rowsum_oracle rejected its arguments (rc={rc})")
+    return (y, a) if with_abs else y

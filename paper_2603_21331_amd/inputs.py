@@ -287,3 +287,26 @@ def crossentropy_bytes(M: int, N: int, dtype: int) -> int:
     """Read the logits once (the model behind the paper's GB/s column for cross_ent; the M
     targets and M losses, 12 bytes per row, are left out as the paper leaves them out)."""
     return M * N * DTYPE_BYTES[dtype]
+
+
+# ----------------------------------------------------------------------------
+# Row-sum workloads (the paper's table lists 8192 x 8192 and 16384 x 4096, FP16, for "reduce")
+# ----------------------------------------------------------------------------
+
+def rowsum_case(seed: int, stream: int, M: int, N: int, dtype: int, mean: float = 0.0,
+                std: float = 1.0):
+    """x ~ N(mean, std) at any shape."""
+    return dict(name=f"rowsum_{DTYPE_NAMES[dtype]}_{M}x{N}", dtype=dtype, M=M, N=N,
+                x=normal_matrix(seed, stream, M, N, dtype, mean, std))
+
+
+def rowsum_paper_shape(which: int, seed: int = 0):
+    """FP16 8192 x 8192 (which = 0) or 16384 x 4096 (which = 1): the paper's two reduce rows."""
+    M, N = ((8192, 8192), (16384, 4096))[which]
+    return rowsum_case(seed, 144 + 4 * which, M, N, FP16)
+
+
+def rowsum_bytes(M: int, N: int, dtype: int) -> int:
+    """Read x once (the model behind the paper's GB/s column for reduce; the M results, 4
+    bytes per row, are left out: they change the figure by less than 0.1 %)."""
+    return M * N * DTYPE_BYTES[dtype]

@@ -197,3 +197,40 @@ def check_crossentropy_parity(got, want, what: str = "", exact_zero=None) -> dic
                                    f"> {bound[worst]:.3e}")
     return {"max_abs_err": float(diff.max()),
             "max_rel_err": float((diff / np.maximum(np.abs(o[ok]), 1.0)).max())}
+
+
+# ---- row sum ---------------------------------------------------------------------------------
+# An fp32 sum has no relative accuracy of its own: when the terms cancel, the result is small
+# and the rounding errors are not.  Each addition rounds by at most 2^-24 of the partial sum it
+# forms, which is at most the sum of magnitudes A = sum_j |x_j| of the row, and an element
+# passes through at most D additions on its way to the result, so |g - exact| <= D * 2^-24 * A
+# whatever the order.  The kernel's D: a thread's chain (at most N / 256 terms: 64 threads, 4
+# lanes of an fp32 vector, is the coarsest split it ever uses), the fold of the chains, six
+# levels across the wavefront and up to 16 wavefront partials in turn, together below
+# N / 256 + 32.  The relative term covers the oracle's own rounding of its result to fp32.
+ROWSUM_DEPTH_BASE = 32
+ROWSUM_TERMS_PER_CHAIN = 256
+
+
+def check_rowsum_parity(got, want, abs_sum, N: int, what: str = "") -> dict:
+    """got: fp32 sums from the GPU; want: the oracle's fp32 sums; abs_sum: the oracle's fp64
+    sums of magnitudes; N: row length."""
+    g = np.asarray(got).astype(np.float64)
+    o = np.asarray(want).astype(np.float64)
+    a = np.asarray(abs_sum, dtype=np.float64)
+    assert g.shape == o.shape == a.shape, f"{what}: shapes {g.shape} {o.shape} {a.shape}"
+    assert np.array_equal(np.isnan(g), np.isnan(o)), f"{what}: NaN positions differ"
+    inf = np.isinf(o)
+    assert np.array_equal(g[inf], o[inf]) and not np.isinf(g[~inf & ~np.isnan(o)]).any(), \
+        f"{what}: infinities differ"
+    ok = np.isfinite(o)
+    if not ok.any():
+        return {"max_err_over_abs_sum": 0.0, "max_abs_err": 0.0}
+    depth = ROWSUM_DEPTH_BASE + N / ROWSUM_TERMS_PER_CHAIN
+    diff = np.abs(g[ok] - o[ok])
+    bound = TOL_FP32_REL * np.abs(o[ok]) + depth * 2.0 ** -24 * a[ok]
+    worst = int(np.argmax(diff - bound))
+    assert np.all(diff <= bound), (f"{what}: |{g[ok][worst]!r} - {o[ok][worst]!r}| = {diff[worst]:.3e} "
+                                   f"> {bound[worst]:.3e}")
+    return {"max_err_over_abs_sum": float((diff / np.maximum(a[ok], FLT_MIN)).max()),
+            "max_abs_err": float(diff.max())}

@@ -118,6 +118,29 @@ CE_MUTANTS = {
 }
 
 
+ROWSUM_SRC = os.path.join(ROOT, "oracle", "rowsum_oracle.cpp")
+ROWSUM_PINS = os.path.join(ROOT, "tests", "test_rowsum_oracle_pins.py")
+
+ROWSUM_MUTANTS = {
+    "first_term_missing": ("    for (int64_t j = 0; j < N; ++j) {\n      const double v", "    for (int64_t j = (N > 1 ? 1 : 0); j < N; ++j) {\n      const double v"),
+    "last_term_missing": ("    for (int64_t j = 0; j < N; ++j) {\n      const double v", "    for (int64_t j = 0; j + 1 < N || j == 0; ++j) {\n      const double v"),
+    "mean_instead_of_sum": ("y[i] = static_cast<float>(total);", "y[i] = static_cast<float>(total / (double)N);"),
+    "fp32_running_total": ("double total = 0.0, total_abs = 0.0;", "float total = 0.0f; double total_abs = 0.0;"),
+    "sum_of_magnitudes_as_result": ("      total += v;\n", "      total += std::fabs(v);\n"),
+    "signed_sum_as_magnitudes": ("total_abs += std::fabs(v);", "total_abs += v;"),
+    "column_major_read": ("const double v = element(x, i * N + j, dtype);", "const double v = element(x, (i + j * (end - first)) % ((end - first) * N) + first * N, dtype);"),
+    "next_rows_element": ("const double v = element(x, i * N + j, dtype);", "const double v = element(x, i * N + (j + 1 < N ? j + 1 : j), dtype);"),
+    "result_rounded_to_bf16_width": ("y[i] = static_cast<float>(total);", "y[i] = static_cast<float>(std::ldexp(std::nearbyint(std::ldexp(total, 7 - std::ilogb(total == 0 ? 1.0 : total))), std::ilogb(total == 0 ? 1.0 : total) - 7));"),
+    "result_truncated": ("y[i] = static_cast<float>(total);", "{ float r = static_cast<float>(total); if (std::fabs((double)r) > std::fabs(total)) r = std::nextafterf(r, 0.0f); y[i] = r; }"),
+    "half_decoded_with_wrong_bias": ("magnitude = std::ldexp(static_cast<double>(1024 + fraction), exponent - 25);", "magnitude = std::ldexp(static_cast<double>(1024 + fraction), exponent - 24);"),
+    "half_subnormals_flushed": ("else if (exponent == 0) magnitude = std::ldexp(static_cast<double>(fraction), -24);", "else if (exponent == 0) magnitude = 0.0;"),
+    "half_hidden_bit_missing": ("static_cast<double>(1024 + fraction), exponent - 25", "static_cast<double>(fraction), exponent - 25"),
+    "bf16_shift": ("static_cast<uint32_t>(bits) << 16;", "static_cast<uint32_t>(bits) << 15;"),
+    "sign_lost": ("return negative ? -magnitude : magnitude;", "return magnitude;"),
+    "half_nan_read_as_infinity": ("magnitude = fraction != 0 ? std::nan(\"\") : INFINITY;", "magnitude = INFINITY;"),
+}
+
+
 def _build(source_text: str, out_dir, name: str) -> str:
     cpp = os.path.join(out_dir, f"{name}.cpp")
     so = os.path.join(out_dir, f"{name}.so")
@@ -192,4 +215,19 @@ def test_planted_crossentropy_mistake_is_caught(tmp_path, name):
     assert text.count(old) >= 1, f"mutation site for {name} not found; update the test"
     so = _build(text.replace(old, new), str(tmp_path), name)
     assert _run_pins(so, "CROSSENTROPY_ORACLE_LIB", CE_PINS) != 0, \
+        f"no pin noticed the planted mistake '{name}'"
+
+
+def test_unmodified_rowsum_oracle_passes_its_pins_through_the_same_route(tmp_path):
+    so = _build(open(ROWSUM_SRC).read(), str(tmp_path), "pristine_rowsum")
+    assert _run_pins(so, "ROWSUM_ORACLE_LIB", ROWSUM_PINS) == 0
+
+
+@pytest.mark.parametrize("name", sorted(ROWSUM_MUTANTS))
+def test_planted_rowsum_mistake_is_caught(tmp_path, name):
+    old, new = ROWSUM_MUTANTS[name]
+    text = open(ROWSUM_SRC).read()
+    assert text.count(old) >= 1, f"mutation site for {name} not found; update the test"
+    so = _build(text.replace(old, new), str(tmp_path), name)
+    assert _run_pins(so, "ROWSUM_ORACLE_LIB", ROWSUM_PINS) != 0, \
         f"no pin noticed the planted mistake '{name}'"
