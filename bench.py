@@ -137,11 +137,14 @@ def main() -> int:
     ap.add_argument("--all-configs", action="store_true",
                     help="after the headline measurement, also time the other four workloads "
                          "(GPU and oracle) and add them to the JSON line under other_configs")
-    ap.add_argument("--op", choices=["rmsnorm", "softmax", "layernorm", "crossentropy"],
+    ap.add_argument("--op", choices=["rmsnorm", "softmax", "layernorm", "crossentropy", "rowsum"],
                     default="rmsnorm",
                     help="rmsnorm (default): the headline benchmark.  softmax / layernorm / "
-                         "crossentropy: the same protocol on the next kernels at the paper's largest "
-                         "shape for each (fp16 8192 x 8192; fp16 8192 x 4096; fp16 8192 x 32000)")
+                         "crossentropy / rowsum: the same protocol on the next kernels at the paper's "
+                         "largest shape for each (fp16 8192 x 8192; fp16 8192 x 4096; fp16 "
+                         "8192 x 32000; fp16 8192 x 8192)")
+    ap.add_argument("--paper-shape", type=int, choices=[0, 1], default=0,
+                    help="with --op rowsum: 0 = fp16 8192 x 8192 (default), 1 = fp16 16384 x 4096")
     ap.add_argument("--profile-only", action="store_true",
                     help="warm-up plus --steps launches and nothing else (for rocprofv3 runs)")
     ap.add_argument("--calib-copy", action="store_true",
@@ -173,6 +176,8 @@ def main() -> int:
         return bench_layernorm(args, dev)
     if args.op == "crossentropy":
         return bench_crossentropy(args, dev)
+    if args.op == "rowsum":
+        return bench_rowsum(args, dev)
 
     M, K, W, S = args.rows, args.steps, args.warmup, max(1, args.buffer_sets)
     t0 = time.time()
@@ -515,6 +520,75 @@ def bench_crossentropy(args, dev) -> int:
         got = losses[0].cpu().numpy()
         result["parity"] = {"checked": "every loss of one output buffer",
                             **compare.check_crossentropy_parity(got, ref, "bench crossentropy")}
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+def bench_rowsum(args, dev) -> int:
+    """Row sum, fp16, 8192 x 8192 (the first reduce row of the paper's performance table:
+    62.2 us, 2156 GB/s on H100; --paper-shape 1 selects its second row, 16384 x 4096), same
+    protocol as the headline benchmark."""
+    import numpy as np
+    import torch
+    from paper_2603_21331_amd import inputs, rowsum
+
+    rowsum.load()
+    K, W = args.steps, args.warmup
+    case = inputs.rowsum_paper_shape(args.paper_shape)
+    M, N = case["M"], case["N"]
+    nbytes = inputs.rowsum_bytes(M, N, inputs.FP16)
+    S = max(args.buffer_sets, 8)               # 8 x 128 MiB: well past the Infinity Cache
+    x0 = torch.from_numpy(case["x"].view(np.int16)).to(dev).view(torch.float16)
+    xs = [x0] + [x0.clone() for _ in range(S - 1)]
+    ys = [torch.empty(M, dtype=torch.float32, device=dev) for _ in range(S)]
+    fns = [rowsum.bind_rowsum_fwd(xs[i], ys[i], threads_per_row=args.threads_per_row)
+           for i in range(S)]
+    settle(fns, args.settle_ms)
+    for i in range(W):
+        fns[i % S]()
+    torch.cuda.synchronize()
+    if args.profile_only:
+        for i in range(K):
+            fns[i % S]()
+        torch.cuda.synchronize()
+        log("profile-only run done")
+        return 0
+    ms_per_step = timed_region(fns, K)
+    value = nbytes / (ms_per_step * 1e-3) / 1e9
+    durs = per_launch_us(fns, K)
+    result = {
+        "metric": f"Row-sum reduce achieved HBM GB/s and % of MI355X peak (fp16, {M}x{N})",
+        "value": round(value, 1), "unit": "GB/s",
+        "pct_of_peak": round(100.0 * value / PEAK_HBM_GBPS, 2),
+        "rows_per_s": round(M / (ms_per_step * 1e-3), 1),
+        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(ms_per_step, 6),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"rowsum_fwd fp16 M={M} N={N}, fp32 sum per row",
+                   "storage_dtype": "fp16",
+                   "threads_per_row": args.threads_per_row
+                   or rowsum.rowsum_auto_threads_per_row(N, inputs.FP16),
+                   "buffer_sets": S, "bytes_per_step": nbytes},
+        "roofline": roofline_object(nbytes, ms_per_step, durs),
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        sys.path.insert(0, os.path.join(ROOT, "tests"))
+        import compare
+        cores = oracle.hardware_threads()
+        best, ref = None, None
+        for _ in range(3):
+            t = time.perf_counter()
+            ref = oracle.rowsum_oracle(case["x"], inputs.FP16, nthreads=cores, with_abs=True)
+            dt = time.perf_counter() - t
+            best = dt if best is None else min(best, dt)
+        result["cpu_baseline"] = {"value": round(nbytes / best / 1e9, 3), "unit": "GB/s",
+                                  "cores": cores, "kind": "oracle",
+                                  "sample": f"the whole workload ({M} x {N}), best of 3 runs, "
+                                            f"{best:.3f} s each"}
+        got = ys[0].cpu().numpy()
+        result["parity"] = {"checked": "every sum of one output buffer",
+                            **compare.check_rowsum_parity(got, ref[0], ref[1], N, "bench rowsum")}
     print(json.dumps(result), flush=True)
     return 0
 

@@ -18,6 +18,9 @@ LAYERNORM_HEADERS = ["layernorm_kernels.h", "vec_io.h", "wave_reduce.h"]
 CROSSENTROPY_LIB_PATH = os.path.join(_HERE, "libcrossentropy_hip.so")
 CROSSENTROPY_SOURCES = ["crossentropy_api.hip"]
 CROSSENTROPY_HEADERS = ["crossentropy_kernels.h", "vec_io.h", "wave_reduce.h"]
+ROWSUM_LIB_PATH = os.path.join(_HERE, "librowsum_hip.so")
+ROWSUM_SOURCES = ["rowsum_api.hip"]
+ROWSUM_HEADERS = ["rowsum_kernels.h", "vec_io.h", "wave_reduce.h"]
 SOFTMAX_SOURCES = ["softmax_api.hip"]
 SOFTMAX_HEADERS = ["softmax_kernels.h", "vec_io.h", "wave_reduce.h"]
 
@@ -51,8 +54,10 @@ def _compile(sources, lib_path: str, verbose: bool) -> str:
 
 
 def build(verbose: bool = False) -> str:
-    """Compiles csrc/ into librmsnorm_hip.so, libsoftmax_hip.so, liblayernorm_hip.so and
-    libcrossentropy_hip.so next to this file; returns the path of the RMSNorm library."""
+    """Compiles csrc/ into librmsnorm_hip.so, libsoftmax_hip.so, liblayernorm_hip.so,
+    libcrossentropy_hip.so and librowsum_hip.so next to this file; returns the path of the
+    RMSNorm library."""
+    _compile(ROWSUM_SOURCES, ROWSUM_LIB_PATH, verbose)
     _compile(SOFTMAX_SOURCES, SOFTMAX_LIB_PATH, verbose)
     _compile(LAYERNORM_SOURCES, LAYERNORM_LIB_PATH, verbose)
     _compile(CROSSENTROPY_SOURCES, CROSSENTROPY_LIB_PATH, verbose)
@@ -76,10 +81,12 @@ def is_stale() -> bool:
     return any(os.path.getmtime(d) > built for d in deps)
 
 
-
-
 def build_crossentropy(verbose: bool = False) -> str:
     return _compile(CROSSENTROPY_SOURCES, CROSSENTROPY_LIB_PATH, verbose)
+
+
+def build_rowsum(verbose: bool = False) -> str:
+    return _compile(ROWSUM_SOURCES, ROWSUM_LIB_PATH, verbose)
 
 
 if __name__ == "__main__":
