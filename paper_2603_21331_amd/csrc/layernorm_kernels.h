@@ -20,8 +20,10 @@
 //
 // Same variants as the other row kernels: 8/16/32 lanes per row for rows up to
 // 1 KiB, one wavefront per row, one workgroup of 256..1024 threads per row (two
-// LDS reductions, two barriers per row), and an element-wise three-pass
-// fallback.  Fixed reduction order, no atomics: bit-identical from run to run.
+// LDS reductions, two barriers per row) either launched per row or, for rows of
+// at most 24 elements per thread, resident with weight and bias in registers, and
+// an element-wise three-pass fallback.  Fixed reduction order, no atomics:
+// bit-identical from run to run.
 #pragma once
 
 #include "vec_io.h"
@@ -33,6 +35,18 @@ constexpr int kLnWave = 64;
 
 __device__ __forceinline__ float ln_rstd(float spread, float n, float eps) {
   return 1.0f / __builtin_sqrtf(spread / n + eps);
+}
+
+// The same value through the hardware reciprocal square root and one Newton step (within
+// 1.5 ulp of the exact value); arguments that are not normal numbers (zero or subnormal: a
+// constant row with eps = 0; infinite; NaN) take the plain formula.  It sits on every
+// thread's path between the arrival of the row and the first store.
+__device__ __forceinline__ float ln_rstd_fast(float spread, float inv_n, float eps) {
+  const float a = __builtin_fmaf(spread, inv_n, eps);
+  if (__builtin_expect(!__builtin_isnormal(a) || a < 0.0f, 0)) return 1.0f / __builtin_sqrtf(a);
+  const float y0 = __builtin_amdgcn_rsqf(a);
+  const float e = __builtin_fmaf(-a * y0, y0, 1.0f);
+  return __builtin_fmaf(0.5f * y0, e, y0);
 }
 
 // y chunk = round(c * rstd * w + b); b_ptr may be null (no bias).
@@ -154,6 +168,158 @@ layernorm_row_kernel(const u32x4* x, const u32x4* __restrict__ w, const u32x4* _
         store_vec<NT>(yr + idx, ln_scale<DT>(f[c], wv, bv, has_bias, rstd));
       }
     }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Resident workgroups.  Measured on MI355X, a one-row-per-workgroup LayerNorm spends 12 % of
+// its time at N = 8192 re-reading weight and bias from L2 for every row (with the row itself
+// that is three streams through the compute unit's vector cache and the L2 crossbar instead
+// of one), and a fifth of its vector-ALU work widening them.  Here a grid of a few workgroups
+// per compute unit stays for the whole launch: each workgroup widens its slices of weight
+// and bias to fp32 ONCE, keeps them in registers, and walks rows blockIdx.x,
+// blockIdx.x + gridDim.x, ...  Two packed register copies of a row take turns: while one is
+// reduced, scaled and stored, the other is being filled with the workgroup's next row (the
+// last step requests its own row again, a cache hit, so that no load hides in a branch, and
+// the loop is unrolled twice so that no register is copied from one copy to the other,
+// which would make the loop wait for loads it has only just issued).
+//
+// Same arithmetic as layernorm_row_kernel (shift by the row's first element, mean of the
+// shifted values, squares of the centred values; two reductions, two barriers).  For rows of
+// at most 24 elements per thread (CHUNKS * VEC), which is what fits in registers next to
+// weight and bias; ragged last chunks are allowed.
+// ---------------------------------------------------------------------------
+// First element of a row as raw bits (no arithmetic hangs on the load), and its value.
+template <int DT>
+__device__ __forceinline__ uint32_t ln_first_raw(const u32x4* row) {
+  if constexpr (DT == kFp32) return *reinterpret_cast<const uint32_t*>(row);
+  else return *reinterpret_cast<const uint16_t*>(row);
+}
+template <int DT>
+__device__ __forceinline__ float ln_first_value(uint32_t raw) {
+  if constexpr (DT == kFp32) return as_f32(raw);
+  else if constexpr (DT == kBf16) return as_f32(raw << 16);
+  else return static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(raw)));
+}
+
+// One row: requests row `pre` into (nxt, nxt_raw), then reduces, scales and stores the row
+// held in (cur, cur_raw).
+template <int DT, int CHUNKS, int G, bool NT>
+__device__ __forceinline__ void ln_resident_step(
+    const u32x4* x, u32x4* y, int64_t row, int64_t pre, int nvec, int t, int lane, int wave,
+    bool last_ok, const u32x4 (&cur)[CHUNKS], uint32_t cur_raw, u32x4 (&nxt)[CHUNKS],
+    uint32_t& nxt_raw, const float (&wf)[CHUNKS][Storage<DT>::kVec],
+    const float (&bf)[CHUNKS][Storage<DT>::kVec], float inv_n, float eps,
+    float (&part_a)[G / kLnWave], float (&part_b)[G / kLnWave]) {
+  using S = Storage<DT>;
+  constexpr int VEC = S::kVec;
+  constexpr int WAVES = G / kLnWave;
+  const int last = (CHUNKS - 1) * G + t;
+#pragma unroll
+  for (int c = 0; c < CHUNKS - 1; ++c) nxt[c] = load_vec<NT>(x + pre * nvec + c * G + t);
+  nxt[CHUNKS - 1] = load_vec<NT>(x + pre * nvec + (last_ok ? last : nvec - 1));
+  nxt_raw = ln_first_raw<DT>(x + pre * nvec);
+
+  const float shift = ln_first_value<DT>(cur_raw);
+  float d[CHUNKS][VEC];
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int c = 0; c < CHUNKS; ++c) {
+    S::unpack(cur[c], d[c]);
+    const bool live = c < CHUNKS - 1 || last_ok;
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) {
+      d[c][k] = live ? d[c][k] - shift : 0.f;
+      acc[k & 3] += d[c][k];
+    }
+  }
+  float s1 = wave_sum((acc[0] + acc[1]) + (acc[2] + acc[3]));
+  if constexpr (WAVES > 1) {
+    if (lane == 0) part_a[wave] = s1;
+    __syncthreads();
+    s1 = part_a[0];
+#pragma unroll
+    for (int k = 1; k < WAVES; ++k) s1 += part_a[k];
+  }
+  const float mean_shifted = s1 * inv_n;
+
+  float sq[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int c = 0; c < CHUNKS; ++c) {
+    const bool live = c < CHUNKS - 1 || last_ok;
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) {
+      d[c][k] = live ? d[c][k] - mean_shifted : 0.f;
+      sq[k & 3] = __builtin_fmaf(d[c][k], d[c][k], sq[k & 3]);
+    }
+  }
+  float s2 = wave_sum((sq[0] + sq[1]) + (sq[2] + sq[3]));
+  if constexpr (WAVES > 1) {
+    if (lane == 0) part_b[wave] = s2;
+    __syncthreads();
+    s2 = part_b[0];
+#pragma unroll
+    for (int k = 1; k < WAVES; ++k) s2 += part_b[k];
+  }
+  const float rstd = ln_rstd_fast(s2, inv_n, eps);
+
+  const __amdgpu_buffer_rsrc_t yr = row_resource(y + row * nvec, nvec * 16);
+#pragma unroll
+  for (int c = 0; c < CHUNKS; ++c) {
+    float yf[VEC];
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) yf[k] = (d[c][k] * rstd) * wf[c][k] + bf[c][k];
+    if (c < CHUNKS - 1 || last_ok) store_row_vec<NT>(yr, c * G + t, S::pack(yf));
+  }
+}
+
+template <int DT, int CHUNKS, int G, bool NT>
+__global__ void __launch_bounds__(G)
+layernorm_row_resident_kernel(const u32x4* x, const u32x4* __restrict__ w,
+                              const u32x4* __restrict__ b, u32x4* y, int64_t M, int nvec,
+                              float inv_n, float eps) {
+  using S = Storage<DT>;
+  constexpr int VEC = S::kVec;
+  constexpr int WAVES = G / kLnWave;
+  __shared__ float part_a[2][WAVES];
+  __shared__ float part_b[2][WAVES];
+  const int t = threadIdx.x;
+  const int lane = t & (kLnWave - 1);
+  const int wave = t / kLnWave;
+  const int last = (CHUNKS - 1) * G + t;
+  const bool last_ok = last < nvec;
+  const u32x4 zero = {0u, 0u, 0u, 0u};
+  const int64_t stride = gridDim.x;
+  int64_t row = blockIdx.x;
+  if (row >= M) return;
+
+  u32x4 ra[CHUNKS], rb[CHUNKS];
+  uint32_t raw_a, raw_b = 0;
+#pragma unroll
+  for (int c = 0; c < CHUNKS - 1; ++c) ra[c] = load_vec<NT>(x + row * nvec + c * G + t);
+  ra[CHUNKS - 1] = load_vec<NT>(x + row * nvec + (last_ok ? last : nvec - 1));
+  raw_a = ln_first_raw<DT>(x + row * nvec);
+
+  float wf[CHUNKS][VEC], bf[CHUNKS][VEC];
+#pragma unroll
+  for (int c = 0; c < CHUNKS; ++c) {
+    const int idx = (c < CHUNKS - 1 || last_ok) ? c * G + t : nvec - 1;
+    S::unpack(w[idx], wf[c]);
+    S::unpack(b != nullptr ? b[idx] : zero, bf[c]);
+  }
+  while (true) {
+    int64_t next = row + stride;
+    ln_resident_step<DT, CHUNKS, G, NT>(x, y, row, next < M ? next : row, nvec, t, lane, wave,
+                                        last_ok, ra, raw_a, rb, raw_b, wf, bf, inv_n, eps,
+                                        part_a[0], part_b[0]);
+    if (next >= M) break;                              // uniform over the workgroup
+    row = next;
+    next = row + stride;
+    ln_resident_step<DT, CHUNKS, G, NT>(x, y, row, next < M ? next : row, nvec, t, lane, wave,
+                                        last_ok, rb, raw_b, ra, raw_a, wf, bf, inv_n, eps,
+                                        part_a[1], part_b[1]);
+    if (next >= M) break;
+    row = next;
   }
 }
 

@@ -64,10 +64,15 @@ def test_empty_batch_unknown_variant_and_unsupported_shapes():
 def test_automatic_threads_per_row():
     auto = layernorm.layernorm_auto_threads_per_row
     assert auto(64, 1) == 8 and auto(128, 2) == 16 and auto(256, 1) == 32 and auto(512, 1) == 64
-    assert auto(2048, 2) == 64 and auto(4096, 1) == 256 and auto(8192, 1) == 256
-    assert auto(16384, 2) == 256 and auto(32768, 1) == 512 and auto(65536, 2) == 1024
+    # past one wavefront: the smallest workgroup whose threads hold at most 24 elements of a
+    # 16-bit type (16 of fp32), which runs the resident kernel ...
+    assert auto(2048, 2) == 64 and auto(4096, 1) == 256 and auto(5120, 1) == 256 and auto(6144, 2) == 256
+    assert auto(8192, 1) == 512 and auto(12288, 2) == 512 and auto(16384, 2) == 1024 and auto(24576, 1) == 1024
+    assert auto(4096, 0) == 256 and auto(8192, 0) == 512 and auto(16384, 0) == 1024
+    # ... and beyond that the smallest one that holds the row in at most 8 chunks per thread
+    assert auto(24584, 1) == 512 and auto(32768, 1) == 512 and auto(65536, 2) == 1024
     assert auto(65544, 2) == 0 and auto(1023, 1) == 0
-    assert auto(8192, 0) == 256 and auto(32768, 0) == 1024 and auto(32772, 0) == 0
+    assert auto(16388, 0) == 1024 and auto(32768, 0) == 1024 and auto(32772, 0) == 0
     assert layernorm.layernorm_register_max_n(1) == 65536 and layernorm.layernorm_register_max_n(0) == 32768
     with pytest.raises(layernorm.LayerNormError):
         auto(0, 1)

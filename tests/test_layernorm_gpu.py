@@ -168,6 +168,31 @@ def test_in_place_and_empty(gpu_device, dtype, N):
     assert tuple(layernorm.layernorm_fwd(empty, wd, bd, 1e-5).shape) == (0, N)
 
 
+# The resident kernel (rows of at most 24 elements per thread, 256..1024 threads) walks rows
+# blockIdx.x, blockIdx.x + gridDim.x, ... with two register copies of a row taking turns: row
+# counts below, at and just past one and two rounds of its grid (256 or 512 workgroups on
+# MI355X), odd and even numbers of rounds, full and ragged last chunks, with and without bias,
+# and in place.
+RESIDENT_SHAPES = [(inputs.FP16, 4096, 256), (inputs.FP16, 5120, 256), (inputs.BF16, 8192, 512),
+                   (inputs.BF16, 8200, 512), (inputs.FP16, 16384, 1024), (inputs.FP32, 4096, 256),
+                   (inputs.FP32, 6148, 512), (inputs.FP32, 12288, 1024)]
+
+
+@pytest.mark.parametrize("dtype,N,threads", RESIDENT_SHAPES)
+def test_resident_workgroups(gpu_device, dtype, N, threads):
+    grid = 512 if threads == 256 else 256
+    for k, M in enumerate((1, grid - 1, grid, grid + 1, 2 * grid, 2 * grid + 3, 3 * grid + grid // 2)):
+        case = inputs.layernorm_case(6, 1480 + 4 * dtype, M, N, dtype, mean=-0.2, std=1.3, bias=(k % 3 != 1))
+        check(case, gpu_device, modes=(0, ("threads", threads)))
+    case = inputs.layernorm_case(6, 1496 + 4 * dtype, 2 * grid + 1, N, dtype)
+    want, mean, rstd = oracle.layernorm_oracle(case["x"], case["w"], case["b"], 1e-5, dtype, stats=True)
+    xd, wd, bd = (H.to_device(case[k], dtype, gpu_device) for k in ("x", "w", "b"))
+    H.say(f"layernorm resident in place N={N} threads={threads}")
+    layernorm.layernorm_fwd_tuned(xd, wd, bd, 1e-5, threads, xd)
+    torch.cuda.synchronize()
+    compare.check_layernorm_parity(H.to_host(xd, dtype), want, scale_of(case, mean, rstd), dtype, "resident in place")
+
+
 def test_binding_rejects_mismatched_tensors(gpu_device):
     x = torch.zeros((4, 64), dtype=torch.float16, device=gpu_device)
     w = torch.ones(64, dtype=torch.float16, device=gpu_device)
