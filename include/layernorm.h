@@ -20,8 +20,9 @@
  * library never allocates, copies or synchronises; work is enqueued on `stream`;
  * x and y are M x N row-major with leading dimension N, w and b have N elements,
  * all of one storage type; b may be NULL (no bias); pointers need only element
- * alignment (rows that are not 16-byte aligned, or too long for registers, take
- * a slower element-wise kernel); y == x exactly is allowed, any other overlap is
+ * alignment (rows that are not 16-byte aligned run a register-resident kernel with
+ * element-aligned accesses; only rows too long for registers take a slower
+ * element-wise kernel); y == x exactly is allowed, any other overlap is
  * undefined; a call returns LAYERNORM_OK or a negative layernorm_status and
  * launches nothing on INVALID_ARG / UNSUPPORTED; results are bit-identical from
  * run to run.
@@ -53,7 +54,9 @@ typedef enum {
   LAYERNORM_VARIANT_WAVE = 1,    /* one wavefront per row */
   LAYERNORM_VARIANT_BLOCK = 2,   /* one workgroup of 256..1024 threads per row */
   LAYERNORM_VARIANT_GENERIC = 3, /* element-wise, three passes, any alignment, any N */
-  LAYERNORM_VARIANT_SUBWAVE = 4  /* 8, 16 or 32 lanes per row; 16-byte aligned rows <= 1 KiB */
+  LAYERNORM_VARIANT_SUBWAVE = 4, /* 8, 16 or 32 lanes per row; 16-byte aligned rows <= 1 KiB */
+  LAYERNORM_VARIANT_UNALIGNED = 5 /* the register-resident row kernel with element-aligned
+                                     128-bit accesses: any alignment, N up to the register limit */
 } layernorm_variant;
 
 /*

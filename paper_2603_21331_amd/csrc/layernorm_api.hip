@@ -88,6 +88,15 @@ int pick_threads(int64_t nvec, int min_threads, int dtype) {
   return 0;
 }
 
+// Threads per row for the element-aligned kernel over `nfull` full 16-byte groups; 0 if the
+// row does not fit in registers.
+int pick_threads_unaligned(int64_t nfull) {
+  if (nfull <= kSmallRowVectors) return 64;
+  for (int g = 256; g <= kMaxThreads; g *= 2)
+    if (nfull <= (int64_t)g * kBlockMaxChunks) return g;
+  return 0;
+}
+
 // Compute units of the current device (256 on MI355X), looked up once per device.
 int compute_units() {
   constexpr int kMaxDevices = 64;
@@ -142,6 +151,13 @@ void launch_subwave(const Args& a) {
   hipLaunchKernelGGL((rms::layernorm_subwave_kernel<DT, CHUNKS, L, true>), dim3((unsigned)blocks),
                      dim3(rms::kLnWave), 0, a.stream, (const u32x4*)a.x, (const u32x4*)a.w,
                      (const u32x4*)a.b, (u32x4*)a.y, a.M, a.nvec, (float)a.N, a.eps);
+}
+
+template <int DT, int CHUNKS, int G>
+void launch_row_unaligned(const Args& a, int nfull) {
+  const int64_t blocks = a.M < kMaxGrid ? a.M : kMaxGrid;
+  hipLaunchKernelGGL((rms::layernorm_row_unaligned_kernel<DT, CHUNKS, G, true>), dim3((unsigned)blocks),
+                     dim3(G), 0, a.stream, a.x, a.w, a.b, a.y, a.M, a.N, nfull, (float)a.N, a.eps);
 }
 
 template <int DT>
@@ -199,10 +215,49 @@ int dispatch(const Args& a, int threads) {
   return LAYERNORM_OK;
 }
 
+// Launches the element-aligned row kernel.  The caller has checked that the row fits.
+template <int DT>
+int dispatch_unaligned(const Args& a) {
+  const int nfull = (int)(a.N / rms::Storage<DT>::kVec);
+  const int threads = pick_threads_unaligned(nfull);
+  int chunks = (nfull + threads - 1) / threads;
+  if (chunks < 1) chunks = 1;
+  switch (threads) {
+    case 64:
+#define LN_L(c) launch_row_unaligned<DT, c, 64>(a, nfull)
+      switch (chunks) {
+        LN_CASE(1, LN_L(1)) LN_CASE(2, LN_L(2)) LN_CASE(3, LN_L(3)) LN_CASE(4, LN_L(4))
+        default: return LAYERNORM_ERR_UNSUPPORTED;
+      }
+#undef LN_L
+      break;
+    case 256:
+#define LN_L(c) launch_row_unaligned<DT, c, 256>(a, nfull)
+      switch (chunks) { LN_CASES_1_8(LN_L) default: return LAYERNORM_ERR_UNSUPPORTED; }
+#undef LN_L
+      break;
+    case 512:
+#define LN_L(c) launch_row_unaligned<DT, c, 512>(a, nfull)
+      switch (chunks) { LN_CASES_1_8(LN_L) default: return LAYERNORM_ERR_UNSUPPORTED; }
+#undef LN_L
+      break;
+    case 1024:
+#define LN_L(c) launch_row_unaligned<DT, c, 1024>(a, nfull)
+      switch (chunks) { LN_CASES_1_8(LN_L) default: return LAYERNORM_ERR_UNSUPPORTED; }
+#undef LN_L
+      break;
+    default:
+      return LAYERNORM_ERR_UNSUPPORTED;
+  }
+  return LAYERNORM_OK;
+}
+
+// threads == 0 means the element-wise kernel, threads == -1 the element-aligned row kernel.
 template <int DT>
 int run_typed(const Args& a, int threads) {
   int rc = LAYERNORM_OK;
   if (threads == 0) launch_generic<DT>(a);
+  else if (threads == -1) rc = dispatch_unaligned<DT>(a);
   else rc = dispatch<DT>(a, threads);
   if (rc != LAYERNORM_OK) return rc;
   return hipGetLastError() == hipSuccess ? LAYERNORM_OK : LAYERNORM_ERR_LAUNCH;
@@ -213,15 +268,20 @@ int run(const void* x, const void* w, const void* b, void* y, int64_t M, int64_t
         int dtype, void* stream, int variant, int threads) {
   int rc = check_args(x, w, b, y, M, N, eps, dtype);
   if (rc != LAYERNORM_OK) return rc;
-  if (variant < -1 || variant > LAYERNORM_VARIANT_SUBWAVE) return LAYERNORM_ERR_INVALID_ARG;
+  if (variant < -1 || variant > LAYERNORM_VARIANT_UNALIGNED) return LAYERNORM_ERR_INVALID_ARG;
   if (variant == -1 && max_chunks_for(threads) == 0) return LAYERNORM_ERR_INVALID_ARG;
   if (M == 0) return LAYERNORM_OK;
 
   const bool vec_ok = rows_vectorisable(x, w, b, y, N, dtype);
   const int64_t nvec = vec_ok ? N * elem_bytes(dtype) / 16 : 0;
+  const bool unaligned_fits = pick_threads_unaligned(N / (16 / elem_bytes(dtype))) != 0;
   switch (variant) {
     case LAYERNORM_VARIANT_AUTO:
-      threads = vec_ok ? pick_threads(nvec, 8, dtype) : 0;
+      threads = vec_ok ? pick_threads(nvec, 8, dtype) : unaligned_fits ? -1 : 0;
+      break;
+    case LAYERNORM_VARIANT_UNALIGNED:
+      if (!unaligned_fits) return LAYERNORM_ERR_UNSUPPORTED;
+      threads = -1;
       break;
     case -1:
       if (!(vec_ok && threads_can(threads, nvec))) return LAYERNORM_ERR_UNSUPPORTED;

@@ -381,6 +381,119 @@ layernorm_subwave_kernel(const u32x4* x, const u32x4* __restrict__ w, const u32x
   }
 }
 
+// ---------------------------------------------------------------------------
+// The one-row-per-workgroup kernel for rows that are NOT 16-byte aligned (odd N such as the
+// paper's edge dims 1023 / 4097 / 1537, or base pointers off a 16-byte boundary).  Rows,
+// weight and bias are addressed in elements: thread t holds the 16-byte groups c * G + t of
+// the floor(N / VEC) full groups, read and written with 128-bit accesses that are only
+// element-aligned (single global_load/store_dwordx4 instructions on this target), and threads
+// 0 .. N % VEC - 1 each take one of the leftover elements at the end of the row.  x is still
+// read exactly once.  Same arithmetic as layernorm_row_kernel.
+// ---------------------------------------------------------------------------
+template <int DT, int CHUNKS, int G, bool NT>
+__global__ void __launch_bounds__(G) __attribute__((amdgpu_waves_per_eu(4)))
+layernorm_row_unaligned_kernel(const void* x, const void* __restrict__ w, const void* __restrict__ b,
+                               void* y, int64_t M, int64_t N, int nfull, float n, float eps) {
+  using S = Storage<DT>;
+  constexpr int VEC = S::kVec;
+  constexpr int WAVES = G / kLnWave;
+  constexpr int kGroupBytes = 16;
+  __shared__ float part_a[2][WAVES];
+  __shared__ float part_b[2][WAVES];
+  const int t = threadIdx.x;
+  const int lane = t & (kLnWave - 1);
+  const int wave = t / kLnWave;
+  const int last = (CHUNKS - 1) * G + t;
+  const bool last_ok = last < nfull;
+  const int rem = (int)(N - (int64_t)nfull * VEC);
+  const bool tail_ok = t < rem;
+  const int64_t tail_col = (int64_t)nfull * VEC + t;
+  const bool has_bias = b != nullptr;
+  const u32x4 zero = {0u, 0u, 0u, 0u};
+  const char* wb = static_cast<const char*>(w);
+  const char* bb = static_cast<const char*>(b);
+  int slot = 0;
+
+  for (int64_t row = blockIdx.x; row < M; row += gridDim.x) {
+    const char* xr = static_cast<const char*>(x) + row * N * S::kBytes;
+    char* yr = static_cast<char*>(y) + row * N * S::kBytes;
+
+    u32x4 v[CHUNKS];
+#pragma unroll
+    for (int c = 0; c < CHUNKS - 1; ++c)
+      v[c] = load_vec_unaligned<NT>(xr + (int64_t)(c * G + t) * kGroupBytes);
+    v[CHUNKS - 1] = zero;
+    if (last_ok) v[CHUNKS - 1] = load_vec_unaligned<NT>(xr + (int64_t)last * kGroupBytes);
+    const float shift = S::load_one(x, row * N);      // the row's first element
+    float tail = 0.f;
+    if (tail_ok) tail = S::load_one(x, row * N + tail_col) - shift;
+
+    float f[CHUNKS][VEC];
+    float acc[4] = {tail, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int c = 0; c < CHUNKS; ++c) {
+      S::unpack(v[c], f[c]);
+      const bool live = c < CHUNKS - 1 || last_ok;
+#pragma unroll
+      for (int k = 0; k < VEC; ++k) {
+        f[c][k] = live ? f[c][k] - shift : 0.f;
+        acc[k & 3] += f[c][k];
+      }
+    }
+    float s1 = wave_sum((acc[0] + acc[1]) + (acc[2] + acc[3]));
+    if constexpr (WAVES > 1) {
+      if (lane == 0) part_a[slot][wave] = s1;
+      __syncthreads();
+      s1 = part_a[slot][0];
+#pragma unroll
+      for (int k = 1; k < WAVES; ++k) s1 += part_a[slot][k];
+    }
+    const float mean_shifted = s1 / n;
+
+    tail = tail_ok ? tail - mean_shifted : 0.f;
+    float sq[4] = {tail * tail, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int c = 0; c < CHUNKS; ++c) {
+      const bool live = c < CHUNKS - 1 || last_ok;
+#pragma unroll
+      for (int k = 0; k < VEC; ++k) {
+        f[c][k] = live ? f[c][k] - mean_shifted : 0.f;
+        sq[k & 3] = __builtin_fmaf(f[c][k], f[c][k], sq[k & 3]);
+      }
+    }
+    float s2 = wave_sum((sq[0] + sq[1]) + (sq[2] + sq[3]));
+    if constexpr (WAVES > 1) {
+      if (lane == 0) part_b[slot][wave] = s2;
+      __syncthreads();
+      s2 = part_b[slot][0];
+#pragma unroll
+      for (int k = 1; k < WAVES; ++k) s2 += part_b[slot][k];
+      slot ^= 1;
+    }
+    const float rstd = ln_rstd(s2, n, eps);
+
+    // weight and bias only now (L2 hits), behind an empty asm so that they are not hoisted
+    // above the reductions, where the centred row already fills the register budget
+    const char* wp = wb;
+    const char* bp = bb;
+    asm volatile("" : "+s"(wp), "+s"(bp));
+#pragma unroll
+    for (int c = 0; c < CHUNKS; ++c) {
+      if (c < CHUNKS - 1 || last_ok) {
+        const int64_t off = (int64_t)(c * G + t) * kGroupBytes;
+        const u32x4 wv = load_vec_unaligned<false>(wp + off);
+        const u32x4 bv = has_bias ? load_vec_unaligned<false>(bp + off) : zero;
+        store_vec_unaligned<NT>(yr + off, ln_scale<DT>(f[c], wv, bv, has_bias, rstd));
+      }
+    }
+    if (tail_ok) {
+      const float tq = (tail * rstd) * S::load_one(w, tail_col);
+      S::store_one(y, row * N + tail_col, has_bias ? tq + S::load_one(b, tail_col) : tq);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
 // Element-wise fallback: any alignment, any N; three passes (shifted sum, centred
 // squares, write).  In-place safe for the same reason as the other fallbacks.
 template <int DT, int T>

@@ -72,6 +72,15 @@ int pick_threads(int64_t nvec, int min_threads) {
   return 0;
 }
 
+// Threads per row for the element-aligned kernel over `nfull` full 16-byte groups (the same
+// bands); 0 if the row does not fit in registers.
+int pick_threads_unaligned(int64_t nfull) {
+  if (nfull <= kSmallRowVectors) return 64;
+  for (int g = 256; g <= kMaxThreads; g *= 2)
+    if (nfull <= (int64_t)g * kBlockMaxChunks) return g;
+  return 0;
+}
+
 struct Args {
   const void* x;
   void* y;
@@ -96,6 +105,13 @@ void launch_subwave(const Args& a) {
   hipLaunchKernelGGL((rms::softmax_subwave_kernel<DT, CHUNKS, L, true>), dim3((unsigned)blocks),
                      dim3(rms::kWaveSize), 0, a.stream, (const u32x4*)a.x, (u32x4*)a.y, a.M,
                      a.nvec);
+}
+
+template <int DT, int CHUNKS, int G>
+void launch_row_unaligned(const Args& a, int nfull) {
+  const int64_t blocks = a.M < kMaxGrid ? a.M : kMaxGrid;
+  hipLaunchKernelGGL((rms::softmax_row_unaligned_kernel<DT, CHUNKS, G, true>), dim3((unsigned)blocks),
+                     dim3(G), 0, a.stream, a.x, a.y, a.M, a.N, nfull);
 }
 
 template <int DT>
@@ -152,10 +168,49 @@ int dispatch(const Args& a, int threads) {
   return SOFTMAX_OK;
 }
 
+// Launches the element-aligned row kernel.  The caller has checked that the row fits.
+template <int DT>
+int dispatch_unaligned(const Args& a) {
+  const int nfull = (int)(a.N / rms::Storage<DT>::kVec);
+  const int threads = pick_threads_unaligned(nfull);
+  int chunks = (nfull + threads - 1) / threads;
+  if (chunks < 1) chunks = 1;
+  switch (threads) {
+    case 64:
+#define SM_L(c) launch_row_unaligned<DT, c, 64>(a, nfull)
+      switch (chunks) {
+        SM_CASE(1, SM_L(1)) SM_CASE(2, SM_L(2)) SM_CASE(3, SM_L(3)) SM_CASE(4, SM_L(4))
+        default: return SOFTMAX_ERR_UNSUPPORTED;
+      }
+#undef SM_L
+      break;
+    case 256:
+#define SM_L(c) launch_row_unaligned<DT, c, 256>(a, nfull)
+      switch (chunks) { SM_CASES_1_8(SM_L) default: return SOFTMAX_ERR_UNSUPPORTED; }
+#undef SM_L
+      break;
+    case 512:
+#define SM_L(c) launch_row_unaligned<DT, c, 512>(a, nfull)
+      switch (chunks) { SM_CASES_1_8(SM_L) default: return SOFTMAX_ERR_UNSUPPORTED; }
+#undef SM_L
+      break;
+    case 1024:
+#define SM_L(c) launch_row_unaligned<DT, c, 1024>(a, nfull)
+      switch (chunks) { SM_CASES_1_8(SM_L) default: return SOFTMAX_ERR_UNSUPPORTED; }
+#undef SM_L
+      break;
+    default:
+      return SOFTMAX_ERR_UNSUPPORTED;
+  }
+  return SOFTMAX_OK;
+}
+
+// threads == 0 means the element-wise kernel, threads == -1 the element-aligned row kernel.
 template <int DT>
 int run_typed(const Args& a, int threads) {
   int rc = SOFTMAX_OK;
   if (threads == 0) launch_generic<DT>(a);
+  else if (threads == -1) rc = dispatch_unaligned<DT>(a);
   else rc = dispatch<DT>(a, threads);
   if (rc != SOFTMAX_OK) return rc;
   return hipGetLastError() == hipSuccess ? SOFTMAX_OK : SOFTMAX_ERR_LAUNCH;
@@ -166,15 +221,20 @@ int run(const void* x, void* y, int64_t M, int64_t N, int dtype, void* stream, i
         int threads) {
   int rc = check_args(x, y, M, N, dtype);
   if (rc != SOFTMAX_OK) return rc;
-  if (variant < -1 || variant > SOFTMAX_VARIANT_SUBWAVE) return SOFTMAX_ERR_INVALID_ARG;
+  if (variant < -1 || variant > SOFTMAX_VARIANT_UNALIGNED) return SOFTMAX_ERR_INVALID_ARG;
   if (variant == -1 && max_chunks_for(threads) == 0) return SOFTMAX_ERR_INVALID_ARG;
   if (M == 0) return SOFTMAX_OK;
 
   const bool vec_ok = rows_vectorisable(x, y, N, dtype);
   const int64_t nvec = vec_ok ? N * elem_bytes(dtype) / 16 : 0;
+  const bool unaligned_fits = pick_threads_unaligned(N / (16 / elem_bytes(dtype))) != 0;
   switch (variant) {
     case SOFTMAX_VARIANT_AUTO:
-      threads = vec_ok ? pick_threads(nvec, 8) : 0;
+      threads = vec_ok ? pick_threads(nvec, 8) : unaligned_fits ? -1 : 0;
+      break;
+    case SOFTMAX_VARIANT_UNALIGNED:
+      if (!unaligned_fits) return SOFTMAX_ERR_UNSUPPORTED;
+      threads = -1;
       break;
     case -1:
       if (!(vec_ok && threads_can(threads, nvec))) return SOFTMAX_ERR_UNSUPPORTED;

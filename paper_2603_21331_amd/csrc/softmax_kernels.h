@@ -17,8 +17,11 @@
 //                                     sum through LDS, two barriers per row.
 //  * softmax_subwave_kernel        : 8, 16 or 32 lanes per row for rows <= 1 KiB
 //                                     (attention scores over short contexts).
-//  * softmax_generic_kernel        : element-wise three-pass fallback, any
-//                                     alignment, any N.
+//  * softmax_row_unaligned_kernel  : the row kernel for rows that are not 16-byte
+//                                     aligned (element-aligned 128-bit accesses
+//                                     plus a scalar tail).
+//  * softmax_generic_kernel        : element-wise three-pass fallback for rows
+//                                     too long for registers.
 //
 // Reductions have a fixed order and use no atomics: results are bit-identical
 // from run to run.
@@ -198,6 +201,105 @@ softmax_subwave_kernel(const u32x4* x, u32x4* y, int64_t M, int nvec) {
       for (int k = 0; k < VEC; ++k) f[c][k] *= inv;
       if (row_ok && idx < nvec) store_vec<NT>(yr + idx, S::pack(f[c]));
     }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// The same register-resident kernel for rows that are NOT 16-byte aligned (odd N such as
+// the paper's edge dims 1023 / 4097 / 1537, or base pointers off a 16-byte boundary).
+// Rows are addressed in elements: thread t holds the 16-byte groups c * G + t of the row's
+// floor(N / VEC) full groups, read and written with 128-bit accesses that are only
+// element-aligned (single global_load/store_dwordx4 instructions on this target), and
+// threads 0 .. N % VEC - 1 each take one of the leftover elements at the end of the row.
+// x is still read exactly once.
+// ---------------------------------------------------------------------------
+template <int DT, int CHUNKS, int G, bool NT>
+__global__ void __launch_bounds__(G)
+softmax_row_unaligned_kernel(const void* x, void* y, int64_t M, int64_t N, int nfull) {
+  using S = Storage<DT>;
+  constexpr int VEC = S::kVec;
+  constexpr int WAVES = G / kWaveSize;
+  constexpr int kGroupBytes = 16;
+  __shared__ float part_max[2][WAVES];
+  __shared__ float part_sum[2][WAVES];
+  const int t = threadIdx.x;
+  const int lane = t & (kWaveSize - 1);
+  const int wave = t / kWaveSize;
+  const int last = (CHUNKS - 1) * G + t;
+  const bool last_ok = last < nfull;
+  const int rem = (int)(N - (int64_t)nfull * VEC);
+  const bool tail_ok = t < rem;
+  const int64_t tail_col = (int64_t)nfull * VEC + t;
+  int slot = 0;
+
+  for (int64_t row = blockIdx.x; row < M; row += gridDim.x) {
+    const char* xr = static_cast<const char*>(x) + row * N * S::kBytes;
+    char* yr = static_cast<char*>(y) + row * N * S::kBytes;
+
+    u32x4 v[CHUNKS];
+#pragma unroll
+    for (int c = 0; c < CHUNKS - 1; ++c)
+      v[c] = load_vec_unaligned<NT>(xr + (int64_t)(c * G + t) * kGroupBytes);
+    {
+      const u32x4 zero = {0u, 0u, 0u, 0u};
+      v[CHUNKS - 1] = zero;
+      if (last_ok) v[CHUNKS - 1] = load_vec_unaligned<NT>(xr + (int64_t)last * kGroupBytes);
+    }
+    float tail = kNegInf;
+    if (tail_ok) tail = S::load_one(x, row * N + tail_col);
+
+    float f[CHUNKS][VEC];
+    float m = tail;
+#pragma unroll
+    for (int c = 0; c < CHUNKS; ++c) {
+      S::unpack(v[c], f[c]);
+      if (c == CHUNKS - 1 && !last_ok) {
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) f[c][k] = kNegInf;
+      }
+#pragma unroll
+      for (int k = 0; k < VEC; ++k) m = __builtin_fmaxf(m, f[c][k]);
+    }
+    m = wave_max(m);
+    if constexpr (WAVES > 1) {
+      if (lane == 0) part_max[slot][wave] = m;
+      __syncthreads();
+      m = part_max[slot][0];
+#pragma unroll
+      for (int k = 1; k < WAVES; ++k) m = __builtin_fmaxf(m, part_max[slot][k]);
+    }
+
+    // a lane without a leftover element adds exactly 0 (its -inf gives exp(-inf) = 0, or
+    // NaN when the whole row is -inf, which is what such a row must give anyway)
+    tail = exp_neg<DT>(tail - m);
+    float acc[4] = {tail, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int c = 0; c < CHUNKS; ++c) {
+#pragma unroll
+      for (int k = 0; k < VEC; ++k) {
+        f[c][k] = exp_neg<DT>(f[c][k] - m);
+        acc[k & 3] += f[c][k];
+      }
+    }
+    float s = wave_sum((acc[0] + acc[1]) + (acc[2] + acc[3]));
+    if constexpr (WAVES > 1) {
+      if (lane == 0) part_sum[slot][wave] = s;
+      __syncthreads();
+      s = part_sum[slot][0];
+#pragma unroll
+      for (int k = 1; k < WAVES; ++k) s += part_sum[slot][k];
+      slot ^= 1;
+    }
+    const float inv = 1.0f / s;
+
+#pragma unroll
+    for (int c = 0; c < CHUNKS; ++c) {
+#pragma unroll
+      for (int k = 0; k < VEC; ++k) f[c][k] *= inv;
+      if (c < CHUNKS - 1 || last_ok)
+        store_vec_unaligned<NT>(yr + (int64_t)(c * G + t) * kGroupBytes, S::pack(f[c]));
+    }
+    if (tail_ok) S::store_one(y, row * N + tail_col, tail * inv);
   }
 }
 

@@ -14,7 +14,7 @@ pytestmark = pytest.mark.gpu
 
 DTYPES = [inputs.FP32, inputs.FP16, inputs.BF16]
 THREADS = (8, 16, 32, 64, 256, 512, 1024)
-MODES = (0, 1, 2, 3, 4) + tuple(("threads", g) for g in THREADS)
+MODES = (0, 1, 2, 3, 4, 5) + tuple(("threads", g) for g in THREADS)
 
 
 def mode_name(m):
@@ -166,6 +166,38 @@ def test_in_place_and_empty(gpu_device, dtype, N):
         compare.check_layernorm_parity(H.to_host(xd, dtype), want, bias64, dtype, f"in place {mode_name(m)}")
     empty = torch.empty((0, N), dtype=H.torch_dtype(dtype), device=gpu_device)
     assert tuple(layernorm.layernorm_fwd(empty, wd, bd, 1e-5).shape) == (0, N)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("N", [2048, 1001, 5])
+def test_misaligned_base_pointers(gpu_device, dtype, N):
+    """x, w, b and y each off a 16-byte boundary by a different number of elements: the
+    automatic path takes the element-aligned kernel, stays inside the buffers and matches the
+    oracle; so does the element-wise kernel; the kernels that need 16-byte rows refuse."""
+    M = 41
+    case = inputs.layernorm_case(5, 1470 + 4 * dtype, M, N, dtype, mean=0.4)
+    want, mean, rstd = oracle.layernorm_oracle(case["x"], case["w"], case["b"], 1e-5, dtype, stats=True)
+    scale = scale_of(case, mean, rstd)
+    td = H.torch_dtype(dtype)
+    xbuf = torch.zeros(M * N + 8, dtype=td, device=gpu_device)
+    wbuf = torch.zeros(N + 8, dtype=td, device=gpu_device)
+    bbuf = torch.zeros(N + 8, dtype=td, device=gpu_device)
+    xd, wd, bd = xbuf[1:1 + M * N].view(M, N), wbuf[3:3 + N], bbuf[2:2 + N]
+    xd.copy_(H.to_device(case["x"], dtype, gpu_device))
+    wd.copy_(H.to_device(case["w"], dtype, gpu_device))
+    bd.copy_(H.to_device(case["b"], dtype, gpu_device))
+    for mode in (0, layernorm.LAYERNORM_VARIANT_UNALIGNED, layernorm.LAYERNORM_VARIANT_GENERIC):
+        whole, y = H.alloc_guarded(M, N, dtype, gpu_device, offset_elems=1)
+        H.say(f"layernorm misaligned bases N={N} mode={mode_name(mode)}")
+        layernorm.layernorm_fwd_variant(xd, wd, bd, 1e-5, mode, y)
+        torch.cuda.synchronize()
+        assert H.guards_intact(whole, M, N, dtype, offset_elems=1)
+        compare.check_layernorm_parity(H.to_host(y, dtype), want, scale, dtype, f"misaligned bases {mode_name(mode)}")
+    _, y = H.alloc_guarded(M, N, dtype, gpu_device, offset_elems=1)
+    for v in (layernorm.LAYERNORM_VARIANT_WAVE, layernorm.LAYERNORM_VARIANT_BLOCK, layernorm.LAYERNORM_VARIANT_SUBWAVE):
+        with pytest.raises(layernorm.LayerNormError) as e:
+            layernorm.layernorm_fwd_variant(xd, wd, bd, 1e-5, v, y)
+        assert e.value.status == layernorm.LAYERNORM_ERR_UNSUPPORTED
 
 
 # The resident kernel (rows of at most 24 elements per thread, 256..1024 threads) walks rows

@@ -57,6 +57,9 @@ def test_empty_batch_unknown_variant_and_unsupported_shapes():
     assert lib.softmax_fwd_tuned(P, P + BIG, 4, 4096, 2, None, 64) == softmax.SOFTMAX_ERR_UNSUPPORTED
     assert lib.softmax_fwd_tuned(P, P + BIG, 1, 65544, 2, None, 1024) == softmax.SOFTMAX_ERR_UNSUPPORTED
     assert lib.softmax_fwd_variant(P, P + BIG, 1, 65544, 2, None, 2) == softmax.SOFTMAX_ERR_UNSUPPORTED
+    # the element-aligned kernel takes any alignment but not rows past the register limit
+    assert lib.softmax_fwd_variant(P, P + BIG, 1, 65544, 2, None, 5) == softmax.SOFTMAX_ERR_UNSUPPORTED
+    assert lib.softmax_fwd_variant(P, P + BIG, 0, 1023, 2, None, 5) == softmax.SOFTMAX_OK
 
 
 def test_automatic_threads_per_row():

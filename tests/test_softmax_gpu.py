@@ -16,7 +16,7 @@ pytestmark = pytest.mark.gpu
 
 DTYPES = [inputs.FP32, inputs.FP16, inputs.BF16]
 THREADS = (8, 16, 32, 64, 256, 512, 1024)
-MODES = (0, 1, 2, 3, 4) + tuple(("threads", g) for g in THREADS)
+MODES = (0, 1, 2, 3, 4, 5) + tuple(("threads", g) for g in THREADS)
 
 
 def mode_name(m):
@@ -205,6 +205,32 @@ def test_in_place_and_empty(gpu_device, dtype, N):
         compare.check_softmax_parity(H.to_host(xd, dtype), want, dtype, f"in place {mode_name(m)}")
     empty = torch.empty((0, N), dtype=H.torch_dtype(dtype), device=gpu_device)
     assert tuple(softmax.softmax_fwd(empty).shape) == (0, N)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("N", [2048, 1001, 5])
+def test_misaligned_base_pointers(gpu_device, dtype, N):
+    """Bases one and three elements off a 16-byte boundary: the automatic path takes the
+    element-aligned kernel, stays inside the buffers and matches the oracle; so does the
+    element-wise kernel; the kernels that need 16-byte rows refuse."""
+    M = 41
+    case = inputs.softmax_case(5, 1180 + dtype, M, N, dtype, 2.0)
+    want = oracle.softmax_oracle(case["x"], dtype)
+    xbuf = torch.zeros(M * N + 8, dtype=H.torch_dtype(dtype), device=gpu_device)
+    xd = xbuf[1:1 + M * N].view(M, N)
+    xd.copy_(H.to_device(case["x"], dtype, gpu_device))
+    for mode in (0, softmax.SOFTMAX_VARIANT_UNALIGNED, softmax.SOFTMAX_VARIANT_GENERIC):
+        whole, y = H.alloc_guarded(M, N, dtype, gpu_device, offset_elems=3)
+        H.say(f"softmax misaligned bases N={N} mode={mode_name(mode)}")
+        softmax.softmax_fwd_variant(xd, mode, y)
+        torch.cuda.synchronize()
+        assert H.guards_intact(whole, M, N, dtype, offset_elems=3)
+        compare.check_softmax_parity(H.to_host(y, dtype), want, dtype, f"misaligned bases {mode_name(mode)}")
+    _, y = H.alloc_guarded(M, N, dtype, gpu_device, offset_elems=3)
+    for v in (softmax.SOFTMAX_VARIANT_WAVE, softmax.SOFTMAX_VARIANT_BLOCK, softmax.SOFTMAX_VARIANT_SUBWAVE):
+        with pytest.raises(softmax.SoftmaxError) as e:
+            softmax.softmax_fwd_variant(xd, v, y)
+        assert e.value.status == softmax.SOFTMAX_ERR_UNSUPPORTED
 
 
 def test_binding_rejects_mismatched_tensors(gpu_device):
