@@ -18,8 +18,9 @@
  * library never allocates, copies or synchronises; work is enqueued on `stream`;
  * x and y are M x N row-major with leading dimension N and share one storage
  * type; pointers need only element alignment (rows that are not 16-byte aligned
- * run the register-resident kernel with element-aligned accesses; only rows too
- * long for registers take a slower element-wise kernel); y == x exactly
+ * run the register-resident kernel with element-aligned accesses; rows too long
+ * for registers, beyond softmax_register_max_n, stream through a two-pass kernel
+ * that reads them a second time from cache); y == x exactly
  * is allowed, any other overlap is undefined; a call returns SOFTMAX_OK or a
  * negative softmax_status and launches nothing on INVALID_ARG / UNSUPPORTED;
  * results are bit-identical from run to run.
@@ -52,8 +53,10 @@ typedef enum {
   SOFTMAX_VARIANT_BLOCK = 2,   /* one workgroup of 256..1024 threads per row */
   SOFTMAX_VARIANT_GENERIC = 3, /* element-wise, three passes, any alignment, any N */
   SOFTMAX_VARIANT_SUBWAVE = 4, /* 8, 16 or 32 lanes per row; 16-byte aligned rows <= 1 KiB */
-  SOFTMAX_VARIANT_UNALIGNED = 5 /* the register-resident row kernel with element-aligned
-                                   128-bit accesses: any alignment, N up to the register limit */
+  SOFTMAX_VARIANT_UNALIGNED = 5, /* the register-resident row kernel with element-aligned
+                                    128-bit accesses: any alignment, N up to the register limit */
+  SOFTMAX_VARIANT_STREAM = 6     /* two streaming passes (online max and sum, then scale) for
+                                    rows too long for registers: any alignment, N < 2^31 */
 } softmax_variant;
 
 /*

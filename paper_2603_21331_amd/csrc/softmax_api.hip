@@ -114,6 +114,20 @@ void launch_row_unaligned(const Args& a, int nfull) {
                      dim3(G), 0, a.stream, a.x, a.y, a.M, a.N, nfull);
 }
 
+// The two-pass streaming kernel: about one batch of four groups per thread, whole wavefronts,
+// at most 1024 threads (what every row long enough to need this kernel gets).
+constexpr int64_t kStreamMaxN = (int64_t)1 << 31;
+
+template <int DT>
+void launch_stream(const Args& a) {
+  const int64_t blocks = a.M < kMaxGrid ? a.M : kMaxGrid;
+  const int64_t nfull = a.N / rms::Storage<DT>::kVec;
+  int64_t threads = (nfull / rms::kStreamBatch + rms::kWaveSize - 1) / rms::kWaveSize * rms::kWaveSize;
+  threads = threads < rms::kWaveSize ? rms::kWaveSize : threads > kMaxThreads ? kMaxThreads : threads;
+  hipLaunchKernelGGL((rms::softmax_stream_kernel<DT>), dim3((unsigned)blocks), dim3((unsigned)threads),
+                     0, a.stream, a.x, a.y, a.M, a.N);
+}
+
 template <int DT>
 void launch_generic(const Args& a) {
   const int64_t blocks = a.M < kMaxGrid ? a.M : kMaxGrid;
@@ -205,12 +219,14 @@ int dispatch_unaligned(const Args& a) {
   return SOFTMAX_OK;
 }
 
-// threads == 0 means the element-wise kernel, threads == -1 the element-aligned row kernel.
+// threads == 0 means the element-wise kernel, -1 the element-aligned row kernel, -2 the
+// two-pass streaming kernel.
 template <int DT>
 int run_typed(const Args& a, int threads) {
   int rc = SOFTMAX_OK;
   if (threads == 0) launch_generic<DT>(a);
   else if (threads == -1) rc = dispatch_unaligned<DT>(a);
+  else if (threads == -2) launch_stream<DT>(a);
   else rc = dispatch<DT>(a, threads);
   if (rc != SOFTMAX_OK) return rc;
   return hipGetLastError() == hipSuccess ? SOFTMAX_OK : SOFTMAX_ERR_LAUNCH;
@@ -221,7 +237,7 @@ int run(const void* x, void* y, int64_t M, int64_t N, int dtype, void* stream, i
         int threads) {
   int rc = check_args(x, y, M, N, dtype);
   if (rc != SOFTMAX_OK) return rc;
-  if (variant < -1 || variant > SOFTMAX_VARIANT_UNALIGNED) return SOFTMAX_ERR_INVALID_ARG;
+  if (variant < -1 || variant > SOFTMAX_VARIANT_STREAM) return SOFTMAX_ERR_INVALID_ARG;
   if (variant == -1 && max_chunks_for(threads) == 0) return SOFTMAX_ERR_INVALID_ARG;
   if (M == 0) return SOFTMAX_OK;
 
@@ -231,6 +247,11 @@ int run(const void* x, void* y, int64_t M, int64_t N, int dtype, void* stream, i
   switch (variant) {
     case SOFTMAX_VARIANT_AUTO:
       threads = vec_ok ? pick_threads(nvec, 8) : unaligned_fits ? -1 : 0;
+      if (threads == 0 && N < kStreamMaxN) threads = -2;     // too long for registers
+      break;
+    case SOFTMAX_VARIANT_STREAM:
+      if (N >= kStreamMaxN) return SOFTMAX_ERR_UNSUPPORTED;
+      threads = -2;
       break;
     case SOFTMAX_VARIANT_UNALIGNED:
       if (!unaligned_fits) return SOFTMAX_ERR_UNSUPPORTED;

@@ -20,8 +20,11 @@
 //  * softmax_row_unaligned_kernel  : the row kernel for rows that are not 16-byte
 //                                     aligned (element-aligned 128-bit accesses
 //                                     plus a scalar tail).
-//  * softmax_generic_kernel        : element-wise three-pass fallback for rows
-//                                     too long for registers.
+//  * softmax_stream_kernel         : rows too long for registers: two streaming
+//                                     passes (online max/sum, then scale), any N
+//                                     and alignment.
+//  * softmax_generic_kernel        : element-wise three-pass kernel, kept as the
+//                                     plainest implementation to test against.
 //
 // Reductions have a fixed order and use no atomics: results are bit-identical
 // from run to run.
@@ -300,6 +303,148 @@ softmax_row_unaligned_kernel(const void* x, void* y, int64_t M, int64_t N, int n
         store_vec_unaligned<NT>(yr + (int64_t)(c * G + t) * kGroupBytes, S::pack(f[c]));
     }
     if (tail_ok) S::store_one(y, row * N + tail_col, tail * inv);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Rows too long for registers (a softmax over a vocabulary of 100 k to 250 k entries, or
+// longer): two streaming passes by one workgroup per row.  Pass one keeps, per thread, a
+// running maximum and a running sum of exponentials relative to it (the online form the
+// paper names for its cross-entropy kernel), folded in batches of four 16-byte groups: the
+// batch maximum first, at most one rescale per batch.  Pass two reads the row again (from
+// L2 or the Infinity Cache: a row of 256 k fp16 values is 512 KiB), forms exp(x - m) / s with
+// the full-accuracy exponential and writes y with streaming stores.  All accesses are
+// element-aligned 128-bit ones over the row's floor(N / VEC) full groups plus a scalar tail,
+// so any N and any base alignment take this one path.  HBM traffic stays one read of x and
+// one write of y as long as the rows in flight fit the Infinity Cache.  In-place safe: a
+// barrier separates every read of pass one from every write of pass two, and in pass two a
+// thread reads a group before it overwrites it.
+// ---------------------------------------------------------------------------
+constexpr int kStreamBatch = 4;
+constexpr int kStreamMaxWaves = 16;
+
+// 2^((a - b) log2 e) for a <= b, with equal arguments (two -inf included) giving exactly 1.
+__device__ __forceinline__ float sm_rescale(float a, float b) {
+  return a == b ? 1.0f : __builtin_amdgcn_exp2f((a - b) * 1.44269502162933349609375f);
+}
+
+// Folds COUNT values into the running (m, s) pair.
+template <int COUNT>
+__device__ __forceinline__ void sm_fold(const float (&f)[COUNT], float& m, float& s) {
+  float bm = m;
+#pragma unroll
+  for (int k = 0; k < COUNT; ++k) bm = __builtin_fmaxf(bm, f[k]);
+  s *= sm_rescale(m, bm);
+  m = bm;
+  // only -inf so far: every term is exp(-inf) = 0; subtracting 0 keeps -inf - (-inf) from NaN
+  const float ref = bm == kNegInf ? 0.0f : bm;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int k = 0; k < COUNT; ++k)
+    acc[k & 3] += __builtin_amdgcn_exp2f((f[k] - ref) * 1.44269502162933349609375f);
+  s += (acc[0] + acc[1]) + (acc[2] + acc[3]);
+}
+
+// Groups (k0 + u) * G + t, u < COUNT, of a row; indices past the last full group (only
+// possible in a thread's last batch) are clamped to it, so that every load is unconditional,
+// and the lanes concerned fold -inf instead of what the clamped load brought.  nfull >= 1.
+template <int DT, int COUNT>
+__device__ __forceinline__ void sm_stream_batch(const char* xr, int k0, int G, int t, int nfull,
+                                                float& m, float& s) {
+  constexpr int VEC = Storage<DT>::kVec;
+  u32x4 v[COUNT];
+#pragma unroll
+  for (int u = 0; u < COUNT; ++u) {
+    const int idx = (k0 + u) * G + t;
+    v[u] = load_vec_unaligned<false>(xr + (int64_t)(idx < nfull ? idx : nfull - 1) * 16);
+  }
+  float f[COUNT * VEC];
+#pragma unroll
+  for (int u = 0; u < COUNT; ++u) {
+    float g[VEC];
+    Storage<DT>::unpack(v[u], g);
+    const bool live = (k0 + u) * G + t < nfull;
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) f[u * VEC + k] = live ? g[k] : kNegInf;
+  }
+  sm_fold<COUNT * VEC>(f, m, s);
+}
+
+template <int DT>
+__global__ void __launch_bounds__(kStreamMaxWaves * kWaveSize)
+softmax_stream_kernel(const void* x, void* y, int64_t M, int64_t N) {
+  using S = Storage<DT>;
+  constexpr int VEC = S::kVec;
+  constexpr int U = kStreamBatch;
+  __shared__ float part_max[2][kStreamMaxWaves];
+  __shared__ float part_sum[2][kStreamMaxWaves];
+  const int G = blockDim.x;
+  const int waves = G / kWaveSize;
+  const int t = threadIdx.x;
+  const int lane = t & (kWaveSize - 1);
+  const int wave = t / kWaveSize;
+  const int nfull = (int)(N / VEC);
+  const int rem = (int)(N - (int64_t)nfull * VEC);
+  const int per_thread = (nfull + G - 1) / G;             // groups k * G + t, k < per_thread
+  int slot = 0;
+
+  for (int64_t row = blockIdx.x; row < M; row += gridDim.x) {
+    const char* xr = static_cast<const char*>(x) + row * N * S::kBytes;
+    char* yr = static_cast<char*>(y) + row * N * S::kBytes;
+
+    // pass one: running maximum and sum
+    float m = kNegInf, s = 0.f;
+    int k = 0;
+    for (; k + U <= per_thread; k += U) sm_stream_batch<DT, U>(xr, k, G, t, nfull, m, s);
+    switch (per_thread - k) {                             // the same for every thread
+      case 1: sm_stream_batch<DT, 1>(xr, k, G, t, nfull, m, s); break;
+      case 2: sm_stream_batch<DT, 2>(xr, k, G, t, nfull, m, s); break;
+      case 3: sm_stream_batch<DT, 3>(xr, k, G, t, nfull, m, s); break;
+      default: break;
+    }
+    float tail = kNegInf;
+    if (t < rem) {
+      tail = S::load_one(x, row * N + (int64_t)nfull * VEC + t);
+      const float single[1] = {tail};
+      sm_fold<1>(single, m, s);
+    }
+    float row_m = wave_max(m);
+    if (waves > 1) {
+      if (lane == 0) part_max[slot][wave] = row_m;
+      __syncthreads();
+      row_m = part_max[slot][0];
+      for (int w = 1; w < waves; ++w) row_m = __builtin_fmaxf(row_m, part_max[slot][w]);
+    }
+    float row_s = wave_sum(s * sm_rescale(m, row_m));
+    if (waves > 1) {
+      if (lane == 0) part_sum[slot][wave] = row_s;
+      __syncthreads();
+      row_s = part_sum[slot][0];
+      for (int w = 1; w < waves; ++w) row_s += part_sum[slot][w];
+      slot ^= 1;
+    }
+    const float inv = 1.0f / row_s;
+
+    // pass two: exp(x - m) / s, written once; four groups requested at a time
+    for (int k2 = 0; k2 < per_thread; k2 += U) {
+      u32x4 v[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int idx = (k2 + u) * G + t;
+        v[u] = load_vec_unaligned<false>(xr + (int64_t)(idx < nfull ? idx : nfull - 1) * 16);
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int idx = (k2 + u) * G + t;
+        float f[VEC];
+        S::unpack(v[u], f);
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) f[j] = exp_neg<DT>(f[j] - row_m) * inv;
+        if (idx < nfull) store_vec_unaligned<true>(yr + (int64_t)idx * 16, S::pack(f));
+      }
+    }
+    if (t < rem)
+      S::store_one(y, row * N + (int64_t)nfull * VEC + t, exp_neg<DT>(tail - row_m) * inv);
   }
 }
 

@@ -60,6 +60,10 @@ def test_empty_batch_unknown_variant_and_unsupported_shapes():
     # the element-aligned kernel takes any alignment but not rows past the register limit
     assert lib.softmax_fwd_variant(P, P + BIG, 1, 65544, 2, None, 5) == softmax.SOFTMAX_ERR_UNSUPPORTED
     assert lib.softmax_fwd_variant(P, P + BIG, 0, 1023, 2, None, 5) == softmax.SOFTMAX_OK
+    # the streaming kernel takes any N below 2^31
+    assert lib.softmax_fwd_variant(P, P + BIG, 0, 1 << 30, 2, None, 6) == softmax.SOFTMAX_OK
+    assert lib.softmax_fwd_variant(P, P + BIG, 1, 1 << 31, 2, None, 6) == softmax.SOFTMAX_ERR_UNSUPPORTED
+    assert lib.softmax_fwd_variant(P, P + BIG, 1, 8, 2, None, 7) == softmax.SOFTMAX_ERR_INVALID_ARG
 
 
 def test_automatic_threads_per_row():
