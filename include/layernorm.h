@@ -21,8 +21,9 @@
  * x and y are M x N row-major with leading dimension N, w and b have N elements,
  * all of one storage type; b may be NULL (no bias); pointers need only element
  * alignment (rows that are not 16-byte aligned run a register-resident kernel with
- * element-aligned accesses; only rows too long for registers take a slower
- * element-wise kernel); y == x exactly is allowed, any other overlap is
+ * element-aligned accesses; rows too long for registers, beyond
+ * layernorm_register_max_n, stream through a three-pass kernel that re-reads them
+ * from cache); y == x exactly is allowed, any other overlap is
  * undefined; a call returns LAYERNORM_OK or a negative layernorm_status and
  * launches nothing on INVALID_ARG / UNSUPPORTED; results are bit-identical from
  * run to run.
@@ -55,8 +56,11 @@ typedef enum {
   LAYERNORM_VARIANT_BLOCK = 2,   /* one workgroup of 256..1024 threads per row */
   LAYERNORM_VARIANT_GENERIC = 3, /* element-wise, three passes, any alignment, any N */
   LAYERNORM_VARIANT_SUBWAVE = 4, /* 8, 16 or 32 lanes per row; 16-byte aligned rows <= 1 KiB */
-  LAYERNORM_VARIANT_UNALIGNED = 5 /* the register-resident row kernel with element-aligned
-                                     128-bit accesses: any alignment, N up to the register limit */
+  LAYERNORM_VARIANT_UNALIGNED = 5, /* the register-resident row kernel with element-aligned
+                                      128-bit accesses: any alignment, N up to the register limit */
+  LAYERNORM_VARIANT_STREAM = 6     /* three streaming passes with 128-bit accesses for rows too
+                                      long for registers (the second and third read come from
+                                      cache); any alignment, N < 2^31 */
 } layernorm_variant;
 
 /*

@@ -67,8 +67,11 @@ typedef enum {
                                    elements: 128-bit accesses that are only element-aligned
                                    plus a scalar tail; any alignment, N up to
                                    rmsnorm_unaligned_max_n(dtype) */
-  RMSNORM_VARIANT_SUBWAVE = 5   /* 8, 16 or 32 lanes per row, several rows per wavefront;
+  RMSNORM_VARIANT_SUBWAVE = 5,  /* 8, 16 or 32 lanes per row, several rows per wavefront;
                                    16-byte aligned rows of at most 1 KiB */
+  RMSNORM_VARIANT_STREAM = 6    /* two streaming passes with 128-bit accesses for rows too
+                                   long for registers (the second read comes from cache);
+                                   any alignment, N < 2^31 */
 } rmsnorm_variant;
 
 /*

@@ -28,8 +28,9 @@ RMSNORM_VARIANT_BLOCK = 2
 RMSNORM_VARIANT_GENERIC = 3
 RMSNORM_VARIANT_UNALIGNED = 4
 RMSNORM_VARIANT_SUBWAVE = 5
+RMSNORM_VARIANT_STREAM = 6
 
-VARIANT_NAMES = {0: "auto", 1: "wave", 2: "block", 3: "generic", 4: "unaligned", 5: "subwave"}
+VARIANT_NAMES = {0: "auto", 1: "wave", 2: "block", 3: "generic", 4: "unaligned", 5: "subwave", 6: "stream"}
 
 _lib = None
 

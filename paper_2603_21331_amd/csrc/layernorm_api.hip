@@ -160,6 +160,20 @@ void launch_row_unaligned(const Args& a, int nfull) {
                      dim3(G), 0, a.stream, a.x, a.w, a.b, a.y, a.M, a.N, nfull, (float)a.N, a.eps);
 }
 
+// The three-pass streaming kernel: about one batch of four groups per thread, whole
+// wavefronts, at most 1024 threads (what every row long enough to need this kernel gets).
+constexpr int64_t kStreamMaxN = (int64_t)1 << 31;   // it counts groups in an int
+
+template <int DT>
+void launch_stream(const Args& a) {
+  const int64_t blocks = a.M < kMaxGrid ? a.M : kMaxGrid;
+  const int64_t nfull = a.N / rms::Storage<DT>::kVec;
+  int64_t threads = (nfull / rms::kLnStreamBatch + rms::kLnWave - 1) / rms::kLnWave * rms::kLnWave;
+  threads = threads < rms::kLnWave ? rms::kLnWave : threads > kMaxThreads ? kMaxThreads : threads;
+  hipLaunchKernelGGL((rms::layernorm_stream_kernel<DT>), dim3((unsigned)blocks), dim3((unsigned)threads),
+                     0, a.stream, a.x, a.w, a.b, a.y, a.M, a.N, (float)a.N, a.eps);
+}
+
 template <int DT>
 void launch_generic(const Args& a) {
   const int64_t blocks = a.M < kMaxGrid ? a.M : kMaxGrid;
@@ -252,12 +266,14 @@ int dispatch_unaligned(const Args& a) {
   return LAYERNORM_OK;
 }
 
-// threads == 0 means the element-wise kernel, threads == -1 the element-aligned row kernel.
+// threads == 0 means the element-wise kernel, -1 the element-aligned row kernel, -2 the
+// three-pass streaming kernel.
 template <int DT>
 int run_typed(const Args& a, int threads) {
   int rc = LAYERNORM_OK;
   if (threads == 0) launch_generic<DT>(a);
   else if (threads == -1) rc = dispatch_unaligned<DT>(a);
+  else if (threads == -2) launch_stream<DT>(a);
   else rc = dispatch<DT>(a, threads);
   if (rc != LAYERNORM_OK) return rc;
   return hipGetLastError() == hipSuccess ? LAYERNORM_OK : LAYERNORM_ERR_LAUNCH;
@@ -268,7 +284,7 @@ int run(const void* x, const void* w, const void* b, void* y, int64_t M, int64_t
         int dtype, void* stream, int variant, int threads) {
   int rc = check_args(x, w, b, y, M, N, eps, dtype);
   if (rc != LAYERNORM_OK) return rc;
-  if (variant < -1 || variant > LAYERNORM_VARIANT_UNALIGNED) return LAYERNORM_ERR_INVALID_ARG;
+  if (variant < -1 || variant > LAYERNORM_VARIANT_STREAM) return LAYERNORM_ERR_INVALID_ARG;
   if (variant == -1 && max_chunks_for(threads) == 0) return LAYERNORM_ERR_INVALID_ARG;
   if (M == 0) return LAYERNORM_OK;
 
@@ -278,6 +294,11 @@ int run(const void* x, const void* w, const void* b, void* y, int64_t M, int64_t
   switch (variant) {
     case LAYERNORM_VARIANT_AUTO:
       threads = vec_ok ? pick_threads(nvec, 8, dtype) : unaligned_fits ? -1 : 0;
+      if (threads == 0 && N < kStreamMaxN) threads = -2;     // too long for registers
+      break;
+    case LAYERNORM_VARIANT_STREAM:
+      if (N >= kStreamMaxN) return LAYERNORM_ERR_UNSUPPORTED;
+      threads = -2;
       break;
     case LAYERNORM_VARIANT_UNALIGNED:
       if (!unaligned_fits) return LAYERNORM_ERR_UNSUPPORTED;

@@ -494,6 +494,125 @@ layernorm_row_unaligned_kernel(const void* x, const void* __restrict__ w, const 
 }
 
 // ---------------------------------------------------------------------------
+// Rows too long for registers: three streaming passes by one workgroup per row (the shifted
+// sum for the mean, the squares of the centred values, the write), four 16-byte groups
+// requested at a time; passes two and three read the row from L2 or the Infinity Cache.
+// All accesses are element-aligned 128-bit ones over the row's floor(N / VEC) full groups
+// plus a scalar tail, so any N and any base alignment take this one path.  Same arithmetic
+// as layernorm_row_kernel.  In-place safe: two barriers separate every read of passes one
+// and two from every write of pass three, where a thread reads a group before it overwrites it.
+// ---------------------------------------------------------------------------
+constexpr int kLnStreamBatch = 4;
+constexpr int kLnStreamMaxWaves = 16;
+
+// Calls fn(values, live) for every batch group of the row that thread t owns: VEC widened
+// values and whether the group exists (clamped loads, so that every load is unconditional).
+template <int DT, typename Fn>
+__device__ __forceinline__ void ln_stream_groups(const char* xr, int per_thread, int G, int t, int nfull,
+                                                 Fn&& fn) {
+  using S = Storage<DT>;
+  constexpr int VEC = S::kVec;
+  constexpr int U = kLnStreamBatch;
+  for (int k0 = 0; k0 < per_thread; k0 += U) {
+    u32x4 v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int idx = (k0 + u) * G + t;
+      v[u] = load_vec_unaligned<false>(xr + (int64_t)(idx < nfull ? idx : nfull - 1) * 16);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float f[VEC];
+      S::unpack(v[u], f);
+      fn(f, (k0 + u) * G + t);
+    }
+  }
+}
+
+template <int DT>
+__global__ void __launch_bounds__(kLnStreamMaxWaves * kLnWave)
+layernorm_stream_kernel(const void* x, const void* __restrict__ w, const void* __restrict__ b, void* y,
+                        int64_t M, int64_t N, float n, float eps) {
+  using S = Storage<DT>;
+  constexpr int VEC = S::kVec;
+  __shared__ float part_a[2][kLnStreamMaxWaves];
+  __shared__ float part_b[2][kLnStreamMaxWaves];
+  const int G = blockDim.x;
+  const int waves = G / kLnWave;
+  const int t = threadIdx.x;
+  const int lane = t & (kLnWave - 1);
+  const int wave = t / kLnWave;
+  const int nfull = (int)(N / VEC);
+  const int rem = (int)(N - (int64_t)nfull * VEC);
+  const int per_thread = (nfull + G - 1) / G;
+  const bool has_bias = b != nullptr;
+  const char* wb = static_cast<const char*>(w);
+  const char* bb = static_cast<const char*>(b);
+  const u32x4 zero = {0u, 0u, 0u, 0u};
+  int slot = 0;
+
+  for (int64_t row = blockIdx.x; row < M; row += gridDim.x) {
+    const char* xr = static_cast<const char*>(x) + row * N * S::kBytes;
+    char* yr = static_cast<char*>(y) + row * N * S::kBytes;
+    const float shift = S::load_one(x, row * N);      // the row's first element
+    const int64_t tail_col = (int64_t)nfull * VEC + t;
+    float tail = 0.f;
+    if (t < rem) tail = S::load_one(x, row * N + tail_col) - shift;
+
+    float acc[4] = {tail, 0.f, 0.f, 0.f};
+    ln_stream_groups<DT>(xr, per_thread, G, t, nfull, [&](const float (&f)[VEC], int idx) {
+      const bool live = idx < nfull;
+#pragma unroll
+      for (int k = 0; k < VEC; ++k) acc[k & 3] += live ? f[k] - shift : 0.f;
+    });
+    float s1 = wave_sum((acc[0] + acc[1]) + (acc[2] + acc[3]));
+    if (waves > 1) {
+      if (lane == 0) part_a[slot][wave] = s1;
+      __syncthreads();
+      s1 = part_a[slot][0];
+      for (int k = 1; k < waves; ++k) s1 += part_a[slot][k];
+    }
+    const float mean_shifted = s1 / n;
+
+    tail = t < rem ? tail - mean_shifted : 0.f;
+    float sq[4] = {tail * tail, 0.f, 0.f, 0.f};
+    ln_stream_groups<DT>(xr, per_thread, G, t, nfull, [&](const float (&f)[VEC], int idx) {
+      const bool live = idx < nfull;
+#pragma unroll
+      for (int k = 0; k < VEC; ++k) {
+        const float c = live ? (f[k] - shift) - mean_shifted : 0.f;
+        sq[k & 3] = __builtin_fmaf(c, c, sq[k & 3]);
+      }
+    });
+    float s2 = wave_sum((sq[0] + sq[1]) + (sq[2] + sq[3]));
+    if (waves > 1) {
+      if (lane == 0) part_b[slot][wave] = s2;
+      __syncthreads();
+      s2 = part_b[slot][0];
+      for (int k = 1; k < waves; ++k) s2 += part_b[slot][k];
+      slot ^= 1;
+    }
+    const float rstd = ln_rstd(s2, n, eps);
+
+    ln_stream_groups<DT>(xr, per_thread, G, t, nfull, [&](const float (&f)[VEC], int idx) {
+      if (idx < nfull) {
+        const int64_t off = (int64_t)idx * 16;
+        float c[VEC];
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) c[k] = (f[k] - shift) - mean_shifted;
+        const u32x4 wv = load_vec_unaligned<false>(wb + off);
+        const u32x4 bv = has_bias ? load_vec_unaligned<false>(bb + off) : zero;
+        store_vec_unaligned<true>(yr + off, ln_scale<DT>(c, wv, bv, has_bias, rstd));
+      }
+    });
+    if (t < rem) {
+      const float tq = (tail * rstd) * S::load_one(w, tail_col);
+      S::store_one(y, row * N + tail_col, has_bias ? tq + S::load_one(b, tail_col) : tq);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
 // Element-wise fallback: any alignment, any N; three passes (shifted sum, centred
 // squares, write).  In-place safe for the same reason as the other fallbacks.
 template <int DT, int T>

@@ -113,13 +113,15 @@ int pick_threads_unaligned(int64_t nfull) {
 
 int64_t full_groups_per_row(int64_t N, int dtype) { return N / (16 / elem_bytes(dtype)); }
 
+constexpr int64_t kStreamMaxN = (int64_t)1 << 31;   // the streaming kernel counts groups in an int
+
 int choose(const void* x, const void* w, const void* y, int64_t N, int dtype) {
   if (!rows_vectorisable(x, w, y, N, dtype)) {
-    return pick_threads_unaligned(full_groups_per_row(N, dtype)) ? RMSNORM_VARIANT_UNALIGNED
-                                                                  : RMSNORM_VARIANT_GENERIC;
+    if (pick_threads_unaligned(full_groups_per_row(N, dtype))) return RMSNORM_VARIANT_UNALIGNED;
+    return N < kStreamMaxN ? RMSNORM_VARIANT_STREAM : RMSNORM_VARIANT_GENERIC;
   }
   const int g = pick_threads(vectors_per_row(N, dtype), 8, dtype);
-  if (g == 0) return RMSNORM_VARIANT_GENERIC;
+  if (g == 0) return N < kStreamMaxN ? RMSNORM_VARIANT_STREAM : RMSNORM_VARIANT_GENERIC;
   if (g < 64) return RMSNORM_VARIANT_SUBWAVE;
   return g == 64 ? RMSNORM_VARIANT_WAVE : RMSNORM_VARIANT_BLOCK;
 }
@@ -172,6 +174,18 @@ void launch_row_unaligned(const Args& a, int nfull) {
   hipLaunchKernelGGL((rms::rmsnorm_row_unaligned_kernel<DT, CHUNKS, G, true>),
                      dim3((unsigned)blocks), dim3(G), 0, a.stream,
                      a.x, a.w, a.y, a.M, a.N, nfull, 1.0f / (float)a.N, a.eps);
+}
+
+// The two-pass streaming kernel: about one batch of four groups per thread, whole wavefronts,
+// at most 1024 threads (what every row long enough to need this kernel gets).
+template <int DT>
+void launch_stream(const Args& a) {
+  const int64_t blocks = a.M < kMaxGrid ? a.M : kMaxGrid;
+  const int64_t nfull = a.N / rms::Storage<DT>::kVec;
+  int64_t threads = (nfull / rms::kStreamBatch + rms::kWave - 1) / rms::kWave * rms::kWave;
+  threads = threads < rms::kWave ? rms::kWave : threads > kBlockMaxThreads ? kBlockMaxThreads : threads;
+  hipLaunchKernelGGL((rms::rmsnorm_stream_kernel<DT>), dim3((unsigned)blocks), dim3((unsigned)threads),
+                     0, a.stream, a.x, a.w, a.y, a.M, a.N, 1.0f / (float)a.N, a.eps);
 }
 
 template <int DT>
@@ -294,12 +308,14 @@ int dispatch_row_unaligned(const Args& a) {
   return RMSNORM_OK;
 }
 
-// threads == 0 means the element-wise kernel, threads == -1 the element-aligned row kernel.
+// threads == 0 means the element-wise kernel, -1 the element-aligned row kernel, -2 the
+// two-pass streaming kernel.
 template <int DT>
 int run_typed(const Args& a, int threads) {
   int rc = RMSNORM_OK;
   if (threads == 0) launch_generic<DT>(a);
   else if (threads == -1) rc = dispatch_row_unaligned<DT>(a);
+  else if (threads == -2) launch_stream<DT>(a);
   else rc = dispatch_row<DT>(a, threads);
   if (rc != RMSNORM_OK) return rc;
   return hipGetLastError() == hipSuccess ? RMSNORM_OK : RMSNORM_ERR_LAUNCH;
@@ -310,7 +326,7 @@ int run(const void* x, const void* w, void* y, int64_t M, int64_t N, float eps, 
         void* stream, int variant, int threads) {
   int rc = check_args(x, w, y, M, N, eps, dtype);
   if (rc != RMSNORM_OK) return rc;
-  if (variant < -1 || variant > RMSNORM_VARIANT_SUBWAVE) return RMSNORM_ERR_INVALID_ARG;
+  if (variant < -1 || variant > RMSNORM_VARIANT_STREAM) return RMSNORM_ERR_INVALID_ARG;
   if (variant == -1 && max_chunks_for(threads, dtype) == 0) return RMSNORM_ERR_INVALID_ARG;
   if (M == 0) return RMSNORM_OK;
 
@@ -337,6 +353,10 @@ int run(const void* x, const void* w, void* y, int64_t M, int64_t N, float eps, 
     case RMSNORM_VARIANT_UNALIGNED:
       if (pick_threads_unaligned(full_groups_per_row(N, dtype)) == 0) return RMSNORM_ERR_UNSUPPORTED;
       threads = -1;
+      break;
+    case RMSNORM_VARIANT_STREAM:
+      if (N >= kStreamMaxN) return RMSNORM_ERR_UNSUPPORTED;
+      threads = -2;
       break;
     default:
       threads = 0;

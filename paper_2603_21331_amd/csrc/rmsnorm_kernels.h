@@ -20,8 +20,10 @@
 //  * rmsnorm_row_unaligned_kernel    : the same, for rows that are not 16-byte
 //                                      aligned (element-aligned 128-bit accesses
 //                                      plus a scalar tail).
-//  * rmsnorm_generic_kernel          : element-wise two-pass fallback for rows
-//                                      too long for registers.
+//  * rmsnorm_stream_kernel           : rows too long for registers: two streaming
+//                                      passes, any N and alignment.
+//  * rmsnorm_generic_kernel          : element-wise two-pass kernel, kept as the
+//                                      plainest implementation to test against.
 //
 // All sums are fp32, in an order fixed by (kernel, shape) alone: no atomics,
 // so repeated runs give identical bits.
@@ -324,6 +326,93 @@ rmsnorm_row_unaligned_kernel(const void* x, const void* __restrict__ w, void* y,
       store_vec_unaligned<NT>(yr + (int64_t)last * kGroupBytes,
                               scale_vec<DT>(v[CHUNKS - 1], wv[CHUNKS - 1], rstd));
     if (tail_ok) S::store_one(y, row * N + tail_col, (tail_x * rstd) * tail_w);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Rows too long for registers: two streaming passes by one workgroup per row.  Pass one adds
+// the squares, four 16-byte groups requested at a time; pass two reads the row again (from
+// L2 or the Infinity Cache), scales it and writes y with streaming stores.  All accesses are
+// element-aligned 128-bit ones over the row's floor(N / VEC) full groups plus a scalar tail,
+// so any N and any base alignment take this one path.  In-place safe: the barrier of the
+// reduction separates every read of pass one from every write of pass two, and in pass two
+// a thread reads a group before it overwrites it.
+// ---------------------------------------------------------------------------
+constexpr int kStreamBatch = 4;
+constexpr int kStreamMaxWaves = 16;
+
+template <int DT>
+__global__ void __launch_bounds__(kStreamMaxWaves * kWave)
+rmsnorm_stream_kernel(const void* x, const void* __restrict__ w, void* y, int64_t M, int64_t N,
+                      float inv_n, float eps) {
+  using S = Storage<DT>;
+  constexpr int VEC = S::kVec;
+  constexpr int U = kStreamBatch;
+  __shared__ float partial[2][kStreamMaxWaves];
+  const int G = blockDim.x;
+  const int waves = G / kWave;
+  const int t = threadIdx.x;
+  const int lane = t & (kWave - 1);
+  const int wave = t / kWave;
+  const int nfull = (int)(N / VEC);
+  const int rem = (int)(N - (int64_t)nfull * VEC);
+  const int per_thread = (nfull + G - 1) / G;             // groups k * G + t, k < per_thread
+  const char* wb = static_cast<const char*>(w);
+  const u32x4 zero = {0u, 0u, 0u, 0u};
+  int slot = 0;
+
+  for (int64_t row = blockIdx.x; row < M; row += gridDim.x) {
+    const char* xr = static_cast<const char*>(x) + row * N * S::kBytes;
+    char* yr = static_cast<char*>(y) + row * N * S::kBytes;
+
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int k0 = 0; k0 < per_thread; k0 += U) {
+      u32x4 v[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {       // clamped, so that every load is unconditional
+        const int idx = (k0 + u) * G + t;
+        v[u] = load_vec_unaligned<false>(xr + (int64_t)(idx < nfull ? idx : nfull - 1) * 16);
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        if ((k0 + u) * G + t >= nfull) v[u] = zero;
+        float f[VEC];
+        S::unpack(v[u], f);
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) acc[k & 3] = __builtin_fmaf(f[k], f[k], acc[k & 3]);
+      }
+    }
+    float tail = 0.f;
+    if (t < rem) tail = S::load_one(x, row * N + (int64_t)nfull * VEC + t);
+    float total = wave_sum(__builtin_fmaf(tail, tail, (acc[0] + acc[1]) + (acc[2] + acc[3])));
+    if (waves > 1) {
+      if (lane == 0) partial[slot][wave] = total;
+      __syncthreads();
+      total = partial[slot][0];
+      for (int k = 1; k < waves; ++k) total += partial[slot][k];
+      slot ^= 1;
+    }
+    const float rstd = row_rstd(total, inv_n, eps);
+
+    for (int k0 = 0; k0 < per_thread; k0 += U) {
+      u32x4 v[U], wv[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int idx = (k0 + u) * G + t;
+        const int64_t off = (int64_t)(idx < nfull ? idx : nfull - 1) * 16;
+        v[u] = load_vec_unaligned<false>(xr + off);
+        wv[u] = load_vec_unaligned<false>(wb + off);
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int idx = (k0 + u) * G + t;
+        if (idx < nfull) store_vec_unaligned<true>(yr + (int64_t)idx * 16, scale_vec<DT>(v[u], wv[u], rstd));
+      }
+    }
+    if (t < rem) {
+      const int64_t col = (int64_t)nfull * VEC + t;
+      S::store_one(y, row * N + col, (tail * rstd) * S::load_one(w, col));
+    }
   }
 }
 

@@ -27,8 +27,9 @@ LAYERNORM_VARIANT_BLOCK = 2
 LAYERNORM_VARIANT_GENERIC = 3
 LAYERNORM_VARIANT_SUBWAVE = 4
 LAYERNORM_VARIANT_UNALIGNED = 5
+LAYERNORM_VARIANT_STREAM = 6
 
-VARIANT_NAMES = {0: "auto", 1: "wave", 2: "block", 3: "generic", 4: "subwave", 5: "unaligned"}
+VARIANT_NAMES = {0: "auto", 1: "wave", 2: "block", 3: "generic", 4: "subwave", 5: "unaligned", 6: "stream"}
 
 _lib = None
 

@@ -175,8 +175,9 @@ def test_dispatch_choice_is_visible_without_a_launch():
     assert sel(P + 2, P + 65536, P + 131072, 16, 1024, 1) == binding.RMSNORM_VARIANT_UNALIGNED
     assert sel(P, P + 65536, P + 131072, 16, 3, 0) == binding.RMSNORM_VARIANT_UNALIGNED
     assert sel(P, P + 65536, P + 131072, 16, 131079, 2) == binding.RMSNORM_VARIANT_UNALIGNED
-    assert sel(P, P + 65536, P + 131072, 16, 131081, 2) == binding.RMSNORM_VARIANT_GENERIC
-    assert sel(P, P + 65536, P + 131072, 16, 1 << 20, 2) == binding.RMSNORM_VARIANT_GENERIC
+    assert sel(P, P + 65536, P + 131072, 16, 131081, 2) == binding.RMSNORM_VARIANT_STREAM
+    assert sel(P, P + 65536, P + 131072, 16, 1 << 20, 2) == binding.RMSNORM_VARIANT_STREAM
+    assert sel(P, P + 65536, P + (1 << 33), 2, 1 << 31, 2) == binding.RMSNORM_VARIANT_GENERIC
     assert sel(P, P + 65536, P + 131072, 16, 0, 2) == binding.RMSNORM_ERR_INVALID_ARG
 
 

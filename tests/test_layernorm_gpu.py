@@ -14,7 +14,7 @@ pytestmark = pytest.mark.gpu
 
 DTYPES = [inputs.FP32, inputs.FP16, inputs.BF16]
 THREADS = (8, 16, 32, 64, 256, 512, 1024)
-MODES = (0, 1, 2, 3, 4, 5) + tuple(("threads", g) for g in THREADS)
+MODES = (0, 1, 2, 3, 4, 5, 6) + tuple(("threads", g) for g in THREADS)
 
 
 def mode_name(m):
@@ -68,7 +68,8 @@ def test_smoke_128x128(gpu_device, dtype):
 SWEEP = [("tiny", 70, 8), ("head_64", 1031, 64), ("dim_128", 4099, 128), ("dim_200", 333, 200),
          ("dim_512", 515, 512), ("ragged_1000", 301, 1000), ("dim_2048", 517, 2048),
          ("standard_4096", 1024, 4096), ("hidden_5120", 259, 5120), ("wide_8192", 259, 8192),
-         ("wide_16384", 67, 16384), ("limit_16bit", 9, 65536), ("past_limit", 5, 65544), ("tall", 8192, 1024)]
+         ("wide_16384", 67, 16384), ("limit_16bit", 9, 65536), ("past_limit", 5, 65544), ("long_131072", 5, 131072),
+         ("long_odd_262145", 3, 262145), ("tall", 8192, 1024)]
 
 
 @pytest.mark.parametrize("dtype", DTYPES)

@@ -28,6 +28,9 @@ SWEEP = [
     ("tall", 8192, 1024),
     ("wide_32768", 67, 32768),
     ("block_limit_fp32", 9, 65536),
+    ("block_limit_16bit", 5, 131072),
+    ("past_every_register_kernel", 5, 131080),
+    ("long_262144", 3, 262144),
 ]
 
 
