@@ -89,7 +89,7 @@ __device__ __forceinline__ void ce_batch(const u32x4* body, int k0, int G, int t
   ce_fold<COUNT * VEC>(f, m, s);
 }
 
-constexpr int kCeMaxWaves = 16;
+constexpr int kCeMaxWaves = kMaxPartials;
 
 // One row per workgroup of G = blockDim.x threads, G any multiple of 64 up to 1024 (the host
 // picks it so that the vectors of a row divide evenly among the threads).
@@ -100,8 +100,8 @@ crossentropy_row_kernel(const void* x, const int64_t* __restrict__ target, float
   using S = Storage<DT>;
   constexpr int VEC = S::kVec;
   static_assert(U == 4, "the remainder switch below covers 1..3 vectors");
-  __shared__ float part_m[2][kCeMaxWaves];
-  __shared__ float part_s[2][kCeMaxWaves];
+  __shared__ __attribute__((aligned(16))) float part_m[2][kCeMaxWaves];
+  __shared__ __attribute__((aligned(16))) float part_s[2][kCeMaxWaves];
   const int G = blockDim.x;
   const int waves = G / kCeWave;
   const int t = threadIdx.x;
@@ -142,17 +142,15 @@ crossentropy_row_kernel(const void* x, const int64_t* __restrict__ target, float
     // combine the per-thread pairs: row maximum, rescale, row sum
     float row_m = wave_max(m);
     if (waves > 1) {
-      if (lane == 0) part_m[slot][wave] = row_m;
+      park_partial(part_m[slot], lane, wave, waves, row_m, kCeNegInf);
       __syncthreads();
-      row_m = part_m[slot][0];
-      for (int w = 1; w < waves; ++w) row_m = __builtin_fmaxf(row_m, part_m[slot][w]);
+      row_m = max16(part_m[slot]);
     }
     float row_s = wave_sum(s * ce_rescale(m, row_m));
     if (waves > 1) {
-      if (lane == 0) part_s[slot][wave] = row_s;
+      park_partial(part_s[slot], lane, wave, waves, row_s, 0.0f);
       __syncthreads();
-      row_s = part_s[slot][0];
-      for (int w = 1; w < waves; ++w) row_s += part_s[slot][w];
+      row_s = sum16(part_s[slot]);
       slot ^= 1;
     }
 

@@ -74,8 +74,8 @@ layernorm_row_kernel(const u32x4* x, const u32x4* __restrict__ w, const u32x4* _
   using S = Storage<DT>;
   constexpr int VEC = S::kVec;
   constexpr int WAVES = G / kLnWave;
-  __shared__ float part_a[2][WAVES];
-  __shared__ float part_b[2][WAVES];
+  __shared__ __attribute__((aligned(16))) float part_a[2][WAVES];
+  __shared__ __attribute__((aligned(16))) float part_b[2][WAVES];
   const int t = threadIdx.x;
   const int lane = t & (kLnWave - 1);
   const int wave = t / kLnWave;
@@ -126,9 +126,7 @@ layernorm_row_kernel(const u32x4* x, const u32x4* __restrict__ w, const u32x4* _
     if constexpr (WAVES > 1) {
       if (lane == 0) part_a[slot][wave] = s1;
       __syncthreads();
-      s1 = part_a[slot][0];
-#pragma unroll
-      for (int k = 1; k < WAVES; ++k) s1 += part_a[slot][k];
+      s1 = sum_waves<WAVES>(part_a[slot]);
     }
     const float mean_shifted = s1 / n;
 
@@ -146,9 +144,7 @@ layernorm_row_kernel(const u32x4* x, const u32x4* __restrict__ w, const u32x4* _
     if constexpr (WAVES > 1) {
       if (lane == 0) part_b[slot][wave] = s2;
       __syncthreads();
-      s2 = part_b[slot][0];
-#pragma unroll
-      for (int k = 1; k < WAVES; ++k) s2 += part_b[slot][k];
+      s2 = sum_waves<WAVES>(part_b[slot]);
       slot ^= 1;
     }
     const float rstd = ln_rstd(s2, n, eps);
@@ -237,9 +233,7 @@ __device__ __forceinline__ void ln_resident_step(
   if constexpr (WAVES > 1) {
     if (lane == 0) part_a[wave] = s1;
     __syncthreads();
-    s1 = part_a[0];
-#pragma unroll
-    for (int k = 1; k < WAVES; ++k) s1 += part_a[k];
+    s1 = sum_waves<WAVES>(part_a);
   }
   const float mean_shifted = s1 * inv_n;
 
@@ -257,9 +251,7 @@ __device__ __forceinline__ void ln_resident_step(
   if constexpr (WAVES > 1) {
     if (lane == 0) part_b[wave] = s2;
     __syncthreads();
-    s2 = part_b[0];
-#pragma unroll
-    for (int k = 1; k < WAVES; ++k) s2 += part_b[k];
+    s2 = sum_waves<WAVES>(part_b);
   }
   const float rstd = ln_rstd_fast(s2, inv_n, eps);
 
@@ -281,8 +273,8 @@ layernorm_row_resident_kernel(const u32x4* x, const u32x4* __restrict__ w,
   using S = Storage<DT>;
   constexpr int VEC = S::kVec;
   constexpr int WAVES = G / kLnWave;
-  __shared__ float part_a[2][WAVES];
-  __shared__ float part_b[2][WAVES];
+  __shared__ __attribute__((aligned(16))) float part_a[2][WAVES];
+  __shared__ __attribute__((aligned(16))) float part_b[2][WAVES];
   const int t = threadIdx.x;
   const int lane = t & (kLnWave - 1);
   const int wave = t / kLnWave;
@@ -398,8 +390,8 @@ layernorm_row_unaligned_kernel(const void* x, const void* __restrict__ w, const 
   constexpr int VEC = S::kVec;
   constexpr int WAVES = G / kLnWave;
   constexpr int kGroupBytes = 16;
-  __shared__ float part_a[2][WAVES];
-  __shared__ float part_b[2][WAVES];
+  __shared__ __attribute__((aligned(16))) float part_a[2][WAVES];
+  __shared__ __attribute__((aligned(16))) float part_b[2][WAVES];
   const int t = threadIdx.x;
   const int lane = t & (kLnWave - 1);
   const int wave = t / kLnWave;
@@ -444,9 +436,7 @@ layernorm_row_unaligned_kernel(const void* x, const void* __restrict__ w, const 
     if constexpr (WAVES > 1) {
       if (lane == 0) part_a[slot][wave] = s1;
       __syncthreads();
-      s1 = part_a[slot][0];
-#pragma unroll
-      for (int k = 1; k < WAVES; ++k) s1 += part_a[slot][k];
+      s1 = sum_waves<WAVES>(part_a[slot]);
     }
     const float mean_shifted = s1 / n;
 
@@ -465,9 +455,7 @@ layernorm_row_unaligned_kernel(const void* x, const void* __restrict__ w, const 
     if constexpr (WAVES > 1) {
       if (lane == 0) part_b[slot][wave] = s2;
       __syncthreads();
-      s2 = part_b[slot][0];
-#pragma unroll
-      for (int k = 1; k < WAVES; ++k) s2 += part_b[slot][k];
+      s2 = sum_waves<WAVES>(part_b[slot]);
       slot ^= 1;
     }
     const float rstd = ln_rstd(s2, n, eps);
@@ -503,7 +491,7 @@ layernorm_row_unaligned_kernel(const void* x, const void* __restrict__ w, const 
 // and two from every write of pass three, where a thread reads a group before it overwrites it.
 // ---------------------------------------------------------------------------
 constexpr int kLnStreamBatch = 4;
-constexpr int kLnStreamMaxWaves = 16;
+constexpr int kLnStreamMaxWaves = kMaxPartials;
 
 // Calls fn(values, live) for every batch group of the row that thread t owns: VEC widened
 // values and whether the group exists (clamped loads, so that every load is unconditional).
@@ -535,8 +523,8 @@ layernorm_stream_kernel(const void* x, const void* __restrict__ w, const void* _
                         int64_t M, int64_t N, float n, float eps) {
   using S = Storage<DT>;
   constexpr int VEC = S::kVec;
-  __shared__ float part_a[2][kLnStreamMaxWaves];
-  __shared__ float part_b[2][kLnStreamMaxWaves];
+  __shared__ __attribute__((aligned(16))) float part_a[2][kLnStreamMaxWaves];
+  __shared__ __attribute__((aligned(16))) float part_b[2][kLnStreamMaxWaves];
   const int G = blockDim.x;
   const int waves = G / kLnWave;
   const int t = threadIdx.x;
@@ -567,10 +555,9 @@ layernorm_stream_kernel(const void* x, const void* __restrict__ w, const void* _
     });
     float s1 = wave_sum((acc[0] + acc[1]) + (acc[2] + acc[3]));
     if (waves > 1) {
-      if (lane == 0) part_a[slot][wave] = s1;
+      park_partial(part_a[slot], lane, wave, waves, s1, 0.0f);
       __syncthreads();
-      s1 = part_a[slot][0];
-      for (int k = 1; k < waves; ++k) s1 += part_a[slot][k];
+      s1 = sum16(part_a[slot]);
     }
     const float mean_shifted = s1 / n;
 
@@ -586,10 +573,9 @@ layernorm_stream_kernel(const void* x, const void* __restrict__ w, const void* _
     });
     float s2 = wave_sum((sq[0] + sq[1]) + (sq[2] + sq[3]));
     if (waves > 1) {
-      if (lane == 0) part_b[slot][wave] = s2;
+      park_partial(part_b[slot], lane, wave, waves, s2, 0.0f);
       __syncthreads();
-      s2 = part_b[slot][0];
-      for (int k = 1; k < waves; ++k) s2 += part_b[slot][k];
+      s2 = sum16(part_b[slot]);
       slot ^= 1;
     }
     const float rstd = ln_rstd(s2, n, eps);
@@ -621,8 +607,8 @@ layernorm_generic_kernel(const void* x, const void* __restrict__ w, const void* 
                          void* y, int64_t M, int64_t N, float n, float eps) {
   using S = Storage<DT>;
   constexpr int WAVES = T / kLnWave;
-  __shared__ float part_a[2][WAVES];
-  __shared__ float part_b[2][WAVES];
+  __shared__ __attribute__((aligned(16))) float part_a[2][WAVES];
+  __shared__ __attribute__((aligned(16))) float part_b[2][WAVES];
   const int tid = threadIdx.x;
   const int lane = tid & (kLnWave - 1);
   const int wave = tid / kLnWave;
@@ -637,9 +623,7 @@ layernorm_generic_kernel(const void* x, const void* __restrict__ w, const void* 
     float s1 = wave_sum(acc);
     if (lane == 0) part_a[slot][wave] = s1;
     __syncthreads();
-    s1 = part_a[slot][0];
-#pragma unroll
-    for (int k = 1; k < WAVES; ++k) s1 += part_a[slot][k];
+    s1 = sum_waves<WAVES>(part_a[slot]);
     const float mean_shifted = s1 / n;
 
     float sq = 0.f;
@@ -650,9 +634,7 @@ layernorm_generic_kernel(const void* x, const void* __restrict__ w, const void* 
     float s2 = wave_sum(sq);
     if (lane == 0) part_b[slot][wave] = s2;
     __syncthreads();
-    s2 = part_b[slot][0];
-#pragma unroll
-    for (int k = 1; k < WAVES; ++k) s2 += part_b[slot][k];
+    s2 = sum_waves<WAVES>(part_b[slot]);
     slot ^= 1;
     const float rstd = ln_rstd(s2, n, eps);
 

@@ -130,7 +130,7 @@ rmsnorm_row_kernel(const u32x4* x, const u32x4* w, u32x4* y,
   constexpr int W_WHEN = G == kWave ? (CHUNKS <= 16 ? kWithRow : kOneByOne)
                          : CHUNKS > 8 ? kOneByOne
                          : CHUNKS > 1 ? kAfterReduce : kWithRow;
-  __shared__ float partial[2][WAVES];
+  __shared__ __attribute__((aligned(16))) float partial[2][WAVES];
   const int t = threadIdx.x;
   const int lane = t & (kWave - 1);
   const int wave = t / kWave;
@@ -182,8 +182,7 @@ rmsnorm_row_kernel(const u32x4* x, const u32x4* w, u32x4* y,
         wv[CHUNKS - 1] = zero;
         if (last_ok) wv[CHUNKS - 1] = wp[last];
       }
-#pragma unroll
-      for (int k = 1; k < WAVES; ++k) total += partial[slot][k];
+      total = sum_waves<WAVES>(partial[slot]);
       slot ^= 1;
     }
     const float rstd = row_rstd(total, inv_n, eps);
@@ -272,7 +271,7 @@ rmsnorm_row_unaligned_kernel(const void* x, const void* __restrict__ w, void* y,
   constexpr int WAVES = G / kWave;
   constexpr int VEC = S::kVec;
   constexpr int kGroupBytes = 16;
-  __shared__ float partial[2][WAVES];
+  __shared__ __attribute__((aligned(16))) float partial[2][WAVES];
   const int t = threadIdx.x;
   const int lane = t & (kWave - 1);
   const int wave = t / kWave;
@@ -311,9 +310,7 @@ rmsnorm_row_unaligned_kernel(const void* x, const void* __restrict__ w, void* y,
     if constexpr (WAVES > 1) {
       if (lane == 0) partial[slot][wave] = total;
       __syncthreads();
-      total = partial[slot][0];
-#pragma unroll
-      for (int k = 1; k < WAVES; ++k) total += partial[slot][k];
+      total = sum_waves<WAVES>(partial[slot]);
       slot ^= 1;
     }
     const float rstd = row_rstd(total, inv_n, eps);
@@ -339,7 +336,7 @@ rmsnorm_row_unaligned_kernel(const void* x, const void* __restrict__ w, void* y,
 // a thread reads a group before it overwrites it.
 // ---------------------------------------------------------------------------
 constexpr int kStreamBatch = 4;
-constexpr int kStreamMaxWaves = 16;
+constexpr int kStreamMaxWaves = kMaxPartials;
 
 template <int DT>
 __global__ void __launch_bounds__(kStreamMaxWaves * kWave)
@@ -348,7 +345,7 @@ rmsnorm_stream_kernel(const void* x, const void* __restrict__ w, void* y, int64_
   using S = Storage<DT>;
   constexpr int VEC = S::kVec;
   constexpr int U = kStreamBatch;
-  __shared__ float partial[2][kStreamMaxWaves];
+  __shared__ __attribute__((aligned(16))) float partial[2][kStreamMaxWaves];
   const int G = blockDim.x;
   const int waves = G / kWave;
   const int t = threadIdx.x;
@@ -386,10 +383,9 @@ rmsnorm_stream_kernel(const void* x, const void* __restrict__ w, void* y, int64_
     if (t < rem) tail = S::load_one(x, row * N + (int64_t)nfull * VEC + t);
     float total = wave_sum(__builtin_fmaf(tail, tail, (acc[0] + acc[1]) + (acc[2] + acc[3])));
     if (waves > 1) {
-      if (lane == 0) partial[slot][wave] = total;
+      park_partial(partial[slot], lane, wave, waves, total, 0.0f);
       __syncthreads();
-      total = partial[slot][0];
-      for (int k = 1; k < waves; ++k) total += partial[slot][k];
+      total = sum16(partial[slot]);
       slot ^= 1;
     }
     const float rstd = row_rstd(total, inv_n, eps);
@@ -428,7 +424,7 @@ __global__ void __launch_bounds__(T)
 rmsnorm_generic_kernel(const void* x, const void* __restrict__ w, void* y,
                        int64_t M, int64_t N, float inv_n, float eps) {
   constexpr int WAVES = T / kWave;
-  __shared__ float partial[2][WAVES];
+  __shared__ __attribute__((aligned(16))) float partial[2][WAVES];
   const int tid = threadIdx.x;
   const int lane = tid & (kWave - 1);
   const int wave = tid / kWave;
@@ -444,9 +440,7 @@ rmsnorm_generic_kernel(const void* x, const void* __restrict__ w, void* y,
     const float wsum = wave_sum(acc);
     if (lane == 0) partial[slot][wave] = wsum;
     __syncthreads();
-    float total = partial[slot][0];
-#pragma unroll
-    for (int k = 1; k < WAVES; ++k) total += partial[slot][k];
+    float total = sum_waves<WAVES>(partial[slot]);
     slot ^= 1;
     const float rstd = row_rstd(total, inv_n, eps);
 

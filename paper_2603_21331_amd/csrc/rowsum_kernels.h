@@ -16,7 +16,7 @@
 namespace rms {
 
 constexpr int kRsWave = 64;
-constexpr int kRsMaxWaves = 16;
+constexpr int kRsMaxWaves = kMaxPartials;
 
 // Adds the elements of one vector to the running sums, position by position.
 template <int DT>
@@ -67,7 +67,7 @@ rowsum_row_kernel(const void* x, float* __restrict__ y, int64_t M, int64_t N) {
   using S = Storage<DT>;
   constexpr int VEC = S::kVec;
   static_assert(U == 4 || U == 8, "the remainder code below covers up to U - 1 vectors");
-  __shared__ float part[2][kRsMaxWaves];
+  __shared__ __attribute__((aligned(16))) float part[2][kRsMaxWaves];
   const int G = blockDim.x;
   const int waves = G / kRsWave;
   const int t = threadIdx.x;
@@ -106,10 +106,9 @@ rowsum_row_kernel(const void* x, float* __restrict__ y, int64_t M, int64_t N) {
 
     float total = wave_sum(rs_fold<VEC>(acc));
     if (waves > 1) {
-      if (lane == 0) part[slot][wave] = total;
+      park_partial(part[slot], lane, wave, waves, total, 0.0f);
       __syncthreads();
-      total = part[slot][0];
-      for (int w = 1; w < waves; ++w) total += part[slot][w];
+      total = sum16(part[slot]);
       slot ^= 1;
     }
     if (t == 0) y[row] = total;

@@ -77,8 +77,8 @@ softmax_row_kernel(const u32x4* x, u32x4* y, int64_t M, int nvec) {
   using S = Storage<DT>;
   constexpr int VEC = S::kVec;
   constexpr int WAVES = G / kWaveSize;
-  __shared__ float part_max[2][WAVES];
-  __shared__ float part_sum[2][WAVES];
+  __shared__ __attribute__((aligned(16))) float part_max[2][WAVES];
+  __shared__ __attribute__((aligned(16))) float part_sum[2][WAVES];
   const int t = threadIdx.x;
   const int lane = t & (kWaveSize - 1);
   const int wave = t / kWaveSize;
@@ -115,9 +115,7 @@ softmax_row_kernel(const u32x4* x, u32x4* y, int64_t M, int nvec) {
     if constexpr (WAVES > 1) {
       if (lane == 0) part_max[slot][wave] = m;
       __syncthreads();
-      m = part_max[slot][0];
-#pragma unroll
-      for (int k = 1; k < WAVES; ++k) m = __builtin_fmaxf(m, part_max[slot][k]);
+      m = max_waves<WAVES>(part_max[slot]);
     }
 
     float acc[4] = {0.f, 0.f, 0.f, 0.f};
@@ -133,9 +131,7 @@ softmax_row_kernel(const u32x4* x, u32x4* y, int64_t M, int nvec) {
     if constexpr (WAVES > 1) {
       if (lane == 0) part_sum[slot][wave] = s;
       __syncthreads();
-      s = part_sum[slot][0];
-#pragma unroll
-      for (int k = 1; k < WAVES; ++k) s += part_sum[slot][k];
+      s = sum_waves<WAVES>(part_sum[slot]);
       slot ^= 1;
     }
     const float inv = 1.0f / s;
@@ -223,8 +219,8 @@ softmax_row_unaligned_kernel(const void* x, void* y, int64_t M, int64_t N, int n
   constexpr int VEC = S::kVec;
   constexpr int WAVES = G / kWaveSize;
   constexpr int kGroupBytes = 16;
-  __shared__ float part_max[2][WAVES];
-  __shared__ float part_sum[2][WAVES];
+  __shared__ __attribute__((aligned(16))) float part_max[2][WAVES];
+  __shared__ __attribute__((aligned(16))) float part_sum[2][WAVES];
   const int t = threadIdx.x;
   const int lane = t & (kWaveSize - 1);
   const int wave = t / kWaveSize;
@@ -267,9 +263,7 @@ softmax_row_unaligned_kernel(const void* x, void* y, int64_t M, int64_t N, int n
     if constexpr (WAVES > 1) {
       if (lane == 0) part_max[slot][wave] = m;
       __syncthreads();
-      m = part_max[slot][0];
-#pragma unroll
-      for (int k = 1; k < WAVES; ++k) m = __builtin_fmaxf(m, part_max[slot][k]);
+      m = max_waves<WAVES>(part_max[slot]);
     }
 
     // a lane without a leftover element adds exactly 0 (its -inf gives exp(-inf) = 0, or
@@ -288,9 +282,7 @@ softmax_row_unaligned_kernel(const void* x, void* y, int64_t M, int64_t N, int n
     if constexpr (WAVES > 1) {
       if (lane == 0) part_sum[slot][wave] = s;
       __syncthreads();
-      s = part_sum[slot][0];
-#pragma unroll
-      for (int k = 1; k < WAVES; ++k) s += part_sum[slot][k];
+      s = sum_waves<WAVES>(part_sum[slot]);
       slot ^= 1;
     }
     const float inv = 1.0f / s;
@@ -321,7 +313,7 @@ softmax_row_unaligned_kernel(const void* x, void* y, int64_t M, int64_t N, int n
 // thread reads a group before it overwrites it.
 // ---------------------------------------------------------------------------
 constexpr int kStreamBatch = 4;
-constexpr int kStreamMaxWaves = 16;
+constexpr int kStreamMaxWaves = kMaxPartials;
 
 // 2^((a - b) log2 e) for a <= b, with equal arguments (two -inf included) giving exactly 1.
 __device__ __forceinline__ float sm_rescale(float a, float b) {
@@ -376,8 +368,8 @@ softmax_stream_kernel(const void* x, void* y, int64_t M, int64_t N) {
   using S = Storage<DT>;
   constexpr int VEC = S::kVec;
   constexpr int U = kStreamBatch;
-  __shared__ float part_max[2][kStreamMaxWaves];
-  __shared__ float part_sum[2][kStreamMaxWaves];
+  __shared__ __attribute__((aligned(16))) float part_max[2][kStreamMaxWaves];
+  __shared__ __attribute__((aligned(16))) float part_sum[2][kStreamMaxWaves];
   const int G = blockDim.x;
   const int waves = G / kWaveSize;
   const int t = threadIdx.x;
@@ -410,17 +402,15 @@ softmax_stream_kernel(const void* x, void* y, int64_t M, int64_t N) {
     }
     float row_m = wave_max(m);
     if (waves > 1) {
-      if (lane == 0) part_max[slot][wave] = row_m;
+      park_partial(part_max[slot], lane, wave, waves, row_m, kNegInf);
       __syncthreads();
-      row_m = part_max[slot][0];
-      for (int w = 1; w < waves; ++w) row_m = __builtin_fmaxf(row_m, part_max[slot][w]);
+      row_m = max16(part_max[slot]);
     }
     float row_s = wave_sum(s * sm_rescale(m, row_m));
     if (waves > 1) {
-      if (lane == 0) part_sum[slot][wave] = row_s;
+      park_partial(part_sum[slot], lane, wave, waves, row_s, 0.0f);
       __syncthreads();
-      row_s = part_sum[slot][0];
-      for (int w = 1; w < waves; ++w) row_s += part_sum[slot][w];
+      row_s = sum16(part_sum[slot]);
       slot ^= 1;
     }
     const float inv = 1.0f / row_s;
@@ -460,8 +450,8 @@ __global__ void __launch_bounds__(T)
 softmax_generic_kernel(const void* x, void* y, int64_t M, int64_t N) {
   using S = Storage<DT>;
   constexpr int WAVES = T / kWaveSize;
-  __shared__ float part_max[2][WAVES];
-  __shared__ float part_sum[2][WAVES];
+  __shared__ __attribute__((aligned(16))) float part_max[2][WAVES];
+  __shared__ __attribute__((aligned(16))) float part_sum[2][WAVES];
   const int tid = threadIdx.x;
   const int lane = tid & (kWaveSize - 1);
   const int wave = tid / kWaveSize;
@@ -474,18 +464,14 @@ softmax_generic_kernel(const void* x, void* y, int64_t M, int64_t N) {
     m = wave_max(m);
     if (lane == 0) part_max[slot][wave] = m;
     __syncthreads();
-    m = part_max[slot][0];
-#pragma unroll
-    for (int k = 1; k < WAVES; ++k) m = __builtin_fmaxf(m, part_max[slot][k]);
+    m = max_waves<WAVES>(part_max[slot]);
 
     float acc = 0.f;
     for (int64_t j = tid; j < N; j += T) acc += exp_neg<DT>(S::load_one(x, base + j) - m);
     float s = wave_sum(acc);
     if (lane == 0) part_sum[slot][wave] = s;
     __syncthreads();
-    s = part_sum[slot][0];
-#pragma unroll
-    for (int k = 1; k < WAVES; ++k) s += part_sum[slot][k];
+    s = sum_waves<WAVES>(part_sum[slot]);
     slot ^= 1;
     const float inv = 1.0f / s;
 

@@ -59,6 +59,68 @@ __device__ __forceinline__ float wave_max(float v) {
   return __builtin_fmaxf(__builtin_fmaxf(r0, r1), __builtin_fmaxf(r2, r3));
 }
 
+// ---------------------------------------------------------------------------
+// Per-wavefront partials parked in LDS and combined by every thread after a barrier.
+// The partials are read with 128-bit LDS loads, all issued before the first is used: a loop
+// that reads them one by one waits for each read in turn, which at 8 wavefronts costs a few
+// tenths of a microsecond on every row's critical path.
+//
+// Compile-time workgroup size: sum_waves / max_waves over exactly WAVES slots (the array
+// must be 16-byte aligned).  Run-time workgroup size: 16 slots; park_partial fills the slots
+// past `waves` with the identity before the barrier, and sum16 / max16 take all 16.
+// ---------------------------------------------------------------------------
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+template <int WAVES>
+__device__ __forceinline__ void read_partials(const float* part, float (&p)[WAVES]) {
+  if constexpr (WAVES % 4 == 0) {
+#pragma unroll
+    for (int q = 0; q < WAVES / 4; ++q) {
+      const f32x4 v = *reinterpret_cast<const f32x4*>(part + 4 * q);
+      p[4 * q] = v.x; p[4 * q + 1] = v.y; p[4 * q + 2] = v.z; p[4 * q + 3] = v.w;
+    }
+  } else {
+#pragma unroll
+    for (int k = 0; k < WAVES; ++k) p[k] = part[k];
+  }
+}
+
+template <int WAVES>
+__device__ __forceinline__ float sum_waves(const float* part) {      // in wave order
+  float p[WAVES];
+  read_partials<WAVES>(part, p);
+  float s = p[0];
+#pragma unroll
+  for (int k = 1; k < WAVES; ++k) s += p[k];
+  return s;
+}
+
+template <int WAVES>
+__device__ __forceinline__ float max_waves(const float* part) {
+  float p[WAVES];
+  read_partials<WAVES>(part, p);
+  float m = p[0];
+#pragma unroll
+  for (int k = 1; k < WAVES; ++k) m = __builtin_fmaxf(m, p[k]);
+  return m;
+}
+
+constexpr int kMaxPartials = 16;
+
+// Lane 0 of every wavefront parks its value; lanes waves .. 15 of wavefront 0 fill the unused
+// slots with `identity` (0 for a sum, -inf for a maximum).  Call before the barrier.
+__device__ __forceinline__ void park_partial(float* part, int lane, int wave, int waves, float v,
+                                             float identity) {
+  if (lane == 0) part[wave] = v;
+  else if (wave == 0 && lane >= waves && lane < kMaxPartials) part[lane] = identity;
+}
+
+__device__ __forceinline__ float sum16(const float* part) {          // in wave order
+  return sum_waves<kMaxPartials>(part);
+}
+
+__device__ __forceinline__ float max16(const float* part) { return max_waves<kMaxPartials>(part); }
+
 template <int L>
 __device__ __forceinline__ float subwave_max(float v) {
   static_assert(L == 8 || L == 16 || L == 32, "group size");
