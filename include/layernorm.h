@@ -93,7 +93,7 @@ int layernorm_fwd_tuned(const void* x, const void* w, const void* b, void* y, in
                         int64_t N, float eps, int dtype, void* stream, int threads_per_row);
 
 /* threads_per_row of the automatic path for 16-byte aligned rows of N elements; 0 if
- * such rows go to the element-wise kernel; a negative layernorm_status for bad arguments. */
+ * such rows do not fit in registers (they take the streaming kernel); a negative layernorm_status for bad arguments. */
 int layernorm_auto_threads_per_row(int64_t N, int dtype);
 
 /* Largest N the register-resident kernels accept for `dtype`; 0 for a bad dtype. */

@@ -25,8 +25,8 @@
  *    start is 16-byte aligned (16-byte aligned bases and N * sizeof(dtype) a
  *    multiple of 16) take the aligned kernels; other rows take the same
  *    register-resident kernel with element-aligned 128-bit accesses; rows too
- *    long for registers take a slower element-wise kernel that reads x twice.
- *    None of these is an error.
+ *    long for registers stream through a two-pass kernel that reads x a second
+ *    time from cache.  None of these is an error.
  *  - y == x (exactly in place) is allowed; any other overlap of y with x or w
  *    is undefined.
  *  - Calls return RMSNORM_OK or a negative rmsnorm_status; nothing throws or
@@ -118,8 +118,8 @@ int rmsnorm_fwd_tuned(const void* x, const void* w, void* y, int64_t M, int64_t 
 
 /*
  * The threads_per_row that RMSNORM_VARIANT_AUTO uses for 16-byte aligned rows
- * of N elements: 0 if such rows go to the element-wise kernel, a negative
- * rmsnorm_status for a bad dtype or N <= 0.
+ * of N elements: 0 if such rows do not fit in registers (they take the
+ * streaming kernel), a negative rmsnorm_status for a bad dtype or N <= 0.
  */
 int rmsnorm_auto_threads_per_row(int64_t N, int dtype);
 

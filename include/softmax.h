@@ -85,7 +85,7 @@ int softmax_fwd_tuned(const void* x, void* y, int64_t M, int64_t N, int dtype, v
                       int threads_per_row);
 
 /* threads_per_row of the automatic path for 16-byte aligned rows of N elements; 0 if
- * such rows go to the element-wise kernel; a negative softmax_status for bad arguments. */
+ * such rows do not fit in registers (they take the streaming kernel); a negative softmax_status for bad arguments. */
 int softmax_auto_threads_per_row(int64_t N, int dtype);
 
 /* Largest N the register-resident kernels accept for `dtype`; 0 for a bad dtype. */
