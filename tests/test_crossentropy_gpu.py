@@ -88,6 +88,12 @@ def test_paper_result_shape_fp16_4096x32000(gpu_device):
     H.say(f"cross-entropy 4096x32000 stats {stats}")
 
 
+def test_benchmark_shape_fp16_8192x32000(gpu_device):
+    """The shape bench.py --op crossentropy times, in its launch configuration (automatic)."""
+    stats = check(inputs.crossentropy_paper_shape(1), gpu_device, modes=(0,))
+    H.say(f"cross-entropy 8192x32000 stats {stats}")
+
+
 # stage 3: stability
 @pytest.mark.parametrize("dtype", DTYPES)
 def test_rows_of_large_identical_values(gpu_device, dtype):
