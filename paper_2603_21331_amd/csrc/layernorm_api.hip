@@ -66,7 +66,7 @@ bool threads_can(int threads, int64_t nvec) {
 }
 
 // Threads per row of the automatic path, from sweeps on the GPU: lane groups for rows up to
-// 32 vectors, one wavefront up to 256 vectors; then the smallest workgroup in which a
+// 64 vectors, one wavefront up to 256 vectors; then the smallest workgroup in which a
 // thread holds at most 24 elements of a 16-bit type or 16 of fp32 (three or four chunks),
 // which runs the resident kernel; rows too long for that (beyond 3072 vectors of a 16-bit
 // type, 4096 of fp32) take the smallest workgroup that holds them in at most 8 chunks per
@@ -75,9 +75,16 @@ constexpr int kResidentMaxElems = 24;    // elements per thread the resident ker
 constexpr int kResidentAutoElems32 = 16; // what the automatic path asks of it for fp32
 
 int pick_threads(int64_t nvec, int min_threads, int dtype) {
-  if (min_threads <= 8)
-    for (int l = 8; l <= 32; l *= 2)
-      if (nvec <= l) return l;
+  if (min_threads <= 8) {
+    if (nvec <= 8) return 8;
+    if (nvec <= 16) return 16;
+    // Two chunks per lane beat twice the lanes with one chunk each (3 to 20 %, most where the
+    // row does not fill the wider group).
+    // In fp32 a lane holds half as many elements and the exact fits keep one chunk.
+    const bool fp32 = dtype == LAYERNORM_DTYPE_FP32;
+    if (nvec <= 32) return (fp32 && nvec == 32) ? 32 : 16;
+    if (nvec <= 64) return (fp32 && nvec == 64) ? 64 : 32;
+  }
   if (min_threads <= 64 && nvec <= kSmallRowVectors) return 64;
   const int vec = 16 / elem_bytes(dtype);
   const int limit = dtype == LAYERNORM_DTYPE_FP32 ? kResidentAutoElems32 : kResidentMaxElems;
@@ -128,10 +135,14 @@ template <int DT, int CHUNKS, int G>
 void launch_row(const Args& a) {
   const int64_t blocks = a.M < kMaxGrid ? a.M : kMaxGrid;
   // Rows of at most 24 elements per thread: resident workgroups, weight and bias in registers.
-  // Eight wavefronts per compute unit (sixteen for 1024 threads, which cannot be fewer)
-  // measured best on MI355X at every shape tried; twice as many are 4 to 8 % slower.
+  // Each workgroup has one row requested ahead, so the workgroups on a compute unit decide
+  // how many bytes it has in flight; about 24 KiB measured best on MI355X.  Rows of 10 KiB
+  // and more: eight wavefronts per compute unit (sixteen for 1024 threads, which cannot be
+  // fewer; twice as many are 4 to 8 % slower).  Shorter rows need more workgroups: three at
+  // 8 KiB (1 % faster than two), four at 6 KiB and below (10 to 15 % faster).
   if constexpr (CHUNKS * rms::Storage<DT>::kVec <= kResidentMaxElems && G >= 256) {
-    int64_t grid = (int64_t)compute_units() * (G == 256 ? 2 : 1);
+    const int per_cu = G != 256 ? 1 : a.nvec <= 384 ? 4 : a.nvec <= 512 ? 3 : 2;
+    int64_t grid = (int64_t)compute_units() * per_cu;
     if (grid > a.M) grid = a.M;
     hipLaunchKernelGGL((rms::layernorm_row_resident_kernel<DT, CHUNKS, G, true>), dim3((unsigned)grid),
                        dim3(G), 0, a.stream, (const u32x4*)a.x, (const u32x4*)a.w,

@@ -115,10 +115,11 @@ layernorm_row_kernel(const u32x4* x, const u32x4* __restrict__ w, const u32x4* _
 #pragma unroll
     for (int c = 0; c < CHUNKS; ++c) {
       S::unpack(v[c], f[c]);
-      const bool live = c < CHUNKS - 1 || last_ok;
+      // a chunk past the end of the row holds zeros; subtracting zero keeps it at zero
+      const float sub = (c < CHUNKS - 1 || last_ok) ? shift : 0.f;
 #pragma unroll
       for (int k = 0; k < VEC; ++k) {
-        f[c][k] = live ? f[c][k] - shift : 0.f;
+        f[c][k] -= sub;
         acc[k & 3] += f[c][k];
       }
     }
@@ -133,10 +134,10 @@ layernorm_row_kernel(const u32x4* x, const u32x4* __restrict__ w, const u32x4* _
     float sq[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int c = 0; c < CHUNKS; ++c) {
-      const bool live = c < CHUNKS - 1 || last_ok;
+      const float sub = (c < CHUNKS - 1 || last_ok) ? mean_shifted : 0.f;
 #pragma unroll
       for (int k = 0; k < VEC; ++k) {
-        f[c][k] = live ? f[c][k] - mean_shifted : 0.f;
+        f[c][k] -= sub;
         sq[k & 3] = __builtin_fmaf(f[c][k], f[c][k], sq[k & 3]);
       }
     }
@@ -336,16 +337,27 @@ layernorm_subwave_kernel(const u32x4* x, const u32x4* __restrict__ w, const u32x
     u32x4* yr = y + row * nvec;
     const float shift = S::load_one(xr, 0);
 
-    float f[CHUNKS][VEC];
-    float acc = 0.f;
+    // Weight and bias are requested with the row (at most 16 more registers), so that
+    // nothing is left to wait for between the second reduction and the stores.
+    u32x4 v[CHUNKS], wv[CHUNKS], bv[CHUNKS];
 #pragma unroll
     for (int c = 0; c < CHUNKS; ++c) {
       const int idx = c * L + sub;
       const bool live = idx < nvec;
-      S::unpack(live ? load_vec<NT>(xr + idx) : zero, f[c]);
+      v[c] = live ? load_vec<NT>(xr + idx) : zero;
+      wv[c] = live ? w[idx] : zero;
+      bv[c] = (live && has_bias) ? b[idx] : zero;
+    }
+    float f[CHUNKS][VEC];
+    float acc = 0.f;
+#pragma unroll
+    for (int c = 0; c < CHUNKS; ++c) {
+      // lanes past the end of the row hold zeros; subtracting zero keeps them at zero
+      const float off = c * L + sub < nvec ? shift : 0.f;
+      S::unpack(v[c], f[c]);
 #pragma unroll
       for (int k = 0; k < VEC; ++k) {
-        f[c][k] = live ? f[c][k] - shift : 0.f;
+        f[c][k] -= off;
         acc += f[c][k];
       }
     }
@@ -353,10 +365,10 @@ layernorm_subwave_kernel(const u32x4* x, const u32x4* __restrict__ w, const u32x
     float sq = 0.f;
 #pragma unroll
     for (int c = 0; c < CHUNKS; ++c) {
-      const bool live = c * L + sub < nvec;
+      const float off = c * L + sub < nvec ? mean_shifted : 0.f;
 #pragma unroll
       for (int k = 0; k < VEC; ++k) {
-        f[c][k] = live ? f[c][k] - mean_shifted : 0.f;
+        f[c][k] -= off;
         sq = __builtin_fmaf(f[c][k], f[c][k], sq);
       }
     }
@@ -364,11 +376,7 @@ layernorm_subwave_kernel(const u32x4* x, const u32x4* __restrict__ w, const u32x
 #pragma unroll
     for (int c = 0; c < CHUNKS; ++c) {
       const int idx = c * L + sub;
-      if (row_ok && idx < nvec) {
-        const u32x4 wv = w[idx];
-        const u32x4 bv = has_bias ? b[idx] : zero;
-        store_vec<NT>(yr + idx, ln_scale<DT>(f[c], wv, bv, has_bias, rstd));
-      }
+      if (row_ok && idx < nvec) store_vec<NT>(yr + idx, ln_scale<DT>(f[c], wv[c], bv[c], has_bias, rstd));
     }
   }
 }

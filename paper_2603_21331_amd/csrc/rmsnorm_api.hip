@@ -81,19 +81,24 @@ bool wave_can(int64_t nvec, int dtype) { return threads_can(64, nvec, dtype); }
 // N = 128 .. 131072 in all three dtypes, each timed in a sustained run (the
 // first milliseconds after idle run in a clock transient): rows of up to 256
 // vectors (4 KiB) run fastest with one wavefront per row; up to 704 vectors with
-// 256 threads; up to 2560 with 512 (at 1024 vectors, the headline row, two
+// 256 threads; up to 2048 with 512 (at 1024 vectors, the headline row, two
 // chunks per thread beat four by 2 %); longer rows with 1024.  Within those
-// bands the neighbouring choices are within about 2 % of each other.
+// bands the neighbouring choices are within about 2 % of each other, with one
+// exception: a row of exactly 256 or 512 vectors (N = 2048 and 4096 in the
+// 16-bit types) runs 2 to 3 % faster with one vector per thread, the whole row
+// in one predicate-free load per wavefront, than with fewer threads.
 // min_threads > 64 restricts the choice to the workgroup-per-row kernels.
 // Returns 0 if the row does not fit in registers at all.
 constexpr int64_t kMax256Vectors = 704;
-constexpr int64_t kMax512Vectors = 2560;
+constexpr int64_t kMax512Vectors = 2048;
 
 int pick_threads(int64_t nvec, int min_threads, int dtype) {
   if (min_threads <= 8) {
     for (int l = 8; l <= 32; l *= 2)
       if (nvec <= l) return l;
+    if (nvec <= 40) return 32;   // two chunks in 32 lanes: 4 % faster than 64 lanes, 3/8 of them idle
   }
+  if ((nvec == 256 && min_threads <= 256) || (nvec == 512 && min_threads <= 512)) return (int)nvec;
   if (min_threads <= 64 && nvec <= kSmallRowVectors && threads_can(64, nvec, dtype)) return 64;
   if (nvec <= kMax256Vectors && min_threads <= 256 && threads_can(256, nvec, dtype)) return 256;
   if (nvec <= kMax512Vectors && min_threads <= 512 && threads_can(512, nvec, dtype)) return 512;

@@ -204,6 +204,18 @@ def random_case(seed: int, stream: int, M: int, N: int, dtype: int, eps: float =
                 w=normal_matrix(seed, stream + 1, 1, N, dtype, 1.0, 0.1)[0])
 
 
+RMSNORM_PAPER_SHAPES = ((4096, 4096), (8192, 4096), (8192, 8192))
+
+
+def rmsnorm_paper_shape(which: int, seed: int = 0):
+    """FP16 4096 x 4096, 8192 x 4096 or 8192 x 8192 (which = 0, 1, 2): the three RMSNorm rows
+    of the paper's table "Kernel performance on H100"; x ~ N(0,1), w ~ N(1,0.1), eps 1e-6."""
+    M, N = RMSNORM_PAPER_SHAPES[which]
+    case = random_case(seed, 160 + 4 * which, M, N, FP16)
+    case["name"] = f"paper_fp16_{M}x{N}"
+    return case
+
+
 def algorithmic_bytes(M: int, N: int, dtype: int) -> int:
     """HBM bytes one launch must move: read x once, write y once, read w once.
 

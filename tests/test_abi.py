@@ -136,8 +136,9 @@ def test_automatic_threads_per_row():
     auto = binding.rmsnorm_auto_threads_per_row
     bf16, fp16, fp32 = binding.RMSNORM_DTYPE_BF16, binding.RMSNORM_DTYPE_FP16, binding.RMSNORM_DTYPE_FP32
     assert auto(8192, bf16) == 512          # headline shape: 2 chunks per thread
-    assert auto(4096, bf16) == 256
-    assert auto(2048, bf16) == 64
+    assert auto(4096, bf16) == 512          # exactly one vector per thread
+    assert auto(4104, bf16) == 256 and auto(4088, bf16) == 256
+    assert auto(2048, bf16) == 256 and auto(2040, bf16) == 64 and auto(2056, bf16) == 256
     assert auto(512, bf16) == 64
     assert auto(256, bf16) == 32
     assert auto(128, bf16) == 16
@@ -145,13 +146,13 @@ def test_automatic_threads_per_row():
     assert auto(8, fp16) == 8
     assert auto(128, fp32) == 32
     assert auto(200, bf16) == 32
-    assert auto(1024, fp32) == 64
+    assert auto(1024, fp32) == 256 and auto(2048, fp32) == 512 and auto(1020, fp32) == 64
     assert auto(768, fp16) == 64
     assert auto(5120, fp16) == 256
     assert auto(5632, fp16) == 256 and auto(5640, fp16) == 512
     assert auto(13824, fp16) == 512
     assert auto(8192, fp32) == 512
-    assert auto(20480, bf16) == 512 and auto(20488, bf16) == 1024
+    assert auto(16384, bf16) == 512 and auto(16392, bf16) == 1024
     assert auto(32768, bf16) == 1024
     assert auto(65536, fp16) == 1024
     assert auto(131072, bf16) == 1024
@@ -169,7 +170,7 @@ def test_dispatch_choice_is_visible_without_a_launch():
     assert sel(P, P + 65536, P + 131072, 16, 8192, 2) == binding.RMSNORM_VARIANT_BLOCK
     assert sel(P, P + 65536, P + 131072, 16, 768, 1) == binding.RMSNORM_VARIANT_WAVE
     assert sel(P, P + 65536, P + 131072, 16, 13824, 1) == binding.RMSNORM_VARIANT_BLOCK
-    assert sel(P, P + 65536, P + 131072, 16, 2048, 2) == binding.RMSNORM_VARIANT_WAVE
+    assert sel(P, P + 65536, P + 131072, 16, 2040, 2) == binding.RMSNORM_VARIANT_WAVE
     assert sel(P, P + 65536, P + 131072, 16, 128, 2) == binding.RMSNORM_VARIANT_SUBWAVE
     assert sel(P, P + 65536, P + 131072, 16, 1023, 1) == binding.RMSNORM_VARIANT_UNALIGNED
     assert sel(P + 2, P + 65536, P + 131072, 16, 1024, 1) == binding.RMSNORM_VARIANT_UNALIGNED

@@ -63,7 +63,10 @@ def test_empty_batch_unknown_variant_and_unsupported_shapes():
 
 def test_automatic_threads_per_row():
     auto = layernorm.layernorm_auto_threads_per_row
-    assert auto(64, 1) == 8 and auto(128, 2) == 16 and auto(256, 1) == 32 and auto(512, 1) == 64
+    assert auto(64, 1) == 8 and auto(128, 2) == 16 and auto(256, 1) == 16 and auto(512, 1) == 32
+    assert auto(264, 1) == 32 and auto(520, 2) == 64
+    assert auto(32, 0) == 8 and auto(64, 0) == 16 and auto(96, 0) == 16 and auto(128, 0) == 32
+    assert auto(192, 0) == 32 and auto(256, 0) == 64
     # past one wavefront: the smallest workgroup whose threads hold at most 24 elements of a
     # 16-bit type (16 of fp32), which runs the resident kernel ...
     assert auto(2048, 2) == 64 and auto(4096, 1) == 256 and auto(5120, 1) == 256 and auto(6144, 2) == 256

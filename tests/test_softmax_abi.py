@@ -69,7 +69,10 @@ def test_empty_batch_unknown_variant_and_unsupported_shapes():
 def test_automatic_threads_per_row():
     auto = softmax.softmax_auto_threads_per_row
     assert auto(64, 1) == 8 and auto(128, 2) == 16 and auto(256, 1) == 32 and auto(512, 1) == 64
-    assert auto(2048, 2) == 64 and auto(4096, 1) == 256 and auto(8192, 1) == 256
+    assert auto(192, 1) == 16 and auto(200, 1) == 32 and auto(384, 2) == 32 and auto(392, 2) == 64
+    assert auto(96, 0) == 16 and auto(100, 0) == 32 and auto(192, 0) == 32 and auto(196, 0) == 64
+    assert auto(2048, 2) == 64 and auto(4096, 1) == 256 and auto(5632, 1) == 256
+    assert auto(5640, 1) == 512 and auto(8192, 1) == 512 and auto(8200, 1) == 256 and auto(4096, 0) == 512
     assert auto(16384, 2) == 256 and auto(32768, 1) == 512 and auto(65536, 2) == 1024
     assert auto(65544, 2) == 0 and auto(1023, 1) == 0
     assert auto(8192, 0) == 256 and auto(32768, 0) == 1024 and auto(32772, 0) == 0
