@@ -43,6 +43,9 @@ typedef enum {
   CROSSENTROPY_OK = 0,
   CROSSENTROPY_ERR_INVALID_ARG = -1, /* null x/target/loss, M < 0, N <= 0 or >= 2^32, bad dtype,
                                         misaligned pointer, bad threads_per_row */
+  CROSSENTROPY_ERR_UNSUPPORTED = -2, /* a forced lane-group size (8, 16, 32) on rows that are not
+                                        16-byte aligned or longer than 8 vectors per lane, or
+                                        one lane per row with N > 64; nothing was launched */
   CROSSENTROPY_ERR_LAUNCH = -3       /* the HIP runtime refused the launch */
 } crossentropy_status;
 
@@ -60,12 +63,18 @@ int crossentropy_fwd(const void* x, const int64_t* target, float* loss, float* l
                      int64_t N, int dtype, void* stream);
 
 /* Same, with the number of threads that share one row forced: a multiple of 64 from 64 to
- * 1024 (any other value is CROSSENTROPY_ERR_INVALID_ARG).  Every count runs every shape. */
+ * 1024 (one workgroup per row; every such count runs every shape), or 8, 16 or 32 (lane
+ * groups, several rows per wavefront: x 16-byte aligned, N * sizeof(dtype) a multiple of 16 and
+ * at most 128 bytes per lane, otherwise CROSSENTROPY_ERR_UNSUPPORTED), or 1 (one lane per row:
+ * any alignment, N <= 64, otherwise CROSSENTROPY_ERR_UNSUPPORTED).  Any other value is
+ * CROSSENTROPY_ERR_INVALID_ARG. */
 int crossentropy_fwd_tuned(const void* x, const int64_t* target, float* loss, float* lse,
                            int64_t M, int64_t N, int dtype, void* stream, int threads_per_row);
 
-/* threads_per_row of the automatic path for rows of N classes; a negative
- * crossentropy_status for a bad dtype or N <= 0. */
+/* threads_per_row of the automatic path for rows of N classes whose base is 16-byte aligned:
+ * 1 for rows shorter than 128 bytes (whatever the alignment), lane groups for rows of whole
+ * 16-byte vectors up to 4 KiB (2 KiB for fp32; an unaligned base takes 64 threads instead);
+ * a negative crossentropy_status for a bad dtype or N <= 0. */
 int crossentropy_auto_threads_per_row(int64_t N, int dtype);
 
 /* Static, human-readable text for a status code. */

@@ -17,6 +17,7 @@ CROSSENTROPY_DTYPE_BF16 = 2
 
 CROSSENTROPY_OK = 0
 CROSSENTROPY_ERR_INVALID_ARG = -1
+CROSSENTROPY_ERR_UNSUPPORTED = -2
 CROSSENTROPY_ERR_LAUNCH = -3
 
 _lib = None

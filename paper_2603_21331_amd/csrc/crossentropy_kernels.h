@@ -166,4 +166,83 @@ crossentropy_row_kernel(const void* x, const int64_t* __restrict__ target, float
   }
 }
 
+// Few classes (16-byte aligned rows of at most 8 * L vectors: a 1000-way classifier, a
+// 128-way head): one workgroup per row would leave most of a wavefront idle and pay a launch
+// slot per kilobyte, so L = 8, 16 or 32 lanes share a row and a wavefront takes 64 / L
+// consecutive rows.  Same batches, same online pair per lane; the combination stays inside
+// the lane group (DPP, one swizzle for L = 32), so there is no LDS and no barrier.  Lanes
+// whose row lies past M work on the last row and store nothing, so the cross-lane steps
+// always see 64 active lanes and every load stays inside x.
+template <int DT, int L, int U, bool NT>
+__global__ void __launch_bounds__(kCeWave)
+crossentropy_subwave_kernel(const u32x4* x, const int64_t* __restrict__ target,
+                            float* __restrict__ loss, float* __restrict__ lse_out, int64_t M,
+                            int64_t N, int nvec) {
+  using S = Storage<DT>;
+  static_assert(U == 4, "the remainder switch below covers 1..3 vectors");
+  constexpr int ROWS = kCeWave / L;
+  const int lane = threadIdx.x;
+  const int sub = lane % L;
+  const int r = lane / L;
+  const int per_lane = (nvec + L - 1) / L;                // at most 8; the same for every lane
+  for (int64_t base = (int64_t)blockIdx.x * ROWS; base < M; base += (int64_t)gridDim.x * ROWS) {
+    const int64_t row = base + r;
+    const bool row_ok = row < M;
+    const u32x4* xr = x + (row_ok ? row : M - 1) * nvec;
+    float m = kCeNegInf, s = 0.f;
+    int k = 0;
+    for (; k + U <= per_lane; k += U) ce_batch<DT, U, NT>(xr, k, L, sub, nvec, m, s);
+    switch (per_lane - k) {
+      case 1: ce_batch<DT, 1, NT>(xr, k, L, sub, nvec, m, s); break;
+      case 2: ce_batch<DT, 2, NT>(xr, k, L, sub, nvec, m, s); break;
+      case 3: ce_batch<DT, 3, NT>(xr, k, L, sub, nvec, m, s); break;
+      default: break;
+    }
+    const float row_m = subwave_max<L>(m);
+    const float row_s = subwave_sum<L>(s * ce_rescale(m, row_m));
+    if (row_ok && sub == 0) {
+      const float log_s = row_m == kCeNegInf ? __builtin_nanf("") : __builtin_logf(row_s);
+      if (lse_out) lse_out[row] = row_m + log_s;
+      const int64_t cls = target[row];
+      float out = 0.0f;                                   // target outside [0, N): ignored row
+      if (cls >= 0 && cls < N) out = log_s - (S::load_one(x, row * N + cls) - row_m);
+      loss[row] = out;
+    }
+  }
+}
+
+// A handful of classes (rows shorter than 128 bytes, any alignment: a 10-way classifier): one
+// row per lane.  Neighbouring lanes read neighbouring rows, so a wavefront's loads still fall
+// into a few contiguous cache lines; the lane folds its row four logits at a time into the same
+// online pair, and nothing crosses lanes.
+constexpr int kCeLaneThreads = 256;
+
+template <int DT>
+__global__ void __launch_bounds__(kCeLaneThreads)
+crossentropy_lane_kernel(const void* x, const int64_t* __restrict__ target, float* __restrict__ loss,
+                         float* __restrict__ lse_out, int64_t M, int N) {
+  using S = Storage<DT>;
+  for (int64_t row = (int64_t)blockIdx.x * kCeLaneThreads + threadIdx.x; row < M;
+       row += (int64_t)gridDim.x * kCeLaneThreads) {
+    const int64_t at = row * N;
+    float m = kCeNegInf, s = 0.f;
+    int j = 0;
+    for (; j + 4 <= N; j += 4) {
+      const float f[4] = {S::load_one(x, at + j), S::load_one(x, at + j + 1),
+                          S::load_one(x, at + j + 2), S::load_one(x, at + j + 3)};
+      ce_fold<4>(f, m, s);
+    }
+    for (; j < N; ++j) {
+      const float f[1] = {S::load_one(x, at + j)};
+      ce_fold<1>(f, m, s);
+    }
+    const float log_s = m == kCeNegInf ? __builtin_nanf("") : __builtin_logf(s);
+    if (lse_out) lse_out[row] = m + log_s;
+    const int64_t cls = target[row];
+    float out = 0.0f;                                     // target outside [0, N): ignored row
+    if (cls >= 0 && cls < N) out = log_s - (S::load_one(x, at + cls) - m);
+    loss[row] = out;
+  }
+}
+
 }  // namespace rms

@@ -48,18 +48,43 @@ def test_empty_batch_and_bad_thread_counts():
     lib = ce.load()
     assert lib.crossentropy_fwd(None, None, None, None, 0, 16, 2, None) == ce.CROSSENTROPY_OK
     assert lib.crossentropy_fwd_tuned(None, None, None, None, 0, 16, 2, None, 64) == ce.CROSSENTROPY_OK
-    for bad in (0, 1, 32, 100, 1088, 2048, -64):
+    for bad in (0, 2, 4, 24, 48, 100, 1088, 2048, -64, -1):
         assert lib.crossentropy_fwd_tuned(P, P + BIG, P + 2 * BIG, None, 4, 4096, 2, None, bad) == \
             ce.CROSSENTROPY_ERR_INVALID_ARG
+
+
+def test_lane_groups_refuse_rows_they_cannot_take():
+    """8, 16 or 32 lanes per row need 16-byte aligned rows of at most 8 vectors per lane."""
+    lib = ce.load()
+    f = lib.crossentropy_fwd_tuned
+    for lanes, n_too_long in ((8, 520), (16, 1032), (32, 2056)):
+        assert f(P, P + BIG, P + 2 * BIG, None, 4, n_too_long, 2, None, lanes) == ce.CROSSENTROPY_ERR_UNSUPPORTED
+        assert f(P, P + BIG, P + 2 * BIG, None, 4, n_too_long // 2 + 4, 0, None, lanes) == ce.CROSSENTROPY_ERR_UNSUPPORTED
+        assert f(P, P + BIG, P + 2 * BIG, None, 4, 100, 1, None, lanes) == ce.CROSSENTROPY_ERR_UNSUPPORTED  # 200-byte rows
+        assert f(P + 2, P + BIG, P + 2 * BIG, None, 4, 64, 1, None, lanes) == ce.CROSSENTROPY_ERR_UNSUPPORTED  # base off by 2 bytes
+        assert f(P, P + BIG, P + 2 * BIG, None, 0, 64, 1, None, lanes) == ce.CROSSENTROPY_OK  # empty batch
+    assert "thread count" in ce.crossentropy_status_string(ce.CROSSENTROPY_ERR_UNSUPPORTED)
+    # one lane per row: any alignment, at most 64 classes
+    assert f(P, P + BIG, P + 2 * BIG, None, 4, 65, 1, None, 1) == ce.CROSSENTROPY_ERR_UNSUPPORTED
+    assert f(P, P + BIG, P + 2 * BIG, None, 4, 4096, 0, None, 1) == ce.CROSSENTROPY_ERR_UNSUPPORTED
+    assert f(P + 2, P + BIG, P + 2 * BIG, None, 0, 10, 1, None, 1) == ce.CROSSENTROPY_OK
 
 
 def test_automatic_threads_per_row():
     auto = ce.crossentropy_auto_threads_per_row
     for dtype in (0, 1, 2):
-        for n in (1, 7, 128, 1000):
+        for n in (1, 7, 10, 31):             # rows shorter than 128 bytes: one lane per row
+            assert auto(n, dtype) == 1
+        for n in (65, 130, 1001):            # longer rows that are not whole 16-byte vectors
             assert auto(n, dtype) == 64
+    assert auto(63, 1) == 1 and auto(64, 1) == 8 and auto(31, 0) == 1 and auto(32, 0) == 8
+    # few classes in whole vectors: lane groups, at most 32 / 64 / 256 (fp32: 128) vectors per row
+    assert auto(128, 1) == 8 and auto(256, 2) == 8 and auto(264, 2) == 16
+    assert auto(512, 1) == 16 and auto(520, 1) == 32 and auto(1000, 1) == 32 and auto(1024, 2) == 32
+    assert auto(2048, 1) == 32 and auto(2056, 2) == 64 and auto(128, 0) == 8 and auto(132, 0) == 16
+    assert auto(256, 0) == 16 and auto(512, 0) == 32 and auto(516, 0) == 64 and auto(1000, 0) == 64
     # about 8 16-byte vectors per thread for the 16-bit types and 4 for fp32, in whole wavefronts
-    assert auto(2048, 1) == 64 and auto(4096, 2) == 64 and auto(8192, 1) == 128 and auto(12288, 2) == 192
+    assert auto(2064, 1) == 64 and auto(4096, 2) == 64 and auto(8192, 1) == 128 and auto(12288, 2) == 192
     assert auto(16384, 1) == 256 and auto(32000, 1) == 512 and auto(50257, 2) == 512
     assert auto(65536, 1) == 1024 and auto(131072, 2) == 1024 and auto(1 << 30, 1) == 1024
     assert auto(1024, 0) == 64 and auto(4096, 0) == 256 and auto(8192, 0) == 512
