@@ -24,9 +24,10 @@
  *  - Pointers need only the alignment of their element type.  Rows whose
  *    start is 16-byte aligned (16-byte aligned bases and N * sizeof(dtype) a
  *    multiple of 16) take the aligned kernels; other rows take the same
- *    register-resident kernel with element-aligned 128-bit accesses; rows too
- *    long for registers stream through a two-pass kernel that reads x a second
- *    time from cache.  None of these is an error.
+ *    register-resident kernel with element-aligned 128-bit accesses (up to 512
+ *    elements: several rows at a time through LDS); rows too long for registers
+ *    stream through a two-pass kernel that reads x a second time from cache.
+ *    None of these is an error.
  *  - y == x (exactly in place) is allowed; any other overlap of y with x or w
  *    is undefined.
  *  - Calls return RMSNORM_OK or a negative rmsnorm_status; nothing throws or
@@ -69,9 +70,13 @@ typedef enum {
                                    rmsnorm_unaligned_max_n(dtype) */
   RMSNORM_VARIANT_SUBWAVE = 5,  /* 8, 16 or 32 lanes per row, several rows per wavefront;
                                    16-byte aligned rows of at most 1 KiB */
-  RMSNORM_VARIANT_STREAM = 6    /* two streaming passes with 128-bit accesses for rows too
+  RMSNORM_VARIANT_STREAM = 6,   /* two streaming passes with 128-bit accesses for rows too
                                    long for registers (the second read comes from cache);
                                    any alignment, N < 2^31 */
+  RMSNORM_VARIANT_PACKED = 7    /* runs of short rows copied through LDS with 128-bit accesses,
+                                   8 to 64 lanes per row; N <= 512, any alignment as long as x
+                                   and y are congruent modulo 16 bytes; what rows that are not
+                                   16-byte aligned take up to that length */
 } rmsnorm_variant;
 
 /*
@@ -95,7 +100,9 @@ int rmsnorm_fwd(const void* x, const void* w, void* y, int64_t M, int64_t N,
  * shape: SUBWAVE needs 16-byte aligned rows of at most 1 KiB, WAVE needs
  * 16-byte aligned rows of at most rmsnorm_wave_max_n(dtype) elements, BLOCK needs 16-byte aligned rows of at most
  * rmsnorm_block_max_n(dtype) elements, UNALIGNED takes any alignment up to
- * rmsnorm_unaligned_max_n(dtype) elements, GENERIC takes everything.
+ * rmsnorm_unaligned_max_n(dtype) elements, PACKED up to 512 elements with x - y a multiple
+ * of 16 bytes, STREAM
+ * any alignment up to N < 2^31, GENERIC takes everything.
  */
 int rmsnorm_fwd_variant(const void* x, const void* w, void* y, int64_t M, int64_t N,
                         float eps, int dtype, void* stream, int variant);

@@ -29,8 +29,9 @@ RMSNORM_VARIANT_GENERIC = 3
 RMSNORM_VARIANT_UNALIGNED = 4
 RMSNORM_VARIANT_SUBWAVE = 5
 RMSNORM_VARIANT_STREAM = 6
+RMSNORM_VARIANT_PACKED = 7
 
-VARIANT_NAMES = {0: "auto", 1: "wave", 2: "block", 3: "generic", 4: "unaligned", 5: "subwave", 6: "stream"}
+VARIANT_NAMES = {0: "auto", 1: "wave", 2: "block", 3: "generic", 4: "unaligned", 5: "subwave", 6: "stream", 7: "packed"}
 
 _lib = None
 

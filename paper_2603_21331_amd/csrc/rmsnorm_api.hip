@@ -120,8 +120,20 @@ int64_t full_groups_per_row(int64_t N, int dtype) { return N / (16 / elem_bytes(
 
 constexpr int64_t kStreamMaxN = (int64_t)1 << 31;   // the streaming kernel counts groups in an int
 
+// The LDS-staged kernel takes rows of at most 8 elements per lane of a 64-lane group at any
+// alignment, provided x and y sit at the same offset from a 16-byte boundary (its tile mirrors
+// that offset, so aligned vectors of x are aligned vectors of y); the automatic path uses it
+// for such rows when they are not 16-byte aligned.
+constexpr int64_t kPackedMaxN = 64 * rms::kPackElems;
+
+bool packed_can(const void* x, const void* y, int64_t N) {
+  return N <= kPackedMaxN && ((reinterpret_cast<uintptr_t>(x) ^ reinterpret_cast<uintptr_t>(y)) & 15u) == 0;
+}
+constexpr int64_t kPackedMaxGrid = 8192;
+
 int choose(const void* x, const void* w, const void* y, int64_t N, int dtype) {
   if (!rows_vectorisable(x, w, y, N, dtype)) {
+    if (packed_can(x, y, N)) return RMSNORM_VARIANT_PACKED;
     if (pick_threads_unaligned(full_groups_per_row(N, dtype))) return RMSNORM_VARIANT_UNALIGNED;
     return N < kStreamMaxN ? RMSNORM_VARIANT_STREAM : RMSNORM_VARIANT_GENERIC;
   }
@@ -273,6 +285,29 @@ int dispatch_row(const Args& a, int threads) {
   return RMSNORM_OK;
 }
 
+// Launches the LDS-staged kernel: the narrowest lane group that holds the row, as many whole
+// rows per step as fit the tile.  The caller has checked N <= kPackedMaxN.
+template <int DT, int L>
+void launch_packed(const Args& a) {
+  const int n = (int)a.N;
+  int tile_rows = rms::kPackTileBytes / (n * rms::Storage<DT>::kBytes);
+  if (tile_rows > a.M) tile_rows = (int)a.M;
+  int64_t blocks = (a.M + tile_rows - 1) / tile_rows;
+  if (blocks > kPackedMaxGrid) blocks = kPackedMaxGrid;   // beyond 128 MiB a workgroup takes several tiles
+  hipLaunchKernelGGL((rms::rmsnorm_packed_kernel<DT, L, true>), dim3((unsigned)blocks),
+                     dim3(rms::kPackThreads), 0, a.stream, a.x, a.w, a.y, a.M, n, tile_rows,
+                     1.0f / (float)a.N, a.eps);
+}
+
+template <int DT>
+void dispatch_packed(const Args& a) {
+  const int64_t per8 = (a.N + rms::kPackElems - 1) / rms::kPackElems;   // lanes the row needs
+  if (per8 <= 8) launch_packed<DT, 8>(a);
+  else if (per8 <= 16) launch_packed<DT, 16>(a);
+  else if (per8 <= 32) launch_packed<DT, 32>(a);
+  else launch_packed<DT, 64>(a);
+}
+
 // Launches the element-aligned row kernel.  The caller has checked that the row fits.
 template <int DT>
 int dispatch_row_unaligned(const Args& a) {
@@ -314,13 +349,14 @@ int dispatch_row_unaligned(const Args& a) {
 }
 
 // threads == 0 means the element-wise kernel, -1 the element-aligned row kernel, -2 the
-// two-pass streaming kernel.
+// two-pass streaming kernel, -3 the LDS-staged kernel.
 template <int DT>
 int run_typed(const Args& a, int threads) {
   int rc = RMSNORM_OK;
   if (threads == 0) launch_generic<DT>(a);
   else if (threads == -1) rc = dispatch_row_unaligned<DT>(a);
   else if (threads == -2) launch_stream<DT>(a);
+  else if (threads == -3) dispatch_packed<DT>(a);
   else rc = dispatch_row<DT>(a, threads);
   if (rc != RMSNORM_OK) return rc;
   return hipGetLastError() == hipSuccess ? RMSNORM_OK : RMSNORM_ERR_LAUNCH;
@@ -331,7 +367,7 @@ int run(const void* x, const void* w, void* y, int64_t M, int64_t N, float eps, 
         void* stream, int variant, int threads) {
   int rc = check_args(x, w, y, M, N, eps, dtype);
   if (rc != RMSNORM_OK) return rc;
-  if (variant < -1 || variant > RMSNORM_VARIANT_STREAM) return RMSNORM_ERR_INVALID_ARG;
+  if (variant < -1 || variant > RMSNORM_VARIANT_PACKED) return RMSNORM_ERR_INVALID_ARG;
   if (variant == -1 && max_chunks_for(threads, dtype) == 0) return RMSNORM_ERR_INVALID_ARG;
   if (M == 0) return RMSNORM_OK;
 
@@ -362,6 +398,10 @@ int run(const void* x, const void* w, void* y, int64_t M, int64_t N, float eps, 
     case RMSNORM_VARIANT_STREAM:
       if (N >= kStreamMaxN) return RMSNORM_ERR_UNSUPPORTED;
       threads = -2;
+      break;
+    case RMSNORM_VARIANT_PACKED:
+      if (!packed_can(x, y, N)) return RMSNORM_ERR_UNSUPPORTED;
+      threads = -3;
       break;
     default:
       threads = 0;

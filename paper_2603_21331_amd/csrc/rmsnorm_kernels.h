@@ -31,6 +31,7 @@
 
 #include "vec_io.h"
 #include "wave_reduce.h"
+#include "packed_rows.h"
 
 namespace rms {
 
@@ -202,6 +203,66 @@ rmsnorm_row_kernel(const u32x4* x, const u32x4* w, u32x4* y,
       const u32x4 wc = W_WHEN == kOneByOne ? wl[last] : wv[W_WHEN == kOneByOne ? 0 : CHUNKS - 1];
       store_row_vec<NT>(yr, last, scale_vec<DT>(v[CHUNKS - 1], wc, rstd));
     }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Short rows that are not 16-byte aligned, several per workgroup, staged through LDS (see
+// packed_rows.h): L lanes per row, at most kPackElems elements per lane (N <= 8 * L), `tile_rows`
+// rows (at most 16 KiB) per step; x and y must be congruent modulo 16 bytes.  A lane keeps its slice of the weight in registers for the
+// whole launch.  Lane groups without a row repeat the last one and write nothing back.
+// ---------------------------------------------------------------------------
+template <int DT, int L, bool NT>
+__global__ void __launch_bounds__(kPackThreads)
+rmsnorm_packed_kernel(const void* x, const void* w, void* y, int64_t M, int N, int tile_rows,
+                      float inv_n, float eps) {
+  using S = Storage<DT>;
+  constexpr int GROUPS = kPackThreads / L;
+  __shared__ u32x4 tile[kPackLdsVecs];
+  const int t = threadIdx.x;
+  const int sub = t % L;
+  const int group = t / L;
+
+  float wf[kPackElems];
+#pragma unroll
+  for (int i = 0; i < kPackElems; ++i) {
+    const int j = sub + i * L;
+    wf[i] = j < N ? S::load_one(w, j) : 0.f;
+  }
+
+  for (int64_t r0 = (int64_t)blockIdx.x * tile_rows; r0 < M; r0 += (int64_t)gridDim.x * tile_rows) {
+    const int rows = (int)(M - r0 < tile_rows ? M - r0 : tile_rows);
+    const char* src = static_cast<const char*>(x) + r0 * N * S::kBytes;
+    const TileCut cut = tile_cut(src, rows * N * S::kBytes);
+    const int origin = cut.skew / S::kBytes;               // tile element of the run's first element
+    tile_fill<DT, NT>(src, tile, cut, t);
+    __syncthreads();
+    for (int first = 0; first < rows; first += GROUPS) {   // the same trip count for every thread
+      const int r = first + group;
+      const int at = origin + (r < rows ? r : rows - 1) * N;
+      float f[kPackElems];
+      float acc = 0.f;
+#pragma unroll
+      for (int i = 0; i < kPackElems; ++i) {
+        f[i] = 0.f;
+        if (i * L < N) {                    // the same for every lane: whole steps are skipped
+          const int j = sub + i * L;
+          if (j < N) f[i] = tile_get<DT>(tile, at + j);
+          acc = __builtin_fmaf(f[i], f[i], acc);
+        }
+      }
+      const float rstd = row_rstd(group_sum<L>(acc), inv_n, eps);
+      if (r < rows) {
+#pragma unroll
+        for (int i = 0; i < kPackElems; ++i) {
+          const int j = sub + i * L;
+          if (j < N) tile_put<DT>(tile, at + j, (f[i] * rstd) * wf[i]);
+        }
+      }
+    }
+    __syncthreads();
+    tile_drain<DT, NT>(static_cast<char*>(y) + r0 * N * S::kBytes, tile, cut, t);
+    __syncthreads();                                       // the next step refills the tile
   }
 }
 

@@ -96,7 +96,7 @@ def test_empty_batch_is_a_successful_no_op():
 
 def test_unknown_variant_and_unsupported_shapes():
     lib = binding.load()
-    assert lib.rmsnorm_fwd_variant(P, P + 4096, P + 8192, 4, 8, 1e-6, 2, None, 9) == \
+    assert lib.rmsnorm_fwd_variant(P, P + 4096, P + 8192, 4, 8, 1e-6, 2, None, 8) == \
         binding.RMSNORM_ERR_INVALID_ARG
     assert lib.rmsnorm_fwd_variant(P, P + 4096, P + 8192, 4, 8, 1e-6, 2, None, -1) == \
         binding.RMSNORM_ERR_INVALID_ARG
@@ -116,6 +116,15 @@ def test_unknown_variant_and_unsupported_shapes():
     # misaligned base pointer
     assert lib.rmsnorm_fwd_variant(P + 2, P + 4096, P + 8192, 4, 8, 1e-6, 2, None,
                                    binding.RMSNORM_VARIANT_WAVE) == binding.RMSNORM_ERR_UNSUPPORTED
+    # more than 512 elements per row is too long for the LDS-staged kernel
+    for dtype in (0, 1, 2):
+        assert lib.rmsnorm_fwd_variant(P, P + (1 << 20), P + (2 << 20), 4, 513, 1e-6, dtype, None,
+                                       binding.RMSNORM_VARIANT_PACKED) == binding.RMSNORM_ERR_UNSUPPORTED
+    assert lib.rmsnorm_fwd_variant(P, P + (1 << 20), P + (2 << 20), 0, 512, 1e-6, 2, None,
+                                   binding.RMSNORM_VARIANT_PACKED) == binding.RMSNORM_OK
+    # ... and it needs x and y at the same offset from a 16-byte boundary
+    assert lib.rmsnorm_fwd_variant(P + 2, P + (1 << 20), P + (2 << 20) + 4, 4, 77, 1e-6, 2, None,
+                                   binding.RMSNORM_VARIANT_PACKED) == binding.RMSNORM_ERR_UNSUPPORTED
 
 
 def test_tuned_entry_argument_checks():
@@ -174,7 +183,14 @@ def test_dispatch_choice_is_visible_without_a_launch():
     assert sel(P, P + 65536, P + 131072, 16, 128, 2) == binding.RMSNORM_VARIANT_SUBWAVE
     assert sel(P, P + 65536, P + 131072, 16, 1023, 1) == binding.RMSNORM_VARIANT_UNALIGNED
     assert sel(P + 2, P + 65536, P + 131072, 16, 1024, 1) == binding.RMSNORM_VARIANT_UNALIGNED
-    assert sel(P, P + 65536, P + 131072, 16, 3, 0) == binding.RMSNORM_VARIANT_UNALIGNED
+    assert sel(P, P + 65536, P + 131072, 16, 513, 1) == binding.RMSNORM_VARIANT_UNALIGNED
+    # short rows that are not 16-byte aligned go through LDS several at a time
+    assert sel(P, P + 65536, P + 131072, 16, 511, 1) == binding.RMSNORM_VARIANT_PACKED
+    assert sel(P + 2, P + 65536, P + 131072 + 18, 16, 512, 1) == binding.RMSNORM_VARIANT_PACKED
+    assert sel(P + 2, P + 65536, P + 131072, 16, 512, 1) == binding.RMSNORM_VARIANT_UNALIGNED  # x - y not a multiple of 16
+    assert sel(P, P + 65536, P + 131072, 16, 197, 2) == binding.RMSNORM_VARIANT_PACKED
+    assert sel(P, P + 65536, P + 131072, 16, 3, 0) == binding.RMSNORM_VARIANT_PACKED
+    assert sel(P, P + 65536, P + 131072, 16, 512, 1) == binding.RMSNORM_VARIANT_WAVE
     assert sel(P, P + 65536, P + 131072, 16, 131079, 2) == binding.RMSNORM_VARIANT_UNALIGNED
     assert sel(P, P + 65536, P + 131072, 16, 131081, 2) == binding.RMSNORM_VARIANT_STREAM
     assert sel(P, P + 65536, P + 131072, 16, 1 << 20, 2) == binding.RMSNORM_VARIANT_STREAM

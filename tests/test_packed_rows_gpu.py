@@ -1,0 +1,96 @@
+"""GPU parity tests of the LDS-staged kernels for short rows that are not 16-byte aligned
+(several rows per workgroup): odd lengths from 1 to 512 (attention rows of 77, 197, 257
+entries), row counts that end inside a tile, inside a lane-group pass and inside a
+wavefront, base pointers off a 16-byte boundary, in place, and aligned shapes forced onto
+the kernel.  Each output is compared with the CPU oracle element by element, and the
+guard elements around y must stay untouched."""
+import numpy as np
+import pytest
+import torch
+
+import compare
+import gpu_harness as H
+import oracle
+from paper_2603_21331_amd import binding, inputs
+
+pytestmark = pytest.mark.gpu
+
+DTYPES = [inputs.FP32, inputs.FP16, inputs.BF16]
+# every lane-group size (8, 16, 32, 64 lanes of up to 8 elements) at its limits and inside
+LENGTHS = [1, 3, 7, 50, 63, 64, 65, 77, 127, 129, 197, 255, 257, 300, 511, 512]
+
+
+def offset_view(a, dtype, device, off, shape):
+    """The array on the device, `off` elements past a 16-byte boundary."""
+    buf = torch.zeros(a.size + 16, dtype=H.torch_dtype(dtype), device=device)
+    view = buf[off:off + a.size].view(*shape)
+    view.copy_(H.to_device(a.reshape(shape), dtype, device))
+    return view
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("N", LENGTHS)
+def test_rmsnorm_packed_lengths(gpu_device, N, dtype):
+    rows_per_tile = 16384 // (N * inputs.DTYPE_BYTES[dtype])
+    M = 2 * rows_per_tile + 5 if rows_per_tile < 3000 else 4099     # two full tiles and a partial one
+    case = inputs.random_case(6, 900 + 2 * dtype, M, N, dtype, 1e-6)
+    want = oracle.rmsnorm_oracle(case["x"], case["w"], 1e-6, dtype)
+    H.check_case(case, gpu_device, variants=(binding.RMSNORM_VARIANT_AUTO, binding.RMSNORM_VARIANT_PACKED,
+                                             binding.RMSNORM_VARIANT_GENERIC), want=want)
+    # x and y the same distance off a 16-byte boundary (w anywhere): still the LDS-staged kernel
+    per16 = 16 // inputs.DTYPE_BYTES[dtype]
+    xd = offset_view(case["x"], dtype, gpu_device, 1, (M, N))
+    wd = offset_view(case["w"], dtype, gpu_device, 3, (N,))
+    for mode in (binding.RMSNORM_VARIANT_AUTO, binding.RMSNORM_VARIANT_PACKED):
+        whole, y = H.alloc_guarded(M, N, dtype, gpu_device, offset_elems=1 + per16)
+        H.say(f"rmsnorm packed offset bases {inputs.DTYPE_NAMES[dtype]} {M}x{N} mode={mode}")
+        binding.rmsnorm_fwd_variant(xd, wd, 1e-6, mode, y)
+        torch.cuda.synchronize()
+        assert H.guards_intact(whole, M, N, dtype, offset_elems=1 + per16)
+        compare.check_parity(H.to_host(y, dtype), want, dtype, f"packed offset bases mode {mode}")
+    assert binding.rmsnorm_select_variant(xd, wd, y) == binding.RMSNORM_VARIANT_PACKED
+    # x and y at different distances: the kernel refuses, the automatic path takes another
+    whole, y = H.alloc_guarded(M, N, dtype, gpu_device, offset_elems=2)
+    with pytest.raises(binding.RmsnormError) as e:
+        binding.rmsnorm_fwd_variant(xd, wd, 1e-6, binding.RMSNORM_VARIANT_PACKED, y)
+    assert e.value.status == binding.RMSNORM_ERR_UNSUPPORTED
+    assert binding.rmsnorm_select_variant(xd, wd, y) == binding.RMSNORM_VARIANT_UNALIGNED
+    binding.rmsnorm_fwd(xd, wd, 1e-6, y)
+    torch.cuda.synchronize()
+    assert H.guards_intact(whole, M, N, dtype, offset_elems=2)
+    compare.check_parity(H.to_host(y, dtype), want, dtype, "x and y at different offsets")
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("M", [1, 2, 31, 33, 64, 1000])
+def test_rmsnorm_packed_row_counts(gpu_device, M, dtype):
+    """Fewer rows than a tile, than a pass of the lane groups, than a wavefront."""
+    N = 77
+    case = inputs.random_case(6, 920 + 2 * dtype, M, N, dtype, 1e-5)
+    H.check_case(case, gpu_device, variants=(binding.RMSNORM_VARIANT_AUTO, binding.RMSNORM_VARIANT_PACKED))
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_rmsnorm_packed_in_place_and_deterministic(gpu_device, dtype):
+    M, N = 3001, 197
+    case = inputs.random_case(6, 940 + 2 * dtype, M, N, dtype, 1e-6)
+    want = oracle.rmsnorm_oracle(case["x"], case["w"], 1e-6, dtype)
+    wd = H.to_device(case["w"], dtype, gpu_device)
+    xd = H.to_device(case["x"], dtype, gpu_device)
+    first = H.to_host(binding.rmsnorm_fwd_variant(xd, wd, 1e-6, binding.RMSNORM_VARIANT_PACKED), dtype).copy()
+    compare.check_parity(first, want, dtype, "packed")
+    for _ in range(2):
+        again = H.to_host(binding.rmsnorm_fwd_variant(xd, wd, 1e-6, binding.RMSNORM_VARIANT_PACKED), dtype)
+        assert np.array_equal(again.view(np.uint8), first.view(np.uint8))
+    H.say("rmsnorm packed in place")
+    binding.rmsnorm_fwd_variant(xd, wd, 1e-6, binding.RMSNORM_VARIANT_PACKED, xd)
+    torch.cuda.synchronize()
+    assert np.array_equal(H.to_host(xd, dtype).view(np.uint8), first.view(np.uint8))
+
+
+def test_rmsnorm_packed_more_tiles_than_the_grid(gpu_device):
+    """The grid stops at 8192 workgroups; with 8 rows of 2 KiB per tile, 65536 + 13 rows make
+    the first workgroups take a second tile and the last of those a partial one."""
+    M, N = 8192 * 8 + 13, 511
+    case = inputs.random_case(6, 960, M, N, inputs.FP32, 1e-6)
+    H.check_case(case, gpu_device, variants=(binding.RMSNORM_VARIANT_PACKED,))
