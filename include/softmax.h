@@ -55,8 +55,12 @@ typedef enum {
   SOFTMAX_VARIANT_SUBWAVE = 4, /* 8, 16 or 32 lanes per row; 16-byte aligned rows <= 1 KiB */
   SOFTMAX_VARIANT_UNALIGNED = 5, /* the register-resident row kernel with element-aligned
                                     128-bit accesses: any alignment, N up to the register limit */
-  SOFTMAX_VARIANT_STREAM = 6     /* two streaming passes (online max and sum, then scale) for
+  SOFTMAX_VARIANT_STREAM = 6,    /* two streaming passes (online max and sum, then scale) for
                                     rows too long for registers: any alignment, N < 2^31 */
+  SOFTMAX_VARIANT_PACKED = 7     /* runs of short rows copied through LDS with 128-bit accesses,
+                                    8 to 64 lanes per row: N <= 512, any alignment as long as x
+                                    and y are congruent modulo 16 bytes; what rows that are not
+                                    16-byte aligned take up to that length */
 } softmax_variant;
 
 /*

@@ -171,6 +171,51 @@ void launch_row_unaligned(const Args& a, int nfull) {
                      dim3(G), 0, a.stream, a.x, a.w, a.b, a.y, a.M, a.N, nfull, (float)a.N, a.eps);
 }
 
+// The LDS-staged kernel for short rows that are not 16-byte aligned: the narrowest lane group
+// that holds the row (8 elements per lane), as many whole rows per step as fit the tile, at
+// most 8192 workgroups (beyond 128 MiB a workgroup takes several tiles).  It needs x and y at
+// the same offset from a 16-byte boundary, which its tile mirrors.
+constexpr int64_t kPackedMaxN = 64 * rms::kPackElems;
+constexpr int64_t kPackedMaxGrid = 8192;
+
+bool packed_can(const void* x, const void* y, int64_t N) {
+  return N <= kPackedMaxN && ((reinterpret_cast<uintptr_t>(x) ^ reinterpret_cast<uintptr_t>(y)) & 15u) == 0;
+}
+
+template <int DT, int L, int E>
+void launch_packed(const Args& a) {
+  const int n = (int)a.N;
+  int tile_rows = rms::kPackTileBytes / (n * rms::Storage<DT>::kBytes);
+  if (tile_rows > a.M) tile_rows = (int)a.M;
+  int64_t blocks = (a.M + tile_rows - 1) / tile_rows;
+  if (blocks > kPackedMaxGrid) blocks = kPackedMaxGrid;
+  hipLaunchKernelGGL((rms::layernorm_packed_kernel<DT, L, E, true>), dim3((unsigned)blocks),
+                     dim3(rms::kPackThreads), 0, a.stream, a.x, a.w, a.b, a.y, a.M, n, tile_rows,
+                     (float)a.N, a.eps);
+}
+
+// Lanes per row: the narrowest group that holds the row with 8 elements per lane; elements per
+// lane: what the row then needs, at least 5 (fewer would fit a narrower group, except in the
+// narrowest one, where rows of 32 elements and less carry idle steps).
+template <int DT, int L>
+void launch_packed_lanes(const Args& a) {
+  switch ((a.N + L - 1) / L) {
+    case 8: launch_packed<DT, L, 8>(a); break;
+    case 7: launch_packed<DT, L, 7>(a); break;
+    case 6: launch_packed<DT, L, 6>(a); break;
+    default: launch_packed<DT, L, 5>(a); break;
+  }
+}
+
+template <int DT>
+void dispatch_packed(const Args& a) {
+  const int64_t lanes = (a.N + rms::kPackElems - 1) / rms::kPackElems;   // lanes the row needs
+  if (lanes <= 8) launch_packed_lanes<DT, 8>(a);
+  else if (lanes <= 16) launch_packed_lanes<DT, 16>(a);
+  else if (lanes <= 32) launch_packed_lanes<DT, 32>(a);
+  else launch_packed_lanes<DT, 64>(a);
+}
+
 // The three-pass streaming kernel: about one batch of four groups per thread, whole
 // wavefronts, at most 1024 threads (what every row long enough to need this kernel gets).
 constexpr int64_t kStreamMaxN = (int64_t)1 << 31;   // it counts groups in an int
@@ -278,13 +323,14 @@ int dispatch_unaligned(const Args& a) {
 }
 
 // threads == 0 means the element-wise kernel, -1 the element-aligned row kernel, -2 the
-// three-pass streaming kernel.
+// three-pass streaming kernel, -3 the LDS-staged kernel.
 template <int DT>
 int run_typed(const Args& a, int threads) {
   int rc = LAYERNORM_OK;
   if (threads == 0) launch_generic<DT>(a);
   else if (threads == -1) rc = dispatch_unaligned<DT>(a);
   else if (threads == -2) launch_stream<DT>(a);
+  else if (threads == -3) dispatch_packed<DT>(a);
   else rc = dispatch<DT>(a, threads);
   if (rc != LAYERNORM_OK) return rc;
   return hipGetLastError() == hipSuccess ? LAYERNORM_OK : LAYERNORM_ERR_LAUNCH;
@@ -295,7 +341,7 @@ int run(const void* x, const void* w, const void* b, void* y, int64_t M, int64_t
         int dtype, void* stream, int variant, int threads) {
   int rc = check_args(x, w, b, y, M, N, eps, dtype);
   if (rc != LAYERNORM_OK) return rc;
-  if (variant < -1 || variant > LAYERNORM_VARIANT_STREAM) return LAYERNORM_ERR_INVALID_ARG;
+  if (variant < -1 || variant > LAYERNORM_VARIANT_PACKED) return LAYERNORM_ERR_INVALID_ARG;
   if (variant == -1 && max_chunks_for(threads) == 0) return LAYERNORM_ERR_INVALID_ARG;
   if (M == 0) return LAYERNORM_OK;
 
@@ -304,8 +350,12 @@ int run(const void* x, const void* w, const void* b, void* y, int64_t M, int64_t
   const bool unaligned_fits = pick_threads_unaligned(N / (16 / elem_bytes(dtype))) != 0;
   switch (variant) {
     case LAYERNORM_VARIANT_AUTO:
-      threads = vec_ok ? pick_threads(nvec, 8, dtype) : unaligned_fits ? -1 : 0;
+      threads = vec_ok ? pick_threads(nvec, 8, dtype) : packed_can(x, y, N) ? -3 : unaligned_fits ? -1 : 0;
       if (threads == 0 && N < kStreamMaxN) threads = -2;     // too long for registers
+      break;
+    case LAYERNORM_VARIANT_PACKED:
+      if (!packed_can(x, y, N)) return LAYERNORM_ERR_UNSUPPORTED;
+      threads = -3;
       break;
     case LAYERNORM_VARIANT_STREAM:
       if (N >= kStreamMaxN) return LAYERNORM_ERR_UNSUPPORTED;

@@ -28,6 +28,7 @@
 
 #include "vec_io.h"
 #include "wave_reduce.h"
+#include "packed_rows.h"
 
 namespace rms {
 
@@ -313,6 +314,75 @@ layernorm_row_resident_kernel(const u32x4* x, const u32x4* __restrict__ w,
                                         part_a[1], part_b[1]);
     if (next >= M) break;
     row = next;
+  }
+}
+
+// Short rows that are not 16-byte aligned, several per workgroup, staged through LDS (see
+// packed_rows.h): L lanes per row, E = 5..8 elements per lane (N <= E * L),
+// `tile_rows` rows (at most 16 KiB) per step; x and y must be congruent modulo 16 bytes.  A
+// lane keeps its slices of weight and bias in registers for the whole launch.  The same two
+// passes over registers as the other kernels: shift by the row's first element, sum, centre,
+// sum of squares.  Lane groups without a row repeat the last one and write nothing back.
+template <int DT, int L, int E, bool NT>
+__global__ void __launch_bounds__(kPackThreads)
+layernorm_packed_kernel(const void* x, const void* w, const void* b, void* y, int64_t M, int N,
+                        int tile_rows, float n, float eps) {
+  using S = Storage<DT>;
+  constexpr int GROUPS = kPackThreads / L;
+  __shared__ u32x4 tile[kPackLdsVecs];
+  const int t = threadIdx.x;
+  const int sub = t % L;
+  const int group = t / L;
+  const bool has_bias = b != nullptr;
+
+  float wf[E], bf[E];
+#pragma unroll
+  for (int i = 0; i < E; ++i) {
+    const int j = sub + i * L;
+    wf[i] = j < N ? S::load_one(w, j) : 0.f;
+    bf[i] = (j < N && has_bias) ? S::load_one(b, j) : 0.f;
+  }
+
+  for (int64_t r0 = (int64_t)blockIdx.x * tile_rows; r0 < M; r0 += (int64_t)gridDim.x * tile_rows) {
+    const int rows = (int)(M - r0 < tile_rows ? M - r0 : tile_rows);
+    const char* src = static_cast<const char*>(x) + r0 * N * S::kBytes;
+    const TileCut cut = tile_cut(src, rows * N * S::kBytes);
+    const int origin = cut.skew / S::kBytes;               // tile element of the run's first element
+    tile_fill<DT, NT>(src, tile, cut, t);
+    __syncthreads();
+    for (int first = 0; first < rows; first += GROUPS) {   // the same trip count for every thread
+      const int r = first + group;
+      const int at = origin + (r < rows ? r : rows - 1) * N;
+      const float shift = tile_get<DT>(tile, at);
+      float f[E];
+      float acc = 0.f;
+#pragma unroll
+      for (int i = 0; i < E; ++i) {
+        const int j = sub + i * L;
+        f[i] = j < N ? tile_get<DT>(tile, at + j) - shift : 0.f;
+        acc += f[i];
+      }
+      const float mean_shifted = group_sum<L>(acc) / n;
+      float sq = 0.f;
+#pragma unroll
+      for (int i = 0; i < E; ++i) {
+        const int j = sub + i * L;
+        f[i] = j < N ? f[i] - mean_shifted : 0.f;
+        sq = __builtin_fmaf(f[i], f[i], sq);
+      }
+      const float rstd = ln_rstd(group_sum<L>(sq), n, eps);
+      if (r < rows) {
+#pragma unroll
+        for (int i = 0; i < E; ++i) {
+          const int j = sub + i * L;
+          const float scaled = (f[i] * rstd) * wf[i];
+          if (j < N) tile_put<DT>(tile, at + j, has_bias ? scaled + bf[i] : scaled);
+        }
+      }
+    }
+    __syncthreads();
+    tile_drain<DT, NT>(static_cast<char*>(y) + r0 * N * S::kBytes, tile, cut, t);
+    __syncthreads();                                       // the next step refills the tile
   }
 }
 

@@ -287,25 +287,38 @@ int dispatch_row(const Args& a, int threads) {
 
 // Launches the LDS-staged kernel: the narrowest lane group that holds the row, as many whole
 // rows per step as fit the tile.  The caller has checked N <= kPackedMaxN.
-template <int DT, int L>
+template <int DT, int L, int E>
 void launch_packed(const Args& a) {
   const int n = (int)a.N;
   int tile_rows = rms::kPackTileBytes / (n * rms::Storage<DT>::kBytes);
   if (tile_rows > a.M) tile_rows = (int)a.M;
   int64_t blocks = (a.M + tile_rows - 1) / tile_rows;
   if (blocks > kPackedMaxGrid) blocks = kPackedMaxGrid;   // beyond 128 MiB a workgroup takes several tiles
-  hipLaunchKernelGGL((rms::rmsnorm_packed_kernel<DT, L, true>), dim3((unsigned)blocks),
+  hipLaunchKernelGGL((rms::rmsnorm_packed_kernel<DT, L, E, true>), dim3((unsigned)blocks),
                      dim3(rms::kPackThreads), 0, a.stream, a.x, a.w, a.y, a.M, n, tile_rows,
                      1.0f / (float)a.N, a.eps);
 }
 
+// Lanes per row: the narrowest group that holds the row with 8 elements per lane; elements per
+// lane: what the row then needs, at least 5 (fewer would fit a narrower group, except in the
+// narrowest one, where rows of 32 elements and less carry idle steps).
+template <int DT, int L>
+void launch_packed_lanes(const Args& a) {
+  switch ((a.N + L - 1) / L) {
+    case 8: launch_packed<DT, L, 8>(a); break;
+    case 7: launch_packed<DT, L, 7>(a); break;
+    case 6: launch_packed<DT, L, 6>(a); break;
+    default: launch_packed<DT, L, 5>(a); break;
+  }
+}
+
 template <int DT>
 void dispatch_packed(const Args& a) {
-  const int64_t per8 = (a.N + rms::kPackElems - 1) / rms::kPackElems;   // lanes the row needs
-  if (per8 <= 8) launch_packed<DT, 8>(a);
-  else if (per8 <= 16) launch_packed<DT, 16>(a);
-  else if (per8 <= 32) launch_packed<DT, 32>(a);
-  else launch_packed<DT, 64>(a);
+  const int64_t lanes = (a.N + rms::kPackElems - 1) / rms::kPackElems;   // lanes the row needs
+  if (lanes <= 8) launch_packed_lanes<DT, 8>(a);
+  else if (lanes <= 16) launch_packed_lanes<DT, 16>(a);
+  else if (lanes <= 32) launch_packed_lanes<DT, 32>(a);
+  else launch_packed_lanes<DT, 64>(a);
 }
 
 // Launches the element-aligned row kernel.  The caller has checked that the row fits.

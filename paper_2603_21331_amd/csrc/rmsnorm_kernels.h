@@ -208,11 +208,11 @@ rmsnorm_row_kernel(const u32x4* x, const u32x4* w, u32x4* y,
 
 // ---------------------------------------------------------------------------
 // Short rows that are not 16-byte aligned, several per workgroup, staged through LDS (see
-// packed_rows.h): L lanes per row, at most kPackElems elements per lane (N <= 8 * L), `tile_rows`
+// packed_rows.h): L lanes per row, E = 5..8 elements per lane (N <= E * L), `tile_rows`
 // rows (at most 16 KiB) per step; x and y must be congruent modulo 16 bytes.  A lane keeps its slice of the weight in registers for the
 // whole launch.  Lane groups without a row repeat the last one and write nothing back.
 // ---------------------------------------------------------------------------
-template <int DT, int L, bool NT>
+template <int DT, int L, int E, bool NT>
 __global__ void __launch_bounds__(kPackThreads)
 rmsnorm_packed_kernel(const void* x, const void* w, void* y, int64_t M, int N, int tile_rows,
                       float inv_n, float eps) {
@@ -223,9 +223,9 @@ rmsnorm_packed_kernel(const void* x, const void* w, void* y, int64_t M, int N, i
   const int sub = t % L;
   const int group = t / L;
 
-  float wf[kPackElems];
+  float wf[E];
 #pragma unroll
-  for (int i = 0; i < kPackElems; ++i) {
+  for (int i = 0; i < E; ++i) {
     const int j = sub + i * L;
     wf[i] = j < N ? S::load_one(w, j) : 0.f;
   }
@@ -240,21 +240,18 @@ rmsnorm_packed_kernel(const void* x, const void* w, void* y, int64_t M, int N, i
     for (int first = 0; first < rows; first += GROUPS) {   // the same trip count for every thread
       const int r = first + group;
       const int at = origin + (r < rows ? r : rows - 1) * N;
-      float f[kPackElems];
+      float f[E];
       float acc = 0.f;
 #pragma unroll
-      for (int i = 0; i < kPackElems; ++i) {
-        f[i] = 0.f;
-        if (i * L < N) {                    // the same for every lane: whole steps are skipped
-          const int j = sub + i * L;
-          if (j < N) f[i] = tile_get<DT>(tile, at + j);
-          acc = __builtin_fmaf(f[i], f[i], acc);
-        }
+      for (int i = 0; i < E; ++i) {
+        const int j = sub + i * L;
+        f[i] = j < N ? tile_get<DT>(tile, at + j) : 0.f;
+        acc = __builtin_fmaf(f[i], f[i], acc);
       }
       const float rstd = row_rstd(group_sum<L>(acc), inv_n, eps);
       if (r < rows) {
 #pragma unroll
-        for (int i = 0; i < kPackElems; ++i) {
+        for (int i = 0; i < E; ++i) {
           const int j = sub + i * L;
           if (j < N) tile_put<DT>(tile, at + j, (f[i] * rstd) * wf[i]);
         }

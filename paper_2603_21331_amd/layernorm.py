@@ -28,8 +28,9 @@ LAYERNORM_VARIANT_GENERIC = 3
 LAYERNORM_VARIANT_SUBWAVE = 4
 LAYERNORM_VARIANT_UNALIGNED = 5
 LAYERNORM_VARIANT_STREAM = 6
+LAYERNORM_VARIANT_PACKED = 7
 
-VARIANT_NAMES = {0: "auto", 1: "wave", 2: "block", 3: "generic", 4: "subwave", 5: "unaligned", 6: "stream"}
+VARIANT_NAMES = {0: "auto", 1: "wave", 2: "block", 3: "generic", 4: "subwave", 5: "unaligned", 6: "stream", 7: "packed"}
 
 _lib = None
 

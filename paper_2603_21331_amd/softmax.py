@@ -28,8 +28,9 @@ SOFTMAX_VARIANT_GENERIC = 3
 SOFTMAX_VARIANT_SUBWAVE = 4
 SOFTMAX_VARIANT_UNALIGNED = 5
 SOFTMAX_VARIANT_STREAM = 6
+SOFTMAX_VARIANT_PACKED = 7
 
-VARIANT_NAMES = {0: "auto", 1: "wave", 2: "block", 3: "generic", 4: "subwave", 5: "unaligned", 6: "stream"}
+VARIANT_NAMES = {0: "auto", 1: "wave", 2: "block", 3: "generic", 4: "subwave", 5: "unaligned", 6: "stream", 7: "packed"}
 
 _lib = None
 

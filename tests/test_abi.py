@@ -96,7 +96,7 @@ def test_empty_batch_is_a_successful_no_op():
 
 def test_unknown_variant_and_unsupported_shapes():
     lib = binding.load()
-    assert lib.rmsnorm_fwd_variant(P, P + 4096, P + 8192, 4, 8, 1e-6, 2, None, 8) == \
+    assert lib.rmsnorm_fwd_variant(P, P + 4096, P + 8192, 4, 8, 1e-6, 2, None, 1000) == \
         binding.RMSNORM_ERR_INVALID_ARG
     assert lib.rmsnorm_fwd_variant(P, P + 4096, P + 8192, 4, 8, 1e-6, 2, None, -1) == \
         binding.RMSNORM_ERR_INVALID_ARG

@@ -48,7 +48,13 @@ def test_empty_batch_unknown_variant_and_unsupported_shapes():
     lib = layernorm.load()
     W, B, Y = P + 2 * BIG, P + 3 * BIG, P + BIG
     assert lib.layernorm_fwd(None, None, None, None, 0, 16, 1e-5, 2, None) == layernorm.LAYERNORM_OK
-    assert lib.layernorm_fwd_variant(P, W, B, Y, 4, 8, 1e-5, 2, None, 9) == layernorm.LAYERNORM_ERR_INVALID_ARG
+    assert lib.layernorm_fwd_variant(P, W, B, Y, 4, 8, 1e-5, 2, None, 1000) == layernorm.LAYERNORM_ERR_INVALID_ARG
+    assert lib.layernorm_fwd_variant(P, W, B, Y, 4, 8, 1e-5, 2, None, 8) == layernorm.LAYERNORM_ERR_INVALID_ARG
+    # the LDS-staged kernel takes at most 512 elements, and x and y congruent modulo 16 bytes
+    for dtype in (0, 1, 2):
+        assert lib.layernorm_fwd_variant(P, W, B, Y, 4, 513, 1e-5, dtype, None, 7) == layernorm.LAYERNORM_ERR_UNSUPPORTED
+    assert lib.layernorm_fwd_variant(P + 2, W, B, Y + 6, 4, 77, 1e-5, 2, None, 7) == layernorm.LAYERNORM_ERR_UNSUPPORTED
+    assert lib.layernorm_fwd_variant(P + 2, W, B, Y + 18, 0, 77, 1e-5, 2, None, 7) == layernorm.LAYERNORM_OK
     assert lib.layernorm_fwd_variant(P, W, B, Y, 4, 8, 1e-5, 2, None, -1) == layernorm.LAYERNORM_ERR_INVALID_ARG
     for bad in (0, 4, 128, 2048):
         assert lib.layernorm_fwd_tuned(P, W, B, Y, 4, 4096, 1e-5, 2, None, bad) == layernorm.LAYERNORM_ERR_INVALID_ARG

@@ -94,3 +94,100 @@ def test_rmsnorm_packed_more_tiles_than_the_grid(gpu_device):
     M, N = 8192 * 8 + 13, 511
     case = inputs.random_case(6, 960, M, N, inputs.FP32, 1e-6)
     H.check_case(case, gpu_device, variants=(binding.RMSNORM_VARIANT_PACKED,))
+
+
+# ---- softmax -----------------------------------------------------------------------------------
+import test_softmax_gpu as SM
+from paper_2603_21331_amd import softmax
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("N", LENGTHS)
+def test_softmax_packed_lengths(gpu_device, N, dtype):
+    rows_per_tile = 16384 // (N * inputs.DTYPE_BYTES[dtype])
+    M = 2 * rows_per_tile + 5 if rows_per_tile < 3000 else 4099
+    case = inputs.softmax_case(6, 1000 + 2 * dtype, M, N, dtype, 2.5)
+    if N > 2:                       # masked scores and one fully masked row (NaN by definition)
+        neg_inf = {inputs.FP32: np.float32(-np.inf), inputs.FP16: 0xFC00, inputs.BF16: 0xFF80}[dtype]
+        case["x"][::5, N // 2] = neg_inf
+        case["x"][7, :] = neg_inf
+    want = oracle.softmax_oracle(case["x"], dtype)
+    SM.check(case, gpu_device, modes=(0, softmax.SOFTMAX_VARIANT_PACKED, softmax.SOFTMAX_VARIANT_GENERIC), want=want)
+    per16 = 16 // inputs.DTYPE_BYTES[dtype]
+    xd = offset_view(case["x"], dtype, gpu_device, 1, (M, N))
+    for mode in (0, softmax.SOFTMAX_VARIANT_PACKED):
+        whole, y = H.alloc_guarded(M, N, dtype, gpu_device, offset_elems=1 + 2 * per16)
+        H.say(f"softmax packed offset bases {inputs.DTYPE_NAMES[dtype]} {M}x{N} mode={mode}")
+        softmax.softmax_fwd_variant(xd, mode, y)
+        torch.cuda.synchronize()
+        assert H.guards_intact(whole, M, N, dtype, offset_elems=1 + 2 * per16)
+        compare.check_softmax_parity(H.to_host(y, dtype), want, dtype, f"softmax packed offset bases mode {mode}")
+    whole, y = H.alloc_guarded(M, N, dtype, gpu_device, offset_elems=2)
+    with pytest.raises(softmax.SoftmaxError) as e:
+        softmax.softmax_fwd_variant(xd, softmax.SOFTMAX_VARIANT_PACKED, y)
+    assert e.value.status == softmax.SOFTMAX_ERR_UNSUPPORTED
+    softmax.softmax_fwd(xd, y)      # the automatic path takes another kernel
+    torch.cuda.synchronize()
+    assert H.guards_intact(whole, M, N, dtype, offset_elems=2)
+    compare.check_softmax_parity(H.to_host(y, dtype), want, dtype, "softmax, x and y at different offsets")
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_softmax_packed_attention_shapes_in_place(gpu_device, dtype):
+    """Square attention-score blocks with odd context lengths, in place, twice for determinism."""
+    for n in (77, 197, 257):
+        M = 12 * n
+        case = inputs.softmax_case(6, 1020 + 2 * dtype, M, n, dtype, 3.0)
+        want = oracle.softmax_oracle(case["x"], dtype)
+        xd = H.to_device(case["x"], dtype, gpu_device)
+        first = H.to_host(softmax.softmax_fwd_variant(xd, softmax.SOFTMAX_VARIANT_PACKED), dtype).copy()
+        compare.check_softmax_parity(first, want, dtype, f"softmax packed {n}")
+        again = H.to_host(softmax.softmax_fwd_variant(xd, softmax.SOFTMAX_VARIANT_PACKED), dtype)
+        assert np.array_equal(again.view(np.uint8), first.view(np.uint8))
+        H.say(f"softmax packed in place n={n}")
+        softmax.softmax_fwd_variant(xd, softmax.SOFTMAX_VARIANT_PACKED, xd)
+        torch.cuda.synchronize()
+        assert np.array_equal(H.to_host(xd, dtype).view(np.uint8), first.view(np.uint8))
+
+
+# ---- LayerNorm ---------------------------------------------------------------------------------
+import test_layernorm_gpu as LN
+from paper_2603_21331_amd import layernorm
+
+
+@pytest.mark.parametrize("bias", [True, False])
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("N", LENGTHS)
+def test_layernorm_packed_lengths(gpu_device, N, dtype, bias):
+    rows_per_tile = 16384 // (N * inputs.DTYPE_BYTES[dtype])
+    M = 2 * rows_per_tile + 5 if rows_per_tile < 3000 else 4099
+    case = inputs.layernorm_case(6, 1040 + 4 * dtype, M, N, dtype, 1e-5, mean=3.0, std=2.0, bias=bias)
+    LN.check(case, gpu_device, modes=(0, layernorm.LAYERNORM_VARIANT_PACKED, layernorm.LAYERNORM_VARIANT_GENERIC))
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_layernorm_packed_offset_bases_and_in_place(gpu_device, dtype):
+    M, N = 3001, 197
+    case = inputs.layernorm_case(6, 1060 + 4 * dtype, M, N, dtype, 1e-5, mean=-2.0, std=0.5)
+    want, mean, rstd = oracle.layernorm_oracle(case["x"], case["w"], case["b"], 1e-5, dtype, stats=True)
+    bias64 = LN.scale_of(case, mean, rstd)
+    per16 = 16 // inputs.DTYPE_BYTES[dtype]
+    xd = offset_view(case["x"], dtype, gpu_device, 3, (M, N))
+    wd = offset_view(case["w"], dtype, gpu_device, 1, (N,))
+    bd = offset_view(case["b"], dtype, gpu_device, 2, (N,))
+    for mode in (0, layernorm.LAYERNORM_VARIANT_PACKED):
+        whole, y = H.alloc_guarded(M, N, dtype, gpu_device, offset_elems=3 + per16)
+        H.say(f"layernorm packed offset bases {inputs.DTYPE_NAMES[dtype]} mode={mode}")
+        layernorm.layernorm_fwd_variant(xd, wd, bd, 1e-5, mode, y)
+        torch.cuda.synchronize()
+        assert H.guards_intact(whole, M, N, dtype, offset_elems=3 + per16)
+        compare.check_layernorm_parity(H.to_host(y, dtype), want, bias64, dtype, f"layernorm packed offset mode {mode}")
+    first = H.to_host(y, dtype).copy()
+    whole, y2 = H.alloc_guarded(M, N, dtype, gpu_device, offset_elems=1)
+    with pytest.raises(layernorm.LayerNormError) as e:
+        layernorm.layernorm_fwd_variant(xd, wd, bd, 1e-5, layernorm.LAYERNORM_VARIANT_PACKED, y2)
+    assert e.value.status == layernorm.LAYERNORM_ERR_UNSUPPORTED
+    H.say("layernorm packed in place")
+    layernorm.layernorm_fwd_variant(xd, wd, bd, 1e-5, layernorm.LAYERNORM_VARIANT_PACKED, xd)
+    torch.cuda.synchronize()
+    assert np.array_equal(H.to_host(xd, dtype).view(np.uint8), first.view(np.uint8))

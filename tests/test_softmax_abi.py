@@ -45,7 +45,7 @@ def test_invalid_arguments_are_rejected_without_a_launch(args):
 def test_empty_batch_unknown_variant_and_unsupported_shapes():
     lib = softmax.load()
     assert lib.softmax_fwd(None, None, 0, 16, 2, None) == softmax.SOFTMAX_OK
-    assert lib.softmax_fwd_variant(P, P + BIG, 4, 8, 2, None, 9) == softmax.SOFTMAX_ERR_INVALID_ARG
+    assert lib.softmax_fwd_variant(P, P + BIG, 4, 8, 2, None, 1000) == softmax.SOFTMAX_ERR_INVALID_ARG
     assert lib.softmax_fwd_variant(P, P + BIG, 4, 8, 2, None, -1) == softmax.SOFTMAX_ERR_INVALID_ARG
     for bad in (0, 4, 128, 2048):
         assert lib.softmax_fwd_tuned(P, P + BIG, 4, 4096, 2, None, bad) == softmax.SOFTMAX_ERR_INVALID_ARG
@@ -63,7 +63,12 @@ def test_empty_batch_unknown_variant_and_unsupported_shapes():
     # the streaming kernel takes any N below 2^31
     assert lib.softmax_fwd_variant(P, P + BIG, 0, 1 << 30, 2, None, 6) == softmax.SOFTMAX_OK
     assert lib.softmax_fwd_variant(P, P + BIG, 1, 1 << 31, 2, None, 6) == softmax.SOFTMAX_ERR_UNSUPPORTED
-    assert lib.softmax_fwd_variant(P, P + BIG, 1, 8, 2, None, 7) == softmax.SOFTMAX_ERR_INVALID_ARG
+    assert lib.softmax_fwd_variant(P, P + BIG, 1, 8, 2, None, 8) == softmax.SOFTMAX_ERR_INVALID_ARG
+    # the LDS-staged kernel takes at most 512 elements, and x and y congruent modulo 16 bytes
+    for dtype in (0, 1, 2):
+        assert lib.softmax_fwd_variant(P, P + BIG, 4, 513, dtype, None, 7) == softmax.SOFTMAX_ERR_UNSUPPORTED
+    assert lib.softmax_fwd_variant(P + 2, P + BIG + 6, 4, 77, 2, None, 7) == softmax.SOFTMAX_ERR_UNSUPPORTED
+    assert lib.softmax_fwd_variant(P + 2, P + BIG + 18, 0, 77, 2, None, 7) == softmax.SOFTMAX_OK
 
 
 def test_automatic_threads_per_row():
