@@ -24,8 +24,13 @@ int elem_bytes(int dtype) {
   }
 }
 
+// threads_per_row == kPackedCode selects the LDS-staged kernel (lane-group width from N).
+constexpr int kPackedCode = 2;
+constexpr int64_t kPackedMaxN = 64 * rms::kPackElems;
+constexpr int64_t kPackedMaxGrid = 8192;
+
 bool threads_ok(int g) {
-  return g == 1 || g == 8 || g == 16 || g == 32 ||
+  return g == 1 || g == kPackedCode || g == 8 || g == 16 || g == 32 ||
          (g >= kWave && g <= kMaxThreads && g % kWave == 0);
 }
 
@@ -60,6 +65,9 @@ int pick_threads(int64_t N, int dtype, bool aligned) {
     if (groups <= 64) return 16;
     if (groups <= (dtype == CROSSENTROPY_DTYPE_FP32 ? 128 : 256)) return 32;
   }
+  // Rows of up to 512 classes that are not whole aligned vectors: several per workgroup
+  // through LDS (fp16 N = 100: 0.55 TB/s with one workgroup per row).
+  if (!aligned && N <= kPackedMaxN) return kPackedCode;
   const int64_t per_thread = dtype == CROSSENTROPY_DTYPE_FP32 ? kBatch : 2 * kBatch;
   const int64_t want = (groups + per_thread - 1) / per_thread;
   if (want >= kMaxThreads) return kMaxThreads;
@@ -91,9 +99,40 @@ void launch_subwave(const void* x, const int64_t* target, float* loss, float* ls
                      dim3(kWave), 0, stream, (const rms::u32x4*)x, target, loss, lse, M, N, nvec);
 }
 
+template <int DT, int L, int E>
+void launch_packed(const void* x, const int64_t* target, float* loss, float* lse, int64_t M,
+                   int64_t N, hipStream_t stream) {
+  int tile_rows = rms::kPackTileBytes / ((int)N * rms::Storage<DT>::kBytes);
+  if (tile_rows > M) tile_rows = (int)M;
+  int64_t blocks = (M + tile_rows - 1) / tile_rows;
+  if (blocks > kPackedMaxGrid) blocks = kPackedMaxGrid;   // beyond 128 MiB a workgroup takes several tiles
+  hipLaunchKernelGGL((rms::crossentropy_packed_kernel<DT, L, E, true>), dim3((unsigned)blocks),
+                     dim3(rms::kPackThreads), 0, stream, x, target, loss, lse, M, (int)N, tile_rows);
+}
+
+// Elements per lane: what the row needs in the chosen lane group, at least 5.
+template <int DT, int L>
+void launch_packed_lanes(const void* x, const int64_t* target, float* loss, float* lse, int64_t M,
+                         int64_t N, hipStream_t stream) {
+  switch ((N + L - 1) / L) {
+    case 8: launch_packed<DT, L, 8>(x, target, loss, lse, M, N, stream); break;
+    case 7: launch_packed<DT, L, 7>(x, target, loss, lse, M, N, stream); break;
+    case 6: launch_packed<DT, L, 6>(x, target, loss, lse, M, N, stream); break;
+    default: launch_packed<DT, L, 5>(x, target, loss, lse, M, N, stream); break;
+  }
+}
+
 template <int DT>
 int run_typed(const void* x, const int64_t* target, float* loss, float* lse, int64_t M, int64_t N,
               hipStream_t stream, int threads) {
+  if (threads == kPackedCode) {
+    const int64_t lanes = (N + rms::kPackElems - 1) / rms::kPackElems;   // lanes the row needs
+    if (lanes <= 8) launch_packed_lanes<DT, 8>(x, target, loss, lse, M, N, stream);
+    else if (lanes <= 16) launch_packed_lanes<DT, 16>(x, target, loss, lse, M, N, stream);
+    else if (lanes <= 32) launch_packed_lanes<DT, 32>(x, target, loss, lse, M, N, stream);
+    else launch_packed_lanes<DT, 64>(x, target, loss, lse, M, N, stream);
+    return hipGetLastError() == hipSuccess ? CROSSENTROPY_OK : CROSSENTROPY_ERR_LAUNCH;
+  }
   if (threads == 1) {
     int64_t blocks = (M + rms::kCeLaneThreads - 1) / rms::kCeLaneThreads;
     if (blocks > kMaxGrid) blocks = kMaxGrid;
@@ -125,7 +164,9 @@ int run(const void* x, const int64_t* target, float* loss, float* lse, int64_t M
   if (threads == 0) {
     const bool aligned = ((uintptr_t)x & 15u) == 0 && (N * b) % 16 == 0;
     threads = pick_threads(N, dtype, aligned);
-  } else if (threads == 1 ? N > kLaneMaxN : (threads < kWave && !subwave_can(x, N, dtype, threads))) {
+  } else if (threads == 1 ? N > kLaneMaxN
+             : threads == kPackedCode ? N > kPackedMaxN
+                                      : (threads < kWave && !subwave_can(x, N, dtype, threads))) {
     return CROSSENTROPY_ERR_UNSUPPORTED;
   }
   hipStream_t s = static_cast<hipStream_t>(stream);

@@ -19,6 +19,7 @@
 
 #include "vec_io.h"
 #include "wave_reduce.h"
+#include "packed_rows.h"
 
 namespace rms {
 
@@ -208,6 +209,57 @@ crossentropy_subwave_kernel(const u32x4* x, const int64_t* __restrict__ target,
       if (cls >= 0 && cls < N) out = log_s - (S::load_one(x, row * N + cls) - row_m);
       loss[row] = out;
     }
+  }
+}
+
+// Up to 512 classes in rows that are not 16-byte aligned (100 classes in fp16, 1000 / 3 of
+// anything): runs of whole rows, up to 16 KiB, are copied into LDS with aligned 128-bit loads
+// that are contiguous across the workgroup (see packed_rows.h), and lane groups of L lanes take
+// one row each out of LDS, E = 5..8 logits per lane, with the same online pair and the same
+// DPP-only combination as the lane-group kernel above.  Nothing is written but one float per
+// row (two with the log-sum-exp), so any alignment of x will do.
+template <int DT, int L, int E, bool NT>
+__global__ void __launch_bounds__(kPackThreads)
+crossentropy_packed_kernel(const void* x, const int64_t* __restrict__ target, float* __restrict__ loss,
+                           float* __restrict__ lse_out, int64_t M, int N, int tile_rows) {
+  using S = Storage<DT>;
+  constexpr int GROUPS = kPackThreads / L;
+  __shared__ u32x4 tile[kPackLdsVecs];
+  const int t = threadIdx.x;
+  const int sub = t % L;
+  const int group = t / L;
+
+  for (int64_t r0 = (int64_t)blockIdx.x * tile_rows; r0 < M; r0 += (int64_t)gridDim.x * tile_rows) {
+    const int rows = (int)(M - r0 < tile_rows ? M - r0 : tile_rows);
+    const char* src = static_cast<const char*>(x) + r0 * N * S::kBytes;
+    const TileCut cut = tile_cut(src, rows * N * S::kBytes);
+    const int origin = cut.skew / S::kBytes;               // tile element of the run's first element
+    tile_fill<DT, NT>(src, tile, cut, t);
+    __syncthreads();
+    for (int first = 0; first < rows; first += GROUPS) {   // the same trip count for every thread
+      const int r = first + group;
+      const int at = origin + (r < rows ? r : rows - 1) * N;
+      float f[E];
+#pragma unroll
+      for (int i = 0; i < E; ++i) {
+        const int j = sub + i * L;
+        f[i] = j < N ? tile_get<DT>(tile, at + j) : kCeNegInf;
+      }
+      float m = kCeNegInf, s = 0.f;
+      ce_fold<E>(f, m, s);
+      const float row_m = group_max<L>(m);
+      const float row_s = group_sum<L>(s * ce_rescale(m, row_m));
+      if (r < rows && sub == 0) {
+        const int64_t row = r0 + r;
+        const float log_s = row_m == kCeNegInf ? __builtin_nanf("") : __builtin_logf(row_s);
+        if (lse_out) lse_out[row] = row_m + log_s;
+        const int64_t cls = target[row];
+        float out = 0.0f;                                  // target outside [0, N): ignored row
+        if (cls >= 0 && cls < N) out = log_s - (tile_get<DT>(tile, at + (int)cls) - row_m);
+        loss[row] = out;
+      }
+    }
+    __syncthreads();                                       // the next step refills the tile
   }
 }
 

@@ -48,7 +48,7 @@ def test_empty_batch_and_bad_thread_counts():
     lib = ce.load()
     assert lib.crossentropy_fwd(None, None, None, None, 0, 16, 2, None) == ce.CROSSENTROPY_OK
     assert lib.crossentropy_fwd_tuned(None, None, None, None, 0, 16, 2, None, 64) == ce.CROSSENTROPY_OK
-    for bad in (0, 2, 4, 24, 48, 100, 1088, 2048, -64, -1):
+    for bad in (0, 3, 4, 24, 48, 100, 1088, 2048, -64, -1):
         assert lib.crossentropy_fwd_tuned(P, P + BIG, P + 2 * BIG, None, 4, 4096, 2, None, bad) == \
             ce.CROSSENTROPY_ERR_INVALID_ARG
 
@@ -64,6 +64,10 @@ def test_lane_groups_refuse_rows_they_cannot_take():
         assert f(P + 2, P + BIG, P + 2 * BIG, None, 4, 64, 1, None, lanes) == ce.CROSSENTROPY_ERR_UNSUPPORTED  # base off by 2 bytes
         assert f(P, P + BIG, P + 2 * BIG, None, 0, 64, 1, None, lanes) == ce.CROSSENTROPY_OK  # empty batch
     assert "thread count" in ce.crossentropy_status_string(ce.CROSSENTROPY_ERR_UNSUPPORTED)
+    # the LDS-staged kernel (code 2): any alignment, at most 512 classes
+    assert f(P + 2, P + BIG, P + 2 * BIG, None, 4, 513, 1, None, 2) == ce.CROSSENTROPY_ERR_UNSUPPORTED
+    assert f(P, P + BIG, P + 2 * BIG, None, 4, 4096, 0, None, 2) == ce.CROSSENTROPY_ERR_UNSUPPORTED
+    assert f(P + 2, P + BIG, P + 2 * BIG, None, 0, 100, 1, None, 2) == ce.CROSSENTROPY_OK
     # one lane per row: any alignment, at most 64 classes
     assert f(P, P + BIG, P + 2 * BIG, None, 4, 65, 1, None, 1) == ce.CROSSENTROPY_ERR_UNSUPPORTED
     assert f(P, P + BIG, P + 2 * BIG, None, 4, 4096, 0, None, 1) == ce.CROSSENTROPY_ERR_UNSUPPORTED
@@ -75,7 +79,9 @@ def test_automatic_threads_per_row():
     for dtype in (0, 1, 2):
         for n in (1, 7, 10, 31):             # rows shorter than 128 bytes: one lane per row
             assert auto(n, dtype) == 1
-        for n in (65, 130, 1001):            # longer rows that are not whole 16-byte vectors
+        for n in (65, 130, 511):             # up to 512 classes, not whole 16-byte vectors: through LDS
+            assert auto(n, dtype) == 2
+        for n in (513, 1001):                # longer rows that are not whole 16-byte vectors
             assert auto(n, dtype) == 64
     assert auto(63, 1) == 1 and auto(64, 1) == 8 and auto(31, 0) == 1 and auto(32, 0) == 8
     # few classes in whole vectors: lane groups, at most 32 / 64 / 256 (fp32: 128) vectors per row

@@ -14,9 +14,10 @@ from paper_2603_21331_amd import inputs
 pytestmark = pytest.mark.gpu
 
 DTYPES = [inputs.FP32, inputs.FP16, inputs.BF16]
-MODES = (0, 1, 8, 16, 32, 64, 128, 256, 320, 512, 1024)  # threads per row; 0 = automatic; 8, 16 and 32
-                                                          # (lane groups) only take short aligned rows,
-                                                          # 1 (a lane per row) at most 64 classes
+MODES = (0, 1, 2, 8, 16, 32, 64, 128, 256, 320, 512, 1024)  # threads per row; 0 = automatic; 8, 16 and 32
+                                                             # (lane groups) only take short aligned rows,
+                                                             # 1 (a lane per row) at most 64 classes, 2
+                                                             # (rows through LDS) at most 512
 GUARD = 16
 SENTINEL = -12345.0
 
@@ -209,7 +210,7 @@ def test_determinism_and_row_independence(gpu_device, N):
         for i in (0, 333, 776):
             one = ce.crossentropy_fwd_tuned(xd[i:i + 1], td[i:i + 1], m)
             assert one.cpu().numpy().view(np.uint32)[0] == first[i]
-    assert ran == {5000: 7, 1000: 9, 96: 10, 24: 11}[N]
+    assert ran == {5000: 7, 1000: 9, 96: 11, 24: 12}[N]
 
 
 # stage 5: edge cases
@@ -230,8 +231,8 @@ def test_base_pointer_aligned_to_one_element_only(gpu_device, dtype):
     want = oracle.crossentropy_oracle(case["x"], case["target"], dtype)
     for m in MODES:
         loss, _ = run_mode(xd, td, m, "offset base")
-        if m in (1, 8, 16, 32):
-            assert loss is None, "lane groups must refuse a base that is not 16-byte aligned, a lane 1001 classes"
+        if m in (1, 2, 8, 16, 32):
+            assert loss is None, "lane groups must refuse a base that is not 16-byte aligned, the others 1001 classes"
             continue
         compare.check_crossentropy_parity(loss, want, f"offset base [threads {m}]")
 
@@ -244,8 +245,8 @@ def test_few_classes_lane_groups(gpu_device, N, dtype):
     takes the shape, the automatic choice and one workgroup per row all agree with the oracle."""
     M = 1027
     case = inputs.crossentropy_case(5, 1760 + 4 * dtype, M, N, dtype, 2.0, ignore_every=11)
-    stats = check(case, gpu_device, modes=(0, 1, 8, 16, 32, 64))
-    assert (1 in stats) == (N <= 64)
+    stats = check(case, gpu_device, modes=(0, 1, 2, 8, 16, 32, 64))
+    assert (1 in stats) == (N <= 64) and (2 in stats) == (N <= 512)
     nvec = N * inputs.DTYPE_BYTES[dtype] // 16
     took = sorted(m for m in stats if m in (8, 16, 32))
     assert took == [l for l in (8, 16, 32) if N * inputs.DTYPE_BYTES[dtype] % 16 == 0 and nvec <= 8 * l]
@@ -303,3 +304,36 @@ def test_handful_of_classes_one_lane_per_row(gpu_device, N, dtype):
         loss, _ = run_mode(xd, td, m, "handful, offset base")
         compare.check_crossentropy_parity(loss, want, f"handful offset base [threads {m}]",
                                           exact_zero=(t < 0) | (t >= N))
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("N", [65, 77, 100, 127, 129, 197, 255, 257, 300, 333, 511, 512])
+def test_up_to_512_classes_through_lds(gpu_device, N, dtype):
+    """Rows that are not whole aligned vectors, several per workgroup through LDS: two full
+    tiles and a partial one, masked classes, ignored targets, and a base pointer one element
+    off; the automatic path must choose this kernel for the odd lengths."""
+    rows_per_tile = 16384 // (N * inputs.DTYPE_BYTES[dtype])
+    M = 2 * rows_per_tile + 5
+    case = inputs.crossentropy_case(5, 1840 + 4 * dtype, M, N, dtype, 3.0, ignore_every=13)
+    neg_inf = {inputs.FP32: np.float32(-np.inf), inputs.FP16: 0xFC00, inputs.BF16: 0xFF80}[dtype]
+    case["x"][::3, N // 2] = neg_inf
+    stats = check(case, gpu_device, modes=(0, 2, 64))
+    assert 2 in stats
+    if N * inputs.DTYPE_BYTES[dtype] % 16:
+        assert ce.crossentropy_auto_threads_per_row(N, dtype) == 2
+    flat = np.concatenate([np.zeros(1, dtype=case["x"].dtype), case["x"].reshape(-1)])
+    xd = H.to_device(flat, dtype, gpu_device)[1:].view(M, N)
+    td = torch.from_numpy(case["target"]).to(gpu_device)
+    want = oracle.crossentropy_oracle(case["x"], case["target"], dtype)
+    t = case["target"]
+    for m in (0, 2):
+        loss, _ = run_mode(xd, td, m, "through LDS, offset base")
+        compare.check_crossentropy_parity(loss, want, f"through LDS, offset base [threads {m}]",
+                                          exact_zero=(t < 0) | (t >= N))
+
+
+def test_through_lds_more_tiles_than_the_grid(gpu_device):
+    """The grid stops at 8192 workgroups: 8 rows of 2 KiB per tile, 65536 + 13 rows."""
+    M, N = 8192 * 8 + 13, 511
+    case = inputs.crossentropy_case(5, 1860, M, N, inputs.FP32, 2.0, ignore_every=1000)
+    check(case, gpu_device, modes=(2,))
