@@ -34,10 +34,10 @@ bool threads_ok(int g) {
          (g >= kWave && g <= kMaxThreads && g % kWave == 0);
 }
 
-// One lane per row: what the forced choice accepts, and where the automatic path takes it
-// (rows shorter than 128 bytes; from there on a lane group of 8 has a vector for every lane).
+// One lane per row: what the forced choice accepts, and where the automatic path takes it.
 constexpr int64_t kLaneMaxN = 64;
-constexpr int64_t kLaneAutoBytes = 128;
+constexpr int64_t kLaneAutoN = 32;           // automatic below this many classes
+constexpr int64_t kPackedAutoBytes = 256;    // aligned rows shorter than this also go through LDS
 
 // Lane groups take 16-byte aligned rows of at most 8 vectors per lane.
 constexpr int kSubwaveMaxChunks = 8;
@@ -55,7 +55,11 @@ bool subwave_can(const void* x, int64_t N, int dtype, int lanes) {
 // more than 512 threads pay off only once every thread of 1024 still gets that much.
 int pick_threads(int64_t N, int dtype, bool aligned) {
   const int b = elem_bytes(dtype);
-  if (N * b < kLaneAutoBytes) return 1;
+  // From sweeps over rows of 16 bytes to 2 KiB: one lane per row below 32 classes; from there
+  // up to 256 bytes per row the LDS-staged kernel beats the lane groups even on aligned rows
+  // (fp16 N = 64: 37 against 51 us per 64 MiB).
+  if (N < kLaneAutoN) return 1;
+  if (N * b < kPackedAutoBytes) return kPackedCode;
   const int64_t groups = N / (16 / b);
   // Few classes: 8, 16 or 32 lanes per row, four to eight vectors per lane.  Measured at
   // 128 MiB of fp16 logits: N = 128 64 us (one workgroup per row: 322), 256 53 (166), 512 48

@@ -12,6 +12,7 @@
 
 #include "vec_io.h"
 #include "wave_reduce.h"
+#include "packed_rows.h"
 
 namespace rms {
 
@@ -147,6 +148,71 @@ rowsum_subwave_kernel(const u32x4* x, float* __restrict__ y, int64_t M, int nvec
     }
     const float total = subwave_sum<L>(rs_fold<VEC>(acc));
     if (row_ok && s == 0) y[row] = total;
+  }
+}
+
+// Rows of up to 512 elements that are not whole aligned vectors (100 elements in fp16, a base
+// pointer off a boundary): runs of whole rows, up to 16 KiB, are copied into LDS with aligned
+// 128-bit loads that are contiguous across the workgroup (see packed_rows.h), and lane groups
+// of L lanes add one row each out of LDS, E = 5..8 elements per lane in index order, then the
+// DPP butterfly inside the group.  Only one float per row is written, so any alignment of x
+// will do.
+template <int DT, int L, int E, bool NT>
+__global__ void __launch_bounds__(kPackThreads)
+rowsum_packed_kernel(const void* x, float* __restrict__ y, int64_t M, int N, int tile_rows) {
+  using S = Storage<DT>;
+  constexpr int GROUPS = kPackThreads / L;
+  __shared__ u32x4 tile[kPackLdsVecs];
+  const int t = threadIdx.x;
+  const int sub = t % L;
+  const int group = t / L;
+
+  for (int64_t r0 = (int64_t)blockIdx.x * tile_rows; r0 < M; r0 += (int64_t)gridDim.x * tile_rows) {
+    const int rows = (int)(M - r0 < tile_rows ? M - r0 : tile_rows);
+    const char* src = static_cast<const char*>(x) + r0 * N * S::kBytes;
+    const TileCut cut = tile_cut(src, rows * N * S::kBytes);
+    const int origin = cut.skew / S::kBytes;               // tile element of the run's first element
+    tile_fill<DT, NT>(src, tile, cut, t);
+    __syncthreads();
+    for (int first = 0; first < rows; first += GROUPS) {   // the same trip count for every thread
+      const int r = first + group;
+      const int at = origin + (r < rows ? r : rows - 1) * N;
+      float acc = 0.f;
+#pragma unroll
+      for (int i = 0; i < E; ++i) {
+        const int j = sub + i * L;
+        acc += j < N ? tile_get<DT>(tile, at + j) : 0.f;
+      }
+      const float total = group_sum<L>(acc);
+      if (r < rows && sub == 0) y[r0 + r] = total;
+    }
+    __syncthreads();                                       // the next step refills the tile
+  }
+}
+
+// A handful of elements per row (rows shorter than 128 bytes, any alignment): one row per
+// lane.  Neighbouring lanes read neighbouring rows, so a wavefront's loads still fall into a
+// few contiguous cache lines.  Four running sums, folded at the end: no element passes through
+// more than N / 4 + 2 additions.
+constexpr int kRsLaneThreads = 256;
+
+template <int DT>
+__global__ void __launch_bounds__(kRsLaneThreads)
+rowsum_lane_kernel(const void* x, float* __restrict__ y, int64_t M, int N) {
+  using S = Storage<DT>;
+  for (int64_t row = (int64_t)blockIdx.x * kRsLaneThreads + threadIdx.x; row < M;
+       row += (int64_t)gridDim.x * kRsLaneThreads) {
+    const int64_t at = row * N;
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    int j = 0;
+    for (; j + 4 <= N; j += 4) {
+      acc[0] += S::load_one(x, at + j);
+      acc[1] += S::load_one(x, at + j + 1);
+      acc[2] += S::load_one(x, at + j + 2);
+      acc[3] += S::load_one(x, at + j + 3);
+    }
+    for (int k = 0; j < N; ++j, ++k) acc[k] += S::load_one(x, at + j);
+    y[row] = (acc[0] + acc[1]) + (acc[2] + acc[3]);
   }
 }
 

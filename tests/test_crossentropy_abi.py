@@ -83,9 +83,11 @@ def test_automatic_threads_per_row():
             assert auto(n, dtype) == 2
         for n in (513, 1001):                # longer rows that are not whole 16-byte vectors
             assert auto(n, dtype) == 64
-    assert auto(63, 1) == 1 and auto(64, 1) == 8 and auto(31, 0) == 1 and auto(32, 0) == 8
+    assert auto(31, 1) == 1 and auto(31, 0) == 1
+    # from 32 classes up to 256 bytes per row: through LDS, aligned or not
+    assert auto(32, 1) == 2 and auto(64, 1) == 2 and auto(120, 2) == 2 and auto(32, 0) == 2 and auto(60, 0) == 2
     # few classes in whole vectors: lane groups, at most 32 / 64 / 256 (fp32: 128) vectors per row
-    assert auto(128, 1) == 8 and auto(256, 2) == 8 and auto(264, 2) == 16
+    assert auto(128, 1) == 8 and auto(64, 0) == 8 and auto(256, 2) == 8 and auto(264, 2) == 16
     assert auto(512, 1) == 16 and auto(520, 1) == 32 and auto(1000, 1) == 32 and auto(1024, 2) == 32
     assert auto(2048, 1) == 32 and auto(2056, 2) == 64 and auto(128, 0) == 8 and auto(132, 0) == 16
     assert auto(256, 0) == 16 and auto(512, 0) == 32 and auto(516, 0) == 64 and auto(1000, 0) == 64

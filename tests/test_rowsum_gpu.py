@@ -34,6 +34,10 @@ def modes_for(N, dtype, aligned=True):
     modes = list(BLOCK_MODES)
     if aligned and N % vec == 0:
         modes += [g for g in (8, 16, 32) if N // vec <= 8 * g]
+    if N <= 64:
+        modes.append(1)          # one lane per row
+    if N <= 512:
+        modes.append(2)          # runs of rows through LDS
     return modes
 
 
@@ -211,3 +215,33 @@ def test_empty_batch_and_binding_checks(gpu_device):
         rs.rowsum_fwd(x.double())
     with pytest.raises(rs.RowSumError):
         rs.rowsum_fwd_tuned(x, 96)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("N", [1, 2, 3, 5, 10, 17, 31, 33, 63, 64, 65, 77, 100, 127, 129, 197, 255, 257, 300, 511, 512])
+def test_short_rows_any_alignment(gpu_device, N, dtype):
+    """Rows of 1 to 512 elements: one lane per row (up to 64), runs of rows through LDS (two full
+    tiles and a partial one), lane groups where the rows are whole aligned vectors, one workgroup
+    per row; then the same with the base pointer one element off a 16-byte boundary, where the
+    automatic path must still take the short-row kernels."""
+    rows_per_tile = 16384 // (N * inputs.DTYPE_BYTES[dtype])
+    M = 2 * rows_per_tile + 5 if rows_per_tile < 3000 else 4099
+    case = inputs.rowsum_case(5, 1900 + 4 * dtype, M, N, dtype, mean=0.25, std=2.0)
+    stats = check(case, gpu_device)
+    assert 2 in stats and (1 in stats) == (N <= 64)
+    want_y, want_abs = oracle.rowsum_oracle(case["x"], dtype, with_abs=True)
+    flat = np.concatenate([np.zeros(1, dtype=case["x"].dtype), case["x"].reshape(-1)])
+    xd = H.to_device(flat, dtype, gpu_device)[1:].view(M, N)
+    for m in [0, 2, 64] + ([1] if N <= 64 else []):
+        y = run_mode(xd, m, "short rows, offset base")
+        compare.check_rowsum_parity(y, want_y, want_abs, N, f"short rows, offset base [threads {m}]")
+    for m in (8, 16, 32):
+        with pytest.raises(rs.RowSumError):
+            rs.rowsum_fwd_tuned(xd, m)
+
+
+def test_through_lds_more_tiles_than_the_grid(gpu_device):
+    """The grid stops at 8192 workgroups: 8 rows of 2 KiB per tile, 65536 + 13 rows."""
+    M, N = 8192 * 8 + 13, 511
+    case = inputs.rowsum_case(5, 1920, M, N, inputs.FP32)
+    check(case, gpu_device, modes=(2,))
