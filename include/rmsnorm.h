@@ -76,7 +76,8 @@ typedef enum {
   RMSNORM_VARIANT_PACKED = 7    /* runs of short rows copied through LDS with 128-bit accesses,
                                    8 to 64 lanes per row; N <= 512, any alignment as long as x
                                    and y are congruent modulo 16 bytes; what rows that are not
-                                   16-byte aligned take up to that length */
+                                   16-byte aligned take up to that length, and aligned
+                                   rows of at most 64 bytes */
 } rmsnorm_variant;
 
 /*

@@ -177,6 +177,9 @@ void launch_row_unaligned(const Args& a, int nfull) {
 // the same offset from a 16-byte boundary, which its tile mirrors.
 constexpr int64_t kPackedMaxN = 64 * rms::kPackElems;
 constexpr int64_t kPackedMaxGrid = 8192;
+// Aligned rows of at most 64 bytes also take it: one to four of the eight lanes of the
+// narrowest lane group would hold a vector, and the LDS-staged kernel is 1.2 to 2 times faster.
+constexpr int64_t kPackedAutoVectors = 4;
 
 bool packed_can(const void* x, const void* y, int64_t N) {
   return N <= kPackedMaxN && ((reinterpret_cast<uintptr_t>(x) ^ reinterpret_cast<uintptr_t>(y)) & 15u) == 0;
@@ -350,7 +353,8 @@ int run(const void* x, const void* w, const void* b, void* y, int64_t M, int64_t
   const bool unaligned_fits = pick_threads_unaligned(N / (16 / elem_bytes(dtype))) != 0;
   switch (variant) {
     case LAYERNORM_VARIANT_AUTO:
-      threads = vec_ok ? pick_threads(nvec, 8, dtype) : packed_can(x, y, N) ? -3 : unaligned_fits ? -1 : 0;
+      threads = vec_ok ? (nvec <= kPackedAutoVectors ? -3 : pick_threads(nvec, 8, dtype))
+                       : packed_can(x, y, N) ? -3 : unaligned_fits ? -1 : 0;
       if (threads == 0 && N < kStreamMaxN) threads = -2;     // too long for registers
       break;
     case LAYERNORM_VARIANT_PACKED:

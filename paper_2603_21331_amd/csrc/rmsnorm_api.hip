@@ -123,13 +123,14 @@ constexpr int64_t kStreamMaxN = (int64_t)1 << 31;   // the streaming kernel coun
 // The LDS-staged kernel takes rows of at most 8 elements per lane of a 64-lane group at any
 // alignment, provided x and y sit at the same offset from a 16-byte boundary (its tile mirrors
 // that offset, so aligned vectors of x are aligned vectors of y); the automatic path uses it
-// for such rows when they are not 16-byte aligned.
+// for such rows when they are not 16-byte aligned, and for aligned rows of at most four vectors.
 constexpr int64_t kPackedMaxN = 64 * rms::kPackElems;
+constexpr int64_t kPackedMaxGrid = 8192;
+constexpr int64_t kPackedAutoVectors = 4;
 
 bool packed_can(const void* x, const void* y, int64_t N) {
   return N <= kPackedMaxN && ((reinterpret_cast<uintptr_t>(x) ^ reinterpret_cast<uintptr_t>(y)) & 15u) == 0;
 }
-constexpr int64_t kPackedMaxGrid = 8192;
 
 int choose(const void* x, const void* w, const void* y, int64_t N, int dtype) {
   if (!rows_vectorisable(x, w, y, N, dtype)) {
@@ -137,6 +138,9 @@ int choose(const void* x, const void* w, const void* y, int64_t N, int dtype) {
     if (pick_threads_unaligned(full_groups_per_row(N, dtype))) return RMSNORM_VARIANT_UNALIGNED;
     return N < kStreamMaxN ? RMSNORM_VARIANT_STREAM : RMSNORM_VARIANT_GENERIC;
   }
+  // Rows of at most 64 bytes leave most of the narrowest lane group idle (one to four of its
+  // eight lanes hold a vector): the LDS-staged kernel is 1.2 to 2.9 times faster there.
+  if (vectors_per_row(N, dtype) <= kPackedAutoVectors) return RMSNORM_VARIANT_PACKED;
   const int g = pick_threads(vectors_per_row(N, dtype), 8, dtype);
   if (g == 0) return N < kStreamMaxN ? RMSNORM_VARIANT_STREAM : RMSNORM_VARIANT_GENERIC;
   if (g < 64) return RMSNORM_VARIANT_SUBWAVE;

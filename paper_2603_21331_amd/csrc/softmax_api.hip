@@ -126,6 +126,9 @@ void launch_row_unaligned(const Args& a, int nfull) {
 // the same offset from a 16-byte boundary, which its tile mirrors.
 constexpr int64_t kPackedMaxN = 64 * rms::kPackElems;
 constexpr int64_t kPackedMaxGrid = 8192;
+// Aligned rows of at most 64 bytes also take it: one to four of the eight lanes of the
+// narrowest lane group would hold a vector, and the LDS-staged kernel is 1.2 to 2 times faster.
+constexpr int64_t kPackedAutoVectors = 4;
 
 bool packed_can(const void* x, const void* y, int64_t N) {
   return N <= kPackedMaxN && ((reinterpret_cast<uintptr_t>(x) ^ reinterpret_cast<uintptr_t>(y)) & 15u) == 0;
@@ -297,7 +300,8 @@ int run(const void* x, void* y, int64_t M, int64_t N, int dtype, void* stream, i
   const bool unaligned_fits = pick_threads_unaligned(N / (16 / elem_bytes(dtype))) != 0;
   switch (variant) {
     case SOFTMAX_VARIANT_AUTO:
-      threads = vec_ok ? pick_threads(nvec, 8) : packed_can(x, y, N) ? -3 : unaligned_fits ? -1 : 0;
+      threads = vec_ok ? (nvec <= kPackedAutoVectors ? -3 : pick_threads(nvec, 8))
+                       : packed_can(x, y, N) ? -3 : unaligned_fits ? -1 : 0;
       if (threads == 0 && N < kStreamMaxN) threads = -2;     // too long for registers
       break;
     case SOFTMAX_VARIANT_PACKED:

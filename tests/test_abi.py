@@ -181,6 +181,12 @@ def test_dispatch_choice_is_visible_without_a_launch():
     assert sel(P, P + 65536, P + 131072, 16, 13824, 1) == binding.RMSNORM_VARIANT_BLOCK
     assert sel(P, P + 65536, P + 131072, 16, 2040, 2) == binding.RMSNORM_VARIANT_WAVE
     assert sel(P, P + 65536, P + 131072, 16, 128, 2) == binding.RMSNORM_VARIANT_SUBWAVE
+    assert sel(P, P + 65536, P + 131072, 16, 40, 2) == binding.RMSNORM_VARIANT_SUBWAVE
+    # aligned rows of at most 64 bytes go through LDS like the unaligned ones
+    assert sel(P, P + 65536, P + 131072, 16, 32, 2) == binding.RMSNORM_VARIANT_PACKED
+    assert sel(P, P + 65536, P + 131072, 16, 8, 1) == binding.RMSNORM_VARIANT_PACKED
+    assert sel(P, P + 65536, P + 131072, 16, 16, 0) == binding.RMSNORM_VARIANT_PACKED
+    assert sel(P, P + 65536, P + 131072, 16, 20, 0) == binding.RMSNORM_VARIANT_SUBWAVE
     assert sel(P, P + 65536, P + 131072, 16, 1023, 1) == binding.RMSNORM_VARIANT_UNALIGNED
     assert sel(P + 2, P + 65536, P + 131072, 16, 1024, 1) == binding.RMSNORM_VARIANT_UNALIGNED
     assert sel(P, P + 65536, P + 131072, 16, 513, 1) == binding.RMSNORM_VARIANT_UNALIGNED
