@@ -64,7 +64,8 @@ bool threads_can(int threads, int64_t nvec) {
 // 16 lanes up to 24 vectors, 32 lanes up to 48; 5 to 11 % faster than the next wider
 // group), one wavefront up to 256 vectors, then 256, 512 and 1024 threads while a thread
 // holds at most 8 chunks; rows of 705 to 1024 vectors (N = 8192 in the 16-bit types) run 3 %
-// faster with two chunks in each of 512 threads than with four in 256.  0: does not fit.
+// faster with two chunks in each of 512 threads than with four in 256, and rows beyond 2048
+// vectors (a 32000-entry vocabulary) 2 to 3 % faster with 1024 threads.  0: does not fit.
 int pick_threads(int64_t nvec, int min_threads) {
   if (min_threads <= 8) {
     if (nvec <= 8) return 8;
@@ -73,6 +74,7 @@ int pick_threads(int64_t nvec, int min_threads) {
   }
   if (min_threads <= 64 && nvec <= kSmallRowVectors) return 64;
   if (nvec > 704 && nvec <= 1024 && min_threads <= 512) return 512;
+  if (nvec > 2048 && threads_can(kMaxThreads, nvec)) return kMaxThreads;   // 2 to 3 % over 512 threads
   for (int g = 256; g <= kMaxThreads; g *= 2)
     if (g >= min_threads && threads_can(g, nvec)) return g;
   return 0;

@@ -78,9 +78,9 @@ def test_automatic_threads_per_row():
     assert auto(96, 0) == 16 and auto(100, 0) == 32 and auto(192, 0) == 32 and auto(196, 0) == 64
     assert auto(2048, 2) == 64 and auto(4096, 1) == 256 and auto(5632, 1) == 256
     assert auto(5640, 1) == 512 and auto(8192, 1) == 512 and auto(8200, 1) == 256 and auto(4096, 0) == 512
-    assert auto(16384, 2) == 256 and auto(32768, 1) == 512 and auto(65536, 2) == 1024
+    assert auto(16384, 2) == 256 and auto(16392, 2) == 1024 and auto(32768, 1) == 1024 and auto(65536, 2) == 1024
     assert auto(65544, 2) == 0 and auto(1023, 1) == 0
-    assert auto(8192, 0) == 256 and auto(32768, 0) == 1024 and auto(32772, 0) == 0
+    assert auto(8192, 0) == 256 and auto(8196, 0) == 1024 and auto(32768, 0) == 1024 and auto(32772, 0) == 0
     assert softmax.softmax_register_max_n(1) == 65536 and softmax.softmax_register_max_n(0) == 32768
     with pytest.raises(softmax.SoftmaxError):
         auto(0, 1)
