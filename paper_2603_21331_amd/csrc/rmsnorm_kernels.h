@@ -52,15 +52,9 @@ __device__ __forceinline__ float lane_sum_sq(const u32x4 (&v)[CHUNKS]) {
   return (acc[0] + acc[1]) + (acc[2] + acc[3]);
 }
 
-// Makes the compiler treat the packed row as new values.  Without it the fp32
-// forms unpacked for the sum of squares are kept alive for the scale pass,
-// which multiplies the register footprint of the row by two (16-bit types) and
-// spills long rows; widening again costs one ALU operation per element.
-template <int CHUNKS>
-__device__ __forceinline__ void forget_unpacked(u32x4 (&v)[CHUNKS]) {
-#pragma unroll
-  for (int c = 0; c < CHUNKS; ++c) asm volatile("" : "+v"(v[c]));
-}
+// (forget_unpacked, from vec_io.h, sits between the sum of squares and the scale pass: without
+// it the fp32 forms unpacked for the sum are kept alive, which multiplies the register
+// footprint of the row by two for the 16-bit types and spills long rows.)
 
 // rstd = 1 / sqrt(sum / n + eps).  Every thread of a row computes it between the arrival of
 // the row and the first store, so its latency is paid once per row on the critical path: the

@@ -71,13 +71,28 @@ __device__ __forceinline__ float exp_neg(float d) {
 // chunk c; only the last chunk can be ragged, and its missing elements are
 // filled with -inf so that they take no part in the maximum and add exp(-inf)
 // = 0 to the sum.
+//
+// With 1024 threads and five chunks or more of a 16-bit type, the fp32 form of the row (8
+// registers per chunk) would leave room for one workgroup per compute unit only, and with
+// one workgroup nothing overlaps its load, reduce and store phases (bf16 4096 x 50304:
+// 4.7 TB/s).  Those instances keep the row packed, widen it again in each of the three passes
+// and take the exponentials twice: 64 registers or fewer, two workgroups per compute unit.
+// The results are the same bits: every pass computes the same values from the same inputs.
 // ---------------------------------------------------------------------------
+template <int DT>
+__device__ __forceinline__ u32x4 sm_neg_inf_vec() {
+  constexpr uint32_t p = DT == kFp32 ? 0xFF800000u : DT == kFp16 ? 0xFC00FC00u : 0xFF80FF80u;
+  u32x4 v = {p, p, p, p};
+  return v;
+}
+
 template <int DT, int CHUNKS, int G, bool NT>
 __global__ void __launch_bounds__(G)
 softmax_row_kernel(const u32x4* x, u32x4* y, int64_t M, int nvec) {
   using S = Storage<DT>;
   constexpr int VEC = S::kVec;
   constexpr int WAVES = G / kWaveSize;
+  constexpr bool LEAN = G == 1024 && CHUNKS >= 5 && DT != kFp32;
   __shared__ __attribute__((aligned(16))) float part_max[2][WAVES];
   __shared__ __attribute__((aligned(16))) float part_sum[2][WAVES];
   const int t = threadIdx.x;
@@ -98,6 +113,49 @@ softmax_row_kernel(const u32x4* x, u32x4* y, int64_t M, int nvec) {
       const u32x4 zero = {0u, 0u, 0u, 0u};
       v[CHUNKS - 1] = zero;
       if (last_ok) v[CHUNKS - 1] = load_vec<NT>(xr + last);
+    }
+
+    if constexpr (LEAN) {
+      // The row stays packed; every pass widens it again and the exponentials are taken twice.
+      if (!last_ok) v[CHUNKS - 1] = sm_neg_inf_vec<DT>();
+      float m = kNegInf;
+#pragma unroll
+      for (int c = 0; c < CHUNKS; ++c) {
+        float g[VEC];
+        S::unpack(v[c], g);
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) m = __builtin_fmaxf(m, g[k]);
+      }
+      m = wave_max(m);
+      if (lane == 0) part_max[slot][wave] = m;
+      __syncthreads();
+      m = max_waves<WAVES>(part_max[slot]);
+      forget_unpacked<CHUNKS>(v);
+      float acc[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int c = 0; c < CHUNKS; ++c) {
+        float g[VEC];
+        S::unpack(v[c], g);
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) acc[k & 3] += exp_neg<DT>(g[k] - m);
+      }
+      float s = wave_sum((acc[0] + acc[1]) + (acc[2] + acc[3]));
+      if (lane == 0) part_sum[slot][wave] = s;
+      __syncthreads();
+      s = sum_waves<WAVES>(part_sum[slot]);
+      slot ^= 1;
+      const float inv = 1.0f / s;
+      forget_unpacked<CHUNKS>(v);
+#pragma unroll
+      for (int c = 0; c < CHUNKS; ++c) {
+        float g[VEC];
+        S::unpack(v[c], g);
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) g[k] = exp_neg<DT>(g[k] - m) * inv;
+        const int idx = c * G + t;
+        if (c < CHUNKS - 1 || last_ok) store_vec<NT>(yr + idx, S::pack(g));
+      }
+      continue;
     }
 
     float f[CHUNKS][VEC];

@@ -67,6 +67,15 @@ __device__ __forceinline__ void store_row_vec(__amdgpu_buffer_rsrc_t res, int in
   __builtin_amdgcn_raw_buffer_store_b128(v, res, index * 16, 0, NT ? kStreamStorePolicy : 0);
 }
 
+// Makes the compiler treat packed vectors as new values, so that fp32 forms unpacked from them
+// earlier cannot be kept alive in registers for a later pass (widening again costs one ALU
+// operation per element; keeping them costs the registers that decide the occupancy).
+template <int CHUNKS>
+__device__ __forceinline__ void forget_unpacked(u32x4 (&v)[CHUNKS]) {
+#pragma unroll
+  for (int c = 0; c < CHUNKS; ++c) asm volatile("" : "+v"(v[c]));
+}
+
 __device__ __forceinline__ float as_f32(uint32_t u) { return __builtin_bit_cast(float, u); }
 __device__ __forceinline__ uint32_t as_u32(float f) { return __builtin_bit_cast(uint32_t, f); }
 
