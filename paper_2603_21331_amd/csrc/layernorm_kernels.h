@@ -68,13 +68,23 @@ __device__ __forceinline__ u32x4 ln_scale(const float (&c)[Storage<DT>::kVec], u
 
 // At least four wavefronts per SIMD (128 VGPRs): without the bound the compiler hoists every
 // weight and bias load above the reductions and long rows drop to two wavefronts per SIMD.
+//
+// 1024 threads of a 16-bit type (rows of 16 k elements and more): the fp32 form of the row
+// would leave room for one workgroup per compute unit, with nothing to overlap its load,
+// reduce and store phases.  Those instances keep the row packed and widen, shift and centre it
+// again in each of the three passes (the same operations on the same values, so the same bits):
+// 64 registers, two workgroups per compute unit.
+template <int DT, int G>
+inline constexpr bool kLnLean = G == 1024 && DT != kFp32;
+
 template <int DT, int CHUNKS, int G, bool NT>
-__global__ void __launch_bounds__(G) __attribute__((amdgpu_waves_per_eu(4)))
+__global__ void __launch_bounds__(G) __attribute__((amdgpu_waves_per_eu(kLnLean<DT, G> ? 8 : 4)))
 layernorm_row_kernel(const u32x4* x, const u32x4* __restrict__ w, const u32x4* __restrict__ b,
                      u32x4* y, int64_t M, int nvec, float n, float eps) {
   using S = Storage<DT>;
   constexpr int VEC = S::kVec;
   constexpr int WAVES = G / kLnWave;
+  constexpr bool LEAN = kLnLean<DT, G>;
   __shared__ __attribute__((aligned(16))) float part_a[2][WAVES];
   __shared__ __attribute__((aligned(16))) float part_b[2][WAVES];
   const int t = threadIdx.x;
@@ -96,6 +106,59 @@ layernorm_row_kernel(const u32x4* x, const u32x4* __restrict__ w, const u32x4* _
     v[CHUNKS - 1] = zero;
     if (last_ok) v[CHUNKS - 1] = load_vec<NT>(xr + last);
     const float shift = S::load_one(xr, 0);           // K: the row's first element
+
+    if constexpr (LEAN) {
+      float acc[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int c = 0; c < CHUNKS; ++c) {
+        float g[VEC];
+        S::unpack(v[c], g);
+        const float sub = (c < CHUNKS - 1 || last_ok) ? shift : 0.f;   // a chunk past the end holds zeros
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) acc[k & 3] += g[k] - sub;
+      }
+      float s1 = wave_sum((acc[0] + acc[1]) + (acc[2] + acc[3]));
+      if (lane == 0) part_a[slot][wave] = s1;
+      __syncthreads();
+      s1 = sum_waves<WAVES>(part_a[slot]);
+      const float mean_shifted = s1 / n;
+      forget_unpacked<CHUNKS>(v);
+      float sq[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int c = 0; c < CHUNKS; ++c) {
+        float g[VEC];
+        S::unpack(v[c], g);
+        const bool live = c < CHUNKS - 1 || last_ok;
+        const float sub = live ? shift : 0.f, sub2 = live ? mean_shifted : 0.f;
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) {
+          const float d = (g[k] - sub) - sub2;
+          sq[k & 3] = __builtin_fmaf(d, d, sq[k & 3]);
+        }
+      }
+      float s2 = wave_sum((sq[0] + sq[1]) + (sq[2] + sq[3]));
+      if (lane == 0) part_b[slot][wave] = s2;
+      __syncthreads();
+      s2 = sum_waves<WAVES>(part_b[slot]);
+      slot ^= 1;
+      const float rstd = ln_rstd(s2, n, eps);
+      forget_unpacked<CHUNKS>(v);
+      const u32x4* wp = w;
+      const u32x4* bp = b;
+      asm volatile("" : "+s"(wp), "+s"(bp));               // keeps the loads below the reductions
+#pragma unroll
+      for (int c = 0; c < CHUNKS; ++c) {
+        const int idx = c * G + t;
+        if (c < CHUNKS - 1 || last_ok) {
+          float g[VEC];
+          S::unpack(v[c], g);
+#pragma unroll
+          for (int k = 0; k < VEC; ++k) g[k] = (g[k] - shift) - mean_shifted;
+          store_vec<NT>(yr + idx, ln_scale<DT>(g, wp[idx], has_bias ? bp[idx] : zero, has_bias, rstd));
+        }
+      }
+      continue;
+    }
 
     // Weight and bias: with up to four chunks per thread they are fetched now, together with
     // the row (32 more registers at most); longer rows fetch them after the reductions.
