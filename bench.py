@@ -39,6 +39,7 @@ PEAK_HBM_GBPS = 8000.0
 TRAFFIC_FILES = {
     "rmsnorm": "hbm_traffic_rmsnorm_bf16_16384x8192.txt",
     "softmax": "hbm_traffic_softmax_fp16_8192x8192.txt",
+    "softmax_attention": "hbm_traffic_softmax_fp16_170320x197.txt",   # --attention-len 197
     "layernorm": "hbm_traffic_layernorm_fp16_8192x4096.txt",
     "crossentropy": "hbm_traffic_crossentropy_fp16_8192x32000.txt",
     "rowsum": "hbm_traffic_rowsum_fp16_8192x8192.txt",
@@ -152,6 +153,10 @@ def main() -> int:
                          "8192 x 32000; fp16 8192 x 8192)")
     ap.add_argument("--paper-shape", type=int, choices=[0, 1], default=0,
                     help="with --op rowsum: 0 = fp16 8192 x 8192 (default), 1 = fp16 16384 x 4096")
+    ap.add_argument("--attention-len", type=int, default=0,
+                    help="with --op softmax: instead of 8192 x 8192, 64 MiB of fp16 attention-score "
+                         "rows over this many positions (e.g. 197: rows that are not 16-byte "
+                         "aligned, several per workgroup through LDS)")
     ap.add_argument("--profile-only", action="store_true",
                     help="warm-up plus --steps launches and nothing else (for rocprofv3 runs)")
     ap.add_argument("--calib-copy", action="store_true",
@@ -331,12 +336,21 @@ def bench_softmax(args, dev) -> int:
     softmax.load()
     n, K, W, S = 8192, args.steps, args.warmup, max(1, args.buffer_sets)
     t0 = time.time()
-    case = inputs.softmax_paper_shape(n)
+    if args.attention_len:
+        # attention scores over a context of `cols` positions (odd lengths such as 77, 197, 257:
+        # the rows are not 16-byte aligned and take the LDS-staged kernel); 64 MiB of them
+        cols = args.attention_len
+        n = (64 << 20) // (2 * cols) // 8 * 8      # whole 16-byte vectors in total, for the calibration copy
+        S = max(S, 8)
+        case = inputs.softmax_case(0, 100, n, cols, inputs.FP16, 2.0)
+    else:
+        cols = n
+        case = inputs.softmax_paper_shape(n)
     log(f"generated {case['name']} in {time.time() - t0:.1f} s")
-    nbytes = inputs.softmax_bytes(n, n, inputs.FP16)
+    nbytes = inputs.softmax_bytes(n, cols, inputs.FP16)
     x_host = torch.from_numpy(case["x"].view(np.int16))
     xs = [x_host.to(dev).view(torch.float16) for _ in range(S)]
-    ys = [torch.empty((n, n), dtype=torch.float16, device=dev) for _ in range(S)]
+    ys = [torch.empty((n, cols), dtype=torch.float16, device=dev) for _ in range(S)]
     fns = [softmax.bind_softmax_fwd(xs[i], ys[i], threads_per_row=args.threads_per_row)
            for i in range(S)]
     settle(fns, args.settle_ms)
@@ -356,18 +370,19 @@ def bench_softmax(args, dev) -> int:
     value = nbytes / (ms_per_step * 1e-3) / 1e9
     durs = per_launch_us(fns, K)
     result = {
-        "metric": "Softmax fwd achieved HBM GB/s and % of MI355X peak (fp16, 8192x8192)",
+        "metric": f"Softmax fwd achieved HBM GB/s and % of MI355X peak (fp16, {n}x{cols})",
         "value": round(value, 1), "unit": "GB/s",
         "pct_of_peak": round(100.0 * value / PEAK_HBM_GBPS, 2),
         "rows_per_s": round(n / (ms_per_step * 1e-3), 1),
         "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(ms_per_step, 6),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": f"softmax_fwd fp16 M={n} N={n}", "storage_dtype": "fp16",
+        "config": {"workload": f"softmax_fwd fp16 M={n} N={cols}", "storage_dtype": "fp16",
                    "threads_per_row": args.threads_per_row
-                   or softmax.softmax_auto_threads_per_row(n, inputs.FP16),
+                   or softmax.softmax_auto_threads_per_row(cols, inputs.FP16),
                    "buffer_sets": S, "bytes_per_step": nbytes},
-        "roofline": roofline_object(nbytes, ms_per_step, durs, read_traffic("softmax")),
+        "roofline": roofline_object(nbytes, ms_per_step, durs,
+                                    read_traffic("softmax_attention" if args.attention_len else "softmax")),
     }
     if not args.no_cpu_baseline:
         import oracle
@@ -382,7 +397,7 @@ def bench_softmax(args, dev) -> int:
             best = dt if best is None else min(best, dt)
         result["cpu_baseline"] = {"value": round(nbytes / best / 1e9, 3), "unit": "GB/s",
                                   "cores": cores, "kind": "oracle",
-                                  "sample": f"the whole workload ({n} x {n}), best of 3 runs, "
+                                  "sample": f"the whole workload ({n} x {cols}), best of 3 runs, "
                                             f"{best:.3f} s each"}
         got = ys[0].view(torch.int16).cpu().numpy().view(np.uint16)
         result["parity"] = {"checked": "every element of one output buffer",

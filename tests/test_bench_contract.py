@@ -48,7 +48,8 @@ def test_trimmed_mean_and_roofline_object():
 
 def test_every_op_has_a_traffic_summary_that_parses():
     b = load_bench()
-    assert sorted(b.TRAFFIC_FILES) == ["crossentropy", "layernorm", "rmsnorm", "rowsum", "softmax"]
+    assert sorted(b.TRAFFIC_FILES) == ["crossentropy", "layernorm", "rmsnorm", "rowsum", "softmax",
+                                       "softmax_attention"]
     for op, name in b.TRAFFIC_FILES.items():
         path = os.path.join(ROOT, "profiles", name)
         assert os.path.exists(path), f"profiles/{name} is missing"
