@@ -215,7 +215,7 @@ crossentropy_subwave_kernel(const u32x4* x, const int64_t* __restrict__ target,
 // Up to 512 classes in rows that are not 16-byte aligned (100 classes in fp16, 1000 / 3 of
 // anything): runs of whole rows, up to 16 KiB, are copied into LDS with aligned 128-bit loads
 // that are contiguous across the workgroup (see packed_rows.h), and lane groups of L lanes take
-// one row each out of LDS, E = 5..8 logits per lane, with the same online pair and the same
+// one row each out of LDS, E logits per lane with (E - 1) * L < N <= E * L, with the same online pair and the same
 // DPP-only combination as the lane-group kernel above.  Nothing is written but one float per
 // row (two with the log-sum-exp), so any alignment of x will do.
 template <int DT, int L, int E, bool NT>
@@ -243,7 +243,8 @@ crossentropy_packed_kernel(const void* x, const int64_t* __restrict__ target, fl
 #pragma unroll
       for (int i = 0; i < E; ++i) {
         const int j = sub + i * L;
-        f[i] = j < N ? tile_get<DT>(tile, at + j) : kCeNegInf;
+        f[i] = tile_get<DT>(tile, (i < E - 1 || j < N) ? at + j : at);   // only the last step can pass N
+        if (i == E - 1 && j >= N) f[i] = kCeNegInf;
       }
       float m = kCeNegInf, s = 0.f;
       ce_fold<E>(f, m, s);

@@ -381,8 +381,9 @@ layernorm_row_resident_kernel(const u32x4* x, const u32x4* __restrict__ w,
 }
 
 // Short rows that are not 16-byte aligned, several per workgroup, staged through LDS (see
-// packed_rows.h): L lanes per row, E = 5..8 elements per lane (N <= E * L),
-// `tile_rows` rows (at most 16 KiB) per step; x and y must be congruent modulo 16 bytes.  A
+// packed_rows.h): L lanes per row, E elements per lane with (E - 1) * L < N <= E * L (so only a
+// lane's last element can lie past the end of its row), `tile_rows` rows (at most 16 KiB) per
+// step; x and y must be congruent modulo 16 bytes.  A
 // lane keeps its slices of weight and bias in registers for the whole launch.  The same two
 // passes over registers as the other kernels: shift by the row's first element, sum, centre,
 // sum of squares.  Lane groups without a row repeat the last one and write nothing back.
@@ -422,7 +423,8 @@ layernorm_packed_kernel(const void* x, const void* w, const void* b, void* y, in
 #pragma unroll
       for (int i = 0; i < E; ++i) {
         const int j = sub + i * L;
-        f[i] = j < N ? tile_get<DT>(tile, at + j) - shift : 0.f;
+        f[i] = tile_get<DT>(tile, (i < E - 1 || j < N) ? at + j : at) - shift;   // only the last step can pass N
+        if (i == E - 1 && j >= N) f[i] = 0.f;
         acc += f[i];
       }
       const float mean_shifted = group_sum<L>(acc) / n;
@@ -430,7 +432,8 @@ layernorm_packed_kernel(const void* x, const void* w, const void* b, void* y, in
 #pragma unroll
       for (int i = 0; i < E; ++i) {
         const int j = sub + i * L;
-        f[i] = j < N ? f[i] - mean_shifted : 0.f;
+        f[i] -= mean_shifted;
+        if (i == E - 1 && j >= N) f[i] = 0.f;
         sq = __builtin_fmaf(f[i], f[i], sq);
       }
       const float rstd = ln_rstd(group_sum<L>(sq), n, eps);
@@ -439,7 +442,7 @@ layernorm_packed_kernel(const void* x, const void* w, const void* b, void* y, in
         for (int i = 0; i < E; ++i) {
           const int j = sub + i * L;
           const float scaled = (f[i] * rstd) * wf[i];
-          if (j < N) tile_put<DT>(tile, at + j, has_bias ? scaled + bf[i] : scaled);
+          if (i < E - 1 || j < N) tile_put<DT>(tile, at + j, has_bias ? scaled + bf[i] : scaled);
         }
       }
     }

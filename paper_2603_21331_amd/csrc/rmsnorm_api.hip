@@ -304,15 +304,25 @@ void launch_packed(const Args& a) {
 }
 
 // Lanes per row: the narrowest group that holds the row with 8 elements per lane; elements per
-// lane: what the row then needs, at least 5 (fewer would fit a narrower group, except in the
-// narrowest one, where rows of 32 elements and less carry idle steps).
+// lane: exactly what the row then needs, (E - 1) * L < N <= E * L, which is 5 to 8 except in the
+// narrowest group, where rows of up to 32 elements need 1 to 4.
 template <int DT, int L>
 void launch_packed_lanes(const Args& a) {
   switch ((a.N + L - 1) / L) {
     case 8: launch_packed<DT, L, 8>(a); break;
     case 7: launch_packed<DT, L, 7>(a); break;
     case 6: launch_packed<DT, L, 6>(a); break;
-    default: launch_packed<DT, L, 5>(a); break;
+    case 5: launch_packed<DT, L, 5>(a); break;
+    default:
+      if constexpr (L == 8) {
+        switch ((a.N + L - 1) / L) {
+          case 4: launch_packed<DT, L, 4>(a); break;
+          case 3: launch_packed<DT, L, 3>(a); break;
+          case 2: launch_packed<DT, L, 2>(a); break;
+          default: launch_packed<DT, L, 1>(a); break;
+        }
+      }
+      break;
   }
 }
 

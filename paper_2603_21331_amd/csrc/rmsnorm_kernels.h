@@ -202,8 +202,9 @@ rmsnorm_row_kernel(const u32x4* x, const u32x4* w, u32x4* y,
 
 // ---------------------------------------------------------------------------
 // Short rows that are not 16-byte aligned, several per workgroup, staged through LDS (see
-// packed_rows.h): L lanes per row, E = 5..8 elements per lane (N <= E * L), `tile_rows`
-// rows (at most 16 KiB) per step; x and y must be congruent modulo 16 bytes.  A lane keeps its slice of the weight in registers for the
+// packed_rows.h): L lanes per row, E elements per lane with (E - 1) * L < N <= E * L (so only
+// a lane's last element can lie past the end of its row), `tile_rows` rows (at most 16 KiB) per
+// step; x and y must be congruent modulo 16 bytes.  A lane keeps its slice of the weight in registers for the
 // whole launch.  Lane groups without a row repeat the last one and write nothing back.
 // ---------------------------------------------------------------------------
 template <int DT, int L, int E, bool NT>
@@ -239,7 +240,8 @@ rmsnorm_packed_kernel(const void* x, const void* w, void* y, int64_t M, int N, i
 #pragma unroll
       for (int i = 0; i < E; ++i) {
         const int j = sub + i * L;
-        f[i] = j < N ? tile_get<DT>(tile, at + j) : 0.f;
+        f[i] = tile_get<DT>(tile, (i < E - 1 || j < N) ? at + j : at);   // only the last step can pass N
+        if (i == E - 1 && j >= N) f[i] = 0.f;
         acc = __builtin_fmaf(f[i], f[i], acc);
       }
       const float rstd = row_rstd(group_sum<L>(acc), inv_n, eps);
@@ -247,7 +249,7 @@ rmsnorm_packed_kernel(const void* x, const void* w, void* y, int64_t M, int N, i
 #pragma unroll
         for (int i = 0; i < E; ++i) {
           const int j = sub + i * L;
-          if (j < N) tile_put<DT>(tile, at + j, (f[i] * rstd) * wf[i]);
+          if (i < E - 1 || j < N) tile_put<DT>(tile, at + j, (f[i] * rstd) * wf[i]);
         }
       }
     }

@@ -117,14 +117,25 @@ void launch_packed(const void* x, float* y, int64_t M, int64_t N, hipStream_t st
                      dim3(rms::kPackThreads), 0, stream, x, y, M, (int)N, tile_rows);
 }
 
-// Elements per lane: what the row needs in the chosen lane group, at least 5.
+// Elements per lane: exactly what the row needs in the chosen lane group, (E - 1) * L < N <=
+// E * L, which is 5 to 8 except in the narrowest group, where rows of up to 32 elements need 1 to 4.
 template <int DT, int L>
 void launch_packed_lanes(const void* x, float* y, int64_t M, int64_t N, hipStream_t stream) {
   switch ((N + L - 1) / L) {
     case 8: launch_packed<DT, L, 8>(x, y, M, N, stream); break;
     case 7: launch_packed<DT, L, 7>(x, y, M, N, stream); break;
     case 6: launch_packed<DT, L, 6>(x, y, M, N, stream); break;
-    default: launch_packed<DT, L, 5>(x, y, M, N, stream); break;
+    case 5: launch_packed<DT, L, 5>(x, y, M, N, stream); break;
+    default:
+      if constexpr (L == 8) {
+        switch ((N + L - 1) / L) {
+          case 4: launch_packed<DT, L, 4>(x, y, M, N, stream); break;
+          case 3: launch_packed<DT, L, 3>(x, y, M, N, stream); break;
+          case 2: launch_packed<DT, L, 2>(x, y, M, N, stream); break;
+          default: launch_packed<DT, L, 1>(x, y, M, N, stream); break;
+        }
+      }
+      break;
   }
 }
 

@@ -154,7 +154,7 @@ rowsum_subwave_kernel(const u32x4* x, float* __restrict__ y, int64_t M, int nvec
 // Rows of up to 512 elements that are not whole aligned vectors (100 elements in fp16, a base
 // pointer off a boundary): runs of whole rows, up to 16 KiB, are copied into LDS with aligned
 // 128-bit loads that are contiguous across the workgroup (see packed_rows.h), and lane groups
-// of L lanes add one row each out of LDS, E = 5..8 elements per lane in index order, then the
+// of L lanes add one row each out of LDS, E elements per lane ((E - 1) * L < N <= E * L) in index order, then the
 // DPP butterfly inside the group.  Only one float per row is written, so any alignment of x
 // will do.
 template <int DT, int L, int E, bool NT>
@@ -181,7 +181,8 @@ rowsum_packed_kernel(const void* x, float* __restrict__ y, int64_t M, int N, int
 #pragma unroll
       for (int i = 0; i < E; ++i) {
         const int j = sub + i * L;
-        acc += j < N ? tile_get<DT>(tile, at + j) : 0.f;
+        const float value = tile_get<DT>(tile, (i < E - 1 || j < N) ? at + j : at);   // only the last step can pass N
+        acc += (i == E - 1 && j >= N) ? 0.f : value;
       }
       const float total = group_sum<L>(acc);
       if (r < rows && sub == 0) y[r0 + r] = total;

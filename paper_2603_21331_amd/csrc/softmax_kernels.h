@@ -207,9 +207,9 @@ softmax_row_kernel(const u32x4* x, u32x4* y, int64_t M, int nvec) {
 
 // ---------------------------------------------------------------------------
 // Short rows that are not 16-byte aligned (an attention row of 77, 197 or 257 scores), several
-// per workgroup, staged through LDS (see packed_rows.h): L lanes per row, E = 5..8
-// elements per lane (N <= E * L), `tile_rows` rows (at most 16 KiB) per step; x and y must be
-// congruent modulo 16 bytes.  Lane groups without a row repeat the last one and write nothing
+// per workgroup, staged through LDS (see packed_rows.h): L lanes per row, E elements per lane
+// with (E - 1) * L < N <= E * L (so only a lane's last element can lie past the end of its row),
+// `tile_rows` rows (at most 16 KiB) per step; x and y must be congruent modulo 16 bytes.  Lane groups without a row repeat the last one and write nothing
 // back.  (Skipping the steps that hold no element of any row, a test that is the same for
 // every lane, was measured and is 10 % slower: the branches keep the LDS reads apart.)
 // ---------------------------------------------------------------------------
@@ -238,7 +238,8 @@ softmax_packed_kernel(const void* x, void* y, int64_t M, int N, int tile_rows) {
 #pragma unroll
       for (int i = 0; i < E; ++i) {
         const int j = sub + i * L;
-        f[i] = j < N ? tile_get<DT>(tile, at + j) : kNegInf;   // exp(-inf - m) adds 0 to the sum
+        f[i] = tile_get<DT>(tile, (i < E - 1 || j < N) ? at + j : at);   // only the last step can pass N
+        if (i == E - 1 && j >= N) f[i] = kNegInf;              // exp(-inf - m) adds 0 to the sum
         m = __builtin_fmaxf(m, f[i]);
       }
       m = group_max<L>(m);
@@ -253,7 +254,7 @@ softmax_packed_kernel(const void* x, void* y, int64_t M, int N, int tile_rows) {
 #pragma unroll
         for (int i = 0; i < E; ++i) {
           const int j = sub + i * L;
-          if (j < N) tile_put<DT>(tile, at + j, f[i] * inv);
+          if (i < E - 1 || j < N) tile_put<DT>(tile, at + j, f[i] * inv);
         }
       }
     }
