@@ -93,6 +93,7 @@ layernorm_row_kernel(const u32x4* x, const u32x4* __restrict__ w, const u32x4* _
   const int last = (CHUNKS - 1) * G + t;
   const bool last_ok = last < nvec;
   const bool has_bias = b != nullptr;
+  const float inv_n = 1.0f / n;       // the mean and the reciprocal root as in the resident kernel
   const u32x4 zero = {0u, 0u, 0u, 0u};
   int slot = 0;
 
@@ -121,7 +122,7 @@ layernorm_row_kernel(const u32x4* x, const u32x4* __restrict__ w, const u32x4* _
       if (lane == 0) part_a[slot][wave] = s1;
       __syncthreads();
       s1 = sum_waves<WAVES>(part_a[slot]);
-      const float mean_shifted = s1 / n;
+      const float mean_shifted = s1 * inv_n;
       forget_unpacked<CHUNKS>(v);
       float sq[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -141,7 +142,7 @@ layernorm_row_kernel(const u32x4* x, const u32x4* __restrict__ w, const u32x4* _
       __syncthreads();
       s2 = sum_waves<WAVES>(part_b[slot]);
       slot ^= 1;
-      const float rstd = ln_rstd(s2, n, eps);
+      const float rstd = ln_rstd_fast(s2, inv_n, eps);
       forget_unpacked<CHUNKS>(v);
       const u32x4* wp = w;
       const u32x4* bp = b;
@@ -193,7 +194,7 @@ layernorm_row_kernel(const u32x4* x, const u32x4* __restrict__ w, const u32x4* _
       __syncthreads();
       s1 = sum_waves<WAVES>(part_a[slot]);
     }
-    const float mean_shifted = s1 / n;
+    const float mean_shifted = s1 * inv_n;
 
     float sq[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -212,7 +213,7 @@ layernorm_row_kernel(const u32x4* x, const u32x4* __restrict__ w, const u32x4* _
       s2 = sum_waves<WAVES>(part_b[slot]);
       slot ^= 1;
     }
-    const float rstd = ln_rstd(s2, n, eps);
+    const float rstd = ln_rstd_fast(s2, inv_n, eps);
 
     // The weight and bias are fetched only now (L2 hits): the empty asm keeps the compiler
     // from hoisting sixteen more vectors above the reductions, where the centred row already
@@ -398,6 +399,9 @@ layernorm_packed_kernel(const void* x, const void* w, const void* b, void* y, in
   const int sub = t % L;
   const int group = t / L;
   const bool has_bias = b != nullptr;
+  // Short rows pay the per-row arithmetic most: the mean through 1 / N and the reciprocal
+  // square root through the hardware instruction plus a Newton step, as in the resident kernel.
+  const float inv_n = 1.0f / n;
 
   float wf[E], bf[E];
 #pragma unroll
@@ -427,7 +431,7 @@ layernorm_packed_kernel(const void* x, const void* w, const void* b, void* y, in
         if (i == E - 1 && j >= N) f[i] = 0.f;
         acc += f[i];
       }
-      const float mean_shifted = group_sum<L>(acc) / n;
+      const float mean_shifted = group_sum<L>(acc) * inv_n;
       float sq = 0.f;
 #pragma unroll
       for (int i = 0; i < E; ++i) {
@@ -436,7 +440,7 @@ layernorm_packed_kernel(const void* x, const void* w, const void* b, void* y, in
         if (i == E - 1 && j >= N) f[i] = 0.f;
         sq = __builtin_fmaf(f[i], f[i], sq);
       }
-      const float rstd = ln_rstd(group_sum<L>(sq), n, eps);
+      const float rstd = ln_rstd_fast(group_sum<L>(sq), inv_n, eps);
       if (r < rows) {
 #pragma unroll
         for (int i = 0; i < E; ++i) {
@@ -464,6 +468,7 @@ layernorm_subwave_kernel(const u32x4* x, const u32x4* __restrict__ w, const u32x
   const int sub = lane % L;
   const int r = lane / L;
   const bool has_bias = b != nullptr;
+  const float inv_n = 1.0f / n;       // short rows pay the per-row arithmetic most: see ln_rstd_fast
   const u32x4 zero = {0u, 0u, 0u, 0u};
 
   for (int64_t base = (int64_t)blockIdx.x * ROWS; base < M; base += (int64_t)gridDim.x * ROWS) {
@@ -497,7 +502,7 @@ layernorm_subwave_kernel(const u32x4* x, const u32x4* __restrict__ w, const u32x
         acc += f[c][k];
       }
     }
-    const float mean_shifted = subwave_sum<L>(acc) / n;
+    const float mean_shifted = subwave_sum<L>(acc) * inv_n;
     float sq = 0.f;
 #pragma unroll
     for (int c = 0; c < CHUNKS; ++c) {
@@ -508,7 +513,7 @@ layernorm_subwave_kernel(const u32x4* x, const u32x4* __restrict__ w, const u32x
         sq = __builtin_fmaf(f[c][k], f[c][k], sq);
       }
     }
-    const float rstd = ln_rstd(subwave_sum<L>(sq), n, eps);
+    const float rstd = ln_rstd_fast(subwave_sum<L>(sq), inv_n, eps);
 #pragma unroll
     for (int c = 0; c < CHUNKS; ++c) {
       const int idx = c * L + sub;

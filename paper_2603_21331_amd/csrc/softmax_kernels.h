@@ -249,7 +249,9 @@ softmax_packed_kernel(const void* x, void* y, int64_t M, int N, int tile_rows) {
         f[i] = exp_neg<DT>(f[i] - m);
         acc += f[i];
       }
-      const float inv = 1.0f / group_sum<L>(acc);
+      // The sum is at least 1 (the maximum contributes exp(0)) and at most N: the hardware
+      // reciprocal (1 ulp) replaces the ten-instruction correctly rounded division.
+      const float inv = __builtin_amdgcn_rcpf(group_sum<L>(acc));
       if (r < rows) {
 #pragma unroll
         for (int i = 0; i < E; ++i) {
