@@ -46,7 +46,7 @@ typedef enum {
   CROSSENTROPY_ERR_UNSUPPORTED = -2, /* a forced lane-group size (8, 16, 32) on rows that are not
                                         16-byte aligned or longer than 8 vectors per lane, one
                                         lane per row with N > 64, or the LDS-staged kernel with
-                                        N > 512; nothing was launched */
+                                        N > 1024; nothing was launched */
   CROSSENTROPY_ERR_LAUNCH = -3       /* the HIP runtime refused the launch */
 } crossentropy_status;
 
@@ -69,7 +69,7 @@ int crossentropy_fwd(const void* x, const int64_t* target, float* loss, float* l
  * at most 128 bytes per lane, otherwise CROSSENTROPY_ERR_UNSUPPORTED), or 1 (one lane per row:
  * any alignment, N <= 64, otherwise CROSSENTROPY_ERR_UNSUPPORTED), or 2 (not a thread count:
  * runs of rows copied through LDS, 8 to 64 lanes per row chosen from N; any alignment,
- * N <= 512, otherwise CROSSENTROPY_ERR_UNSUPPORTED).  Any other value is
+ * N <= 1024, otherwise CROSSENTROPY_ERR_UNSUPPORTED).  Any other value is
  * CROSSENTROPY_ERR_INVALID_ARG. */
 int crossentropy_fwd_tuned(const void* x, const int64_t* target, float* loss, float* lse,
                            int64_t M, int64_t N, int dtype, void* stream, int threads_per_row);
@@ -77,7 +77,7 @@ int crossentropy_fwd_tuned(const void* x, const int64_t* target, float* loss, fl
 /* threads_per_row of the automatic path for rows of N classes whose base is 16-byte aligned:
  * 1 below 32 classes (whatever the alignment), 2 for longer rows below 256 bytes, lane groups
  * for rows of whole 16-byte vectors up to 4 KiB (2 KiB for fp32), 2 for other rows of at most
- * 512 classes (an unaligned base makes every such row take 2, and longer ones 64 threads);
+ * 1024 classes (an unaligned base makes every such row take 2, and longer ones 64 threads);
  * a negative crossentropy_status for a bad dtype or N <= 0. */
 int crossentropy_auto_threads_per_row(int64_t N, int dtype);
 

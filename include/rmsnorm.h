@@ -24,7 +24,7 @@
  *  - Pointers need only the alignment of their element type.  Rows whose
  *    start is 16-byte aligned (16-byte aligned bases and N * sizeof(dtype) a
  *    multiple of 16) take the aligned kernels; other rows take the same
- *    register-resident kernel with element-aligned 128-bit accesses (up to 512
+ *    register-resident kernel with element-aligned 128-bit accesses (up to 1024
  *    elements: several rows at a time through LDS); rows too long for registers
  *    stream through a two-pass kernel that reads x a second time from cache.
  *    None of these is an error.
@@ -74,7 +74,7 @@ typedef enum {
                                    long for registers (the second read comes from cache);
                                    any alignment, N < 2^31 */
   RMSNORM_VARIANT_PACKED = 7    /* runs of short rows copied through LDS with 128-bit accesses,
-                                   8 to 64 lanes per row; N <= 512, any alignment as long as x
+                                   8 to 64 lanes per row; N <= 1024, any alignment as long as x
                                    and y are congruent modulo 16 bytes; what rows that are not
                                    16-byte aligned take up to that length, and aligned
                                    rows of at most 64 bytes */
@@ -101,7 +101,7 @@ int rmsnorm_fwd(const void* x, const void* w, void* y, int64_t M, int64_t N,
  * shape: SUBWAVE needs 16-byte aligned rows of at most 1 KiB, WAVE needs
  * 16-byte aligned rows of at most rmsnorm_wave_max_n(dtype) elements, BLOCK needs 16-byte aligned rows of at most
  * rmsnorm_block_max_n(dtype) elements, UNALIGNED takes any alignment up to
- * rmsnorm_unaligned_max_n(dtype) elements, PACKED up to 512 elements with x - y a multiple
+ * rmsnorm_unaligned_max_n(dtype) elements, PACKED up to 1024 elements with x - y a multiple
  * of 16 bytes, STREAM
  * any alignment up to N < 2^31, GENERIC takes everything.
  */

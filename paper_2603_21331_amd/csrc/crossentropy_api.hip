@@ -115,26 +115,12 @@ void launch_packed(const void* x, const int64_t* target, float* loss, float* lse
 }
 
 // Elements per lane: exactly what the row needs in the chosen lane group, (E - 1) * L < N <=
-// E * L, which is 5 to 8 except in the narrowest group, where rows of up to 32 elements need 1 to 4.
-template <int DT, int L>
+// E * L, which is 9 to 16 except in the narrowest group, where rows of up to 64 elements need 1 to 8.
+template <int DT, int L, int E = rms::kPackElems>
 void launch_packed_lanes(const void* x, const int64_t* target, float* loss, float* lse, int64_t M,
                          int64_t N, hipStream_t stream) {
-  switch ((N + L - 1) / L) {
-    case 8: launch_packed<DT, L, 8>(x, target, loss, lse, M, N, stream); break;
-    case 7: launch_packed<DT, L, 7>(x, target, loss, lse, M, N, stream); break;
-    case 6: launch_packed<DT, L, 6>(x, target, loss, lse, M, N, stream); break;
-    case 5: launch_packed<DT, L, 5>(x, target, loss, lse, M, N, stream); break;
-    default:
-      if constexpr (L == 8) {
-        switch ((N + L - 1) / L) {
-          case 4: launch_packed<DT, L, 4>(x, target, loss, lse, M, N, stream); break;
-          case 3: launch_packed<DT, L, 3>(x, target, loss, lse, M, N, stream); break;
-          case 2: launch_packed<DT, L, 2>(x, target, loss, lse, M, N, stream); break;
-          default: launch_packed<DT, L, 1>(x, target, loss, lse, M, N, stream); break;
-        }
-      }
-      break;
-  }
+  if ((N + L - 1) / L == E) launch_packed<DT, L, E>(x, target, loss, lse, M, N, stream);
+  else if constexpr (E > (L == 8 ? 1 : rms::kPackElems / 2 + 1)) launch_packed_lanes<DT, L, E - 1>(x, target, loss, lse, M, N, stream);
 }
 
 template <int DT>

@@ -172,7 +172,7 @@ void launch_row_unaligned(const Args& a, int nfull) {
 }
 
 // The LDS-staged kernel for short rows that are not 16-byte aligned: the narrowest lane group
-// that holds the row (8 elements per lane), as many whole rows per step as fit the tile, at
+// that holds the row (16 elements per lane), as many whole rows per step as fit the tile, at
 // most 8192 workgroups (beyond 128 MiB a workgroup takes several tiles).  It needs x and y at
 // the same offset from a 16-byte boundary, which its tile mirrors.
 constexpr int64_t kPackedMaxN = 64 * rms::kPackElems;
@@ -197,27 +197,13 @@ void launch_packed(const Args& a) {
                      (float)a.N, a.eps);
 }
 
-// Lanes per row: the narrowest group that holds the row with 8 elements per lane; elements per
-// lane: exactly what the row then needs, (E - 1) * L < N <= E * L, which is 5 to 8 except in the
-// narrowest group, where rows of up to 32 elements need 1 to 4.
-template <int DT, int L>
+// Lanes per row: the narrowest group that holds the row with 16 elements per lane; elements per
+// lane: exactly what the row then needs, (E - 1) * L < N <= E * L, which is 9 to 16 except in the
+// narrowest group, where rows of up to 64 elements need 1 to 8.
+template <int DT, int L, int E = rms::kPackElems>
 void launch_packed_lanes(const Args& a) {
-  switch ((a.N + L - 1) / L) {
-    case 8: launch_packed<DT, L, 8>(a); break;
-    case 7: launch_packed<DT, L, 7>(a); break;
-    case 6: launch_packed<DT, L, 6>(a); break;
-    case 5: launch_packed<DT, L, 5>(a); break;
-    default:
-      if constexpr (L == 8) {
-        switch ((a.N + L - 1) / L) {
-          case 4: launch_packed<DT, L, 4>(a); break;
-          case 3: launch_packed<DT, L, 3>(a); break;
-          case 2: launch_packed<DT, L, 2>(a); break;
-          default: launch_packed<DT, L, 1>(a); break;
-        }
-      }
-      break;
-  }
+  if ((a.N + L - 1) / L == E) launch_packed<DT, L, E>(a);
+  else if constexpr (E > (L == 8 ? 1 : rms::kPackElems / 2 + 1)) launch_packed_lanes<DT, L, E - 1>(a);
 }
 
 template <int DT>

@@ -7,8 +7,10 @@
 // 16 KiB), copies that byte range into LDS with aligned 128-bit accesses that are contiguous
 // across the workgroup (the few bytes before the first and after the last 16-byte boundary go
 // element by element), lets lane groups of L = 8, 16, 32 or 64 lanes work on one row each
-// out of LDS (element reads, up to kPackElems elements per lane, results written back in
-// place), and copies the range out to y the same way.  Every byte of x and y still crosses
+// out of LDS (element reads, up to kPackElems elements per lane: the kernels are bound by
+// vector-ALU issue, and the reductions and the per-row arithmetic of a lane group cost the same
+// however many elements its lanes hold, so few lanes with many elements beat many lanes with
+// few; results written back in place), and copies the range out to y the same way.  Every byte of x and y still crosses
 // HBM once.  The paper's playbook names the ingredients (vectorised, coalesced accesses;
 // shared-memory staging) without giving a kernel; the arrangement is this library's.
 #pragma once
@@ -23,7 +25,7 @@ constexpr int kPackTileBytes = 16384;                 // LDS per workgroup
 constexpr int kPackTileVecs = kPackTileBytes / 16;
 constexpr int kPackLdsVecs = kPackTileVecs + 1;          // the run keeps its skew inside the tile
 constexpr int kPackVecsPerThread = kPackTileVecs / kPackThreads;   // 4
-constexpr int kPackElems = 8;                         // elements a lane holds at most
+constexpr int kPackElems = 16;                        // elements a lane holds at most
 
 // Element `i` of the tile, widened to fp32 / rounded from fp32.  `tile` points into LDS.
 template <int DT>

@@ -120,7 +120,7 @@ int64_t full_groups_per_row(int64_t N, int dtype) { return N / (16 / elem_bytes(
 
 constexpr int64_t kStreamMaxN = (int64_t)1 << 31;   // the streaming kernel counts groups in an int
 
-// The LDS-staged kernel takes rows of at most 8 elements per lane of a 64-lane group at any
+// The LDS-staged kernel takes rows of at most 16 elements per lane of a 64-lane group at any
 // alignment, provided x and y sit at the same offset from a 16-byte boundary (its tile mirrors
 // that offset, so aligned vectors of x are aligned vectors of y); the automatic path uses it
 // for such rows when they are not 16-byte aligned, and for aligned rows of at most four vectors.
@@ -303,27 +303,13 @@ void launch_packed(const Args& a) {
                      1.0f / (float)a.N, a.eps);
 }
 
-// Lanes per row: the narrowest group that holds the row with 8 elements per lane; elements per
-// lane: exactly what the row then needs, (E - 1) * L < N <= E * L, which is 5 to 8 except in the
-// narrowest group, where rows of up to 32 elements need 1 to 4.
-template <int DT, int L>
+// Lanes per row: the narrowest group that holds the row with 16 elements per lane; elements per
+// lane: exactly what the row then needs, (E - 1) * L < N <= E * L, which is 9 to 16 except in the
+// narrowest group, where rows of up to 64 elements need 1 to 8.
+template <int DT, int L, int E = rms::kPackElems>
 void launch_packed_lanes(const Args& a) {
-  switch ((a.N + L - 1) / L) {
-    case 8: launch_packed<DT, L, 8>(a); break;
-    case 7: launch_packed<DT, L, 7>(a); break;
-    case 6: launch_packed<DT, L, 6>(a); break;
-    case 5: launch_packed<DT, L, 5>(a); break;
-    default:
-      if constexpr (L == 8) {
-        switch ((a.N + L - 1) / L) {
-          case 4: launch_packed<DT, L, 4>(a); break;
-          case 3: launch_packed<DT, L, 3>(a); break;
-          case 2: launch_packed<DT, L, 2>(a); break;
-          default: launch_packed<DT, L, 1>(a); break;
-        }
-      }
-      break;
-  }
+  if ((a.N + L - 1) / L == E) launch_packed<DT, L, E>(a);
+  else if constexpr (E > (L == 8 ? 1 : rms::kPackElems / 2 + 1)) launch_packed_lanes<DT, L, E - 1>(a);
 }
 
 template <int DT>

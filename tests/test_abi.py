@@ -116,9 +116,9 @@ def test_unknown_variant_and_unsupported_shapes():
     # misaligned base pointer
     assert lib.rmsnorm_fwd_variant(P + 2, P + 4096, P + 8192, 4, 8, 1e-6, 2, None,
                                    binding.RMSNORM_VARIANT_WAVE) == binding.RMSNORM_ERR_UNSUPPORTED
-    # more than 512 elements per row is too long for the LDS-staged kernel
+    # more than 1024 elements per row is too long for the LDS-staged kernel
     for dtype in (0, 1, 2):
-        assert lib.rmsnorm_fwd_variant(P, P + (1 << 20), P + (2 << 20), 4, 513, 1e-6, dtype, None,
+        assert lib.rmsnorm_fwd_variant(P, P + (1 << 20), P + (2 << 20), 4, 1025, 1e-6, dtype, None,
                                        binding.RMSNORM_VARIANT_PACKED) == binding.RMSNORM_ERR_UNSUPPORTED
     assert lib.rmsnorm_fwd_variant(P, P + (1 << 20), P + (2 << 20), 0, 512, 1e-6, 2, None,
                                    binding.RMSNORM_VARIANT_PACKED) == binding.RMSNORM_OK
@@ -187,9 +187,11 @@ def test_dispatch_choice_is_visible_without_a_launch():
     assert sel(P, P + 65536, P + 131072, 16, 8, 1) == binding.RMSNORM_VARIANT_PACKED
     assert sel(P, P + 65536, P + 131072, 16, 16, 0) == binding.RMSNORM_VARIANT_PACKED
     assert sel(P, P + 65536, P + 131072, 16, 20, 0) == binding.RMSNORM_VARIANT_SUBWAVE
-    assert sel(P, P + 65536, P + 131072, 16, 1023, 1) == binding.RMSNORM_VARIANT_UNALIGNED
-    assert sel(P + 2, P + 65536, P + 131072, 16, 1024, 1) == binding.RMSNORM_VARIANT_UNALIGNED
-    assert sel(P, P + 65536, P + 131072, 16, 513, 1) == binding.RMSNORM_VARIANT_UNALIGNED
+    assert sel(P, P + 65536, P + 131072, 16, 1023, 1) == binding.RMSNORM_VARIANT_PACKED
+    assert sel(P, P + 65536, P + 131072, 16, 4097, 1) == binding.RMSNORM_VARIANT_UNALIGNED
+    assert sel(P + 2, P + 65536, P + 131072, 16, 2048, 1) == binding.RMSNORM_VARIANT_UNALIGNED
+    assert sel(P, P + 65536, P + 131072, 16, 1025, 1) == binding.RMSNORM_VARIANT_UNALIGNED
+    assert sel(P, P + 65536, P + 131072, 16, 513, 1) == binding.RMSNORM_VARIANT_PACKED
     # short rows that are not 16-byte aligned go through LDS several at a time
     assert sel(P, P + 65536, P + 131072, 16, 511, 1) == binding.RMSNORM_VARIANT_PACKED
     assert sel(P + 2, P + 65536, P + 131072 + 18, 16, 512, 1) == binding.RMSNORM_VARIANT_PACKED

@@ -64,8 +64,8 @@ def test_lane_groups_refuse_rows_they_cannot_take():
         assert f(P + 2, P + BIG, P + 2 * BIG, None, 4, 64, 1, None, lanes) == ce.CROSSENTROPY_ERR_UNSUPPORTED  # base off by 2 bytes
         assert f(P, P + BIG, P + 2 * BIG, None, 0, 64, 1, None, lanes) == ce.CROSSENTROPY_OK  # empty batch
     assert "thread count" in ce.crossentropy_status_string(ce.CROSSENTROPY_ERR_UNSUPPORTED)
-    # the LDS-staged kernel (code 2): any alignment, at most 512 classes
-    assert f(P + 2, P + BIG, P + 2 * BIG, None, 4, 513, 1, None, 2) == ce.CROSSENTROPY_ERR_UNSUPPORTED
+    # the LDS-staged kernel (code 2): any alignment, at most 1024 classes
+    assert f(P + 2, P + BIG, P + 2 * BIG, None, 4, 1025, 1, None, 2) == ce.CROSSENTROPY_ERR_UNSUPPORTED
     assert f(P, P + BIG, P + 2 * BIG, None, 4, 4096, 0, None, 2) == ce.CROSSENTROPY_ERR_UNSUPPORTED
     assert f(P + 2, P + BIG, P + 2 * BIG, None, 0, 100, 1, None, 2) == ce.CROSSENTROPY_OK
     # one lane per row: any alignment, at most 64 classes
@@ -79,10 +79,10 @@ def test_automatic_threads_per_row():
     for dtype in (0, 1, 2):
         for n in (1, 7, 10, 31):             # rows shorter than 128 bytes: one lane per row
             assert auto(n, dtype) == 1
-        for n in (65, 130, 511):             # up to 512 classes, not whole 16-byte vectors: through LDS
+        for n in (65, 130, 511, 1001):       # up to 1024 classes, not whole 16-byte vectors: through LDS
             assert auto(n, dtype) == 2
-        for n in (513, 1001):                # longer rows that are not whole 16-byte vectors
-            assert auto(n, dtype) == 64
+        for n in (1025, 1031):               # longer rows that are not whole 16-byte vectors: a workgroup
+            assert auto(n, dtype) in (64, 128)
     assert auto(31, 1) == 1 and auto(31, 0) == 1
     # from 32 classes up to 256 bytes per row: through LDS, aligned or not
     assert auto(32, 1) == 2 and auto(64, 1) == 2 and auto(120, 2) == 2 and auto(32, 0) == 2 and auto(60, 0) == 2

@@ -1,5 +1,5 @@
 """GPU parity tests of the LDS-staged kernels for short rows that are not 16-byte aligned
-(several rows per workgroup): odd lengths from 1 to 512 (attention rows of 77, 197, 257
+(several rows per workgroup): odd lengths from 1 to 1024 (attention rows of 77, 197, 257
 entries), row counts that end inside a tile, inside a lane-group pass and inside a
 wavefront, base pointers off a 16-byte boundary, in place, and aligned shapes forced onto
 the kernel.  Each output is compared with the CPU oracle element by element, and the
@@ -16,8 +16,8 @@ from paper_2603_21331_amd import binding, inputs
 pytestmark = pytest.mark.gpu
 
 DTYPES = [inputs.FP32, inputs.FP16, inputs.BF16]
-# every lane-group size (8, 16, 32, 64 lanes of up to 8 elements) at its limits and inside
-LENGTHS = [1, 3, 7, 50, 63, 64, 65, 77, 127, 129, 197, 255, 257, 300, 511, 512]
+# every lane-group size (8, 16, 32, 64 lanes of up to 16 elements) at its limits and inside
+LENGTHS = [1, 3, 7, 50, 63, 64, 65, 77, 127, 129, 197, 255, 257, 300, 511, 512, 513, 777, 1023, 1024]
 
 
 def offset_view(a, dtype, device, off, shape):

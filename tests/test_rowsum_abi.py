@@ -49,11 +49,11 @@ def test_empty_batch_and_bad_thread_counts():
     assert lib.rowsum_fwd_tuned(None, None, 0, 16, 2, None, 64) == rs.ROWSUM_OK
     for bad in (0, 1, 2, 3, 4, 24, 100, 1088, 2048, -64):   # 1 and 2: valid codes, but not for 4096 elements
         assert lib.rowsum_fwd_tuned(P, P + BIG, 4, 4096, 2, None, bad) == rs.ROWSUM_ERR_INVALID_ARG
-    # one lane per row takes at most 64 elements, the LDS-staged kernel at most 512; any alignment
+    # one lane per row takes at most 64 elements, the LDS-staged kernel at most 1024; any alignment
     assert lib.rowsum_fwd_tuned(P + 2, P + BIG, 4, 65, 1, None, 1) == rs.ROWSUM_ERR_INVALID_ARG
-    assert lib.rowsum_fwd_tuned(P + 2, P + BIG, 4, 513, 1, None, 2) == rs.ROWSUM_ERR_INVALID_ARG
+    assert lib.rowsum_fwd_tuned(P + 2, P + BIG, 4, 1025, 1, None, 2) == rs.ROWSUM_ERR_INVALID_ARG
     assert lib.rowsum_fwd_tuned(P + 2, P + BIG, 0, 64, 1, None, 1) == rs.ROWSUM_OK
-    assert lib.rowsum_fwd_tuned(P + 2, P + BIG, 0, 512, 1, None, 2) == rs.ROWSUM_OK
+    assert lib.rowsum_fwd_tuned(P + 2, P + BIG, 0, 1024, 1, None, 2) == rs.ROWSUM_OK
     # several rows per wavefront: only aligned rows of at most 8 vectors per lane
     assert lib.rowsum_fwd_tuned(P, P + BIG, 0, 512, 2, None, 8) == rs.ROWSUM_OK            # 64 vectors
     assert lib.rowsum_fwd_tuned(P, P + BIG, 4, 520, 2, None, 8) == rs.ROWSUM_ERR_INVALID_ARG
@@ -70,12 +70,12 @@ def test_automatic_threads_per_row():
     assert auto(1032, 1) == 64 and auto(2048, 1) == 64 and auto(4096, 1) == 192 and auto(8192, 1) == 384
     assert auto(4096, 0) == 384 and auto(8192, 0) == 768 and auto(8192, 2) == 384
     assert auto(32000, 1) == 768 and auto(65536, 1) == 768 and auto(1 << 30, 2) == 768
-    assert auto(1023, 2) == 64 and auto(513, 0) == 64                          # not 16-byte rows
+    assert auto(1025, 2) == 64 and auto(1031, 0) == 64                          # not 16-byte rows
     # up to 32 bytes per row: one lane per row; below 256 bytes, and up to 512 elements when not
     # whole vectors: through LDS
     assert auto(1, 1) == 1 and auto(7, 0) == 1 and auto(16, 2) == 1 and auto(8, 0) == 1
     assert auto(17, 1) == 2 and auto(9, 0) == 2 and auto(64, 1) == 2 and auto(120, 2) == 2 and auto(32, 0) == 2
-    assert auto(65, 1) == 2 and auto(100, 2) == 2 and auto(511, 0) == 2 and auto(33, 0) == 2 and auto(63, 0) == 2
+    assert auto(65, 1) == 2 and auto(100, 2) == 2 and auto(511, 0) == 2 and auto(1023, 1) == 2 and auto(33, 0) == 2 and auto(63, 0) == 2
     with pytest.raises(rs.RowSumError):
         auto(0, 1)
     with pytest.raises(rs.RowSumError):

@@ -36,7 +36,7 @@ def modes_for(N, dtype, aligned=True):
         modes += [g for g in (8, 16, 32) if N // vec <= 8 * g]
     if N <= 64:
         modes.append(1)          # one lane per row
-    if N <= 512:
+    if N <= 1024:
         modes.append(2)          # runs of rows through LDS
     return modes
 
@@ -218,9 +218,9 @@ def test_empty_batch_and_binding_checks(gpu_device):
 
 
 @pytest.mark.parametrize("dtype", DTYPES)
-@pytest.mark.parametrize("N", [1, 2, 3, 5, 10, 17, 31, 33, 63, 64, 65, 77, 100, 127, 129, 197, 255, 257, 300, 511, 512])
+@pytest.mark.parametrize("N", [1, 2, 3, 5, 10, 17, 31, 33, 63, 64, 65, 77, 100, 127, 129, 197, 255, 257, 300, 511, 512, 513, 1001, 1024])
 def test_short_rows_any_alignment(gpu_device, N, dtype):
-    """Rows of 1 to 512 elements: one lane per row (up to 64), runs of rows through LDS (two full
+    """Rows of 1 to 1024 elements: one lane per row (up to 64), runs of rows through LDS (two full
     tiles and a partial one), lane groups where the rows are whole aligned vectors, one workgroup
     per row; then the same with the base pointer one element off a 16-byte boundary, where the
     automatic path must still take the short-row kernels."""
