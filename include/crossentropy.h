@@ -75,7 +75,8 @@ int crossentropy_fwd_tuned(const void* x, const int64_t* target, float* loss, fl
                            int64_t M, int64_t N, int dtype, void* stream, int threads_per_row);
 
 /* threads_per_row of the automatic path for rows of N classes whose base is 16-byte aligned:
- * 1 below 32 classes (whatever the alignment), 2 for longer rows below 256 bytes, lane groups
+ * 1 below 32 classes (whatever the alignment), 2 for longer rows up to 256 bytes and for fp32
+ * rows up to 1024 classes, lane groups
  * for rows of whole 16-byte vectors up to 4 KiB (2 KiB for fp32), 2 for other rows of at most
  * 1024 classes (an unaligned base makes every such row take 2, and longer ones 64 threads);
  * a negative crossentropy_status for a bad dtype or N <= 0. */

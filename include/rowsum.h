@@ -66,8 +66,8 @@ int rowsum_fwd_tuned(const void* x, float* y, int64_t M, int64_t N, int dtype, v
                      int threads_per_row);
 
 /* threads_per_row of the automatic path for rows of N elements whose base is 16-byte aligned:
- * 1 up to 32 bytes per row, 2 for longer rows below 256 bytes and for rows of at most 1024
- * elements that are not whole 16-byte vectors, otherwise a thread count; a negative rowsum_status for a bad dtype or
+ * 1 up to 32 bytes per row, 2 for longer rows of at most 1024 elements, otherwise a thread
+ * count; a negative rowsum_status for a bad dtype or
  * N <= 0.  (With a base that is not 16-byte aligned every row of at most 1024 elements takes 2,
  * and longer ones the workgroup-per-row kernel with at least 64 threads.) */
 int rowsum_auto_threads_per_row(int64_t N, int dtype);

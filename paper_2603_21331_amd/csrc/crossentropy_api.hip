@@ -55,11 +55,12 @@ bool subwave_can(const void* x, int64_t N, int dtype, int lanes) {
 // more than 512 threads pay off only once every thread of 1024 still gets that much.
 int pick_threads(int64_t N, int dtype, bool aligned) {
   const int b = elem_bytes(dtype);
-  // From sweeps over rows of 16 bytes to 2 KiB: one lane per row below 32 classes; from there
+  // From sweeps over rows of 16 bytes to 4 KiB: one lane per row below 32 classes; from there
   // up to 256 bytes per row the LDS-staged kernel beats the lane groups even on aligned rows
-  // (fp16 N = 64: 37 against 51 us per 64 MiB).
+  // (fp16 N = 128: 27 against 34 us per 128 MiB), and for fp32 logits up to its limit of 1024
+  // classes (12.2 to 14.2 against 12.8 to 18.3 us per 64 MiB).
   if (N < kLaneAutoN) return 1;
-  if (N * b < kPackedAutoBytes) return kPackedCode;
+  if (N * b <= kPackedAutoBytes || (dtype == CROSSENTROPY_DTYPE_FP32 && N <= kPackedMaxN)) return kPackedCode;
   const int64_t groups = N / (16 / b);
   // Few classes: 8, 16 or 32 lanes per row, four to eight vectors per lane.  Measured at
   // 128 MiB of fp16 logits: N = 128 64 us (one workgroup per row: 322), 256 53 (166), 512 48

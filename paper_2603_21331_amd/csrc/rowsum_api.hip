@@ -34,7 +34,6 @@ constexpr int kLaneCode = 1;
 constexpr int kPackedCode = 2;
 constexpr int64_t kLaneMaxN = 64;
 constexpr int64_t kLaneAutoBytes = 32;       // automatic up to this many bytes per row
-constexpr int64_t kPackedAutoBytes = 256;    // aligned rows shorter than this also go through LDS
 constexpr int64_t kPackedMaxN = 64 * rms::kPackElems;
 constexpr int64_t kPackedMaxGrid = 8192;
 bool subwave_threads_ok(int g) { return g == 8 || g == 16 || g == 32; }
@@ -45,7 +44,8 @@ bool rows_aligned(const void* x, int64_t N, int dtype) {
 
 // Threads per row for aligned rows of `groups` 16-byte vectors, from sweeps on the GPU (fp16,
 // bf16, fp32; N = 128 ... 262144).  Rows of up to two kilobytes share a wavefront, about four
-// vectors per lane; longer rows get a workgroup in which a thread takes two or three vectors
+// vectors per lane (since the automatic path sends every row of up to 1024 elements through LDS,
+// it no longer reaches these lane groups: they remain as a forced choice); longer rows get a workgroup in which a thread takes two or three vectors
 // (all of them requested at once: a read-only stream wants loads in flight, not reuse), in
 // whole wavefronts, and no more than 768 threads: beyond that the barrier costs more than
 // the extra loads in flight bring.
@@ -57,15 +57,15 @@ int pick_threads(int64_t groups) {
   return (int)(want < kWave ? kWave : want > kWideThreads ? kWideThreads : want);
 }
 
-// The automatic choice, from sweeps over rows of 16 bytes to 2 KiB: one lane per row up to 32
-// bytes; the LDS-staged kernel for rows shorter than 256 bytes (3 to 30 % faster there than
-// lane groups even on aligned rows, ten times faster than one lane per row at 126 bytes) and
-// for rows of up to 512 elements that are not whole aligned vectors; lane groups or a
-// workgroup for the other aligned rows; a workgroup of at least one wavefront for the rest.
+// The automatic choice, from sweeps over rows of 16 bytes to 4 KiB: one lane per row up to 32
+// bytes; the LDS-staged kernel for every other row of up to 1024 elements, aligned or not (ten
+// times faster than one lane per row at 126 bytes, 30 % faster than lane groups at 128 bytes,
+// level with them to 2 % better from 256 bytes on); lane groups or a workgroup for longer
+// aligned rows; a workgroup of at least one wavefront for the rest.
 int pick_auto(int64_t N, int dtype, bool aligned) {
   const int b = elem_bytes(dtype);
   if (N * b <= kLaneAutoBytes) return kLaneCode;
-  if ((!aligned || N * b < kPackedAutoBytes) && N <= kPackedMaxN) return kPackedCode;
+  if (N <= kPackedMaxN) return kPackedCode;
   const int threads = pick_threads(N / (16 / b));
   return (!aligned && threads < kWave) ? kWave : threads;
 }

@@ -85,17 +85,17 @@ def test_automatic_threads_per_row():
             assert auto(n, dtype) in (64, 128)
     assert auto(31, 1) == 1 and auto(31, 0) == 1
     # from 32 classes up to 256 bytes per row: through LDS, aligned or not
-    assert auto(32, 1) == 2 and auto(64, 1) == 2 and auto(120, 2) == 2 and auto(32, 0) == 2 and auto(60, 0) == 2
+    assert auto(32, 1) == 2 and auto(64, 1) == 2 and auto(128, 2) == 2 and auto(32, 0) == 2 and auto(60, 0) == 2
     # few classes in whole vectors: lane groups, at most 32 / 64 / 256 (fp32: 128) vectors per row
-    assert auto(128, 1) == 8 and auto(64, 0) == 8 and auto(256, 2) == 8 and auto(264, 2) == 16
+    assert auto(136, 1) == 8 and auto(256, 2) == 8 and auto(264, 2) == 16
     assert auto(512, 1) == 16 and auto(520, 1) == 32 and auto(1000, 1) == 32 and auto(1024, 2) == 32
-    assert auto(2048, 1) == 32 and auto(2056, 2) == 64 and auto(128, 0) == 8 and auto(132, 0) == 16
-    assert auto(256, 0) == 16 and auto(512, 0) == 32 and auto(516, 0) == 64 and auto(1000, 0) == 64
+    assert auto(2048, 1) == 32 and auto(2056, 2) == 64
+    assert auto(128, 0) == 2 and auto(512, 0) == 2 and auto(1024, 0) == 2 and auto(1028, 0) == 128   # fp32: through LDS up to 1024
     # about 8 16-byte vectors per thread for the 16-bit types and 4 for fp32, in whole wavefronts
     assert auto(2064, 1) == 64 and auto(4096, 2) == 64 and auto(8192, 1) == 128 and auto(12288, 2) == 192
     assert auto(16384, 1) == 256 and auto(32000, 1) == 512 and auto(50257, 2) == 512
     assert auto(65536, 1) == 1024 and auto(131072, 2) == 1024 and auto(1 << 30, 1) == 1024
-    assert auto(1024, 0) == 64 and auto(4096, 0) == 256 and auto(8192, 0) == 512
+    assert auto(2048, 0) == 128 and auto(4096, 0) == 256 and auto(8192, 0) == 512
     assert auto(16000, 0) == 512 and auto(32000, 0) == 1024 and auto(65536, 0) == 1024
     with pytest.raises(ce.CrossEntropyError):
         auto(0, 1)

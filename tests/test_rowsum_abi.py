@@ -63,11 +63,11 @@ def test_empty_batch_and_bad_thread_counts():
 
 def test_automatic_threads_per_row():
     auto = rs.rowsum_auto_threads_per_row
-    # rows of up to 2 KiB share a wavefront, about four 16-byte vectors per lane
-    assert auto(128, 1) == 8 and auto(64, 0) == 8 and auto(256, 2) == 8 and auto(512, 1) == 16 and auto(256, 0) == 16
-    assert auto(1024, 1) == 32 and auto(512, 0) == 32
+    # just past the LDS-staged kernel's 1024 elements: one wavefront per row
+    assert auto(1032, 1) == 64 and auto(2048, 1) == 64 and auto(1028, 0) == 64 and auto(2048, 0) == 192
+    # (rows of up to 1024 elements never get here: they go through LDS, see below)
     # longer rows: two or three vectors per thread, whole wavefronts, at most 768 threads
-    assert auto(1032, 1) == 64 and auto(2048, 1) == 64 and auto(4096, 1) == 192 and auto(8192, 1) == 384
+    assert auto(4096, 1) == 192 and auto(8192, 1) == 384
     assert auto(4096, 0) == 384 and auto(8192, 0) == 768 and auto(8192, 2) == 384
     assert auto(32000, 1) == 768 and auto(65536, 1) == 768 and auto(1 << 30, 2) == 768
     assert auto(1025, 2) == 64 and auto(1031, 0) == 64                          # not 16-byte rows
@@ -76,6 +76,7 @@ def test_automatic_threads_per_row():
     assert auto(1, 1) == 1 and auto(7, 0) == 1 and auto(16, 2) == 1 and auto(8, 0) == 1
     assert auto(17, 1) == 2 and auto(9, 0) == 2 and auto(64, 1) == 2 and auto(120, 2) == 2 and auto(32, 0) == 2
     assert auto(65, 1) == 2 and auto(100, 2) == 2 and auto(511, 0) == 2 and auto(1023, 1) == 2 and auto(33, 0) == 2 and auto(63, 0) == 2
+    assert auto(128, 1) == 2 and auto(512, 2) == 2 and auto(1024, 1) == 2 and auto(1024, 0) == 2
     with pytest.raises(rs.RowSumError):
         auto(0, 1)
     with pytest.raises(rs.RowSumError):
