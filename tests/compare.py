@@ -76,7 +76,7 @@ def check_parity(got: np.ndarray, want: np.ndarray, dtype: int, what: str = "") 
 
 
 # ---- row softmax ---------------------------------------------------------------------------
-# Tolerances (derived in the design doc): bf16 <= 1 ulp, fp16 <= 2 ulp against the oracle after its
+# Tolerances: bf16 <= 1 ulp, fp16 <= 2 ulp against the oracle after its
 # single rounding; fp32 |g - o| <= 1e-5 |o| + 2 subnormal quanta (outputs below FLT_MIN have
 # fewer than 24 significant bits, so a purely relative bound cannot hold there).
 SOFTMAX_FP32_ABS_FLOOR = 2.0 * 2.0 ** -149
