@@ -1,18 +1,20 @@
-// Short rows that are not 16-byte aligned (odd lengths such as a 77- or 197-entry attention
-// row, or a base pointer off a boundary), staged through LDS.
+// Short rows, several per workgroup, staged through LDS: rows that are not 16-byte aligned (odd
+// lengths such as a 77- or 197-entry attention row, or a base pointer off a boundary) and rows
+// too short to fill a lane group.
 //
 // One workgroup per row pays a launch slot and two partly used cache lines for a few hundred
 // bytes, and a lane group cannot use 128-bit accesses on rows that start anywhere.  Consecutive
 // rows are contiguous in memory, though: a workgroup of 256 threads takes a run of rows (up to
 // 16 KiB), copies that byte range into LDS with aligned 128-bit accesses that are contiguous
 // across the workgroup (the few bytes before the first and after the last 16-byte boundary go
-// element by element), lets lane groups of L = 8, 16, 32 or 64 lanes work on one row each
-// out of LDS (element reads, up to kPackElems elements per lane: the kernels are bound by
-// vector-ALU issue, and the reductions and the per-row arithmetic of a lane group cost the same
-// however many elements its lanes hold, so few lanes with many elements beat many lanes with
-// few; results written back in place), and copies the range out to y the same way.  Every byte of x and y still crosses
-// HBM once.  The paper's playbook names the ingredients (vectorised, coalesced accesses;
-// shared-memory staging) without giving a kernel; the arrangement is this library's.
+// element by element), lets lane groups of L = 8, 16, 32 or 64 lanes work on one row each out
+// of LDS (element reads, up to kPackElems elements per lane, results written back in place),
+// and copies the range out to y the same way.  Every byte of x and y still crosses HBM once.
+// The kernels are bound by vector-ALU issue, and the reductions and the per-row arithmetic of a
+// lane group cost the same however many elements its lanes hold, so few lanes with many
+// elements beat many lanes with few.  The paper's playbook names the ingredients (vectorised,
+// coalesced accesses; shared-memory staging) without giving a kernel; the arrangement is this
+// library's.
 #pragma once
 
 #include "vec_io.h"
