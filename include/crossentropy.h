@@ -44,9 +44,9 @@ typedef enum {
   CROSSENTROPY_ERR_INVALID_ARG = -1, /* null x/target/loss, M < 0, N <= 0 or >= 2^32, bad dtype,
                                         misaligned pointer, bad threads_per_row */
   CROSSENTROPY_ERR_UNSUPPORTED = -2, /* a forced lane-group size (8, 16, 32) on rows that are not
-                                        16-byte aligned or longer than 8 vectors per lane, one
-                                        lane per row with N > 64, or the LDS-staged kernel with
-                                        N > 1024; nothing was launched */
+                                        16-byte aligned or longer than 8 vectors per lane, or
+                                        the LDS-staged kernel with N > 1024; nothing was
+                                        launched */
   CROSSENTROPY_ERR_LAUNCH = -3       /* the HIP runtime refused the launch */
 } crossentropy_status;
 
@@ -66,17 +66,15 @@ int crossentropy_fwd(const void* x, const int64_t* target, float* loss, float* l
 /* Same, with the number of threads that share one row forced: a multiple of 64 from 64 to
  * 1024 (one workgroup per row; every such count runs every shape), or 8, 16 or 32 (lane
  * groups, several rows per wavefront: x 16-byte aligned, N * sizeof(dtype) a multiple of 16 and
- * at most 128 bytes per lane, otherwise CROSSENTROPY_ERR_UNSUPPORTED), or 1 (one lane per row:
- * any alignment, N <= 64, otherwise CROSSENTROPY_ERR_UNSUPPORTED), or 2 (not a thread count:
- * runs of rows copied through LDS, 8 to 64 lanes per row chosen from N; any alignment,
+ * at most 128 bytes per lane, otherwise CROSSENTROPY_ERR_UNSUPPORTED), or 2 (not a thread count:
+ * runs of rows copied through LDS, 1 to 64 lanes per row chosen from N; any alignment,
  * N <= 1024, otherwise CROSSENTROPY_ERR_UNSUPPORTED).  Any other value is
  * CROSSENTROPY_ERR_INVALID_ARG. */
 int crossentropy_fwd_tuned(const void* x, const int64_t* target, float* loss, float* lse,
                            int64_t M, int64_t N, int dtype, void* stream, int threads_per_row);
 
 /* threads_per_row of the automatic path for rows of N classes whose base is 16-byte aligned:
- * 1 below 32 classes (whatever the alignment), 2 for longer rows up to 256 bytes and for fp32
- * rows up to 1024 classes, lane groups
+ * 2 for rows up to 256 bytes and for fp32 rows up to 1024 classes, lane groups
  * for rows of whole 16-byte vectors up to 4 KiB (2 KiB for fp32), 2 for other rows of at most
  * 1024 classes (an unaligned base makes every such row take 2, and longer ones 64 threads);
  * a negative crossentropy_status for a bad dtype or N <= 0. */

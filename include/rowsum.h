@@ -58,17 +58,16 @@ int rowsum_fwd(const void* x, float* y, int64_t M, int64_t N, int dtype, void* s
 
 /* Same, with the number of threads that share one row forced: a multiple of 64 from 64 to
  * 1024 (one workgroup per row, every shape), or 8, 16 or 32 (several rows per wavefront:
- * only for 16-byte aligned rows of at most 8 * threads_per_row 16-byte vectors), or 1 (one
- * lane per row: any alignment, N <= 64), or 2 (not a thread count: runs of rows copied through
- * LDS, 8 to 64 lanes per row chosen from N; any alignment, N <= 1024).  Any other value, or a
- * shape the value does not allow, is ROWSUM_ERR_INVALID_ARG. */
+ * only for 16-byte aligned rows of at most 8 * threads_per_row 16-byte vectors), or 2 (not a
+ * thread count: runs of rows copied through LDS, 1 to 64 lanes per row chosen from N; any
+ * alignment, N <= 1024).  Any other value, or a shape the value does not allow, is
+ * ROWSUM_ERR_INVALID_ARG. */
 int rowsum_fwd_tuned(const void* x, float* y, int64_t M, int64_t N, int dtype, void* stream,
                      int threads_per_row);
 
 /* threads_per_row of the automatic path for rows of N elements whose base is 16-byte aligned:
- * 1 up to 32 bytes per row, 2 for longer rows of at most 1024 elements, otherwise a thread
- * count; a negative rowsum_status for a bad dtype or
- * N <= 0.  (With a base that is not 16-byte aligned every row of at most 1024 elements takes 2,
+ * 2 for rows of at most 1024 elements, otherwise a thread count; a negative rowsum_status for
+ * a bad dtype or N <= 0.  (With a base that is not 16-byte aligned every row of at most 1024 elements takes 2,
  * and longer ones the workgroup-per-row kernel with at least 64 threads.) */
 int rowsum_auto_threads_per_row(int64_t N, int dtype);
 

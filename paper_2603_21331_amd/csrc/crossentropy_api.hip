@@ -30,14 +30,11 @@ constexpr int64_t kPackedMaxN = 64 * rms::kPackElems;
 constexpr int64_t kPackedMaxGrid = 8192;
 
 bool threads_ok(int g) {
-  return g == 1 || g == kPackedCode || g == 8 || g == 16 || g == 32 ||
+  return g == kPackedCode || g == 8 || g == 16 || g == 32 ||
          (g >= kWave && g <= kMaxThreads && g % kWave == 0);
 }
 
-// One lane per row: what the forced choice accepts, and where the automatic path takes it.
-constexpr int64_t kLaneMaxN = 64;
-constexpr int64_t kLaneAutoN = 32;           // automatic below this many classes
-constexpr int64_t kPackedAutoBytes = 256;    // aligned rows shorter than this also go through LDS
+constexpr int64_t kPackedAutoBytes = 256;    // aligned 16-bit rows up to this long also go through LDS
 
 // Lane groups take 16-byte aligned rows of at most 8 vectors per lane.
 constexpr int kSubwaveMaxChunks = 8;
@@ -55,11 +52,10 @@ bool subwave_can(const void* x, int64_t N, int dtype, int lanes) {
 // more than 512 threads pay off only once every thread of 1024 still gets that much.
 int pick_threads(int64_t N, int dtype, bool aligned) {
   const int b = elem_bytes(dtype);
-  // From sweeps over rows of 16 bytes to 4 KiB: one lane per row below 32 classes; from there
-  // up to 256 bytes per row the LDS-staged kernel beats the lane groups even on aligned rows
-  // (fp16 N = 128: 27 against 34 us per 128 MiB), and for fp32 logits up to its limit of 1024
-  // classes (12.2 to 14.2 against 12.8 to 18.3 us per 64 MiB).
-  if (N < kLaneAutoN) return 1;
+  // From sweeps over rows of 16 bytes to 4 KiB: up to 256 bytes per row the LDS-staged kernel
+  // beats the lane groups even on aligned rows (fp16 N = 128: 27 against 34 us per 128 MiB), and
+  // for fp32 logits up to its limit of 1024 classes (12.2 to 14.2 against 12.8 to 18.3 us per
+  // 64 MiB); a handful of classes (a 10-way classifier) take it with one lane per row.
   if (N * b <= kPackedAutoBytes || (dtype == CROSSENTROPY_DTYPE_FP32 && N <= kPackedMaxN)) return kPackedCode;
   const int64_t groups = N / (16 / b);
   // Few classes: 8, 16 or 32 lanes per row, four to eight vectors per lane.  Measured at
@@ -116,30 +112,29 @@ void launch_packed(const void* x, const int64_t* target, float* loss, float* lse
 }
 
 // Elements per lane: exactly what the row needs in the chosen lane group, (E - 1) * L < N <=
-// E * L, which is 9 to 16 except in the narrowest group, where rows of up to 64 elements need 1 to 8.
+// E * L, which is 9 to 16 except for one lane per row, where rows of up to 16 elements need 1 to 16.
 template <int DT, int L, int E = rms::kPackElems>
 void launch_packed_lanes(const void* x, const int64_t* target, float* loss, float* lse, int64_t M,
                          int64_t N, hipStream_t stream) {
   if ((N + L - 1) / L == E) launch_packed<DT, L, E>(x, target, loss, lse, M, N, stream);
-  else if constexpr (E > (L == 8 ? 1 : rms::kPackElems / 2 + 1)) launch_packed_lanes<DT, L, E - 1>(x, target, loss, lse, M, N, stream);
+  else if constexpr (E > ((L == 1 || L == 8) ? 1 : rms::kPackElems / 2 + 1)) launch_packed_lanes<DT, L, E - 1>(x, target, loss, lse, M, N, stream);
 }
 
 template <int DT>
 int run_typed(const void* x, const int64_t* target, float* loss, float* lse, int64_t M, int64_t N,
               hipStream_t stream, int threads) {
   if (threads == kPackedCode) {
-    const int64_t lanes = (N + rms::kPackElems - 1) / rms::kPackElems;   // lanes the row needs
-    if (lanes <= 8) launch_packed_lanes<DT, 8>(x, target, loss, lse, M, N, stream);
+    int64_t lanes = (N + rms::kPackElems - 1) / rms::kPackElems;   // lanes the row needs
+  // Rows of a multiple of 128 bytes put the rows of narrow lane groups on a few LDS banks; such
+  // rows get at least 8 lanes (at 64 bytes the narrow groups still win here: fewer reductions).
+  if ((N * rms::Storage<DT>::kBytes) % 128 == 0 && lanes < 8) lanes = 8;
+    if (lanes <= 1) launch_packed_lanes<DT, 1>(x, target, loss, lse, M, N, stream);
+    else if (lanes <= 2) launch_packed_lanes<DT, 2>(x, target, loss, lse, M, N, stream);
+    else if (lanes <= 4) launch_packed_lanes<DT, 4>(x, target, loss, lse, M, N, stream);
+    else if (lanes <= 8) launch_packed_lanes<DT, 8>(x, target, loss, lse, M, N, stream);
     else if (lanes <= 16) launch_packed_lanes<DT, 16>(x, target, loss, lse, M, N, stream);
     else if (lanes <= 32) launch_packed_lanes<DT, 32>(x, target, loss, lse, M, N, stream);
     else launch_packed_lanes<DT, 64>(x, target, loss, lse, M, N, stream);
-    return hipGetLastError() == hipSuccess ? CROSSENTROPY_OK : CROSSENTROPY_ERR_LAUNCH;
-  }
-  if (threads == 1) {
-    int64_t blocks = (M + rms::kCeLaneThreads - 1) / rms::kCeLaneThreads;
-    if (blocks > kMaxGrid) blocks = kMaxGrid;
-    hipLaunchKernelGGL((rms::crossentropy_lane_kernel<DT>), dim3((unsigned)blocks),
-                       dim3(rms::kCeLaneThreads), 0, stream, x, target, loss, lse, M, (int)N);
     return hipGetLastError() == hipSuccess ? CROSSENTROPY_OK : CROSSENTROPY_ERR_LAUNCH;
   }
   if (threads < kWave) {
@@ -166,9 +161,8 @@ int run(const void* x, const int64_t* target, float* loss, float* lse, int64_t M
   if (threads == 0) {
     const bool aligned = ((uintptr_t)x & 15u) == 0 && (N * b) % 16 == 0;
     threads = pick_threads(N, dtype, aligned);
-  } else if (threads == 1 ? N > kLaneMaxN
-             : threads == kPackedCode ? N > kPackedMaxN
-                                      : (threads < kWave && !subwave_can(x, N, dtype, threads))) {
+  } else if (threads == kPackedCode ? N > kPackedMaxN
+                                    : (threads < kWave && !subwave_can(x, N, dtype, threads))) {
     return CROSSENTROPY_ERR_UNSUPPORTED;
   }
   hipStream_t s = static_cast<hipStream_t>(stream);

@@ -272,38 +272,4 @@ crossentropy_packed_kernel(const void* x, const int64_t* __restrict__ target, fl
   }
 }
 
-// A handful of classes (rows shorter than 128 bytes, any alignment: a 10-way classifier): one
-// row per lane.  Neighbouring lanes read neighbouring rows, so a wavefront's loads still fall
-// into a few contiguous cache lines; the lane folds its row four logits at a time into the same
-// online pair, and nothing crosses lanes.
-constexpr int kCeLaneThreads = 256;
-
-template <int DT>
-__global__ void __launch_bounds__(kCeLaneThreads)
-crossentropy_lane_kernel(const void* x, const int64_t* __restrict__ target, float* __restrict__ loss,
-                         float* __restrict__ lse_out, int64_t M, int N) {
-  using S = Storage<DT>;
-  for (int64_t row = (int64_t)blockIdx.x * kCeLaneThreads + threadIdx.x; row < M;
-       row += (int64_t)gridDim.x * kCeLaneThreads) {
-    const int64_t at = row * N;
-    float m = kCeNegInf, s = 0.f;
-    int j = 0;
-    for (; j + 4 <= N; j += 4) {
-      const float f[4] = {S::load_one(x, at + j), S::load_one(x, at + j + 1),
-                          S::load_one(x, at + j + 2), S::load_one(x, at + j + 3)};
-      ce_fold<4>(f, m, s);
-    }
-    for (; j < N; ++j) {
-      const float f[1] = {S::load_one(x, at + j)};
-      ce_fold<1>(f, m, s);
-    }
-    const float log_s = m == kCeNegInf ? __builtin_nanf("") : ce_log_fast(s);
-    if (lse_out) lse_out[row] = m + log_s;
-    const int64_t cls = target[row];
-    float out = 0.0f;                                     // target outside [0, N): ignored row
-    if (cls >= 0 && cls < N) out = log_s - (S::load_one(x, at + cls) - m);
-    loss[row] = out;
-  }
-}
-
 }  // namespace rms

@@ -197,19 +197,25 @@ void launch_packed(const Args& a) {
                      (float)a.N, a.eps);
 }
 
-// Lanes per row: the narrowest group that holds the row with 16 elements per lane; elements per
-// lane: exactly what the row then needs, (E - 1) * L < N <= E * L, which is 9 to 16 except in the
-// narrowest group, where rows of up to 64 elements need 1 to 8.
+// Lanes per row: the narrowest group (1, 2, 4 ... 64 lanes) that holds the row with 16 elements per lane; elements per
+// lane: exactly what the row then needs, (E - 1) * L < N <= E * L, which is 9 to 16 except for
+// one lane per row, where rows of up to 16 elements need 1 to 16.
 template <int DT, int L, int E = rms::kPackElems>
 void launch_packed_lanes(const Args& a) {
   if ((a.N + L - 1) / L == E) launch_packed<DT, L, E>(a);
-  else if constexpr (E > (L == 8 ? 1 : rms::kPackElems / 2 + 1)) launch_packed_lanes<DT, L, E - 1>(a);
+  else if constexpr (E > ((L == 1 || L == 8) ? 1 : rms::kPackElems / 2 + 1)) launch_packed_lanes<DT, L, E - 1>(a);
 }
 
 template <int DT>
 void dispatch_packed(const Args& a) {
-  const int64_t lanes = (a.N + rms::kPackElems - 1) / rms::kPackElems;   // lanes the row needs
-  if (lanes <= 8) launch_packed_lanes<DT, 8>(a);
+  int64_t lanes = (a.N + rms::kPackElems - 1) / rms::kPackElems;   // lanes the row needs
+  // Rows of a multiple of 64 bytes put the rows of narrow lane groups on a few LDS banks (64-byte
+  // rows on one or two lanes each: 34 us against 27 on eight); such rows get at least 8 lanes.
+  if ((a.N * rms::Storage<DT>::kBytes) % 64 == 0 && lanes < 8) lanes = 8;
+  if (lanes <= 1) launch_packed_lanes<DT, 1>(a);
+  else if (lanes <= 2) launch_packed_lanes<DT, 2>(a);
+  else if (lanes <= 4) launch_packed_lanes<DT, 4>(a);
+  else if (lanes <= 8) launch_packed_lanes<DT, 8>(a);
   else if (lanes <= 16) launch_packed_lanes<DT, 16>(a);
   else if (lanes <= 32) launch_packed_lanes<DT, 32>(a);
   else launch_packed_lanes<DT, 64>(a);

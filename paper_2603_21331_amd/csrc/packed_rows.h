@@ -7,7 +7,7 @@
 // rows are contiguous in memory, though: a workgroup of 256 threads takes a run of rows (up to
 // 16 KiB), copies that byte range into LDS with aligned 128-bit accesses that are contiguous
 // across the workgroup (the few bytes before the first and after the last 16-byte boundary go
-// element by element), lets lane groups of L = 8, 16, 32 or 64 lanes work on one row each out
+// element by element), lets lane groups of L = 1, 2, 4 ... 64 lanes work on one row each out
 // of LDS (element reads, up to kPackElems elements per lane, results written back in place),
 // and copies the range out to y the same way.  Every byte of x and y still crosses HBM once.
 // The kernels are bound by vector-ALU issue, and the reductions and the per-row arithmetic of a
@@ -117,17 +117,24 @@ __device__ __forceinline__ void tile_drain(char* dst, const u32x4* tile, TileCut
   if (t < c.tail / EB) Storage<DT>::store_one(dst, done + t, tile_get<DT>(tile, skew_elems + done + t));
 }
 
-// Sum / maximum over aligned groups of L lanes (L == 64: the whole wavefront), result in
-// every lane of the group.  All 64 lanes must be active.
+// Sum / maximum over aligned groups of L lanes (1: the lane itself; 2 and 4: the first steps of
+// the butterfly inside a quad; 64: the whole wavefront), result in every lane of the group.
+// All 64 lanes must be active.
 template <int L>
 __device__ __forceinline__ float group_sum(float v) {
-  if constexpr (L == 64) return wave_sum(v);
+  if constexpr (L == 1) return v;
+  else if constexpr (L == 2) return add_dpp<0xB1>(v);
+  else if constexpr (L == 4) return add_dpp<0x4E>(add_dpp<0xB1>(v));
+  else if constexpr (L == 64) return wave_sum(v);
   else return subwave_sum<L>(v);
 }
 
 template <int L>
 __device__ __forceinline__ float group_max(float v) {
-  if constexpr (L == 64) return wave_max(v);
+  if constexpr (L == 1) return v;
+  else if constexpr (L == 2) return max_dpp<0xB1>(v);
+  else if constexpr (L == 4) return max_dpp<0x4E>(max_dpp<0xB1>(v));
+  else if constexpr (L == 64) return wave_max(v);
   else return subwave_max<L>(v);
 }
 

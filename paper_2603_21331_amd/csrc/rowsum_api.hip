@@ -27,13 +27,9 @@ int elem_bytes(int dtype) {
 
 bool block_threads_ok(int g) { return g >= kWave && g <= kMaxThreads && g % kWave == 0; }
 
-// threads_per_row 1: one lane per row (N <= 64; automatic up to 32 bytes per row).
-// threads_per_row 2: not a thread count, the LDS-staged kernel (N <= 512, lane groups from N;
-// automatic for such rows when they are not whole aligned vectors).
-constexpr int kLaneCode = 1;
+// threads_per_row 2: not a thread count, the LDS-staged kernel (N <= 1024, lane groups of 1 to
+// 64 lanes chosen from N; what the automatic path takes for every such row).
 constexpr int kPackedCode = 2;
-constexpr int64_t kLaneMaxN = 64;
-constexpr int64_t kLaneAutoBytes = 32;       // automatic up to this many bytes per row
 constexpr int64_t kPackedMaxN = 64 * rms::kPackElems;
 constexpr int64_t kPackedMaxGrid = 8192;
 bool subwave_threads_ok(int g) { return g == 8 || g == 16 || g == 32; }
@@ -57,14 +53,13 @@ int pick_threads(int64_t groups) {
   return (int)(want < kWave ? kWave : want > kWideThreads ? kWideThreads : want);
 }
 
-// The automatic choice, from sweeps over rows of 16 bytes to 4 KiB: one lane per row up to 32
-// bytes; the LDS-staged kernel for every other row of up to 1024 elements, aligned or not (ten
-// times faster than one lane per row at 126 bytes, 30 % faster than lane groups at 128 bytes,
-// level with them to 2 % better from 256 bytes on); lane groups or a workgroup for longer
-// aligned rows; a workgroup of at least one wavefront for the rest.
+// The automatic choice, from sweeps over rows of 16 bytes to 4 KiB: the LDS-staged kernel for
+// every row of up to 1024 elements, aligned or not (a handful of elements: one lane per row,
+// 14.5 us per 64 MiB at fp16 N = 8; 30 % faster than lane groups at 128 bytes, level with them to
+// 2 % better from 256 bytes on); lane groups or a workgroup for longer aligned rows; a workgroup
+// of at least one wavefront for the rest.
 int pick_auto(int64_t N, int dtype, bool aligned) {
   const int b = elem_bytes(dtype);
-  if (N * b <= kLaneAutoBytes) return kLaneCode;
   if (N <= kPackedMaxN) return kPackedCode;
   const int threads = pick_threads(N / (16 / b));
   return (!aligned && threads < kWave) ? kWave : threads;
@@ -98,15 +93,6 @@ int run_subwave_l(const void* x, float* y, int64_t M, int nvec, hipStream_t stre
   return hipGetLastError() == hipSuccess ? ROWSUM_OK : ROWSUM_ERR_LAUNCH;
 }
 
-template <int DT>
-int run_lane(const void* x, float* y, int64_t M, int64_t N, hipStream_t stream) {
-  int64_t blocks = (M + rms::kRsLaneThreads - 1) / rms::kRsLaneThreads;
-  if (blocks > kMaxGrid) blocks = kMaxGrid;
-  hipLaunchKernelGGL((rms::rowsum_lane_kernel<DT>), dim3((unsigned)blocks), dim3(rms::kRsLaneThreads),
-                     0, stream, x, y, M, (int)N);
-  return hipGetLastError() == hipSuccess ? ROWSUM_OK : ROWSUM_ERR_LAUNCH;
-}
-
 template <int DT, int L, int E>
 void launch_packed(const void* x, float* y, int64_t M, int64_t N, hipStream_t stream) {
   int tile_rows = rms::kPackTileBytes / ((int)N * rms::Storage<DT>::kBytes);
@@ -118,17 +104,23 @@ void launch_packed(const void* x, float* y, int64_t M, int64_t N, hipStream_t st
 }
 
 // Elements per lane: exactly what the row needs in the chosen lane group, (E - 1) * L < N <=
-// E * L, which is 9 to 16 except in the narrowest group, where rows of up to 64 elements need 1 to 8.
+// E * L, which is 9 to 16 except for one lane per row, where rows of up to 16 elements need 1 to 16.
 template <int DT, int L, int E = rms::kPackElems>
 void launch_packed_lanes(const void* x, float* y, int64_t M, int64_t N, hipStream_t stream) {
   if ((N + L - 1) / L == E) launch_packed<DT, L, E>(x, y, M, N, stream);
-  else if constexpr (E > (L == 8 ? 1 : rms::kPackElems / 2 + 1)) launch_packed_lanes<DT, L, E - 1>(x, y, M, N, stream);
+  else if constexpr (E > ((L == 1 || L == 8) ? 1 : rms::kPackElems / 2 + 1)) launch_packed_lanes<DT, L, E - 1>(x, y, M, N, stream);
 }
 
 template <int DT>
 int run_packed(const void* x, float* y, int64_t M, int64_t N, hipStream_t stream) {
-  const int64_t lanes = (N + rms::kPackElems - 1) / rms::kPackElems;   // lanes the row needs
-  if (lanes <= 8) launch_packed_lanes<DT, 8>(x, y, M, N, stream);
+  int64_t lanes = (N + rms::kPackElems - 1) / rms::kPackElems;   // lanes the row needs
+  // Rows of a multiple of 64 bytes put the rows of narrow lane groups on a few LDS banks; such
+  // rows get at least 8 lanes.
+  if ((N * rms::Storage<DT>::kBytes) % 64 == 0 && lanes < 8) lanes = 8;
+  if (lanes <= 1) launch_packed_lanes<DT, 1>(x, y, M, N, stream);
+  else if (lanes <= 2) launch_packed_lanes<DT, 2>(x, y, M, N, stream);
+  else if (lanes <= 4) launch_packed_lanes<DT, 4>(x, y, M, N, stream);
+  else if (lanes <= 8) launch_packed_lanes<DT, 8>(x, y, M, N, stream);
   else if (lanes <= 16) launch_packed_lanes<DT, 16>(x, y, M, N, stream);
   else if (lanes <= 32) launch_packed_lanes<DT, 32>(x, y, M, N, stream);
   else launch_packed_lanes<DT, 64>(x, y, M, N, stream);
@@ -139,7 +131,6 @@ template <int DT>
 int run_typed(const void* x, float* y, int64_t M, int64_t N, int nvec, hipStream_t stream,
               int threads) {
   switch (threads) {
-    case kLaneCode: return run_lane<DT>(x, y, M, N, stream);
     case kPackedCode: return run_packed<DT>(x, y, M, N, stream);
     case 8: return run_subwave_l<DT, 8>(x, y, M, nvec, stream);
     case 16: return run_subwave_l<DT, 16>(x, y, M, nvec, stream);
@@ -154,9 +145,7 @@ int run(const void* x, float* y, int64_t M, int64_t N, int dtype, void* stream, 
   const int64_t groups = N / (16 / elem_bytes(dtype));
   const bool aligned = rows_aligned(x, N, dtype);
   if (threads != 0) {
-    if (threads == kLaneCode) {
-      if (N > kLaneMaxN) return ROWSUM_ERR_INVALID_ARG;
-    } else if (threads == kPackedCode) {
+    if (threads == kPackedCode) {
       if (N > kPackedMaxN) return ROWSUM_ERR_INVALID_ARG;
     } else if (subwave_threads_ok(threads)) {
       if (!aligned || groups > (int64_t)threads * kSubwaveMaxChunks) return ROWSUM_ERR_INVALID_ARG;

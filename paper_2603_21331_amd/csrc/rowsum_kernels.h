@@ -191,30 +191,4 @@ rowsum_packed_kernel(const void* x, float* __restrict__ y, int64_t M, int N, int
   }
 }
 
-// A handful of elements per row (rows shorter than 128 bytes, any alignment): one row per
-// lane.  Neighbouring lanes read neighbouring rows, so a wavefront's loads still fall into a
-// few contiguous cache lines.  Four running sums, folded at the end: no element passes through
-// more than N / 4 + 2 additions.
-constexpr int kRsLaneThreads = 256;
-
-template <int DT>
-__global__ void __launch_bounds__(kRsLaneThreads)
-rowsum_lane_kernel(const void* x, float* __restrict__ y, int64_t M, int N) {
-  using S = Storage<DT>;
-  for (int64_t row = (int64_t)blockIdx.x * kRsLaneThreads + threadIdx.x; row < M;
-       row += (int64_t)gridDim.x * kRsLaneThreads) {
-    const int64_t at = row * N;
-    float acc[4] = {0.f, 0.f, 0.f, 0.f};
-    int j = 0;
-    for (; j + 4 <= N; j += 4) {
-      acc[0] += S::load_one(x, at + j);
-      acc[1] += S::load_one(x, at + j + 1);
-      acc[2] += S::load_one(x, at + j + 2);
-      acc[3] += S::load_one(x, at + j + 3);
-    }
-    for (int k = 0; j < N; ++j, ++k) acc[k] += S::load_one(x, at + j);
-    y[row] = (acc[0] + acc[1]) + (acc[2] + acc[3]);
-  }
-}
-
 }  // namespace rms

@@ -48,7 +48,7 @@ def test_empty_batch_and_bad_thread_counts():
     lib = ce.load()
     assert lib.crossentropy_fwd(None, None, None, None, 0, 16, 2, None) == ce.CROSSENTROPY_OK
     assert lib.crossentropy_fwd_tuned(None, None, None, None, 0, 16, 2, None, 64) == ce.CROSSENTROPY_OK
-    for bad in (0, 3, 4, 24, 48, 100, 1088, 2048, -64, -1):
+    for bad in (0, 1, 3, 4, 24, 48, 100, 1088, 2048, -64, -1):
         assert lib.crossentropy_fwd_tuned(P, P + BIG, P + 2 * BIG, None, 4, 4096, 2, None, bad) == \
             ce.CROSSENTROPY_ERR_INVALID_ARG
 
@@ -68,22 +68,19 @@ def test_lane_groups_refuse_rows_they_cannot_take():
     assert f(P + 2, P + BIG, P + 2 * BIG, None, 4, 1025, 1, None, 2) == ce.CROSSENTROPY_ERR_UNSUPPORTED
     assert f(P, P + BIG, P + 2 * BIG, None, 4, 4096, 0, None, 2) == ce.CROSSENTROPY_ERR_UNSUPPORTED
     assert f(P + 2, P + BIG, P + 2 * BIG, None, 0, 100, 1, None, 2) == ce.CROSSENTROPY_OK
-    # one lane per row: any alignment, at most 64 classes
-    assert f(P, P + BIG, P + 2 * BIG, None, 4, 65, 1, None, 1) == ce.CROSSENTROPY_ERR_UNSUPPORTED
-    assert f(P, P + BIG, P + 2 * BIG, None, 4, 4096, 0, None, 1) == ce.CROSSENTROPY_ERR_UNSUPPORTED
-    assert f(P + 2, P + BIG, P + 2 * BIG, None, 0, 10, 1, None, 1) == ce.CROSSENTROPY_OK
+    # 1 was one lane per row once; the LDS-staged kernel covers those rows now
+    assert f(P, P + BIG, P + 2 * BIG, None, 4, 10, 1, None, 1) == ce.CROSSENTROPY_ERR_INVALID_ARG
 
 
 def test_automatic_threads_per_row():
     auto = ce.crossentropy_auto_threads_per_row
     for dtype in (0, 1, 2):
-        for n in (1, 7, 10, 31):             # rows shorter than 128 bytes: one lane per row
-            assert auto(n, dtype) == 1
+        for n in (1, 7, 10, 31):             # a handful of classes: through LDS, one lane per row
+            assert auto(n, dtype) == 2
         for n in (65, 130, 511, 1001):       # up to 1024 classes, not whole 16-byte vectors: through LDS
             assert auto(n, dtype) == 2
         for n in (1025, 1031):               # longer rows that are not whole 16-byte vectors: a workgroup
             assert auto(n, dtype) in (64, 128)
-    assert auto(31, 1) == 1 and auto(31, 0) == 1
     # from 32 classes up to 256 bytes per row: through LDS, aligned or not
     assert auto(32, 1) == 2 and auto(64, 1) == 2 and auto(128, 2) == 2 and auto(32, 0) == 2 and auto(60, 0) == 2
     # few classes in whole vectors: lane groups, at most 32 / 64 / 256 (fp32: 128) vectors per row

@@ -16,8 +16,8 @@ from paper_2603_21331_amd import binding, inputs
 pytestmark = pytest.mark.gpu
 
 DTYPES = [inputs.FP32, inputs.FP16, inputs.BF16]
-# every lane-group size (8, 16, 32, 64 lanes of up to 16 elements) at its limits and inside
-LENGTHS = [1, 3, 7, 50, 63, 64, 65, 77, 127, 129, 197, 255, 257, 300, 511, 512, 513, 777, 1023, 1024]
+# every lane-group size (1, 2, 4 ... 64 lanes of up to 16 elements) at its limits and inside
+LENGTHS = [1, 3, 7, 16, 17, 31, 32, 33, 50, 63, 64, 65, 77, 127, 129, 197, 255, 257, 300, 511, 512, 513, 777, 1023, 1024]
 
 
 def offset_view(a, dtype, device, off, shape):

@@ -47,12 +47,10 @@ def test_empty_batch_and_bad_thread_counts():
     lib = rs.load()
     assert lib.rowsum_fwd(None, None, 0, 16, 2, None) == rs.ROWSUM_OK
     assert lib.rowsum_fwd_tuned(None, None, 0, 16, 2, None, 64) == rs.ROWSUM_OK
-    for bad in (0, 1, 2, 3, 4, 24, 100, 1088, 2048, -64):   # 1 and 2: valid codes, but not for 4096 elements
+    for bad in (0, 1, 2, 3, 4, 24, 100, 1088, 2048, -64):   # 2: a valid code, but not for 4096 elements
         assert lib.rowsum_fwd_tuned(P, P + BIG, 4, 4096, 2, None, bad) == rs.ROWSUM_ERR_INVALID_ARG
-    # one lane per row takes at most 64 elements, the LDS-staged kernel at most 1024; any alignment
-    assert lib.rowsum_fwd_tuned(P + 2, P + BIG, 4, 65, 1, None, 1) == rs.ROWSUM_ERR_INVALID_ARG
+    # the LDS-staged kernel (code 2) takes at most 1024 elements, at any alignment
     assert lib.rowsum_fwd_tuned(P + 2, P + BIG, 4, 1025, 1, None, 2) == rs.ROWSUM_ERR_INVALID_ARG
-    assert lib.rowsum_fwd_tuned(P + 2, P + BIG, 0, 64, 1, None, 1) == rs.ROWSUM_OK
     assert lib.rowsum_fwd_tuned(P + 2, P + BIG, 0, 1024, 1, None, 2) == rs.ROWSUM_OK
     # several rows per wavefront: only aligned rows of at most 8 vectors per lane
     assert lib.rowsum_fwd_tuned(P, P + BIG, 0, 512, 2, None, 8) == rs.ROWSUM_OK            # 64 vectors
@@ -71,11 +69,9 @@ def test_automatic_threads_per_row():
     assert auto(4096, 0) == 384 and auto(8192, 0) == 768 and auto(8192, 2) == 384
     assert auto(32000, 1) == 768 and auto(65536, 1) == 768 and auto(1 << 30, 2) == 768
     assert auto(1025, 2) == 64 and auto(1031, 0) == 64                          # not 16-byte rows
-    # up to 32 bytes per row: one lane per row; below 256 bytes, and up to 512 elements when not
-    # whole vectors: through LDS
-    assert auto(1, 1) == 1 and auto(7, 0) == 1 and auto(16, 2) == 1 and auto(8, 0) == 1
-    assert auto(17, 1) == 2 and auto(9, 0) == 2 and auto(64, 1) == 2 and auto(120, 2) == 2 and auto(32, 0) == 2
-    assert auto(65, 1) == 2 and auto(100, 2) == 2 and auto(511, 0) == 2 and auto(1023, 1) == 2 and auto(33, 0) == 2 and auto(63, 0) == 2
+    # up to 1024 elements: through LDS, aligned or not
+    assert auto(1, 1) == 2 and auto(7, 0) == 2 and auto(16, 2) == 2 and auto(8, 0) == 2
+    assert auto(17, 1) == 2 and auto(64, 1) == 2 and auto(120, 2) == 2 and auto(511, 0) == 2 and auto(1023, 1) == 2
     assert auto(128, 1) == 2 and auto(512, 2) == 2 and auto(1024, 1) == 2 and auto(1024, 0) == 2
     with pytest.raises(rs.RowSumError):
         auto(0, 1)

@@ -34,8 +34,6 @@ def modes_for(N, dtype, aligned=True):
     modes = list(BLOCK_MODES)
     if aligned and N % vec == 0:
         modes += [g for g in (8, 16, 32) if N // vec <= 8 * g]
-    if N <= 64:
-        modes.append(1)          # one lane per row
     if N <= 1024:
         modes.append(2)          # runs of rows through LDS
     return modes
@@ -220,19 +218,18 @@ def test_empty_batch_and_binding_checks(gpu_device):
 @pytest.mark.parametrize("dtype", DTYPES)
 @pytest.mark.parametrize("N", [1, 2, 3, 5, 10, 17, 31, 33, 63, 64, 65, 77, 100, 127, 129, 197, 255, 257, 300, 511, 512, 513, 1001, 1024])
 def test_short_rows_any_alignment(gpu_device, N, dtype):
-    """Rows of 1 to 1024 elements: one lane per row (up to 64), runs of rows through LDS (two full
-    tiles and a partial one), lane groups where the rows are whole aligned vectors, one workgroup
+    """Rows of 1 to 1024 elements: runs of rows through LDS (two full tiles and a partial one), lane groups where the rows are whole aligned vectors, one workgroup
     per row; then the same with the base pointer one element off a 16-byte boundary, where the
     automatic path must still take the short-row kernels."""
     rows_per_tile = 16384 // (N * inputs.DTYPE_BYTES[dtype])
     M = 2 * rows_per_tile + 5 if rows_per_tile < 3000 else 4099
     case = inputs.rowsum_case(5, 1900 + 4 * dtype, M, N, dtype, mean=0.25, std=2.0)
     stats = check(case, gpu_device)
-    assert 2 in stats and (1 in stats) == (N <= 64)
+    assert 2 in stats
     want_y, want_abs = oracle.rowsum_oracle(case["x"], dtype, with_abs=True)
     flat = np.concatenate([np.zeros(1, dtype=case["x"].dtype), case["x"].reshape(-1)])
     xd = H.to_device(flat, dtype, gpu_device)[1:].view(M, N)
-    for m in [0, 2, 64] + ([1] if N <= 64 else []):
+    for m in (0, 2, 64):
         y = run_mode(xd, m, "short rows, offset base")
         compare.check_rowsum_parity(y, want_y, want_abs, N, f"short rows, offset base [threads {m}]")
     for m in (8, 16, 32):
