@@ -181,12 +181,15 @@ def test_dispatch_choice_is_visible_without_a_launch():
     assert sel(P, P + 65536, P + 131072, 16, 13824, 1) == binding.RMSNORM_VARIANT_BLOCK
     assert sel(P, P + 65536, P + 131072, 16, 2040, 2) == binding.RMSNORM_VARIANT_WAVE
     assert sel(P, P + 65536, P + 131072, 16, 128, 2) == binding.RMSNORM_VARIANT_SUBWAVE
-    assert sel(P, P + 65536, P + 131072, 16, 40, 2) == binding.RMSNORM_VARIANT_SUBWAVE
+    assert sel(P, P + 65536, P + 131072, 16, 48, 2) == binding.RMSNORM_VARIANT_SUBWAVE
+    assert sel(P, P + 65536, P + 131072, 16, 40, 2) == binding.RMSNORM_VARIANT_PACKED   # 5 vectors on 8 lanes
+    assert sel(P, P + 65536, P + 131072, 16, 72, 1) == binding.RMSNORM_VARIANT_PACKED   # 9 vectors on 16 lanes
+    assert sel(P, P + 65536, P + 131072, 16, 96, 1) == binding.RMSNORM_VARIANT_SUBWAVE
     # aligned rows of at most 64 bytes go through LDS like the unaligned ones
     assert sel(P, P + 65536, P + 131072, 16, 32, 2) == binding.RMSNORM_VARIANT_PACKED
     assert sel(P, P + 65536, P + 131072, 16, 8, 1) == binding.RMSNORM_VARIANT_PACKED
     assert sel(P, P + 65536, P + 131072, 16, 16, 0) == binding.RMSNORM_VARIANT_PACKED
-    assert sel(P, P + 65536, P + 131072, 16, 20, 0) == binding.RMSNORM_VARIANT_SUBWAVE
+    assert sel(P, P + 65536, P + 131072, 16, 24, 0) == binding.RMSNORM_VARIANT_SUBWAVE
     assert sel(P, P + 65536, P + 131072, 16, 1023, 1) == binding.RMSNORM_VARIANT_PACKED
     assert sel(P, P + 65536, P + 131072, 16, 4097, 1) == binding.RMSNORM_VARIANT_UNALIGNED
     assert sel(P + 2, P + 65536, P + 131072, 16, 2048, 1) == binding.RMSNORM_VARIANT_UNALIGNED
