@@ -191,3 +191,77 @@ def test_layernorm_packed_offset_bases_and_in_place(gpu_device, dtype):
     layernorm.layernorm_fwd_variant(xd, wd, bd, 1e-5, layernorm.LAYERNORM_VARIANT_PACKED, xd)
     torch.cuda.synchronize()
     assert np.array_equal(H.to_host(xd, dtype).view(np.uint8), first.view(np.uint8))
+
+
+# ---- every row length, every instantiation ---------------------------------------------------
+# Lane groups of 1 to 64 lanes with 1 to 16 elements per lane are separate instantiations; the
+# lengths 1 .. 1024 visit every one of them, with the row ending at every position of a lane's
+# last step.  37 rows: more than a pass of the widest groups, fewer than one of the narrowest.
+from paper_2603_21331_amd import crossentropy as ce, rowsum as rs
+
+ALL_LENGTHS = list(range(1, 1025))
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_rmsnorm_packed_every_length(gpu_device, dtype):
+    M = 37
+    for N in ALL_LENGTHS:
+        case = inputs.random_case(7, 1100 + 2 * dtype, M, N, dtype, 1e-6)
+        want = oracle.rmsnorm_oracle(case["x"], case["w"], 1e-6, dtype)
+        xd, wd = H.to_device(case["x"], dtype, gpu_device), H.to_device(case["w"], dtype, gpu_device)
+        whole, y = H.alloc_guarded(M, N, dtype, gpu_device)
+        H.say(f"rmsnorm packed every length: {inputs.DTYPE_NAMES[dtype]} N={N}")
+        binding.rmsnorm_fwd_variant(xd, wd, 1e-6, binding.RMSNORM_VARIANT_PACKED, y)
+        torch.cuda.synchronize()
+        assert H.guards_intact(whole, M, N, dtype), f"N={N}: wrote outside y"
+        compare.check_parity(H.to_host(y, dtype), want, dtype, f"rmsnorm packed N={N}")
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_softmax_packed_every_length(gpu_device, dtype):
+    M = 37
+    for N in ALL_LENGTHS:
+        case = inputs.softmax_case(7, 1120 + 2 * dtype, M, N, dtype, 2.0)
+        want = oracle.softmax_oracle(case["x"], dtype)
+        xd = H.to_device(case["x"], dtype, gpu_device)
+        whole, y = H.alloc_guarded(M, N, dtype, gpu_device)
+        H.say(f"softmax packed every length: {inputs.DTYPE_NAMES[dtype]} N={N}")
+        softmax.softmax_fwd_variant(xd, softmax.SOFTMAX_VARIANT_PACKED, y)
+        torch.cuda.synchronize()
+        assert H.guards_intact(whole, M, N, dtype), f"N={N}: wrote outside y"
+        compare.check_softmax_parity(H.to_host(y, dtype), want, dtype, f"softmax packed N={N}")
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_layernorm_packed_every_length(gpu_device, dtype):
+    M = 37
+    for N in ALL_LENGTHS:
+        case = inputs.layernorm_case(7, 1140 + 4 * dtype, M, N, dtype, 1e-5, mean=1.0, std=2.0)
+        want, mean, rstd = oracle.layernorm_oracle(case["x"], case["w"], case["b"], 1e-5, dtype, stats=True)
+        bias64 = LN.scale_of(case, mean, rstd)
+        xd, wd, bd = (H.to_device(case[k], dtype, gpu_device) for k in ("x", "w", "b"))
+        whole, y = H.alloc_guarded(M, N, dtype, gpu_device)
+        H.say(f"layernorm packed every length: {inputs.DTYPE_NAMES[dtype]} N={N}")
+        layernorm.layernorm_fwd_variant(xd, wd, bd, 1e-5, layernorm.LAYERNORM_VARIANT_PACKED, y)
+        torch.cuda.synchronize()
+        assert H.guards_intact(whole, M, N, dtype), f"N={N}: wrote outside y"
+        compare.check_layernorm_parity(H.to_host(y, dtype), want, bias64, dtype, f"layernorm packed N={N}")
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_crossentropy_and_rowsum_packed_every_length(gpu_device, dtype):
+    M = 37
+    for N in ALL_LENGTHS:
+        case = inputs.crossentropy_case(7, 1160 + 4 * dtype, M, N, dtype, 2.0, ignore_every=9)
+        t = np.asarray(case["target"], dtype=np.int64)
+        want_loss = oracle.crossentropy_oracle(case["x"], t, dtype)
+        want_sum, want_abs = oracle.rowsum_oracle(case["x"], dtype, with_abs=True)
+        xd = H.to_device(case["x"], dtype, gpu_device)
+        td = torch.from_numpy(t).to(gpu_device)
+        H.say(f"cross-entropy and row sum packed every length: {inputs.DTYPE_NAMES[dtype]} N={N}")
+        loss = ce.crossentropy_fwd_tuned(xd, td, 2)
+        total = rs.rowsum_fwd_tuned(xd, 2)
+        torch.cuda.synchronize()
+        compare.check_crossentropy_parity(loss.cpu().numpy(), want_loss, f"cross-entropy packed N={N}",
+                                          exact_zero=(t < 0) | (t >= N))
+        compare.check_rowsum_parity(total.cpu().numpy(), want_sum, want_abs, N, f"row sum packed N={N}")
