@@ -62,10 +62,10 @@ typedef enum {
                                       long for registers (the second and third read come from
                                       cache); any alignment, N < 2^31 */
   LAYERNORM_VARIANT_PACKED = 7     /* runs of short rows copied through LDS with 128-bit accesses,
-                                      8 to 64 lanes per row: N <= 1024, any alignment as long as x
+                                      1 to 64 lanes per row: N <= 1024, any alignment as long as x
                                       and y are congruent modulo 16 bytes; what rows that are not
-                                      16-byte aligned take up to that length, and aligned
-                                      rows of at most 64 bytes */
+                                      16-byte aligned take up to that length, and aligned rows
+                                      that are very short or fill their lane group badly */
 } layernorm_variant;
 
 /*

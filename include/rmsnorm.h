@@ -23,11 +23,12 @@
  *    w has N elements.  x, w and y share one storage type `dtype`.
  *  - Pointers need only the alignment of their element type.  Rows whose
  *    start is 16-byte aligned (16-byte aligned bases and N * sizeof(dtype) a
- *    multiple of 16) take the aligned kernels; other rows take the same
- *    register-resident kernel with element-aligned 128-bit accesses (up to 1024
- *    elements: several rows at a time through LDS); rows too long for registers
- *    stream through a two-pass kernel that reads x a second time from cache.
- *    None of these is an error.
+ *    multiple of 16) take the aligned kernels; other rows of up to 1024
+ *    elements go through LDS several at a time with aligned 128-bit accesses
+ *    (if x and y sit at the same offset from a 16-byte boundary), longer ones
+ *    take the register-resident kernel with element-aligned 128-bit accesses;
+ *    rows too long for registers stream through a two-pass kernel that reads x
+ *    a second time from cache.  None of these is an error.
  *  - y == x (exactly in place) is allowed; any other overlap of y with x or w
  *    is undefined.
  *  - Calls return RMSNORM_OK or a negative rmsnorm_status; nothing throws or
@@ -74,10 +75,10 @@ typedef enum {
                                    long for registers (the second read comes from cache);
                                    any alignment, N < 2^31 */
   RMSNORM_VARIANT_PACKED = 7    /* runs of short rows copied through LDS with 128-bit accesses,
-                                   8 to 64 lanes per row; N <= 1024, any alignment as long as x
+                                   1 to 64 lanes per row; N <= 1024, any alignment as long as x
                                    and y are congruent modulo 16 bytes; what rows that are not
-                                   16-byte aligned take up to that length, and aligned
-                                   rows of at most 64 bytes */
+                                   16-byte aligned take up to that length, and aligned rows
+                                   that are very short or fill their lane group badly */
 } rmsnorm_variant;
 
 /*
@@ -99,11 +100,11 @@ int rmsnorm_fwd(const void* x, const void* w, void* y, int64_t M, int64_t N,
  * to run every kernel on every shape it supports).  `variant` is an
  * rmsnorm_variant.  RMSNORM_ERR_UNSUPPORTED if that kernel cannot take the
  * shape: SUBWAVE needs 16-byte aligned rows of at most 1 KiB, WAVE needs
- * 16-byte aligned rows of at most rmsnorm_wave_max_n(dtype) elements, BLOCK needs 16-byte aligned rows of at most
- * rmsnorm_block_max_n(dtype) elements, UNALIGNED takes any alignment up to
- * rmsnorm_unaligned_max_n(dtype) elements, PACKED up to 1024 elements with x - y a multiple
- * of 16 bytes, STREAM
- * any alignment up to N < 2^31, GENERIC takes everything.
+ * 16-byte aligned rows of at most rmsnorm_wave_max_n(dtype) elements, BLOCK
+ * needs 16-byte aligned rows of at most rmsnorm_block_max_n(dtype) elements,
+ * UNALIGNED takes any alignment up to rmsnorm_unaligned_max_n(dtype) elements,
+ * PACKED up to 1024 elements with x - y a multiple of 16 bytes, STREAM any
+ * alignment up to N < 2^31, GENERIC takes everything.
  */
 int rmsnorm_fwd_variant(const void* x, const void* w, void* y, int64_t M, int64_t N,
                         float eps, int dtype, void* stream, int variant);
@@ -118,8 +119,9 @@ int rmsnorm_fwd_variant(const void* x, const void* w, void* y, int64_t M, int64_
  * ceil(N * sizeof(dtype) / 16 / threads_per_row) 16-byte chunks of the row in
  * registers; RMSNORM_ERR_UNSUPPORTED if that exceeds what is built for the
  * thread count (8, 16, 32: 2 chunks; 64: 16 chunks, 32 for fp32; 128, 256,
- * 512: 8 chunks; 1024: 16 chunks) or if the rows are not 16-byte aligned.  Tests use it to run every instantiation; tuning sweeps use it to
- * check the automatic choice.
+ * 512: 8 chunks; 1024: 16 chunks) or if the rows are not 16-byte aligned.
+ * Tests use it to run every instantiation; tuning sweeps use it to check the
+ * automatic choice.
  */
 int rmsnorm_fwd_tuned(const void* x, const void* w, void* y, int64_t M, int64_t N,
                       float eps, int dtype, void* stream, int threads_per_row);
