@@ -56,8 +56,13 @@ typedef enum {
   LAYERNORM_VARIANT_BLOCK = 2,   /* one workgroup of 256..1024 threads per row */
   LAYERNORM_VARIANT_GENERIC = 3, /* element-wise, three passes, any alignment, any N */
   LAYERNORM_VARIANT_SUBWAVE = 4, /* 8, 16 or 32 lanes per row; 16-byte aligned rows <= 1 KiB */
-  LAYERNORM_VARIANT_UNALIGNED = 5, /* the register-resident row kernel with element-aligned
-                                      128-bit accesses: any alignment, N up to the register limit */
+  LAYERNORM_VARIANT_UNALIGNED = 5, /* the register-resident row kernel addressed in elements:
+                                      single elements at both ends of a row and 128-bit accesses
+                                      between them, which resident workgroups put on 16-byte
+                                      boundaries when x and y are congruent modulo 16 bytes and
+                                      there are enough rows (16-bit types; see
+                                      layernorm_unaligned_walk_grid), only element-aligned
+                                      otherwise: any alignment, N up to the register limit */
   LAYERNORM_VARIANT_STREAM = 6,    /* three streaming passes with 128-bit accesses for rows too
                                       long for registers (the second and third read come from
                                       cache); any alignment, N < 2^31 */
@@ -100,6 +105,19 @@ int layernorm_fwd_tuned(const void* x, const void* w, const void* b, void* y, in
 /* threads_per_row of the automatic path for 16-byte aligned rows of N elements; 0 if
  * such rows do not fit in registers (they take the streaming kernel); a negative layernorm_status for bad arguments. */
 int layernorm_auto_threads_per_row(int64_t N, int dtype);
+
+/*
+ * How LAYERNORM_VARIANT_UNALIGNED would run this call, without launching anything: the
+ * number of resident workgroups of its walking form (each takes rows blockIdx,
+ * blockIdx + grid, ..., all of which start at the same offset from a 16-byte boundary,
+ * reads its slices of weight and bias once and cuts every row at the boundaries), or 0
+ * if it would run one workgroup per row with element-aligned accesses (fp32; x and y at
+ * different offsets from a boundary; fewer than four rows per workgroup; N of at most
+ * 2055 or beyond 32775 elements).  A negative layernorm_status for arguments
+ * layernorm_fwd would reject.  Only pointer alignment is inspected.
+ */
+int64_t layernorm_unaligned_walk_grid(const void* x, const void* w, const void* b, const void* y,
+                                      int64_t M, int64_t N, int dtype);
 
 /* Largest N the register-resident kernels accept for `dtype`; 0 for a bad dtype. */
 int64_t layernorm_register_max_n(int dtype);

@@ -66,8 +66,12 @@ typedef enum {
                                   registers, cross-wave reduction in LDS */
   RMSNORM_VARIANT_GENERIC = 3, /* element-wise, any alignment, any N; reads x twice */
   RMSNORM_VARIANT_UNALIGNED = 4, /* row held in registers like WAVE / BLOCK, but addressed in
-                                   elements: 128-bit accesses that are only element-aligned
-                                   plus a scalar tail; any alignment, N up to
+                                   elements: single elements at both ends and 128-bit
+                                   accesses between them, which resident workgroups put on
+                                   16-byte boundaries when x and y are congruent modulo 16
+                                   bytes and there are enough rows (16-bit types; see
+                                   rmsnorm_unaligned_walk_grid) and which are only
+                                   element-aligned otherwise; any alignment, N up to
                                    rmsnorm_unaligned_max_n(dtype) */
   RMSNORM_VARIANT_SUBWAVE = 5,  /* 8, 16 or 32 lanes per row, several rows per wavefront;
                                    16-byte aligned rows of at most 1 KiB */
@@ -140,6 +144,19 @@ int rmsnorm_auto_threads_per_row(int64_t N, int dtype);
  */
 int rmsnorm_select_variant(const void* x, const void* w, const void* y, int64_t M,
                            int64_t N, int dtype);
+
+/*
+ * How RMSNORM_VARIANT_UNALIGNED would run this call, without launching anything: the
+ * number of resident workgroups of its walking form (each takes rows blockIdx,
+ * blockIdx + grid, ..., all of which start at the same offset from a 16-byte boundary,
+ * reads its slice of the weight once and cuts every row at the boundaries), or 0 if it
+ * would run one workgroup per row with element-aligned accesses (fp32; x and y at
+ * different offsets from a boundary; fewer than four rows per workgroup; rows of more
+ * than 8 groups per thread; N beyond rmsnorm_unaligned_max_n).  A negative rmsnorm_status
+ * for arguments rmsnorm_fwd would reject.  Only pointer alignment is inspected.
+ */
+int64_t rmsnorm_unaligned_walk_grid(const void* x, const void* w, const void* y, int64_t M,
+                                    int64_t N, int dtype);
 
 /* Largest N the register-resident kernels accept for `dtype`; 0 for a bad dtype. */
 int64_t rmsnorm_wave_max_n(int dtype);

@@ -65,6 +65,8 @@ def load() -> ctypes.CDLL:
     lib.rmsnorm_auto_threads_per_row.restype = i32
     lib.rmsnorm_select_variant.argtypes = [vp, vp, vp, i64, i64, i32]
     lib.rmsnorm_select_variant.restype = i32
+    lib.rmsnorm_unaligned_walk_grid.argtypes = [vp, vp, vp, i64, i64, i32]
+    lib.rmsnorm_unaligned_walk_grid.restype = i64
     lib.rmsnorm_wave_max_n.argtypes = [i32]
     lib.rmsnorm_wave_max_n.restype = i64
     lib.rmsnorm_block_max_n.argtypes = [i32]
@@ -163,6 +165,14 @@ def rmsnorm_auto_threads_per_row(N: int, dtype: int) -> int:
 def rmsnorm_select_variant(x, w, y) -> int:
     M, N, code, _ = _marshal(x, w, y)
     rc = load().rmsnorm_select_variant(x.data_ptr(), w.data_ptr(), y.data_ptr(), M, N, code)
+    if rc < 0:
+        _check(rc)
+    return rc
+
+
+def rmsnorm_unaligned_walk_grid(x, w, y) -> int:
+    M, N, code, _ = _marshal(x, w, y)
+    rc = int(load().rmsnorm_unaligned_walk_grid(x.data_ptr(), w.data_ptr(), y.data_ptr(), M, N, code))
     if rc < 0:
         _check(rc)
     return rc

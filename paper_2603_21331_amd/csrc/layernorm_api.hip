@@ -164,11 +164,77 @@ void launch_subwave(const Args& a) {
                      (const u32x4*)a.b, (u32x4*)a.y, a.M, a.nvec, (float)a.N, a.eps);
 }
 
+// x and y at the same offset from a 16-byte boundary: then so is every row of theirs.
+bool same_skew(const void* x, const void* y) {
+  return ((reinterpret_cast<uintptr_t>(x) ^ reinterpret_cast<uintptr_t>(y)) & 15u) == 0;
+}
+
+constexpr int kWalkMaxChunks = 4;   // what fits in registers next to the packed weight and bias
+constexpr int64_t kWalkBytesPerCu = 48 * 1024;
+
+// Workgroups of the walking form's grid, 0 if the one-row-per-workgroup form should run.
+// Each resident workgroup has one row in flight, and the sweeps on MI355X (N = 1025 .. 40961)
+// put the best grid where about `bytes_per_cu` of rows are in flight per compute unit.  Around
+// that number the grid is chosen so that the rows divide evenly among the workgroups (8192 rows
+// over 5 workgroups per compute unit leave a sixth of the last round idle; over 4 none), and it
+// stays a multiple of the compute units (other grids load them unevenly, measured 10 to 20 %
+// slower) and of 8.  With fewer than four rows per workgroup there is nothing to spread the
+// weight over.
+int64_t walk_grid(int64_t M, int64_t row_bytes, int threads, int64_t bytes_per_cu) {
+  constexpr int kMaxThreadsPerCu = 2048;
+  constexpr int64_t kMinRows = 4;
+  const int64_t cus = compute_units();
+  if (cus % 8 != 0) return 0;
+  const double want = (double)bytes_per_cu / (double)row_bytes;
+  int64_t most = kMaxThreadsPerCu / threads;
+  if (most > M / (kMinRows * cus)) most = M / (kMinRows * cus);
+  int64_t best = 0;
+  double best_cost = 0.0;
+  for (int64_t p = 1; p <= most; ++p) {
+    if ((double)p < 0.55 * want || (double)p > 1.5 * want + 1.0) continue;
+    const int64_t grid = cus * p;
+    const double rounds = (double)((M + grid - 1) / grid);
+    const double miss = ((double)p > want ? (double)p - want : want - (double)p) / want;
+    const double cost = rounds * (double)grid / (double)M * (1.0 + 0.15 * miss);
+    if (best == 0 || cost < best_cost) {
+      best = p;
+      best_cost = cost;
+    }
+  }
+  return cus * best;
+}
+
+// The grid of the walking form for this call and its threads per row, 0 for one workgroup
+// per row: rows of a 16-bit type (dword-aligned 128-bit accesses, which is all that fp32 rows
+// can be off by, run at full rate) with x and y at the same offset from a 16-byte boundary, in
+// the smallest workgroup that holds the row in kWalkMaxChunks groups per thread.  Rows of up to
+// 256 groups, which one wavefront holds, gain nothing measurable and stay as they are.
+int64_t unaligned_walk_grid(const void* x, const void* y, int64_t M, int64_t N, int bytes,
+                            int* threads) {
+  if (bytes != 2 || !same_skew(x, y)) return 0;
+  const int64_t nfull = N / (16 / bytes);
+  int g = 256;
+  while (g < kMaxThreads && nfull > (int64_t)g * kWalkMaxChunks) g *= 2;
+  if (nfull <= rms::kLnWave * kWalkMaxChunks || nfull > (int64_t)g * kWalkMaxChunks) return 0;
+  *threads = g;
+  return walk_grid(M, N * bytes, g, kWalkBytesPerCu);
+}
+
+// walk > 0: the walking form with that many resident workgroups.
 template <int DT, int CHUNKS, int G>
-void launch_row_unaligned(const Args& a, int nfull) {
+void launch_row_unaligned(const Args& a, int64_t walk) {
+  if constexpr (DT != rms::kFp32 && CHUNKS <= kWalkMaxChunks) {
+    if (walk > 0) {
+      hipLaunchKernelGGL((rms::layernorm_row_unaligned_kernel<DT, CHUNKS, G, true, true>),
+                         dim3((unsigned)walk), dim3(G), 0, a.stream, a.x, a.w, a.b, a.y, a.M,
+                         (int)a.N, (float)a.N, a.eps);
+      return;
+    }
+  }
   const int64_t blocks = a.M < kMaxGrid ? a.M : kMaxGrid;
-  hipLaunchKernelGGL((rms::layernorm_row_unaligned_kernel<DT, CHUNKS, G, true>), dim3((unsigned)blocks),
-                     dim3(G), 0, a.stream, a.x, a.w, a.b, a.y, a.M, a.N, nfull, (float)a.N, a.eps);
+  hipLaunchKernelGGL((rms::layernorm_row_unaligned_kernel<DT, CHUNKS, G, true, false>),
+                     dim3((unsigned)blocks), dim3(G), 0, a.stream, a.x, a.w, a.b, a.y, a.M,
+                     (int)a.N, (float)a.N, a.eps);
 }
 
 // The LDS-staged kernel for short rows that are not 16-byte aligned: the narrowest lane group
@@ -189,9 +255,7 @@ bool packed_beats_lanes(int64_t nvec, int lanes) {
   return nvec <= 16 && nvec * 10 < slots * 7;
 }
 
-bool packed_can(const void* x, const void* y, int64_t N) {
-  return N <= kPackedMaxN && ((reinterpret_cast<uintptr_t>(x) ^ reinterpret_cast<uintptr_t>(y)) & 15u) == 0;
-}
+bool packed_can(const void* x, const void* y, int64_t N) { return N <= kPackedMaxN && same_skew(x, y); }
 
 template <int DT, int L, int E>
 void launch_packed(const Args& a) {
@@ -302,12 +366,15 @@ int dispatch(const Args& a, int threads) {
 template <int DT>
 int dispatch_unaligned(const Args& a) {
   const int nfull = (int)(a.N / rms::Storage<DT>::kVec);
-  const int threads = pick_threads_unaligned(nfull);
+  int threads = pick_threads_unaligned(nfull);
+  int walk_threads = 0;
+  const int64_t walk = unaligned_walk_grid(a.x, a.y, a.M, a.N, rms::Storage<DT>::kBytes, &walk_threads);
+  if (walk > 0) threads = walk_threads;
   int chunks = (nfull + threads - 1) / threads;
   if (chunks < 1) chunks = 1;
   switch (threads) {
     case 64:
-#define LN_L(c) launch_row_unaligned<DT, c, 64>(a, nfull)
+#define LN_L(c) launch_row_unaligned<DT, c, 64>(a, walk)
       switch (chunks) {
         LN_CASE(1, LN_L(1)) LN_CASE(2, LN_L(2)) LN_CASE(3, LN_L(3)) LN_CASE(4, LN_L(4))
         default: return LAYERNORM_ERR_UNSUPPORTED;
@@ -315,17 +382,17 @@ int dispatch_unaligned(const Args& a) {
 #undef LN_L
       break;
     case 256:
-#define LN_L(c) launch_row_unaligned<DT, c, 256>(a, nfull)
+#define LN_L(c) launch_row_unaligned<DT, c, 256>(a, walk)
       switch (chunks) { LN_CASES_1_8(LN_L) default: return LAYERNORM_ERR_UNSUPPORTED; }
 #undef LN_L
       break;
     case 512:
-#define LN_L(c) launch_row_unaligned<DT, c, 512>(a, nfull)
+#define LN_L(c) launch_row_unaligned<DT, c, 512>(a, walk)
       switch (chunks) { LN_CASES_1_8(LN_L) default: return LAYERNORM_ERR_UNSUPPORTED; }
 #undef LN_L
       break;
     case 1024:
-#define LN_L(c) launch_row_unaligned<DT, c, 1024>(a, nfull)
+#define LN_L(c) launch_row_unaligned<DT, c, 1024>(a, walk)
       switch (chunks) { LN_CASES_1_8(LN_L) default: return LAYERNORM_ERR_UNSUPPORTED; }
 #undef LN_L
       break;
@@ -434,6 +501,14 @@ int layernorm_auto_threads_per_row(int64_t N, int dtype) {
   if (b == 0 || N <= 0) return LAYERNORM_ERR_INVALID_ARG;
   if ((N * b) % 16 != 0) return 0;
   return pick_threads(N * b / 16, 8, dtype);
+}
+
+int64_t layernorm_unaligned_walk_grid(const void* x, const void* w, const void* b, const void* y,
+                                      int64_t M, int64_t N, int dtype) {
+  if (check_args(x, w, b, y, M, N, 0.0f, dtype) != LAYERNORM_OK) return LAYERNORM_ERR_INVALID_ARG;
+  if (pick_threads_unaligned(N / (16 / elem_bytes(dtype))) == 0) return 0;
+  int threads = 0;
+  return unaligned_walk_grid(x, y, M, N, elem_bytes(dtype), &threads);
 }
 
 int64_t layernorm_register_max_n(int dtype) {

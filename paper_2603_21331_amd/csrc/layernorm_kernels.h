@@ -523,51 +523,92 @@ layernorm_subwave_kernel(const u32x4* x, const u32x4* __restrict__ w, const u32x
 }
 
 // ---------------------------------------------------------------------------
-// The one-row-per-workgroup kernel for rows that are NOT 16-byte aligned (odd N such as the
+// The register-resident kernel for rows that are NOT 16-byte aligned (odd N such as the
 // paper's edge dims 1023 / 4097 / 1537, or base pointers off a 16-byte boundary).  Rows,
-// weight and bias are addressed in elements: thread t holds the 16-byte groups c * G + t of
-// the floor(N / VEC) full groups, read and written with 128-bit accesses that are only
-// element-aligned (single global_load/store_dwordx4 instructions on this target), and threads
-// 0 .. N % VEC - 1 each take one of the leftover elements at the end of the row.  x is still
-// read exactly once.  Same arithmetic as layernorm_row_kernel.
+// weight and bias are addressed in elements.  A row is cut into `head` single elements,
+// 16-byte groups and single elements again: thread t holds groups c * G + t, threads
+// 0 .. head - 1 one leading element each, threads 16 .. 16 + tail - 1 one trailing element
+// each.  x is still read exactly once.  Same arithmetic as layernorm_row_kernel.
+//
+//  WALK == false : head is 0, one row per workgroup (striding only beyond the grid limit);
+//                  every 128-bit access is only element-aligned (single
+//                  global_load/store_dwordx4 instructions on this target, at a lower rate
+//                  in the 16-bit types); weight and bias are read in the epilogue.
+//  WALK == true  : x and y sit at the same offset from a 16-byte boundary and the grid is
+//                  a multiple of 8 workgroups that stay for the whole launch.  Rows
+//                  blockIdx.x + k * gridDim.x then all start at the same offset, head
+//                  brings their groups onto 16-byte boundaries in x and in y alike, and the
+//                  workgroup reads its slices of weight and bias (off the boundaries by
+//                  that head) once, into registers.
 // ---------------------------------------------------------------------------
-template <int DT, int CHUNKS, int G, bool NT>
+template <int DT, int CHUNKS, int G, bool NT, bool WALK>
 __global__ void __launch_bounds__(G) __attribute__((amdgpu_waves_per_eu(4)))
 layernorm_row_unaligned_kernel(const void* x, const void* __restrict__ w, const void* __restrict__ b,
-                               void* y, int64_t M, int64_t N, int nfull, float n, float eps) {
+                               void* y, int64_t M, int n_cols, float n, float eps) {
   using S = Storage<DT>;
   constexpr int VEC = S::kVec;
   constexpr int WAVES = G / kLnWave;
   constexpr int kGroupBytes = 16;
+  constexpr int kTailThread = 16;                       // first thread that takes a trailing element
   __shared__ __attribute__((aligned(16))) float part_a[2][WAVES];
   __shared__ __attribute__((aligned(16))) float part_b[2][WAVES];
   const int t = threadIdx.x;
   const int lane = t & (kLnWave - 1);
   const int wave = t / kLnWave;
   const int last = (CHUNKS - 1) * G + t;
-  const bool last_ok = last < nfull;
-  const int rem = (int)(N - (int64_t)nfull * VEC);
-  const bool tail_ok = t < rem;
-  const int64_t tail_col = (int64_t)nfull * VEC + t;
   const bool has_bias = b != nullptr;
   const u32x4 zero = {0u, 0u, 0u, 0u};
-  const char* wb = static_cast<const char*>(w);
-  const char* bb = static_cast<const char*>(b);
   int slot = 0;
+  if (blockIdx.x >= M) return;
+
+  // The cut, the same for every row of this workgroup.
+  int head = 0;
+  if constexpr (WALK) {
+    const char* first = static_cast<const char*>(x) + (int64_t)blockIdx.x * n_cols * S::kBytes;
+    head = (int)((16u - (unsigned)(reinterpret_cast<uintptr_t>(first) & 15u)) & 15u) / S::kBytes;
+    head = head < n_cols ? head : n_cols;
+  }
+  const int groups = (n_cols - head) / VEC;             // at most CHUNKS * G, at least (CHUNKS - 1) * G
+  const int tail_n = n_cols - head - groups * VEC;
+  const bool last_ok = last < groups;
+  const bool tail_ok = t < head || (t >= kTailThread && t - kTailThread < tail_n);
+  const int tail_col = t < head ? t : head + groups * VEC + (t - kTailThread);
+  const char* wb = static_cast<const char*>(w) + head * S::kBytes;
+  const char* bb = static_cast<const char*>(b) + head * S::kBytes;
+
+  u32x4 wv[WALK ? CHUNKS : 1], bv[WALK ? CHUNKS : 1];
+  float tail_w = 0.f, tail_b = 0.f;
+  if constexpr (WALK) {
+#pragma unroll
+    for (int c = 0; c < CHUNKS; ++c) {
+      const int64_t off = (int64_t)(c * G + t) * kGroupBytes;
+      wv[c] = bv[c] = zero;
+      if (c < CHUNKS - 1 || last_ok) {
+        wv[c] = load_vec_unaligned<false>(wb + off);
+        if (has_bias) bv[c] = load_vec_unaligned<false>(bb + off);
+      }
+    }
+    if (tail_ok) {
+      tail_w = S::load_one(w, tail_col);
+      tail_b = has_bias ? S::load_one(b, tail_col) : 0.f;
+    }
+  }
 
   for (int64_t row = blockIdx.x; row < M; row += gridDim.x) {
-    const char* xr = static_cast<const char*>(x) + row * N * S::kBytes;
-    char* yr = static_cast<char*>(y) + row * N * S::kBytes;
+    const char* xr = static_cast<const char*>(x) + row * n_cols * S::kBytes;
+    char* yr = static_cast<char*>(y) + row * n_cols * S::kBytes;
+    const char* xb = xr + head * S::kBytes;
+    char* yb = yr + head * S::kBytes;
 
     u32x4 v[CHUNKS];
 #pragma unroll
     for (int c = 0; c < CHUNKS - 1; ++c)
-      v[c] = load_vec_unaligned<NT>(xr + (int64_t)(c * G + t) * kGroupBytes);
+      v[c] = load_vec_unaligned<NT>(xb + (int64_t)(c * G + t) * kGroupBytes);
     v[CHUNKS - 1] = zero;
-    if (last_ok) v[CHUNKS - 1] = load_vec_unaligned<NT>(xr + (int64_t)last * kGroupBytes);
-    const float shift = S::load_one(x, row * N);      // the row's first element
+    if (last_ok) v[CHUNKS - 1] = load_vec_unaligned<NT>(xb + (int64_t)last * kGroupBytes);
+    const float shift = S::load_one(xr, 0);             // the row's first element
     float tail = 0.f;
-    if (tail_ok) tail = S::load_one(x, row * N + tail_col) - shift;
+    if (tail_ok) tail = S::load_one(xr, tail_col) - shift;
 
     float f[CHUNKS][VEC];
     float acc[4] = {tail, 0.f, 0.f, 0.f};
@@ -609,23 +650,35 @@ layernorm_row_unaligned_kernel(const void* x, const void* __restrict__ w, const 
     }
     const float rstd = ln_rstd(s2, n, eps);
 
-    // weight and bias only now (L2 hits), behind an empty asm so that they are not hoisted
-    // above the reductions, where the centred row already fills the register budget
-    const char* wp = wb;
-    const char* bp = bb;
-    asm volatile("" : "+s"(wp), "+s"(bp));
+    if constexpr (WALK) {
 #pragma unroll
-    for (int c = 0; c < CHUNKS; ++c) {
-      if (c < CHUNKS - 1 || last_ok) {
-        const int64_t off = (int64_t)(c * G + t) * kGroupBytes;
-        const u32x4 wv = load_vec_unaligned<false>(wp + off);
-        const u32x4 bv = has_bias ? load_vec_unaligned<false>(bp + off) : zero;
-        store_vec_unaligned<NT>(yr + off, ln_scale<DT>(f[c], wv, bv, has_bias, rstd));
+      for (int c = 0; c < CHUNKS; ++c)
+        if (c < CHUNKS - 1 || last_ok)
+          store_vec_unaligned<NT>(yb + (int64_t)(c * G + t) * kGroupBytes,
+                                  ln_scale<DT>(f[c], wv[c], bv[c], has_bias, rstd));
+    } else {
+      // weight and bias only now (L2 hits), behind an empty asm so that they are not hoisted
+      // above the reductions, where the centred row already fills the register budget
+      const char* wp = wb;
+      const char* bp = bb;
+      asm volatile("" : "+s"(wp), "+s"(bp));
+#pragma unroll
+      for (int c = 0; c < CHUNKS; ++c) {
+        if (c < CHUNKS - 1 || last_ok) {
+          const int64_t off = (int64_t)(c * G + t) * kGroupBytes;
+          const u32x4 wc = load_vec_unaligned<false>(wp + off);
+          const u32x4 bc = has_bias ? load_vec_unaligned<false>(bp + off) : zero;
+          store_vec_unaligned<NT>(yb + off, ln_scale<DT>(f[c], wc, bc, has_bias, rstd));
+        }
+      }
+      if (tail_ok) {
+        tail_w = S::load_one(w, tail_col);
+        tail_b = has_bias ? S::load_one(b, tail_col) : 0.f;
       }
     }
     if (tail_ok) {
-      const float tq = (tail * rstd) * S::load_one(w, tail_col);
-      S::store_one(y, row * N + tail_col, has_bias ? tq + S::load_one(b, tail_col) : tq);
+      const float tq = (tail * rstd) * tail_w;
+      S::store_one(yr, tail_col, has_bias ? tq + tail_b : tq);
     }
   }
 }

@@ -136,9 +136,12 @@ bool packed_beats_lanes(int64_t nvec, int lanes) {
   return nvec <= 16 && nvec * 10 < slots * 7;
 }
 
-bool packed_can(const void* x, const void* y, int64_t N) {
-  return N <= kPackedMaxN && ((reinterpret_cast<uintptr_t>(x) ^ reinterpret_cast<uintptr_t>(y)) & 15u) == 0;
+// x and y at the same offset from a 16-byte boundary: then so is every row of theirs.
+bool same_skew(const void* x, const void* y) {
+  return ((reinterpret_cast<uintptr_t>(x) ^ reinterpret_cast<uintptr_t>(y)) & 15u) == 0;
 }
+
+bool packed_can(const void* x, const void* y, int64_t N) { return N <= kPackedMaxN && same_skew(x, y); }
 
 int choose(const void* x, const void* w, const void* y, int64_t N, int dtype) {
   if (!rows_vectorisable(x, w, y, N, dtype)) {
@@ -198,12 +201,87 @@ void launch_subwave(const Args& a) {
                      1.0f / (float)a.N, a.eps);
 }
 
+// Compute units of the current device (256 on MI355X), looked up once per device.
+int compute_units() {
+  constexpr int kMaxDevices = 64;
+  static int cached[kMaxDevices] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 256;
+  if (cached[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+      n = 256;
+    cached[dev] = n;
+  }
+  return cached[dev];
+}
+
+// Rows of a 16-bit type with x and y at the same offset from a 16-byte boundary, more of them
+// than resident workgroups: the walking form (aligned row accesses, weight in registers).  Its
+// grid must be a multiple of 8 workgroups, so that every row of a workgroup starts at the same
+// offset from a boundary (8 rows of any length in a 16-bit type are a multiple of 16 bytes).
+// fp32 rows gain nothing from it (dword-aligned 128-bit accesses run at full rate).
+// Workgroups of the walking form's grid, 0 if the one-row-per-workgroup form should run.
+// Each resident workgroup has one row in flight, and the sweeps on MI355X (N = 1025 .. 40961)
+// put the best grid where about `bytes_per_cu` of rows are in flight per compute unit.  Around
+// that number the grid is chosen so that the rows divide evenly among the workgroups (8192 rows
+// over 5 workgroups per compute unit leave a sixth of the last round idle; over 4 none), and it
+// stays a multiple of the compute units (other grids load them unevenly, measured 10 to 20 %
+// slower) and of 8.  With fewer than four rows per workgroup there is nothing to spread the
+// weight over.
+int64_t walk_grid(int64_t M, int64_t row_bytes, int threads, int64_t bytes_per_cu) {
+  constexpr int kMaxThreadsPerCu = 2048;
+  constexpr int64_t kMinRows = 4;
+  const int64_t cus = compute_units();
+  if (cus % 8 != 0) return 0;
+  const double want = (double)bytes_per_cu / (double)row_bytes;
+  int64_t most = kMaxThreadsPerCu / threads;
+  if (most > M / (kMinRows * cus)) most = M / (kMinRows * cus);
+  int64_t best = 0;
+  double best_cost = 0.0;
+  for (int64_t p = 1; p <= most; ++p) {
+    if ((double)p < 0.55 * want || (double)p > 1.5 * want + 1.0) continue;
+    const int64_t grid = cus * p;
+    const double rounds = (double)((M + grid - 1) / grid);
+    const double miss = ((double)p > want ? (double)p - want : want - (double)p) / want;
+    const double cost = rounds * (double)grid / (double)M * (1.0 + 0.15 * miss);
+    if (best == 0 || cost < best_cost) {
+      best = p;
+      best_cost = cost;
+    }
+  }
+  return cus * best;
+}
+
+constexpr int64_t kWalkBytesPerCu = 26 * 1024;
+constexpr int kWalkMaxChunks = 8;   // what fits in registers next to the packed weight
+
+// The grid of the walking form for this call, 0 for one workgroup per row: rows of a 16-bit
+// type (dword-aligned 128-bit accesses, which is all that fp32 rows can be off by, run at full
+// rate) with x and y at the same offset from a 16-byte boundary.
+int64_t unaligned_walk_grid(const void* x, const void* y, int64_t M, int64_t N, int dtype) {
+  if (dtype == RMSNORM_DTYPE_FP32 || !same_skew(x, y)) return 0;
+  const int64_t nfull = full_groups_per_row(N, dtype);
+  const int threads = pick_threads_unaligned(nfull);
+  if (threads == 0 || (nfull + threads - 1) / threads > kWalkMaxChunks) return 0;
+  return walk_grid(M, N * elem_bytes(dtype), threads, kWalkBytesPerCu);
+}
+
+// walk > 0: the walking form with that many resident workgroups.
 template <int DT, int CHUNKS, int G>
-void launch_row_unaligned(const Args& a, int nfull) {
+void launch_row_unaligned(const Args& a, int64_t walk) {
+  if constexpr (DT != rms::kFp32 && CHUNKS <= kWalkMaxChunks) {
+    if (walk > 0) {
+      hipLaunchKernelGGL((rms::rmsnorm_row_unaligned_kernel<DT, CHUNKS, G, true, true>),
+                         dim3((unsigned)walk), dim3(G), 0, a.stream,
+                         a.x, a.w, a.y, a.M, (int)a.N, 1.0f / (float)a.N, a.eps);
+      return;
+    }
+  }
   const int64_t blocks = a.M < kMaxGrid ? a.M : kMaxGrid;
-  hipLaunchKernelGGL((rms::rmsnorm_row_unaligned_kernel<DT, CHUNKS, G, true>),
+  hipLaunchKernelGGL((rms::rmsnorm_row_unaligned_kernel<DT, CHUNKS, G, true, false>),
                      dim3((unsigned)blocks), dim3(G), 0, a.stream,
-                     a.x, a.w, a.y, a.M, a.N, nfull, 1.0f / (float)a.N, a.eps);
+                     a.x, a.w, a.y, a.M, (int)a.N, 1.0f / (float)a.N, a.eps);
 }
 
 // The two-pass streaming kernel: about one batch of four groups per thread, whole wavefronts,
@@ -341,11 +419,13 @@ template <int DT>
 int dispatch_row_unaligned(const Args& a) {
   const int nfull = (int)full_groups_per_row(a.N, DT == rms::kFp32 ? RMSNORM_DTYPE_FP32 : RMSNORM_DTYPE_FP16);
   const int threads = pick_threads_unaligned(nfull);
+  const int64_t walk = unaligned_walk_grid(a.x, a.y, a.M, a.N,
+                                           DT == rms::kFp32 ? RMSNORM_DTYPE_FP32 : RMSNORM_DTYPE_FP16);
   int chunks = (nfull + threads - 1) / threads;
   if (chunks < 1) chunks = 1;
   switch (threads) {
     case 64:
-#define RMS_L(c) launch_row_unaligned<DT, c, 64>(a, nfull)
+#define RMS_L(c) launch_row_unaligned<DT, c, 64>(a, walk)
       switch (chunks) {
         RMS_CASE(1, RMS_L(1)) RMS_CASE(2, RMS_L(2)) RMS_CASE(3, RMS_L(3)) RMS_CASE(4, RMS_L(4))
         default: return RMSNORM_ERR_UNSUPPORTED;
@@ -353,17 +433,17 @@ int dispatch_row_unaligned(const Args& a) {
 #undef RMS_L
       break;
     case 256:
-#define RMS_L(c) launch_row_unaligned<DT, c, 256>(a, nfull)
+#define RMS_L(c) launch_row_unaligned<DT, c, 256>(a, walk)
       switch (chunks) { RMS_CASES_1_8(RMS_L) default: return RMSNORM_ERR_UNSUPPORTED; }
 #undef RMS_L
       break;
     case 512:
-#define RMS_L(c) launch_row_unaligned<DT, c, 512>(a, nfull)
+#define RMS_L(c) launch_row_unaligned<DT, c, 512>(a, walk)
       switch (chunks) { RMS_CASES_1_8(RMS_L) default: return RMSNORM_ERR_UNSUPPORTED; }
 #undef RMS_L
       break;
     case 1024:
-#define RMS_L(c) launch_row_unaligned<DT, c, 1024>(a, nfull)
+#define RMS_L(c) launch_row_unaligned<DT, c, 1024>(a, walk)
       switch (chunks) {
         RMS_CASES_1_8(RMS_L) RMS_CASES_9_16(RMS_L)
         default: return RMSNORM_ERR_UNSUPPORTED;
@@ -492,6 +572,13 @@ int64_t rmsnorm_block_max_n(int dtype) {
 int64_t rmsnorm_unaligned_max_n(int dtype) {
   const int b = elem_bytes(dtype);
   return b ? (int64_t)kBlockMaxThreads * kBlockMaxChunks * (16 / b) + (16 / b - 1) : 0;
+}
+
+int64_t rmsnorm_unaligned_walk_grid(const void* x, const void* w, const void* y, int64_t M,
+                                    int64_t N, int dtype) {
+  if (check_args(x, w, y, M, N, 0.0f, dtype) != RMSNORM_OK) return RMSNORM_ERR_INVALID_ARG;
+  if (pick_threads_unaligned(full_groups_per_row(N, dtype)) == 0) return 0;
+  return unaligned_walk_grid(x, y, M, N, dtype);
 }
 
 int rmsnorm_calib_copy(const void* src, void* dst, int64_t bytes, void* stream) {

@@ -312,54 +312,87 @@ rmsnorm_subwave_kernel(const u32x4* x, const u32x4* __restrict__ w, u32x4* y,
 // ---------------------------------------------------------------------------
 // The same register-resident kernel for rows that are NOT 16-byte aligned (odd
 // N such as 1023 or 4097, or base pointers off a 16-byte boundary).  Rows are
-// addressed in elements: thread t holds the 16-byte groups c * G + t of the
-// row's floor(N / VEC) full groups, read and written with element-aligned
-// 128-bit accesses, and threads 0 .. N % VEC - 1 each take one of the leftover
-// elements at the end of the row.  x is still read exactly once.
+// addressed in elements.  A row is cut into `head` single elements, 16-byte
+// groups and single elements again: thread t holds groups c * G + t, threads
+// 0 .. head - 1 one leading element each, threads 16 .. 16 + tail - 1 one
+// trailing element each.  x is still read exactly once.
+//
+//  WALK == false : head is 0, one row per workgroup (striding only beyond the
+//                  grid limit); every 128-bit access is only element-aligned
+//                  (single global_load/store_dwordx4 instructions on this
+//                  target, at three quarters of the bandwidth in the 16-bit
+//                  types).
+//  WALK == true  : x and y sit at the same offset from a 16-byte boundary and
+//                  the grid is a multiple of 8 workgroups that stay for the
+//                  whole launch.  Rows blockIdx.x + k * gridDim.x then all
+//                  start at the same offset, head brings their groups onto
+//                  16-byte boundaries in x and in y alike, and the workgroup
+//                  reads its slices of the weight (which are off the
+//                  boundaries by that head) once, into registers.  Measured,
+//                  element-aligned weight loads repeated for every row cost
+//                  more than the aligned row accesses gain.
 // ---------------------------------------------------------------------------
-template <int DT, int CHUNKS, int G, bool NT>
+template <int DT, int CHUNKS, int G, bool NT, bool WALK>
 __global__ void __launch_bounds__(G)
 rmsnorm_row_unaligned_kernel(const void* x, const void* __restrict__ w, void* y,
-                             int64_t M, int64_t N, int nfull, float inv_n, float eps) {
+                             int64_t M, int n, float inv_n, float eps) {
   using S = Storage<DT>;
   constexpr int WAVES = G / kWave;
   constexpr int VEC = S::kVec;
   constexpr int kGroupBytes = 16;
+  constexpr int kTailThread = 16;                       // first thread that takes a trailing element
   __shared__ __attribute__((aligned(16))) float partial[2][WAVES];
   const int t = threadIdx.x;
   const int lane = t & (kWave - 1);
   const int wave = t / kWave;
   const int last = (CHUNKS - 1) * G + t;
-  const bool last_ok = last < nfull;
-  const int rem = (int)(N - (int64_t)nfull * VEC);
-  const bool tail_ok = t < rem;
-  const int64_t tail_col = (int64_t)nfull * VEC + t;
   const u32x4 zero = {0u, 0u, 0u, 0u};
-  const char* wb = static_cast<const char*>(w);
   int slot = 0;
+  if (blockIdx.x >= M) return;
 
-  for (int64_t row = blockIdx.x; row < M; row += gridDim.x) {
-    const char* xr = static_cast<const char*>(x) + row * N * S::kBytes;
-    char* yr = static_cast<char*>(y) + row * N * S::kBytes;
+  // The cut, the same for every row of this workgroup.
+  int head = 0;
+  if constexpr (WALK) {
+    const char* first = static_cast<const char*>(x) + (int64_t)blockIdx.x * n * S::kBytes;
+    head = (int)((16u - (unsigned)(reinterpret_cast<uintptr_t>(first) & 15u)) & 15u) / S::kBytes;
+    head = head < n ? head : n;
+  }
+  const int groups = (n - head) / VEC;                  // at most CHUNKS * G, at least (CHUNKS - 1) * G
+  const int tail = n - head - groups * VEC;
+  const bool last_ok = last < groups;
+  const bool edge_ok = t < head || (t >= kTailThread && t - kTailThread < tail);
+  const int edge_col = t < head ? t : head + groups * VEC + (t - kTailThread);
+  const char* wb = static_cast<const char*>(w) + head * S::kBytes;
 
-    u32x4 v[CHUNKS], wv[CHUNKS];
-#pragma unroll
-    for (int c = 0; c < CHUNKS - 1; ++c)
-      v[c] = load_vec_unaligned<NT>(xr + (int64_t)(c * G + t) * kGroupBytes);
-    v[CHUNKS - 1] = zero;
-    if (last_ok) v[CHUNKS - 1] = load_vec_unaligned<NT>(xr + (int64_t)last * kGroupBytes);
-    float tail_x = 0.f, tail_w = 0.f;
-    if (tail_ok) {
-      tail_x = S::load_one(x, row * N + tail_col);
-      tail_w = S::load_one(w, tail_col);
-    }
+  u32x4 wv[CHUNKS];
+  float edge_w = 0.f;
+  auto load_weight = [&]() {
 #pragma unroll
     for (int c = 0; c < CHUNKS - 1; ++c)
       wv[c] = load_vec_unaligned<false>(wb + (int64_t)(c * G + t) * kGroupBytes);
     wv[CHUNKS - 1] = zero;
     if (last_ok) wv[CHUNKS - 1] = load_vec_unaligned<false>(wb + (int64_t)last * kGroupBytes);
+    if (edge_ok) edge_w = S::load_one(w, edge_col);
+  };
+  if constexpr (WALK) load_weight();
 
-    float total = wave_sum(__builtin_fmaf(tail_x, tail_x, lane_sum_sq<DT, CHUNKS>(v)));
+  for (int64_t row = blockIdx.x; row < M; row += gridDim.x) {
+    const char* xr = static_cast<const char*>(x) + row * n * S::kBytes;
+    char* yr = static_cast<char*>(y) + row * n * S::kBytes;
+    const char* xb = xr + head * S::kBytes;
+    char* yb = yr + head * S::kBytes;
+
+    u32x4 v[CHUNKS];
+#pragma unroll
+    for (int c = 0; c < CHUNKS - 1; ++c)
+      v[c] = load_vec_unaligned<NT>(xb + (int64_t)(c * G + t) * kGroupBytes);
+    v[CHUNKS - 1] = zero;
+    if (last_ok) v[CHUNKS - 1] = load_vec_unaligned<NT>(xb + (int64_t)last * kGroupBytes);
+    float edge_x = 0.f;
+    if (edge_ok) edge_x = S::load_one(xr, edge_col);
+    if constexpr (!WALK) load_weight();
+
+    float total = wave_sum(__builtin_fmaf(edge_x, edge_x, lane_sum_sq<DT, CHUNKS>(v)));
     forget_unpacked<CHUNKS>(v);
     if constexpr (WAVES > 1) {
       if (lane == 0) partial[slot][wave] = total;
@@ -371,12 +404,12 @@ rmsnorm_row_unaligned_kernel(const void* x, const void* __restrict__ w, void* y,
 
 #pragma unroll
     for (int c = 0; c < CHUNKS - 1; ++c)
-      store_vec_unaligned<NT>(yr + (int64_t)(c * G + t) * kGroupBytes,
+      store_vec_unaligned<NT>(yb + (int64_t)(c * G + t) * kGroupBytes,
                               scale_vec<DT>(v[c], wv[c], rstd));
     if (last_ok)
-      store_vec_unaligned<NT>(yr + (int64_t)last * kGroupBytes,
+      store_vec_unaligned<NT>(yb + (int64_t)last * kGroupBytes,
                               scale_vec<DT>(v[CHUNKS - 1], wv[CHUNKS - 1], rstd));
-    if (tail_ok) S::store_one(y, row * N + tail_col, (tail_x * rstd) * tail_w);
+    if (edge_ok) S::store_one(yr, edge_col, (edge_x * rstd) * edge_w);
   }
 }
 

@@ -115,11 +115,17 @@ void launch_subwave(const Args& a) {
                      a.nvec);
 }
 
+// x and y at the same offset from a 16-byte boundary: then so is every row of theirs.
+bool same_skew(const void* x, const void* y) {
+  return ((reinterpret_cast<uintptr_t>(x) ^ reinterpret_cast<uintptr_t>(y)) & 15u) == 0;
+}
+
 template <int DT, int CHUNKS, int G>
-void launch_row_unaligned(const Args& a, int nfull) {
+void launch_row_unaligned(const Args& a) {
   const int64_t blocks = a.M < kMaxGrid ? a.M : kMaxGrid;
   hipLaunchKernelGGL((rms::softmax_row_unaligned_kernel<DT, CHUNKS, G, true>), dim3((unsigned)blocks),
-                     dim3(G), 0, a.stream, a.x, a.y, a.M, a.N, nfull);
+                     dim3(G), 0, a.stream, a.x, a.y, a.M, (int)a.N,
+                     (DT != rms::kFp32 && same_skew(a.x, a.y)) ? 1 : 0);
 }
 
 // The LDS-staged kernel for short rows that are not 16-byte aligned: the narrowest lane group
@@ -140,9 +146,7 @@ bool packed_beats_lanes(int64_t nvec, int lanes) {
   return nvec <= 16 && nvec * 10 < slots * 7;
 }
 
-bool packed_can(const void* x, const void* y, int64_t N) {
-  return N <= kPackedMaxN && ((reinterpret_cast<uintptr_t>(x) ^ reinterpret_cast<uintptr_t>(y)) & 15u) == 0;
-}
+bool packed_can(const void* x, const void* y, int64_t N) { return N <= kPackedMaxN && same_skew(x, y); }
 
 template <int DT, int L, int E>
 void launch_packed(const Args& a) {
@@ -256,7 +260,7 @@ int dispatch_unaligned(const Args& a) {
   if (chunks < 1) chunks = 1;
   switch (threads) {
     case 64:
-#define SM_L(c) launch_row_unaligned<DT, c, 64>(a, nfull)
+#define SM_L(c) launch_row_unaligned<DT, c, 64>(a)
       switch (chunks) {
         SM_CASE(1, SM_L(1)) SM_CASE(2, SM_L(2)) SM_CASE(3, SM_L(3)) SM_CASE(4, SM_L(4))
         default: return SOFTMAX_ERR_UNSUPPORTED;
@@ -264,17 +268,17 @@ int dispatch_unaligned(const Args& a) {
 #undef SM_L
       break;
     case 256:
-#define SM_L(c) launch_row_unaligned<DT, c, 256>(a, nfull)
+#define SM_L(c) launch_row_unaligned<DT, c, 256>(a)
       switch (chunks) { SM_CASES_1_8(SM_L) default: return SOFTMAX_ERR_UNSUPPORTED; }
 #undef SM_L
       break;
     case 512:
-#define SM_L(c) launch_row_unaligned<DT, c, 512>(a, nfull)
+#define SM_L(c) launch_row_unaligned<DT, c, 512>(a)
       switch (chunks) { SM_CASES_1_8(SM_L) default: return SOFTMAX_ERR_UNSUPPORTED; }
 #undef SM_L
       break;
     case 1024:
-#define SM_L(c) launch_row_unaligned<DT, c, 1024>(a, nfull)
+#define SM_L(c) launch_row_unaligned<DT, c, 1024>(a)
       switch (chunks) { SM_CASES_1_8(SM_L) default: return SOFTMAX_ERR_UNSUPPORTED; }
 #undef SM_L
       break;

@@ -326,46 +326,58 @@ softmax_subwave_kernel(const u32x4* x, u32x4* y, int64_t M, int nvec) {
 // ---------------------------------------------------------------------------
 // The same register-resident kernel for rows that are NOT 16-byte aligned (odd N such as
 // the paper's edge dims 1023 / 4097 / 1537, or base pointers off a 16-byte boundary).
-// Rows are addressed in elements: thread t holds the 16-byte groups c * G + t of the row's
-// floor(N / VEC) full groups, read and written with 128-bit accesses that are only
-// element-aligned (single global_load/store_dwordx4 instructions on this target), and
-// threads 0 .. N % VEC - 1 each take one of the leftover elements at the end of the row.
-// x is still read exactly once.
+// Rows are addressed in elements.  A row is cut into `head` single elements, 16-byte groups
+// and single elements again: thread t holds groups c * G + t, threads 0 .. head - 1 one
+// leading element each, threads 16 .. 16 + tail - 1 one trailing element each.  With
+// align_body set (the host sets it when x and y sit at the same offset from a 16-byte
+// boundary) head is what brings the groups of this row onto 16-byte boundaries, in x and in
+// y alike; without it head is 0 and the 128-bit accesses are only element-aligned (single
+// global_load/store_dwordx4 instructions on this target, at a lower rate).  x is still read
+// exactly once.
 // ---------------------------------------------------------------------------
 template <int DT, int CHUNKS, int G, bool NT>
 __global__ void __launch_bounds__(G)
-softmax_row_unaligned_kernel(const void* x, void* y, int64_t M, int64_t N, int nfull) {
+softmax_row_unaligned_kernel(const void* x, void* y, int64_t M, int n, int align_body) {
   using S = Storage<DT>;
   constexpr int VEC = S::kVec;
   constexpr int WAVES = G / kWaveSize;
   constexpr int kGroupBytes = 16;
+  constexpr int kTailThread = 16;                       // first thread that takes a trailing element
   __shared__ __attribute__((aligned(16))) float part_max[2][WAVES];
   __shared__ __attribute__((aligned(16))) float part_sum[2][WAVES];
   const int t = threadIdx.x;
   const int lane = t & (kWaveSize - 1);
   const int wave = t / kWaveSize;
   const int last = (CHUNKS - 1) * G + t;
-  const bool last_ok = last < nfull;
-  const int rem = (int)(N - (int64_t)nfull * VEC);
-  const bool tail_ok = t < rem;
-  const int64_t tail_col = (int64_t)nfull * VEC + t;
   int slot = 0;
 
   for (int64_t row = blockIdx.x; row < M; row += gridDim.x) {
-    const char* xr = static_cast<const char*>(x) + row * N * S::kBytes;
-    char* yr = static_cast<char*>(y) + row * N * S::kBytes;
+    const char* xr = static_cast<const char*>(x) + row * n * S::kBytes;
+    char* yr = static_cast<char*>(y) + row * n * S::kBytes;
+    int head = 0;
+    if (align_body) {
+      head = (int)((16u - (unsigned)(reinterpret_cast<uintptr_t>(xr) & 15u)) & 15u) / S::kBytes;
+      head = head < n ? head : n;
+    }
+    const int groups = (n - head) / VEC;                // at most CHUNKS * G, at least (CHUNKS - 1) * G
+    const int tail_n = n - head - groups * VEC;
+    const bool last_ok = last < groups;
+    const bool tail_ok = t < head || (t >= kTailThread && t - kTailThread < tail_n);
+    const int tail_col = t < head ? t : head + groups * VEC + (t - kTailThread);
+    const char* xb = xr + head * S::kBytes;
+    char* yb = yr + head * S::kBytes;
 
     u32x4 v[CHUNKS];
 #pragma unroll
     for (int c = 0; c < CHUNKS - 1; ++c)
-      v[c] = load_vec_unaligned<NT>(xr + (int64_t)(c * G + t) * kGroupBytes);
+      v[c] = load_vec_unaligned<NT>(xb + (int64_t)(c * G + t) * kGroupBytes);
     {
       const u32x4 zero = {0u, 0u, 0u, 0u};
       v[CHUNKS - 1] = zero;
-      if (last_ok) v[CHUNKS - 1] = load_vec_unaligned<NT>(xr + (int64_t)last * kGroupBytes);
+      if (last_ok) v[CHUNKS - 1] = load_vec_unaligned<NT>(xb + (int64_t)last * kGroupBytes);
     }
     float tail = kNegInf;
-    if (tail_ok) tail = S::load_one(x, row * N + tail_col);
+    if (tail_ok) tail = S::load_one(xr, tail_col);
 
     float f[CHUNKS][VEC];
     float m = tail;
@@ -412,9 +424,9 @@ softmax_row_unaligned_kernel(const void* x, void* y, int64_t M, int64_t N, int n
 #pragma unroll
       for (int k = 0; k < VEC; ++k) f[c][k] *= inv;
       if (c < CHUNKS - 1 || last_ok)
-        store_vec_unaligned<NT>(yr + (int64_t)(c * G + t) * kGroupBytes, S::pack(f[c]));
+        store_vec_unaligned<NT>(yb + (int64_t)(c * G + t) * kGroupBytes, S::pack(f[c]));
     }
-    if (tail_ok) S::store_one(y, row * N + tail_col, tail * inv);
+    if (tail_ok) S::store_one(yr, tail_col, tail * inv);
   }
 }
 

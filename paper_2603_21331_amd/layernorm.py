@@ -63,6 +63,8 @@ def load() -> ctypes.CDLL:
     lib.layernorm_fwd_tuned.restype = i32
     lib.layernorm_auto_threads_per_row.argtypes = [i64, i32]
     lib.layernorm_auto_threads_per_row.restype = i32
+    lib.layernorm_unaligned_walk_grid.argtypes = [vp, vp, vp, vp, i64, i64, i32]
+    lib.layernorm_unaligned_walk_grid.restype = i64
     lib.layernorm_register_max_n.argtypes = [i32]
     lib.layernorm_register_max_n.restype = i64
     lib.layernorm_status_string.argtypes = [i32]
@@ -145,6 +147,14 @@ def layernorm_fwd_tuned(x, w, b, eps: float, threads_per_row: int, y=None):
 
 def layernorm_auto_threads_per_row(N: int, dtype: int) -> int:
     rc = int(load().layernorm_auto_threads_per_row(int(N), int(dtype)))
+    if rc < 0:
+        _check(rc)
+    return rc
+
+
+def layernorm_unaligned_walk_grid(x, w, b, y) -> int:
+    M, N, code, _ = _marshal(x, w, b, y)
+    rc = int(load().layernorm_unaligned_walk_grid(x.data_ptr(), w.data_ptr(), _ptr(b), y.data_ptr(), M, N, code))
     if rc < 0:
         _check(rc)
     return rc

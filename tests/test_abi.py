@@ -215,3 +215,25 @@ def test_calib_copy_argument_checks():
     assert lib.rmsnorm_calib_copy(P, P + 4096, 24, None) == binding.RMSNORM_ERR_INVALID_ARG
     assert lib.rmsnorm_calib_copy(P + 4, P + 4096, 32, None) == binding.RMSNORM_ERR_INVALID_ARG
     assert lib.rmsnorm_calib_copy(None, P, 32, None) == binding.RMSNORM_ERR_INVALID_ARG
+
+
+def test_unaligned_walk_grid_query():
+    """The grid of the walking form: a multiple of the compute units (256 without a device) near
+    26 KiB of rows in flight per compute unit, chosen so that the rows divide evenly; 0 where
+    the one-row-per-workgroup form runs."""
+    lib = binding.load()
+    X, W, Y = P, P + (1 << 30), P + (2 << 30)
+    q = lib.rmsnorm_unaligned_walk_grid
+    assert q(X, W, Y, 8192, 4097, 1) == 1024 and q(X, W, Y, 16384, 8191, 2) == 512
+    assert q(X, W, Y, 16384, 1025, 1) == 13 * 256 and q(X, W, Y, 8191, 1537, 1) == 7 * 256
+    assert q(X, W, Y, 3000, 4097, 1) == 512 and q(X, W, Y, 4096, 20481, 2) == 256
+    assert q(X + 6, W + 2, Y + 22, 8192, 4097, 1) == 1024      # same offset from a boundary
+    assert q(X, W, Y + 2, 8192, 4097, 1) == 0                  # different offsets
+    assert q(X, W, Y, 8192, 4097, 0) == 0                      # fp32
+    assert q(X, W, Y, 1500, 4097, 1) == 0                      # too few rows
+    assert q(X, W, Y, 1061, 131079, 1) == 0                    # more than 8 groups per thread
+    assert q(X, W, Y, 4, 1 << 20, 1) == 0                      # does not fit in registers
+    assert q(X, W, Y, 0, 4097, 1) == 0
+    assert q(X, W, Y, 8192, 0, 1) == binding.RMSNORM_ERR_INVALID_ARG
+    assert q(X, W, Y, 8192, 4097, 7) == binding.RMSNORM_ERR_INVALID_ARG
+    assert q(0, W, Y, 8192, 4097, 1) == binding.RMSNORM_ERR_INVALID_ARG

@@ -86,3 +86,22 @@ def test_automatic_threads_per_row():
     with pytest.raises(layernorm.LayerNormError):
         auto(0, 1)
     assert layernorm.layernorm_status_string(0) == "ok" and layernorm.layernorm_status_string(-2)
+
+
+def test_unaligned_walk_grid_query():
+    """The grid of the walking form: a multiple of the compute units (256 without a device) near
+    48 KiB of rows in flight per compute unit, chosen so that the rows divide evenly; 0 where
+    the one-row-per-workgroup form runs."""
+    lib = layernorm.load()
+    X, W, B, Y = P, P + 2 * BIG, P + 3 * BIG, P + 8 * BIG
+    q = lib.layernorm_unaligned_walk_grid
+    assert q(X, W, B, Y, 8192, 4097, 1) == 1024 and q(X, W, B, Y, 16384, 8191, 2) == 768
+    assert q(X, W, B, Y, 4096, 20481, 2) == 256 and q(X, W, None, Y, 8192, 4097, 1) == 1024
+    assert q(X + 6, W + 2, B + 4, Y + 22, 8192, 4097, 1) == 1024   # same offset from a boundary
+    assert q(X, W, B, Y + 2, 8192, 4097, 1) == 0                   # different offsets
+    assert q(X, W, B, Y, 8192, 4097, 0) == 0                       # fp32
+    assert q(X, W, B, Y, 3000, 4097, 1) == 0                       # too few rows
+    assert q(X, W, B, Y, 16384, 2055, 1) == 0 and q(X, W, B, Y, 16384, 2056, 1) > 0
+    assert q(X, W, B, Y, 2048, 32775, 1) == 256 and q(X, W, B, Y, 2048, 32776, 1) == 0
+    assert q(X, W, B, Y, 8192, 0, 1) == layernorm.LAYERNORM_ERR_INVALID_ARG
+    assert q(0, W, B, Y, 8192, 4097, 1) == layernorm.LAYERNORM_ERR_INVALID_ARG

@@ -227,6 +227,13 @@ def test_misaligned_base_pointers(gpu_device, dtype, N):
         torch.cuda.synchronize()
         assert H.guards_intact(whole, M, N, dtype, offset_elems=3)
         compare.check_softmax_parity(H.to_host(y, dtype), want, dtype, f"misaligned bases {mode_name(mode)}")
+    # y at the same offset from a 16-byte boundary as x: the kernel cuts every row at the
+    # boundaries the two share
+    whole, y = H.alloc_guarded(M, N, dtype, gpu_device, offset_elems=1)
+    softmax.softmax_fwd_variant(xd, softmax.SOFTMAX_VARIANT_UNALIGNED, y)
+    torch.cuda.synchronize()
+    assert H.guards_intact(whole, M, N, dtype, offset_elems=1)
+    compare.check_softmax_parity(H.to_host(y, dtype), want, dtype, "misaligned bases, same offset")
     _, y = H.alloc_guarded(M, N, dtype, gpu_device, offset_elems=3)
     for v in (softmax.SOFTMAX_VARIANT_WAVE, softmax.SOFTMAX_VARIANT_BLOCK, softmax.SOFTMAX_VARIANT_SUBWAVE):
         with pytest.raises(softmax.SoftmaxError) as e:

@@ -85,6 +85,13 @@ def test_misaligned_base_pointers(gpu_device, dtype):
     torch.cuda.synchronize()
     assert H.guards_intact(whole2, M, N, dtype, offset_elems=3)
     compare.check_parity(H.to_host(y2, dtype), want, dtype, "misaligned bases, element-wise")
+    # x and y at different offsets from a 16-byte boundary: no cut of the rows aligns both
+    whole3, y3 = H.alloc_guarded(M, N, dtype, gpu_device, offset_elems=2)
+    assert binding.rmsnorm_select_variant(xd, wd, y3) == binding.RMSNORM_VARIANT_UNALIGNED
+    binding.rmsnorm_fwd(xd, wd, 1e-6, y3)
+    torch.cuda.synchronize()
+    assert H.guards_intact(whole3, M, N, dtype, offset_elems=2)
+    compare.check_parity(H.to_host(y3, dtype), want, dtype, "misaligned bases, x and y skewed differently")
     for v in (binding.RMSNORM_VARIANT_WAVE, binding.RMSNORM_VARIANT_BLOCK,
               binding.RMSNORM_VARIANT_SUBWAVE) + \
             tuple(("threads", g) for g in H.THREADS):
