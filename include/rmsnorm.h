@@ -26,7 +26,9 @@
  *    multiple of 16) take the aligned kernels; other rows of up to 1024
  *    elements go through LDS several at a time with aligned 128-bit accesses
  *    (if x and y sit at the same offset from a 16-byte boundary), longer ones
- *    take the register-resident kernel with element-aligned 128-bit accesses;
+ *    take the register-resident kernel addressed in elements (its 128-bit
+ *    accesses fall on 16-byte boundaries under that same condition in the
+ *    16-bit types, and are element-aligned otherwise);
  *    rows too long for registers stream through a two-pass kernel that reads x
  *    a second time from cache.  None of these is an error.
  *  - y == x (exactly in place) is allowed; any other overlap of y with x or w
