@@ -11,18 +11,18 @@ LIB_PATH = os.path.join(_HERE, "librmsnorm_hip.so")
 SOFTMAX_LIB_PATH = os.path.join(_HERE, "libsoftmax_hip.so")
 
 SOURCES = ["rmsnorm_api.hip"]
-HEADERS = ["rmsnorm_kernels.h", "vec_io.h", "wave_reduce.h"]
+HEADERS = ["rmsnorm_kernels.h", "vec_io.h", "wave_reduce.h", "packed_rows.h", "launch_util.h"]
 LAYERNORM_LIB_PATH = os.path.join(_HERE, "liblayernorm_hip.so")
 LAYERNORM_SOURCES = ["layernorm_api.hip"]
-LAYERNORM_HEADERS = ["layernorm_kernels.h", "vec_io.h", "wave_reduce.h"]
+LAYERNORM_HEADERS = ["layernorm_kernels.h", "vec_io.h", "wave_reduce.h", "packed_rows.h", "launch_util.h"]
 CROSSENTROPY_LIB_PATH = os.path.join(_HERE, "libcrossentropy_hip.so")
 CROSSENTROPY_SOURCES = ["crossentropy_api.hip"]
-CROSSENTROPY_HEADERS = ["crossentropy_kernels.h", "vec_io.h", "wave_reduce.h"]
+CROSSENTROPY_HEADERS = ["crossentropy_kernels.h", "vec_io.h", "wave_reduce.h", "packed_rows.h"]
 ROWSUM_LIB_PATH = os.path.join(_HERE, "librowsum_hip.so")
 ROWSUM_SOURCES = ["rowsum_api.hip"]
-ROWSUM_HEADERS = ["rowsum_kernels.h", "vec_io.h", "wave_reduce.h"]
+ROWSUM_HEADERS = ["rowsum_kernels.h", "vec_io.h", "wave_reduce.h", "packed_rows.h"]
 SOFTMAX_SOURCES = ["softmax_api.hip"]
-SOFTMAX_HEADERS = ["softmax_kernels.h", "vec_io.h", "wave_reduce.h"]
+SOFTMAX_HEADERS = ["softmax_kernels.h", "vec_io.h", "wave_reduce.h", "packed_rows.h", "launch_util.h"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC", "-Wall",

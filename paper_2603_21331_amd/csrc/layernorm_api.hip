@@ -4,9 +4,14 @@
 
 #include <hip/hip_runtime.h>
 
+#include "launch_util.h"
 #include "layernorm_kernels.h"
 
 namespace {
+
+using rms::host::compute_units;
+using rms::host::same_skew;
+using rms::host::walk_grid;
 
 using rms::u32x4;
 
@@ -104,21 +109,6 @@ int pick_threads_unaligned(int64_t nfull) {
   return 0;
 }
 
-// Compute units of the current device (256 on MI355X), looked up once per device.
-int compute_units() {
-  constexpr int kMaxDevices = 64;
-  static int cached[kMaxDevices] = {};
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 256;
-  if (cached[dev] == 0) {
-    int n = 0;
-    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
-      n = 256;
-    cached[dev] = n;
-  }
-  return cached[dev];
-}
-
 struct Args {
   const void* x;
   const void* w;
@@ -164,45 +154,12 @@ void launch_subwave(const Args& a) {
                      (const u32x4*)a.b, (u32x4*)a.y, a.M, a.nvec, (float)a.N, a.eps);
 }
 
-// x and y at the same offset from a 16-byte boundary: then so is every row of theirs.
-bool same_skew(const void* x, const void* y) {
-  return ((reinterpret_cast<uintptr_t>(x) ^ reinterpret_cast<uintptr_t>(y)) & 15u) == 0;
-}
-
-constexpr int kWalkMaxChunks = 4;   // what fits in registers next to the packed weight and bias
+// The walking form of the element-addressed kernel: groups per thread that fit in registers
+// next to the packed weight and bias, and where its grid is best, in bytes of rows in flight
+// per compute unit (each resident workgroup has one row in flight; swept on MI355X: 6
+// workgroups of 256 threads at N = 4097, 3 at N = 8191, 2 of 512 at N = 12289).
+constexpr int kWalkMaxChunks = 4;
 constexpr int64_t kWalkBytesPerCu = 48 * 1024;
-
-// Workgroups of the walking form's grid, 0 if the one-row-per-workgroup form should run.
-// Each resident workgroup has one row in flight, and the sweeps on MI355X (N = 1025 .. 40961)
-// put the best grid where about `bytes_per_cu` of rows are in flight per compute unit.  Around
-// that number the grid is chosen so that the rows divide evenly among the workgroups (8192 rows
-// over 5 workgroups per compute unit leave a sixth of the last round idle; over 4 none), and it
-// stays a multiple of the compute units (other grids load them unevenly, measured 10 to 20 %
-// slower) and of 8.  With fewer than four rows per workgroup there is nothing to spread the
-// weight over.
-int64_t walk_grid(int64_t M, int64_t row_bytes, int threads, int64_t bytes_per_cu) {
-  constexpr int kMaxThreadsPerCu = 2048;
-  constexpr int64_t kMinRows = 4;
-  const int64_t cus = compute_units();
-  if (cus % 8 != 0) return 0;
-  const double want = (double)bytes_per_cu / (double)row_bytes;
-  int64_t most = kMaxThreadsPerCu / threads;
-  if (most > M / (kMinRows * cus)) most = M / (kMinRows * cus);
-  int64_t best = 0;
-  double best_cost = 0.0;
-  for (int64_t p = 1; p <= most; ++p) {
-    if ((double)p < 0.55 * want || (double)p > 1.5 * want + 1.0) continue;
-    const int64_t grid = cus * p;
-    const double rounds = (double)((M + grid - 1) / grid);
-    const double miss = ((double)p > want ? (double)p - want : want - (double)p) / want;
-    const double cost = rounds * (double)grid / (double)M * (1.0 + 0.15 * miss);
-    if (best == 0 || cost < best_cost) {
-      best = p;
-      best_cost = cost;
-    }
-  }
-  return cus * best;
-}
 
 // The grid of the walking form for this call and its threads per row, 0 for one workgroup
 // per row: rows of a 16-bit type (dword-aligned 128-bit accesses, which is all that fp32 rows

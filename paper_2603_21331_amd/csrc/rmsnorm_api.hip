@@ -4,9 +4,14 @@
 
 #include <hip/hip_runtime.h>
 
+#include "launch_util.h"
 #include "rmsnorm_kernels.h"
 
 namespace {
+
+using rms::host::compute_units;
+using rms::host::same_skew;
+using rms::host::walk_grid;
 
 using rms::u32x4;
 
@@ -136,11 +141,6 @@ bool packed_beats_lanes(int64_t nvec, int lanes) {
   return nvec <= 16 && nvec * 10 < slots * 7;
 }
 
-// x and y at the same offset from a 16-byte boundary: then so is every row of theirs.
-bool same_skew(const void* x, const void* y) {
-  return ((reinterpret_cast<uintptr_t>(x) ^ reinterpret_cast<uintptr_t>(y)) & 15u) == 0;
-}
-
 bool packed_can(const void* x, const void* y, int64_t N) { return N <= kPackedMaxN && same_skew(x, y); }
 
 int choose(const void* x, const void* w, const void* y, int64_t N, int dtype) {
@@ -201,58 +201,10 @@ void launch_subwave(const Args& a) {
                      1.0f / (float)a.N, a.eps);
 }
 
-// Compute units of the current device (256 on MI355X), looked up once per device.
-int compute_units() {
-  constexpr int kMaxDevices = 64;
-  static int cached[kMaxDevices] = {};
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 256;
-  if (cached[dev] == 0) {
-    int n = 0;
-    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
-      n = 256;
-    cached[dev] = n;
-  }
-  return cached[dev];
-}
-
-// Rows of a 16-bit type with x and y at the same offset from a 16-byte boundary, more of them
-// than resident workgroups: the walking form (aligned row accesses, weight in registers).  Its
-// grid must be a multiple of 8 workgroups, so that every row of a workgroup starts at the same
-// offset from a boundary (8 rows of any length in a 16-bit type are a multiple of 16 bytes).
-// fp32 rows gain nothing from it (dword-aligned 128-bit accesses run at full rate).
-// Workgroups of the walking form's grid, 0 if the one-row-per-workgroup form should run.
-// Each resident workgroup has one row in flight, and the sweeps on MI355X (N = 1025 .. 40961)
-// put the best grid where about `bytes_per_cu` of rows are in flight per compute unit.  Around
-// that number the grid is chosen so that the rows divide evenly among the workgroups (8192 rows
-// over 5 workgroups per compute unit leave a sixth of the last round idle; over 4 none), and it
-// stays a multiple of the compute units (other grids load them unevenly, measured 10 to 20 %
-// slower) and of 8.  With fewer than four rows per workgroup there is nothing to spread the
-// weight over.
-int64_t walk_grid(int64_t M, int64_t row_bytes, int threads, int64_t bytes_per_cu) {
-  constexpr int kMaxThreadsPerCu = 2048;
-  constexpr int64_t kMinRows = 4;
-  const int64_t cus = compute_units();
-  if (cus % 8 != 0) return 0;
-  const double want = (double)bytes_per_cu / (double)row_bytes;
-  int64_t most = kMaxThreadsPerCu / threads;
-  if (most > M / (kMinRows * cus)) most = M / (kMinRows * cus);
-  int64_t best = 0;
-  double best_cost = 0.0;
-  for (int64_t p = 1; p <= most; ++p) {
-    if ((double)p < 0.55 * want || (double)p > 1.5 * want + 1.0) continue;
-    const int64_t grid = cus * p;
-    const double rounds = (double)((M + grid - 1) / grid);
-    const double miss = ((double)p > want ? (double)p - want : want - (double)p) / want;
-    const double cost = rounds * (double)grid / (double)M * (1.0 + 0.15 * miss);
-    if (best == 0 || cost < best_cost) {
-      best = p;
-      best_cost = cost;
-    }
-  }
-  return cus * best;
-}
-
+// The walking form of the element-addressed kernel: where its grid is best, in bytes of rows in
+// flight per compute unit (each resident workgroup has one row in flight; swept over
+// N = 1025 .. 40961: 12 single-wavefront workgroups per compute unit at N = 1025, 3 or 4 of
+// 256 threads at N = 4097, 2 at N = 8191, 1 from N = 12289 on).
 constexpr int64_t kWalkBytesPerCu = 26 * 1024;
 constexpr int kWalkMaxChunks = 8;   // what fits in registers next to the packed weight
 

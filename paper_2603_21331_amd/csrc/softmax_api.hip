@@ -4,9 +4,12 @@
 
 #include <hip/hip_runtime.h>
 
+#include "launch_util.h"
 #include "softmax_kernels.h"
 
 namespace {
+
+using rms::host::same_skew;
 
 using rms::u32x4;
 
@@ -113,11 +116,6 @@ void launch_subwave(const Args& a) {
   hipLaunchKernelGGL((rms::softmax_subwave_kernel<DT, CHUNKS, L, true>), dim3((unsigned)blocks),
                      dim3(rms::kWaveSize), 0, a.stream, (const u32x4*)a.x, (u32x4*)a.y, a.M,
                      a.nvec);
-}
-
-// x and y at the same offset from a 16-byte boundary: then so is every row of theirs.
-bool same_skew(const void* x, const void* y) {
-  return ((reinterpret_cast<uintptr_t>(x) ^ reinterpret_cast<uintptr_t>(y)) & 15u) == 0;
 }
 
 template <int DT, int CHUNKS, int G>
