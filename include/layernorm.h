@@ -58,9 +58,9 @@ typedef enum {
   LAYERNORM_VARIANT_SUBWAVE = 4, /* 8, 16 or 32 lanes per row; 16-byte aligned rows <= 1 KiB */
   LAYERNORM_VARIANT_UNALIGNED = 5, /* the register-resident row kernel addressed in elements:
                                       single elements at both ends of a row and 128-bit accesses
-                                      between them, which resident workgroups put on 16-byte
-                                      boundaries when x and y are congruent modulo 16 bytes and
-                                      there are enough rows (16-bit types; see
+                                      between them, which resident workgroups put on the 16-byte
+                                      boundaries of x (of y too if x and y are congruent modulo
+                                      16 bytes) when there are enough rows (16-bit types; see
                                       layernorm_unaligned_walk_grid), only element-aligned
                                       otherwise: any alignment, N up to the register limit */
   LAYERNORM_VARIANT_STREAM = 6,    /* three streaming passes with 128-bit accesses for rows too
@@ -111,10 +111,9 @@ int layernorm_auto_threads_per_row(int64_t N, int dtype);
  * number of resident workgroups of its walking form (each takes rows blockIdx,
  * blockIdx + grid, ..., all of which start at the same offset from a 16-byte boundary,
  * reads its slices of weight and bias once and cuts every row at the boundaries), or 0
- * if it would run one workgroup per row with element-aligned accesses (fp32; x and y at
- * different offsets from a boundary; fewer than four rows per workgroup; N of at most
- * 2055 or beyond 32775 elements).  A negative layernorm_status for arguments
- * layernorm_fwd would reject.  Only pointer alignment is inspected.
+ * if it would run one workgroup per row with element-aligned accesses (fp32; fewer than
+ * four rows per workgroup; N of at most 2055 or beyond 32775 elements).  A negative
+ * layernorm_status for arguments layernorm_fwd would reject.  No memory is touched.
  */
 int64_t layernorm_unaligned_walk_grid(const void* x, const void* w, const void* b, const void* y,
                                       int64_t M, int64_t N, int dtype);

@@ -26,9 +26,9 @@
  *    multiple of 16) take the aligned kernels; other rows of up to 1024
  *    elements go through LDS several at a time with aligned 128-bit accesses
  *    (if x and y sit at the same offset from a 16-byte boundary), longer ones
- *    take the register-resident kernel addressed in elements (its 128-bit
- *    accesses fall on 16-byte boundaries under that same condition in the
- *    16-bit types, and are element-aligned otherwise);
+ *    take the register-resident kernel addressed in elements (given enough
+ *    rows of a 16-bit type its 128-bit loads fall on 16-byte boundaries, and
+ *    its stores too under that same condition);
  *    rows too long for registers stream through a two-pass kernel that reads x
  *    a second time from cache.  None of these is an error.
  *  - y == x (exactly in place) is allowed; any other overlap of y with x or w
@@ -70,10 +70,10 @@ typedef enum {
   RMSNORM_VARIANT_UNALIGNED = 4, /* row held in registers like WAVE / BLOCK, but addressed in
                                    elements: single elements at both ends and 128-bit
                                    accesses between them, which resident workgroups put on
-                                   16-byte boundaries when x and y are congruent modulo 16
-                                   bytes and there are enough rows (16-bit types; see
-                                   rmsnorm_unaligned_walk_grid) and which are only
-                                   element-aligned otherwise; any alignment, N up to
+                                   the 16-byte boundaries of x (of y too if x and y are
+                                   congruent modulo 16 bytes) when there are enough rows
+                                   (16-bit types; see rmsnorm_unaligned_walk_grid) and
+                                   which are only element-aligned otherwise; any alignment, N up to
                                    rmsnorm_unaligned_max_n(dtype) */
   RMSNORM_VARIANT_SUBWAVE = 5,  /* 8, 16 or 32 lanes per row, several rows per wavefront;
                                    16-byte aligned rows of at most 1 KiB */
@@ -152,10 +152,10 @@ int rmsnorm_select_variant(const void* x, const void* w, const void* y, int64_t 
  * number of resident workgroups of its walking form (each takes rows blockIdx,
  * blockIdx + grid, ..., all of which start at the same offset from a 16-byte boundary,
  * reads its slice of the weight once and cuts every row at the boundaries), or 0 if it
- * would run one workgroup per row with element-aligned accesses (fp32; x and y at
- * different offsets from a boundary; fewer than four rows per workgroup; rows of more
- * than 8 groups per thread; N beyond rmsnorm_unaligned_max_n).  A negative rmsnorm_status
- * for arguments rmsnorm_fwd would reject.  Only pointer alignment is inspected.
+ * would run one workgroup per row with element-aligned accesses (fp32; fewer than four
+ * rows per workgroup; rows of more than 8 groups per thread; N beyond
+ * rmsnorm_unaligned_max_n).  A negative rmsnorm_status for arguments rmsnorm_fwd would
+ * reject.  No memory is touched.
  */
 int64_t rmsnorm_unaligned_walk_grid(const void* x, const void* w, const void* y, int64_t M,
                                     int64_t N, int dtype);

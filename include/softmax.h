@@ -55,9 +55,9 @@ typedef enum {
   SOFTMAX_VARIANT_SUBWAVE = 4, /* 8, 16 or 32 lanes per row; 16-byte aligned rows <= 1 KiB */
   SOFTMAX_VARIANT_UNALIGNED = 5, /* the register-resident row kernel addressed in elements: single
                                     elements at both ends of a row and 128-bit accesses between
-                                    them, on 16-byte boundaries when x and y are congruent modulo
-                                    16 bytes (16-bit types), only element-aligned otherwise: any
-                                    alignment, N up to the register limit */
+                                    them, on the 16-byte boundaries of x (of y too if x and y are
+                                    congruent modulo 16 bytes) in the 16-bit types, dword-aligned
+                                    in fp32: any alignment, N up to the register limit */
   SOFTMAX_VARIANT_STREAM = 6,    /* two streaming passes (online max and sum, then scale) for
                                     rows too long for registers: any alignment, N < 2^31 */
   SOFTMAX_VARIANT_PACKED = 7     /* runs of short rows copied through LDS with 128-bit accesses,

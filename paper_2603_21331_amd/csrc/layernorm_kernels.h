@@ -534,12 +534,13 @@ layernorm_subwave_kernel(const u32x4* x, const u32x4* __restrict__ w, const u32x
 //                  every 128-bit access is only element-aligned (single
 //                  global_load/store_dwordx4 instructions on this target, at a lower rate
 //                  in the 16-bit types); weight and bias are read in the epilogue.
-//  WALK == true  : x and y sit at the same offset from a 16-byte boundary and the grid is
-//                  a multiple of 8 workgroups that stay for the whole launch.  Rows
-//                  blockIdx.x + k * gridDim.x then all start at the same offset, head
-//                  brings their groups onto 16-byte boundaries in x and in y alike, and the
-//                  workgroup reads its slices of weight and bias (off the boundaries by
-//                  that head) once, into registers.
+//  WALK == true  : the grid is a multiple of 8 workgroups that stay for the whole launch.
+//                  Rows blockIdx.x + k * gridDim.x then all start at the same offset from
+//                  a 16-byte boundary, head brings their groups onto the boundaries of x
+//                  (and of y, if y sits at the same offset as x; otherwise the stores stay
+//                  element-aligned, which costs little), and the workgroup reads its slices
+//                  of weight and bias (off the boundaries by that head) once, into
+//                  registers.
 // ---------------------------------------------------------------------------
 template <int DT, int CHUNKS, int G, bool NT, bool WALK>
 __global__ void __launch_bounds__(G) __attribute__((amdgpu_waves_per_eu(4)))

@@ -210,9 +210,10 @@ constexpr int kWalkMaxChunks = 8;   // what fits in registers next to the packed
 
 // The grid of the walking form for this call, 0 for one workgroup per row: rows of a 16-bit
 // type (dword-aligned 128-bit accesses, which is all that fp32 rows can be off by, run at full
-// rate) with x and y at the same offset from a 16-byte boundary.
-int64_t unaligned_walk_grid(const void* x, const void* y, int64_t M, int64_t N, int dtype) {
-  if (dtype == RMSNORM_DTYPE_FP32 || !same_skew(x, y)) return 0;
+// rate).  The rows are cut at the 16-byte boundaries of x; where y sits at another offset its
+// stores stay element-aligned, which costs 2 to 5 % (element-aligned loads cost 10 to 15 %).
+int64_t unaligned_walk_grid(int64_t M, int64_t N, int dtype) {
+  if (dtype == RMSNORM_DTYPE_FP32) return 0;
   const int64_t nfull = full_groups_per_row(N, dtype);
   const int threads = pick_threads_unaligned(nfull);
   if (threads == 0 || (nfull + threads - 1) / threads > kWalkMaxChunks) return 0;
@@ -371,7 +372,7 @@ template <int DT>
 int dispatch_row_unaligned(const Args& a) {
   const int nfull = (int)full_groups_per_row(a.N, DT == rms::kFp32 ? RMSNORM_DTYPE_FP32 : RMSNORM_DTYPE_FP16);
   const int threads = pick_threads_unaligned(nfull);
-  const int64_t walk = unaligned_walk_grid(a.x, a.y, a.M, a.N,
+  const int64_t walk = unaligned_walk_grid(a.M, a.N,
                                            DT == rms::kFp32 ? RMSNORM_DTYPE_FP32 : RMSNORM_DTYPE_FP16);
   int chunks = (nfull + threads - 1) / threads;
   if (chunks < 1) chunks = 1;
@@ -530,7 +531,7 @@ int64_t rmsnorm_unaligned_walk_grid(const void* x, const void* w, const void* y,
                                     int64_t N, int dtype) {
   if (check_args(x, w, y, M, N, 0.0f, dtype) != RMSNORM_OK) return RMSNORM_ERR_INVALID_ARG;
   if (pick_threads_unaligned(full_groups_per_row(N, dtype)) == 0) return 0;
-  return unaligned_walk_grid(x, y, M, N, dtype);
+  return unaligned_walk_grid(M, N, dtype);
 }
 
 int rmsnorm_calib_copy(const void* src, void* dst, int64_t bytes, void* stream) {

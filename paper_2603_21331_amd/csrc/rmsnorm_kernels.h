@@ -322,15 +322,16 @@ rmsnorm_subwave_kernel(const u32x4* x, const u32x4* __restrict__ w, u32x4* y,
 //                  (single global_load/store_dwordx4 instructions on this
 //                  target, at three quarters of the bandwidth in the 16-bit
 //                  types).
-//  WALK == true  : x and y sit at the same offset from a 16-byte boundary and
-//                  the grid is a multiple of 8 workgroups that stay for the
+//  WALK == true  : the grid is a multiple of 8 workgroups that stay for the
 //                  whole launch.  Rows blockIdx.x + k * gridDim.x then all
-//                  start at the same offset, head brings their groups onto
-//                  16-byte boundaries in x and in y alike, and the workgroup
-//                  reads its slices of the weight (which are off the
-//                  boundaries by that head) once, into registers.  Measured,
-//                  element-aligned weight loads repeated for every row cost
-//                  more than the aligned row accesses gain.
+//                  start at the same offset from a 16-byte boundary, head
+//                  brings their groups onto the boundaries of x (and of y,
+//                  if y sits at the same offset as x; otherwise the stores
+//                  stay element-aligned, which costs little), and the
+//                  workgroup reads its slices of the weight (which are off
+//                  the boundaries by that head) once, into registers.
+//                  Measured, element-aligned weight loads repeated for every
+//                  row cost more than the aligned row accesses gain.
 // ---------------------------------------------------------------------------
 template <int DT, int CHUNKS, int G, bool NT, bool WALK>
 __global__ void __launch_bounds__(G)

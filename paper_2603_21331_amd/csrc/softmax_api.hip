@@ -123,7 +123,7 @@ void launch_row_unaligned(const Args& a) {
   const int64_t blocks = a.M < kMaxGrid ? a.M : kMaxGrid;
   hipLaunchKernelGGL((rms::softmax_row_unaligned_kernel<DT, CHUNKS, G, true>), dim3((unsigned)blocks),
                      dim3(G), 0, a.stream, a.x, a.y, a.M, (int)a.N,
-                     (DT != rms::kFp32 && same_skew(a.x, a.y)) ? 1 : 0);
+                     DT != rms::kFp32 ? 1 : 0);
 }
 
 // The LDS-staged kernel for short rows that are not 16-byte aligned: the narrowest lane group

@@ -329,11 +329,12 @@ softmax_subwave_kernel(const u32x4* x, u32x4* y, int64_t M, int nvec) {
 // Rows are addressed in elements.  A row is cut into `head` single elements, 16-byte groups
 // and single elements again: thread t holds groups c * G + t, threads 0 .. head - 1 one
 // leading element each, threads 16 .. 16 + tail - 1 one trailing element each.  With
-// align_body set (the host sets it when x and y sit at the same offset from a 16-byte
-// boundary) head is what brings the groups of this row onto 16-byte boundaries, in x and in
-// y alike; without it head is 0 and the 128-bit accesses are only element-aligned (single
-// global_load/store_dwordx4 instructions on this target, at a lower rate).  x is still read
-// exactly once.
+// align_body set (the host sets it for the 16-bit types) head is what brings the groups of
+// this row onto the 16-byte boundaries of x, and of y if y sits at the same offset as x
+// (otherwise the stores stay element-aligned, which costs little); without it head is 0 and
+// the 128-bit accesses are only element-aligned (single global_load/store_dwordx4
+// instructions on this target: full rate when dword-aligned, as fp32 rows always are, three
+// quarters of it otherwise).  x is still read exactly once.
 // ---------------------------------------------------------------------------
 template <int DT, int CHUNKS, int G, bool NT>
 __global__ void __launch_bounds__(G)

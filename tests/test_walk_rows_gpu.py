@@ -4,7 +4,8 @@ offset from a 16-byte boundary, cuts them at the boundaries and keeps its slices
 (and bias) in registers.  Every thread count and number of groups per thread of that form, all
 eight offsets (odd N walks through them from row to row), bases off a boundary, in place, and
 a row count that does not divide evenly; RMSNorm, softmax (whose kernel makes the same cut
-without residency) and LayerNorm against the CPU oracle, element by element."""
+without residency) and LayerNorm against the CPU oracle, element by element; also with y at
+another offset from a boundary than x (the cut follows x, the stores are element-aligned)."""
 import pytest
 import torch
 
@@ -103,6 +104,24 @@ def test_walking_form_off_a_boundary_in_place_and_without_bias(gpu_device, N, of
     compare.check_softmax_parity(H.to_host(ys, dtype), want_s, dtype, "softmax off a boundary")
     compare.check_layernorm_parity(H.to_host(yl, dtype), want_l, scale, dtype, "layernorm off a boundary")
     compare.check_layernorm_parity(H.to_host(yn, dtype), want_n, scale_n, dtype, "layernorm, no bias")
+
+    # y one element further from the boundary than x: the rows are cut at x's boundaries and
+    # the stores are element-aligned
+    other = offset + 1
+    wr, yr = H.alloc_guarded(M, N, dtype, gpu_device, offset_elems=other)
+    ws, ys = H.alloc_guarded(M, N, dtype, gpu_device, offset_elems=other)
+    wl, yl = H.alloc_guarded(M, N, dtype, gpu_device, offset_elems=other)
+    assert binding.rmsnorm_unaligned_walk_grid(xd, wd, yr) > 0
+    H.say(f"walking form, y at another offset {inputs.DTYPE_NAMES[dtype]} {M}x{N} offsets {offset}, {other}")
+    binding.rmsnorm_fwd_variant(xd, wd, 1e-5, binding.RMSNORM_VARIANT_UNALIGNED, yr)
+    softmax.softmax_fwd_variant(xd, softmax.SOFTMAX_VARIANT_UNALIGNED, ys)
+    layernorm.layernorm_fwd_variant(xd, wd, bd, 1e-5, layernorm.LAYERNORM_VARIANT_UNALIGNED, yl)
+    torch.cuda.synchronize()
+    for whole in (wr, ws, wl):
+        assert H.guards_intact(whole, M, N, dtype, offset_elems=other)
+    compare.check_parity(H.to_host(yr, dtype), want_r, dtype, "rmsnorm, y at another offset")
+    compare.check_softmax_parity(H.to_host(ys, dtype), want_s, dtype, "softmax, y at another offset")
+    compare.check_layernorm_parity(H.to_host(yl, dtype), want_l, scale, dtype, "layernorm, y at another offset")
 
     for name, launch, check in (
             ("rmsnorm", lambda t: binding.rmsnorm_fwd_variant(t, wd, 1e-5, binding.RMSNORM_VARIANT_UNALIGNED, t),
