@@ -24,11 +24,11 @@
  *  - Pointers need only the alignment of their element type.  Rows whose
  *    start is 16-byte aligned (16-byte aligned bases and N * sizeof(dtype) a
  *    multiple of 16) take the aligned kernels; other rows of up to 1024
- *    elements go through LDS several at a time with aligned 128-bit accesses
- *    (if x and y sit at the same offset from a 16-byte boundary), longer ones
- *    take the register-resident kernel addressed in elements (given enough
- *    rows of a 16-bit type its 128-bit loads fall on 16-byte boundaries, and
- *    its stores too under that same condition);
+ *    elements go through LDS several at a time, longer ones take the
+ *    register-resident kernel addressed in elements (given enough rows of a
+ *    16-bit type); both read x with 128-bit loads on 16-byte boundaries and
+ *    write y the same way if x and y sit at the same offset from a boundary,
+ *    with element-aligned 128-bit stores otherwise;
  *    rows too long for registers stream through a two-pass kernel that reads x
  *    a second time from cache.  None of these is an error.
  *  - y == x (exactly in place) is allowed; any other overlap of y with x or w
@@ -81,10 +81,11 @@ typedef enum {
                                    long for registers (the second read comes from cache);
                                    any alignment, N < 2^31 */
   RMSNORM_VARIANT_PACKED = 7    /* runs of short rows copied through LDS with 128-bit accesses,
-                                   1 to 64 lanes per row; N <= 1024, any alignment as long as x
-                                   and y are congruent modulo 16 bytes; what rows that are not
-                                   16-byte aligned take up to that length, and aligned rows
-                                   that are very short or fill their lane group badly */
+                                   1 to 64 lanes per row; N <= 1024, any alignment (the stores
+                                   fall on 16-byte boundaries if x and y are congruent modulo 16
+                                   bytes); what rows that are not 16-byte aligned take up to that
+                                   length, and aligned rows that are very short or fill their
+                                   lane group badly */
 } rmsnorm_variant;
 
 /*
@@ -109,7 +110,7 @@ int rmsnorm_fwd(const void* x, const void* w, void* y, int64_t M, int64_t N,
  * 16-byte aligned rows of at most rmsnorm_wave_max_n(dtype) elements, BLOCK
  * needs 16-byte aligned rows of at most rmsnorm_block_max_n(dtype) elements,
  * UNALIGNED takes any alignment up to rmsnorm_unaligned_max_n(dtype) elements,
- * PACKED up to 1024 elements with x - y a multiple of 16 bytes, STREAM any
+ * PACKED any alignment up to 1024 elements, STREAM any
  * alignment up to N < 2^31, GENERIC takes everything.
  */
 int rmsnorm_fwd_variant(const void* x, const void* w, void* y, int64_t M, int64_t N,

@@ -61,10 +61,11 @@ typedef enum {
   SOFTMAX_VARIANT_STREAM = 6,    /* two streaming passes (online max and sum, then scale) for
                                     rows too long for registers: any alignment, N < 2^31 */
   SOFTMAX_VARIANT_PACKED = 7     /* runs of short rows copied through LDS with 128-bit accesses,
-                                    1 to 64 lanes per row: N <= 1024, any alignment as long as x
-                                    and y are congruent modulo 16 bytes; what rows that are not
-                                    16-byte aligned take up to that length, and aligned rows
-                                    that are very short or fill their lane group badly */
+                                    1 to 64 lanes per row: N <= 1024, any alignment (the stores
+                                    fall on 16-byte boundaries if x and y are congruent modulo 16
+                                    bytes); what rows that are not 16-byte aligned take up to that
+                                    length, and aligned rows that are very short or fill their
+                                    lane group badly */
 } softmax_variant;
 
 /*

@@ -10,7 +10,6 @@
 namespace {
 
 using rms::host::compute_units;
-using rms::host::same_skew;
 using rms::host::walk_grid;
 
 using rms::u32x4;
@@ -196,8 +195,8 @@ void launch_row_unaligned(const Args& a, int64_t walk) {
 
 // The LDS-staged kernel for short rows that are not 16-byte aligned: the narrowest lane group
 // that holds the row (16 elements per lane), as many whole rows per step as fit the tile, at
-// most 8192 workgroups (beyond 128 MiB a workgroup takes several tiles).  It needs x and y at
-// the same offset from a 16-byte boundary, which its tile mirrors.
+// most 8192 workgroups (beyond 128 MiB a workgroup takes several tiles).  Its tile mirrors the
+// offset of x from a 16-byte boundary; where y sits at another, the stores are element-aligned.
 constexpr int64_t kPackedMaxN = 64 * rms::kPackElems;
 constexpr int64_t kPackedMaxGrid = 8192;
 // Aligned rows of at most 64 bytes also take it: one to four of the eight lanes of the
@@ -212,7 +211,7 @@ bool packed_beats_lanes(int64_t nvec, int lanes) {
   return nvec <= 16 && nvec * 10 < slots * 7;
 }
 
-bool packed_can(const void* x, const void* y, int64_t N) { return N <= kPackedMaxN && same_skew(x, y); }
+bool packed_can(int64_t N) { return N <= kPackedMaxN; }
 
 template <int DT, int L, int E>
 void launch_packed(const Args& a) {
@@ -388,12 +387,12 @@ int run(const void* x, const void* w, const void* b, void* y, int64_t M, int64_t
   switch (variant) {
     case LAYERNORM_VARIANT_AUTO:
       threads = vec_ok ? (nvec <= kPackedAutoVectors ? -3 : pick_threads(nvec, 8, dtype))
-                       : packed_can(x, y, N) ? -3 : unaligned_fits ? -1 : 0;
+                       : packed_can(N) ? -3 : unaligned_fits ? -1 : 0;
       if (vec_ok && threads > 0 && threads < 64 && packed_beats_lanes(nvec, threads)) threads = -3;
       if (threads == 0 && N < kStreamMaxN) threads = -2;     // too long for registers
       break;
     case LAYERNORM_VARIANT_PACKED:
-      if (!packed_can(x, y, N)) return LAYERNORM_ERR_UNSUPPORTED;
+      if (!packed_can(N)) return LAYERNORM_ERR_UNSUPPORTED;
       threads = -3;
       break;
     case LAYERNORM_VARIANT_STREAM:

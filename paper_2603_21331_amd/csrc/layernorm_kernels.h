@@ -384,8 +384,7 @@ layernorm_row_resident_kernel(const u32x4* x, const u32x4* __restrict__ w,
 // Short rows that are not 16-byte aligned, several per workgroup, staged through LDS (see
 // packed_rows.h): L lanes per row, E elements per lane with (E - 1) * L < N <= E * L (so only a
 // lane's last element can lie past the end of its row), `tile_rows` rows (at most 16 KiB) per
-// step; x and y must be congruent modulo 16 bytes.  A
-// lane keeps its slices of weight and bias in registers for the whole launch.  The same two
+// step.  A lane keeps its slices of weight and bias in registers for the whole launch.  The same two
 // passes over registers as the other kernels: shift by the row's first element, sum, centre,
 // sum of squares.  Lane groups without a row repeat the last one and write nothing back.
 template <int DT, int L, int E, bool NT>

@@ -6,8 +6,8 @@
 // bytes, and a lane group cannot use 128-bit accesses on rows that start anywhere.  Consecutive
 // rows are contiguous in memory, though: a workgroup of 256 threads takes a run of rows (up to
 // 16 KiB), copies that byte range into LDS with aligned 128-bit accesses that are contiguous
-// across the workgroup (the few bytes before the first and after the last 16-byte boundary go
-// element by element), lets lane groups of L = 1, 2, 4 ... 64 lanes work on one row each out
+// across the workgroup (the few bytes before the first and after the last 16-byte boundary of
+// x go element by element), lets lane groups of L = 1, 2, 4 ... 64 lanes work on one row each out
 // of LDS (element reads, up to kPackElems elements per lane, results written back in place),
 // and copies the range out to y the same way.  Every byte of x and y still crosses HBM once.
 // The kernels are bound by vector-ALU issue, and the reductions and the per-row arithmetic of a
@@ -99,17 +99,19 @@ __device__ __forceinline__ void tile_fill(const char* src, u32x4* tile, TileCut 
   if (has_tail) tile_put<DT>(tile, skew_elems + done + t, tail);
 }
 
-// The reverse: the tile's run to global memory at `dst`, which must have the skew the tile
-// was filled with: the host only launches these kernels when x and y are congruent modulo 16.
+// The reverse: the tile's run to global memory at `dst`, in the cut it was filled with.  Where
+// dst sits at the same offset from a 16-byte boundary as the source (both aligned, or in
+// place) the vector stores fall on the boundaries; elsewhere they are element-aligned, which
+// costs a few per cent.
 template <int DT, bool NT>
 __device__ __forceinline__ void tile_drain(char* dst, const u32x4* tile, TileCut c, int t) {
   constexpr int EB = Storage<DT>::kBytes;
   const int first = (c.skew + c.head) >> 4;
-  u32x4* body = reinterpret_cast<u32x4*>(dst + c.head);
+  char* body = dst + c.head;
 #pragma unroll
   for (int k = 0; k < kPackVecsPerThread; ++k) {
     const int i = k * kPackThreads + t;
-    if (i < c.nvec) store_vec<NT>(body + i, tile[first + i]);
+    if (i < c.nvec) store_vec_unaligned<NT>(body + 16 * i, tile[first + i]);
   }
   const int skew_elems = c.skew / EB;
   if (t < c.head / EB) Storage<DT>::store_one(dst, t, tile_get<DT>(tile, skew_elems + t));

@@ -10,7 +10,6 @@
 namespace {
 
 using rms::host::compute_units;
-using rms::host::same_skew;
 using rms::host::walk_grid;
 
 using rms::u32x4;
@@ -126,9 +125,10 @@ int64_t full_groups_per_row(int64_t N, int dtype) { return N / (16 / elem_bytes(
 constexpr int64_t kStreamMaxN = (int64_t)1 << 31;   // the streaming kernel counts groups in an int
 
 // The LDS-staged kernel takes rows of at most 16 elements per lane of a 64-lane group at any
-// alignment, provided x and y sit at the same offset from a 16-byte boundary (its tile mirrors
-// that offset, so aligned vectors of x are aligned vectors of y); the automatic path uses it
-// for such rows when they are not 16-byte aligned, and for aligned rows of at most four vectors.
+// alignment (its tile mirrors the offset of x from a 16-byte boundary, so aligned vectors of x
+// are aligned vectors of LDS, and of y when y sits at the same offset); the automatic path uses
+// it for such rows when they are not 16-byte aligned, and for aligned rows of at most four
+// vectors.
 constexpr int64_t kPackedMaxN = 64 * rms::kPackElems;
 constexpr int64_t kPackedMaxGrid = 8192;
 constexpr int64_t kPackedAutoVectors = 4;
@@ -141,11 +141,11 @@ bool packed_beats_lanes(int64_t nvec, int lanes) {
   return nvec <= 16 && nvec * 10 < slots * 7;
 }
 
-bool packed_can(const void* x, const void* y, int64_t N) { return N <= kPackedMaxN && same_skew(x, y); }
+bool packed_can(int64_t N) { return N <= kPackedMaxN; }
 
 int choose(const void* x, const void* w, const void* y, int64_t N, int dtype) {
   if (!rows_vectorisable(x, w, y, N, dtype)) {
-    if (packed_can(x, y, N)) return RMSNORM_VARIANT_PACKED;
+    if (packed_can(N)) return RMSNORM_VARIANT_PACKED;
     if (pick_threads_unaligned(full_groups_per_row(N, dtype))) return RMSNORM_VARIANT_UNALIGNED;
     return N < kStreamMaxN ? RMSNORM_VARIANT_STREAM : RMSNORM_VARIANT_GENERIC;
   }
@@ -461,7 +461,7 @@ int run(const void* x, const void* w, void* y, int64_t M, int64_t N, float eps, 
       threads = -2;
       break;
     case RMSNORM_VARIANT_PACKED:
-      if (!packed_can(x, y, N)) return RMSNORM_ERR_UNSUPPORTED;
+      if (!packed_can(N)) return RMSNORM_ERR_UNSUPPORTED;
       threads = -3;
       break;
     default:

@@ -204,8 +204,7 @@ rmsnorm_row_kernel(const u32x4* x, const u32x4* w, u32x4* y,
 // Short rows that are not 16-byte aligned, several per workgroup, staged through LDS (see
 // packed_rows.h): L lanes per row, E elements per lane with (E - 1) * L < N <= E * L (so only
 // a lane's last element can lie past the end of its row), `tile_rows` rows (at most 16 KiB) per
-// step; x and y must be congruent modulo 16 bytes.  A lane keeps its slice of the weight in registers for the
-// whole launch.  Lane groups without a row repeat the last one and write nothing back.
+// step.  A lane keeps its slice of the weight in registers for the whole launch.  Lane groups without a row repeat the last one and write nothing back.
 // ---------------------------------------------------------------------------
 template <int DT, int L, int E, bool NT>
 __global__ void __launch_bounds__(kPackThreads)

@@ -9,7 +9,6 @@
 
 namespace {
 
-using rms::host::same_skew;
 
 using rms::u32x4;
 
@@ -128,8 +127,8 @@ void launch_row_unaligned(const Args& a) {
 
 // The LDS-staged kernel for short rows that are not 16-byte aligned: the narrowest lane group
 // that holds the row (16 elements per lane), as many whole rows per step as fit the tile, at
-// most 8192 workgroups (beyond 128 MiB a workgroup takes several tiles).  It needs x and y at
-// the same offset from a 16-byte boundary, which its tile mirrors.
+// most 8192 workgroups (beyond 128 MiB a workgroup takes several tiles).  Its tile mirrors the
+// offset of x from a 16-byte boundary; where y sits at another, the stores are element-aligned.
 constexpr int64_t kPackedMaxN = 64 * rms::kPackElems;
 constexpr int64_t kPackedMaxGrid = 8192;
 // Aligned rows of at most 64 bytes also take it: one to four of the eight lanes of the
@@ -144,7 +143,7 @@ bool packed_beats_lanes(int64_t nvec, int lanes) {
   return nvec <= 16 && nvec * 10 < slots * 7;
 }
 
-bool packed_can(const void* x, const void* y, int64_t N) { return N <= kPackedMaxN && same_skew(x, y); }
+bool packed_can(int64_t N) { return N <= kPackedMaxN; }
 
 template <int DT, int L, int E>
 void launch_packed(const Args& a) {
@@ -315,12 +314,12 @@ int run(const void* x, void* y, int64_t M, int64_t N, int dtype, void* stream, i
   switch (variant) {
     case SOFTMAX_VARIANT_AUTO:
       threads = vec_ok ? (nvec <= kPackedAutoVectors ? -3 : pick_threads(nvec, 8))
-                       : packed_can(x, y, N) ? -3 : unaligned_fits ? -1 : 0;
+                       : packed_can(N) ? -3 : unaligned_fits ? -1 : 0;
       if (vec_ok && threads > 0 && threads < 64 && packed_beats_lanes(nvec, threads)) threads = -3;
       if (threads == 0 && N < kStreamMaxN) threads = -2;     // too long for registers
       break;
     case SOFTMAX_VARIANT_PACKED:
-      if (!packed_can(x, y, N)) return SOFTMAX_ERR_UNSUPPORTED;
+      if (!packed_can(N)) return SOFTMAX_ERR_UNSUPPORTED;
       threads = -3;
       break;
     case SOFTMAX_VARIANT_STREAM:

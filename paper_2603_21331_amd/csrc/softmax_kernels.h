@@ -209,8 +209,8 @@ softmax_row_kernel(const u32x4* x, u32x4* y, int64_t M, int nvec) {
 // Short rows that are not 16-byte aligned (an attention row of 77, 197 or 257 scores), several
 // per workgroup, staged through LDS (see packed_rows.h): L lanes per row, E elements per lane
 // with (E - 1) * L < N <= E * L (so only a lane's last element can lie past the end of its row),
-// `tile_rows` rows (at most 16 KiB) per step; x and y must be congruent modulo 16 bytes.  Lane groups without a row repeat the last one and write nothing
-// back.  (Skipping the steps that hold no element of any row, a test that is the same for
+// `tile_rows` rows (at most 16 KiB) per step.  Lane groups without a row repeat the last one
+// and write nothing back.  (Skipping the steps that hold no element of any row, a test that is the same for
 // every lane, was measured and is 10 % slower: the branches keep the LDS reads apart.)
 // ---------------------------------------------------------------------------
 template <int DT, int L, int E, bool NT>

@@ -49,16 +49,14 @@ def test_rmsnorm_packed_lengths(gpu_device, N, dtype):
         assert H.guards_intact(whole, M, N, dtype, offset_elems=1 + per16)
         compare.check_parity(H.to_host(y, dtype), want, dtype, f"packed offset bases mode {mode}")
     assert binding.rmsnorm_select_variant(xd, wd, y) == binding.RMSNORM_VARIANT_PACKED
-    # x and y at different distances: the kernel refuses, the automatic path takes another
-    whole, y = H.alloc_guarded(M, N, dtype, gpu_device, offset_elems=2)
-    with pytest.raises(binding.RmsnormError) as e:
-        binding.rmsnorm_fwd_variant(xd, wd, 1e-6, binding.RMSNORM_VARIANT_PACKED, y)
-    assert e.value.status == binding.RMSNORM_ERR_UNSUPPORTED
-    assert binding.rmsnorm_select_variant(xd, wd, y) == binding.RMSNORM_VARIANT_UNALIGNED
-    binding.rmsnorm_fwd(xd, wd, 1e-6, y)
-    torch.cuda.synchronize()
-    assert H.guards_intact(whole, M, N, dtype, offset_elems=2)
-    compare.check_parity(H.to_host(y, dtype), want, dtype, "x and y at different offsets")
+    # x and y at different distances: the same kernel, with element-aligned stores
+    for mode in (binding.RMSNORM_VARIANT_AUTO, binding.RMSNORM_VARIANT_PACKED):
+        whole, y = H.alloc_guarded(M, N, dtype, gpu_device, offset_elems=2)
+        assert binding.rmsnorm_select_variant(xd, wd, y) == binding.RMSNORM_VARIANT_PACKED
+        binding.rmsnorm_fwd_variant(xd, wd, 1e-6, mode, y)
+        torch.cuda.synchronize()
+        assert H.guards_intact(whole, M, N, dtype, offset_elems=2)
+        compare.check_parity(H.to_host(y, dtype), want, dtype, "x and y at different offsets")
 
 
 @pytest.mark.parametrize("dtype", DTYPES)
@@ -122,14 +120,12 @@ def test_softmax_packed_lengths(gpu_device, N, dtype):
         torch.cuda.synchronize()
         assert H.guards_intact(whole, M, N, dtype, offset_elems=1 + 2 * per16)
         compare.check_softmax_parity(H.to_host(y, dtype), want, dtype, f"softmax packed offset bases mode {mode}")
-    whole, y = H.alloc_guarded(M, N, dtype, gpu_device, offset_elems=2)
-    with pytest.raises(softmax.SoftmaxError) as e:
-        softmax.softmax_fwd_variant(xd, softmax.SOFTMAX_VARIANT_PACKED, y)
-    assert e.value.status == softmax.SOFTMAX_ERR_UNSUPPORTED
-    softmax.softmax_fwd(xd, y)      # the automatic path takes another kernel
-    torch.cuda.synchronize()
-    assert H.guards_intact(whole, M, N, dtype, offset_elems=2)
-    compare.check_softmax_parity(H.to_host(y, dtype), want, dtype, "softmax, x and y at different offsets")
+    for mode in (0, softmax.SOFTMAX_VARIANT_PACKED):     # the same kernel, element-aligned stores
+        whole, y = H.alloc_guarded(M, N, dtype, gpu_device, offset_elems=2)
+        softmax.softmax_fwd_variant(xd, mode, y)
+        torch.cuda.synchronize()
+        assert H.guards_intact(whole, M, N, dtype, offset_elems=2)
+        compare.check_softmax_parity(H.to_host(y, dtype), want, dtype, "softmax, x and y at different offsets")
 
 
 @pytest.mark.parametrize("dtype", DTYPES)
@@ -183,10 +179,12 @@ def test_layernorm_packed_offset_bases_and_in_place(gpu_device, dtype):
         assert H.guards_intact(whole, M, N, dtype, offset_elems=3 + per16)
         compare.check_layernorm_parity(H.to_host(y, dtype), want, bias64, dtype, f"layernorm packed offset mode {mode}")
     first = H.to_host(y, dtype).copy()
-    whole, y2 = H.alloc_guarded(M, N, dtype, gpu_device, offset_elems=1)
-    with pytest.raises(layernorm.LayerNormError) as e:
-        layernorm.layernorm_fwd_variant(xd, wd, bd, 1e-5, layernorm.LAYERNORM_VARIANT_PACKED, y2)
-    assert e.value.status == layernorm.LAYERNORM_ERR_UNSUPPORTED
+    for mode in (0, layernorm.LAYERNORM_VARIANT_PACKED):  # y at another offset: element-aligned stores
+        whole, y2 = H.alloc_guarded(M, N, dtype, gpu_device, offset_elems=1)
+        layernorm.layernorm_fwd_variant(xd, wd, bd, 1e-5, mode, y2)
+        torch.cuda.synchronize()
+        assert H.guards_intact(whole, M, N, dtype, offset_elems=1)
+        compare.check_layernorm_parity(H.to_host(y2, dtype), want, bias64, dtype, "layernorm, y at another offset")
     H.say("layernorm packed in place")
     layernorm.layernorm_fwd_variant(xd, wd, bd, 1e-5, layernorm.LAYERNORM_VARIANT_PACKED, xd)
     torch.cuda.synchronize()
