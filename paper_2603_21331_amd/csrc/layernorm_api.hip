@@ -213,6 +213,15 @@ bool packed_beats_lanes(int64_t nvec, int lanes) {
 
 bool packed_can(int64_t N) { return N <= kPackedMaxN; }
 
+// Rows of at least 1 KiB whose loads are all 16-byte aligned, so that only y sits off a
+// boundary: the register-resident kernel with element-aligned stores beats the LDS-staged one
+// there (fp16 N = 1024: 3 to 30 % over the three operations); shorter rows stay with the
+// LDS-staged kernel (N = 256: 12 to 25 % the other way).
+bool only_stores_unaligned(const void* x, const void* w, const void* b, int64_t N, int dtype) {
+  const int64_t row_bytes = N * elem_bytes(dtype);
+  return aligned16(x) && aligned16(w) && aligned16(b) && row_bytes % 16 == 0 && row_bytes >= 1024;
+}
+
 template <int DT, int L, int E>
 void launch_packed(const Args& a) {
   const int n = (int)a.N;
@@ -387,7 +396,8 @@ int run(const void* x, const void* w, const void* b, void* y, int64_t M, int64_t
   switch (variant) {
     case LAYERNORM_VARIANT_AUTO:
       threads = vec_ok ? (nvec <= kPackedAutoVectors ? -3 : pick_threads(nvec, 8, dtype))
-                       : packed_can(N) ? -3 : unaligned_fits ? -1 : 0;
+                       : (packed_can(N) && !only_stores_unaligned(x, w, b, N, dtype)) ? -3
+                       : unaligned_fits ? -1 : 0;
       if (vec_ok && threads > 0 && threads < 64 && packed_beats_lanes(nvec, threads)) threads = -3;
       if (threads == 0 && N < kStreamMaxN) threads = -2;     // too long for registers
       break;

@@ -143,9 +143,18 @@ bool packed_beats_lanes(int64_t nvec, int lanes) {
 
 bool packed_can(int64_t N) { return N <= kPackedMaxN; }
 
+// Rows of at least 1 KiB whose loads are all 16-byte aligned, so that only y sits off a
+// boundary: the register-resident kernel with element-aligned stores beats the LDS-staged one
+// there (fp16 N = 1024: 3 to 30 % over the three operations); shorter rows stay with the
+// LDS-staged kernel (N = 256: 12 to 25 % the other way).
+bool only_stores_unaligned(const void* x, const void* w, int64_t N, int dtype) {
+  const int64_t row_bytes = N * elem_bytes(dtype);
+  return aligned16(x) && aligned16(w) && row_bytes % 16 == 0 && row_bytes >= 1024;
+}
+
 int choose(const void* x, const void* w, const void* y, int64_t N, int dtype) {
   if (!rows_vectorisable(x, w, y, N, dtype)) {
-    if (packed_can(N)) return RMSNORM_VARIANT_PACKED;
+    if (packed_can(N) && !only_stores_unaligned(x, w, N, dtype)) return RMSNORM_VARIANT_PACKED;
     if (pick_threads_unaligned(full_groups_per_row(N, dtype))) return RMSNORM_VARIANT_UNALIGNED;
     return N < kStreamMaxN ? RMSNORM_VARIANT_STREAM : RMSNORM_VARIANT_GENERIC;
   }

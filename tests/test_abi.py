@@ -196,6 +196,11 @@ def test_dispatch_choice_is_visible_without_a_launch():
     assert sel(P, P + 65536, P + 131072, 16, 511, 1) == binding.RMSNORM_VARIANT_PACKED
     assert sel(P + 2, P + 65536, P + 131072 + 18, 16, 512, 1) == binding.RMSNORM_VARIANT_PACKED
     assert sel(P + 2, P + 65536, P + 131072, 16, 512, 1) == binding.RMSNORM_VARIANT_PACKED  # x - y not a multiple of 16
+    # only y off a boundary: rows of 1 KiB and more keep the register kernel (aligned loads)
+    assert sel(P, P + 65536, P + 131072 + 2, 16, 512, 1) == binding.RMSNORM_VARIANT_UNALIGNED
+    assert sel(P, P + 65536, P + 131072 + 2, 16, 504, 1) == binding.RMSNORM_VARIANT_PACKED
+    assert sel(P, P + 65536, P + 131072 + 4, 16, 256, 0) == binding.RMSNORM_VARIANT_UNALIGNED
+    assert sel(P, P + 65536 + 2, P + 131072 + 2, 16, 512, 1) == binding.RMSNORM_VARIANT_PACKED
     assert sel(P, P + 65536, P + 131072, 16, 197, 2) == binding.RMSNORM_VARIANT_PACKED
     assert sel(P, P + 65536, P + 131072, 16, 3, 0) == binding.RMSNORM_VARIANT_PACKED
     assert sel(P, P + 65536, P + 131072, 16, 512, 1) == binding.RMSNORM_VARIANT_WAVE
