@@ -154,7 +154,7 @@ int rmsnorm_select_variant(const void* x, const void* w, const void* y, int64_t 
  * blockIdx + grid, ..., all of which start at the same offset from a 16-byte boundary,
  * reads its slice of the weight once and cuts every row at the boundaries), or 0 if it
  * would run one workgroup per row with element-aligned accesses (fp32; fewer than four
- * rows per workgroup; rows of more than 8 groups per thread; N beyond
+ * rows per workgroup; rows of more than 8 groups per thread, 7 with 1024 threads; N beyond
  * rmsnorm_unaligned_max_n).  A negative rmsnorm_status for arguments rmsnorm_fwd would
  * reject.  No memory is touched.
  */

@@ -225,14 +225,16 @@ int64_t unaligned_walk_grid(int64_t M, int64_t N, int dtype) {
   if (dtype == RMSNORM_DTYPE_FP32) return 0;
   const int64_t nfull = full_groups_per_row(N, dtype);
   const int threads = pick_threads_unaligned(nfull);
-  if (threads == 0 || (nfull + threads - 1) / threads > kWalkMaxChunks) return 0;
+  if (threads == 0) return 0;
+  // (1024 threads are capped at 128 registers each: 7 groups next to their weight)
+  if ((nfull + threads - 1) / threads > (threads == kBlockMaxThreads ? kWalkMaxChunks - 1 : kWalkMaxChunks)) return 0;
   return walk_grid(M, N * elem_bytes(dtype), threads, kWalkBytesPerCu);
 }
 
 // walk > 0: the walking form with that many resident workgroups.
 template <int DT, int CHUNKS, int G>
 void launch_row_unaligned(const Args& a, int64_t walk) {
-  if constexpr (DT != rms::kFp32 && CHUNKS <= kWalkMaxChunks) {
+  if constexpr (DT != rms::kFp32 && CHUNKS <= (G == kBlockMaxThreads ? kWalkMaxChunks - 1 : kWalkMaxChunks)) {
     if (walk > 0) {
       hipLaunchKernelGGL((rms::rmsnorm_row_unaligned_kernel<DT, CHUNKS, G, true, true>),
                          dim3((unsigned)walk), dim3(G), 0, a.stream,

@@ -364,14 +364,20 @@ rmsnorm_row_unaligned_kernel(const void* x, const void* __restrict__ w, void* y,
   const int edge_col = t < head ? t : head + groups * VEC + (t - kTailThread);
   const char* wb = static_cast<const char*>(w) + head * S::kBytes;
 
-  u32x4 wv[CHUNKS];
+  // 1024 threads with 8 and more groups each (a workgroup of that size is capped at 128
+  // registers per thread): the weight is fetched group by group in the epilogue instead of
+  // all at once with the row, which would spill.
+  constexpr bool W_LATE = !WALK && G == 1024 && CHUNKS >= 8;
+  u32x4 wv[W_LATE ? 1 : CHUNKS];
   float edge_w = 0.f;
   auto load_weight = [&]() {
+    if constexpr (!W_LATE) {
 #pragma unroll
-    for (int c = 0; c < CHUNKS - 1; ++c)
-      wv[c] = load_vec_unaligned<false>(wb + (int64_t)(c * G + t) * kGroupBytes);
-    wv[CHUNKS - 1] = zero;
-    if (last_ok) wv[CHUNKS - 1] = load_vec_unaligned<false>(wb + (int64_t)last * kGroupBytes);
+      for (int c = 0; c < CHUNKS - 1; ++c)
+        wv[c] = load_vec_unaligned<false>(wb + (int64_t)(c * G + t) * kGroupBytes);
+      wv[CHUNKS - 1] = zero;
+      if (last_ok) wv[CHUNKS - 1] = load_vec_unaligned<false>(wb + (int64_t)last * kGroupBytes);
+    }
     if (edge_ok) edge_w = S::load_one(w, edge_col);
   };
   if constexpr (WALK) load_weight();
@@ -402,13 +408,19 @@ rmsnorm_row_unaligned_kernel(const void* x, const void* __restrict__ w, void* y,
     }
     const float rstd = row_rstd(total, inv_n, eps);
 
+    const char* wp = wb;
+    if constexpr (W_LATE) asm volatile("" : "+s"(wp) : "v"(rstd));   // not before the reduction
 #pragma unroll
-    for (int c = 0; c < CHUNKS - 1; ++c)
-      store_vec_unaligned<NT>(yb + (int64_t)(c * G + t) * kGroupBytes,
-                              scale_vec<DT>(v[c], wv[c], rstd));
-    if (last_ok)
-      store_vec_unaligned<NT>(yb + (int64_t)last * kGroupBytes,
-                              scale_vec<DT>(v[CHUNKS - 1], wv[CHUNKS - 1], rstd));
+    for (int c = 0; c < CHUNKS - 1; ++c) {
+      const int64_t off = (int64_t)(c * G + t) * kGroupBytes;
+      const u32x4 wc = W_LATE ? load_vec_unaligned<false>(wp + off) : wv[W_LATE ? 0 : c];
+      store_vec_unaligned<NT>(yb + off, scale_vec<DT>(v[c], wc, rstd));
+    }
+    if (last_ok) {
+      const int64_t off = (int64_t)last * kGroupBytes;
+      const u32x4 wc = W_LATE ? load_vec_unaligned<false>(wp + off) : wv[W_LATE ? 0 : CHUNKS - 1];
+      store_vec_unaligned<NT>(yb + off, scale_vec<DT>(v[CHUNKS - 1], wc, rstd));
+    }
     if (edge_ok) S::store_one(yr, edge_col, (edge_x * rstd) * edge_w);
   }
 }

@@ -234,6 +234,7 @@ def test_unaligned_walk_grid_query():
     assert q(X, W, Y, 8192, 4097, 0) == 0                      # fp32
     assert q(X, W, Y, 1500, 4097, 1) == 0                      # too few rows
     assert q(X, W, Y, 1061, 131079, 1) == 0                    # more than 8 groups per thread
+    assert q(X, W, Y, 1061, 57343, 1) == 256 and q(X, W, Y, 1061, 65535, 1) == 0   # 1024 threads: 7
     assert q(X, W, Y, 4, 1 << 20, 1) == 0                      # does not fit in registers
     assert q(X, W, Y, 0, 4097, 1) == 0
     assert q(X, W, Y, 8192, 0, 1) == binding.RMSNORM_ERR_INVALID_ARG

@@ -19,7 +19,7 @@ DTYPES = [inputs.FP32, inputs.FP16, inputs.BF16]
 @pytest.mark.parametrize("dtype", DTYPES)
 @pytest.mark.parametrize("M,N", [(1023, 1023), (33, 4097), (129, 1537), (4097, 24), (1537, 1023),
                                  (5, 8193), (3, 40001), (65, 2049), (9, 16391), (7, 33001),
-                                 (3, 131079), (2, 131080), (6, 7), (6, 9), (11, 3)])
+                                 (3, 131079), (2, 131080), (5, 65535), (3, 98305), (6, 7), (6, 9), (11, 3)])
 def test_paper_edge_dims(gpu_device, M, N, dtype):
     H.check_case(inputs.random_case(5, 800 + 2 * dtype, M, N, dtype, 1e-6), gpu_device)
 
