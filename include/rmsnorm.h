@@ -18,7 +18,8 @@
  *  - All tensor pointers are DEVICE pointers owned by the caller.  The library
  *    never allocates, frees, copies or synchronises; a call enqueues work on
  *    `stream` and returns at once.  Buffers must stay alive until that work
- *    has run.
+ *    has run.  (The library holds one static device array of 128 KiB per GPU,
+ *    part of its code object: the counters described under rmsnorm_fwd.)
  *  - x and y are M x N, row-major, leading dimension N (no stride argument);
  *    w has N elements.  x, w and y share one storage type `dtype`.
  *  - Pointers need only the alignment of their element type.  Rows whose
@@ -37,7 +38,9 @@
  *    aborts.  On RMSNORM_ERR_INVALID_ARG and RMSNORM_ERR_UNSUPPORTED nothing
  *    was launched.
  *  - Results are bit-identical from run to run for a given (shape, dtype,
- *    alignment, variant): reductions have a fixed order and use no atomics.
+ *    alignment, variant): reductions have a fixed order and no sum goes through
+ *    an atomic (RMSNORM_VARIANT_QUEUE hands out rows with atomic counters; which
+ *    workgroup takes a row does not change the row's arithmetic).
  */
 #ifndef RMSNORM_H_
 #define RMSNORM_H_
@@ -80,12 +83,19 @@ typedef enum {
   RMSNORM_VARIANT_STREAM = 6,   /* two streaming passes with 128-bit accesses for rows too
                                    long for registers (the second read comes from cache);
                                    any alignment, N < 2^31 */
-  RMSNORM_VARIANT_PACKED = 7    /* runs of short rows copied through LDS with 128-bit accesses,
+  RMSNORM_VARIANT_PACKED = 7,   /* runs of short rows copied through LDS with 128-bit accesses,
                                    1 to 64 lanes per row; N <= 1024, any alignment (the stores
                                    fall on 16-byte boundaries if x and y are congruent modulo 16
                                    bytes); what rows that are not 16-byte aligned take up to that
                                    length, and aligned rows that are very short or fill their
                                    lane group badly */
+  RMSNORM_VARIANT_QUEUE = 8     /* BLOCK's arithmetic on a grid of one or two workgroups per compute
+                                   unit that stay for the whole launch, keep their slices of the
+                                   weight in registers and draw rows from counters in device
+                                   memory; 16-byte aligned rows of 513 to 4096 vectors of 16 bytes
+                                   (8 KiB to 64 KiB), fewer than 2^30 rows.  What AUTO takes for rows
+                                   of 16 KiB and more once the launch reads 96 MiB, on streams
+                                   that have counters (see rmsnorm_fwd) */
 } rmsnorm_variant;
 
 /*
@@ -98,6 +108,15 @@ typedef enum {
  *   eps    added to the mean of squares inside the root; must be >= 0
  *   dtype  an rmsnorm_dtype
  *   stream a hipStream_t passed as void*; NULL is the default stream
+ *
+ * Large launches of long rows (RMSNORM_VARIANT_QUEUE) need 4 KiB of counters in device memory.
+ * This entry point takes them from an array inside the library, one block per stream: launches
+ * on one stream run one after the other, so a block is never used by two kernels at once, and
+ * the kernel leaves its counters at zero for the next launch.  The first 32 streams seen on a
+ * device get a block each and keep it; a call on any other stream, on the per-thread default
+ * stream, or on a stream that is being captured into a graph (a graph can be replayed on any
+ * stream) runs the one-workgroup-per-row kernel instead, with the same bits in y.  The only
+ * state kept between calls is which stream owns which block.
  */
 int rmsnorm_fwd(const void* x, const void* w, void* y, int64_t M, int64_t N,
                 float eps, int dtype, void* stream);
@@ -111,7 +130,9 @@ int rmsnorm_fwd(const void* x, const void* w, void* y, int64_t M, int64_t N,
  * needs 16-byte aligned rows of at most rmsnorm_block_max_n(dtype) elements,
  * UNALIGNED takes any alignment up to rmsnorm_unaligned_max_n(dtype) elements,
  * PACKED any alignment up to 1024 elements, STREAM any
- * alignment up to N < 2^31, GENERIC takes everything.
+ * alignment up to N < 2^31, GENERIC takes everything.  QUEUE needs 16-byte
+ * aligned rows of 513 to 4096 vectors and a stream that has counters (see
+ * rmsnorm_fwd).
  */
 int rmsnorm_fwd_variant(const void* x, const void* w, void* y, int64_t M, int64_t N,
                         float eps, int dtype, void* stream, int variant);
@@ -132,6 +153,49 @@ int rmsnorm_fwd_variant(const void* x, const void* w, void* y, int64_t M, int64_
  */
 int rmsnorm_fwd_tuned(const void* x, const void* w, void* y, int64_t M, int64_t N,
                       float eps, int dtype, void* stream, int threads_per_row);
+
+/*
+ * The work-queue kernel (RMSNORM_VARIANT_QUEUE: the paper's single fused pass, Section 7.1,
+ * with the weight multiply of Section 7.3 tier 3 fed from registers instead of from cache) on
+ * counters that the caller brings.
+ *   workspace        device memory, 4-byte aligned, at least rmsnorm_workspace_bytes() bytes,
+ *                    owned by the caller.  It must be zero-filled before its first use; every
+ *                    call leaves it zero-filled, so it can be passed again without clearing.
+ *                    Two calls whose kernels may run at the same time need a workspace each.
+ *   workspace_bytes  its size
+ * Other arguments as for rmsnorm_fwd.  RMSNORM_ERR_INVALID_ARG for a workspace that is null,
+ * misaligned or too small; RMSNORM_ERR_UNSUPPORTED for rows the kernel does not take (see
+ * RMSNORM_VARIANT_QUEUE); nothing is launched in either case.  y holds the same bits as after
+ * rmsnorm_fwd_tuned with 512 threads per row.
+ */
+int rmsnorm_fwd_workspace(const void* x, const void* w, void* y, int64_t M, int64_t N, float eps,
+                          int dtype, void* stream, void* workspace, int64_t workspace_bytes);
+
+/* Bytes of workspace that rmsnorm_fwd_workspace and rmsnorm_fwd_queue_tuned need (4096). */
+int64_t rmsnorm_workspace_bytes(void);
+
+/*
+ * rmsnorm_fwd_workspace with the launch shape forced (tests run odd shapes through it, tuning
+ * sweeps check the automatic choice):
+ *   grid        resident workgroups of 512 threads, a multiple of `shards`, at most 65536
+ *   shards      1 .. 32 groups of workgroups, each with its own counters and its own rows
+ *   block_rows  a power of two up to 65536: rows are dealt to the shards in blocks of that many
+ *   prefetch    non-zero: a workgroup requests its next row before it stores the current one
+ * RMSNORM_ERR_INVALID_ARG for values outside these ranges.
+ */
+int rmsnorm_fwd_queue_tuned(const void* x, const void* w, void* y, int64_t M, int64_t N, float eps,
+                            int dtype, void* stream, void* workspace, int64_t workspace_bytes,
+                            int grid, int shards, int block_rows, int prefetch);
+
+/*
+ * The launch shape RMSNORM_VARIANT_QUEUE uses for M rows of N elements on the current device
+ * (any of the four output pointers may be NULL).  Returns 1 if RMSNORM_VARIANT_AUTO takes that
+ * variant for such a call (given 16-byte aligned pointers and a stream with counters), 0 if the
+ * variant can run it but AUTO prefers another, RMSNORM_ERR_UNSUPPORTED if it cannot run it,
+ * RMSNORM_ERR_INVALID_ARG for a bad dtype, N <= 0 or M < 0.  No memory is touched.
+ */
+int rmsnorm_queue_plan(int64_t M, int64_t N, int dtype, int* grid, int* shards, int* block_rows,
+                       int* prefetch);
 
 /*
  * The threads_per_row that RMSNORM_VARIANT_AUTO uses for 16-byte aligned rows

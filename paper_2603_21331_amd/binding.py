@@ -30,8 +30,10 @@ RMSNORM_VARIANT_UNALIGNED = 4
 RMSNORM_VARIANT_SUBWAVE = 5
 RMSNORM_VARIANT_STREAM = 6
 RMSNORM_VARIANT_PACKED = 7
+RMSNORM_VARIANT_QUEUE = 8
 
-VARIANT_NAMES = {0: "auto", 1: "wave", 2: "block", 3: "generic", 4: "unaligned", 5: "subwave", 6: "stream", 7: "packed"}
+VARIANT_NAMES = {0: "auto", 1: "wave", 2: "block", 3: "generic", 4: "unaligned", 5: "subwave", 6: "stream", 7: "packed",
+                 8: "queue"}
 
 _lib = None
 
@@ -61,6 +63,15 @@ def load() -> ctypes.CDLL:
     lib.rmsnorm_fwd_variant.restype = i32
     lib.rmsnorm_fwd_tuned.argtypes = [vp, vp, vp, i64, i64, f32, i32, vp, i32]
     lib.rmsnorm_fwd_tuned.restype = i32
+    lib.rmsnorm_fwd_workspace.argtypes = [vp, vp, vp, i64, i64, f32, i32, vp, vp, i64]
+    lib.rmsnorm_fwd_workspace.restype = i32
+    lib.rmsnorm_fwd_queue_tuned.argtypes = [vp, vp, vp, i64, i64, f32, i32, vp, vp, i64, i32, i32, i32, i32]
+    lib.rmsnorm_fwd_queue_tuned.restype = i32
+    lib.rmsnorm_workspace_bytes.argtypes = []
+    lib.rmsnorm_workspace_bytes.restype = i64
+    ip = ctypes.POINTER(ctypes.c_int)
+    lib.rmsnorm_queue_plan.argtypes = [i64, i64, i32, ip, ip, ip, ip]
+    lib.rmsnorm_queue_plan.restype = i32
     lib.rmsnorm_auto_threads_per_row.argtypes = [i64, i32]
     lib.rmsnorm_auto_threads_per_row.restype = i32
     lib.rmsnorm_select_variant.argtypes = [vp, vp, vp, i64, i64, i32]
@@ -153,6 +164,64 @@ def rmsnorm_fwd_tuned(x, w, eps: float, threads_per_row: int, y=None):
                                    stream, int(threads_per_row))
     _check(rc)
     return y
+
+
+def rmsnorm_workspace_bytes() -> int:
+    return int(load().rmsnorm_workspace_bytes())
+
+
+def new_workspace(device):
+    """A zero-filled workspace for rmsnorm_fwd_workspace on `device` (the caller owns it)."""
+    import torch
+    return torch.zeros(rmsnorm_workspace_bytes() // 4, dtype=torch.int32, device=device)
+
+
+def _workspace_args(workspace, x):
+    if not (workspace.is_cuda and workspace.is_contiguous() and workspace.device == x.device):
+        raise ValueError("rmsnorm: the workspace must be a contiguous tensor on the device of x")
+    return workspace.data_ptr(), workspace.numel() * workspace.element_size()
+
+
+def rmsnorm_fwd_workspace(x, w, eps: float, workspace, y=None):
+    """The work-queue kernel on the caller's workspace (see new_workspace); returns y."""
+    import torch
+    lib = load()
+    if y is None:
+        y = torch.empty_like(x)
+    M, N, code, stream = _marshal(x, w, y)
+    wp, wbytes = _workspace_args(workspace, x)
+    with torch.cuda.device(x.device):
+        rc = lib.rmsnorm_fwd_workspace(x.data_ptr(), w.data_ptr(), y.data_ptr(), M, N, eps, code,
+                                       stream, wp, wbytes)
+    _check(rc)
+    return y
+
+
+def rmsnorm_fwd_queue_tuned(x, w, eps: float, workspace, grid: int, shards: int, block_rows: int,
+                            prefetch: bool, y=None):
+    """rmsnorm_fwd_workspace with the launch shape forced."""
+    import torch
+    lib = load()
+    if y is None:
+        y = torch.empty_like(x)
+    M, N, code, stream = _marshal(x, w, y)
+    wp, wbytes = _workspace_args(workspace, x)
+    with torch.cuda.device(x.device):
+        rc = lib.rmsnorm_fwd_queue_tuned(x.data_ptr(), w.data_ptr(), y.data_ptr(), M, N, eps, code,
+                                         stream, wp, wbytes, int(grid), int(shards), int(block_rows),
+                                         1 if prefetch else 0)
+    _check(rc)
+    return y
+
+
+def rmsnorm_queue_plan(M: int, N: int, dtype: int):
+    """(auto_takes_it, grid, shards, block_rows, prefetch) of RMSNORM_VARIANT_QUEUE for M x N on
+    the current device; raises if the variant cannot run such rows."""
+    out = [ctypes.c_int(0) for _ in range(4)]
+    rc = int(load().rmsnorm_queue_plan(int(M), int(N), int(dtype), *[ctypes.byref(o) for o in out]))
+    if rc < 0:
+        _check(rc)
+    return (rc == 1, out[0].value, out[1].value, out[2].value, bool(out[3].value))
 
 
 def rmsnorm_auto_threads_per_row(N: int, dtype: int) -> int:

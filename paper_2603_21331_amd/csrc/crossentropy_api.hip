@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include "launch_util.h"
 #include "crossentropy_kernels.h"
 
 namespace {
@@ -96,7 +97,7 @@ void launch_subwave(const void* x, const int64_t* target, float* loss, float* ls
   int64_t blocks = (M + kRows - 1) / kRows;
   if (blocks > ((int64_t)1 << 24)) blocks = (int64_t)1 << 24;
   const int nvec = (int)(N / rms::Storage<DT>::kVec);
-  hipLaunchKernelGGL((rms::crossentropy_subwave_kernel<DT, L, kBatch, true>), dim3((unsigned)blocks),
+  RMS_LAUNCH((rms::crossentropy_subwave_kernel<DT, L, kBatch, true>), dim3((unsigned)blocks),
                      dim3(kWave), 0, stream, (const rms::u32x4*)x, target, loss, lse, M, N, nvec);
 }
 
@@ -107,7 +108,7 @@ void launch_packed(const void* x, const int64_t* target, float* loss, float* lse
   if (tile_rows > M) tile_rows = (int)M;
   int64_t blocks = (M + tile_rows - 1) / tile_rows;
   if (blocks > kPackedMaxGrid) blocks = kPackedMaxGrid;   // beyond 128 MiB a workgroup takes several tiles
-  hipLaunchKernelGGL((rms::crossentropy_packed_kernel<DT, L, E, true>), dim3((unsigned)blocks),
+  RMS_LAUNCH((rms::crossentropy_packed_kernel<DT, L, E, true>), dim3((unsigned)blocks),
                      dim3(rms::kPackThreads), 0, stream, x, target, loss, lse, M, (int)N, tile_rows);
 }
 
@@ -135,7 +136,7 @@ int run_typed(const void* x, const int64_t* target, float* loss, float* lse, int
     else if (lanes <= 16) launch_packed_lanes<DT, 16>(x, target, loss, lse, M, N, stream);
     else if (lanes <= 32) launch_packed_lanes<DT, 32>(x, target, loss, lse, M, N, stream);
     else launch_packed_lanes<DT, 64>(x, target, loss, lse, M, N, stream);
-    return hipGetLastError() == hipSuccess ? CROSSENTROPY_OK : CROSSENTROPY_ERR_LAUNCH;
+    return rms::host::launch_status() == hipSuccess ? CROSSENTROPY_OK : CROSSENTROPY_ERR_LAUNCH;
   }
   if (threads < kWave) {
     switch (threads) {
@@ -143,12 +144,12 @@ int run_typed(const void* x, const int64_t* target, float* loss, float* lse, int
       case 16: launch_subwave<DT, 16>(x, target, loss, lse, M, N, stream); break;
       default: launch_subwave<DT, 32>(x, target, loss, lse, M, N, stream); break;
     }
-    return hipGetLastError() == hipSuccess ? CROSSENTROPY_OK : CROSSENTROPY_ERR_LAUNCH;
+    return rms::host::launch_status() == hipSuccess ? CROSSENTROPY_OK : CROSSENTROPY_ERR_LAUNCH;
   }
   const int64_t blocks = M < kMaxGrid ? M : kMaxGrid;
-  hipLaunchKernelGGL((rms::crossentropy_row_kernel<DT, kBatch, true>), dim3((unsigned)blocks),
+  RMS_LAUNCH((rms::crossentropy_row_kernel<DT, kBatch, true>), dim3((unsigned)blocks),
                      dim3((unsigned)threads), 0, stream, x, target, loss, lse, M, N);
-  return hipGetLastError() == hipSuccess ? CROSSENTROPY_OK : CROSSENTROPY_ERR_LAUNCH;
+  return rms::host::launch_status() == hipSuccess ? CROSSENTROPY_OK : CROSSENTROPY_ERR_LAUNCH;
 }
 
 int run(const void* x, const int64_t* target, float* loss, float* lse, int64_t M, int64_t N,

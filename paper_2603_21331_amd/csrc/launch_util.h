@@ -4,10 +4,43 @@
 
 #include <hip/hip_runtime.h>
 
+#include <cstddef>
 #include <cstdint>
+#include <tuple>
+#include <utility>
 
 namespace rms {
 namespace host {
+
+// Kernel launch whose status is this launch's own.  hipGetLastError() after a <<<>>> launch
+// also returns, and clears, an error that an earlier and unrelated runtime call of the thread
+// left behind: a healthy launch would be blamed and the caller's pending error lost.
+// hipLaunchKernel returns the status of the launch itself.  The arguments are converted to
+// the kernel's parameter types first, as a <<<>>> launch would convert them.
+template <typename... Params, typename... Args, size_t... I>
+inline hipError_t launch_impl(void (*kernel)(Params...), dim3 grid, dim3 block, size_t lds_bytes,
+                              hipStream_t stream, std::index_sequence<I...>, Args&&... args) {
+  std::tuple<Params...> params{static_cast<Params>(args)...};
+  void* ptrs[] = {static_cast<void*>(&std::get<I>(params))...};
+  return hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, ptrs, lds_bytes, stream);
+}
+
+template <typename... Params, typename... Args>
+inline hipError_t launch(void (*kernel)(Params...), dim3 grid, dim3 block, size_t lds_bytes,
+                         hipStream_t stream, Args&&... args) {
+  static_assert(sizeof...(Params) == sizeof...(Args), "kernel argument count");
+  return launch_impl(kernel, grid, block, lds_bytes, stream, std::index_sequence_for<Params...>{},
+                     std::forward<Args>(args)...);
+}
+
+// Status of the calling thread's most recent RMS_LAUNCH.
+inline hipError_t& launch_status() {
+  static thread_local hipError_t status = hipSuccess;
+  return status;
+}
+
+#define RMS_LAUNCH(kernel, grid, block, lds_bytes, stream, ...) \
+  (::rms::host::launch_status() = ::rms::host::launch(kernel, grid, block, lds_bytes, stream, __VA_ARGS__))
 
 // x and y at the same offset from a 16-byte boundary: then so is every row of theirs.
 inline bool same_skew(const void* x, const void* y) {

@@ -133,12 +133,12 @@ void launch_row(const Args& a) {
     const int per_cu = G != 256 ? 1 : a.nvec <= 384 ? 4 : a.nvec <= 512 ? 3 : 2;
     int64_t grid = (int64_t)compute_units() * per_cu;
     if (grid > a.M) grid = a.M;
-    hipLaunchKernelGGL((rms::layernorm_row_resident_kernel<DT, CHUNKS, G, true>), dim3((unsigned)grid),
+    RMS_LAUNCH((rms::layernorm_row_resident_kernel<DT, CHUNKS, G, true>), dim3((unsigned)grid),
                        dim3(G), 0, a.stream, (const u32x4*)a.x, (const u32x4*)a.w,
                        (const u32x4*)a.b, (u32x4*)a.y, a.M, a.nvec, 1.0f / (float)a.N, a.eps);
     return;
   }
-  hipLaunchKernelGGL((rms::layernorm_row_kernel<DT, CHUNKS, G, true>), dim3((unsigned)blocks),
+  RMS_LAUNCH((rms::layernorm_row_kernel<DT, CHUNKS, G, true>), dim3((unsigned)blocks),
                      dim3(G), 0, a.stream, (const u32x4*)a.x, (const u32x4*)a.w,
                      (const u32x4*)a.b, (u32x4*)a.y, a.M, a.nvec, (float)a.N, a.eps);
 }
@@ -148,7 +148,7 @@ void launch_subwave(const Args& a) {
   constexpr int kRows = rms::kLnWave / L;
   int64_t blocks = (a.M + kRows - 1) / kRows;
   if (blocks > ((int64_t)1 << 24)) blocks = (int64_t)1 << 24;
-  hipLaunchKernelGGL((rms::layernorm_subwave_kernel<DT, CHUNKS, L, true>), dim3((unsigned)blocks),
+  RMS_LAUNCH((rms::layernorm_subwave_kernel<DT, CHUNKS, L, true>), dim3((unsigned)blocks),
                      dim3(rms::kLnWave), 0, a.stream, (const u32x4*)a.x, (const u32x4*)a.w,
                      (const u32x4*)a.b, (u32x4*)a.y, a.M, a.nvec, (float)a.N, a.eps);
 }
@@ -181,14 +181,14 @@ template <int DT, int CHUNKS, int G>
 void launch_row_unaligned(const Args& a, int64_t walk) {
   if constexpr (DT != rms::kFp32 && CHUNKS <= kWalkMaxChunks) {
     if (walk > 0) {
-      hipLaunchKernelGGL((rms::layernorm_row_unaligned_kernel<DT, CHUNKS, G, true, true>),
+      RMS_LAUNCH((rms::layernorm_row_unaligned_kernel<DT, CHUNKS, G, true, true>),
                          dim3((unsigned)walk), dim3(G), 0, a.stream, a.x, a.w, a.b, a.y, a.M,
                          (int)a.N, (float)a.N, a.eps);
       return;
     }
   }
   const int64_t blocks = a.M < kMaxGrid ? a.M : kMaxGrid;
-  hipLaunchKernelGGL((rms::layernorm_row_unaligned_kernel<DT, CHUNKS, G, true, false>),
+  RMS_LAUNCH((rms::layernorm_row_unaligned_kernel<DT, CHUNKS, G, true, false>),
                      dim3((unsigned)blocks), dim3(G), 0, a.stream, a.x, a.w, a.b, a.y, a.M,
                      (int)a.N, (float)a.N, a.eps);
 }
@@ -229,7 +229,7 @@ void launch_packed(const Args& a) {
   if (tile_rows > a.M) tile_rows = (int)a.M;
   int64_t blocks = (a.M + tile_rows - 1) / tile_rows;
   if (blocks > kPackedMaxGrid) blocks = kPackedMaxGrid;
-  hipLaunchKernelGGL((rms::layernorm_packed_kernel<DT, L, E, true>), dim3((unsigned)blocks),
+  RMS_LAUNCH((rms::layernorm_packed_kernel<DT, L, E, true>), dim3((unsigned)blocks),
                      dim3(rms::kPackThreads), 0, a.stream, a.x, a.w, a.b, a.y, a.M, n, tile_rows,
                      (float)a.N, a.eps);
 }
@@ -268,14 +268,14 @@ void launch_stream(const Args& a) {
   const int64_t nfull = a.N / rms::Storage<DT>::kVec;
   int64_t threads = (nfull / rms::kLnStreamBatch + rms::kLnWave - 1) / rms::kLnWave * rms::kLnWave;
   threads = threads < rms::kLnWave ? rms::kLnWave : threads > kMaxThreads ? kMaxThreads : threads;
-  hipLaunchKernelGGL((rms::layernorm_stream_kernel<DT>), dim3((unsigned)blocks), dim3((unsigned)threads),
+  RMS_LAUNCH((rms::layernorm_stream_kernel<DT>), dim3((unsigned)blocks), dim3((unsigned)threads),
                      0, a.stream, a.x, a.w, a.b, a.y, a.M, a.N, (float)a.N, a.eps);
 }
 
 template <int DT>
 void launch_generic(const Args& a) {
   const int64_t blocks = a.M < kMaxGrid ? a.M : kMaxGrid;
-  hipLaunchKernelGGL((rms::layernorm_generic_kernel<DT, kGenericThreads>), dim3((unsigned)blocks),
+  RMS_LAUNCH((rms::layernorm_generic_kernel<DT, kGenericThreads>), dim3((unsigned)blocks),
                      dim3(kGenericThreads), 0, a.stream, a.x, a.w, a.b, a.y, a.M, a.N, (float)a.N,
                      a.eps);
 }
@@ -378,7 +378,7 @@ int run_typed(const Args& a, int threads) {
   else if (threads == -3) dispatch_packed<DT>(a);
   else rc = dispatch<DT>(a, threads);
   if (rc != LAYERNORM_OK) return rc;
-  return hipGetLastError() == hipSuccess ? LAYERNORM_OK : LAYERNORM_ERR_LAUNCH;
+  return rms::host::launch_status() == hipSuccess ? LAYERNORM_OK : LAYERNORM_ERR_LAUNCH;
 }
 
 // variant: a layernorm_variant, or -1 with `threads` forced by the caller.

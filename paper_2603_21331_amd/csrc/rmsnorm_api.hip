@@ -4,8 +4,22 @@
 
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "launch_util.h"
 #include "rmsnorm_kernels.h"
+
+// Counters of the work-queue kernel for callers that bring no workspace: one block of
+// kQueueSlotWords words per stream, all zero between launches (the kernel leaves them zero).
+// In host code this name is only a handle for hipGetSymbolAddress: the device address of each
+// GPU's copy is looked up once per device (queue_scratch below) and only that address is ever
+// passed to a kernel.
+namespace {
+constexpr int kQueueSlotWords = rms::kQueueMaxShards * rms::kQueueStride;   // 4 KiB
+constexpr int kStreamSlots = 32;
+constexpr int kScratchSlots = kStreamSlots;
+}  // namespace
+static __device__ __align__(256) unsigned scratch[kScratchSlots * kQueueSlotWords];
 
 namespace {
 
@@ -168,6 +182,108 @@ int choose(const void* x, const void* w, const void* y, int64_t N, int dtype) {
   return g == 64 ? RMSNORM_VARIANT_WAVE : RMSNORM_VARIANT_BLOCK;
 }
 
+
+// ---------------------------------------------------------------------------
+// The work-queue kernel: when it runs, with what grid, and where its counters live.
+// ---------------------------------------------------------------------------
+constexpr int kQueueThreads = 512;
+constexpr int kQueueMaxChunks = 8;
+constexpr int64_t kQueueMaxRows = (int64_t)1 << 30;          // tickets are 32-bit
+
+struct QueuePlan {
+  int grid;          // resident workgroups, a multiple of `shards`
+  int shards;        // 1 .. kQueueMaxShards
+  int block_shift;   // rows are handed to the shards in blocks of 1 << block_shift
+  bool prefetch;     // next row requested before the stores of the current one
+};
+
+// Rows the kernel can take at all: 16-byte aligned rows of 513 .. 4096 vectors (2 to 8 chunks in
+// 512 threads), fewer than 2^30 of them.
+bool queue_can(int64_t M, int64_t nvec) {
+  return nvec > kQueueThreads && nvec <= (int64_t)kQueueThreads * kQueueMaxChunks && M >= 1 && M < kQueueMaxRows;
+}
+
+// Tuned on MI355X (bf16, sustained runs over rotating buffers):
+//   rows of 16 KiB: two workgroups per compute unit, 16 shards, blocks of 8 rows (128 KiB), no
+//     prefetch: 81.8 us at 16384 rows against 84.7 for one workgroup per row; grids of 1.75 and
+//     2.25 per compute unit are 2 to 4 us slower, blocks of 4 or 16 rows 1 to 1.5 us;
+//   rows of 32 KiB: one workgroup per compute unit with prefetch, 8 shards, blocks of 4 rows:
+//     170 us at 16384 rows against 184.
+// In between the choice follows the bytes a compute unit has in flight (about 32 KiB).
+QueuePlan queue_plan(int64_t M, int64_t row_bytes) {
+  const int cus = compute_units();
+  QueuePlan p;
+  const bool two_per_cu = row_bytes <= 20 * 1024;
+  p.shards = two_per_cu ? 16 : 8;
+  p.prefetch = !two_per_cu;
+  p.grid = (two_per_cu ? 2 * cus : cus) / p.shards * p.shards;
+  if (p.grid < p.shards) p.grid = p.shards;
+  int shift = 0;
+  while (((int64_t)2 << shift) * row_bytes <= 128 * 1024) ++shift;   // largest block of at most 128 KiB
+  p.block_shift = shift;
+  (void)M;
+  return p;
+}
+
+// Whether the automatic path takes the work-queue kernel: it wins once the launch moves a few
+// hundred megabytes (16 KiB rows: level with one workgroup per row at 4096 rows, 1.3 % ahead at
+// 8192, 3.5 % at 16384; 32 KiB rows: level at 4096, 4 % at 8192, 8 % at 16384).
+constexpr int64_t kQueueMinBytes = (int64_t)96 << 20;
+constexpr int64_t kQueueMinRowBytes = 16 * 1024;
+
+bool queue_pays(int64_t M, int64_t nvec) {
+  return queue_can(M, nvec) && nvec * 16 >= kQueueMinRowBytes && M * nvec * 16 >= kQueueMinBytes;
+}
+
+// Device address of this GPU's copy of `scratch`, looked up once per device with that device
+// current; nullptr if the lookup fails.
+unsigned* queue_scratch() {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static unsigned* base[kMaxDevices] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(mu);
+  if (base[dev] == nullptr) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+    base[dev] = static_cast<unsigned*>(p);
+  }
+  return base[dev];
+}
+
+// The counter block of `stream` on the current device for rmsnorm_fwd, nullptr if the call
+// has to do without the work-queue kernel.  Launches on one stream run one after the other, so
+// one block per stream is never shared by two running kernels; a block, once given to a
+// stream, stays with it (streams are few and long-lived; the 33rd gets none).  Two cases get
+// none: the per-thread default stream, whose one handle stands for a different stream in every
+// host thread, and a stream that is being captured into a graph, because a graph can be
+// replayed on any stream, next to anything.
+unsigned* queue_counters_for(hipStream_t stream) {
+  if (stream == hipStreamPerThread) return nullptr;
+  hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(stream, &capture) != hipSuccess) {
+    (void)hipGetLastError();
+    return nullptr;
+  }
+  if (capture != hipStreamCaptureStatusNone) return nullptr;
+  unsigned* base = queue_scratch();
+  if (base == nullptr) return nullptr;
+  constexpr int kMaxDevices = 64;
+  struct Table { hipStream_t owner[kStreamSlots]; int used; };
+  static std::mutex mu;
+  static Table tables[kMaxDevices] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(mu);
+  Table& tb = tables[dev];
+  for (int k = 0; k < tb.used; ++k)
+    if (tb.owner[k] == stream) return base + (size_t)k * kQueueSlotWords;
+  if (tb.used == kStreamSlots) return nullptr;
+  tb.owner[tb.used] = stream;
+  return base + (size_t)(tb.used++) * kQueueSlotWords;
+}
+
 struct Args {
   const void* x;
   const void* w;
@@ -177,6 +293,8 @@ struct Args {
   int nvec;
   float eps;
   hipStream_t stream;
+  unsigned* counters;   // the work-queue kernel's counters for this call (nullptr: none)
+  QueuePlan plan;
 };
 
 template <int DT, int CHUNKS, int G>
@@ -186,14 +304,14 @@ void launch_row(const Args& a) {
   // predicates and loop bookkeeping (256 and 512 threads, where the headline shapes fall).
   if constexpr ((G == 256 || G == 512) && CHUNKS <= 8) {
     if (a.nvec == CHUNKS * G && blocks == a.M) {
-      hipLaunchKernelGGL((rms::rmsnorm_row_kernel<DT, CHUNKS, G, true, true>),
+      RMS_LAUNCH((rms::rmsnorm_row_kernel<DT, CHUNKS, G, true, true>),
                          dim3((unsigned)blocks), dim3(G), 0, a.stream,
                          (const u32x4*)a.x, (const u32x4*)a.w, (u32x4*)a.y, a.M, a.nvec,
                          1.0f / (float)a.N, a.eps);
       return;
     }
   }
-  hipLaunchKernelGGL((rms::rmsnorm_row_kernel<DT, CHUNKS, G, true>),
+  RMS_LAUNCH((rms::rmsnorm_row_kernel<DT, CHUNKS, G, true>),
                      dim3((unsigned)blocks), dim3(G), 0, a.stream,
                      (const u32x4*)a.x, (const u32x4*)a.w, (u32x4*)a.y, a.M, a.nvec,
                      1.0f / (float)a.N, a.eps);
@@ -204,7 +322,7 @@ void launch_subwave(const Args& a) {
   constexpr int kRows = rms::kWave / L;
   int64_t blocks = (a.M + kRows - 1) / kRows;
   if (blocks > ((int64_t)1 << 24)) blocks = (int64_t)1 << 24;
-  hipLaunchKernelGGL((rms::rmsnorm_subwave_kernel<DT, CHUNKS, L, true>),
+  RMS_LAUNCH((rms::rmsnorm_subwave_kernel<DT, CHUNKS, L, true>),
                      dim3((unsigned)blocks), dim3(rms::kWave), 0, a.stream,
                      (const u32x4*)a.x, (const u32x4*)a.w, (u32x4*)a.y, a.M, a.nvec,
                      1.0f / (float)a.N, a.eps);
@@ -236,14 +354,14 @@ template <int DT, int CHUNKS, int G>
 void launch_row_unaligned(const Args& a, int64_t walk) {
   if constexpr (DT != rms::kFp32 && CHUNKS <= (G == kBlockMaxThreads ? kWalkMaxChunks - 1 : kWalkMaxChunks)) {
     if (walk > 0) {
-      hipLaunchKernelGGL((rms::rmsnorm_row_unaligned_kernel<DT, CHUNKS, G, true, true>),
+      RMS_LAUNCH((rms::rmsnorm_row_unaligned_kernel<DT, CHUNKS, G, true, true>),
                          dim3((unsigned)walk), dim3(G), 0, a.stream,
                          a.x, a.w, a.y, a.M, (int)a.N, 1.0f / (float)a.N, a.eps);
       return;
     }
   }
   const int64_t blocks = a.M < kMaxGrid ? a.M : kMaxGrid;
-  hipLaunchKernelGGL((rms::rmsnorm_row_unaligned_kernel<DT, CHUNKS, G, true, false>),
+  RMS_LAUNCH((rms::rmsnorm_row_unaligned_kernel<DT, CHUNKS, G, true, false>),
                      dim3((unsigned)blocks), dim3(G), 0, a.stream,
                      a.x, a.w, a.y, a.M, (int)a.N, 1.0f / (float)a.N, a.eps);
 }
@@ -256,14 +374,14 @@ void launch_stream(const Args& a) {
   const int64_t nfull = a.N / rms::Storage<DT>::kVec;
   int64_t threads = (nfull / rms::kStreamBatch + rms::kWave - 1) / rms::kWave * rms::kWave;
   threads = threads < rms::kWave ? rms::kWave : threads > kBlockMaxThreads ? kBlockMaxThreads : threads;
-  hipLaunchKernelGGL((rms::rmsnorm_stream_kernel<DT>), dim3((unsigned)blocks), dim3((unsigned)threads),
+  RMS_LAUNCH((rms::rmsnorm_stream_kernel<DT>), dim3((unsigned)blocks), dim3((unsigned)threads),
                      0, a.stream, a.x, a.w, a.y, a.M, a.N, 1.0f / (float)a.N, a.eps);
 }
 
 template <int DT>
 void launch_generic(const Args& a) {
   const int64_t blocks = a.M < kMaxGrid ? a.M : kMaxGrid;
-  hipLaunchKernelGGL((rms::rmsnorm_generic_kernel<DT, kGenericThreads>),
+  RMS_LAUNCH((rms::rmsnorm_generic_kernel<DT, kGenericThreads>),
                      dim3((unsigned)blocks), dim3(kGenericThreads), 0, a.stream,
                      a.x, a.w, a.y, a.M, a.N, 1.0f / (float)a.N, a.eps);
 }
@@ -349,7 +467,7 @@ void launch_packed(const Args& a) {
   if (tile_rows > a.M) tile_rows = (int)a.M;
   int64_t blocks = (a.M + tile_rows - 1) / tile_rows;
   if (blocks > kPackedMaxGrid) blocks = kPackedMaxGrid;   // beyond 128 MiB a workgroup takes several tiles
-  hipLaunchKernelGGL((rms::rmsnorm_packed_kernel<DT, L, E, true>), dim3((unsigned)blocks),
+  RMS_LAUNCH((rms::rmsnorm_packed_kernel<DT, L, E, true>), dim3((unsigned)blocks),
                      dim3(rms::kPackThreads), 0, a.stream, a.x, a.w, a.y, a.M, n, tile_rows,
                      1.0f / (float)a.N, a.eps);
 }
@@ -420,32 +538,80 @@ int dispatch_row_unaligned(const Args& a) {
   return RMSNORM_OK;
 }
 
+
+template <int DT, int CHUNKS>
+void launch_queue(const Args& a) {
+  if (a.plan.prefetch)
+    RMS_LAUNCH((rms::rmsnorm_queue_kernel<DT, CHUNKS, kQueueThreads, true>), dim3((unsigned)a.plan.grid),
+               dim3(kQueueThreads), 0, a.stream, (const u32x4*)a.x, (const u32x4*)a.w, (u32x4*)a.y, a.M, a.nvec,
+               1.0f / (float)a.N, a.eps, a.counters, a.plan.shards, a.plan.block_shift);
+  else
+    RMS_LAUNCH((rms::rmsnorm_queue_kernel<DT, CHUNKS, kQueueThreads, false>), dim3((unsigned)a.plan.grid),
+               dim3(kQueueThreads), 0, a.stream, (const u32x4*)a.x, (const u32x4*)a.w, (u32x4*)a.y, a.M, a.nvec,
+               1.0f / (float)a.N, a.eps, a.counters, a.plan.shards, a.plan.block_shift);
+}
+
+// The caller has checked queue_can and that the plan is valid.
+template <int DT>
+int dispatch_queue(const Args& a) {
+  const int chunks = (a.nvec + kQueueThreads - 1) / kQueueThreads;
+#define RMS_L(c) launch_queue<DT, c>(a)
+  switch (chunks) {
+    RMS_CASE(2, RMS_L(2)) RMS_CASE(3, RMS_L(3)) RMS_CASE(4, RMS_L(4)) RMS_CASE(5, RMS_L(5))
+    RMS_CASE(6, RMS_L(6)) RMS_CASE(7, RMS_L(7)) RMS_CASE(8, RMS_L(8))
+    default: return RMSNORM_ERR_UNSUPPORTED;
+  }
+#undef RMS_L
+  return RMSNORM_OK;
+}
+
 // threads == 0 means the element-wise kernel, -1 the element-aligned row kernel, -2 the
-// two-pass streaming kernel, -3 the LDS-staged kernel.
+// two-pass streaming kernel, -3 the LDS-staged kernel, -4 the work-queue kernel.
 template <int DT>
 int run_typed(const Args& a, int threads) {
   int rc = RMSNORM_OK;
+  rms::host::launch_status() = hipSuccess;
   if (threads == 0) launch_generic<DT>(a);
   else if (threads == -1) rc = dispatch_row_unaligned<DT>(a);
   else if (threads == -2) launch_stream<DT>(a);
   else if (threads == -3) dispatch_packed<DT>(a);
+  else if (threads == -4) rc = dispatch_queue<DT>(a);
   else rc = dispatch_row<DT>(a, threads);
   if (rc != RMSNORM_OK) return rc;
-  return hipGetLastError() == hipSuccess ? RMSNORM_OK : RMSNORM_ERR_LAUNCH;
+  return rms::host::launch_status() == hipSuccess ? RMSNORM_OK : RMSNORM_ERR_LAUNCH;
+}
+
+// Whether a plan is one the kernel can run: a grid that is a whole number of shards.
+bool plan_valid(const QueuePlan& p) {
+  return p.shards >= 1 && p.shards <= rms::kQueueMaxShards && p.grid >= p.shards && p.grid % p.shards == 0 &&
+         p.grid <= (1 << 16) && p.block_shift >= 0 && p.block_shift <= 16;
 }
 
 // variant: an rmsnorm_variant, or -1 with `threads` forced by the caller.
+// counters: the work-queue kernel's counters if the caller brings them; nullptr means the block
+// of `stream` in the library's own array (which some streams do not get, see queue_counters_for).
+// forced_plan: nullptr for the tuned plan.
 int run(const void* x, const void* w, void* y, int64_t M, int64_t N, float eps, int dtype,
-        void* stream, int variant, int threads) {
+        void* stream, int variant, int threads, unsigned* counters = nullptr,
+        const QueuePlan* forced_plan = nullptr) {
   int rc = check_args(x, w, y, M, N, eps, dtype);
   if (rc != RMSNORM_OK) return rc;
-  if (variant < -1 || variant > RMSNORM_VARIANT_PACKED) return RMSNORM_ERR_INVALID_ARG;
+  if (variant < -1 || variant > RMSNORM_VARIANT_QUEUE) return RMSNORM_ERR_INVALID_ARG;
   if (variant == -1 && max_chunks_for(threads, dtype) == 0) return RMSNORM_ERR_INVALID_ARG;
+  if (forced_plan && !plan_valid(*forced_plan)) return RMSNORM_ERR_INVALID_ARG;
   if (M == 0) return RMSNORM_OK;
 
   const bool vec_ok = rows_vectorisable(x, w, y, N, dtype);
   const int64_t nvec = vec_ok ? vectors_per_row(N, dtype) : 0;
-  if (variant == RMSNORM_VARIANT_AUTO) variant = choose(x, w, y, N, dtype);
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  if (variant == RMSNORM_VARIANT_AUTO) {
+    variant = choose(x, w, y, N, dtype);
+    // The work-queue kernel where it pays, if this call has counters to run it on.
+    if (variant == RMSNORM_VARIANT_BLOCK && queue_pays(M, nvec)) {
+      if (counters == nullptr) counters = queue_counters_for(hs);
+      if (counters != nullptr) variant = RMSNORM_VARIANT_QUEUE;
+    }
+  }
   switch (variant) {
     case -1:
       if (!(vec_ok && threads_can(threads, nvec, dtype))) return RMSNORM_ERR_UNSUPPORTED;
@@ -475,18 +641,32 @@ int run(const void* x, const void* w, void* y, int64_t M, int64_t N, float eps, 
       if (!packed_can(N)) return RMSNORM_ERR_UNSUPPORTED;
       threads = -3;
       break;
+    case RMSNORM_VARIANT_QUEUE:
+      if (!(vec_ok && queue_can(M, nvec))) return RMSNORM_ERR_UNSUPPORTED;
+      if (counters == nullptr) counters = queue_counters_for(hs);
+      if (counters == nullptr) return RMSNORM_ERR_UNSUPPORTED;   // a stream that gets no counters
+      threads = -4;
+      break;
     default:
       threads = 0;
       break;
   }
 
-  Args a{x, w, y, M, N, (int)nvec, eps, static_cast<hipStream_t>(stream)};
+  Args a{x, w, y, M, N, (int)nvec, eps, hs, counters, QueuePlan{}};
+  if (threads == -4) a.plan = forced_plan ? *forced_plan : queue_plan(M, nvec * 16);
   switch (dtype) {
     case RMSNORM_DTYPE_FP32: return run_typed<rms::kFp32>(a, threads);
     case RMSNORM_DTYPE_FP16: return run_typed<rms::kFp16>(a, threads);
     case RMSNORM_DTYPE_BF16: return run_typed<rms::kBf16>(a, threads);
     default: return RMSNORM_ERR_INVALID_ARG;
   }
+}
+
+// A caller's workspace as the kernel's counters; nullptr if it does not qualify.
+unsigned* workspace_counters(void* workspace, int64_t workspace_bytes) {
+  if (workspace == nullptr || workspace_bytes < (int64_t)kQueueSlotWords * 4) return nullptr;
+  if (reinterpret_cast<uintptr_t>(workspace) & 3u) return nullptr;
+  return static_cast<unsigned*>(workspace);
 }
 
 }  // namespace
@@ -509,6 +689,39 @@ int rmsnorm_fwd_tuned(const void* x, const void* w, void* y, int64_t M, int64_t 
   return run(x, w, y, M, N, eps, dtype, stream, -1, threads_per_row);
 }
 
+int64_t rmsnorm_workspace_bytes(void) { return (int64_t)kQueueSlotWords * 4; }
+
+int rmsnorm_fwd_workspace(const void* x, const void* w, void* y, int64_t M, int64_t N, float eps,
+                          int dtype, void* stream, void* workspace, int64_t workspace_bytes) {
+  unsigned* counters = workspace_counters(workspace, workspace_bytes);
+  if (counters == nullptr) return RMSNORM_ERR_INVALID_ARG;
+  return run(x, w, y, M, N, eps, dtype, stream, RMSNORM_VARIANT_QUEUE, 0, counters);
+}
+
+int rmsnorm_fwd_queue_tuned(const void* x, const void* w, void* y, int64_t M, int64_t N, float eps,
+                            int dtype, void* stream, void* workspace, int64_t workspace_bytes,
+                            int grid, int shards, int block_rows, int prefetch) {
+  unsigned* counters = workspace_counters(workspace, workspace_bytes);
+  if (counters == nullptr) return RMSNORM_ERR_INVALID_ARG;
+  if (block_rows < 1 || (block_rows & (block_rows - 1)) != 0) return RMSNORM_ERR_INVALID_ARG;
+  QueuePlan plan{grid, shards, 0, prefetch != 0};
+  while ((1 << plan.block_shift) < block_rows) ++plan.block_shift;
+  return run(x, w, y, M, N, eps, dtype, stream, RMSNORM_VARIANT_QUEUE, 0, counters, &plan);
+}
+
+int rmsnorm_queue_plan(int64_t M, int64_t N, int dtype, int* grid, int* shards, int* block_rows,
+                       int* prefetch) {
+  const int b = elem_bytes(dtype);
+  if (b == 0 || N <= 0 || M < 0) return RMSNORM_ERR_INVALID_ARG;
+  if ((N * b) % 16 != 0 || !queue_can(M, vectors_per_row(N, dtype))) return RMSNORM_ERR_UNSUPPORTED;
+  const QueuePlan p = queue_plan(M, N * b);
+  if (grid) *grid = p.grid;
+  if (shards) *shards = p.shards;
+  if (block_rows) *block_rows = 1 << p.block_shift;
+  if (prefetch) *prefetch = p.prefetch ? 1 : 0;
+  return queue_pays(M, vectors_per_row(N, dtype)) ? 1 : 0;
+}
+
 int rmsnorm_auto_threads_per_row(int64_t N, int dtype) {
   const int b = elem_bytes(dtype);
   if (b == 0 || N <= 0) return RMSNORM_ERR_INVALID_ARG;
@@ -520,7 +733,9 @@ int rmsnorm_select_variant(const void* x, const void* w, const void* y, int64_t 
                            int dtype) {
   const int rc = check_args(x, w, y, M, N, 0.0f, dtype);
   if (rc != RMSNORM_OK) return rc;
-  return choose(x, w, y, N, dtype);
+  const int variant = choose(x, w, y, N, dtype);
+  if (variant == RMSNORM_VARIANT_BLOCK && queue_pays(M, vectors_per_row(N, dtype))) return RMSNORM_VARIANT_QUEUE;
+  return variant;
 }
 
 int64_t rmsnorm_wave_max_n(int dtype) {
@@ -552,9 +767,9 @@ int rmsnorm_calib_copy(const void* src, void* dst, int64_t bytes, void* stream) 
   const int64_t nvec = bytes / 16;
   int64_t blocks = (nvec + rms::kWave - 1) / rms::kWave;
   if (blocks > (int64_t)1 << 24) blocks = (int64_t)1 << 24;
-  hipLaunchKernelGGL(rms::calib_copy_kernel, dim3((unsigned)blocks), dim3(rms::kWave), 0,
+  RMS_LAUNCH(rms::calib_copy_kernel, dim3((unsigned)blocks), dim3(rms::kWave), 0,
                      static_cast<hipStream_t>(stream), (const u32x4*)src, (u32x4*)dst, nvec);
-  return hipGetLastError() == hipSuccess ? RMSNORM_OK : RMSNORM_ERR_LAUNCH;
+  return rms::host::launch_status() == hipSuccess ? RMSNORM_OK : RMSNORM_ERR_LAUNCH;
 }
 
 const char* rmsnorm_status_string(int status) {

@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include "launch_util.h"
 #include "rowsum_kernels.h"
 
 namespace {
@@ -78,9 +79,9 @@ int check_args(const void* x, const float* y, int64_t M, int64_t N, int dtype) {
 template <int DT>
 int run_block(const void* x, float* y, int64_t M, int64_t N, hipStream_t stream, int threads) {
   const int64_t blocks = M < kMaxGrid ? M : kMaxGrid;
-  hipLaunchKernelGGL((rms::rowsum_row_kernel<DT, kBatch, true>), dim3((unsigned)blocks),
+  RMS_LAUNCH((rms::rowsum_row_kernel<DT, kBatch, true>), dim3((unsigned)blocks),
                      dim3((unsigned)threads), 0, stream, x, y, M, N);
-  return hipGetLastError() == hipSuccess ? ROWSUM_OK : ROWSUM_ERR_LAUNCH;
+  return rms::host::launch_status() == hipSuccess ? ROWSUM_OK : ROWSUM_ERR_LAUNCH;
 }
 
 template <int DT, int L>
@@ -88,9 +89,9 @@ int run_subwave_l(const void* x, float* y, int64_t M, int nvec, hipStream_t stre
   constexpr int kRows = kWave / L;
   int64_t blocks = (M + kRows - 1) / kRows;
   if (blocks > kMaxGrid) blocks = kMaxGrid;
-  hipLaunchKernelGGL((rms::rowsum_subwave_kernel<DT, L, true>), dim3((unsigned)blocks), dim3(kWave),
+  RMS_LAUNCH((rms::rowsum_subwave_kernel<DT, L, true>), dim3((unsigned)blocks), dim3(kWave),
                      0, stream, (const rms::u32x4*)x, y, M, nvec);
-  return hipGetLastError() == hipSuccess ? ROWSUM_OK : ROWSUM_ERR_LAUNCH;
+  return rms::host::launch_status() == hipSuccess ? ROWSUM_OK : ROWSUM_ERR_LAUNCH;
 }
 
 template <int DT, int L, int E>
@@ -99,7 +100,7 @@ void launch_packed(const void* x, float* y, int64_t M, int64_t N, hipStream_t st
   if (tile_rows > M) tile_rows = (int)M;
   int64_t blocks = (M + tile_rows - 1) / tile_rows;
   if (blocks > kPackedMaxGrid) blocks = kPackedMaxGrid;   // beyond 128 MiB a workgroup takes several tiles
-  hipLaunchKernelGGL((rms::rowsum_packed_kernel<DT, L, E, true>), dim3((unsigned)blocks),
+  RMS_LAUNCH((rms::rowsum_packed_kernel<DT, L, E, true>), dim3((unsigned)blocks),
                      dim3(rms::kPackThreads), 0, stream, x, y, M, (int)N, tile_rows);
 }
 
@@ -124,7 +125,7 @@ int run_packed(const void* x, float* y, int64_t M, int64_t N, hipStream_t stream
   else if (lanes <= 16) launch_packed_lanes<DT, 16>(x, y, M, N, stream);
   else if (lanes <= 32) launch_packed_lanes<DT, 32>(x, y, M, N, stream);
   else launch_packed_lanes<DT, 64>(x, y, M, N, stream);
-  return hipGetLastError() == hipSuccess ? ROWSUM_OK : ROWSUM_ERR_LAUNCH;
+  return rms::host::launch_status() == hipSuccess ? ROWSUM_OK : ROWSUM_ERR_LAUNCH;
 }
 
 template <int DT>

@@ -103,7 +103,7 @@ struct Args {
 template <int DT, int CHUNKS, int G>
 void launch_row(const Args& a) {
   const int64_t blocks = a.M < kMaxGrid ? a.M : kMaxGrid;
-  hipLaunchKernelGGL((rms::softmax_row_kernel<DT, CHUNKS, G, true>), dim3((unsigned)blocks),
+  RMS_LAUNCH((rms::softmax_row_kernel<DT, CHUNKS, G, true>), dim3((unsigned)blocks),
                      dim3(G), 0, a.stream, (const u32x4*)a.x, (u32x4*)a.y, a.M, a.nvec);
 }
 
@@ -112,7 +112,7 @@ void launch_subwave(const Args& a) {
   constexpr int kRows = rms::kWaveSize / L;
   int64_t blocks = (a.M + kRows - 1) / kRows;
   if (blocks > ((int64_t)1 << 24)) blocks = (int64_t)1 << 24;
-  hipLaunchKernelGGL((rms::softmax_subwave_kernel<DT, CHUNKS, L, true>), dim3((unsigned)blocks),
+  RMS_LAUNCH((rms::softmax_subwave_kernel<DT, CHUNKS, L, true>), dim3((unsigned)blocks),
                      dim3(rms::kWaveSize), 0, a.stream, (const u32x4*)a.x, (u32x4*)a.y, a.M,
                      a.nvec);
 }
@@ -120,7 +120,7 @@ void launch_subwave(const Args& a) {
 template <int DT, int CHUNKS, int G>
 void launch_row_unaligned(const Args& a) {
   const int64_t blocks = a.M < kMaxGrid ? a.M : kMaxGrid;
-  hipLaunchKernelGGL((rms::softmax_row_unaligned_kernel<DT, CHUNKS, G, true>), dim3((unsigned)blocks),
+  RMS_LAUNCH((rms::softmax_row_unaligned_kernel<DT, CHUNKS, G, true>), dim3((unsigned)blocks),
                      dim3(G), 0, a.stream, a.x, a.y, a.M, (int)a.N,
                      DT != rms::kFp32 ? 1 : 0);
 }
@@ -161,7 +161,7 @@ void launch_packed(const Args& a) {
   if (tile_rows > a.M) tile_rows = (int)a.M;
   int64_t blocks = (a.M + tile_rows - 1) / tile_rows;
   if (blocks > kPackedMaxGrid) blocks = kPackedMaxGrid;
-  hipLaunchKernelGGL((rms::softmax_packed_kernel<DT, L, E, true>), dim3((unsigned)blocks),
+  RMS_LAUNCH((rms::softmax_packed_kernel<DT, L, E, true>), dim3((unsigned)blocks),
                      dim3(rms::kPackThreads), 0, a.stream, a.x, a.y, a.M, n, tile_rows);
 }
 
@@ -199,14 +199,14 @@ void launch_stream(const Args& a) {
   const int64_t nfull = a.N / rms::Storage<DT>::kVec;
   int64_t threads = (nfull / rms::kStreamBatch + rms::kWaveSize - 1) / rms::kWaveSize * rms::kWaveSize;
   threads = threads < rms::kWaveSize ? rms::kWaveSize : threads > kMaxThreads ? kMaxThreads : threads;
-  hipLaunchKernelGGL((rms::softmax_stream_kernel<DT>), dim3((unsigned)blocks), dim3((unsigned)threads),
+  RMS_LAUNCH((rms::softmax_stream_kernel<DT>), dim3((unsigned)blocks), dim3((unsigned)threads),
                      0, a.stream, a.x, a.y, a.M, a.N);
 }
 
 template <int DT>
 void launch_generic(const Args& a) {
   const int64_t blocks = a.M < kMaxGrid ? a.M : kMaxGrid;
-  hipLaunchKernelGGL((rms::softmax_generic_kernel<DT, kGenericThreads>), dim3((unsigned)blocks),
+  RMS_LAUNCH((rms::softmax_generic_kernel<DT, kGenericThreads>), dim3((unsigned)blocks),
                      dim3(kGenericThreads), 0, a.stream, a.x, a.y, a.M, a.N);
 }
 
@@ -305,7 +305,7 @@ int run_typed(const Args& a, int threads) {
   else if (threads == -3) dispatch_packed<DT>(a);
   else rc = dispatch<DT>(a, threads);
   if (rc != SOFTMAX_OK) return rc;
-  return hipGetLastError() == hipSuccess ? SOFTMAX_OK : SOFTMAX_ERR_LAUNCH;
+  return rms::host::launch_status() == hipSuccess ? SOFTMAX_OK : SOFTMAX_ERR_LAUNCH;
 }
 
 // variant: a softmax_variant, or -1 with `threads` forced by the caller.

@@ -18,7 +18,8 @@ GUARD = 64            # guard elements on each side of y (a multiple of 16 bytes
 VARIANTS = (binding.RMSNORM_VARIANT_AUTO, binding.RMSNORM_VARIANT_WAVE,
             binding.RMSNORM_VARIANT_BLOCK, binding.RMSNORM_VARIANT_GENERIC,
             binding.RMSNORM_VARIANT_UNALIGNED, binding.RMSNORM_VARIANT_SUBWAVE,
-            binding.RMSNORM_VARIANT_STREAM, binding.RMSNORM_VARIANT_PACKED)
+            binding.RMSNORM_VARIANT_STREAM, binding.RMSNORM_VARIANT_PACKED,
+            binding.RMSNORM_VARIANT_QUEUE)
 THREADS = (8, 16, 32, 64, 128, 256, 512, 1024)
 # A mode is a variant code (0..3) or ("threads", G): every way the ABI can be told to run.
 ALL_MODES = VARIANTS + tuple(("threads", g) for g in THREADS)

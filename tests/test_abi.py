@@ -240,3 +240,55 @@ def test_unaligned_walk_grid_query():
     assert q(X, W, Y, 8192, 0, 1) == binding.RMSNORM_ERR_INVALID_ARG
     assert q(X, W, Y, 8192, 4097, 7) == binding.RMSNORM_ERR_INVALID_ARG
     assert q(0, W, Y, 8192, 4097, 1) == binding.RMSNORM_ERR_INVALID_ARG
+
+
+def test_queue_plan_and_dispatch_threshold():
+    """The work-queue kernel's launch shape and the sizes at which the automatic path takes it,
+    without a launch (off a GPU machine the library assumes MI355X's 256 compute units)."""
+    bf16, fp32 = binding.RMSNORM_DTYPE_BF16, binding.RMSNORM_DTYPE_FP32
+    takes, grid, shards, block_rows, prefetch = binding.rmsnorm_queue_plan(16384, 8192, bf16)
+    assert takes and (grid, shards, block_rows, prefetch) == (512, 16, 8, False)
+    assert grid % shards == 0
+    takes, grid, shards, block_rows, prefetch = binding.rmsnorm_queue_plan(16384, 16384, bf16)
+    assert takes and (grid, shards, block_rows, prefetch) == (256, 8, 4, True)
+    takes, grid, shards, block_rows, prefetch = binding.rmsnorm_queue_plan(16384, 4096, fp32)
+    assert takes and (grid, shards, block_rows, prefetch) == (512, 16, 8, False)
+    # a block is the largest power of two of rows within 128 KiB
+    assert binding.rmsnorm_queue_plan(100000, 5120, bf16)[3] == 8        # 10 KiB rows
+    assert binding.rmsnorm_queue_plan(100000, 32768, bf16)[3] == 2       # 64 KiB rows
+    # small launches and rows under 16 KiB stay with one workgroup per row
+    assert binding.rmsnorm_queue_plan(4096, 8192, bf16)[0] is False
+    assert binding.rmsnorm_queue_plan(6144, 8192, bf16)[0] is True
+    assert binding.rmsnorm_queue_plan(1 << 20, 4104, bf16)[0] is False
+    lib = binding.load()
+    plan = lib.rmsnorm_queue_plan
+    assert plan(16, 4096, bf16, None, None, None, None) == binding.RMSNORM_ERR_UNSUPPORTED   # 512 vectors
+    assert plan(16, 32776, bf16, None, None, None, None) == binding.RMSNORM_ERR_UNSUPPORTED  # 4097 vectors
+    assert plan(16, 8191, bf16, None, None, None, None) == binding.RMSNORM_ERR_UNSUPPORTED   # not aligned
+    assert plan(1 << 30, 8192, bf16, None, None, None, None) == binding.RMSNORM_ERR_UNSUPPORTED
+    assert plan(16, 8192, 7, None, None, None, None) == binding.RMSNORM_ERR_INVALID_ARG
+    assert plan(-1, 8192, bf16, None, None, None, None) == binding.RMSNORM_ERR_INVALID_ARG
+    sel = lib.rmsnorm_select_variant
+    assert sel(P, P + 65536, P + 131072, 16384, 8192, 2) == binding.RMSNORM_VARIANT_QUEUE
+    assert sel(P, P + 65536, P + 131072, 4096, 8192, 2) == binding.RMSNORM_VARIANT_BLOCK
+    assert sel(P, P + 65536, P + 131072, 16384, 4096, 2) == binding.RMSNORM_VARIANT_BLOCK   # 8 KiB rows
+    assert sel(P, P + 65536, P + 131072 + 2, 16384, 8192, 2) == binding.RMSNORM_VARIANT_UNALIGNED
+
+
+def test_workspace_entry_argument_checks():
+    lib = binding.load()
+    assert binding.rmsnorm_workspace_bytes() == 4096
+    f = lib.rmsnorm_fwd_workspace
+    W = P + (1 << 24)
+    assert f(P, P + 65536, P + 131072, 4, 8192, 1e-6, 2, None, None, 4096) == binding.RMSNORM_ERR_INVALID_ARG
+    assert f(P, P + 65536, P + 131072, 4, 8192, 1e-6, 2, None, W, 4095) == binding.RMSNORM_ERR_INVALID_ARG
+    assert f(P, P + 65536, P + 131072, 4, 8192, 1e-6, 2, None, W + 2, 8192) == binding.RMSNORM_ERR_INVALID_ARG
+    assert f(P, P + 65536, P + 131072, 4, 4096, 1e-6, 2, None, W, 4096) == binding.RMSNORM_ERR_UNSUPPORTED
+    assert f(P, P + 65536, P + 131072, 4, 8191, 1e-6, 2, None, W, 4096) == binding.RMSNORM_ERR_UNSUPPORTED
+    assert f(P, P + 65536, P + 131072, 0, 8192, 1e-6, 2, None, W, 4096) == binding.RMSNORM_OK
+    assert f(None, P + 65536, P + 131072, 4, 8192, 1e-6, 2, None, W, 4096) == binding.RMSNORM_ERR_INVALID_ARG
+    g = lib.rmsnorm_fwd_queue_tuned
+    for grid, shards, block_rows in [(10, 16, 8), (48, 32, 8), (64, 0, 8), (64, 33, 8), (64, 16, 3),
+                                     (64, 16, 0), (0, 1, 1), (1 << 17, 1, 1), (64, 16, 1 << 17)]:
+        assert g(P, P + 65536, P + 131072, 4, 8192, 1e-6, 2, None, W, 4096, grid, shards, block_rows, 0) == \
+            binding.RMSNORM_ERR_INVALID_ARG, (grid, shards, block_rows)
