@@ -8,17 +8,26 @@ resident in HBM before the timed region.  The metric is achieved HBM GB/s by the
 bytes model of the paper's kernel performance table (read x once, write y once,
 plus the weight) and its fraction of the 8 TB/s peak.
 
-Protocol (the paper's Section 7 setup, with HIP events): a settling phase of
-back-to-back launches (the first ~20 ms of work after idle run in a clock
-transient in which kernels take up to 40 % longer), W warm-up launches, then K
-launches in one timed region bracketed by device synchronisation and by a pair
-of events on the launch stream (-> value, ms_per_step, and the kernel's average
-duration for the roofline object: launches on one stream run back to back with
-no gap, which the rocprofv3 trace confirms); then K more launches each
-bracketed by its own event pair (-> the 10 % trimmed mean the paper uses, median
-and minimum; an event pair reads ~1 us longer than the kernel).  Launches rotate
-over several buffer sets whose total size exceeds the 256 MB Infinity Cache, so
-the figure is an HBM figure.
+Protocol: a settling phase of back-to-back launches (the first ~20 ms of work
+after idle run in a clock transient in which kernels take up to 40 % longer; the
+JSON line records how many launches it took as settle_launches), W warm-up
+launches, then two measurements of K launches each.
+  1. One timed region: K launches back to back, bracketed by device
+     synchronisation and by a pair of events on the launch stream.  This is what
+     `value`, `ms_per_step` and `roofline.achieved` / `roofline.frac` are computed
+     from (`config.timing` says "back_to_back_region"): launches on one stream run
+     with no gap between them, and the rocprofv3 kernel trace of the same command
+     gives the same average duration per dispatch.
+  2. The paper's Section 7 protocol: every launch inside its own event pair, the
+     10 % trimmed mean of the K durations (also median and minimum).  An event
+     pair around a single launch reads 1 to 2 us longer than the dispatch itself,
+     so this figure is lower; it is reported next to the first one as
+     `roofline.event_pair_trimmed_mean_us` and `roofline.frac_event_pair`.
+Launches rotate over several buffer sets whose total size exceeds the 256 MB
+Infinity Cache, so the figure is an HBM figure.  `roofline.traffic` is the HBM
+bytes per launch that the hardware counters read in the committed rocprofv3 run
+named by `roofline.traffic_source` (it is not re-measured by this script);
+`roofline.traffic_gbps` is that traffic over this run's time per launch.
 
 Prints ONE JSON line on stdout; progress goes to stderr.
 """
@@ -67,12 +76,12 @@ def trimmed_mean(values, frac=0.10):
     return sum(core) / len(core)
 
 
-def settle(launchers, ms: float) -> None:
+def settle(launchers, ms: float) -> int:
     """Untimed back-to-back launches for about `ms` milliseconds of GPU time: lets the clocks
-    settle after idle before anything is measured."""
+    settle after idle before anything is measured.  Returns how many launches that took."""
     import torch
     if ms <= 0:
-        return
+        return 0
     n = len(launchers)
     a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     done, spent = 0, 0.0
@@ -85,6 +94,7 @@ def settle(launchers, ms: float) -> None:
         spent += a.elapsed_time(b)
         done += 100
     log(f"settled: {done} launches, {spent:.1f} ms")
+    return done
 
 
 def timed_region(launchers, K: int):
@@ -116,16 +126,31 @@ def per_launch_us(launchers, K: int):
     return [a.elapsed_time(b) * 1e3 for a, b in pairs]
 
 
-def roofline_object(nbytes: int, ms_per_step: float, durs_us, traffic=None, **extra):
+def roofline_object(nbytes: int, ms_per_step: float, durs_us, traffic=None, traffic_source=None,
+                    **extra):
+    """The roofline object of the JSON line.  achieved / frac: algorithmic bytes over the time
+    per launch of the back-to-back region; frac_event_pair: the same bytes over the 10 %
+    trimmed mean of the per-launch event pairs; traffic: counter-derived HBM bytes per launch
+    from the committed profile `traffic_source`, traffic_gbps: those bytes over this run's time
+    per launch."""
     achieved = nbytes / (ms_per_step * 1e-3) / 1e9
+    pair_us = trimmed_mean(durs_us)
     obj = {"bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
            "frac": round(achieved / PEAK_HBM_GBPS, 4), "traffic": traffic,
-           "kernel_mean_us": round(ms_per_step * 1e3, 3),
-           "event_pair_trimmed_mean_us": round(trimmed_mean(durs_us), 3),
+           "traffic_source": traffic_source if traffic is not None else None,
+           "traffic_gbps": round(traffic / (ms_per_step * 1e-3) / 1e9, 1) if traffic else None,
+           "region_us_per_launch": round(ms_per_step * 1e3, 3),
+           "event_pair_trimmed_mean_us": round(pair_us, 3),
+           "frac_event_pair": round(nbytes / (pair_us * 1e-6) / 1e9 / PEAK_HBM_GBPS, 4),
            "event_pair_median_us": round(sorted(durs_us)[len(durs_us) // 2], 3),
            "event_pair_min_us": round(min(durs_us), 3)}
     obj.update(extra)
     return obj
+
+
+def traffic_fields(op: str) -> dict:
+    """traffic and traffic_source arguments of roofline_object for `op`."""
+    return {"traffic": read_traffic(op), "traffic_source": "profiles/" + TRAFFIC_FILES[op]}
 
 
 def main() -> int:
@@ -151,8 +176,13 @@ def main() -> int:
                          "crossentropy / rowsum: the same protocol on the next kernels at the paper's "
                          "largest shape for each (fp16 8192 x 8192; fp16 8192 x 4096; fp16 "
                          "8192 x 32000; fp16 8192 x 8192)")
-    ap.add_argument("--paper-shape", type=int, choices=[0, 1], default=0,
-                    help="with --op rowsum: 0 = fp16 8192 x 8192 (default), 1 = fp16 16384 x 4096")
+    ap.add_argument("--paper-shape", type=int, choices=[0, 1], default=None,
+                    help="with --op: which of the kernel's two FP16 rows of the paper's performance "
+                         "table to run.  softmax: 0 = 4096 x 4096, 1 = 8192 x 8192 (default); "
+                         "layernorm: 0 = 4096 x 5120, 1 = 8192 x 4096 (default); crossentropy: "
+                         "0 = 4096 x 32000, 1 = 8192 x 32000 (default); rowsum: 0 = 8192 x 8192 "
+                         "(default), 1 = 16384 x 4096.  The committed traffic summaries are those of "
+                         "the default shapes; for the other shape `traffic` is null")
     ap.add_argument("--attention-len", type=int, default=0,
                     help="with --op softmax: instead of 8192 x 8192, 64 MiB of fp16 attention-score "
                          "rows over this many positions (e.g. 197: rows that are not 16-byte "
@@ -171,7 +201,7 @@ def main() -> int:
 
     import numpy as np
     import torch
-    from paper_2603_21331_amd import binding, inputs
+    from paper_2603_21331_amd import binding, inputs, measure
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
@@ -180,6 +210,7 @@ def main() -> int:
         print("bench.py: librmsnorm_hip.so is not built (run __graft_entry__.build())", file=sys.stderr)
         return 2
     binding.load()
+    measure.load()
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     if args.op == "softmax":
@@ -205,11 +236,17 @@ def main() -> int:
         xs.append(x_host.to(dev).view(torch.bfloat16))
         ys.append(torch.empty((M, N), dtype=torch.bfloat16, device=dev))
     auto_threads = binding.rmsnorm_auto_threads_per_row(N, dtype)
+    variant = binding.VARIANT_NAMES[binding.rmsnorm_select_variant(xs[0], w_dev, ys[0])]
+    plan = None
+    if variant == "queue" and not args.threads_per_row:
+        _, grid, shards, block_rows, prefetch = binding.rmsnorm_queue_plan(M, N, dtype)
+        plan = {"resident_workgroups": grid, "threads_per_workgroup": 512, "shards": shards,
+                "rows_per_block": block_rows, "prefetch": prefetch}
     launchers = [binding.bind_rmsnorm_fwd(xs[i], w_dev, ys[i], eps,
                                           threads_per_row=args.threads_per_row) for i in range(S)]
     torch.cuda.synchronize()
 
-    settle(launchers, args.settle_ms)
+    settled = settle(launchers, args.settle_ms)
     for i in range(W):
         launchers[i % S]()
     torch.cuda.synchronize()
@@ -219,7 +256,7 @@ def main() -> int:
             launchers[i % S]()
         if args.calib_copy:
             for i in range(K):
-                binding.rmsnorm_calib_copy(xs[i % S], ys[i % S])
+                measure.measure_copy(xs[i % S], ys[i % S])
         torch.cuda.synchronize()
         log("profile-only run done")
         return 0
@@ -248,7 +285,7 @@ def main() -> int:
     same_us = trimmed_mean([a.elapsed_time(b) * 1e3 for a, b in pairs1])
 
     # streaming-copy ceiling on the same buffers (2 * M * N * 2 bytes, no weight), same protocol
-    copies = [(lambda i=i: binding.rmsnorm_calib_copy(xs[i], ys[i])) for i in range(S)]
+    copies = [(lambda i=i: measure.measure_copy(xs[i], ys[i])) for i in range(S)]
     for i in range(W):
         copies[i % S]()
     copy_us = timed_region(copies, K) * 1e3
@@ -263,6 +300,7 @@ def main() -> int:
         "n_gpus": 1,
         "steps": K,
         "warmup": W,
+        "settle_launches": settled,
         "ms_per_step": round(ms_per_step, 6),
         "higher_is_better": True,
         "scaling": "weak",
@@ -272,12 +310,15 @@ def main() -> int:
         "config": {
             "workload": f"rmsnorm_fwd bf16 M={M} N={N} eps={eps} (configs[2], headline shape)",
             "storage_dtype": "bf16",
-            "threads_per_row": args.threads_per_row or auto_threads,
+            "timing": "back_to_back_region",
+            "threads_per_row": args.threads_per_row or (512 if plan else auto_threads),
             "dispatch": "forced" if args.threads_per_row else "auto",
+            "kernel": "block" if args.threads_per_row else variant,
+            "queue_plan": plan,
             "buffer_sets": S,
             "bytes_per_step": nbytes,
         },
-        "roofline": roofline_object(nbytes, ms_per_step, durs_us, read_traffic(),
+        "roofline": roofline_object(nbytes, ms_per_step, durs_us, **traffic_fields("rmsnorm"),
                                     same_buffer_trimmed_mean_us=round(same_us, 3),
                                     copy_ceiling_gbps=round(copy_gbps, 1),
                                     copy_mean_us=round(copy_us, 3)),
@@ -331,10 +372,13 @@ def bench_softmax(args, dev) -> int:
     table: 95.9 us, 2800 GB/s on H100), same protocol as the headline benchmark."""
     import numpy as np
     import torch
-    from paper_2603_21331_amd import binding, inputs, softmax
+    from paper_2603_21331_amd import inputs, measure, softmax
 
     softmax.load()
-    n, K, W, S = 8192, args.steps, args.warmup, max(1, args.buffer_sets)
+    measure.load()
+    n, K, W, S = (4096 if args.paper_shape == 0 else 8192), args.steps, args.warmup, max(1, args.buffer_sets)
+    if n == 4096:
+        S = max(S, 8)                          # 8 x 64 MiB: past the Infinity Cache
     t0 = time.time()
     if args.attention_len:
         # attention scores over a context of `cols` positions (odd lengths such as 77, 197, 257:
@@ -353,7 +397,7 @@ def bench_softmax(args, dev) -> int:
     ys = [torch.empty((n, cols), dtype=torch.float16, device=dev) for _ in range(S)]
     fns = [softmax.bind_softmax_fwd(xs[i], ys[i], threads_per_row=args.threads_per_row)
            for i in range(S)]
-    settle(fns, args.settle_ms)
+    settled = settle(fns, args.settle_ms)
     for i in range(W):
         fns[i % S]()
     torch.cuda.synchronize()
@@ -362,27 +406,33 @@ def bench_softmax(args, dev) -> int:
             fns[i % S]()
         if args.calib_copy:
             for i in range(K):
-                binding.rmsnorm_calib_copy(xs[i % S], ys[i % S])
+                measure.measure_copy(xs[i % S], ys[i % S])
         torch.cuda.synchronize()
         log("profile-only run done")
         return 0
     ms_per_step = timed_region(fns, K)
     value = nbytes / (ms_per_step * 1e-3) / 1e9
     durs = per_launch_us(fns, K)
+    traffic = {}                               # summaries exist for 8192 x 8192 and for 197 positions
+    if args.attention_len == 197:
+        traffic = traffic_fields("softmax_attention")
+    elif not args.attention_len and args.paper_shape != 0:
+        traffic = traffic_fields("softmax")
     result = {
         "metric": f"Softmax fwd achieved HBM GB/s and % of MI355X peak (fp16, {n}x{cols})",
         "value": round(value, 1), "unit": "GB/s",
         "pct_of_peak": round(100.0 * value / PEAK_HBM_GBPS, 2),
         "rows_per_s": round(n / (ms_per_step * 1e-3), 1),
-        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(ms_per_step, 6),
+        "n_gpus": 1, "steps": K, "warmup": W, "settle_launches": settled,
+        "ms_per_step": round(ms_per_step, 6),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": f"softmax_fwd fp16 M={n} N={cols}", "storage_dtype": "fp16",
+                   "timing": "back_to_back_region",
                    "threads_per_row": args.threads_per_row
                    or softmax.softmax_auto_threads_per_row(cols, inputs.FP16),
                    "buffer_sets": S, "bytes_per_step": nbytes},
-        "roofline": roofline_object(nbytes, ms_per_step, durs,
-                                    read_traffic("softmax_attention" if args.attention_len else "softmax")),
+        "roofline": roofline_object(nbytes, ms_per_step, durs, **traffic),
     }
     if not args.no_cpu_baseline:
         import oracle
@@ -411,11 +461,13 @@ def bench_layernorm(args, dev) -> int:
     table: 51.9 us, 2586 GB/s on H100), same protocol as the headline benchmark."""
     import numpy as np
     import torch
-    from paper_2603_21331_amd import binding, inputs, layernorm
+    from paper_2603_21331_amd import inputs, layernorm, measure
 
     layernorm.load()
+    measure.load()
     K, W = args.steps, args.warmup
-    case = inputs.layernorm_paper_shape(1)
+    which = 1 if args.paper_shape is None else args.paper_shape
+    case = inputs.layernorm_paper_shape(which)
     M, N, eps = case["M"], case["N"], case["eps"]
     nbytes = inputs.layernorm_bytes(M, N, inputs.FP16)
     S = max(args.buffer_sets, 8)               # 8 x 128 MiB: well past the Infinity Cache
@@ -425,7 +477,7 @@ def bench_layernorm(args, dev) -> int:
     ys = [torch.empty_like(x0) for _ in range(S)]
     fns = [layernorm.bind_layernorm_fwd(xs[i], wd, bd, ys[i], eps,
                                         threads_per_row=args.threads_per_row) for i in range(S)]
-    settle(fns, args.settle_ms)
+    settled = settle(fns, args.settle_ms)
     for i in range(W):
         fns[i % S]()
     torch.cuda.synchronize()
@@ -434,7 +486,7 @@ def bench_layernorm(args, dev) -> int:
             fns[i % S]()
         if args.calib_copy:
             for i in range(K):
-                binding.rmsnorm_calib_copy(xs[i % S], ys[i % S])
+                measure.measure_copy(xs[i % S], ys[i % S])
         torch.cuda.synchronize()
         log("profile-only run done")
         return 0
@@ -442,19 +494,21 @@ def bench_layernorm(args, dev) -> int:
     value = nbytes / (ms_per_step * 1e-3) / 1e9
     durs = per_launch_us(fns, K)
     result = {
-        "metric": "LayerNorm fwd achieved HBM GB/s and % of MI355X peak (fp16, 8192x4096)",
+        "metric": f"LayerNorm fwd achieved HBM GB/s and % of MI355X peak (fp16, {M}x{N})",
         "value": round(value, 1), "unit": "GB/s",
         "pct_of_peak": round(100.0 * value / PEAK_HBM_GBPS, 2),
         "rows_per_s": round(M / (ms_per_step * 1e-3), 1),
-        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(ms_per_step, 6),
+        "n_gpus": 1, "steps": K, "warmup": W, "settle_launches": settled,
+        "ms_per_step": round(ms_per_step, 6),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": f"layernorm_fwd fp16 M={M} N={N} eps={eps} with bias",
-                   "storage_dtype": "fp16",
+                   "storage_dtype": "fp16", "timing": "back_to_back_region",
                    "threads_per_row": args.threads_per_row
                    or layernorm.layernorm_auto_threads_per_row(N, inputs.FP16),
                    "buffer_sets": S, "bytes_per_step": nbytes},
-        "roofline": roofline_object(nbytes, ms_per_step, durs, read_traffic("layernorm")),
+        "roofline": roofline_object(nbytes, ms_per_step, durs,
+                                    **(traffic_fields("layernorm") if which == 1 else {})),
     }
     if not args.no_cpu_baseline:
         import oracle
@@ -487,12 +541,14 @@ def bench_crossentropy(args, dev) -> int:
     performance table: 253.3 us, 2070 GB/s on H100), same protocol as the headline benchmark."""
     import numpy as np
     import torch
-    from paper_2603_21331_amd import binding, crossentropy, inputs
+    from paper_2603_21331_amd import crossentropy, inputs, measure
 
     crossentropy.load()
+    measure.load()
     K, W, S = args.steps, args.warmup, max(1, args.buffer_sets)
     t0 = time.time()
-    case = inputs.crossentropy_paper_shape(1)
+    which = 1 if args.paper_shape is None else args.paper_shape
+    case = inputs.crossentropy_paper_shape(which)
     M, N = case["M"], case["N"]
     log(f"generated {case['name']} in {time.time() - t0:.1f} s")
     nbytes = inputs.crossentropy_bytes(M, N, inputs.FP16)
@@ -502,7 +558,7 @@ def bench_crossentropy(args, dev) -> int:
     losses = [torch.empty(M, dtype=torch.float32, device=dev) for _ in range(S)]
     fns = [crossentropy.bind_crossentropy_fwd(xs[i], td, losses[i], None,
                                               threads_per_row=args.threads_per_row) for i in range(S)]
-    settle(fns, args.settle_ms)
+    settled = settle(fns, args.settle_ms)
     for i in range(W):
         fns[i % S]()
     torch.cuda.synchronize()
@@ -511,7 +567,7 @@ def bench_crossentropy(args, dev) -> int:
             fns[i % S]()
         if args.calib_copy:             # every buffer set holds the same logits: copying one
             for i in range(K):          # onto the next changes nothing
-                binding.rmsnorm_calib_copy(xs[i % S], xs[(i + 1) % S])
+                measure.measure_copy(xs[i % S], xs[(i + 1) % S])
         torch.cuda.synchronize()
         log("profile-only run done")
         return 0
@@ -519,19 +575,21 @@ def bench_crossentropy(args, dev) -> int:
     value = nbytes / (ms_per_step * 1e-3) / 1e9
     durs = per_launch_us(fns, K)
     result = {
-        "metric": "Cross-entropy fwd achieved HBM GB/s and % of MI355X peak (fp16, 8192x32000)",
+        "metric": f"Cross-entropy fwd achieved HBM GB/s and % of MI355X peak (fp16, {M}x{N})",
         "value": round(value, 1), "unit": "GB/s",
         "pct_of_peak": round(100.0 * value / PEAK_HBM_GBPS, 2),
         "rows_per_s": round(M / (ms_per_step * 1e-3), 1),
-        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(ms_per_step, 6),
+        "n_gpus": 1, "steps": K, "warmup": W, "settle_launches": settled,
+        "ms_per_step": round(ms_per_step, 6),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": f"crossentropy_fwd fp16 M={M} N={N}, int64 targets, fp32 loss per row",
-                   "storage_dtype": "fp16",
+                   "storage_dtype": "fp16", "timing": "back_to_back_region",
                    "threads_per_row": args.threads_per_row
                    or crossentropy.crossentropy_auto_threads_per_row(N, inputs.FP16),
                    "buffer_sets": S, "bytes_per_step": nbytes},
-        "roofline": roofline_object(nbytes, ms_per_step, durs, read_traffic("crossentropy")),
+        "roofline": roofline_object(nbytes, ms_per_step, durs,
+                                    **(traffic_fields("crossentropy") if which == 1 else {})),
     }
     if not args.no_cpu_baseline:
         import oracle
@@ -561,11 +619,13 @@ def bench_rowsum(args, dev) -> int:
     protocol as the headline benchmark."""
     import numpy as np
     import torch
-    from paper_2603_21331_amd import binding, inputs, rowsum
+    from paper_2603_21331_amd import inputs, measure, rowsum
 
     rowsum.load()
+    measure.load()
     K, W = args.steps, args.warmup
-    case = inputs.rowsum_paper_shape(args.paper_shape)
+    which = 0 if args.paper_shape is None else args.paper_shape
+    case = inputs.rowsum_paper_shape(which)
     M, N = case["M"], case["N"]
     nbytes = inputs.rowsum_bytes(M, N, inputs.FP16)
     S = max(args.buffer_sets, 8)               # 8 x 128 MiB: well past the Infinity Cache
@@ -574,16 +634,16 @@ def bench_rowsum(args, dev) -> int:
     ys = [torch.empty(M, dtype=torch.float32, device=dev) for _ in range(S)]
     fns = [rowsum.bind_rowsum_fwd(xs[i], ys[i], threads_per_row=args.threads_per_row)
            for i in range(S)]
-    settle(fns, args.settle_ms)
+    settled = settle(fns, args.settle_ms)
     for i in range(W):
         fns[i % S]()
     torch.cuda.synchronize()
     if args.profile_only:
         for i in range(K):
             fns[i % S]()
-        if args.calib_copy:             # every buffer set holds the same logits: copying one
+        if args.calib_copy:             # every buffer set holds the same values: copying one
             for i in range(K):          # onto the next changes nothing
-                binding.rmsnorm_calib_copy(xs[i % S], xs[(i + 1) % S])
+                measure.measure_copy(xs[i % S], xs[(i + 1) % S])
         torch.cuda.synchronize()
         log("profile-only run done")
         return 0
@@ -595,15 +655,17 @@ def bench_rowsum(args, dev) -> int:
         "value": round(value, 1), "unit": "GB/s",
         "pct_of_peak": round(100.0 * value / PEAK_HBM_GBPS, 2),
         "rows_per_s": round(M / (ms_per_step * 1e-3), 1),
-        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(ms_per_step, 6),
+        "n_gpus": 1, "steps": K, "warmup": W, "settle_launches": settled,
+        "ms_per_step": round(ms_per_step, 6),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": f"rowsum_fwd fp16 M={M} N={N}, fp32 sum per row",
-                   "storage_dtype": "fp16",
+                   "storage_dtype": "fp16", "timing": "back_to_back_region",
                    "threads_per_row": args.threads_per_row
                    or rowsum.rowsum_auto_threads_per_row(N, inputs.FP16),
                    "buffer_sets": S, "bytes_per_step": nbytes},
-        "roofline": roofline_object(nbytes, ms_per_step, durs, read_traffic("rowsum")),
+        "roofline": roofline_object(nbytes, ms_per_step, durs,
+                                    **(traffic_fields("rowsum") if which == 0 else {})),
     }
     if not args.no_cpu_baseline:
         import oracle

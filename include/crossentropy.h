@@ -83,6 +83,9 @@ int crossentropy_auto_threads_per_row(int64_t N, int dtype);
 /* Static, human-readable text for a status code. */
 const char* crossentropy_status_string(int status);
 
+/* "RMS_BUILD_ID:" followed by the hash of the sources this library was built from. */
+extern const char crossentropy_build_id[];
+
 #ifdef __cplusplus
 }
 #endif

@@ -104,7 +104,10 @@ int layernorm_fwd_tuned(const void* x, const void* w, const void* b, void* y, in
                         int64_t N, float eps, int dtype, void* stream, int threads_per_row);
 
 /* threads_per_row of the automatic path for 16-byte aligned rows of N elements; 0 if
- * such rows do not fit in registers (they take the streaming kernel); a negative layernorm_status for bad arguments. */
+ * such rows do not fit in registers (they take the streaming kernel); 1 if it sends them
+ * through LDS several rows at a time (LAYERNORM_VARIANT_PACKED: rows of at most 64 bytes, and
+ * short rows that would fill their lane group badly); a negative layernorm_status for bad
+ * arguments. */
 int layernorm_auto_threads_per_row(int64_t N, int dtype);
 
 /*
@@ -124,6 +127,9 @@ int64_t layernorm_register_max_n(int dtype);
 
 /* Static, human-readable text for a status code. */
 const char* layernorm_status_string(int status);
+
+/* "RMS_BUILD_ID:" followed by the hash of the sources this library was built from. */
+extern const char layernorm_build_id[];
 
 #ifdef __cplusplus
 }

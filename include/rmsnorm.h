@@ -200,7 +200,11 @@ int rmsnorm_queue_plan(int64_t M, int64_t N, int dtype, int* grid, int* shards, 
 /*
  * The threads_per_row that RMSNORM_VARIANT_AUTO uses for 16-byte aligned rows
  * of N elements: 0 if such rows do not fit in registers (they take the
- * streaming kernel), a negative rmsnorm_status for a bad dtype or N <= 0.
+ * streaming kernel), 1 if it sends them through LDS several rows at a time
+ * (RMSNORM_VARIANT_PACKED: rows of at most 64 bytes, and short rows that would
+ * fill their lane group badly), a negative rmsnorm_status for a bad dtype or
+ * N <= 0.  Large launches of long rows run RMSNORM_VARIANT_QUEUE with 512
+ * threads per row whatever this returns (see rmsnorm_queue_plan).
  */
 int rmsnorm_auto_threads_per_row(int64_t N, int dtype);
 
@@ -230,17 +234,11 @@ int64_t rmsnorm_wave_max_n(int dtype);
 int64_t rmsnorm_block_max_n(int dtype);
 int64_t rmsnorm_unaligned_max_n(int dtype);
 
-/*
- * Plain device-to-device streaming copy of `bytes` bytes (a multiple of 16,
- * both pointers 16-byte aligned) with the same 128-bit access pattern as the
- * RMSNorm kernels.  A measurement aid: its known traffic calibrates the
- * FETCH_SIZE / WRITE_SIZE hardware counters and gives the practical bandwidth
- * ceiling that the roofline fraction is read against.
- */
-int rmsnorm_calib_copy(const void* src, void* dst, int64_t bytes, void* stream);
-
 /* Static, human-readable text for a status code. */
 const char* rmsnorm_status_string(int status);
+
+/* "RMS_BUILD_ID:" followed by the hash of the sources this library was built from. */
+extern const char rmsnorm_build_id[];
 
 #ifdef __cplusplus
 }

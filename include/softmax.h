@@ -94,7 +94,10 @@ int softmax_fwd_tuned(const void* x, void* y, int64_t M, int64_t N, int dtype, v
                       int threads_per_row);
 
 /* threads_per_row of the automatic path for 16-byte aligned rows of N elements; 0 if
- * such rows do not fit in registers (they take the streaming kernel); a negative softmax_status for bad arguments. */
+ * such rows do not fit in registers (they take the streaming kernel); 1 if it sends them
+ * through LDS several rows at a time (SOFTMAX_VARIANT_PACKED: rows of at most 64 bytes, and
+ * short rows that would fill their lane group badly); a negative softmax_status for bad
+ * arguments. */
 int softmax_auto_threads_per_row(int64_t N, int dtype);
 
 /* Largest N the register-resident kernels accept for `dtype`; 0 for a bad dtype. */
@@ -102,6 +105,9 @@ int64_t softmax_register_max_n(int dtype);
 
 /* Static, human-readable text for a status code. */
 const char* softmax_status_string(int status);
+
+/* "RMS_BUILD_ID:" followed by the hash of the sources this library was built from. */
+extern const char softmax_build_id[];
 
 #ifdef __cplusplus
 }

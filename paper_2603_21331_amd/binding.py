@@ -9,7 +9,6 @@ eager fallback: if the library cannot be loaded, or a call fails, this raises.
 from __future__ import annotations
 
 import ctypes
-import os
 
 from . import build as _build
 
@@ -49,13 +48,11 @@ def library_path() -> str:
 
 
 def load() -> ctypes.CDLL:
-    """Loads librmsnorm_hip.so, building it first only if no built library exists."""
+    """Loads librmsnorm_hip.so (rebuilt first if it is missing or does not match its sources)."""
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(_build.LIB_PATH):
-        _build.build()
-    lib = ctypes.CDLL(_build.LIB_PATH)
+    lib = ctypes.CDLL(_build.ensure("rmsnorm"))
     vp, i64, i32, f32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_float
     lib.rmsnorm_fwd.argtypes = [vp, vp, vp, i64, i64, f32, i32, vp]
     lib.rmsnorm_fwd.restype = i32
@@ -84,8 +81,6 @@ def load() -> ctypes.CDLL:
     lib.rmsnorm_block_max_n.restype = i64
     lib.rmsnorm_unaligned_max_n.argtypes = [i32]
     lib.rmsnorm_unaligned_max_n.restype = i64
-    lib.rmsnorm_calib_copy.argtypes = [vp, vp, i64, vp]
-    lib.rmsnorm_calib_copy.restype = i32
     lib.rmsnorm_status_string.argtypes = [i32]
     lib.rmsnorm_status_string.restype = ctypes.c_char_p
     _lib = lib
@@ -257,19 +252,6 @@ def rmsnorm_block_max_n(dtype: int) -> int:
 
 def rmsnorm_unaligned_max_n(dtype: int) -> int:
     return int(load().rmsnorm_unaligned_max_n(int(dtype)))
-
-
-def rmsnorm_calib_copy(src, dst) -> None:
-    """dst <- src, byte for byte, with the library's streaming copy kernel."""
-    import torch
-    if not (src.is_cuda and dst.is_cuda and src.is_contiguous() and dst.is_contiguous()):
-        raise ValueError("rmsnorm_calib_copy: contiguous device tensors required")
-    nbytes = src.numel() * src.element_size()
-    if nbytes != dst.numel() * dst.element_size():
-        raise ValueError("rmsnorm_calib_copy: size mismatch")
-    stream = torch.cuda.current_stream(src.device).cuda_stream
-    with torch.cuda.device(src.device):
-        _check(load().rmsnorm_calib_copy(src.data_ptr(), dst.data_ptr(), nbytes, stream))
 
 
 def bind_rmsnorm_fwd(x, w, y, eps: float, variant: int = RMSNORM_VARIANT_AUTO,

@@ -1,28 +1,38 @@
-"""Builds the HIP library for gfx950 with hipcc (cross-compiles without a GPU)."""
+"""Builds the HIP libraries for gfx950 with hipcc (cross-compiles without a GPU), and tells a
+built library that no longer matches its sources from one that does.
+
+Every library carries a build id: a hash over the compiler flags and the contents of every file
+it is built from (its .hip source, the csrc headers it includes, its public header).  The id is
+compiled into the library as a string, so it can be read back from the file without loading
+it, and it does not depend on modification times (a copy of the tree to another machine keeps
+it valid).  `ensure(name)` is what the bindings call before loading: a missing or stale library
+is rebuilt if hipcc is there, otherwise the call raises and names the stale file.
+"""
 from __future__ import annotations
 
+import hashlib
 import os
+import re
+import shutil
 import subprocess
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
-LIB_PATH = os.path.join(_HERE, "librmsnorm_hip.so")
-SOFTMAX_LIB_PATH = os.path.join(_HERE, "libsoftmax_hip.so")
+INCLUDE = os.path.join(ROOT, "include")
 
-SOURCES = ["rmsnorm_api.hip"]
-HEADERS = ["rmsnorm_kernels.h", "vec_io.h", "wave_reduce.h", "packed_rows.h", "launch_util.h"]
-LAYERNORM_LIB_PATH = os.path.join(_HERE, "liblayernorm_hip.so")
-LAYERNORM_SOURCES = ["layernorm_api.hip"]
-LAYERNORM_HEADERS = ["layernorm_kernels.h", "vec_io.h", "wave_reduce.h", "packed_rows.h", "launch_util.h"]
-CROSSENTROPY_LIB_PATH = os.path.join(_HERE, "libcrossentropy_hip.so")
-CROSSENTROPY_SOURCES = ["crossentropy_api.hip"]
-CROSSENTROPY_HEADERS = ["crossentropy_kernels.h", "vec_io.h", "wave_reduce.h", "packed_rows.h"]
-ROWSUM_LIB_PATH = os.path.join(_HERE, "librowsum_hip.so")
-ROWSUM_SOURCES = ["rowsum_api.hip"]
-ROWSUM_HEADERS = ["rowsum_kernels.h", "vec_io.h", "wave_reduce.h", "packed_rows.h"]
-SOFTMAX_SOURCES = ["softmax_api.hip"]
-SOFTMAX_HEADERS = ["softmax_kernels.h", "vec_io.h", "wave_reduce.h", "packed_rows.h", "launch_util.h"]
+_COMMON = ["vec_io.h", "wave_reduce.h", "packed_rows.h", "launch_util.h", "build_id.h"]
+
+# name -> (library file, source, csrc headers, public header)
+LIBRARIES = {
+    "rmsnorm": ("librmsnorm_hip.so", "rmsnorm_api.hip", ["rmsnorm_kernels.h"] + _COMMON, "rmsnorm.h"),
+    "softmax": ("libsoftmax_hip.so", "softmax_api.hip", ["softmax_kernels.h"] + _COMMON, "softmax.h"),
+    "layernorm": ("liblayernorm_hip.so", "layernorm_api.hip", ["layernorm_kernels.h"] + _COMMON, "layernorm.h"),
+    "crossentropy": ("libcrossentropy_hip.so", "crossentropy_api.hip",
+                     ["crossentropy_kernels.h"] + _COMMON, "crossentropy.h"),
+    "rowsum": ("librowsum_hip.so", "rowsum_api.hip", ["rowsum_kernels.h"] + _COMMON, "rowsum.h"),
+    "measure": ("libmeasure_hip.so", "measure_api.hip", ["vec_io.h", "launch_util.h", "build_id.h"], "measure.h"),
+}
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC", "-Wall",
@@ -30,17 +40,71 @@ HIPCC_FLAGS = [
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
 ]
 
+BUILD_ID_MARKER = b"RMS_BUILD_ID:"
 
-def hipcc() -> str:
-    for cand in (os.environ.get("HIPCC"), "/opt/rocm/bin/hipcc", "hipcc"):
-        if cand and (os.path.sep not in cand or os.path.exists(cand)):
+
+def lib_path(name: str) -> str:
+    return os.path.join(_HERE, LIBRARIES[name][0])
+
+
+# Paths under their old names (the bindings and the benchmark refer to them).
+LIB_PATH = lib_path("rmsnorm")
+SOFTMAX_LIB_PATH = lib_path("softmax")
+LAYERNORM_LIB_PATH = lib_path("layernorm")
+CROSSENTROPY_LIB_PATH = lib_path("crossentropy")
+ROWSUM_LIB_PATH = lib_path("rowsum")
+MEASURE_LIB_PATH = lib_path("measure")
+
+
+def dependencies(name: str) -> list:
+    """Every file the library is built from, in a fixed order."""
+    _, source, headers, public = LIBRARIES[name]
+    return [os.path.join(CSRC, source)] + [os.path.join(CSRC, h) for h in headers] + \
+        [os.path.join(INCLUDE, public)]
+
+
+def source_id(name: str) -> str:
+    """Hash of the flags and of the contents of the library's dependencies, as they are now."""
+    h = hashlib.sha256()
+    h.update(" ".join(HIPCC_FLAGS).encode())
+    for path in dependencies(name):
+        h.update(b"\0" + os.path.basename(path).encode() + b"\0")
+        with open(path, "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:32]
+
+
+def built_id(name: str):
+    """The build id compiled into the library file, None if there is no file or no id in it."""
+    try:
+        with open(lib_path(name), "rb") as f:
+            blob = f.read()
+    except OSError:
+        return None
+    m = re.search(re.escape(BUILD_ID_MARKER) + rb"([0-9a-f]{32})", blob)
+    return m.group(1).decode() if m else None
+
+
+def is_stale(name: str = "rmsnorm") -> bool:
+    """True if the library is missing or was built from other sources than the present ones."""
+    return built_id(name) != source_id(name)
+
+
+def hipcc():
+    """Path of hipcc, or None if this machine has none."""
+    for cand in (os.environ.get("HIPCC"), "/opt/rocm/bin/hipcc"):
+        if cand and os.path.exists(cand):
             return cand
-    return "hipcc"
+    return shutil.which("hipcc")
 
 
-def _compile(sources, lib_path: str, verbose: bool) -> str:
-    cmd = [hipcc(), *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-o", lib_path,
-           *[os.path.join(CSRC, s) for s in sources]]
+def compile_library(name: str, verbose: bool = False) -> str:
+    cc = hipcc()
+    if cc is None:
+        raise RuntimeError(f"no hipcc on this machine: cannot build {lib_path(name)}")
+    _, source, _, _ = LIBRARIES[name]
+    cmd = [cc, *HIPCC_FLAGS, f'-DRMS_BUILD_ID="{source_id(name)}"', "-I", INCLUDE, "-o", lib_path(name),
+           os.path.join(CSRC, source)]
     if verbose:
         print(" ".join(cmd), flush=True)
     proc = subprocess.run(cmd, capture_output=True, text=True)
@@ -50,43 +114,28 @@ def _compile(sources, lib_path: str, verbose: bool) -> str:
         raise RuntimeError(f"hipcc failed ({proc.returncode}):\n{err}")
     if verbose and err.strip():
         print(err)
-    return lib_path
+    return lib_path(name)
 
 
 def build(verbose: bool = False) -> str:
-    """Compiles csrc/ into librmsnorm_hip.so, libsoftmax_hip.so, liblayernorm_hip.so,
-    libcrossentropy_hip.so and librowsum_hip.so next to this file; returns the path of the
+    """Compiles every library, whether or not a built one is there; returns the path of the
     RMSNorm library."""
-    _compile(ROWSUM_SOURCES, ROWSUM_LIB_PATH, verbose)
-    _compile(SOFTMAX_SOURCES, SOFTMAX_LIB_PATH, verbose)
-    _compile(LAYERNORM_SOURCES, LAYERNORM_LIB_PATH, verbose)
-    _compile(CROSSENTROPY_SOURCES, CROSSENTROPY_LIB_PATH, verbose)
-    return _compile(SOURCES, LIB_PATH, verbose)
+    for name in ("measure", "rowsum", "softmax", "layernorm", "crossentropy"):
+        compile_library(name, verbose)
+    return compile_library("rmsnorm", verbose)
 
 
-def build_softmax(verbose: bool = False) -> str:
-    return _compile(SOFTMAX_SOURCES, SOFTMAX_LIB_PATH, verbose)
-
-
-def build_layernorm(verbose: bool = False) -> str:
-    return _compile(LAYERNORM_SOURCES, LAYERNORM_LIB_PATH, verbose)
-
-
-def is_stale() -> bool:
-    if not os.path.exists(LIB_PATH):
-        return True
-    built = os.path.getmtime(LIB_PATH)
-    deps = [os.path.join(CSRC, f) for f in SOURCES + HEADERS]
-    deps.append(os.path.join(ROOT, "include", "rmsnorm.h"))
-    return any(os.path.getmtime(d) > built for d in deps)
-
-
-def build_crossentropy(verbose: bool = False) -> str:
-    return _compile(CROSSENTROPY_SOURCES, CROSSENTROPY_LIB_PATH, verbose)
-
-
-def build_rowsum(verbose: bool = False) -> str:
-    return _compile(ROWSUM_SOURCES, ROWSUM_LIB_PATH, verbose)
+def ensure(name: str) -> str:
+    """Path of an up-to-date library: builds it if it is missing or stale; on a machine without
+    hipcc a missing or stale library is an error that names the file."""
+    if is_stale(name):
+        path = lib_path(name)
+        if hipcc() is None:
+            state = "is missing" if not os.path.exists(path) else \
+                f"is stale (built from other sources than the present {', '.join(os.path.basename(d) for d in dependencies(name))})"
+            raise RuntimeError(f"{path} {state} and this machine has no hipcc to rebuild it")
+        compile_library(name)
+    return lib_path(name)
 
 
 if __name__ == "__main__":

@@ -34,13 +34,11 @@ def library_path() -> str:
 
 
 def load() -> ctypes.CDLL:
-    """Loads libcrossentropy_hip.so, building it first only if no built library exists."""
+    """Loads libcrossentropy_hip.so (rebuilt first if it is missing or does not match its sources)."""
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(_build.CROSSENTROPY_LIB_PATH):
-        _build.build_crossentropy()
-    lib = ctypes.CDLL(_build.CROSSENTROPY_LIB_PATH)
+    lib = ctypes.CDLL(_build.ensure("crossentropy"))
     vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
     lib.crossentropy_fwd.argtypes = [vp, vp, vp, vp, i64, i64, i32, vp]
     lib.crossentropy_fwd.restype = i32

@@ -4,8 +4,11 @@
 
 #include <hip/hip_runtime.h>
 
+#include "build_id.h"
 #include "launch_util.h"
 #include "layernorm_kernels.h"
+
+RMS_DEFINE_BUILD_ID(layernorm_build_id);
 
 namespace {
 
@@ -466,7 +469,11 @@ int layernorm_auto_threads_per_row(int64_t N, int dtype) {
   const int b = elem_bytes(dtype);
   if (b == 0 || N <= 0) return LAYERNORM_ERR_INVALID_ARG;
   if ((N * b) % 16 != 0) return 0;
-  return pick_threads(N * b / 16, 8, dtype);
+  const int64_t nvec = N * b / 16;
+  const int g = pick_threads(nvec, 8, dtype);
+  // the aligned rows that the automatic path sends through LDS instead (see run)
+  if (nvec <= kPackedAutoVectors || (g > 0 && g < 64 && packed_beats_lanes(nvec, g))) return 1;
+  return g;
 }
 
 int64_t layernorm_unaligned_walk_grid(const void* x, const void* w, const void* b, const void* y,

@@ -6,8 +6,11 @@
 
 #include <mutex>
 
+#include "build_id.h"
 #include "launch_util.h"
 #include "rmsnorm_kernels.h"
+
+RMS_DEFINE_BUILD_ID(rmsnorm_build_id);
 
 // Counters of the work-queue kernel for callers that bring no workspace: one block of
 // kQueueSlotWords words per stream, all zero between launches (the kernel leaves them zero).
@@ -203,36 +206,42 @@ bool queue_can(int64_t M, int64_t nvec) {
   return nvec > kQueueThreads && nvec <= (int64_t)kQueueThreads * kQueueMaxChunks && M >= 1 && M < kQueueMaxRows;
 }
 
-// Tuned on MI355X (bf16, sustained runs over rotating buffers):
+// Tuned on MI355X (bf16, sustained runs over rotating buffers, 256 MiB of x per launch; one
+// workgroup per row in brackets):
 //   rows of 16 KiB: two workgroups per compute unit, 16 shards, blocks of 8 rows (128 KiB), no
-//     prefetch: 81.8 us at 16384 rows against 84.7 for one workgroup per row; grids of 1.75 and
-//     2.25 per compute unit are 2 to 4 us slower, blocks of 4 or 16 rows 1 to 1.5 us;
-//   rows of 32 KiB: one workgroup per compute unit with prefetch, 8 shards, blocks of 4 rows:
-//     170 us at 16384 rows against 184.
-// In between the choice follows the bytes a compute unit has in flight (about 32 KiB).
-QueuePlan queue_plan(int64_t M, int64_t row_bytes) {
+//     prefetch: 81.9 us (84.9); grids of 1.75 and 2.25 per compute unit are 2 to 4 us slower,
+//     blocks of 4 or 16 rows 1 to 1.5 us, 8 shards 2 us;
+//   rows of 20 and 24 KiB: the same with blocks of 4 rows: 85.5 (87.3) and 84.9 (88.6);
+//   rows of 32 KiB: two per compute unit, 8 shards, blocks of 4 rows: 85.7 (90.6);
+//   rows of 40 to 64 KiB: one workgroup per compute unit, which then has to request its next
+//     row before it stores the current one, 8 shards, blocks of 2 rows: 85.7 (85.6), 86.2
+//     (87.6), 86.7 (90.7).
+// Rows of 10 and 12 KiB gain under 1 % and stay with one workgroup per row.
+QueuePlan queue_plan(int64_t row_bytes) {
   const int cus = compute_units();
   QueuePlan p;
-  const bool two_per_cu = row_bytes <= 20 * 1024;
-  p.shards = two_per_cu ? 16 : 8;
+  const bool two_per_cu = row_bytes <= 32 * 1024;
+  p.shards = row_bytes <= 24 * 1024 ? 16 : 8;
   p.prefetch = !two_per_cu;
   p.grid = (two_per_cu ? 2 * cus : cus) / p.shards * p.shards;
   if (p.grid < p.shards) p.grid = p.shards;
   int shift = 0;
   while (((int64_t)2 << shift) * row_bytes <= 128 * 1024) ++shift;   // largest block of at most 128 KiB
   p.block_shift = shift;
-  (void)M;
   return p;
 }
 
 // Whether the automatic path takes the work-queue kernel: it wins once the launch moves a few
-// hundred megabytes (16 KiB rows: level with one workgroup per row at 4096 rows, 1.3 % ahead at
-// 8192, 3.5 % at 16384; 32 KiB rows: level at 4096, 4 % at 8192, 8 % at 16384).
-constexpr int64_t kQueueMinBytes = (int64_t)96 << 20;
+// hundred megabytes (x of 128 MiB: 1 to 3 % ahead of one workgroup per row at rows of 16 to
+// 32 KiB, level or behind at 40 and 48 KiB; x of 256 MiB: 2 to 5 % ahead, level at 40 KiB).
 constexpr int64_t kQueueMinRowBytes = 16 * 1024;
+constexpr int64_t kQueueMinBytes = (int64_t)96 << 20;        // rows up to 32 KiB
+constexpr int64_t kQueueMinBytesLong = (int64_t)192 << 20;   // longer rows
 
 bool queue_pays(int64_t M, int64_t nvec) {
-  return queue_can(M, nvec) && nvec * 16 >= kQueueMinRowBytes && M * nvec * 16 >= kQueueMinBytes;
+  const int64_t row_bytes = nvec * 16;
+  if (!queue_can(M, nvec) || row_bytes < kQueueMinRowBytes) return false;
+  return M * row_bytes >= (row_bytes <= 32 * 1024 ? kQueueMinBytes : kQueueMinBytesLong);
 }
 
 // Device address of this GPU's copy of `scratch`, looked up once per device with that device
@@ -653,7 +662,7 @@ int run(const void* x, const void* w, void* y, int64_t M, int64_t N, float eps, 
   }
 
   Args a{x, w, y, M, N, (int)nvec, eps, hs, counters, QueuePlan{}};
-  if (threads == -4) a.plan = forced_plan ? *forced_plan : queue_plan(M, nvec * 16);
+  if (threads == -4) a.plan = forced_plan ? *forced_plan : queue_plan(nvec * 16);
   switch (dtype) {
     case RMSNORM_DTYPE_FP32: return run_typed<rms::kFp32>(a, threads);
     case RMSNORM_DTYPE_FP16: return run_typed<rms::kFp16>(a, threads);
@@ -714,7 +723,7 @@ int rmsnorm_queue_plan(int64_t M, int64_t N, int dtype, int* grid, int* shards, 
   const int b = elem_bytes(dtype);
   if (b == 0 || N <= 0 || M < 0) return RMSNORM_ERR_INVALID_ARG;
   if ((N * b) % 16 != 0 || !queue_can(M, vectors_per_row(N, dtype))) return RMSNORM_ERR_UNSUPPORTED;
-  const QueuePlan p = queue_plan(M, N * b);
+  const QueuePlan p = queue_plan(N * b);
   if (grid) *grid = p.grid;
   if (shards) *shards = p.shards;
   if (block_rows) *block_rows = 1 << p.block_shift;
@@ -726,7 +735,11 @@ int rmsnorm_auto_threads_per_row(int64_t N, int dtype) {
   const int b = elem_bytes(dtype);
   if (b == 0 || N <= 0) return RMSNORM_ERR_INVALID_ARG;
   if ((N * b) % 16 != 0) return 0;
-  return pick_threads(vectors_per_row(N, dtype), 8, dtype);
+  const int64_t nvec = vectors_per_row(N, dtype);
+  const int g = pick_threads(nvec, 8, dtype);
+  // the aligned rows that the automatic path sends through LDS instead (see choose)
+  if (nvec <= kPackedAutoVectors || (g > 0 && g < 64 && packed_beats_lanes(nvec, g))) return 1;
+  return g;
 }
 
 int rmsnorm_select_variant(const void* x, const void* w, const void* y, int64_t M, int64_t N,
@@ -758,18 +771,6 @@ int64_t rmsnorm_unaligned_walk_grid(const void* x, const void* w, const void* y,
   if (check_args(x, w, y, M, N, 0.0f, dtype) != RMSNORM_OK) return RMSNORM_ERR_INVALID_ARG;
   if (pick_threads_unaligned(full_groups_per_row(N, dtype)) == 0) return 0;
   return unaligned_walk_grid(M, N, dtype);
-}
-
-int rmsnorm_calib_copy(const void* src, void* dst, int64_t bytes, void* stream) {
-  if (bytes < 0 || bytes % 16 != 0) return RMSNORM_ERR_INVALID_ARG;
-  if (bytes == 0) return RMSNORM_OK;
-  if (!src || !dst || !aligned16(src) || !aligned16(dst)) return RMSNORM_ERR_INVALID_ARG;
-  const int64_t nvec = bytes / 16;
-  int64_t blocks = (nvec + rms::kWave - 1) / rms::kWave;
-  if (blocks > (int64_t)1 << 24) blocks = (int64_t)1 << 24;
-  RMS_LAUNCH(rms::calib_copy_kernel, dim3((unsigned)blocks), dim3(rms::kWave), 0,
-                     static_cast<hipStream_t>(stream), (const u32x4*)src, (u32x4*)dst, nvec);
-  return rms::host::launch_status() == hipSuccess ? RMSNORM_OK : RMSNORM_ERR_LAUNCH;
 }
 
 const char* rmsnorm_status_string(int status) {

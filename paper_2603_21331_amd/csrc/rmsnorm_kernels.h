@@ -672,15 +672,4 @@ rmsnorm_generic_kernel(const void* x, const void* __restrict__ w, void* y,
   }
 }
 
-// Streaming copy (measurement aid): one 16-byte vector per thread, one wavefront
-// per workgroup.  Of the copy shapes tried on MI355X this finest one is the
-// fastest, so its rate serves as the practical ceiling for a stream that is half
-// reads and half writes.
-__global__ void __launch_bounds__(kWave)
-calib_copy_kernel(const u32x4* src, u32x4* dst, int64_t nvec) {
-  const int64_t stride = (int64_t)gridDim.x * kWave;
-  for (int64_t i = (int64_t)blockIdx.x * kWave + threadIdx.x; i < nvec; i += stride)
-    store_vec<true>(dst + i, load_vec<true>(src + i));
-}
-
 }  // namespace rms

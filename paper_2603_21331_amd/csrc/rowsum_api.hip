@@ -4,8 +4,11 @@
 
 #include <hip/hip_runtime.h>
 
+#include "build_id.h"
 #include "launch_util.h"
 #include "rowsum_kernels.h"
+
+RMS_DEFINE_BUILD_ID(rowsum_build_id);
 
 namespace {
 

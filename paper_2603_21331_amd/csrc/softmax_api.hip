@@ -4,8 +4,11 @@
 
 #include <hip/hip_runtime.h>
 
+#include "build_id.h"
 #include "launch_util.h"
 #include "softmax_kernels.h"
+
+RMS_DEFINE_BUILD_ID(softmax_build_id);
 
 namespace {
 
@@ -392,7 +395,11 @@ int softmax_auto_threads_per_row(int64_t N, int dtype) {
   const int b = elem_bytes(dtype);
   if (b == 0 || N <= 0) return SOFTMAX_ERR_INVALID_ARG;
   if ((N * b) % 16 != 0) return 0;
-  return pick_threads(N * b / 16, 8);
+  const int64_t nvec = N * b / 16;
+  const int g = pick_threads(nvec, 8);
+  // the aligned rows that the automatic path sends through LDS instead (see run)
+  if (nvec <= kPackedAutoVectors || (g > 0 && g < 64 && packed_beats_lanes(nvec, g))) return 1;
+  return g;
 }
 
 int64_t softmax_register_max_n(int dtype) {

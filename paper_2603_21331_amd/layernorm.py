@@ -46,13 +46,11 @@ def library_path() -> str:
 
 
 def load() -> ctypes.CDLL:
-    """Loads liblayernorm_hip.so, building it first only if no built library exists."""
+    """Loads liblayernorm_hip.so (rebuilt first if it is missing or does not match its sources)."""
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(_build.LAYERNORM_LIB_PATH):
-        _build.build_layernorm()
-    lib = ctypes.CDLL(_build.LAYERNORM_LIB_PATH)
+    lib = ctypes.CDLL(_build.ensure("layernorm"))
     vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
     f32 = ctypes.c_float
     lib.layernorm_fwd.argtypes = [vp, vp, vp, vp, i64, i64, f32, i32, vp]

@@ -33,13 +33,11 @@ def library_path() -> str:
 
 
 def load() -> ctypes.CDLL:
-    """Loads librowsum_hip.so, building it first only if no built library exists."""
+    """Loads librowsum_hip.so (rebuilt first if it is missing or does not match its sources)."""
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(_build.ROWSUM_LIB_PATH):
-        _build.build_rowsum()
-    lib = ctypes.CDLL(_build.ROWSUM_LIB_PATH)
+    lib = ctypes.CDLL(_build.ensure("rowsum"))
     vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
     lib.rowsum_fwd.argtypes = [vp, vp, i64, i64, i32, vp]
     lib.rowsum_fwd.restype = i32

@@ -46,13 +46,11 @@ def library_path() -> str:
 
 
 def load() -> ctypes.CDLL:
-    """Loads libsoftmax_hip.so, building it first only if no built library exists."""
+    """Loads libsoftmax_hip.so (rebuilt first if it is missing or does not match its sources)."""
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(_build.SOFTMAX_LIB_PATH):
-        _build.build_softmax()
-    lib = ctypes.CDLL(_build.SOFTMAX_LIB_PATH)
+    lib = ctypes.CDLL(_build.ensure("softmax"))
     vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
     lib.softmax_fwd.argtypes = [vp, vp, i64, i64, i32, vp]
     lib.softmax_fwd.restype = i32

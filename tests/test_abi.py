@@ -149,7 +149,11 @@ def test_automatic_threads_per_row():
     assert auto(256, bf16) == 32
     assert auto(128, bf16) == 16
     assert auto(64, fp16) == 8
-    assert auto(8, fp16) == 8
+    # aligned rows that the automatic path sends through LDS report 1 (RMSNORM_VARIANT_PACKED):
+    # rows of at most 64 bytes, and 5 vectors on 8 lanes, 9 or 10 on 16
+    assert auto(8, fp16) == 1 and auto(32, bf16) == 1 and auto(16, fp32) == 1 and auto(40, bf16) == 1
+    assert auto(40, fp16) == 1 and auto(72, bf16) == 1 and auto(80, fp16) == 1 and auto(96, fp16) == 16
+    assert auto(48, bf16) == 8 and auto(24, fp32) == 8
     assert auto(128, fp32) == 32
     assert auto(200, bf16) == 32
     assert auto(1024, fp32) == 256 and auto(2048, fp32) == 512 and auto(1020, fp32) == 64
@@ -211,14 +215,6 @@ def test_dispatch_choice_is_visible_without_a_launch():
     assert sel(P, P + 65536, P + 131072, 16, 0, 2) == binding.RMSNORM_ERR_INVALID_ARG
 
 
-def test_calib_copy_argument_checks():
-    lib = binding.load()
-    assert lib.rmsnorm_calib_copy(P, P + 4096, 0, None) == binding.RMSNORM_OK
-    assert lib.rmsnorm_calib_copy(P, P + 4096, 24, None) == binding.RMSNORM_ERR_INVALID_ARG
-    assert lib.rmsnorm_calib_copy(P + 4, P + 4096, 32, None) == binding.RMSNORM_ERR_INVALID_ARG
-    assert lib.rmsnorm_calib_copy(None, P, 32, None) == binding.RMSNORM_ERR_INVALID_ARG
-
-
 def test_unaligned_walk_grid_query():
     """The grid of the walking form: a multiple of the compute units (256 without a device) near
     26 KiB of rows in flight per compute unit, chosen so that the rows divide evenly; 0 where
@@ -250,7 +246,10 @@ def test_queue_plan_and_dispatch_threshold():
     assert takes and (grid, shards, block_rows, prefetch) == (512, 16, 8, False)
     assert grid % shards == 0
     takes, grid, shards, block_rows, prefetch = binding.rmsnorm_queue_plan(16384, 16384, bf16)
-    assert takes and (grid, shards, block_rows, prefetch) == (256, 8, 4, True)
+    assert takes and (grid, shards, block_rows, prefetch) == (512, 8, 4, False)
+    takes, grid, shards, block_rows, prefetch = binding.rmsnorm_queue_plan(16384, 20480, bf16)
+    assert takes and (grid, shards, block_rows, prefetch) == (256, 8, 2, True)
+    assert binding.rmsnorm_queue_plan(3276, 20480, bf16)[0] is False      # 128 MiB of 40 KiB rows
     takes, grid, shards, block_rows, prefetch = binding.rmsnorm_queue_plan(16384, 4096, fp32)
     assert takes and (grid, shards, block_rows, prefetch) == (512, 16, 8, False)
     # a block is the largest power of two of rows within 128 KiB

@@ -29,7 +29,7 @@ def test_more_than_one_gpu_is_refused_with_a_message():
 def test_help_lists_the_driver_flags_and_every_op():
     proc = subprocess.run([sys.executable, BENCH, "--help"], capture_output=True, text=True, cwd=ROOT)
     assert proc.returncode == 0
-    for flag in ("--gpus", "--steps", "--warmup", "--op", "--profile-only", "--calib-copy"):
+    for flag in ("--gpus", "--steps", "--warmup", "--op", "--profile-only", "--calib-copy", "--paper-shape"):
         assert flag in proc.stdout
     for op in ("rmsnorm", "softmax", "layernorm", "crossentropy", "rowsum"):
         assert op in proc.stdout
@@ -39,11 +39,32 @@ def test_trimmed_mean_and_roofline_object():
     b = load_bench()
     assert b.trimmed_mean([1.0] * 8 + [100.0, -100.0]) == 1.0            # 10 % cut from each end
     assert b.trimmed_mean([3.0]) == 3.0
-    obj = b.roofline_object(8_000_000, 0.001, [1.0, 1.2, 1.1], traffic=8_100_000.0, extra_field=1)
+    obj = b.roofline_object(8_000_000, 0.001, [1.0, 1.25, 1.25], traffic=8_100_000.0,
+                            traffic_source="profiles/some_summary.txt", extra_field=1)
     assert obj["bound"] == "hbm" and obj["unit"] == "GB/s" and obj["peak"] == 8000.0
     assert obj["achieved"] == pytest.approx(8000.0) and obj["frac"] == pytest.approx(1.0)
-    assert obj["traffic"] == 8_100_000.0 and obj["kernel_mean_us"] == pytest.approx(1.0)
+    # the back-to-back region's time per launch, under a name that says what it is
+    assert obj["region_us_per_launch"] == pytest.approx(1.0) and "kernel_mean_us" not in obj
+    # the per-launch event-pair protocol beside it: 10 % trimmed mean and the fraction it gives
+    assert obj["event_pair_trimmed_mean_us"] == pytest.approx(3.5 / 3, abs=1e-3)
+    assert obj["frac_event_pair"] == pytest.approx(3 / 3.5, abs=1e-3)
+    # counter-derived traffic, where it came from, and the rate it gives at this run's time
+    assert obj["traffic"] == 8_100_000.0 and obj["traffic_source"] == "profiles/some_summary.txt"
+    assert obj["traffic_gbps"] == pytest.approx(8100.0)
     assert obj["extra_field"] == 1
+    bare = b.roofline_object(8_000_000, 0.001, [1.0])
+    assert bare["traffic"] is None and bare["traffic_source"] is None and bare["traffic_gbps"] is None
+
+
+def test_the_json_line_names_its_timing_protocol_and_its_settling_launches():
+    """Every --op writes config.timing and settle_launches, and no op reaches the measurement
+    copy through the RMSNorm library any more."""
+    text = open(BENCH).read()
+    assert text.count('"timing": "back_to_back_region"') == 5
+    assert text.count('"settle_launches": settled') == 5
+    assert "rmsnorm_calib_copy" not in text and text.count("measure.measure_copy(") == 6
+    b = load_bench()
+    assert b.traffic_fields("rmsnorm")["traffic_source"] == "profiles/" + b.TRAFFIC_FILES["rmsnorm"]
 
 
 def test_every_op_has_a_traffic_summary_that_parses():

@@ -72,6 +72,10 @@ def test_empty_batch_unknown_variant_and_unsupported_shapes():
 
 def test_automatic_threads_per_row():
     auto = softmax.softmax_auto_threads_per_row
+    # aligned rows that the automatic path sends through LDS report 1: rows of at most 64
+    # bytes, and 5 vectors on 8 lanes, 9 or 10 on 16
+    assert auto(8, 1) == 1 and auto(32, 2) == 1 and auto(16, 0) == 1 and auto(40, 2) == 1
+    assert auto(72, 2) == 1 and auto(80, 1) == 1 and auto(96, 1) == 16 and auto(48, 2) == 8
     assert auto(64, 1) == 8 and auto(128, 2) == 16 and auto(256, 1) == 32 and auto(512, 1) == 64
     assert auto(192, 1) == 16 and auto(200, 1) == 32 and auto(384, 2) == 32 and auto(392, 2) == 64
     assert auto(96, 0) == 16 and auto(100, 0) == 32 and auto(192, 0) == 32 and auto(196, 0) == 64
