@@ -18,7 +18,7 @@
  *  - All tensor pointers are DEVICE pointers owned by the caller.  The library
  *    never allocates, frees, copies or synchronises; a call enqueues work on
  *    `stream` and returns at once.  Buffers must stay alive until that work
- *    has run.  (The library holds one static device array of 128 KiB per GPU,
+ *    has run.  (The library holds one static device array of 132 KiB per GPU,
  *    part of its code object: the counters described under rmsnorm_fwd.)
  *  - x and y are M x N, row-major, leading dimension N (no stride argument);
  *    w has N elements.  x, w and y share one storage type `dtype`.
@@ -61,7 +61,9 @@ typedef enum {
   RMSNORM_OK = 0,
   RMSNORM_ERR_INVALID_ARG = -1, /* null pointer, M < 0, N <= 0, bad dtype, eps < 0 or NaN */
   RMSNORM_ERR_UNSUPPORTED = -2, /* the forced variant cannot run this shape or alignment */
-  RMSNORM_ERR_LAUNCH = -3       /* the HIP runtime refused the launch */
+  RMSNORM_ERR_LAUNCH = -3,      /* the HIP runtime refused the launch */
+  RMSNORM_ERR_TOO_LARGE = -4    /* rmsnorm_fwd_static only: more rows, or longer rows, than its fixed
+                                   scratch covers */
 } rmsnorm_status;
 
 typedef enum {
@@ -170,6 +172,28 @@ int rmsnorm_fwd_tuned(const void* x, const void* w, void* y, int64_t M, int64_t 
  */
 int rmsnorm_fwd_workspace(const void* x, const void* w, void* y, int64_t M, int64_t N, float eps,
                           int dtype, void* stream, void* workspace, int64_t workspace_bytes);
+
+/*
+ * rmsnorm_fwd_workspace for callers that cannot allocate device memory at all (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid it) and therefore cannot bring a
+ * workspace: the counters live in one fixed block of 4 KiB inside the library's static device
+ * array (each GPU the library runs on holds its own copy until the process ends; its address is
+ * looked up once per device, on the first call with that device current).  The call allocates
+ * nothing and calls no allocating routine.  Same arguments, kernel, launch shape and result
+ * bits as rmsnorm_fwd_workspace.
+ *   Limits: rows of at most 4096 vectors of 16 bytes (64 KiB) and fewer than 2^30 rows, which
+ *   is what the block and its 32-bit row tickets cover; beyond either, RMSNORM_ERR_TOO_LARGE
+ *   and nothing is launched.  Rows the kernel does not take for other reasons (513 vectors at
+ *   least, 16-byte aligned): RMSNORM_ERR_UNSUPPORTED, as for rmsnorm_fwd_workspace.
+ *   Sharing: every call on a GPU uses that GPU's one block, whatever the stream.  The block
+ *   keeps what the last kernel left in it, which is all zeros once that kernel has finished
+ *   (every launch puts its counters back), so calls need no clearing between them; but two
+ *   calls whose kernels overlap on one GPU (two streams, two host threads, a graph replayed
+ *   beside an eager call) race on the counters and give wrong rows.  Callers that need
+ *   overlap use rmsnorm_fwd_workspace with a workspace per stream, or rmsnorm_fwd.
+ */
+int rmsnorm_fwd_static(const void* x, const void* w, void* y, int64_t M, int64_t N, float eps,
+                       int dtype, void* stream);
 
 /* Bytes of workspace that rmsnorm_fwd_workspace and rmsnorm_fwd_queue_tuned need (4096). */
 int64_t rmsnorm_workspace_bytes(void);

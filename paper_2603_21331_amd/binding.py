@@ -20,6 +20,7 @@ RMSNORM_OK = 0
 RMSNORM_ERR_INVALID_ARG = -1
 RMSNORM_ERR_UNSUPPORTED = -2
 RMSNORM_ERR_LAUNCH = -3
+RMSNORM_ERR_TOO_LARGE = -4
 
 RMSNORM_VARIANT_AUTO = 0
 RMSNORM_VARIANT_WAVE = 1
@@ -62,6 +63,8 @@ def load() -> ctypes.CDLL:
     lib.rmsnorm_fwd_tuned.restype = i32
     lib.rmsnorm_fwd_workspace.argtypes = [vp, vp, vp, i64, i64, f32, i32, vp, vp, i64]
     lib.rmsnorm_fwd_workspace.restype = i32
+    lib.rmsnorm_fwd_static.argtypes = [vp, vp, vp, i64, i64, f32, i32, vp]
+    lib.rmsnorm_fwd_static.restype = i32
     lib.rmsnorm_fwd_queue_tuned.argtypes = [vp, vp, vp, i64, i64, f32, i32, vp, vp, i64, i32, i32, i32, i32]
     lib.rmsnorm_fwd_queue_tuned.restype = i32
     lib.rmsnorm_workspace_bytes.argtypes = []
@@ -188,6 +191,20 @@ def rmsnorm_fwd_workspace(x, w, eps: float, workspace, y=None):
     with torch.cuda.device(x.device):
         rc = lib.rmsnorm_fwd_workspace(x.data_ptr(), w.data_ptr(), y.data_ptr(), M, N, eps, code,
                                        stream, wp, wbytes)
+    _check(rc)
+    return y
+
+
+def rmsnorm_fwd_static(x, w, eps: float, y=None):
+    """The work-queue kernel on the library's own fixed counters (allocates nothing; calls that
+    overlap on one GPU race); returns y."""
+    import torch
+    lib = load()
+    if y is None:
+        y = torch.empty_like(x)
+    M, N, code, stream = _marshal(x, w, y)
+    with torch.cuda.device(x.device):
+        rc = lib.rmsnorm_fwd_static(x.data_ptr(), w.data_ptr(), y.data_ptr(), M, N, eps, code, stream)
     _check(rc)
     return y
 

@@ -12,15 +12,18 @@
 
 RMS_DEFINE_BUILD_ID(rmsnorm_build_id);
 
-// Counters of the work-queue kernel for callers that bring no workspace: one block of
-// kQueueSlotWords words per stream, all zero between launches (the kernel leaves them zero).
+// Counters of the work-queue kernel for callers that bring no workspace: blocks of
+// kQueueSlotWords words, all zero between launches (the kernel leaves them zero).  Blocks
+// 0 .. kStreamSlots - 1 are handed to streams by rmsnorm_fwd; the last block belongs to
+// rmsnorm_fwd_static.  132 KiB per GPU, held until the process ends.
 // In host code this name is only a handle for hipGetSymbolAddress: the device address of each
 // GPU's copy is looked up once per device (queue_scratch below) and only that address is ever
 // passed to a kernel.
 namespace {
 constexpr int kQueueSlotWords = rms::kQueueMaxShards * rms::kQueueStride;   // 4 KiB
 constexpr int kStreamSlots = 32;
-constexpr int kScratchSlots = kStreamSlots;
+constexpr int kStaticSlot = kStreamSlots;
+constexpr int kScratchSlots = kStreamSlots + 1;
 }  // namespace
 static __device__ __align__(256) unsigned scratch[kScratchSlots * kQueueSlotWords];
 
@@ -707,6 +710,20 @@ int rmsnorm_fwd_workspace(const void* x, const void* w, void* y, int64_t M, int6
   return run(x, w, y, M, N, eps, dtype, stream, RMSNORM_VARIANT_QUEUE, 0, counters);
 }
 
+int rmsnorm_fwd_static(const void* x, const void* w, void* y, int64_t M, int64_t N, float eps,
+                       int dtype, void* stream) {
+  int rc = check_args(x, w, y, M, N, eps, dtype);
+  if (rc != RMSNORM_OK) return rc;
+  // beyond what the fixed scratch and its 32-bit tickets cover
+  if (M >= kQueueMaxRows || N * elem_bytes(dtype) > (int64_t)kQueueThreads * kQueueMaxChunks * 16)
+    return RMSNORM_ERR_TOO_LARGE;
+  if (M == 0) return RMSNORM_OK;
+  unsigned* base = queue_scratch();
+  if (base == nullptr) return RMSNORM_ERR_LAUNCH;
+  return run(x, w, y, M, N, eps, dtype, stream, RMSNORM_VARIANT_QUEUE, 0,
+             base + (size_t)kStaticSlot * kQueueSlotWords);
+}
+
 int rmsnorm_fwd_queue_tuned(const void* x, const void* w, void* y, int64_t M, int64_t N, float eps,
                             int dtype, void* stream, void* workspace, int64_t workspace_bytes,
                             int grid, int shards, int block_rows, int prefetch) {
@@ -779,6 +796,7 @@ const char* rmsnorm_status_string(int status) {
     case RMSNORM_ERR_INVALID_ARG: return "invalid argument";
     case RMSNORM_ERR_UNSUPPORTED: return "variant does not support this shape or alignment";
     case RMSNORM_ERR_LAUNCH: return "kernel launch failed";
+    case RMSNORM_ERR_TOO_LARGE: return "larger than the fixed scratch of this entry point covers";
     default: return "unknown status";
   }
 }
