@@ -233,6 +233,15 @@ int rmsnorm_queue_plan(int64_t M, int64_t N, int dtype, int* grid, int* shards, 
 int rmsnorm_auto_threads_per_row(int64_t N, int dtype);
 
 /*
+ * The same for a batch of M rows: batches of one to three rounds of resident workgroups at the
+ * usual thread count run with narrower workgroups (256 or 128 threads) if the whole batch then
+ * fits on the GPU at once; every other M gives what rmsnorm_auto_threads_per_row gives.  (The
+ * tier-1 axis of the paper's playbook, Section 3.3, chosen per launch instead of per kernel.)
+ * Uses the compute-unit count of the current device (256 if there is none).
+ */
+int rmsnorm_auto_threads_for_batch(int64_t M, int64_t N, int dtype);
+
+/*
  * Which kernel RMSNORM_VARIANT_AUTO would pick for this call (an
  * rmsnorm_variant), without launching anything; a negative rmsnorm_status for
  * arguments rmsnorm_fwd would reject.  Only pointer alignment is inspected.

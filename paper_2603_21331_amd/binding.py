@@ -74,6 +74,8 @@ def load() -> ctypes.CDLL:
     lib.rmsnorm_queue_plan.restype = i32
     lib.rmsnorm_auto_threads_per_row.argtypes = [i64, i32]
     lib.rmsnorm_auto_threads_per_row.restype = i32
+    lib.rmsnorm_auto_threads_for_batch.argtypes = [i64, i64, i32]
+    lib.rmsnorm_auto_threads_for_batch.restype = i32
     lib.rmsnorm_select_variant.argtypes = [vp, vp, vp, i64, i64, i32]
     lib.rmsnorm_select_variant.restype = i32
     lib.rmsnorm_unaligned_walk_grid.argtypes = [vp, vp, vp, i64, i64, i32]
@@ -238,6 +240,13 @@ def rmsnorm_queue_plan(M: int, N: int, dtype: int):
 
 def rmsnorm_auto_threads_per_row(N: int, dtype: int) -> int:
     rc = int(load().rmsnorm_auto_threads_per_row(int(N), int(dtype)))
+    if rc < 0:
+        _check(rc)
+    return rc
+
+
+def rmsnorm_auto_threads_for_batch(M: int, N: int, dtype: int) -> int:
+    rc = int(load().rmsnorm_auto_threads_for_batch(int(M), int(N), int(dtype)))
     if rc < 0:
         _check(rc)
     return rc

@@ -291,3 +291,29 @@ def test_workspace_entry_argument_checks():
                                      (64, 16, 0), (0, 1, 1), (1 << 17, 1, 1), (64, 16, 1 << 17)]:
         assert g(P, P + 65536, P + 131072, 4, 8192, 1e-6, 2, None, W, 4096, grid, shards, block_rows, 0) == \
             binding.RMSNORM_ERR_INVALID_ARG, (grid, shards, block_rows)
+
+
+def test_thread_count_follows_the_batch_size():
+    """Batches of one to three rounds of resident workgroups run with narrower workgroups when
+    the whole batch then fits on the GPU at once (256 compute units assumed off a GPU machine: a
+    round is 1024 workgroups of 512 threads, 2048 of 256, 4096 of 128)."""
+    f = binding.rmsnorm_auto_threads_for_batch
+    bf16, fp16, fp32 = binding.RMSNORM_DTYPE_BF16, binding.RMSNORM_DTYPE_FP16, binding.RMSNORM_DTYPE_FP32
+    # N = 8192 in a 16-bit type: 1024 vectors, 512 threads by default
+    assert [f(M, 8192, bf16) for M in (1, 1024, 1025, 1536, 2048, 2049, 3072, 3073, 16384)] == \
+        [512, 512, 256, 256, 256, 512, 512, 512, 512]                      # 128 threads would need 8 chunks
+    # N = 4096: 512 vectors
+    assert [f(M, 4096, fp16) for M in (1024, 1025, 2048, 2049, 3072, 3073, 4096)] == \
+        [512, 256, 256, 128, 128, 512, 512]
+    # N = 2048: 256 vectors, 256 threads by default, a round of 2048
+    assert [f(M, 2048, bf16) for M in (2048, 2049, 4096, 4097, 6144, 6145)] == [256, 128, 128, 256, 256, 256]
+    assert f(1536, 4096, fp32) == 256 and f(3000, 2048, fp32) == 128
+    # rows that need more than 4 chunks in the narrower workgroup keep the default
+    assert f(3000, 5120, bf16) == 256 and f(1200, 32768, bf16) == 1024
+    # rows of one wavefront or less, and the special return codes, pass through
+    for N in (512, 128, 40, 8, 1023, 131080):
+        assert f(5000, N, bf16) == binding.rmsnorm_auto_threads_per_row(N, bf16)
+    with pytest.raises(binding.RmsnormError):
+        f(-1, 8192, bf16)
+    with pytest.raises(binding.RmsnormError):
+        f(16, 0, bf16)
