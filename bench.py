@@ -126,18 +126,30 @@ def per_launch_us(launchers, K: int):
     return [a.elapsed_time(b) * 1e3 for a, b in pairs]
 
 
-def copy_ceiling(srcs, dsts, K: int, W: int) -> dict:
+def copy_ceiling(srcs, dsts, K: int, W: int, staged: bool = False) -> dict:
     """The measurement library's streaming copy over the same buffers with the same protocol
     (W warm-up launches, K back to back in one event pair): what a stream that is half reads
-    and half writes reaches at this launch size, launch and ramp-up included."""
+    and half writes reaches at this launch size, launch and ramp-up included.  With `staged`
+    also the copy that goes through LDS tiles in workgroups of 256 threads, the ceiling of the
+    kernels that stage short rows that way."""
     from paper_2603_21331_amd import measure
+    import torch
     n = len(srcs)
-    copies = [(lambda i=i: measure.measure_copy(srcs[i], dsts[i])) for i in range(n)]
-    for i in range(W):
-        copies[i % n]()
-    us = timed_region(copies, K) * 1e3
-    nbytes = 2 * srcs[0].numel() * srcs[0].element_size()
-    return {"copy_mean_us": round(us, 3), "copy_ceiling_gbps": round(nbytes / (us * 1e-6) / 1e9, 1)}
+    # the copies move whole 16-byte vectors: at most 15 bytes of a buffer are left out
+    whole = srcs[0].numel() * srcs[0].element_size() // 16 * 16
+    srcs = [t.view(-1).view(torch.uint8)[:whole] for t in srcs]
+    dsts = [t.view(-1).view(torch.uint8)[:whole] for t in dsts]
+    nbytes = 2 * whole
+    out = {}
+    entries = [("copy", measure.measure_copy)] + ([("staged_copy", measure.measure_staged_copy)] if staged else [])
+    for name, entry in entries:
+        copies = [(lambda i=i: entry(srcs[i], dsts[i])) for i in range(n)]
+        for i in range(W):
+            copies[i % n]()
+        us = timed_region(copies, K) * 1e3
+        out[f"{name}_mean_us"] = round(us, 3)
+        out[f"{name}_ceiling_gbps"] = round(nbytes / (us * 1e-6) / 1e9, 1)
+    return out
 
 
 def roofline_object(nbytes: int, ms_per_step: float, durs_us, traffic=None, traffic_source=None,
@@ -177,6 +189,9 @@ def main() -> int:
     ap.add_argument("--threads-per-row", type=int, default=0,
                     help="force the block size through rmsnorm_fwd_tuned (0 = automatic dispatch)")
     ap.add_argument("--rows", type=int, default=16384, help="M (the headline workload is 16384)")
+    ap.add_argument("--cols", type=int, default=8192,
+                    help="N (the headline workload is 8192; other values run the same bf16 recipe at "
+                         "that row length, e.g. 197 for rows that are not 16-byte aligned)")
     ap.add_argument("--settle-ms", type=float, default=60.0,
                     help="untimed back-to-back launches for this many milliseconds before the "
                          "warm-up, so that the clock transient after idle is over (0 = none)")
@@ -198,9 +213,9 @@ def main() -> int:
                          "(default), 1 = 16384 x 4096.  The committed traffic summaries are those of "
                          "the default shapes; for the other shape `traffic` is null")
     ap.add_argument("--attention-len", type=int, default=0,
-                    help="with --op softmax: instead of 8192 x 8192, 64 MiB of fp16 attention-score "
-                         "rows over this many positions (e.g. 197: rows that are not 16-byte "
-                         "aligned, several per workgroup through LDS)")
+                    help="with --op softmax or layernorm: instead of the paper's shape, 64 MiB of "
+                         "fp16 rows of this many elements (e.g. the 197 positions of an attention "
+                         "row: not 16-byte aligned, several rows per workgroup through LDS)")
     ap.add_argument("--profile-only", action="store_true",
                     help="warm-up plus --steps launches and nothing else (for rocprofv3 runs)")
     ap.add_argument("--calib-copy", action="store_true",
@@ -238,7 +253,10 @@ def main() -> int:
 
     M, K, W, S = args.rows, args.steps, args.warmup, max(1, args.buffer_sets)
     t0 = time.time()
-    case = inputs.config3(M=M)
+    if args.cols == 8192:
+        case = inputs.config3(M=M)
+    else:                                       # the same recipe (streams 48 / 49) at another row length
+        case = inputs.random_case(0, 48, M, args.cols, inputs.BF16, 1e-5)
     N, eps, dtype = case["N"], case["eps"], case["dtype"]
     log(f"generated {case['name']} in {time.time() - t0:.1f} s")
     nbytes = inputs.algorithmic_bytes(M, N, dtype)
@@ -246,6 +264,8 @@ def main() -> int:
     x_host = torch.from_numpy(case["x"].view(np.int16))
     w_dev = torch.from_numpy(case["w"].view(np.int16)).to(dev).view(torch.bfloat16)
     xs, ys = [], []
+    if args.cols != 8192 and 2 * M * N * 2 < (256 << 20):
+        S = max(S, min(32, (1 << 30) // (2 * M * N * 2)))       # at least 1 GiB of buffers in rotation
     for _ in range(S):
         xs.append(x_host.to(dev).view(torch.bfloat16))
         ys.append(torch.empty((M, N), dtype=torch.bfloat16, device=dev))
@@ -299,10 +319,10 @@ def main() -> int:
     same_us = trimmed_mean([a.elapsed_time(b) * 1e3 for a, b in pairs1])
 
     # streaming-copy ceiling on the same buffers (2 * M * N * 2 bytes, no weight), same protocol
-    ceiling = copy_ceiling(xs, ys, K, W)
+    ceiling = copy_ceiling(xs, ys, K, W, staged=N * 2 < 2048)
 
     result = {
-        "metric": "RMSNorm fwd achieved HBM GB/s and % of MI355X peak (bf16, 16384x8192)",
+        "metric": f"RMSNorm fwd achieved HBM GB/s and % of MI355X peak (bf16, {M}x{N})",
         "value": round(value, 1),
         "unit": "GB/s",
         "pct_of_peak": round(100.0 * value / PEAK_HBM_GBPS, 2),
@@ -318,7 +338,8 @@ def main() -> int:
         "dtype": "f32",
         "data": "synthetic",
         "config": {
-            "workload": f"rmsnorm_fwd bf16 M={M} N={N} eps={eps} (configs[2], headline shape)",
+            "workload": f"rmsnorm_fwd bf16 M={M} N={N} eps={eps}" +
+                        (" (configs[2], headline shape)" if (M, N) == (16384, 8192) else ""),
             "storage_dtype": "bf16",
             "timing": "back_to_back_region",
             "threads_per_row": args.threads_per_row or (512 if plan else auto_threads),
@@ -328,7 +349,8 @@ def main() -> int:
             "buffer_sets": S,
             "bytes_per_step": nbytes,
         },
-        "roofline": roofline_object(nbytes, ms_per_step, durs_us, **traffic_fields("rmsnorm"),
+        "roofline": roofline_object(nbytes, ms_per_step, durs_us,
+                                    **(traffic_fields("rmsnorm") if (M, N) == (16384, 8192) else {}),
                                     same_buffer_trimmed_mean_us=round(same_us, 3), **ceiling),
     }
 
@@ -443,7 +465,7 @@ def bench_softmax(args, dev) -> int:
         "roofline": roofline_object(nbytes, ms_per_step, durs, **traffic),
     }
     y_keep = ys[0].clone()
-    result["roofline"].update(copy_ceiling(xs, ys, K, W))
+    result["roofline"].update(copy_ceiling(xs, ys, K, W, staged=bool(args.attention_len)))
     ys[0].copy_(y_keep)
     if not args.no_cpu_baseline:
         import oracle
@@ -478,7 +500,14 @@ def bench_layernorm(args, dev) -> int:
     measure.load()
     K, W = args.steps, args.warmup
     which = 1 if args.paper_shape is None else args.paper_shape
-    case = inputs.layernorm_paper_shape(which)
+    if args.attention_len:
+        # 64 MiB of short rows (e.g. 197 elements: not 16-byte aligned, several per workgroup
+        # through LDS), a whole number of 16-byte vectors in total for the copy beside it
+        which = -1
+        cols = args.attention_len
+        case = inputs.layernorm_case(0, 130, (64 << 20) // (2 * cols) // 8 * 8, cols, inputs.FP16)
+    else:
+        case = inputs.layernorm_paper_shape(which)
     M, N, eps = case["M"], case["N"], case["eps"]
     nbytes = inputs.layernorm_bytes(M, N, inputs.FP16)
     S = max(args.buffer_sets, 8)               # 8 x 128 MiB: well past the Infinity Cache
@@ -522,7 +551,7 @@ def bench_layernorm(args, dev) -> int:
                                     **(traffic_fields("layernorm") if which == 1 else {})),
     }
     y_keep = ys[0].clone()
-    result["roofline"].update(copy_ceiling(xs, ys, K, W))
+    result["roofline"].update(copy_ceiling(xs, ys, K, W, staged=bool(args.attention_len)))
     ys[0].copy_(y_keep)
     if not args.no_cpu_baseline:
         import oracle

@@ -32,6 +32,15 @@ typedef enum {
  */
 int measure_copy(const void* src, void* dst, int64_t bytes, void* stream);
 
+/*
+ * The same copy through LDS, the way the kernels for short rows stage their data: workgroups of
+ * 256 threads load a tile of 8 KiB, write it to LDS, meet at a barrier, read it back and store
+ * it.  Same arguments, traffic and behaviour as measure_copy (a last tile that is not full is
+ * handled).  Its rate is the ceiling for a kernel that stages whole tiles through LDS; what
+ * such a kernel loses beyond it goes to its arithmetic and to rows that do not fill vectors.
+ */
+int measure_staged_copy(const void* src, void* dst, int64_t bytes, void* stream);
+
 /* Static, human-readable text for a status code. */
 const char* measure_status_string(int status);
 

@@ -107,10 +107,11 @@ void launch_subwave(const void* x, const int64_t* target, float* loss, float* ls
 template <int DT, int L, int E>
 void launch_packed(const void* x, const int64_t* target, float* loss, float* lse, int64_t M,
                    int64_t N, hipStream_t stream) {
-  int tile_rows = rms::kPackTileBytes / ((int)N * rms::Storage<DT>::kBytes);
-  if (tile_rows > M) tile_rows = (int)M;
-  int64_t blocks = (M + tile_rows - 1) / tile_rows;
-  if (blocks > kPackedMaxGrid) blocks = kPackedMaxGrid;   // beyond 128 MiB a workgroup takes several tiles
+  const rms::host::PackedShape shape = rms::host::packed_shape(M, N * rms::Storage<DT>::kBytes, L, rms::kPackThreads,
+                                                               rms::kPackTileBytes,
+                                                               rms::host::kPackedTargetReadOnly, kPackedMaxGrid);
+  const int tile_rows = shape.tile_rows;
+  const int64_t blocks = shape.blocks;
   RMS_LAUNCH((rms::crossentropy_packed_kernel<DT, L, E, true>), dim3((unsigned)blocks),
                      dim3(rms::kPackThreads), 0, stream, x, target, loss, lse, M, (int)N, tile_rows);
 }

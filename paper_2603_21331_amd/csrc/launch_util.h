@@ -47,6 +47,53 @@ inline bool same_skew(const void* x, const void* y) {
   return ((reinterpret_cast<uintptr_t>(x) ^ reinterpret_cast<uintptr_t>(y)) & 15u) == 0;
 }
 
+// Launch shape of the LDS-staged short-row kernels (packed_rows.h): rows per tile and
+// workgroups.  A workgroup of `threads` threads works on threads / lanes rows at a time (one
+// pass), so a tile is a whole number of passes wherever more than one pass fits: 41 rows of 197
+// fp16 elements in passes of 16 leave a sixth of the third pass idle.  Among the whole numbers
+// the one nearest to `target_bytes` is taken.  Kernels that write the tile back want small
+// tiles (kPackedTargetReadWrite): then a launch is several workgroup generations whose load,
+// compute and store phases overlap, where two generations of 16 KiB tiles run in lockstep
+// (fp16 softmax over 64 MiB: 197 elements per row 26.0 -> 24.4 us, 77 elements 27.9 -> 25.0,
+// 257 elements 26.5 -> 25.1).  Kernels that only read (row sum, cross-entropy) have no store
+// phase to overlap and want as many bytes in flight as the tile holds (kPackedTargetReadOnly;
+// row sum over 64 MiB of fp16 rows of 100 to 1001 elements: 11.9 to 12.4 us against 13.3 to 15.0
+// with the small tiles).
+constexpr int64_t kPackedTargetReadWrite = 7 * 1024;
+constexpr int64_t kPackedTargetReadOnly = 16 * 1024;
+
+struct PackedShape {
+  int tile_rows;
+  int64_t blocks;
+};
+
+inline PackedShape packed_shape(int64_t M, int64_t row_bytes, int lanes, int threads, int tile_bytes,
+                                int64_t target_bytes, int64_t max_blocks) {
+  const int groups = threads / lanes;
+  const int64_t fit = tile_bytes / row_bytes;              // rows the tile can hold (at least 1)
+  int64_t rows = fit;
+  if (fit > groups) {
+    const int64_t pass_bytes = groups * row_bytes;
+    int64_t passes = (target_bytes + pass_bytes / 2) / pass_bytes;
+    if (passes < 1) passes = 1;
+    rows = passes * groups;
+    if (rows > fit) rows = fit / groups * groups;
+  }
+  if (rows > M) rows = M;
+  if (rows < 1) rows = 1;
+  PackedShape s;
+  s.tile_rows = (int)rows;
+  s.blocks = (M + rows - 1) / rows;
+  if (s.blocks > max_blocks) {
+    // A workgroup takes several tiles then: as many workgroups as share them out evenly (10646
+    // tiles over 2048 workgroups are six rounds, the last of them a fifth full; over 1775 all
+    // six are full).
+    const int64_t rounds = (s.blocks + max_blocks - 1) / max_blocks;
+    s.blocks = (s.blocks + rounds - 1) / rounds;
+  }
+  return s;
+}
+
 // Compute units of the current device (256 on MI355X), looked up once per device.
 inline int compute_units() {
   constexpr int kMaxDevices = 64;

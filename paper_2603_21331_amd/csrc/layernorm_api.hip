@@ -197,11 +197,13 @@ void launch_row_unaligned(const Args& a, int64_t walk) {
 }
 
 // The LDS-staged kernel for short rows that are not 16-byte aligned: the narrowest lane group
-// that holds the row (16 elements per lane), as many whole rows per step as fit the tile, at
-// most 8192 workgroups (beyond 128 MiB a workgroup takes several tiles).  Its tile mirrors the
-// offset of x from a 16-byte boundary; where y sits at another, the stores are element-aligned.
+// that holds the row (16 elements per lane), whole passes of the workgroup's lane groups per
+// tile, at most 4096 workgroups (beyond that a workgroup takes several tiles and pays for its
+// slices of weight and bias once; 64 MiB of 77-, 197- and 257-element fp16 rows: 26.5 to 27.0 us
+// at 4096 workgroups, 28.5 to 32.4 with a workgroup per tile).  Its tile mirrors the offset of
+// x from a 16-byte boundary; where y sits at another, the stores are element-aligned.
 constexpr int64_t kPackedMaxN = 64 * rms::kPackElems;
-constexpr int64_t kPackedMaxGrid = 8192;
+constexpr int64_t kPackedMaxGrid = 4096;
 // Aligned rows of at most 64 bytes also take it: one to four of the eight lanes of the
 // narrowest lane group would hold a vector, and the LDS-staged kernel is 1.2 to 2 times faster.
 constexpr int64_t kPackedAutoVectors = 4;
@@ -228,10 +230,11 @@ bool only_stores_unaligned(const void* x, const void* w, const void* b, int64_t 
 template <int DT, int L, int E>
 void launch_packed(const Args& a) {
   const int n = (int)a.N;
-  int tile_rows = rms::kPackTileBytes / (n * rms::Storage<DT>::kBytes);
-  if (tile_rows > a.M) tile_rows = (int)a.M;
-  int64_t blocks = (a.M + tile_rows - 1) / tile_rows;
-  if (blocks > kPackedMaxGrid) blocks = kPackedMaxGrid;
+  const rms::host::PackedShape shape = rms::host::packed_shape(a.M, (int64_t)n * rms::Storage<DT>::kBytes, L,
+                                                               rms::kPackThreads, rms::kPackTileBytes,
+                                                               rms::host::kPackedTargetReadWrite, kPackedMaxGrid);
+  const int tile_rows = shape.tile_rows;
+  const int64_t blocks = shape.blocks;
   RMS_LAUNCH((rms::layernorm_packed_kernel<DT, L, E, true>), dim3((unsigned)blocks),
                      dim3(rms::kPackThreads), 0, a.stream, a.x, a.w, a.b, a.y, a.M, n, tile_rows,
                      (float)a.N, a.eps);

@@ -384,7 +384,7 @@ layernorm_row_resident_kernel(const u32x4* x, const u32x4* __restrict__ w,
 // Short rows that are not 16-byte aligned, several per workgroup, staged through LDS (see
 // packed_rows.h): L lanes per row, E elements per lane with (E - 1) * L < N <= E * L (so only a
 // lane's last element can lie past the end of its row), `tile_rows` rows (at most 16 KiB) per
-// step.  A lane keeps its slices of weight and bias in registers for the whole launch.  The same two
+// step.  A lane keeps its slices of weight and bias in registers for all the tiles of its workgroup.  The same two
 // passes over registers as the other kernels: shift by the row's first element, sum, centre,
 // sum of squares.  Lane groups without a row repeat the last one and write nothing back.
 template <int DT, int L, int E, bool NT>
@@ -402,21 +402,53 @@ layernorm_packed_kernel(const void* x, const void* w, const void* b, void* y, in
   // square root through the hardware instruction plus a Newton step, as in the resident kernel.
   const float inv_n = 1.0f / n;
 
-  float wf[E], bf[E];
-#pragma unroll
-  for (int i = 0; i < E; ++i) {
-    const int j = sub + i * L;
-    wf[i] = j < N ? S::load_one(w, j) : 0.f;
-    bf[i] = (j < N && has_bias) ? S::load_one(b, j) : 0.f;
-  }
+  // Weight and bias go through LDS as well (see param_request).
+  __shared__ u32x4 wl[param_lds_vecs<DT>()];
+  __shared__ u32x4 bl[param_lds_vecs<DT>()];
+  ParamRegs wregs, bregs;
+  param_request<DT>(w, N, t, wregs);
+  if (has_bias) param_request<DT>(b, N, t, bregs);
 
-  for (int64_t r0 = (int64_t)blockIdx.x * tile_rows; r0 < M; r0 += (int64_t)gridDim.x * tile_rows) {
-    const int rows = (int)(M - r0 < tile_rows ? M - r0 : tile_rows);
-    const char* src = static_cast<const char*>(x) + r0 * N * S::kBytes;
-    const TileCut cut = tile_cut(src, rows * N * S::kBytes);
+  // The run of a tile is requested one tile ahead (see tile_request).
+  const int64_t stride = (int64_t)gridDim.x * tile_rows;
+  auto run_of = [&](int64_t r0, int& rows, const char*& src) {
+    rows = (int)(M - r0 < tile_rows ? M - r0 : tile_rows);
+    src = static_cast<const char*>(x) + r0 * N * S::kBytes;
+    return tile_cut(src, rows * N * S::kBytes);
+  };
+  TileRegs<DT> regs;
+  int next_rows = 0;
+  const char* src = nullptr;
+  TileCut next_cut = {};
+  int64_t r0 = (int64_t)blockIdx.x * tile_rows;
+  if (r0 < M) {
+    next_cut = run_of(r0, next_rows, src);
+    tile_request<DT, NT>(src, next_cut, t, regs);
+  }
+  param_commit<DT>(wl, N, t, wregs);
+  if (has_bias) param_commit<DT>(bl, N, t, bregs);
+  float wf[E], bf[E];
+  bool have_params = false;
+  for (; r0 < M; r0 += stride) {
+    const TileCut cut = next_cut;
+    const int rows = next_rows;
     const int origin = cut.skew / S::kBytes;               // tile element of the run's first element
-    tile_fill<DT, NT>(src, tile, cut, t);
+    tile_commit<DT>(tile, cut, t, regs);
     __syncthreads();
+    if (r0 + stride < M) {
+      next_cut = run_of(r0 + stride, next_rows, src);
+      tile_request<DT, NT>(src, next_cut, t, regs);
+    }
+    if (!have_params) {                                    // after the first tile's barrier
+      param_slice<DT, L, E>(wl, N, sub, wf);
+      if (has_bias) {
+        param_slice<DT, L, E>(bl, N, sub, bf);
+      } else {
+#pragma unroll
+        for (int i = 0; i < E; ++i) bf[i] = 0.f;
+      }
+      have_params = true;
+    }
     for (int first = 0; first < rows; first += GROUPS) {   // the same trip count for every thread
       const int r = first + group;
       const int at = origin + (r < rows ? r : rows - 1) * N;

@@ -176,6 +176,9 @@ constexpr int64_t kStreamMaxN = (int64_t)1 << 31;   // the streaming kernel coun
 // it for such rows when they are not 16-byte aligned, and for aligned rows of at most four
 // vectors.
 constexpr int64_t kPackedMaxN = 64 * rms::kPackElems;
+// Workgroups at most: beyond that a workgroup takes several tiles and pays for its weight slice
+// once (64 MiB of 77-, 197- and 257-element bf16 rows: 25.5 us at 1024, 24.2 to 24.8 at 8192,
+// 24.5 to 26.6 with a workgroup per tile).
 constexpr int64_t kPackedMaxGrid = 8192;
 constexpr int64_t kPackedAutoVectors = 4;
 
@@ -501,10 +504,11 @@ int dispatch_row(const Args& a, int threads) {
 template <int DT, int L, int E>
 void launch_packed(const Args& a) {
   const int n = (int)a.N;
-  int tile_rows = rms::kPackTileBytes / (n * rms::Storage<DT>::kBytes);
-  if (tile_rows > a.M) tile_rows = (int)a.M;
-  int64_t blocks = (a.M + tile_rows - 1) / tile_rows;
-  if (blocks > kPackedMaxGrid) blocks = kPackedMaxGrid;   // beyond 128 MiB a workgroup takes several tiles
+  const rms::host::PackedShape shape = rms::host::packed_shape(a.M, (int64_t)n * rms::Storage<DT>::kBytes, L,
+                                                               rms::kPackThreads, rms::kPackTileBytes,
+                                                               rms::host::kPackedTargetReadWrite, kPackedMaxGrid);
+  const int tile_rows = shape.tile_rows;
+  const int64_t blocks = shape.blocks;
   RMS_LAUNCH((rms::rmsnorm_packed_kernel<DT, L, E, true>), dim3((unsigned)blocks),
                      dim3(rms::kPackThreads), 0, a.stream, a.x, a.w, a.y, a.M, n, tile_rows,
                      1.0f / (float)a.N, a.eps);

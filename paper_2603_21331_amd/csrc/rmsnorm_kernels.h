@@ -325,7 +325,8 @@ rmsnorm_queue_kernel(const u32x4* x, const u32x4* __restrict__ w, u32x4* y, int6
 // Short rows that are not 16-byte aligned, several per workgroup, staged through LDS (see
 // packed_rows.h): L lanes per row, E elements per lane with (E - 1) * L < N <= E * L (so only
 // a lane's last element can lie past the end of its row), `tile_rows` rows (at most 16 KiB) per
-// step.  A lane keeps its slice of the weight in registers for the whole launch.  Lane groups without a row repeat the last one and write nothing back.
+// step.  A lane keeps its slice of the weight in registers for all the tiles of its workgroup.
+// Lane groups without a row repeat the last one and write nothing back.
 // ---------------------------------------------------------------------------
 template <int DT, int L, int E, bool NT>
 __global__ void __launch_bounds__(kPackThreads)
@@ -338,20 +339,44 @@ rmsnorm_packed_kernel(const void* x, const void* w, void* y, int64_t M, int N, i
   const int sub = t % L;
   const int group = t / L;
 
-  float wf[E];
-#pragma unroll
-  for (int i = 0; i < E; ++i) {
-    const int j = sub + i * L;
-    wf[i] = j < N ? S::load_one(w, j) : 0.f;
-  }
+  // The weight goes through LDS as well (see param_request).
+  __shared__ u32x4 wl[param_lds_vecs<DT>()];
+  ParamRegs wregs;
+  param_request<DT>(w, N, t, wregs);
 
-  for (int64_t r0 = (int64_t)blockIdx.x * tile_rows; r0 < M; r0 += (int64_t)gridDim.x * tile_rows) {
-    const int rows = (int)(M - r0 < tile_rows ? M - r0 : tile_rows);
-    const char* src = static_cast<const char*>(x) + r0 * N * S::kBytes;
-    const TileCut cut = tile_cut(src, rows * N * S::kBytes);
+  // The run of a tile is requested one tile ahead (see tile_request).
+  const int64_t stride = (int64_t)gridDim.x * tile_rows;
+  auto run_of = [&](int64_t r0, int& rows, const char*& src) {
+    rows = (int)(M - r0 < tile_rows ? M - r0 : tile_rows);
+    src = static_cast<const char*>(x) + r0 * N * S::kBytes;
+    return tile_cut(src, rows * N * S::kBytes);
+  };
+  TileRegs<DT> regs;
+  int next_rows = 0;
+  const char* src = nullptr;
+  TileCut next_cut = {};
+  int64_t r0 = (int64_t)blockIdx.x * tile_rows;
+  if (r0 < M) {
+    next_cut = run_of(r0, next_rows, src);
+    tile_request<DT, NT>(src, next_cut, t, regs);
+  }
+  param_commit<DT>(wl, N, t, wregs);
+  float wf[E];
+  bool have_w = false;
+  for (; r0 < M; r0 += stride) {
+    const TileCut cut = next_cut;
+    const int rows = next_rows;
     const int origin = cut.skew / S::kBytes;               // tile element of the run's first element
-    tile_fill<DT, NT>(src, tile, cut, t);
+    tile_commit<DT>(tile, cut, t, regs);
     __syncthreads();
+    if (r0 + stride < M) {
+      next_cut = run_of(r0 + stride, next_rows, src);
+      tile_request<DT, NT>(src, next_cut, t, regs);
+    }
+    if (!have_w) {                                         // after the first tile's barrier
+      param_slice<DT, L, E>(wl, N, sub, wf);
+      have_w = true;
+    }
     for (int first = 0; first < rows; first += GROUPS) {   // the same trip count for every thread
       const int r = first + group;
       const int at = origin + (r < rows ? r : rows - 1) * N;

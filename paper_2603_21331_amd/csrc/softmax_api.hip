@@ -129,11 +129,14 @@ void launch_row_unaligned(const Args& a) {
 }
 
 // The LDS-staged kernel for short rows that are not 16-byte aligned: the narrowest lane group
-// that holds the row (16 elements per lane), as many whole rows per step as fit the tile, at
-// most 8192 workgroups (beyond 128 MiB a workgroup takes several tiles).  Its tile mirrors the
-// offset of x from a 16-byte boundary; where y sits at another, the stores are element-aligned.
+// that holds the row (16 elements per lane), whole passes of the workgroup's lane groups per
+// tile (about 7 KiB), a workgroup per tile up to 32768 workgroups (with nothing to carry from
+// tile to tile, workgroups that walk several tiles were slower at every grid tried: 64 MiB of
+// 197-element fp16 rows 25.0 to 26.7 us on 1536 to 4096 workgroups, 24.2 with one per tile).
+// Its tile mirrors the offset of x from a 16-byte boundary; where y sits at another, the stores
+// are element-aligned.
 constexpr int64_t kPackedMaxN = 64 * rms::kPackElems;
-constexpr int64_t kPackedMaxGrid = 8192;
+constexpr int64_t kPackedMaxGrid = 1 << 15;
 // Aligned rows of at most 64 bytes also take it: one to four of the eight lanes of the
 // narrowest lane group would hold a vector, and the LDS-staged kernel is 1.2 to 2 times faster.
 constexpr int64_t kPackedAutoVectors = 4;
@@ -160,10 +163,11 @@ bool only_stores_unaligned(const void* x, int64_t N, int dtype) {
 template <int DT, int L, int E>
 void launch_packed(const Args& a) {
   const int n = (int)a.N;
-  int tile_rows = rms::kPackTileBytes / (n * rms::Storage<DT>::kBytes);
-  if (tile_rows > a.M) tile_rows = (int)a.M;
-  int64_t blocks = (a.M + tile_rows - 1) / tile_rows;
-  if (blocks > kPackedMaxGrid) blocks = kPackedMaxGrid;
+  const rms::host::PackedShape shape = rms::host::packed_shape(a.M, (int64_t)n * rms::Storage<DT>::kBytes, L,
+                                                               rms::kPackThreads, rms::kPackTileBytes,
+                                                               rms::host::kPackedTargetReadWrite, kPackedMaxGrid);
+  const int tile_rows = shape.tile_rows;
+  const int64_t blocks = shape.blocks;
   RMS_LAUNCH((rms::softmax_packed_kernel<DT, L, E, true>), dim3((unsigned)blocks),
                      dim3(rms::kPackThreads), 0, a.stream, a.x, a.y, a.M, n, tile_rows);
 }

@@ -223,16 +223,35 @@ softmax_packed_kernel(const void* x, void* y, int64_t M, int N, int tile_rows) {
   const int sub = t % L;
   const int group = t / L;
 
-  for (int64_t r0 = (int64_t)blockIdx.x * tile_rows; r0 < M; r0 += (int64_t)gridDim.x * tile_rows) {
-    const int rows = (int)(M - r0 < tile_rows ? M - r0 : tile_rows);
-    const char* src = static_cast<const char*>(x) + r0 * N * S::kBytes;
-    const TileCut cut = tile_cut(src, rows * N * S::kBytes);
+  // The run of a tile is requested one tile ahead (see tile_request).
+  const int64_t stride = (int64_t)gridDim.x * tile_rows;
+  auto run_of = [&](int64_t r0, int& rows, const char*& src) {
+    rows = (int)(M - r0 < tile_rows ? M - r0 : tile_rows);
+    src = static_cast<const char*>(x) + r0 * N * S::kBytes;
+    return tile_cut(src, rows * N * S::kBytes);
+  };
+  TileRegs<DT> regs;
+  int rows = 0;
+  const char* src = nullptr;
+  TileCut cut = {};
+  int64_t r0 = (int64_t)blockIdx.x * tile_rows;
+  if (r0 < M) {
+    cut = run_of(r0, rows, src);
+    tile_request<DT, NT>(src, cut, t, regs);
+  }
+  for (; r0 < M; r0 += stride) {
     const int origin = cut.skew / S::kBytes;               // tile element of the run's first element
-    tile_fill<DT, NT>(src, tile, cut, t);
+    tile_commit<DT>(tile, cut, t, regs);
     __syncthreads();
-    for (int first = 0; first < rows; first += GROUPS) {   // the same trip count for every thread
+    const TileCut this_cut = cut;
+    const int this_rows = rows;
+    if (r0 + stride < M) {
+      cut = run_of(r0 + stride, rows, src);
+      tile_request<DT, NT>(src, cut, t, regs);
+    }
+    for (int first = 0; first < this_rows; first += GROUPS) {   // the same trip count for every thread
       const int r = first + group;
-      const int at = origin + (r < rows ? r : rows - 1) * N;
+      const int at = origin + (r < this_rows ? r : this_rows - 1) * N;
       float f[E];
       float m = kNegInf;
 #pragma unroll
@@ -252,7 +271,7 @@ softmax_packed_kernel(const void* x, void* y, int64_t M, int N, int tile_rows) {
       // The sum is at least 1 (the maximum contributes exp(0)) and at most N: the hardware
       // reciprocal (1 ulp) replaces the ten-instruction correctly rounded division.
       const float inv = __builtin_amdgcn_rcpf(group_sum<L>(acc));
-      if (r < rows) {
+      if (r < this_rows) {
 #pragma unroll
         for (int i = 0; i < E; ++i) {
           const int j = sub + i * L;
@@ -261,7 +280,7 @@ softmax_packed_kernel(const void* x, void* y, int64_t M, int N, int tile_rows) {
       }
     }
     __syncthreads();
-    tile_drain<DT, NT>(static_cast<char*>(y) + r0 * N * S::kBytes, tile, cut, t);
+    tile_drain<DT, NT>(static_cast<char*>(y) + r0 * N * S::kBytes, tile, this_cut, t);
     __syncthreads();                                       // the next step refills the tile
   }
 }

@@ -32,6 +32,8 @@ def load() -> ctypes.CDLL:
         vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
         lib.measure_copy.argtypes = [vp, vp, i64, vp]
         lib.measure_copy.restype = i32
+        lib.measure_staged_copy.argtypes = [vp, vp, i64, vp]
+        lib.measure_staged_copy.restype = i32
         lib.measure_status_string.argtypes = [i32]
         lib.measure_status_string.restype = ctypes.c_char_p
         _lib = lib
@@ -44,14 +46,23 @@ def measure_status_string(status: int) -> str:
 
 def measure_copy(src, dst) -> None:
     """dst <- src, byte for byte, with the library's streaming copy kernel, on the current stream."""
+    _copy("measure_copy", src, dst)
+
+
+def measure_staged_copy(src, dst) -> None:
+    """dst <- src through LDS tiles (the staging of the short-row kernels), on the current stream."""
+    _copy("measure_staged_copy", src, dst)
+
+
+def _copy(entry: str, src, dst) -> None:
     import torch
     if not (src.is_cuda and dst.is_cuda and src.is_contiguous() and dst.is_contiguous()):
-        raise ValueError("measure_copy: contiguous device tensors required")
+        raise ValueError(f"{entry}: contiguous device tensors required")
     nbytes = src.numel() * src.element_size()
     if nbytes != dst.numel() * dst.element_size():
-        raise ValueError("measure_copy: size mismatch")
+        raise ValueError(f"{entry}: size mismatch")
     stream = torch.cuda.current_stream(src.device).cuda_stream
     with torch.cuda.device(src.device):
-        rc = load().measure_copy(src.data_ptr(), dst.data_ptr(), nbytes, stream)
+        rc = getattr(load(), entry)(src.data_ptr(), dst.data_ptr(), nbytes, stream)
     if rc != MEASURE_OK:
         raise MeasureError(rc, measure_status_string(rc))

@@ -62,7 +62,7 @@ def test_the_json_line_names_its_timing_protocol_and_its_settling_launches():
     text = open(BENCH).read()
     assert text.count('"timing": "back_to_back_region"') == 5
     assert text.count('"settle_launches": settled') == 5
-    assert "rmsnorm_calib_copy" not in text and text.count("measure.measure_copy(") == 6
+    assert "rmsnorm_calib_copy" not in text and text.count("measure.measure_copy(") == 5 and "measure.measure_staged_copy" in text
     b = load_bench()
     assert b.traffic_fields("rmsnorm")["traffic_source"] == "profiles/" + b.TRAFFIC_FILES["rmsnorm"]
 

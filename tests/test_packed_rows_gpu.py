@@ -87,8 +87,8 @@ def test_rmsnorm_packed_in_place_and_deterministic(gpu_device, dtype):
 
 
 def test_rmsnorm_packed_more_tiles_than_the_grid(gpu_device):
-    """The grid stops at 8192 workgroups; with 8 rows of 2 KiB per tile, 65536 + 13 rows make
-    the first workgroups take a second tile and the last of those a partial one."""
+    """The grid stops at 8192 workgroups; with 8 rows of 2 KiB per tile, 65536 + 13 rows are 8194
+    tiles: the workgroups take two tiles each, the last of them a partial one, and some only one."""
     M, N = 8192 * 8 + 13, 511
     case = inputs.random_case(6, 960, M, N, inputs.FP32, 1e-6)
     H.check_case(case, gpu_device, variants=(binding.RMSNORM_VARIANT_PACKED,))
@@ -146,9 +146,26 @@ def test_softmax_packed_attention_shapes_in_place(gpu_device, dtype):
         assert np.array_equal(H.to_host(xd, dtype).view(np.uint8), first.view(np.uint8))
 
 
+def test_softmax_packed_more_tiles_than_the_grid(gpu_device):
+    """The grid stops at 32768 workgroups; fp16 rows of 1001 elements go 4 to a tile, so
+    131072 + 13 rows are 32772 tiles: two for most workgroups, the last of all a partial one."""
+    M, N = 32768 * 4 + 13, 1001
+    case = inputs.softmax_case(6, 1030, M, N, inputs.FP16, 2.0)
+    SM.check(case, gpu_device, modes=(0, softmax.SOFTMAX_VARIANT_PACKED))
+
+
 # ---- LayerNorm ---------------------------------------------------------------------------------
 import test_layernorm_gpu as LN
 from paper_2603_21331_amd import layernorm
+
+
+def test_layernorm_packed_more_tiles_than_the_grid(gpu_device):
+    """The grid stops at 4096 workgroups; with 8 rows of 2 KiB per tile, 32768 + 13 rows are 4098
+    tiles: two for most workgroups (weight and bias fetched once, the second tile requested while
+    the first is worked on), the last of all a partial one."""
+    M, N = 4096 * 8 + 13, 511
+    case = inputs.layernorm_case(6, 1080, M, N, inputs.FP32, 1e-5, mean=1.0, std=2.0)
+    LN.check(case, gpu_device, modes=(0, layernorm.LAYERNORM_VARIANT_PACKED))
 
 
 @pytest.mark.parametrize("bias", [True, False])
