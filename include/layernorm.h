@@ -56,13 +56,15 @@ typedef enum {
   LAYERNORM_VARIANT_BLOCK = 2,   /* one workgroup of 256..1024 threads per row */
   LAYERNORM_VARIANT_GENERIC = 3, /* element-wise, three passes, any alignment, any N */
   LAYERNORM_VARIANT_SUBWAVE = 4, /* 8, 16 or 32 lanes per row; 16-byte aligned rows <= 1 KiB */
-  LAYERNORM_VARIANT_UNALIGNED = 5, /* the register-resident row kernel addressed in elements:
-                                      single elements at both ends of a row and 128-bit accesses
-                                      between them, which resident workgroups put on the 16-byte
-                                      boundaries of x (of y too if x and y are congruent modulo
-                                      16 bytes) when there are enough rows (16-bit types; see
-                                      layernorm_unaligned_walk_grid), only element-aligned
-                                      otherwise: any alignment, N up to the register limit */
+  LAYERNORM_VARIANT_UNALIGNED = 5, /* the register-resident row kernel addressed in bytes:
+                                      128-bit accesses on the 16-byte boundaries of x, laid out
+                                      from the 128-byte line in which the row starts so that a
+                                      wavefront's accesses cover whole lines (of y too if x and
+                                      y are congruent modulo 128 bytes), single elements at both
+                                      ends; with enough rows, resident workgroups that read their
+                                      slices of weight and bias once (see
+                                      layernorm_unaligned_walk_grid): any alignment, N up to the
+                                      register limit */
   LAYERNORM_VARIANT_STREAM = 6,    /* three streaming passes with 128-bit accesses for rows too
                                       long for registers (the second and third read come from
                                       cache); any alignment, N < 2^31 */
@@ -112,12 +114,13 @@ int layernorm_auto_threads_per_row(int64_t N, int dtype);
 
 /*
  * How LAYERNORM_VARIANT_UNALIGNED would run this call, without launching anything: the
- * number of resident workgroups of its walking form (each takes rows blockIdx,
- * blockIdx + grid, ..., all of which start at the same offset from a 16-byte boundary,
- * reads its slices of weight and bias once and cuts every row at the boundaries), or 0
- * if it would run one workgroup per row with element-aligned accesses (fp32; fewer than
- * four rows per workgroup; N of at most 2055 or beyond 32775 elements).  A negative
- * layernorm_status for arguments layernorm_fwd would reject.  No memory is touched.
+ * number of resident workgroups of its walking form (a multiple of 64; each takes rows
+ * blockIdx, blockIdx + grid, ..., all of which start at the same offset from a 128-byte line,
+ * and reads its slices of weight and bias once), or 0 if it would run one workgroup per row
+ * and read those slices for every row (fewer than four rows per workgroup; rows of at most
+ * 256 or more than 4096 whole 16-byte pieces: N below 2056 or above 32775 elements of a
+ * 16-bit type, below 1028 or above 16387 of fp32).  A negative layernorm_status for arguments
+ * layernorm_fwd would reject.  No memory is touched.
  */
 int64_t layernorm_unaligned_walk_grid(const void* x, const void* w, const void* b, const void* y,
                                       int64_t M, int64_t N, int dtype);

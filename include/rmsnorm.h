@@ -73,12 +73,13 @@ typedef enum {
                                   registers, cross-wave reduction in LDS */
   RMSNORM_VARIANT_GENERIC = 3, /* element-wise, any alignment, any N; reads x twice */
   RMSNORM_VARIANT_UNALIGNED = 4, /* row held in registers like WAVE / BLOCK, but addressed in
-                                   elements: single elements at both ends and 128-bit
-                                   accesses between them, which resident workgroups put on
-                                   the 16-byte boundaries of x (of y too if x and y are
-                                   congruent modulo 16 bytes) when there are enough rows
-                                   (16-bit types; see rmsnorm_unaligned_walk_grid) and
-                                   which are only element-aligned otherwise; any alignment, N up to
+                                   bytes: 128-bit accesses on the 16-byte boundaries of x,
+                                   laid out from the 128-byte line in which the row starts
+                                   so that a wavefront's accesses cover whole lines (of y
+                                   too if x and y are congruent modulo 128 bytes), single
+                                   elements at both ends; with enough rows, resident
+                                   workgroups that read their weight slices once (see
+                                   rmsnorm_unaligned_walk_grid); any alignment, N up to
                                    rmsnorm_unaligned_max_n(dtype) */
   RMSNORM_VARIANT_SUBWAVE = 5,  /* 8, 16 or 32 lanes per row, several rows per wavefront;
                                    16-byte aligned rows of at most 1 KiB */
@@ -251,11 +252,11 @@ int rmsnorm_select_variant(const void* x, const void* w, const void* y, int64_t 
 
 /*
  * How RMSNORM_VARIANT_UNALIGNED would run this call, without launching anything: the
- * number of resident workgroups of its walking form (each takes rows blockIdx,
- * blockIdx + grid, ..., all of which start at the same offset from a 16-byte boundary,
- * reads its slice of the weight once and cuts every row at the boundaries), or 0 if it
- * would run one workgroup per row with element-aligned accesses (fp32; fewer than four
- * rows per workgroup; rows of more than 8 groups per thread, 7 with 1024 threads; N beyond
+ * number of resident workgroups of its walking form (a multiple of 64; each takes rows
+ * blockIdx, blockIdx + grid, ..., all of which start at the same offset from a 128-byte
+ * line, and reads its slices of the weight once), or 0 if it would run one workgroup per
+ * row and read the weight slices for every row (fewer than four rows per workgroup; rows of
+ * more than 8 16-byte pieces per thread, 7 with 1024 threads; N beyond
  * rmsnorm_unaligned_max_n).  A negative rmsnorm_status for arguments rmsnorm_fwd would
  * reject.  No memory is touched.
  */

@@ -53,11 +53,12 @@ typedef enum {
   SOFTMAX_VARIANT_BLOCK = 2,   /* one workgroup of 256..1024 threads per row */
   SOFTMAX_VARIANT_GENERIC = 3, /* element-wise, three passes, any alignment, any N */
   SOFTMAX_VARIANT_SUBWAVE = 4, /* 8, 16 or 32 lanes per row; 16-byte aligned rows <= 1 KiB */
-  SOFTMAX_VARIANT_UNALIGNED = 5, /* the register-resident row kernel addressed in elements: single
-                                    elements at both ends of a row and 128-bit accesses between
-                                    them, on the 16-byte boundaries of x (of y too if x and y are
-                                    congruent modulo 16 bytes) in the 16-bit types, dword-aligned
-                                    in fp32: any alignment, N up to the register limit */
+  SOFTMAX_VARIANT_UNALIGNED = 5, /* the register-resident row kernel addressed in bytes: 128-bit
+                                    accesses on the 16-byte boundaries of x, laid out from the
+                                    128-byte line in which the row starts so that a wavefront's
+                                    accesses cover whole lines (of y too if x and y are
+                                    congruent modulo 128 bytes), single elements at both ends:
+                                    any alignment, N up to the register limit */
   SOFTMAX_VARIANT_STREAM = 6,    /* two streaming passes (online max and sum, then scale) for
                                     rows too long for registers: any alignment, N < 2^31 */
   SOFTMAX_VARIANT_PACKED = 7     /* runs of short rows copied through LDS with 128-bit accesses,

@@ -94,6 +94,13 @@ inline PackedShape packed_shape(int64_t M, int64_t row_bytes, int lanes, int thr
   return s;
 }
 
+// Workgroups of a flat grid of one workgroup per row whose kernel takes its row from
+// xcd_block_row (vec_io.h): M, or `max_grid` (a multiple of 64) if that is less, rounded up to a
+// multiple of 64; workgroups whose row lies past M have nothing to do.
+inline int64_t flat_grid(int64_t M, int64_t max_grid) {
+  return ((M < max_grid ? M : max_grid) + 63) / 64 * 64;
+}
+
 // Compute units of the current device (256 on MI355X), looked up once per device.
 inline int compute_units() {
   constexpr int kMaxDevices = 64;
@@ -117,13 +124,14 @@ inline int compute_units() {
 // that number the grid is chosen so that the rows divide evenly among the workgroups (8192 rows
 // over 5 workgroups per compute unit leave a sixth of the last round idle; over 4 none), and it
 // stays a multiple of the compute units (other grids load them unevenly, measured 10 to 20 %
-// slower) and of 8.  With fewer than four rows per workgroup there is nothing to spread the
-// weight over.
+// slower) and of 64: rows that many apart start at the same offset from a 128-byte line
+// whatever the row length, which the walking kernels rely on.  With fewer than four rows per
+// workgroup there is nothing to spread the weight over.
 inline int64_t walk_grid(int64_t M, int64_t row_bytes, int threads, int64_t bytes_per_cu) {
   constexpr int kMaxThreadsPerCu = 2048;
   constexpr int64_t kMinRows = 4;
   const int64_t cus = compute_units();
-  if (cus % 8 != 0) return 0;
+  if (cus % 64 != 0) return 0;
   const double want = (double)bytes_per_cu / (double)row_bytes;
   int64_t most = kMaxThreadsPerCu / threads;
   if (most > M / (kMinRows * cus)) most = M / (kMinRows * cus);

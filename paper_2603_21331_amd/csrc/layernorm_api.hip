@@ -102,12 +102,18 @@ int pick_threads(int64_t nvec, int min_threads, int dtype) {
   return 0;
 }
 
-// Threads per row for the element-aligned kernel over `nfull` full 16-byte groups; 0 if the
-// row does not fit in registers.
-int pick_threads_unaligned(int64_t nfull) {
-  if (nfull <= kSmallRowVectors) return 64;
+// 16-byte slots that the element-addressed kernel's workgroup must hold: the whole 16-byte
+// pieces of a row, at most floor(row bytes / 16) wherever the row starts (the slots are counted
+// from the 128-byte line in which the row starts, and those past the last chunk wrap onto the
+// lanes that the row's offset from the line leaves idle in the first).
+int64_t unaligned_slots(int64_t N, int64_t elem) { return N * elem / 16; }
+
+// Threads per row for the element-addressed kernel over that many slots; 0 if the row does
+// not fit in registers.
+int pick_threads_unaligned(int64_t slots) {
+  if (slots <= kSmallRowVectors) return 64;
   for (int g = 256; g <= kMaxThreads; g *= 2)
-    if (nfull <= (int64_t)g * kBlockMaxChunks) return g;
+    if (slots <= (int64_t)g * kBlockMaxChunks) return g;
   return 0;
 }
 
@@ -164,17 +170,16 @@ constexpr int kWalkMaxChunks = 4;
 constexpr int64_t kWalkBytesPerCu = 48 * 1024;
 
 // The grid of the walking form for this call and its threads per row, 0 for one workgroup
-// per row: rows of a 16-bit type (dword-aligned 128-bit accesses, which is all that fp32 rows
-// can be off by, run at full rate), in the smallest workgroup that holds the row in
-// kWalkMaxChunks groups per thread.  Rows of up to 256 groups, which one wavefront holds, gain
-// nothing measurable and stay as they are.  The rows are cut at the 16-byte boundaries of x;
-// where y sits at another offset its stores stay element-aligned, which costs 2 to 5 %.
+// per row: the smallest workgroup that holds the row's slots in kWalkMaxChunks per thread.
+// Rows of up to 256 slots, which one wavefront holds, gain nothing measurable and stay as they
+// are.  The rows are cut at the 128-byte lines of x; where y sits at another offset from a line
+// its stores straddle the lines.  walk_grid returns multiples of 64 workgroups only, which is
+// what keeps every row of a workgroup at the same offset from a line.
 int64_t unaligned_walk_grid(int64_t M, int64_t N, int bytes, int* threads) {
-  if (bytes != 2) return 0;
-  const int64_t nfull = N / (16 / bytes);
+  const int64_t slots = unaligned_slots(N, bytes);
   int g = 256;
-  while (g < kMaxThreads && nfull > (int64_t)g * kWalkMaxChunks) g *= 2;
-  if (nfull <= rms::kLnWave * kWalkMaxChunks || nfull > (int64_t)g * kWalkMaxChunks) return 0;
+  while (g < kMaxThreads && slots > (int64_t)g * kWalkMaxChunks) g *= 2;
+  if (slots <= rms::kLnWave * kWalkMaxChunks || slots > (int64_t)g * kWalkMaxChunks) return 0;
   *threads = g;
   return walk_grid(M, N * bytes, g, kWalkBytesPerCu);
 }
@@ -182,7 +187,7 @@ int64_t unaligned_walk_grid(int64_t M, int64_t N, int bytes, int* threads) {
 // walk > 0: the walking form with that many resident workgroups.
 template <int DT, int CHUNKS, int G>
 void launch_row_unaligned(const Args& a, int64_t walk) {
-  if constexpr (DT != rms::kFp32 && CHUNKS <= kWalkMaxChunks) {
+  if constexpr (CHUNKS <= kWalkMaxChunks) {
     if (walk > 0) {
       RMS_LAUNCH((rms::layernorm_row_unaligned_kernel<DT, CHUNKS, G, true, true>),
                          dim3((unsigned)walk), dim3(G), 0, a.stream, a.x, a.w, a.b, a.y, a.M,
@@ -190,7 +195,7 @@ void launch_row_unaligned(const Args& a, int64_t walk) {
       return;
     }
   }
-  const int64_t blocks = a.M < kMaxGrid ? a.M : kMaxGrid;
+  const int64_t blocks = rms::host::flat_grid(a.M, kMaxGrid);
   RMS_LAUNCH((rms::layernorm_row_unaligned_kernel<DT, CHUNKS, G, true, false>),
                      dim3((unsigned)blocks), dim3(G), 0, a.stream, a.x, a.w, a.b, a.y, a.M,
                      (int)a.N, (float)a.N, a.eps);
@@ -336,12 +341,12 @@ int dispatch(const Args& a, int threads) {
 // Launches the element-aligned row kernel.  The caller has checked that the row fits.
 template <int DT>
 int dispatch_unaligned(const Args& a) {
-  const int nfull = (int)(a.N / rms::Storage<DT>::kVec);
-  int threads = pick_threads_unaligned(nfull);
+  const int slots = (int)unaligned_slots(a.N, rms::Storage<DT>::kBytes);
+  int threads = pick_threads_unaligned(slots);
   int walk_threads = 0;
   const int64_t walk = unaligned_walk_grid(a.M, a.N, rms::Storage<DT>::kBytes, &walk_threads);
   if (walk > 0) threads = walk_threads;
-  int chunks = (nfull + threads - 1) / threads;
+  int chunks = (slots + threads - 1) / threads;
   if (chunks < 1) chunks = 1;
   switch (threads) {
     case 64:
@@ -398,7 +403,7 @@ int run(const void* x, const void* w, const void* b, void* y, int64_t M, int64_t
 
   const bool vec_ok = rows_vectorisable(x, w, b, y, N, dtype);
   const int64_t nvec = vec_ok ? N * elem_bytes(dtype) / 16 : 0;
-  const bool unaligned_fits = pick_threads_unaligned(N / (16 / elem_bytes(dtype))) != 0;
+  const bool unaligned_fits = pick_threads_unaligned(unaligned_slots(N, elem_bytes(dtype))) != 0;
   switch (variant) {
     case LAYERNORM_VARIANT_AUTO:
       threads = vec_ok ? (nvec <= kPackedAutoVectors ? -3 : pick_threads(nvec, 8, dtype))
@@ -482,7 +487,7 @@ int layernorm_auto_threads_per_row(int64_t N, int dtype) {
 int64_t layernorm_unaligned_walk_grid(const void* x, const void* w, const void* b, const void* y,
                                       int64_t M, int64_t N, int dtype) {
   if (check_args(x, w, b, y, M, N, 0.0f, dtype) != LAYERNORM_OK) return LAYERNORM_ERR_INVALID_ARG;
-  if (pick_threads_unaligned(N / (16 / elem_bytes(dtype))) == 0) return 0;
+  if (pick_threads_unaligned(unaligned_slots(N, elem_bytes(dtype))) == 0) return 0;
   int threads = 0;
   return unaligned_walk_grid(M, N, elem_bytes(dtype), &threads);
 }

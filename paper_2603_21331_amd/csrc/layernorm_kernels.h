@@ -556,22 +556,26 @@ layernorm_subwave_kernel(const u32x4* x, const u32x4* __restrict__ w, const u32x
 // ---------------------------------------------------------------------------
 // The register-resident kernel for rows that are NOT 16-byte aligned (odd N such as the
 // paper's edge dims 1023 / 4097 / 1537, or base pointers off a 16-byte boundary).  Rows,
-// weight and bias are addressed in elements.  A row is cut into `head` single elements,
-// 16-byte groups and single elements again: thread t holds groups c * G + t, threads
-// 0 .. head - 1 one leading element each, threads 16 .. 16 + tail - 1 one trailing element
-// each.  x is still read exactly once.  Same arithmetic as layernorm_row_kernel.
+// weight and bias are addressed in bytes, and the 16-byte slots of a row are counted from the
+// 128-byte line in which it starts (RowCut in vec_io.h): thread t holds slots c * G + t, so
+// every load and store instruction of a wavefront covers eight whole lines; the slots that
+// the row does not cover whole hold nothing, the at most VEC - 1 elements before the first
+// whole slot go to threads 0 .. head - 1 one each, those after the last to threads
+// 16 .. 16 + tail - 1.  CHUNKS * G need only be the whole 16-byte pieces of a row,
+// floor(N * sizeof(element) / 16): the slots a row reaches past slot CHUNKS * G - 1 (at most
+// as many as it starts into its line) go to the lanes of chunk 0 that this start leaves idle.
+// x is still read exactly once.  Same arithmetic as layernorm_row_kernel.
 //
-//  WALK == false : head is 0, one row per workgroup (striding only beyond the grid limit);
-//                  every 128-bit access is only element-aligned (single
-//                  global_load/store_dwordx4 instructions on this target, at a lower rate
-//                  in the 16-bit types); weight and bias are read in the epilogue.
-//  WALK == true  : the grid is a multiple of 8 workgroups that stay for the whole launch.
-//                  Rows blockIdx.x + k * gridDim.x then all start at the same offset from
-//                  a 16-byte boundary, head brings their groups onto the boundaries of x
-//                  (and of y, if y sits at the same offset as x; otherwise the stores stay
-//                  element-aligned, which costs little), and the workgroup reads its slices
-//                  of weight and bias (off the boundaries by that head) once, into
-//                  registers.
+//  Either way the grid is a multiple of 64 workgroups and workgroup b starts with row
+//  xcd_block_row(b) (vec_io.h): eight consecutive rows out of every 64 for each XCD.
+//  WALK == false : one row per workgroup (striding only beyond the grid limit), the cut taken
+//                  per row; weight and bias slices, at element-aligned addresses, are read in
+//                  the epilogue of every row.
+//  WALK == true  : the grid is a multiple of 64 workgroups that stay for the whole launch.
+//                  Rows blockIdx.x + k * gridDim.x then all start at the same offset from a
+//                  line, so the cut is the workgroup's, and it reads its slices of weight and
+//                  bias once, into registers.
+//  Where y sits at another offset from a line than x, its stores straddle the lines.
 // ---------------------------------------------------------------------------
 template <int DT, int CHUNKS, int G, bool NT, bool WALK>
 __global__ void __launch_bounds__(G) __attribute__((amdgpu_waves_per_eu(4)))
@@ -587,37 +591,39 @@ layernorm_row_unaligned_kernel(const void* x, const void* __restrict__ w, const 
   const int t = threadIdx.x;
   const int lane = t & (kLnWave - 1);
   const int wave = t / kLnWave;
-  const int last = (CHUNKS - 1) * G + t;
   const bool has_bias = b != nullptr;
   const u32x4 zero = {0u, 0u, 0u, 0u};
   int slot = 0;
-  if (blockIdx.x >= M) return;
+  const int64_t first_row = xcd_block_row(blockIdx.x);   // either way the grid is a multiple of 64
+  if (first_row >= M) return;
 
-  // The cut, the same for every row of this workgroup.
-  int head = 0;
-  if constexpr (WALK) {
-    const char* first = static_cast<const char*>(x) + (int64_t)blockIdx.x * n_cols * S::kBytes;
-    head = (int)((16u - (unsigned)(reinterpret_cast<uintptr_t>(first) & 15u)) & 15u) / S::kBytes;
-    head = head < n_cols ? head : n_cols;
-  }
-  const int groups = (n_cols - head) / VEC;             // at most CHUNKS * G, at least (CHUNKS - 1) * G
-  const int tail_n = n_cols - head - groups * VEC;
-  const bool last_ok = last < groups;
-  const bool tail_ok = t < head || (t >= kTailThread && t - kTailThread < tail_n);
-  const int tail_col = t < head ? t : head + groups * VEC + (t - kTailThread);
-  const char* wb = static_cast<const char*>(w) + head * S::kBytes;
-  const char* bb = static_cast<const char*>(b) + head * S::kBytes;
+  RowCut cut = row_cut<S::kBytes>(static_cast<const char*>(x) + first_row * n_cols * S::kBytes, n_cols);
+  // Lane t holds slot c * G + t in chunk c, except that the lanes of chunk 0 before the row's
+  // first whole slot take the slots past the last chunk.
+  auto slot_of = [&](int c) { return (c == 0 && t < cut.first) ? CHUNKS * G + t : c * G + t; };
+  auto holds = [&](int c) { return (c > 0 && c < CHUNKS - 1) || slot_of(c) < cut.end; };
+  bool tail_ok = false;
+  int tail_col = 0;
+  const char* wl = nullptr;                             // weight / bias bytes of slot 0
+  const char* bl = nullptr;
+  auto place_edges = [&]() {
+    tail_ok = t < cut.head || (t >= kTailThread && t - kTailThread < cut.tail);
+    tail_col = t < cut.head ? t : n_cols - cut.tail + (t - kTailThread);
+    wl = static_cast<const char*>(w) - cut.off;
+    bl = static_cast<const char*>(b) - cut.off;
+  };
 
   u32x4 wv[WALK ? CHUNKS : 1], bv[WALK ? CHUNKS : 1];
   float tail_w = 0.f, tail_b = 0.f;
   if constexpr (WALK) {
+    place_edges();
 #pragma unroll
     for (int c = 0; c < CHUNKS; ++c) {
-      const int64_t off = (int64_t)(c * G + t) * kGroupBytes;
+      const int64_t at = (int64_t)slot_of(c) * kGroupBytes;
       wv[c] = bv[c] = zero;
-      if (c < CHUNKS - 1 || last_ok) {
-        wv[c] = load_vec_unaligned<false>(wb + off);
-        if (has_bias) bv[c] = load_vec_unaligned<false>(bb + off);
+      if (holds(c)) {
+        wv[c] = load_vec_unaligned<false>(wl + at);
+        if (has_bias) bv[c] = load_vec_unaligned<false>(bl + at);
       }
     }
     if (tail_ok) {
@@ -626,18 +632,22 @@ layernorm_row_unaligned_kernel(const void* x, const void* __restrict__ w, const 
     }
   }
 
-  for (int64_t row = blockIdx.x; row < M; row += gridDim.x) {
+  for (int64_t row = first_row; row < M; row += gridDim.x) {
     const char* xr = static_cast<const char*>(x) + row * n_cols * S::kBytes;
     char* yr = static_cast<char*>(y) + row * n_cols * S::kBytes;
-    const char* xb = xr + head * S::kBytes;
-    char* yb = yr + head * S::kBytes;
+    if constexpr (!WALK) {
+      cut = row_cut<S::kBytes>(xr, n_cols);
+      place_edges();
+    }
+    const char* xl = xr - cut.off;                      // the line the row starts in
+    char* yl = yr - cut.off;
 
     u32x4 v[CHUNKS];
 #pragma unroll
-    for (int c = 0; c < CHUNKS - 1; ++c)
-      v[c] = load_vec_unaligned<NT>(xb + (int64_t)(c * G + t) * kGroupBytes);
-    v[CHUNKS - 1] = zero;
-    if (last_ok) v[CHUNKS - 1] = load_vec_unaligned<NT>(xb + (int64_t)last * kGroupBytes);
+    for (int c = 0; c < CHUNKS; ++c) {
+      v[c] = zero;
+      if (holds(c)) v[c] = load_vec_unaligned<NT>(xl + (int64_t)slot_of(c) * kGroupBytes);
+    }
     const float shift = S::load_one(xr, 0);             // the row's first element
     float tail = 0.f;
     if (tail_ok) tail = S::load_one(xr, tail_col) - shift;
@@ -647,7 +657,7 @@ layernorm_row_unaligned_kernel(const void* x, const void* __restrict__ w, const 
 #pragma unroll
     for (int c = 0; c < CHUNKS; ++c) {
       S::unpack(v[c], f[c]);
-      const bool live = c < CHUNKS - 1 || last_ok;
+      const bool live = holds(c);
 #pragma unroll
       for (int k = 0; k < VEC; ++k) {
         f[c][k] = live ? f[c][k] - shift : 0.f;
@@ -666,7 +676,7 @@ layernorm_row_unaligned_kernel(const void* x, const void* __restrict__ w, const 
     float sq[4] = {tail * tail, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int c = 0; c < CHUNKS; ++c) {
-      const bool live = c < CHUNKS - 1 || last_ok;
+      const bool live = holds(c);
 #pragma unroll
       for (int k = 0; k < VEC; ++k) {
         f[c][k] = live ? f[c][k] - mean_shifted : 0.f;
@@ -685,22 +695,22 @@ layernorm_row_unaligned_kernel(const void* x, const void* __restrict__ w, const 
     if constexpr (WALK) {
 #pragma unroll
       for (int c = 0; c < CHUNKS; ++c)
-        if (c < CHUNKS - 1 || last_ok)
-          store_vec_unaligned<NT>(yb + (int64_t)(c * G + t) * kGroupBytes,
+        if (holds(c))
+          store_vec_unaligned<NT>(yl + (int64_t)slot_of(c) * kGroupBytes,
                                   ln_scale<DT>(f[c], wv[c], bv[c], has_bias, rstd));
     } else {
       // weight and bias only now (L2 hits), behind an empty asm so that they are not hoisted
       // above the reductions, where the centred row already fills the register budget
-      const char* wp = wb;
-      const char* bp = bb;
+      const char* wp = wl;
+      const char* bp = bl;
       asm volatile("" : "+s"(wp), "+s"(bp));
 #pragma unroll
       for (int c = 0; c < CHUNKS; ++c) {
-        if (c < CHUNKS - 1 || last_ok) {
-          const int64_t off = (int64_t)(c * G + t) * kGroupBytes;
-          const u32x4 wc = load_vec_unaligned<false>(wp + off);
-          const u32x4 bc = has_bias ? load_vec_unaligned<false>(bp + off) : zero;
-          store_vec_unaligned<NT>(yb + off, ln_scale<DT>(f[c], wc, bc, has_bias, rstd));
+        if (holds(c)) {
+          const int64_t at = (int64_t)slot_of(c) * kGroupBytes;
+          const u32x4 wc = load_vec_unaligned<false>(wp + at);
+          const u32x4 bc = has_bias ? load_vec_unaligned<false>(bp + at) : zero;
+          store_vec_unaligned<NT>(yl + at, ln_scale<DT>(f[c], wc, bc, has_bias, rstd));
         }
       }
       if (tail_ok) {

@@ -155,18 +155,22 @@ int pick_threads_batch(int64_t nvec, int64_t M, int dtype) {
   return g0;
 }
 
-// Threads per row for the element-aligned kernel (fewer instantiations: 64
-// threads up to 4 chunks, 256 and 512 up to 8, 1024 up to 16); 0 if the row
-// does not fit in registers.
-int pick_threads_unaligned(int64_t nfull) {
-  if (nfull <= kSmallRowVectors) return 64;
-  if (nfull <= 256 * kMidMaxChunks) return 256;
-  if (nfull <= 512 * kMidMaxChunks) return 512;
-  if (nfull <= (int64_t)kBlockMaxThreads * kBlockMaxChunks) return 1024;
+// Threads per row for the element-addressed kernel, from the 16-byte slots its workgroup must
+// cover (fewer instantiations: 64 threads up to 4 chunks, 256 and 512 up to 8, 1024 up to 16);
+// 0 if the row does not fit in registers.
+int pick_threads_unaligned(int64_t slots) {
+  if (slots <= kSmallRowVectors) return 64;
+  if (slots <= 256 * kMidMaxChunks) return 256;
+  if (slots <= 512 * kMidMaxChunks) return 512;
+  if (slots <= (int64_t)kBlockMaxThreads * kBlockMaxChunks) return 1024;
   return 0;
 }
 
-int64_t full_groups_per_row(int64_t N, int dtype) { return N / (16 / elem_bytes(dtype)); }
+// 16-byte slots that the element-addressed kernel's workgroup must hold: the whole 16-byte
+// pieces of a row, at most floor(row bytes / 16) wherever the row starts (the slots are counted
+// from the 128-byte line in which the row starts, and those past the last chunk wrap onto the
+// lanes that the row's offset from the line leaves idle in the first).
+int64_t slots_per_row(int64_t N, int dtype) { return N * elem_bytes(dtype) / 16; }
 
 constexpr int64_t kStreamMaxN = (int64_t)1 << 31;   // the streaming kernel counts groups in an int
 
@@ -204,7 +208,7 @@ bool only_stores_unaligned(const void* x, const void* w, int64_t N, int dtype) {
 int choose(const void* x, const void* w, const void* y, int64_t N, int dtype) {
   if (!rows_vectorisable(x, w, y, N, dtype)) {
     if (packed_can(N) && !only_stores_unaligned(x, w, N, dtype)) return RMSNORM_VARIANT_PACKED;
-    if (pick_threads_unaligned(full_groups_per_row(N, dtype))) return RMSNORM_VARIANT_UNALIGNED;
+    if (pick_threads_unaligned(slots_per_row(N, dtype))) return RMSNORM_VARIANT_UNALIGNED;
     return N < kStreamMaxN ? RMSNORM_VARIANT_STREAM : RMSNORM_VARIANT_GENERIC;
   }
   // Rows of at most 64 bytes leave most of the narrowest lane group idle (one to four of its
@@ -376,24 +380,23 @@ void launch_subwave(const Args& a) {
 constexpr int64_t kWalkBytesPerCu = 26 * 1024;
 constexpr int kWalkMaxChunks = 8;   // what fits in registers next to the packed weight
 
-// The grid of the walking form for this call, 0 for one workgroup per row: rows of a 16-bit
-// type (dword-aligned 128-bit accesses, which is all that fp32 rows can be off by, run at full
-// rate).  The rows are cut at the 16-byte boundaries of x; where y sits at another offset its
-// stores stay element-aligned, which costs 2 to 5 % (element-aligned loads cost 10 to 15 %).
+// The grid of the walking form for this call, 0 for one workgroup per row.  Its rows are cut at
+// the 128-byte lines of x; where y sits at another offset from a line its stores straddle the
+// lines.  walk_grid returns multiples of 64 workgroups only, which is what keeps every row of a
+// workgroup at the same offset from a line.
 int64_t unaligned_walk_grid(int64_t M, int64_t N, int dtype) {
-  if (dtype == RMSNORM_DTYPE_FP32) return 0;
-  const int64_t nfull = full_groups_per_row(N, dtype);
-  const int threads = pick_threads_unaligned(nfull);
+  const int64_t slots = slots_per_row(N, dtype);
+  const int threads = pick_threads_unaligned(slots);
   if (threads == 0) return 0;
   // (1024 threads are capped at 128 registers each: 7 groups next to their weight)
-  if ((nfull + threads - 1) / threads > (threads == kBlockMaxThreads ? kWalkMaxChunks - 1 : kWalkMaxChunks)) return 0;
+  if ((slots + threads - 1) / threads > (threads == kBlockMaxThreads ? kWalkMaxChunks - 1 : kWalkMaxChunks)) return 0;
   return walk_grid(M, N * elem_bytes(dtype), threads, kWalkBytesPerCu);
 }
 
 // walk > 0: the walking form with that many resident workgroups.
 template <int DT, int CHUNKS, int G>
 void launch_row_unaligned(const Args& a, int64_t walk) {
-  if constexpr (DT != rms::kFp32 && CHUNKS <= (G == kBlockMaxThreads ? kWalkMaxChunks - 1 : kWalkMaxChunks)) {
+  if constexpr (CHUNKS <= (G == kBlockMaxThreads ? kWalkMaxChunks - 1 : kWalkMaxChunks)) {
     if (walk > 0) {
       RMS_LAUNCH((rms::rmsnorm_row_unaligned_kernel<DT, CHUNKS, G, true, true>),
                          dim3((unsigned)walk), dim3(G), 0, a.stream,
@@ -401,7 +404,7 @@ void launch_row_unaligned(const Args& a, int64_t walk) {
       return;
     }
   }
-  const int64_t blocks = a.M < kMaxGrid ? a.M : kMaxGrid;
+  const int64_t blocks = rms::host::flat_grid(a.M, kMaxGrid);
   RMS_LAUNCH((rms::rmsnorm_row_unaligned_kernel<DT, CHUNKS, G, true, false>),
                      dim3((unsigned)blocks), dim3(G), 0, a.stream,
                      a.x, a.w, a.y, a.M, (int)a.N, 1.0f / (float)a.N, a.eps);
@@ -541,11 +544,11 @@ void dispatch_packed(const Args& a) {
 // Launches the element-aligned row kernel.  The caller has checked that the row fits.
 template <int DT>
 int dispatch_row_unaligned(const Args& a) {
-  const int nfull = (int)full_groups_per_row(a.N, DT == rms::kFp32 ? RMSNORM_DTYPE_FP32 : RMSNORM_DTYPE_FP16);
-  const int threads = pick_threads_unaligned(nfull);
-  const int64_t walk = unaligned_walk_grid(a.M, a.N,
-                                           DT == rms::kFp32 ? RMSNORM_DTYPE_FP32 : RMSNORM_DTYPE_FP16);
-  int chunks = (nfull + threads - 1) / threads;
+  const int dtype = DT == rms::kFp32 ? RMSNORM_DTYPE_FP32 : RMSNORM_DTYPE_FP16;
+  const int slots = (int)slots_per_row(a.N, dtype);
+  const int threads = pick_threads_unaligned(slots);
+  const int64_t walk = unaligned_walk_grid(a.M, a.N, dtype);
+  int chunks = (slots + threads - 1) / threads;
   if (chunks < 1) chunks = 1;
   switch (threads) {
     case 64:
@@ -673,7 +676,7 @@ int run(const void* x, const void* w, void* y, int64_t M, int64_t N, float eps, 
       if (threads == 0) return RMSNORM_ERR_UNSUPPORTED;
       break;
     case RMSNORM_VARIANT_UNALIGNED:
-      if (pick_threads_unaligned(full_groups_per_row(N, dtype)) == 0) return RMSNORM_ERR_UNSUPPORTED;
+      if (pick_threads_unaligned(slots_per_row(N, dtype)) == 0) return RMSNORM_ERR_UNSUPPORTED;
       threads = -1;
       break;
     case RMSNORM_VARIANT_STREAM:
@@ -823,7 +826,7 @@ int64_t rmsnorm_unaligned_max_n(int dtype) {
 int64_t rmsnorm_unaligned_walk_grid(const void* x, const void* w, const void* y, int64_t M,
                                     int64_t N, int dtype) {
   if (check_args(x, w, y, M, N, 0.0f, dtype) != RMSNORM_OK) return RMSNORM_ERR_INVALID_ARG;
-  if (pick_threads_unaligned(full_groups_per_row(N, dtype)) == 0) return 0;
+  if (pick_threads_unaligned(slots_per_row(N, dtype)) == 0) return 0;
   return unaligned_walk_grid(M, N, dtype);
 }
 

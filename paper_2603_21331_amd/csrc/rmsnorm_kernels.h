@@ -457,26 +457,40 @@ rmsnorm_subwave_kernel(const u32x4* x, const u32x4* __restrict__ w, u32x4* y,
 // ---------------------------------------------------------------------------
 // The same register-resident kernel for rows that are NOT 16-byte aligned (odd
 // N such as 1023 or 4097, or base pointers off a 16-byte boundary).  Rows are
-// addressed in elements.  A row is cut into `head` single elements, 16-byte
-// groups and single elements again: thread t holds groups c * G + t, threads
-// 0 .. head - 1 one leading element each, threads 16 .. 16 + tail - 1 one
-// trailing element each.  x is still read exactly once.
+// addressed in bytes, and the 16-byte slots of a row are counted from the
+// 128-byte line in which the row starts, not from its first element: slot j
+// lies at line + 16 * j, thread t holds slots c * G + t, so the kilobyte that
+// one load or store instruction of a wavefront covers is always eight whole
+// lines.  (Slots counted from the row's first aligned group put every such
+// kilobyte across nine lines, and both neighbours of a line then request it
+// again: a plain copy with its wavefronts 16 bytes off the lines runs at 67 to
+// 76 % of peak where the aligned one reaches 83.)  The slots that the row does
+// not cover whole (some before its start, one at each end in part, the rest
+// after its end) hold nothing; the at most VEC - 1 elements before the first
+// whole slot go to threads 0 .. head - 1 one each, those after the last to
+// threads 16 .. 16 + tail - 1.  x is still read exactly once.  CHUNKS * G
+// need only be the whole 16-byte pieces of a row, floor(N * sizeof(element) /
+// 16): a row that starts `first` slots into its line leaves the first `first`
+// lanes of chunk 0 idle and can reach at most `first` slots past slot
+// CHUNKS * G - 1, and those lanes take these slots (slot CHUNKS * G + t for
+// lane t), so a row of 8191 or 4097 elements needs no more chunks than its
+// aligned neighbour.  Only chunk 0 and the last chunk can hold nothing.
 //
-//  WALK == false : head is 0, one row per workgroup (striding only beyond the
-//                  grid limit); every 128-bit access is only element-aligned
-//                  (single global_load/store_dwordx4 instructions on this
-//                  target, at three quarters of the bandwidth in the 16-bit
-//                  types).
-//  WALK == true  : the grid is a multiple of 8 workgroups that stay for the
+//  Either way the grid is a multiple of 64 workgroups and workgroup b starts
+//  with row xcd_block_row(b) (vec_io.h): eight consecutive rows out of every
+//  64 for each XCD.
+//  WALK == false : one row per workgroup (striding only beyond the grid
+//                  limit), the cut taken per row; the weight slices, which sit
+//                  at element-aligned addresses, are read for every row.
+//  WALK == true  : the grid is a multiple of 64 workgroups that stay for the
 //                  whole launch.  Rows blockIdx.x + k * gridDim.x then all
-//                  start at the same offset from a 16-byte boundary, head
-//                  brings their groups onto the boundaries of x (and of y,
-//                  if y sits at the same offset as x; otherwise the stores
-//                  stay element-aligned, which costs little), and the
-//                  workgroup reads its slices of the weight (which are off
-//                  the boundaries by that head) once, into registers.
-//                  Measured, element-aligned weight loads repeated for every
-//                  row cost more than the aligned row accesses gain.
+//                  start at the same offset from a line, so the cut is the
+//                  workgroup's, and it reads its slices of the weight once,
+//                  into registers.  Measured, element-aligned weight loads
+//                  repeated for every row cost more than the aligned row
+//                  accesses gain.
+//  Where y sits at another offset from a line than x, its stores are off the
+//  lines whatever the cut; that costs what it costs a copy.
 // ---------------------------------------------------------------------------
 template <int DT, int CHUNKS, int G, bool NT, bool WALK>
 __global__ void __launch_bounds__(G)
@@ -484,31 +498,22 @@ rmsnorm_row_unaligned_kernel(const void* x, const void* __restrict__ w, void* y,
                              int64_t M, int n, float inv_n, float eps) {
   using S = Storage<DT>;
   constexpr int WAVES = G / kWave;
-  constexpr int VEC = S::kVec;
   constexpr int kGroupBytes = 16;
   constexpr int kTailThread = 16;                       // first thread that takes a trailing element
   __shared__ __attribute__((aligned(16))) float partial[2][WAVES];
   const int t = threadIdx.x;
   const int lane = t & (kWave - 1);
   const int wave = t / kWave;
-  const int last = (CHUNKS - 1) * G + t;
   const u32x4 zero = {0u, 0u, 0u, 0u};
   int slot = 0;
-  if (blockIdx.x >= M) return;
+  const int64_t first_row = xcd_block_row(blockIdx.x);   // either way the grid is a multiple of 64
+  if (first_row >= M) return;
 
-  // The cut, the same for every row of this workgroup.
-  int head = 0;
-  if constexpr (WALK) {
-    const char* first = static_cast<const char*>(x) + (int64_t)blockIdx.x * n * S::kBytes;
-    head = (int)((16u - (unsigned)(reinterpret_cast<uintptr_t>(first) & 15u)) & 15u) / S::kBytes;
-    head = head < n ? head : n;
-  }
-  const int groups = (n - head) / VEC;                  // at most CHUNKS * G, at least (CHUNKS - 1) * G
-  const int tail = n - head - groups * VEC;
-  const bool last_ok = last < groups;
-  const bool edge_ok = t < head || (t >= kTailThread && t - kTailThread < tail);
-  const int edge_col = t < head ? t : head + groups * VEC + (t - kTailThread);
-  const char* wb = static_cast<const char*>(w) + head * S::kBytes;
+  RowCut cut = row_cut<S::kBytes>(static_cast<const char*>(x) + first_row * n * S::kBytes, n);
+  // Lane t holds slot c * G + t in chunk c, except that the lanes of chunk 0 before the row's
+  // first whole slot take the slots past the last chunk.
+  auto slot_of = [&](int c) { return (c == 0 && t < cut.first) ? CHUNKS * G + t : c * G + t; };
+  auto holds = [&](int c) { return (c > 0 && c < CHUNKS - 1) || slot_of(c) < cut.end; };
 
   // 1024 threads with 8 and more groups each (a workgroup of that size is capped at 128
   // registers per thread): the weight is fetched group by group in the epilogue instead of
@@ -516,30 +521,45 @@ rmsnorm_row_unaligned_kernel(const void* x, const void* __restrict__ w, void* y,
   constexpr bool W_LATE = !WALK && G == 1024 && CHUNKS >= 8;
   u32x4 wv[W_LATE ? 1 : CHUNKS];
   float edge_w = 0.f;
+  bool edge_ok = false;
+  int edge_col = 0;
+  const char* wl = nullptr;                             // weight bytes of slot 0 (element-aligned)
+  auto place_edges = [&]() {
+    edge_ok = t < cut.head || (t >= kTailThread && t - kTailThread < cut.tail);
+    edge_col = t < cut.head ? t : n - cut.tail + (t - kTailThread);
+    wl = static_cast<const char*>(w) - cut.off;
+  };
   auto load_weight = [&]() {
     if constexpr (!W_LATE) {
 #pragma unroll
-      for (int c = 0; c < CHUNKS - 1; ++c)
-        wv[c] = load_vec_unaligned<false>(wb + (int64_t)(c * G + t) * kGroupBytes);
-      wv[CHUNKS - 1] = zero;
-      if (last_ok) wv[CHUNKS - 1] = load_vec_unaligned<false>(wb + (int64_t)last * kGroupBytes);
+      for (int c = 0; c < CHUNKS; ++c) {
+        wv[c] = zero;
+        if (holds(c)) wv[c] = load_vec_unaligned<false>(wl + (int64_t)slot_of(c) * kGroupBytes);
+      }
     }
     if (edge_ok) edge_w = S::load_one(w, edge_col);
   };
-  if constexpr (WALK) load_weight();
+  if constexpr (WALK) {
+    place_edges();
+    load_weight();
+  }
 
-  for (int64_t row = blockIdx.x; row < M; row += gridDim.x) {
+  for (int64_t row = first_row; row < M; row += gridDim.x) {
     const char* xr = static_cast<const char*>(x) + row * n * S::kBytes;
     char* yr = static_cast<char*>(y) + row * n * S::kBytes;
-    const char* xb = xr + head * S::kBytes;
-    char* yb = yr + head * S::kBytes;
+    if constexpr (!WALK) {
+      cut = row_cut<S::kBytes>(xr, n);
+      place_edges();
+    }
+    const char* xl = xr - cut.off;                      // the line the row starts in
+    char* yl = yr - cut.off;
 
     u32x4 v[CHUNKS];
 #pragma unroll
-    for (int c = 0; c < CHUNKS - 1; ++c)
-      v[c] = load_vec_unaligned<NT>(xb + (int64_t)(c * G + t) * kGroupBytes);
-    v[CHUNKS - 1] = zero;
-    if (last_ok) v[CHUNKS - 1] = load_vec_unaligned<NT>(xb + (int64_t)last * kGroupBytes);
+    for (int c = 0; c < CHUNKS; ++c) {
+      v[c] = zero;
+      if (holds(c)) v[c] = load_vec_unaligned<NT>(xl + (int64_t)slot_of(c) * kGroupBytes);
+    }
     float edge_x = 0.f;
     if (edge_ok) edge_x = S::load_one(xr, edge_col);
     if constexpr (!WALK) load_weight();
@@ -554,18 +574,15 @@ rmsnorm_row_unaligned_kernel(const void* x, const void* __restrict__ w, void* y,
     }
     const float rstd = row_rstd(total, inv_n, eps);
 
-    const char* wp = wb;
+    const char* wp = wl;
     if constexpr (W_LATE) asm volatile("" : "+s"(wp) : "v"(rstd));   // not before the reduction
 #pragma unroll
-    for (int c = 0; c < CHUNKS - 1; ++c) {
-      const int64_t off = (int64_t)(c * G + t) * kGroupBytes;
-      const u32x4 wc = W_LATE ? load_vec_unaligned<false>(wp + off) : wv[W_LATE ? 0 : c];
-      store_vec_unaligned<NT>(yb + off, scale_vec<DT>(v[c], wc, rstd));
-    }
-    if (last_ok) {
-      const int64_t off = (int64_t)last * kGroupBytes;
-      const u32x4 wc = W_LATE ? load_vec_unaligned<false>(wp + off) : wv[W_LATE ? 0 : CHUNKS - 1];
-      store_vec_unaligned<NT>(yb + off, scale_vec<DT>(v[CHUNKS - 1], wc, rstd));
+    for (int c = 0; c < CHUNKS; ++c) {
+      if (holds(c)) {
+        const int64_t at = (int64_t)slot_of(c) * kGroupBytes;
+        const u32x4 wc = W_LATE ? load_vec_unaligned<false>(wp + at) : wv[W_LATE ? 0 : c];
+        store_vec_unaligned<NT>(yl + at, scale_vec<DT>(v[c], wc, rstd));
+      }
     }
     if (edge_ok) S::store_one(yr, edge_col, (edge_x * rstd) * edge_w);
   }

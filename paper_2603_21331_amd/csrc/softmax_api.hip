@@ -85,12 +85,18 @@ int pick_threads(int64_t nvec, int min_threads) {
   return 0;
 }
 
-// Threads per row for the element-aligned kernel over `nfull` full 16-byte groups (the same
-// bands); 0 if the row does not fit in registers.
-int pick_threads_unaligned(int64_t nfull) {
-  if (nfull <= kSmallRowVectors) return 64;
+// 16-byte slots that the element-addressed kernel's workgroup must hold: the whole 16-byte
+// pieces of a row, at most floor(row bytes / 16) wherever the row starts (the slots are counted
+// from the 128-byte line in which the row starts, and those past the last chunk wrap onto the
+// lanes that the row's offset from the line leaves idle in the first).
+int64_t unaligned_slots(int64_t N, int64_t elem) { return N * elem / 16; }
+
+// Threads per row for the element-addressed kernel over that many slots (the same bands); 0 if
+// the row does not fit in registers.
+int pick_threads_unaligned(int64_t slots) {
+  if (slots <= kSmallRowVectors) return 64;
   for (int g = 256; g <= kMaxThreads; g *= 2)
-    if (nfull <= (int64_t)g * kBlockMaxChunks) return g;
+    if (slots <= (int64_t)g * kBlockMaxChunks) return g;
   return 0;
 }
 
@@ -122,10 +128,9 @@ void launch_subwave(const Args& a) {
 
 template <int DT, int CHUNKS, int G>
 void launch_row_unaligned(const Args& a) {
-  const int64_t blocks = a.M < kMaxGrid ? a.M : kMaxGrid;
+  const int64_t blocks = rms::host::flat_grid(a.M, kMaxGrid);
   RMS_LAUNCH((rms::softmax_row_unaligned_kernel<DT, CHUNKS, G, true>), dim3((unsigned)blocks),
-                     dim3(G), 0, a.stream, a.x, a.y, a.M, (int)a.N,
-                     DT != rms::kFp32 ? 1 : 0);
+                     dim3(G), 0, a.stream, a.x, a.y, a.M, (int)a.N);
 }
 
 // The LDS-staged kernel for short rows that are not 16-byte aligned: the narrowest lane group
@@ -267,9 +272,9 @@ int dispatch(const Args& a, int threads) {
 // Launches the element-aligned row kernel.  The caller has checked that the row fits.
 template <int DT>
 int dispatch_unaligned(const Args& a) {
-  const int nfull = (int)(a.N / rms::Storage<DT>::kVec);
-  const int threads = pick_threads_unaligned(nfull);
-  int chunks = (nfull + threads - 1) / threads;
+  const int slots = (int)unaligned_slots(a.N, rms::Storage<DT>::kBytes);
+  const int threads = pick_threads_unaligned(slots);
+  int chunks = (slots + threads - 1) / threads;
   if (chunks < 1) chunks = 1;
   switch (threads) {
     case 64:
@@ -326,7 +331,7 @@ int run(const void* x, void* y, int64_t M, int64_t N, int dtype, void* stream, i
 
   const bool vec_ok = rows_vectorisable(x, y, N, dtype);
   const int64_t nvec = vec_ok ? N * elem_bytes(dtype) / 16 : 0;
-  const bool unaligned_fits = pick_threads_unaligned(N / (16 / elem_bytes(dtype))) != 0;
+  const bool unaligned_fits = pick_threads_unaligned(unaligned_slots(N, elem_bytes(dtype))) != 0;
   switch (variant) {
     case SOFTMAX_VARIANT_AUTO:
       threads = vec_ok ? (nvec <= kPackedAutoVectors ? -3 : pick_threads(nvec, 8))

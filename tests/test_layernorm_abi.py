@@ -100,9 +100,11 @@ def test_unaligned_walk_grid_query():
     q = lib.layernorm_unaligned_walk_grid
     assert q(X, W, B, Y, 8192, 4097, 1) == 1024 and q(X, W, B, Y, 16384, 8191, 2) == 768
     assert q(X, W, B, Y, 4096, 20481, 2) == 256 and q(X, W, None, Y, 8192, 4097, 1) == 1024
-    assert q(X + 6, W + 2, B + 4, Y + 22, 8192, 4097, 1) == 1024   # same offset from a boundary
-    assert q(X, W, B, Y + 2, 8192, 4097, 1) == 1024                # different offsets: cut at x's boundaries
-    assert q(X, W, B, Y, 8192, 4097, 0) == 0                       # fp32
+    assert q(X + 6, W + 2, B + 4, Y + 22, 8192, 4097, 1) == 1024   # same offset from a line
+    assert q(X, W, B, Y + 2, 8192, 4097, 1) == 1024                # different offsets: cut at x's lines
+    assert q(X, W, B, Y, 8192, 4097, 0) == 768                     # fp32 walks too
+    assert q(X, W, B, Y, 8192, 1027, 0) == 0 and q(X, W, B, Y, 8192, 1028, 0) == 2048
+    assert q(X, W, B, Y, 2048, 16387, 0) == 256 and q(X, W, B, Y, 2048, 16388, 0) == 0
     assert q(X, W, B, Y, 3000, 4097, 1) == 0                       # too few rows
     assert q(X, W, B, Y, 16384, 2055, 1) == 0 and q(X, W, B, Y, 16384, 2056, 1) > 0
     assert q(X, W, B, Y, 2048, 32775, 1) == 256 and q(X, W, B, Y, 2048, 32776, 1) == 0

@@ -1,11 +1,12 @@
-"""Rows of a 16-bit type that are not 16-byte aligned, with enough of them for the resident
-("walking") form of the element-aligned kernels: every workgroup takes rows that start at one
-offset from a 16-byte boundary, cuts them at the boundaries and keeps its slices of the weight
-(and bias) in registers.  Every thread count and number of groups per thread of that form, all
-eight offsets (odd N walks through them from row to row), bases off a boundary, in place, and
-a row count that does not divide evenly; RMSNorm, softmax (whose kernel makes the same cut
-without residency) and LayerNorm against the CPU oracle, element by element; also with y at
-another offset from a boundary than x (the cut follows x, the stores are element-aligned)."""
+"""Rows that are not 16-byte aligned, with enough of them for the resident ("walking") form of
+the element-addressed kernels: every workgroup takes rows that start at one offset from a
+128-byte line, lays its 16-byte slots out from that line and keeps its slices of the weight
+(and bias) in registers.  Every thread count and number of slots per thread of that form, all
+the offsets a row can have (odd N walks through them from row to row), bases off a boundary,
+in place, and a row count that does not divide evenly; RMSNorm, softmax (whose kernel makes
+the same cut per row, without residency) and LayerNorm against the CPU oracle, element by
+element, in fp16, bf16 and fp32; also with y at another offset from a line than x (the cut
+follows x, the stores straddle the lines)."""
 import pytest
 import torch
 
@@ -18,25 +19,32 @@ from paper_2603_21331_amd import binding, inputs, layernorm, softmax
 pytestmark = pytest.mark.gpu
 
 DTYPES = [inputs.FP16, inputs.BF16]
-# N: 64 threads with 2, 3, 4 groups each; 256 with 2, 4, 6, 8; 512 with 5, 8; 1024 with 5, 7
+# N: 64 threads with 2, 3, 4 slots each; 256 with 2, 4, 6, 8; 512 with 5, 8; 1024 with 5, 7
 # (RMSNorm) and 256 with 1..4, 512 with 3, 4, 1024 with 3, 4 (LayerNorm).
 LENGTHS = [1025, 1537, 2047, 2057, 4097, 8191, 12289, 16383, 20481, 32767, 40961, 57343]
+# the same slot counts in fp32
+LENGTHS_FP32 = [513, 769, 1023, 1029, 2049, 4095, 6145, 8191, 10241, 16383, 20481, 28671]
+CASES = [(N, d) for d in DTYPES for N in LENGTHS] + [(N, inputs.FP32) for N in LENGTHS_FP32]
 
 
-def rows_for(N: int) -> int:
+def rows_for(N: int, dtype: int = inputs.FP16) -> int:
     """Enough rows for four per workgroup of the smallest grid LayerNorm's form takes (the
     larger of the two), and 37 more so that the last round is ragged."""
-    want = 48 * 1024 / (2 * N)
+    want = 48 * 1024 / (inputs.DTYPE_BYTES[dtype] * N)
     per_cu = 1
     while per_cu < 0.55 * want:
         per_cu += 1
     return 4 * 256 * min(per_cu, 8) + 37
 
 
-@pytest.mark.parametrize("dtype", DTYPES)
-@pytest.mark.parametrize("N", LENGTHS)
+def layernorm_walks(N: int, dtype: int) -> bool:
+    """More than 256 and at most 4096 whole 16-byte pieces per row."""
+    return 256 < N * inputs.DTYPE_BYTES[dtype] // 16 <= 4096
+
+
+@pytest.mark.parametrize("N,dtype", CASES)
 def test_walking_form_matches_the_oracle(gpu_device, N, dtype):
-    M = rows_for(N)
+    M = rows_for(N, dtype)
     case = inputs.layernorm_case(9, 1400 + 4 * dtype + N % 89, M, N, dtype, 1e-5, mean=0.5, std=1.5)
     xd, wd, bd = (H.to_device(case[k], dtype, gpu_device) for k in ("x", "w", "b"))
     wr, yr = H.alloc_guarded(M, N, dtype, gpu_device)
@@ -44,8 +52,8 @@ def test_walking_form_matches_the_oracle(gpu_device, N, dtype):
     wl, yl = H.alloc_guarded(M, N, dtype, gpu_device)
     walk_r = binding.rmsnorm_unaligned_walk_grid(xd, wd, yr)
     walk_l = layernorm.layernorm_unaligned_walk_grid(xd, wd, bd, yl)
-    assert walk_r > 0 and walk_r % 8 == 0, "the RMSNorm call does not reach the walking form"
-    assert (walk_l > 0 and walk_l % 8 == 0) == (2056 <= N <= 32775)
+    assert walk_r > 0 and walk_r % 64 == 0, "the RMSNorm call does not reach the walking form"
+    assert (walk_l > 0 and walk_l % 64 == 0) == layernorm_walks(N, dtype)
     H.say(f"walking form {inputs.DTYPE_NAMES[dtype]} {M}x{N}: grids {walk_r}, {walk_l}")
     binding.rmsnorm_fwd(xd, wd, 1e-5, yr)
     softmax.softmax_fwd(xd, ys)
@@ -62,16 +70,16 @@ def test_walking_form_matches_the_oracle(gpu_device, N, dtype):
                                    f"layernorm {M}x{N}")
 
 
-@pytest.mark.parametrize("dtype", DTYPES)
-@pytest.mark.parametrize("N,offset", [(4097, 3), (2050, 5), (8192, 1), (1026, 7)])
+@pytest.mark.parametrize("dtype", DTYPES + [inputs.FP32])
+@pytest.mark.parametrize("N,offset", [(4097, 3), (2050, 5), (8192, 1), (1026, 7), (2048, 40)])
 def test_walking_form_off_a_boundary_in_place_and_without_bias(gpu_device, N, offset, dtype):
     """x and y `offset` elements past a 16-byte boundary (even N included: every row then
-    starts at that one offset), weight and bias at offsets of their own; then in place; then
-    LayerNorm without a bias."""
-    M = rows_for(N)
+    starts at that one offset; 40 elements: whole 16-byte slots, but off the 128-byte lines),
+    weight and bias at offsets of their own; then in place; then LayerNorm without a bias."""
+    M = rows_for(N, dtype)
     td = H.torch_dtype(dtype)
     case = inputs.layernorm_case(9, 1460 + 4 * dtype + offset, M, N, dtype, 1e-5, mean=-0.25, std=2.0)
-    xbuf = torch.zeros(M * N + 16, dtype=td, device=gpu_device)
+    xbuf = torch.zeros(M * N + 64, dtype=td, device=gpu_device)
     wbuf = torch.zeros(N + 16, dtype=td, device=gpu_device)
     bbuf = torch.zeros(N + 16, dtype=td, device=gpu_device)
     xd = xbuf[offset:offset + M * N].view(M, N)
@@ -91,7 +99,7 @@ def test_walking_form_off_a_boundary_in_place_and_without_bias(gpu_device, N, of
     wl, yl = H.alloc_guarded(M, N, dtype, gpu_device, offset_elems=offset)
     wn, yn = H.alloc_guarded(M, N, dtype, gpu_device, offset_elems=offset)
     assert binding.rmsnorm_unaligned_walk_grid(xd, wd, yr) > 0
-    assert (layernorm.layernorm_unaligned_walk_grid(xd, wd, bd, yl) > 0) == (N >= 2056)
+    assert (layernorm.layernorm_unaligned_walk_grid(xd, wd, bd, yl) > 0) == layernorm_walks(N, dtype)
     H.say(f"walking form off a boundary {inputs.DTYPE_NAMES[dtype]} {M}x{N} offset {offset}")
     binding.rmsnorm_fwd_variant(xd, wd, 1e-5, binding.RMSNORM_VARIANT_UNALIGNED, yr)
     softmax.softmax_fwd_variant(xd, softmax.SOFTMAX_VARIANT_UNALIGNED, ys)
@@ -105,8 +113,8 @@ def test_walking_form_off_a_boundary_in_place_and_without_bias(gpu_device, N, of
     compare.check_layernorm_parity(H.to_host(yl, dtype), want_l, scale, dtype, "layernorm off a boundary")
     compare.check_layernorm_parity(H.to_host(yn, dtype), want_n, scale_n, dtype, "layernorm, no bias")
 
-    # y one element further from the boundary than x: the rows are cut at x's boundaries and
-    # the stores are element-aligned
+    # y one element further from the boundary than x: the rows are cut at x's lines and the
+    # stores are element-aligned
     other = offset + 1
     wr, yr = H.alloc_guarded(M, N, dtype, gpu_device, offset_elems=other)
     ws, ys = H.alloc_guarded(M, N, dtype, gpu_device, offset_elems=other)
