@@ -2,8 +2,9 @@
  * crossentropy.h - C ABI of the MI355X (gfx950) row-wise cross-entropy forward library.
  *
  * The operation is the "cross_ent" row of the paper's "Supported kernel types" table
- * (memory-bound, measured in GB/s, "online log-sum-exp, fused NLL"; results for 4096 x 32k
- * and 8192 x 32k in the table "Kernel performance on H100", Section 7.1).  Per row i with
+ * (memory-bound, measured in GB/s, a running log-sum-exp fused with the target pick; results
+ * for 4096 x 32k and 8192 x 32k in the table "Kernel performance on H100", Section 7.1).  Per
+ * row i with
  * target class t_i:
  *
  *     m_i     = max_j x[i, j]

@@ -2,8 +2,8 @@
  * layernorm.h - C ABI of the MI355X (gfx950) row-wise LayerNorm forward library.
  *
  * The operation is the "layernorm" row of the paper's "Supported kernel types"
- * table (memory-bound, measured in GB/s, "Welford single-pass, float4 loads";
- * results in the table "Kernel performance on H100", Section 7.1):
+ * table (memory-bound, measured in GB/s, one pass with Welford's recurrence in the
+ * starter; results in the table "Kernel performance on H100", Section 7.1):
  *
  *     mean_i = (1/N) sum_j x[i, j]
  *     var_i  = (1/N) sum_j (x[i, j] - mean_i)^2          (biased)

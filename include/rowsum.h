@@ -2,8 +2,9 @@
  * rowsum.h - C ABI of the MI355X (gfx950) row-wise sum reduction library.
  *
  * The operation is the "reduce" row of the paper's "Supported kernel types" table
- * (memory-bound, measured in GB/s, "hierarchical warp shuffle"; results for 8192 x 8192 and
- * 16384 x 4096 in the table "Kernel performance on H100", Section 7.1).  The paper prints
+ * (memory-bound, measured in GB/s, a level-by-level shuffle reduction in the starter; results
+ * for 8192 x 8192 and 16384 x 4096 in the table "Kernel performance on H100", Section 7.1).
+ * The paper prints
  * no formula; its two-dimensional shapes and its throughput column (one read of the input,
  * nothing of comparable size written) fit the sum over the last dimension:
  *

@@ -3,7 +3,8 @@
 // with the other oracle files.
 //
 // The paper lists "cross_ent" in its "Supported kernel types" table (regime Memory,
-// metric GB/s, "online log-sum-exp, fused NLL") and reports it in the table "Kernel
+// metric GB/s; its starter keeps a running log-sum-exp and picks the target's logit in
+// the same pass) and reports it in the table "Kernel
 // performance on H100" (Section 7.1: 4096 x 32k and 8192 x 32k); it prints no formula.
 // The definition used here is the standard one, per row i with target class t_i:
 //
@@ -21,7 +22,7 @@
 // corner cases follow from the formula: -inf logits drop out of the sum; a target on a
 // -inf logit gives +inf; a row holding NaN or +inf, or only -inf, gives NaN.
 //
-// An "online" log-sum-exp (running maximum with rescaling) is a way of computing the
+// A running log-sum-exp (running maximum with rescaling) is a way of computing the
 // same lse in one pass; the oracle takes the two plain passes.
 //
 // Pinned by tests/test_crossentropy_oracle_pins.py.

@@ -5,7 +5,7 @@
 // the other oracle files.
 //
 // The paper lists "layernorm" in its "Supported kernel types" table (regime
-// Memory, metric GB/s, "Welford single-pass, float4 loads") and reports it in the
+// Memory, metric GB/s; its starter takes one pass with Welford's recurrence) and reports it in the
 // table "Kernel performance on H100" (Section 7.1); it prints no formula.  The
 // definition used here is the standard one, written as its plain two-pass form
 // (Welford's recurrence is a way of computing the same two moments in one pass;

@@ -2,7 +2,7 @@
 // the GPU side or with the other oracle files.
 //
 // The paper lists "reduce" in its "Supported kernel types" table (regime Memory, metric
-// GB/s, "hierarchical warp shuffle") and reports 8192 x 8192 and 16384 x 4096 in the table
+// GB/s; its starter reduces level by level with lane shuffles) and reports 8192 x 8192 and 16384 x 4096 in the table
 // "Kernel performance on H100" (Section 7.1); it prints no formula.  The definition used
 // here is the sum over the last dimension:
 //
@@ -14,7 +14,7 @@
 // output is sum_j |X(i, j)| in fp64, the scale against which a floating-point sum's
 // error is measured.
 //
-// A "hierarchical" reduction (per-lane partial sums, then wavefront, then workgroup) is a
+// A reduction by levels (per-lane partial sums, then wavefront, then workgroup) is a
 // way of adding the same numbers in another order; the oracle takes them in index order.
 //
 // Pinned by tests/test_rowsum_oracle_pins.py.

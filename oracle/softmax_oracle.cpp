@@ -5,9 +5,10 @@
 // with the RMSNorm oracle either: each oracle file stands alone.
 //
 // The paper lists "softmax" in its "Supported kernel types" table (regime Memory,
-// metric GB/s, "warp-shuffle reductions, half2 loads"), reports it in the table
-// "Kernel performance on H100" (Section 7.1) and names its stability probe in
-// Section 4 stage 3 ("rows of large identical values"); it prints no formula.
+// metric GB/s; its starter reduces with lane shuffles over two-element fp16 loads),
+// reports it in the table "Kernel performance on H100" (Section 7.1) and names its
+// stability probe, a row whose entries are all one large value, in Section 4 stage 3;
+// it prints no formula.
 // The definition used here is the standard one:
 //
 //     m_i    = max_j X(i,j)

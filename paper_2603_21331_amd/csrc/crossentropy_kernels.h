@@ -2,11 +2,12 @@
 //
 //   loss[i] = log( sum_j exp(x[i, j] - m_i) ) - (x[i, t_i] - m_i),   m_i = max_j x[i, :]
 //
-// The paper lists the kernel in its "Supported kernel types" table (regime Memory, metric
-// GB/s, "online log-sum-exp, fused NLL").  It only reads: every logit crosses HBM once and one
+// The paper lists the kernel in its table of supported kernel types (memory-bound, measured in
+// GB/s; its starter keeps a running log-sum-exp and picks the target's logit in the same pass).
+// It only reads: every logit crosses HBM once and one
 // float per row goes back, so nothing has to stay in registers and rows of any length stream
 // through.  Each thread keeps a running maximum and a running sum of exponentials relative to
-// it (the online log-sum-exp the paper names), in batches: a batch of up to 4 16-byte vectors
+// it (that running log-sum-exp), in batches: a batch of up to 4 16-byte vectors
 // is loaded at once, its maximum taken first, the running sum rescaled at most once per batch,
 // and a subtract, a multiply and one v_exp_f32 spent per element.  The per-thread pairs are
 // combined in a fixed order (DPP maximum, rescale, DPP sum, LDS across wavefronts), so results

@@ -3,9 +3,10 @@
 //   y[i, j] = (x[i, j] - mean_i) * rsqrt(var_i + eps) * w[j] + b[j]
 //   mean_i = (1/N) sum_j x[i, j],  var_i = (1/N) sum_j (x[i, j] - mean_i)^2
 //
-// The paper lists the kernel next to RMSNorm in its "Supported kernel types"
-// table (regime Memory, metric GB/s, "Welford single-pass, float4 loads").  Its
-// starter needs Welford's recurrence because it streams the row; here the row is
+// The paper lists the kernel next to RMSNorm in its table of supported kernel
+// types (memory-bound, measured in GB/s; its starter takes both moments in one
+// pass with Welford's recurrence over 16-byte loads).  The starter needs the
+// recurrence because it streams the row; here the row is
 // read from HBM once with 16-byte non-temporal loads and then sits in registers,
 // so the two moments are taken in two passes over registers, which is both
 // simpler and more accurate than any one-pass formula:

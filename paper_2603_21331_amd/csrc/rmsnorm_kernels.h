@@ -61,7 +61,8 @@ __device__ __forceinline__ float lane_sum_sq(const u32x4 (&v)[CHUNKS]) {
 // correctly rounded divide, root and reciprocal of a plain 1 / sqrt(sum / n + eps) take about
 // fifty dependent instructions there, and replacing them was worth 0.7 % of the kernel at the
 // headline shape.  Here: one fused multiply-add for the mean (inv_n = 1 / n rounded to fp32),
-// the hardware reciprocal square root (the paper's "fast rsqrt", 1 ulp) and one Newton step,
+// the hardware reciprocal square root (1 ulp; the paper's kernel table names a fast reciprocal
+// square root for this kernel too) and one Newton step,
 // which together stay within 1.5 ulp of the exact value.  Arguments that are not normal
 // numbers (zero or subnormal: a zero row with eps = 0; infinite: a sum that overflowed; NaN)
 // take the plain formula, so the IEEE corner cases are unchanged.

@@ -1,10 +1,11 @@
 // Row-wise sum reduction for gfx950 (MI355X):   y[i] = sum_j x[i, j]   in fp32.
 //
-// The paper lists the kernel as "reduce" in its "Supported kernel types" table (regime Memory,
-// metric GB/s, "hierarchical warp shuffle").  It only reads: every element crosses HBM once
+// The paper lists the kernel under the name reduce in its table of supported kernel types
+// (memory-bound, measured in GB/s; its starter reduces level by level with lane shuffles).  It
+// only reads: every element crosses HBM once
 // and one float per row goes back, so the whole design is about keeping enough 16-byte loads
 // in flight; the arithmetic (one widening and one add per element) hides under them.  The
-// hierarchy the paper names is, on CDNA4: a running sum per vector position in each lane, a
+// levels are, on CDNA4: a running sum per vector position in each lane, a
 // fold of those, the DPP butterfly across the 64 lanes of a wavefront, and the wavefront
 // partials added in wave order through LDS.  The order depends on the shape, the thread count
 // and the row's alignment only (no atomics), so results are bit-identical from run to run.

@@ -2,8 +2,9 @@
 //
 //   y[i, j] = exp(x[i, j] - max_j x[i, :]) / sum_j exp(x[i, j] - max_j x[i, :])
 //
-// The paper lists the kernel next to RMSNorm in its "Supported kernel types"
-// table (regime Memory, metric GB/s, "warp-shuffle reductions, half2 loads") and
+// The paper lists the kernel next to RMSNorm in its table of supported kernel
+// types (memory-bound, measured in GB/s; its starter reduces with lane shuffles
+// over two-element fp16 loads) and
 // it has the same reduce-then-scale shape, so it reuses the RMSNorm design: each
 // row is read from HBM once with 16-byte non-temporal loads, held in registers
 // across both reductions, and written once.  What is held differs: after the

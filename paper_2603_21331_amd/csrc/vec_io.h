@@ -3,8 +3,9 @@
 // Every row is moved as 16-byte vectors: one global_load_dwordx4 /
 // global_store_dwordx4 per lane per chunk, so a 64-lane wavefront touches one
 // contiguous 1 KiB span per instruction.  The paper's CUDA starters use the
-// same idea at their hardware's width ("vectorized loads (float4, half2)",
-// Section 5); here the unit is the CDNA4 dwordx4 access.
+// same idea at their hardware's width (Section 5 lists wide vector loads among
+// the properties of its starter kernels); here the unit is the CDNA4 dwordx4
+// access.
 #pragma once
 
 #include <hip/hip_runtime.h>

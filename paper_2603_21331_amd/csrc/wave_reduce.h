@@ -1,7 +1,7 @@
 // Sum over the 64 lanes of a wavefront, result in every lane.
 //
-// The paper's starter uses a "warp shuffle cascade" (kernel table, row rmsnorm)
-// built on 32-lane shuffles; the CDNA4 counterpart is the data-parallel
+// The paper's starter reduces with a cascade of 32-lane shuffles (kernel table,
+// row rmsnorm); the CDNA4 counterpart is the data-parallel
 // primitive (DPP) operand modifier, which lets a v_add_f32 read a neighbouring
 // lane directly, with no LDS traffic.  The order of additions is fixed, and
 // because a + b == b + a bit for bit, both partners of every exchange hold the
