@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 
 #include "build_id.h"
+#include "dispatch_util.h"
 #include "launch_util.h"
 #include "crossentropy_kernels.h"
 
@@ -116,30 +117,16 @@ void launch_packed(const void* x, const int64_t* target, float* loss, float* lse
                      dim3(rms::kPackThreads), 0, stream, x, target, loss, lse, M, (int)N, tile_rows);
 }
 
-// Elements per lane: exactly what the row needs in the chosen lane group, (E - 1) * L < N <=
-// E * L, which is 9 to 16 except for one lane per row, where rows of up to 16 elements need 1 to 16.
-template <int DT, int L, int E = rms::kPackElems>
-void launch_packed_lanes(const void* x, const int64_t* target, float* loss, float* lse, int64_t M,
-                         int64_t N, hipStream_t stream) {
-  if ((N + L - 1) / L == E) launch_packed<DT, L, E>(x, target, loss, lse, M, N, stream);
-  else if constexpr (E > ((L == 1 || L == 8) ? 1 : rms::kPackElems / 2 + 1)) launch_packed_lanes<DT, L, E - 1>(x, target, loss, lse, M, N, stream);
-}
-
 template <int DT>
 int run_typed(const void* x, const int64_t* target, float* loss, float* lse, int64_t M, int64_t N,
               hipStream_t stream, int threads) {
   if (threads == kPackedCode) {
-    int64_t lanes = (N + rms::kPackElems - 1) / rms::kPackElems;   // lanes the row needs
-  // Rows of a multiple of 128 bytes put the rows of narrow lane groups on a few LDS banks; such
-  // rows get at least 8 lanes (at 64 bytes the narrow groups still win here: fewer reductions).
-  if ((N * rms::Storage<DT>::kBytes) % 128 == 0 && lanes < 8) lanes = 8;
-    if (lanes <= 1) launch_packed_lanes<DT, 1>(x, target, loss, lse, M, N, stream);
-    else if (lanes <= 2) launch_packed_lanes<DT, 2>(x, target, loss, lse, M, N, stream);
-    else if (lanes <= 4) launch_packed_lanes<DT, 4>(x, target, loss, lse, M, N, stream);
-    else if (lanes <= 8) launch_packed_lanes<DT, 8>(x, target, loss, lse, M, N, stream);
-    else if (lanes <= 16) launch_packed_lanes<DT, 16>(x, target, loss, lse, M, N, stream);
-    else if (lanes <= 32) launch_packed_lanes<DT, 32>(x, target, loss, lse, M, N, stream);
-    else launch_packed_lanes<DT, 64>(x, target, loss, lse, M, N, stream);
+    // Lanes per row and elements per lane: see with_packed_shape.  Rows of a multiple of 128
+    // bytes get at least 8 lanes (at 64 bytes the narrow groups still win here: fewer
+    // reductions).
+    rms::host::with_packed_shape(N, rms::Storage<DT>::kBytes, 128, [&](auto lanes, auto elems) {
+      launch_packed<DT, decltype(lanes)::value, decltype(elems)::value>(x, target, loss, lse, M, N, stream);
+    });
     return rms::host::launch_status() == hipSuccess ? CROSSENTROPY_OK : CROSSENTROPY_ERR_LAUNCH;
   }
   if (threads < kWave) {

@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 
 #include "build_id.h"
+#include "dispatch_util.h"
 #include "launch_util.h"
 #include "layernorm_kernels.h"
 
@@ -102,14 +103,8 @@ int pick_threads(int64_t nvec, int min_threads, int dtype) {
   return 0;
 }
 
-// 16-byte slots that the element-addressed kernel's workgroup must hold: the whole 16-byte
-// pieces of a row, at most floor(row bytes / 16) wherever the row starts (the slots are counted
-// from the 128-byte line in which the row starts, and those past the last chunk wrap onto the
-// lanes that the row's offset from the line leaves idle in the first).
-int64_t unaligned_slots(int64_t N, int64_t elem) { return N * elem / 16; }
-
-// Threads per row for the element-addressed kernel over that many slots; 0 if the row does
-// not fit in registers.
+// Threads per row for the element-addressed kernel over the whole 16-byte pieces of a row
+// (whole_pieces); 0 if the row does not fit in registers.
 int pick_threads_unaligned(int64_t slots) {
   if (slots <= kSmallRowVectors) return 64;
   for (int g = 256; g <= kMaxThreads; g *= 2)
@@ -176,7 +171,7 @@ constexpr int64_t kWalkBytesPerCu = 48 * 1024;
 // its stores straddle the lines.  walk_grid returns multiples of 64 workgroups only, which is
 // what keeps every row of a workgroup at the same offset from a line.
 int64_t unaligned_walk_grid(int64_t M, int64_t N, int bytes, int* threads) {
-  const int64_t slots = unaligned_slots(N, bytes);
+  const int64_t slots = rms::host::whole_pieces(N, bytes);
   int g = 256;
   while (g < kMaxThreads && slots > (int64_t)g * kWalkMaxChunks) g *= 2;
   if (slots <= rms::kLnWave * kWalkMaxChunks || slots > (int64_t)g * kWalkMaxChunks) return 0;
@@ -245,28 +240,12 @@ void launch_packed(const Args& a) {
                      (float)a.N, a.eps);
 }
 
-// Lanes per row: the narrowest group (1, 2, 4 ... 64 lanes) that holds the row with 16 elements per lane; elements per
-// lane: exactly what the row then needs, (E - 1) * L < N <= E * L, which is 9 to 16 except for
-// one lane per row, where rows of up to 16 elements need 1 to 16.
-template <int DT, int L, int E = rms::kPackElems>
-void launch_packed_lanes(const Args& a) {
-  if ((a.N + L - 1) / L == E) launch_packed<DT, L, E>(a);
-  else if constexpr (E > ((L == 1 || L == 8) ? 1 : rms::kPackElems / 2 + 1)) launch_packed_lanes<DT, L, E - 1>(a);
-}
-
+// Lanes per row and elements per lane: see with_packed_shape.
 template <int DT>
 void dispatch_packed(const Args& a) {
-  int64_t lanes = (a.N + rms::kPackElems - 1) / rms::kPackElems;   // lanes the row needs
-  // Rows of a multiple of 64 bytes put the rows of narrow lane groups on a few LDS banks (64-byte
-  // rows on one or two lanes each: 34 us against 27 on eight); such rows get at least 8 lanes.
-  if ((a.N * rms::Storage<DT>::kBytes) % 64 == 0 && lanes < 8) lanes = 8;
-  if (lanes <= 1) launch_packed_lanes<DT, 1>(a);
-  else if (lanes <= 2) launch_packed_lanes<DT, 2>(a);
-  else if (lanes <= 4) launch_packed_lanes<DT, 4>(a);
-  else if (lanes <= 8) launch_packed_lanes<DT, 8>(a);
-  else if (lanes <= 16) launch_packed_lanes<DT, 16>(a);
-  else if (lanes <= 32) launch_packed_lanes<DT, 32>(a);
-  else launch_packed_lanes<DT, 64>(a);
+  rms::host::with_packed_shape(a.N, rms::Storage<DT>::kBytes, 64, [&](auto lanes, auto elems) {
+    launch_packed<DT, decltype(lanes)::value, decltype(elems)::value>(a);
+  });
 }
 
 // The three-pass streaming kernel: about one batch of four groups per thread, whole
@@ -291,91 +270,34 @@ void launch_generic(const Args& a) {
                      a.eps);
 }
 
-#define LN_CASE(n, call) case n: call; break;
-#define LN_CASES_1_8(M_)                                                          \
-  LN_CASE(1, M_(1)) LN_CASE(2, M_(2)) LN_CASE(3, M_(3)) LN_CASE(4, M_(4))         \
-  LN_CASE(5, M_(5)) LN_CASE(6, M_(6)) LN_CASE(7, M_(7)) LN_CASE(8, M_(8))
-
 template <int DT>
 int dispatch(const Args& a, int threads) {
+  using rms::host::with_shape;
   const int chunks = (a.nvec + threads - 1) / threads;
-  switch (threads) {
-    case 8:
-      if (chunks == 1) launch_subwave<DT, 1, 8>(a); else launch_subwave<DT, 2, 8>(a);
-      break;
-    case 16:
-      if (chunks == 1) launch_subwave<DT, 1, 16>(a); else launch_subwave<DT, 2, 16>(a);
-      break;
-    case 32:
-      if (chunks == 1) launch_subwave<DT, 1, 32>(a); else launch_subwave<DT, 2, 32>(a);
-      break;
-    case 64:
-#define LN_L(c) launch_row<DT, c, 64>(a)
-      switch (chunks) {
-        LN_CASE(1, LN_L(1)) LN_CASE(2, LN_L(2)) LN_CASE(3, LN_L(3)) LN_CASE(4, LN_L(4))
-        default: return LAYERNORM_ERR_UNSUPPORTED;
-      }
-#undef LN_L
-      break;
-    case 256:
-#define LN_L(c) launch_row<DT, c, 256>(a)
-      switch (chunks) { LN_CASES_1_8(LN_L) default: return LAYERNORM_ERR_UNSUPPORTED; }
-#undef LN_L
-      break;
-    case 512:
-#define LN_L(c) launch_row<DT, c, 512>(a)
-      switch (chunks) { LN_CASES_1_8(LN_L) default: return LAYERNORM_ERR_UNSUPPORTED; }
-#undef LN_L
-      break;
-    case 1024:
-#define LN_L(c) launch_row<DT, c, 1024>(a)
-      switch (chunks) { LN_CASES_1_8(LN_L) default: return LAYERNORM_ERR_UNSUPPORTED; }
-#undef LN_L
-      break;
-    default:
-      return LAYERNORM_ERR_UNSUPPORTED;
-  }
-  return LAYERNORM_OK;
+  auto subwave = [&](auto l, auto c) { launch_subwave<DT, decltype(c)::value, decltype(l)::value>(a); };
+  auto row = [&](auto g, auto c) { launch_row<DT, decltype(c)::value, decltype(g)::value>(a); };
+  const bool launched = with_shape<8, 2>(threads, chunks, subwave) || with_shape<16, 2>(threads, chunks, subwave) ||
+                        with_shape<32, 2>(threads, chunks, subwave) || with_shape<64, 4>(threads, chunks, row) ||
+                        with_shape<256, 8>(threads, chunks, row) || with_shape<512, 8>(threads, chunks, row) ||
+                        with_shape<1024, 8>(threads, chunks, row);
+  return launched ? LAYERNORM_OK : LAYERNORM_ERR_UNSUPPORTED;
 }
 
-// Launches the element-aligned row kernel.  The caller has checked that the row fits.
+// Launches the element-addressed row kernel.  The caller has checked that the row fits.
 template <int DT>
 int dispatch_unaligned(const Args& a) {
-  const int slots = (int)unaligned_slots(a.N, rms::Storage<DT>::kBytes);
+  using rms::host::with_shape;
+  const int slots = (int)rms::host::whole_pieces(a.N, rms::Storage<DT>::kBytes);
   int threads = pick_threads_unaligned(slots);
   int walk_threads = 0;
   const int64_t walk = unaligned_walk_grid(a.M, a.N, rms::Storage<DT>::kBytes, &walk_threads);
   if (walk > 0) threads = walk_threads;
   int chunks = (slots + threads - 1) / threads;
   if (chunks < 1) chunks = 1;
-  switch (threads) {
-    case 64:
-#define LN_L(c) launch_row_unaligned<DT, c, 64>(a, walk)
-      switch (chunks) {
-        LN_CASE(1, LN_L(1)) LN_CASE(2, LN_L(2)) LN_CASE(3, LN_L(3)) LN_CASE(4, LN_L(4))
-        default: return LAYERNORM_ERR_UNSUPPORTED;
-      }
-#undef LN_L
-      break;
-    case 256:
-#define LN_L(c) launch_row_unaligned<DT, c, 256>(a, walk)
-      switch (chunks) { LN_CASES_1_8(LN_L) default: return LAYERNORM_ERR_UNSUPPORTED; }
-#undef LN_L
-      break;
-    case 512:
-#define LN_L(c) launch_row_unaligned<DT, c, 512>(a, walk)
-      switch (chunks) { LN_CASES_1_8(LN_L) default: return LAYERNORM_ERR_UNSUPPORTED; }
-#undef LN_L
-      break;
-    case 1024:
-#define LN_L(c) launch_row_unaligned<DT, c, 1024>(a, walk)
-      switch (chunks) { LN_CASES_1_8(LN_L) default: return LAYERNORM_ERR_UNSUPPORTED; }
-#undef LN_L
-      break;
-    default:
-      return LAYERNORM_ERR_UNSUPPORTED;
-  }
-  return LAYERNORM_OK;
+  auto row = [&](auto g, auto c) { launch_row_unaligned<DT, decltype(c)::value, decltype(g)::value>(a, walk); };
+  const bool launched = with_shape<64, 4>(threads, chunks, row) || with_shape<256, 8>(threads, chunks, row) ||
+                        with_shape<512, 8>(threads, chunks, row) || with_shape<1024, 8>(threads, chunks, row);
+  return launched ? LAYERNORM_OK : LAYERNORM_ERR_UNSUPPORTED;
 }
 
 // threads == 0 means the element-wise kernel, -1 the element-aligned row kernel, -2 the
@@ -403,7 +325,7 @@ int run(const void* x, const void* w, const void* b, void* y, int64_t M, int64_t
 
   const bool vec_ok = rows_vectorisable(x, w, b, y, N, dtype);
   const int64_t nvec = vec_ok ? N * elem_bytes(dtype) / 16 : 0;
-  const bool unaligned_fits = pick_threads_unaligned(unaligned_slots(N, elem_bytes(dtype))) != 0;
+  const bool unaligned_fits = pick_threads_unaligned(rms::host::whole_pieces(N, elem_bytes(dtype))) != 0;
   switch (variant) {
     case LAYERNORM_VARIANT_AUTO:
       threads = vec_ok ? (nvec <= kPackedAutoVectors ? -3 : pick_threads(nvec, 8, dtype))
@@ -487,7 +409,7 @@ int layernorm_auto_threads_per_row(int64_t N, int dtype) {
 int64_t layernorm_unaligned_walk_grid(const void* x, const void* w, const void* b, const void* y,
                                       int64_t M, int64_t N, int dtype) {
   if (check_args(x, w, b, y, M, N, 0.0f, dtype) != LAYERNORM_OK) return LAYERNORM_ERR_INVALID_ARG;
-  if (pick_threads_unaligned(unaligned_slots(N, elem_bytes(dtype))) == 0) return 0;
+  if (pick_threads_unaligned(rms::host::whole_pieces(N, elem_bytes(dtype))) == 0) return 0;
   int threads = 0;
   return unaligned_walk_grid(M, N, elem_bytes(dtype), &threads);
 }

@@ -7,6 +7,7 @@
 #include <mutex>
 
 #include "build_id.h"
+#include "dispatch_util.h"
 #include "launch_util.h"
 #include "rmsnorm_kernels.h"
 
@@ -170,7 +171,7 @@ int pick_threads_unaligned(int64_t slots) {
 // pieces of a row, at most floor(row bytes / 16) wherever the row starts (the slots are counted
 // from the 128-byte line in which the row starts, and those past the last chunk wrap onto the
 // lanes that the row's offset from the line leaves idle in the first).
-int64_t slots_per_row(int64_t N, int dtype) { return N * elem_bytes(dtype) / 16; }
+int64_t slots_per_row(int64_t N, int dtype) { return rms::host::whole_pieces(N, elem_bytes(dtype)); }
 
 constexpr int64_t kStreamMaxN = (int64_t)1 << 31;   // the streaming kernel counts groups in an int
 
@@ -430,76 +431,21 @@ void launch_generic(const Args& a) {
                      a.x, a.w, a.y, a.M, a.N, 1.0f / (float)a.N, a.eps);
 }
 
-#define RMS_CASE(n, call) case n: call; break;
-#define RMS_CASES_1_8(M_)                                                             \
-  RMS_CASE(1, M_(1)) RMS_CASE(2, M_(2)) RMS_CASE(3, M_(3)) RMS_CASE(4, M_(4))         \
-  RMS_CASE(5, M_(5)) RMS_CASE(6, M_(6)) RMS_CASE(7, M_(7)) RMS_CASE(8, M_(8))
-#define RMS_CASES_9_16(M_)                                                            \
-  RMS_CASE(9, M_(9)) RMS_CASE(10, M_(10)) RMS_CASE(11, M_(11)) RMS_CASE(12, M_(12))   \
-  RMS_CASE(13, M_(13)) RMS_CASE(14, M_(14)) RMS_CASE(15, M_(15)) RMS_CASE(16, M_(16))
-#define RMS_CASES_17_32(M_)                                                           \
-  RMS_CASE(17, M_(17)) RMS_CASE(18, M_(18)) RMS_CASE(19, M_(19)) RMS_CASE(20, M_(20)) \
-  RMS_CASE(21, M_(21)) RMS_CASE(22, M_(22)) RMS_CASE(23, M_(23)) RMS_CASE(24, M_(24)) \
-  RMS_CASE(25, M_(25)) RMS_CASE(26, M_(26)) RMS_CASE(27, M_(27)) RMS_CASE(28, M_(28)) \
-  RMS_CASE(29, M_(29)) RMS_CASE(30, M_(30)) RMS_CASE(31, M_(31)) RMS_CASE(32, M_(32))
-
 // Launches the row kernel with `threads` threads per row.  The caller has
 // checked threads_can(threads, nvec, DT).
 template <int DT>
 int dispatch_row(const Args& a, int threads) {
+  using rms::host::with_shape;
   const int chunks = (a.nvec + threads - 1) / threads;
-  switch (threads) {
-    case 8:
-      if (chunks == 1) launch_subwave<DT, 1, 8>(a); else launch_subwave<DT, 2, 8>(a);
-      break;
-    case 16:
-      if (chunks == 1) launch_subwave<DT, 1, 16>(a); else launch_subwave<DT, 2, 16>(a);
-      break;
-    case 32:
-      if (chunks == 1) launch_subwave<DT, 1, 32>(a); else launch_subwave<DT, 2, 32>(a);
-      break;
-    case 64:
-#define RMS_L(c) launch_row<DT, c, 64>(a)
-      if constexpr (DT == rms::kFp32) {
-        switch (chunks) {
-          RMS_CASES_1_8(RMS_L) RMS_CASES_9_16(RMS_L) RMS_CASES_17_32(RMS_L)
-          default: return RMSNORM_ERR_UNSUPPORTED;
-        }
-      } else {
-        switch (chunks) {
-          RMS_CASES_1_8(RMS_L) RMS_CASES_9_16(RMS_L)
-          default: return RMSNORM_ERR_UNSUPPORTED;
-        }
-      }
-#undef RMS_L
-      break;
-    case 128:
-#define RMS_L(c) launch_row<DT, c, 128>(a)
-      switch (chunks) { RMS_CASES_1_8(RMS_L) default: return RMSNORM_ERR_UNSUPPORTED; }
-#undef RMS_L
-      break;
-    case 256:
-#define RMS_L(c) launch_row<DT, c, 256>(a)
-      switch (chunks) { RMS_CASES_1_8(RMS_L) default: return RMSNORM_ERR_UNSUPPORTED; }
-#undef RMS_L
-      break;
-    case 512:
-#define RMS_L(c) launch_row<DT, c, 512>(a)
-      switch (chunks) { RMS_CASES_1_8(RMS_L) default: return RMSNORM_ERR_UNSUPPORTED; }
-#undef RMS_L
-      break;
-    case 1024:
-#define RMS_L(c) launch_row<DT, c, 1024>(a)
-      switch (chunks) {
-        RMS_CASES_1_8(RMS_L) RMS_CASES_9_16(RMS_L)
-        default: return RMSNORM_ERR_UNSUPPORTED;
-      }
-#undef RMS_L
-      break;
-    default:
-      return RMSNORM_ERR_UNSUPPORTED;
-  }
-  return RMSNORM_OK;
+  auto subwave = [&](auto l, auto c) { launch_subwave<DT, decltype(c)::value, decltype(l)::value>(a); };
+  auto row = [&](auto g, auto c) { launch_row<DT, decltype(c)::value, decltype(g)::value>(a); };
+  constexpr int kWaveChunks = DT == rms::kFp32 ? kWaveMaxChunks32 : kWaveMaxChunks16;
+  const bool launched =
+      with_shape<8, kSubwaveMaxChunks>(threads, chunks, subwave) || with_shape<16, kSubwaveMaxChunks>(threads, chunks, subwave) ||
+      with_shape<32, kSubwaveMaxChunks>(threads, chunks, subwave) || with_shape<64, kWaveChunks>(threads, chunks, row) ||
+      with_shape<128, kMidMaxChunks>(threads, chunks, row) || with_shape<256, kMidMaxChunks>(threads, chunks, row) ||
+      with_shape<512, kMidMaxChunks>(threads, chunks, row) || with_shape<kBlockMaxThreads, kBlockMaxChunks>(threads, chunks, row);
+  return launched ? RMSNORM_OK : RMSNORM_ERR_UNSUPPORTED;
 }
 
 // Launches the LDS-staged kernel: the narrowest lane group that holds the row, as many whole
@@ -517,72 +463,30 @@ void launch_packed(const Args& a) {
                      1.0f / (float)a.N, a.eps);
 }
 
-// Lanes per row: the narrowest group (1, 2, 4 ... 64 lanes) that holds the row with 16 elements per lane; elements per
-// lane: exactly what the row then needs, (E - 1) * L < N <= E * L, which is 9 to 16 except for
-// one lane per row, where rows of up to 16 elements need 1 to 16.
-template <int DT, int L, int E = rms::kPackElems>
-void launch_packed_lanes(const Args& a) {
-  if ((a.N + L - 1) / L == E) launch_packed<DT, L, E>(a);
-  else if constexpr (E > ((L == 1 || L == 8) ? 1 : rms::kPackElems / 2 + 1)) launch_packed_lanes<DT, L, E - 1>(a);
-}
-
+// Lanes per row and elements per lane: see with_packed_shape.
 template <int DT>
 void dispatch_packed(const Args& a) {
-  int64_t lanes = (a.N + rms::kPackElems - 1) / rms::kPackElems;   // lanes the row needs
-  // Rows of a multiple of 64 bytes put the rows of narrow lane groups on a few LDS banks (64-byte
-  // rows on one or two lanes each: 34 us against 27 on eight); such rows get at least 8 lanes.
-  if ((a.N * rms::Storage<DT>::kBytes) % 64 == 0 && lanes < 8) lanes = 8;
-  if (lanes <= 1) launch_packed_lanes<DT, 1>(a);
-  else if (lanes <= 2) launch_packed_lanes<DT, 2>(a);
-  else if (lanes <= 4) launch_packed_lanes<DT, 4>(a);
-  else if (lanes <= 8) launch_packed_lanes<DT, 8>(a);
-  else if (lanes <= 16) launch_packed_lanes<DT, 16>(a);
-  else if (lanes <= 32) launch_packed_lanes<DT, 32>(a);
-  else launch_packed_lanes<DT, 64>(a);
+  rms::host::with_packed_shape(a.N, rms::Storage<DT>::kBytes, 64, [&](auto lanes, auto elems) {
+    launch_packed<DT, decltype(lanes)::value, decltype(elems)::value>(a);
+  });
 }
 
-// Launches the element-aligned row kernel.  The caller has checked that the row fits.
+// Launches the element-addressed row kernel.  The caller has checked that the row fits.
 template <int DT>
 int dispatch_row_unaligned(const Args& a) {
+  using rms::host::with_shape;
   const int dtype = DT == rms::kFp32 ? RMSNORM_DTYPE_FP32 : RMSNORM_DTYPE_FP16;
   const int slots = (int)slots_per_row(a.N, dtype);
   const int threads = pick_threads_unaligned(slots);
   const int64_t walk = unaligned_walk_grid(a.M, a.N, dtype);
   int chunks = (slots + threads - 1) / threads;
   if (chunks < 1) chunks = 1;
-  switch (threads) {
-    case 64:
-#define RMS_L(c) launch_row_unaligned<DT, c, 64>(a, walk)
-      switch (chunks) {
-        RMS_CASE(1, RMS_L(1)) RMS_CASE(2, RMS_L(2)) RMS_CASE(3, RMS_L(3)) RMS_CASE(4, RMS_L(4))
-        default: return RMSNORM_ERR_UNSUPPORTED;
-      }
-#undef RMS_L
-      break;
-    case 256:
-#define RMS_L(c) launch_row_unaligned<DT, c, 256>(a, walk)
-      switch (chunks) { RMS_CASES_1_8(RMS_L) default: return RMSNORM_ERR_UNSUPPORTED; }
-#undef RMS_L
-      break;
-    case 512:
-#define RMS_L(c) launch_row_unaligned<DT, c, 512>(a, walk)
-      switch (chunks) { RMS_CASES_1_8(RMS_L) default: return RMSNORM_ERR_UNSUPPORTED; }
-#undef RMS_L
-      break;
-    case 1024:
-#define RMS_L(c) launch_row_unaligned<DT, c, 1024>(a, walk)
-      switch (chunks) {
-        RMS_CASES_1_8(RMS_L) RMS_CASES_9_16(RMS_L)
-        default: return RMSNORM_ERR_UNSUPPORTED;
-      }
-#undef RMS_L
-      break;
-    default:
-      return RMSNORM_ERR_UNSUPPORTED;
-  }
-  return RMSNORM_OK;
+  auto row = [&](auto g, auto c) { launch_row_unaligned<DT, decltype(c)::value, decltype(g)::value>(a, walk); };
+  const bool launched = with_shape<64, 4>(threads, chunks, row) || with_shape<256, kMidMaxChunks>(threads, chunks, row) ||
+                        with_shape<512, kMidMaxChunks>(threads, chunks, row) ||
+                        with_shape<kBlockMaxThreads, kBlockMaxChunks>(threads, chunks, row);
+  return launched ? RMSNORM_OK : RMSNORM_ERR_UNSUPPORTED;
 }
-
 
 template <int DT, int CHUNKS>
 void launch_queue(const Args& a) {
@@ -600,14 +504,8 @@ void launch_queue(const Args& a) {
 template <int DT>
 int dispatch_queue(const Args& a) {
   const int chunks = (a.nvec + kQueueThreads - 1) / kQueueThreads;
-#define RMS_L(c) launch_queue<DT, c>(a)
-  switch (chunks) {
-    RMS_CASE(2, RMS_L(2)) RMS_CASE(3, RMS_L(3)) RMS_CASE(4, RMS_L(4)) RMS_CASE(5, RMS_L(5))
-    RMS_CASE(6, RMS_L(6)) RMS_CASE(7, RMS_L(7)) RMS_CASE(8, RMS_L(8))
-    default: return RMSNORM_ERR_UNSUPPORTED;
-  }
-#undef RMS_L
-  return RMSNORM_OK;
+  const bool launched = rms::host::with_chunks<2, 8>(chunks, [&](auto c) { launch_queue<DT, decltype(c)::value>(a); });
+  return launched ? RMSNORM_OK : RMSNORM_ERR_UNSUPPORTED;
 }
 
 // threads == 0 means the element-wise kernel, -1 the element-aligned row kernel, -2 the

@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 
 #include "build_id.h"
+#include "dispatch_util.h"
 #include "launch_util.h"
 #include "rowsum_kernels.h"
 
@@ -108,27 +109,12 @@ void launch_packed(const void* x, float* y, int64_t M, int64_t N, hipStream_t st
                      dim3(rms::kPackThreads), 0, stream, x, y, M, (int)N, tile_rows);
 }
 
-// Elements per lane: exactly what the row needs in the chosen lane group, (E - 1) * L < N <=
-// E * L, which is 9 to 16 except for one lane per row, where rows of up to 16 elements need 1 to 16.
-template <int DT, int L, int E = rms::kPackElems>
-void launch_packed_lanes(const void* x, float* y, int64_t M, int64_t N, hipStream_t stream) {
-  if ((N + L - 1) / L == E) launch_packed<DT, L, E>(x, y, M, N, stream);
-  else if constexpr (E > ((L == 1 || L == 8) ? 1 : rms::kPackElems / 2 + 1)) launch_packed_lanes<DT, L, E - 1>(x, y, M, N, stream);
-}
-
 template <int DT>
 int run_packed(const void* x, float* y, int64_t M, int64_t N, hipStream_t stream) {
-  int64_t lanes = (N + rms::kPackElems - 1) / rms::kPackElems;   // lanes the row needs
-  // Rows of a multiple of 64 bytes put the rows of narrow lane groups on a few LDS banks; such
-  // rows get at least 8 lanes.
-  if ((N * rms::Storage<DT>::kBytes) % 64 == 0 && lanes < 8) lanes = 8;
-  if (lanes <= 1) launch_packed_lanes<DT, 1>(x, y, M, N, stream);
-  else if (lanes <= 2) launch_packed_lanes<DT, 2>(x, y, M, N, stream);
-  else if (lanes <= 4) launch_packed_lanes<DT, 4>(x, y, M, N, stream);
-  else if (lanes <= 8) launch_packed_lanes<DT, 8>(x, y, M, N, stream);
-  else if (lanes <= 16) launch_packed_lanes<DT, 16>(x, y, M, N, stream);
-  else if (lanes <= 32) launch_packed_lanes<DT, 32>(x, y, M, N, stream);
-  else launch_packed_lanes<DT, 64>(x, y, M, N, stream);
+  // Lanes per row and elements per lane: see with_packed_shape.
+  rms::host::with_packed_shape(N, rms::Storage<DT>::kBytes, 64, [&](auto lanes, auto elems) {
+    launch_packed<DT, decltype(lanes)::value, decltype(elems)::value>(x, y, M, N, stream);
+  });
   return rms::host::launch_status() == hipSuccess ? ROWSUM_OK : ROWSUM_ERR_LAUNCH;
 }
 

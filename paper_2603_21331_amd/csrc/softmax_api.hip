@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 
 #include "build_id.h"
+#include "dispatch_util.h"
 #include "launch_util.h"
 #include "softmax_kernels.h"
 
@@ -85,14 +86,8 @@ int pick_threads(int64_t nvec, int min_threads) {
   return 0;
 }
 
-// 16-byte slots that the element-addressed kernel's workgroup must hold: the whole 16-byte
-// pieces of a row, at most floor(row bytes / 16) wherever the row starts (the slots are counted
-// from the 128-byte line in which the row starts, and those past the last chunk wrap onto the
-// lanes that the row's offset from the line leaves idle in the first).
-int64_t unaligned_slots(int64_t N, int64_t elem) { return N * elem / 16; }
-
-// Threads per row for the element-addressed kernel over that many slots (the same bands); 0 if
-// the row does not fit in registers.
+// Threads per row for the element-addressed kernel over the whole 16-byte pieces of a row
+// (whole_pieces; the same bands); 0 if the row does not fit in registers.
 int pick_threads_unaligned(int64_t slots) {
   if (slots <= kSmallRowVectors) return 64;
   for (int g = 256; g <= kMaxThreads; g *= 2)
@@ -177,28 +172,12 @@ void launch_packed(const Args& a) {
                      dim3(rms::kPackThreads), 0, a.stream, a.x, a.y, a.M, n, tile_rows);
 }
 
-// Lanes per row: the narrowest group (1, 2, 4 ... 64 lanes) that holds the row with 16 elements per lane; elements per
-// lane: exactly what the row then needs, (E - 1) * L < N <= E * L, which is 9 to 16 except for
-// one lane per row, where rows of up to 16 elements need 1 to 16.
-template <int DT, int L, int E = rms::kPackElems>
-void launch_packed_lanes(const Args& a) {
-  if ((a.N + L - 1) / L == E) launch_packed<DT, L, E>(a);
-  else if constexpr (E > ((L == 1 || L == 8) ? 1 : rms::kPackElems / 2 + 1)) launch_packed_lanes<DT, L, E - 1>(a);
-}
-
+// Lanes per row and elements per lane: see with_packed_shape.
 template <int DT>
 void dispatch_packed(const Args& a) {
-  int64_t lanes = (a.N + rms::kPackElems - 1) / rms::kPackElems;   // lanes the row needs
-  // Rows of a multiple of 64 bytes put the rows of narrow lane groups on a few LDS banks (64-byte
-  // rows on one or two lanes each: 34 us against 27 on eight); such rows get at least 8 lanes.
-  if ((a.N * rms::Storage<DT>::kBytes) % 64 == 0 && lanes < 8) lanes = 8;
-  if (lanes <= 1) launch_packed_lanes<DT, 1>(a);
-  else if (lanes <= 2) launch_packed_lanes<DT, 2>(a);
-  else if (lanes <= 4) launch_packed_lanes<DT, 4>(a);
-  else if (lanes <= 8) launch_packed_lanes<DT, 8>(a);
-  else if (lanes <= 16) launch_packed_lanes<DT, 16>(a);
-  else if (lanes <= 32) launch_packed_lanes<DT, 32>(a);
-  else launch_packed_lanes<DT, 64>(a);
+  rms::host::with_packed_shape(a.N, rms::Storage<DT>::kBytes, 64, [&](auto lanes, auto elems) {
+    launch_packed<DT, decltype(lanes)::value, decltype(elems)::value>(a);
+  });
 }
 
 // The two-pass streaming kernel: about one batch of four groups per thread, whole wavefronts,
@@ -222,88 +201,31 @@ void launch_generic(const Args& a) {
                      dim3(kGenericThreads), 0, a.stream, a.x, a.y, a.M, a.N);
 }
 
-#define SM_CASE(n, call) case n: call; break;
-#define SM_CASES_1_8(M_)                                                          \
-  SM_CASE(1, M_(1)) SM_CASE(2, M_(2)) SM_CASE(3, M_(3)) SM_CASE(4, M_(4))         \
-  SM_CASE(5, M_(5)) SM_CASE(6, M_(6)) SM_CASE(7, M_(7)) SM_CASE(8, M_(8))
-
 template <int DT>
 int dispatch(const Args& a, int threads) {
+  using rms::host::with_shape;
   const int chunks = (a.nvec + threads - 1) / threads;
-  switch (threads) {
-    case 8:
-      if (chunks == 1) launch_subwave<DT, 1, 8>(a); else launch_subwave<DT, 2, 8>(a);
-      break;
-    case 16:
-      if (chunks == 1) launch_subwave<DT, 1, 16>(a); else launch_subwave<DT, 2, 16>(a);
-      break;
-    case 32:
-      if (chunks == 1) launch_subwave<DT, 1, 32>(a); else launch_subwave<DT, 2, 32>(a);
-      break;
-    case 64:
-#define SM_L(c) launch_row<DT, c, 64>(a)
-      switch (chunks) {
-        SM_CASE(1, SM_L(1)) SM_CASE(2, SM_L(2)) SM_CASE(3, SM_L(3)) SM_CASE(4, SM_L(4))
-        default: return SOFTMAX_ERR_UNSUPPORTED;
-      }
-#undef SM_L
-      break;
-    case 256:
-#define SM_L(c) launch_row<DT, c, 256>(a)
-      switch (chunks) { SM_CASES_1_8(SM_L) default: return SOFTMAX_ERR_UNSUPPORTED; }
-#undef SM_L
-      break;
-    case 512:
-#define SM_L(c) launch_row<DT, c, 512>(a)
-      switch (chunks) { SM_CASES_1_8(SM_L) default: return SOFTMAX_ERR_UNSUPPORTED; }
-#undef SM_L
-      break;
-    case 1024:
-#define SM_L(c) launch_row<DT, c, 1024>(a)
-      switch (chunks) { SM_CASES_1_8(SM_L) default: return SOFTMAX_ERR_UNSUPPORTED; }
-#undef SM_L
-      break;
-    default:
-      return SOFTMAX_ERR_UNSUPPORTED;
-  }
-  return SOFTMAX_OK;
+  auto subwave = [&](auto l, auto c) { launch_subwave<DT, decltype(c)::value, decltype(l)::value>(a); };
+  auto row = [&](auto g, auto c) { launch_row<DT, decltype(c)::value, decltype(g)::value>(a); };
+  const bool launched = with_shape<8, 2>(threads, chunks, subwave) || with_shape<16, 2>(threads, chunks, subwave) ||
+                        with_shape<32, 2>(threads, chunks, subwave) || with_shape<64, 4>(threads, chunks, row) ||
+                        with_shape<256, 8>(threads, chunks, row) || with_shape<512, 8>(threads, chunks, row) ||
+                        with_shape<1024, 8>(threads, chunks, row);
+  return launched ? SOFTMAX_OK : SOFTMAX_ERR_UNSUPPORTED;
 }
 
-// Launches the element-aligned row kernel.  The caller has checked that the row fits.
+// Launches the element-addressed row kernel.  The caller has checked that the row fits.
 template <int DT>
 int dispatch_unaligned(const Args& a) {
-  const int slots = (int)unaligned_slots(a.N, rms::Storage<DT>::kBytes);
+  using rms::host::with_shape;
+  const int slots = (int)rms::host::whole_pieces(a.N, rms::Storage<DT>::kBytes);
   const int threads = pick_threads_unaligned(slots);
   int chunks = (slots + threads - 1) / threads;
   if (chunks < 1) chunks = 1;
-  switch (threads) {
-    case 64:
-#define SM_L(c) launch_row_unaligned<DT, c, 64>(a)
-      switch (chunks) {
-        SM_CASE(1, SM_L(1)) SM_CASE(2, SM_L(2)) SM_CASE(3, SM_L(3)) SM_CASE(4, SM_L(4))
-        default: return SOFTMAX_ERR_UNSUPPORTED;
-      }
-#undef SM_L
-      break;
-    case 256:
-#define SM_L(c) launch_row_unaligned<DT, c, 256>(a)
-      switch (chunks) { SM_CASES_1_8(SM_L) default: return SOFTMAX_ERR_UNSUPPORTED; }
-#undef SM_L
-      break;
-    case 512:
-#define SM_L(c) launch_row_unaligned<DT, c, 512>(a)
-      switch (chunks) { SM_CASES_1_8(SM_L) default: return SOFTMAX_ERR_UNSUPPORTED; }
-#undef SM_L
-      break;
-    case 1024:
-#define SM_L(c) launch_row_unaligned<DT, c, 1024>(a)
-      switch (chunks) { SM_CASES_1_8(SM_L) default: return SOFTMAX_ERR_UNSUPPORTED; }
-#undef SM_L
-      break;
-    default:
-      return SOFTMAX_ERR_UNSUPPORTED;
-  }
-  return SOFTMAX_OK;
+  auto row = [&](auto g, auto c) { launch_row_unaligned<DT, decltype(c)::value, decltype(g)::value>(a); };
+  const bool launched = with_shape<64, 4>(threads, chunks, row) || with_shape<256, 8>(threads, chunks, row) ||
+                        with_shape<512, 8>(threads, chunks, row) || with_shape<1024, 8>(threads, chunks, row);
+  return launched ? SOFTMAX_OK : SOFTMAX_ERR_UNSUPPORTED;
 }
 
 // threads == 0 means the element-wise kernel, -1 the element-aligned row kernel, -2 the
@@ -331,7 +253,7 @@ int run(const void* x, void* y, int64_t M, int64_t N, int dtype, void* stream, i
 
   const bool vec_ok = rows_vectorisable(x, y, N, dtype);
   const int64_t nvec = vec_ok ? N * elem_bytes(dtype) / 16 : 0;
-  const bool unaligned_fits = pick_threads_unaligned(unaligned_slots(N, elem_bytes(dtype))) != 0;
+  const bool unaligned_fits = pick_threads_unaligned(rms::host::whole_pieces(N, elem_bytes(dtype))) != 0;
   switch (variant) {
     case SOFTMAX_VARIANT_AUTO:
       threads = vec_ok ? (nvec <= kPackedAutoVectors ? -3 : pick_threads(nvec, 8))
