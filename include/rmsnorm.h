@@ -12,7 +12,9 @@
  * Inputs are widened exactly to fp32, the sum of squares and both products are
  * carried in fp32, and the result is rounded once (nearest-even) to the
  * storage type.  Domain: finite inputs whose row sum of squares stays below
- * FLT_MAX; NaN and infinity propagate by IEEE rules.
+ * FLT_MAX; NaN and infinity propagate by IEEE rules.  A finite row past that
+ * limit (a square or the sum overflows fp32) comes back as zeros carrying the
+ * sign of x[j] * w[j] from every kernel: the sum is +inf, so the scale is 0.
  *
  * Conventions for every entry point:
  *  - All tensor pointers are DEVICE pointers owned by the caller.  The library

@@ -98,3 +98,42 @@ def test_nan_and_inf_propagate(gpu_device):
             continue
         assert np.array_equal(np.isnan(got), np.isnan(want))
         assert np.array_equal(got[0], got[0]) and not np.isnan(got[0]).any()
+
+
+@pytest.mark.parametrize("dtype", [inputs.FP32, inputs.BF16])
+@pytest.mark.parametrize("N", [197, 2048, 4097, 8192, 40000])
+def test_rows_past_the_stated_domain_give_signed_zeros(gpu_device, N, dtype):
+    """The contract covers rows whose sum of squares stays below FLT_MAX.  Past it (every square
+    overflowing fp32, or only their sum) the fp32 sum is +inf, so rstd is exactly 0 and every
+    kernel returns the row as zeros that carry the sign of x[j] * w[j]: never NaN, never a
+    partly scaled row, and the rows next to it are untouched.  (The fp64 oracle is finite there;
+    such rows are outside the parity claim.)  N covers the LDS-staged, register-resident,
+    element-addressed and streaming kernels."""
+    import compare
+    M = 6
+    z = inputs.normal(3, 640, 0, M * N).reshape(M, N)
+    z[0] = np.where(z[0] < 0, -1e20, 1e20)              # every square overflows
+    z[1] *= 2e18 / np.sqrt(N / 4096)                      # squares finite, their sum overflows (N >= 197)
+    if N < 1024:
+        z[1] = np.where(z[1] < 0, -1.5e19, 1.5e19)      # few elements: squares of 2.25e38 each
+    z[4] = z[0]
+    case = _case(f"past_domain_{N}", z, dtype)
+    want = oracle.rmsnorm_oracle(case["x"], case["w"], case["eps"], dtype)
+    xd = H.to_device(case["x"], dtype, gpu_device)
+    wd = H.to_device(case["w"], dtype, gpu_device)
+    x64 = inputs.storage_to_f64(case["x"], dtype)
+    w64 = inputs.storage_to_f64(case["w"], dtype)
+    ran = 0
+    for mode in H.ALL_MODES:
+        got = H.run_variant(xd, wd, case["eps"], dtype, mode, case["name"])
+        if got is None:
+            continue
+        ran += 1
+        g64 = inputs.storage_to_f64(got, dtype)
+        for r in (0, 1, 4):
+            assert np.all(g64[r] == 0.0), f"{H.mode_name(mode)} row {r}: not all zero"
+            assert np.array_equal(np.signbit(g64[r]), np.signbit(x64[r]) ^ np.signbit(w64)), \
+                f"{H.mode_name(mode)} row {r}: sign of the zeros"
+        keep = [2, 3, 5]
+        compare.check_parity(got[keep], want[keep], dtype, f"{case['name']} [{H.mode_name(mode)}] in-domain rows")
+    assert ran >= 2
