@@ -20,8 +20,9 @@
  * library never allocates, copies or synchronises; work is enqueued on `stream`;
  * x and y are M x N row-major with leading dimension N, w and b have N elements,
  * all of one storage type; b may be NULL (no bias); pointers need only element
- * alignment (rows that are not 16-byte aligned run a register-resident kernel with
- * element-aligned accesses; rows too long for registers, beyond
+ * alignment (rows that are not 16-byte aligned go through LDS several at a time up to 1024
+ * elements and beyond that run a register-resident kernel addressed in bytes, see
+ * LAYERNORM_VARIANT_UNALIGNED; rows too long for registers, beyond
  * layernorm_register_max_n, stream through a three-pass kernel that re-reads them
  * from cache); y == x exactly is allowed, any other overlap is
  * undefined; a call returns LAYERNORM_OK or a negative layernorm_status and

@@ -28,10 +28,11 @@
  *    start is 16-byte aligned (16-byte aligned bases and N * sizeof(dtype) a
  *    multiple of 16) take the aligned kernels; other rows of up to 1024
  *    elements go through LDS several at a time, longer ones take the
- *    register-resident kernel addressed in elements (given enough rows of a
- *    16-bit type); both read x with 128-bit loads on 16-byte boundaries and
- *    write y the same way if x and y sit at the same offset from a boundary,
- *    with element-aligned 128-bit stores otherwise;
+ *    register-resident kernel addressed in bytes; both read x with 128-bit
+ *    loads on 16-byte boundaries (the longer rows laid out from the 128-byte
+ *    line they start in, so that a wavefront's accesses cover whole lines)
+ *    and write y the same way if x and y sit at the same offset from a
+ *    boundary (from a line), with element-aligned 128-bit stores otherwise;
  *    rows too long for registers stream through a two-pass kernel that reads x
  *    a second time from cache.  None of these is an error.
  *  - y == x (exactly in place) is allowed; any other overlap of y with x or w

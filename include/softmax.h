@@ -18,7 +18,8 @@
  * library never allocates, copies or synchronises; work is enqueued on `stream`;
  * x and y are M x N row-major with leading dimension N and share one storage
  * type; pointers need only element alignment (rows that are not 16-byte aligned
- * run the register-resident kernel with element-aligned accesses; rows too long
+ * go through LDS several at a time up to 1024 elements and beyond that run the
+ * register-resident kernel addressed in bytes, SOFTMAX_VARIANT_UNALIGNED; rows too long
  * for registers, beyond softmax_register_max_n, stream through a two-pass kernel
  * that reads them a second time from cache); y == x exactly
  * is allowed, any other overlap is undefined; a call returns SOFTMAX_OK or a

@@ -300,7 +300,7 @@ int dispatch_unaligned(const Args& a) {
   return launched ? LAYERNORM_OK : LAYERNORM_ERR_UNSUPPORTED;
 }
 
-// threads == 0 means the element-wise kernel, -1 the element-aligned row kernel, -2 the
+// threads == 0 means the element-wise kernel, -1 the element-addressed row kernel, -2 the
 // three-pass streaming kernel, -3 the LDS-staged kernel.
 template <int DT>
 int run_typed(const Args& a, int threads) {

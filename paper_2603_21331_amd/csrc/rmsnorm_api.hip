@@ -508,7 +508,7 @@ int dispatch_queue(const Args& a) {
   return launched ? RMSNORM_OK : RMSNORM_ERR_UNSUPPORTED;
 }
 
-// threads == 0 means the element-wise kernel, -1 the element-aligned row kernel, -2 the
+// threads == 0 means the element-wise kernel, -1 the element-addressed row kernel, -2 the
 // two-pass streaming kernel, -3 the LDS-staged kernel, -4 the work-queue kernel.
 template <int DT>
 int run_typed(const Args& a, int threads) {
