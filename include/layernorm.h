@@ -118,9 +118,10 @@ int layernorm_auto_threads_per_row(int64_t N, int dtype);
  * number of resident workgroups of its walking form (a multiple of 64; each takes rows
  * blockIdx, blockIdx + grid, ..., all of which start at the same offset from a 128-byte line,
  * and reads its slices of weight and bias once), or 0 if it would run one workgroup per row
- * and read those slices for every row (fewer than four rows per workgroup; rows of at most
- * 256 or more than 4096 whole 16-byte pieces: N below 2056 or above 32775 elements of a
- * 16-bit type, below 1028 or above 16387 of fp32).  A negative layernorm_status for arguments
+ * and read those slices for every row (fewer than two rows per workgroup, or fewer than four
+ * on a grid well below the best one; rows of at most 256 or more than 4096 whole 16-byte
+ * pieces: N below 2056 or above 32775 elements of a 16-bit type, below 1028 or above 16387 of
+ * fp32).  A negative layernorm_status for arguments
  * layernorm_fwd would reject.  No memory is touched.
  */
 int64_t layernorm_unaligned_walk_grid(const void* x, const void* w, const void* b, const void* y,

@@ -258,9 +258,9 @@ int rmsnorm_select_variant(const void* x, const void* w, const void* y, int64_t 
  * number of resident workgroups of its walking form (a multiple of 64; each takes rows
  * blockIdx, blockIdx + grid, ..., all of which start at the same offset from a 128-byte
  * line, and reads its slices of the weight once), or 0 if it would run one workgroup per
- * row and read the weight slices for every row (fewer than four rows per workgroup; rows of
- * more than 8 16-byte pieces per thread, 7 with 1024 threads; N beyond
- * rmsnorm_unaligned_max_n).  A negative rmsnorm_status for arguments rmsnorm_fwd would
+ * row and read the weight slices for every row (fewer than two rows per workgroup, or
+ * fewer than four on a grid well below the best one; rows of more than 8 16-byte pieces
+ * per thread, 7 with 1024 threads; N beyond rmsnorm_unaligned_max_n).  A negative rmsnorm_status for arguments rmsnorm_fwd would
  * reject.  No memory is touched.
  */
 int64_t rmsnorm_unaligned_walk_grid(const void* x, const void* w, const void* y, int64_t M,

@@ -223,12 +223,14 @@ def test_unaligned_walk_grid_query():
     X, W, Y = P, P + (1 << 30), P + (2 << 30)
     q = lib.rmsnorm_unaligned_walk_grid
     assert q(X, W, Y, 8192, 4097, 1) == 1024 and q(X, W, Y, 16384, 8191, 2) == 512
-    assert q(X, W, Y, 16384, 1025, 1) == 13 * 256 and q(X, W, Y, 8191, 1537, 1) == 7 * 256
-    assert q(X, W, Y, 3000, 4097, 1) == 512 and q(X, W, Y, 4096, 20481, 2) == 256
+    assert q(X, W, Y, 16384, 1025, 1) == 13 * 256 and q(X, W, Y, 8191, 1537, 1) == 8 * 256
+    assert q(X, W, Y, 3000, 4097, 1) == 768 and q(X, W, Y, 4096, 20481, 2) == 256
     assert q(X + 6, W + 2, Y + 22, 8192, 4097, 1) == 1024      # same offset from a line
     assert q(X, W, Y + 2, 8192, 4097, 1) == 1024               # different offsets: cut at x's lines
     assert q(X, W, Y, 8192, 4097, 0) == 512 and q(X, W, Y, 16384, 4097, 0) == 512   # fp32 walks too
-    assert q(X, W, Y, 1500, 4097, 1) == 0                      # too few rows
+    # two or three rows per workgroup are enough where the grid is close to the best one
+    assert q(X, W, Y, 2048, 4097, 1) == 1024 and q(X, W, Y, 1024, 8191, 2) == 512
+    assert q(X, W, Y, 1500, 4097, 1) == 0 and q(X, W, Y, 768, 8191, 2) == 0    # too few rows
     assert q(X, W, Y, 1061, 131079, 1) == 0                    # more than 8 groups per thread
     assert q(X, W, Y, 1061, 57343, 1) == 256 and q(X, W, Y, 1061, 65535, 1) == 0   # 1024 threads: 7
     assert q(X, W, Y, 4, 1 << 20, 1) == 0                      # does not fit in registers
