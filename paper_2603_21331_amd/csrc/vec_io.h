@@ -178,7 +178,7 @@ struct RowCut {
 };
 
 template <int EB>
-__device__ __forceinline__ RowCut row_cut(const void* row, int n) {
+__host__ __device__ __forceinline__ RowCut row_cut(const void* row, int n) {
   RowCut c;
   c.off = (int)(reinterpret_cast<uintptr_t>(row) & (kLineBytes - 1));
   c.first = (c.off + 15) >> 4;
@@ -202,7 +202,7 @@ __device__ __forceinline__ RowCut row_cut(const void* row, int n) {
 // row classes r mod 64 it keeps every row of a resident workgroup at one offset from a line.
 constexpr bool kXcdRowBlocks = true;
 
-__device__ __forceinline__ int64_t xcd_block_row(unsigned block) {
+__host__ __device__ __forceinline__ int64_t xcd_block_row(unsigned block) {
   if constexpr (kXcdRowBlocks) return (int64_t)(block & ~63u) + ((block & 7u) << 3) + ((block >> 3) & 7u);
   else return (int64_t)block;
 }
