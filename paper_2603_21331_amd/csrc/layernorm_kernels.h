@@ -593,6 +593,9 @@ layernorm_row_unaligned_kernel(const void* x, const void* __restrict__ w, const 
   const int lane = t & (kLnWave - 1);
   const int wave = t / kLnWave;
   const bool has_bias = b != nullptr;
+  // the mean through 1 / N and the reciprocal root through the hardware instruction plus a
+  // Newton step, as in the resident kernel: both sit between the row's arrival and its stores
+  const float inv_n = 1.0f / n;
   const u32x4 zero = {0u, 0u, 0u, 0u};
   int slot = 0;
   const int64_t first_row = xcd_block_row(blockIdx.x);   // either way the grid is a multiple of 64
@@ -671,7 +674,7 @@ layernorm_row_unaligned_kernel(const void* x, const void* __restrict__ w, const 
       __syncthreads();
       s1 = sum_waves<WAVES>(part_a[slot]);
     }
-    const float mean_shifted = s1 / n;
+    const float mean_shifted = s1 * inv_n;
 
     tail = tail_ok ? tail - mean_shifted : 0.f;
     float sq[4] = {tail * tail, 0.f, 0.f, 0.f};
@@ -691,7 +694,7 @@ layernorm_row_unaligned_kernel(const void* x, const void* __restrict__ w, const 
       s2 = sum_waves<WAVES>(part_b[slot]);
       slot ^= 1;
     }
-    const float rstd = ln_rstd(s2, n, eps);
+    const float rstd = ln_rstd_fast(s2, inv_n, eps);
 
     if constexpr (WALK) {
 #pragma unroll
