@@ -117,12 +117,17 @@ def compile_library(name: str, verbose: bool = False) -> str:
     return lib_path(name)
 
 
-def build(verbose: bool = False) -> str:
-    """Compiles every library, whether or not a built one is there; returns the path of the
-    RMSNorm library."""
-    for name in ("measure", "rowsum", "softmax", "layernorm", "crossentropy"):
-        compile_library(name, verbose)
-    return compile_library("rmsnorm", verbose)
+def build(verbose: bool = False, jobs: int = 0) -> str:
+    """Compiles every library, whether or not a built one is there (several hipcc processes side
+    by side: the libraries do not depend on each other); returns the path of the RMSNorm
+    library."""
+    from concurrent.futures import ThreadPoolExecutor
+    names = ["rmsnorm", "layernorm", "softmax", "crossentropy", "rowsum", "measure"]   # longest first
+    jobs = jobs or max(1, min(len(names), (os.cpu_count() or 2) // 2))
+    with ThreadPoolExecutor(max_workers=jobs) as pool:
+        for path in pool.map(lambda n: compile_library(n, verbose), names):
+            pass
+    return lib_path("rmsnorm")
 
 
 def ensure(name: str) -> str:
