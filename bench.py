@@ -192,9 +192,11 @@ def main() -> int:
     ap.add_argument("--cols", type=int, default=8192,
                     help="N (the headline workload is 8192; other values run the same bf16 recipe at "
                          "that row length, e.g. 197 for rows that are not 16-byte aligned)")
-    ap.add_argument("--settle-ms", type=float, default=60.0,
+    ap.add_argument("--settle-ms", type=float, default=100.0,
                     help="untimed back-to-back launches for this many milliseconds before the "
-                         "warm-up, so that the clock transient after idle is over (0 = none)")
+                         "warm-up, so that the clock transient after idle is over (0 = none; "
+                         "measured with a timed region of 20 launches: 20 ms of settling leave the "
+                         "figure 1 to 1.5 %% low, 60 and 200 ms give the same)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--all-configs", action="store_true",
                     help="after the headline measurement, also time the other four workloads "
