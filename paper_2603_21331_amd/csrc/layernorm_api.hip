@@ -184,9 +184,17 @@ template <int DT, int CHUNKS, int G>
 void launch_row_unaligned(const Args& a, int64_t walk) {
   if constexpr (CHUNKS <= kWalkMaxChunks) {
     if (walk > 0) {
-      RMS_LAUNCH((rms::layernorm_row_unaligned_kernel<DT, CHUNKS, G, true, true>),
-                         dim3((unsigned)walk), dim3(G), 0, a.stream, a.x, a.w, a.b, a.y, a.M,
-                         (int)a.N, (float)a.N, a.eps);
+      // The 16-bit types with the next row requested ahead (2 to 15 % faster: fp16 16384 x 2057
+      // 40.7 -> 34.7 us, bf16 4096 x 20481 69.4 -> 61.3, fp16 16384 x 8191 99.6 -> 97.1); fp32 rows,
+      // with half the elements to work on per byte, are level to 4 % slower that way.
+      if constexpr (DT != rms::kFp32)
+        RMS_LAUNCH((rms::layernorm_walk_kernel<DT, CHUNKS, G, true>),
+                           dim3((unsigned)walk), dim3(G), 0, a.stream, a.x, a.w, a.b, a.y, a.M,
+                           (int)a.N, (float)a.N, a.eps);
+      else
+        RMS_LAUNCH((rms::layernorm_row_unaligned_kernel<DT, CHUNKS, G, true, true>),
+                           dim3((unsigned)walk), dim3(G), 0, a.stream, a.x, a.w, a.b, a.y, a.M,
+                           (int)a.N, (float)a.N, a.eps);
       return;
     }
   }

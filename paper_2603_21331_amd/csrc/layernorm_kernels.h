@@ -730,6 +730,182 @@ layernorm_row_unaligned_kernel(const void* x, const void* __restrict__ w, const 
 }
 
 // ---------------------------------------------------------------------------
+// The walking form of the kernel above with the next row requested ahead, as the resident
+// kernel for aligned rows does: two packed register copies of a row take turns, and while one
+// is reduced, scaled and stored the other is being filled with the workgroup's next row
+// (first + k * gridDim, all at the workgroup's offset from a line, so one cut serves them
+// all).  Without it a workgroup has nothing in flight while it works on a row, and with the
+// four wavefronts per SIMD that the centred row, weight and bias leave room for, that shows in
+// the 16-bit types, which is where this kernel is used (fp16 16384 x 2057: 40.7 -> 34.7 us;
+// bf16 4096 x 20481: 69.4 -> 61.3; fp16 8192 x 4097: 28.4 -> 27.8).  No load sits in
+// a branch: a slot that the row does not cover reads the row's first whole slot instead and is
+// masked afterwards, the last step requests its own row again, and the loop is unrolled twice
+// so that no register is copied from one copy to the other.
+// ---------------------------------------------------------------------------
+template <int DT>
+__device__ __forceinline__ uint32_t ln_elem_raw(const void* p, int64_t i) {
+  if constexpr (DT == kFp32) return static_cast<const uint32_t*>(p)[i];
+  else return static_cast<const uint16_t*>(p)[i];
+}
+
+// What a thread of the walking form keeps for the whole launch.
+template <int CHUNKS>
+struct LnWalkLane {
+  RowCut cut;
+  int slot_bytes[CHUNKS];       // byte offset of the thread's slot of chunk c from the row's line
+  bool holds[CHUNKS];           // whether the row covers that slot whole
+  bool edge_ok;                 // whether the thread holds a single leading or trailing element
+  int edge_col;                 // ... and which
+};
+
+// One row: requests row `pre` into (nxt, nxt_first, nxt_edge), then reduces, scales and stores
+// the row held in (cur, cur_first, cur_edge).
+template <int DT, int CHUNKS, int G, bool NT>
+__device__ __forceinline__ void ln_walk_step(
+    const void* x, void* y, int64_t row, int64_t pre, int n_cols, const LnWalkLane<CHUNKS>& ln,
+    int lane, int wave, const u32x4 (&cur)[CHUNKS], uint32_t cur_first, uint32_t cur_edge,
+    u32x4 (&nxt)[CHUNKS], uint32_t& nxt_first, uint32_t& nxt_edge, u32x4 (&wv)[CHUNKS],
+    u32x4 (&bv)[CHUNKS], float edge_w, float edge_b, bool has_bias, float inv_n, float eps,
+    float (&part_a)[G / kLnWave], float (&part_b)[G / kLnWave]) {
+  using S = Storage<DT>;
+  constexpr int VEC = S::kVec;
+  constexpr int WAVES = G / kLnWave;
+  const char* xp = static_cast<const char*>(x) + pre * n_cols * S::kBytes;
+#pragma unroll
+  for (int c = 0; c < CHUNKS; ++c) nxt[c] = load_vec_unaligned<NT>(xp - ln.cut.off + ln.slot_bytes[c]);
+  nxt_first = ln_elem_raw<DT>(xp, 0);
+  nxt_edge = ln_elem_raw<DT>(xp, ln.edge_col);
+
+  const float shift = ln_first_value<DT>(cur_first);
+  float tail = ln.edge_ok ? ln_first_value<DT>(cur_edge) - shift : 0.f;
+  float f[CHUNKS][VEC];
+  float acc[4] = {tail, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int c = 0; c < CHUNKS; ++c) {
+    S::unpack(cur[c], f[c]);
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) {
+      f[c][k] = ln.holds[c] ? f[c][k] - shift : 0.f;
+      acc[k & 3] += f[c][k];
+    }
+  }
+  float s1 = wave_sum((acc[0] + acc[1]) + (acc[2] + acc[3]));
+  if constexpr (WAVES > 1) {
+    if (lane == 0) part_a[wave] = s1;
+    __syncthreads();
+    s1 = sum_waves<WAVES>(part_a);
+  }
+  const float mean_shifted = s1 * inv_n;
+
+  tail = ln.edge_ok ? tail - mean_shifted : 0.f;
+  float sq[4] = {tail * tail, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int c = 0; c < CHUNKS; ++c) {
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) {
+      f[c][k] = ln.holds[c] ? f[c][k] - mean_shifted : 0.f;
+      sq[k & 3] = __builtin_fmaf(f[c][k], f[c][k], sq[k & 3]);
+    }
+  }
+  float s2 = wave_sum((sq[0] + sq[1]) + (sq[2] + sq[3]));
+  if constexpr (WAVES > 1) {
+    if (lane == 0) part_b[wave] = s2;
+    __syncthreads();
+    s2 = sum_waves<WAVES>(part_b);
+  }
+  const float rstd = ln_rstd_fast(s2, inv_n, eps);
+
+  // weight and bias stay packed from row to row: widened once for the whole launch they would
+  // take the registers that the second copy of the row needs
+  forget_unpacked<CHUNKS>(wv);
+  forget_unpacked<CHUNKS>(bv);
+  char* yr = static_cast<char*>(y) + row * n_cols * S::kBytes;
+#pragma unroll
+  for (int c = 0; c < CHUNKS; ++c)
+    if (ln.holds[c])
+      store_vec_unaligned<NT>(yr - ln.cut.off + ln.slot_bytes[c], ln_scale<DT>(f[c], wv[c], bv[c], has_bias, rstd));
+  if (ln.edge_ok) {
+    const float tq = (tail * rstd) * edge_w;
+    S::store_one(yr, ln.edge_col, has_bias ? tq + edge_b : tq);
+  }
+}
+
+template <int DT, int CHUNKS, int G, bool NT>
+__global__ void __launch_bounds__(G) __attribute__((amdgpu_waves_per_eu(4)))
+layernorm_walk_kernel(const void* x, const void* __restrict__ w, const void* __restrict__ b, void* y,
+                      int64_t M, int n_cols, float n, float eps) {
+  using S = Storage<DT>;
+  constexpr int WAVES = G / kLnWave;
+  constexpr int kGroupBytes = 16;
+  constexpr int kTailThread = 16;                       // first thread that takes a trailing element
+  __shared__ __attribute__((aligned(16))) float part_a[2][WAVES];
+  __shared__ __attribute__((aligned(16))) float part_b[2][WAVES];
+  const int t = threadIdx.x;
+  const int lane = t & (kLnWave - 1);
+  const int wave = t / kLnWave;
+  const bool has_bias = b != nullptr;
+  const u32x4 zero = {0u, 0u, 0u, 0u};
+  const float inv_n = 1.0f / n;
+  int64_t row = xcd_block_row(blockIdx.x);               // the grid is a multiple of 64
+  if (row >= M) return;
+  const int64_t stride = gridDim.x;
+
+  LnWalkLane<CHUNKS> ln;
+  ln.cut = row_cut<S::kBytes>(static_cast<const char*>(x) + row * n_cols * S::kBytes, n_cols);
+  // Lane t holds slot c * G + t in chunk c, except that the lanes of chunk 0 before the row's
+  // first whole slot take the slots past the last chunk.
+#pragma unroll
+  for (int c = 0; c < CHUNKS; ++c) {
+    const int slot = (c == 0 && t < ln.cut.first) ? CHUNKS * G + t : c * G + t;
+    ln.holds[c] = (c > 0 && c < CHUNKS - 1) || slot < ln.cut.end;
+    ln.slot_bytes[c] = (ln.holds[c] ? slot : ln.cut.first) * kGroupBytes;
+  }
+  ln.edge_ok = t < ln.cut.head || (t >= kTailThread && t - kTailThread < ln.cut.tail);
+  ln.edge_col = !ln.edge_ok ? 0 : t < ln.cut.head ? t : n_cols - ln.cut.tail + (t - kTailThread);
+
+  const char* wl = static_cast<const char*>(w) - ln.cut.off;
+  const char* bl = static_cast<const char*>(b) - ln.cut.off;
+  u32x4 wv[CHUNKS], bv[CHUNKS];
+#pragma unroll
+  for (int c = 0; c < CHUNKS; ++c) {
+    wv[c] = bv[c] = zero;
+    if (ln.holds[c]) {
+      wv[c] = load_vec_unaligned<false>(wl + ln.slot_bytes[c]);
+      if (has_bias) bv[c] = load_vec_unaligned<false>(bl + ln.slot_bytes[c]);
+    }
+  }
+  float edge_w = 0.f, edge_b = 0.f;
+  if (ln.edge_ok) {
+    edge_w = S::load_one(w, ln.edge_col);
+    edge_b = has_bias ? S::load_one(b, ln.edge_col) : 0.f;
+  }
+
+  u32x4 ra[CHUNKS], rb[CHUNKS];
+  uint32_t first_a, first_b = 0, edge_a, edge_b_raw = 0;
+  {
+    const char* xr = static_cast<const char*>(x) + row * n_cols * S::kBytes;
+#pragma unroll
+    for (int c = 0; c < CHUNKS; ++c) ra[c] = load_vec_unaligned<NT>(xr - ln.cut.off + ln.slot_bytes[c]);
+    first_a = ln_elem_raw<DT>(xr, 0);
+    edge_a = ln_elem_raw<DT>(xr, ln.edge_col);
+  }
+  while (true) {
+    int64_t next = row + stride;
+    ln_walk_step<DT, CHUNKS, G, NT>(x, y, row, next < M ? next : row, n_cols, ln, lane, wave, ra, first_a, edge_a,
+                                    rb, first_b, edge_b_raw, wv, bv, edge_w, edge_b, has_bias, inv_n, eps,
+                                    part_a[0], part_b[0]);
+    if (next >= M) break;                              // uniform over the workgroup
+    row = next;
+    next = row + stride;
+    ln_walk_step<DT, CHUNKS, G, NT>(x, y, row, next < M ? next : row, n_cols, ln, lane, wave, rb, first_b, edge_b_raw,
+                                    ra, first_a, edge_a, wv, bv, edge_w, edge_b, has_bias, inv_n, eps,
+                                    part_a[1], part_b[1]);
+    if (next >= M) break;
+    row = next;
+  }
+}
+
+// ---------------------------------------------------------------------------
 // Rows too long for registers: three streaming passes by one workgroup per row (the shifted
 // sum for the mean, the squares of the centred values, the write), four 16-byte groups
 // requested at a time; passes two and three read the row from L2 or the Infinity Cache.
