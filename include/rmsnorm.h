@@ -100,7 +100,8 @@ typedef enum {
                                    weight in registers and draw rows from counters in device
                                    memory; 16-byte aligned rows of 513 to 4096 vectors of 16 bytes
                                    (8 KiB to 64 KiB), fewer than 2^30 rows.  What AUTO takes for rows
-                                   of 16 KiB and more once the launch reads 96 MiB, on streams
+                                   of 16 KiB and more once the launch reads 96 MiB (192 MiB beyond
+                                   32 KiB rows), and for shorter ones from 320 MiB on, on streams
                                    that have counters (see rmsnorm_fwd) */
 } rmsnorm_variant;
 

@@ -253,7 +253,10 @@ bool queue_can(int64_t M, int64_t nvec) {
 //   rows of 40 to 64 KiB: one workgroup per compute unit, which then has to request its next
 //     row before it stores the current one, 8 shards, blocks of 2 rows: 85.7 (85.6), 86.2
 //     (87.6), 86.7 (90.7).
-// Rows of 10 and 12 KiB gain under 1 % and stay with one workgroup per row.
+// Rows of 10 to 14 KiB gain under 1 % at that size; from x of 320 MiB on they gain 1 to 3.5 %
+// (32768 rows of 10 / 12 / 14 KiB: 107.4 -> 105.7, 125.9 -> 125.0, 149.1 -> 143.8 us; fp32
+// 32768 x 3072: 128.5 -> 124.2; 65536 x 5120 bf16: 216.8 -> 210.9).  Rows of 8 KiB and less
+// would be one chunk per thread of the 512, and lose 4 to 20 % to one workgroup per row.
 QueuePlan queue_plan(int64_t row_bytes) {
   const int cus = compute_units();
   QueuePlan p;
@@ -274,10 +277,12 @@ QueuePlan queue_plan(int64_t row_bytes) {
 constexpr int64_t kQueueMinRowBytes = 16 * 1024;
 constexpr int64_t kQueueMinBytes = (int64_t)96 << 20;        // rows up to 32 KiB
 constexpr int64_t kQueueMinBytesLong = (int64_t)192 << 20;   // longer rows
+constexpr int64_t kQueueMinBytesShort = (int64_t)320 << 20;  // rows below 16 KiB
 
 bool queue_pays(int64_t M, int64_t nvec) {
   const int64_t row_bytes = nvec * 16;
-  if (!queue_can(M, nvec) || row_bytes < kQueueMinRowBytes) return false;
+  if (!queue_can(M, nvec)) return false;
+  if (row_bytes < kQueueMinRowBytes) return M * row_bytes >= kQueueMinBytesShort;
   return M * row_bytes >= (row_bytes <= 32 * 1024 ? kQueueMinBytes : kQueueMinBytesLong);
 }
 

@@ -257,10 +257,13 @@ def test_queue_plan_and_dispatch_threshold():
     # a block is the largest power of two of rows within 128 KiB
     assert binding.rmsnorm_queue_plan(100000, 5120, bf16)[3] == 8        # 10 KiB rows
     assert binding.rmsnorm_queue_plan(100000, 32768, bf16)[3] == 2       # 64 KiB rows
-    # small launches and rows under 16 KiB stay with one workgroup per row
+    # small launches stay with one workgroup per row; rows under 16 KiB take the kernel from 320 MiB on
     assert binding.rmsnorm_queue_plan(4096, 8192, bf16)[0] is False
     assert binding.rmsnorm_queue_plan(6144, 8192, bf16)[0] is True
-    assert binding.rmsnorm_queue_plan(1 << 20, 4104, bf16)[0] is False
+    assert binding.rmsnorm_queue_plan(32767, 5120, bf16)[0] is False
+    assert binding.rmsnorm_queue_plan(32768, 5120, bf16)[0] is True
+    assert binding.rmsnorm_queue_plan(1 << 20, 4104, bf16)[0] is True
+    assert binding.rmsnorm_queue_plan(40000, 4104, bf16)[0] is False
     lib = binding.load()
     plan = lib.rmsnorm_queue_plan
     assert plan(16, 4096, bf16, None, None, None, None) == binding.RMSNORM_ERR_UNSUPPORTED   # 512 vectors

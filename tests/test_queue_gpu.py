@@ -171,6 +171,30 @@ def test_automatic_path_takes_the_queue_for_large_launches(gpu_device):
         assert np.array_equal(H.to_host(y, inputs.BF16), flat)
 
 
+def test_automatic_path_takes_the_queue_for_rows_under_16_kib_from_320_mib_on(gpu_device):
+    """32768 rows of 10 KiB (320 MiB of x): the automatic path runs the work-queue kernel, with
+    the bits of 512 threads per row; one row less and it does not.  A sample of rows against
+    the oracle."""
+    M, N = 32768, 5120
+    bf16 = binding.RMSNORM_DTYPE_BF16
+    assert binding.rmsnorm_queue_plan(M, N, bf16)[0] and not binding.rmsnorm_queue_plan(M - 1, N, bf16)[0]
+    gen = torch.Generator(device=gpu_device).manual_seed(41)
+    x = torch.randn((M, N), generator=gen, device=gpu_device).to(torch.bfloat16)
+    w = (1.0 + 0.1 * torch.randn(N, generator=gen, device=gpu_device)).to(torch.bfloat16)
+    assert binding.rmsnorm_select_variant(x, w, torch.empty_like(x)) == binding.RMSNORM_VARIANT_QUEUE
+    H.say("queue auto, 10 KiB rows")
+    got = binding.rmsnorm_fwd(x, w, EPS)
+    flat = binding.rmsnorm_fwd_tuned(x, w, EPS, 512)
+    torch.cuda.synchronize()
+    assert torch.equal(got.view(torch.int16), flat.view(torch.int16))
+    rows = torch.tensor([0, 1, 7, 8, 4095, 4096, 20000, M - 9, M - 1], device=gpu_device)
+    xs = x[rows].contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+    ws = w.view(torch.int16).cpu().numpy().view(np.uint16)
+    want = oracle.rmsnorm_oracle(xs, ws, EPS, inputs.BF16, 0)
+    compare.check_parity(got[rows].contiguous().view(torch.int16).cpu().numpy().view(np.uint16), want, inputs.BF16,
+                         "sampled rows of 32768 x 5120")
+
+
 def test_a_captured_call_does_not_use_the_shared_counters(gpu_device):
     """Under stream capture the automatic path takes the one-workgroup-per-row kernel (a graph
     may be replayed next to anything) and the forced variant reports that it cannot run; the
