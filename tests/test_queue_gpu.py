@@ -144,6 +144,27 @@ def test_two_streams_with_a_workspace_each(gpu_device):
         assert int(spaces[k].abs().max().item()) == 0
 
 
+def test_automatic_path_on_two_streams_at_once(gpu_device):
+    """rmsnorm_fwd on two streams whose kernels may overlap: each stream gets its own block of
+    the library's counters, so neither launch sees the other's tickets."""
+    cases = [inputs.random_case(6, 985 + k, 6144, 8192, inputs.BF16, EPS) for k in range(2)]
+    xs = [H.to_device(c["x"], inputs.BF16, gpu_device) for c in cases]
+    ws_ = [H.to_device(c["w"], inputs.BF16, gpu_device) for c in cases]
+    ys = [torch.empty_like(x) for x in xs]
+    flat = [H.to_host(binding.rmsnorm_fwd_tuned(x, w, EPS, 512), inputs.BF16) for x, w in zip(xs, ws_)]
+    streams = [torch.cuda.Stream(device=gpu_device) for _ in cases]
+    torch.cuda.synchronize()
+    H.say("queue auto on two streams")
+    for rep in range(6):
+        for k, s in enumerate(streams):
+            with torch.cuda.stream(s):
+                assert binding.rmsnorm_select_variant(xs[k], ws_[k], ys[k]) == binding.RMSNORM_VARIANT_QUEUE
+                binding.rmsnorm_fwd(xs[k], ws_[k], EPS, ys[k])
+    torch.cuda.synchronize()
+    for k in range(2):
+        assert np.array_equal(H.to_host(ys[k], inputs.BF16), flat[k])
+
+
 def test_automatic_path_takes_the_queue_for_large_launches(gpu_device):
     """96 MiB of 16 KiB rows: rmsnorm_fwd runs the work-queue kernel on the stream's own counters
     (on the default stream, on a side stream, several times in a row), with the bits of one
