@@ -69,12 +69,26 @@ typedef enum {
   LAYERNORM_VARIANT_STREAM = 6,    /* three streaming passes with 128-bit accesses for rows too
                                       long for registers (the second and third read come from
                                       cache); any alignment, N < 2^31 */
-  LAYERNORM_VARIANT_PACKED = 7     /* runs of short rows copied through LDS with 128-bit accesses,
+  LAYERNORM_VARIANT_PACKED = 7,    /* runs of short rows copied through LDS with 128-bit accesses,
                                       1 to 64 lanes per row: N <= 1024, any alignment (the stores
                                       fall on 16-byte boundaries if x and y are congruent modulo 16
                                       bytes); what rows that are not 16-byte aligned take up to that
                                       length, and aligned rows that are very short or fill their
                                       lane group badly */
+  LAYERNORM_VARIANT_QUEUE = 8      /* resident workgroups that keep their slices of weight and
+                                      bias in registers and draw their rows from counters in
+                                      device memory, in blocks of consecutive rows per XCD
+                                      (see layernorm_queue_plan): 16-byte aligned rows that 256
+                                      or 512 threads hold with at most 24 elements each, fewer
+                                      than 2^30 rows; what the automatic path takes for such
+                                      rows in launches of a few hundred megabytes.  The counters
+                                      are the library's own (a static array of 128 KiB of device
+                                      memory per GPU, one 4 KiB block per stream for up to 32
+                                      streams per device, zero between launches); a stream that
+                                      gets none (the 33rd, the per-thread default stream, a
+                                      stream under graph capture) gets LAYERNORM_ERR_UNSUPPORTED
+                                      when the variant is forced and the other kernels on the
+                                      automatic path.  Same bits as the other kernels. */
 } layernorm_variant;
 
 /*
@@ -126,6 +140,19 @@ int layernorm_auto_threads_per_row(int64_t N, int dtype);
  */
 int64_t layernorm_unaligned_walk_grid(const void* x, const void* w, const void* b, const void* y,
                                       int64_t M, int64_t N, int dtype);
+
+/*
+ * How LAYERNORM_VARIANT_QUEUE would run M rows of N elements, without launching anything:
+ * *threads (256 or 512 threads hold a row; the workgroup has one wavefront more, which draws
+ * the rows), *grid resident workgroups in *shards groups, rows dealt to the groups in blocks of
+ * *block_rows consecutive rows (any of the pointers may be NULL).  Returns 1 if layernorm_fwd
+ * takes this kernel for such a call (on a stream that has counters), 0 if it can run but the
+ * automatic path prefers another, LAYERNORM_ERR_UNSUPPORTED if it cannot run (rows that are not
+ * a multiple of 16 bytes, rows the resident kernel does not take with 256 or 512 threads, 2^30
+ * rows or more, M == 0), LAYERNORM_ERR_INVALID_ARG for a bad dtype, N <= 0 or M < 0.
+ */
+int layernorm_queue_plan(int64_t M, int64_t N, int dtype, int* threads, int* grid, int* shards,
+                         int* block_rows);
 
 /* Largest N the register-resident kernels accept for `dtype`; 0 for a bad dtype. */
 int64_t layernorm_register_max_n(int dtype);

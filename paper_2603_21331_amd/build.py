@@ -21,7 +21,7 @@ ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
 INCLUDE = os.path.join(ROOT, "include")
 
-_COMMON = ["vec_io.h", "wave_reduce.h", "packed_rows.h", "launch_util.h", "dispatch_util.h", "build_id.h"]
+_COMMON = ["vec_io.h", "wave_reduce.h", "packed_rows.h", "launch_util.h", "dispatch_util.h", "queue_slots.h", "build_id.h"]
 
 # name -> (library file, source, csrc headers, public header)
 LIBRARIES = {

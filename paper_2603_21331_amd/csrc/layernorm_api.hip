@@ -4,12 +4,25 @@
 
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "build_id.h"
 #include "dispatch_util.h"
 #include "launch_util.h"
 #include "layernorm_kernels.h"
+#include "queue_slots.h"
 
 RMS_DEFINE_BUILD_ID(layernorm_build_id);
+
+// Counters of the work-queue kernel: one block of kQueueSlotWords words per stream slot
+// (queue_slots.h), all zero between launches (the kernel leaves them zero).  128 KiB per GPU,
+// held until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress: the device address of each GPU's copy is looked up once per device
+// (queue_base below) and only that address is ever passed to a kernel.
+namespace {
+constexpr int kQueueSlotWords = rms::kLnQueueMaxShards * rms::kLnQueueStride;   // 4 KiB
+}  // namespace
+static __device__ __align__(256) unsigned queue_counters[rms::host::kStreamSlots * kQueueSlotWords];
 
 namespace {
 
@@ -112,6 +125,107 @@ int pick_threads_unaligned(int64_t slots) {
   return 0;
 }
 
+// ---------------------------------------------------------------------------
+// The work-queue form of the resident kernel: when it runs, with what grid, and where its
+// counters live.
+// ---------------------------------------------------------------------------
+constexpr int64_t kQueueMaxRows = (int64_t)1 << 30;          // tickets are 32-bit
+
+struct QueuePlan {
+  int threads;       // 256 or 512 threads hold the row; the workgroup has one wavefront more
+  int grid;          // resident workgroups, a multiple of `shards`
+  int shards;        // 1 .. kLnQueueMaxShards
+  int block_shift;   // rows are handed to the shards in blocks of 1 << block_shift
+};
+
+// Threads that hold a row in the work-queue kernel, 0 if it cannot take the row: the rows the
+// automatic path gives the resident kernel with 256 or 512 threads (pick_threads; with 1024 the
+// workgroup has no room for the wavefront that draws), fewer than 2^30 of them.
+int queue_threads(int64_t M, int64_t nvec, int dtype) {
+  if (nvec < 1 || M < 1 || M >= kQueueMaxRows) return 0;
+  const int vec = 16 / elem_bytes(dtype);
+  const int limit = dtype == LAYERNORM_DTYPE_FP32 ? kResidentAutoElems32 : kResidentMaxElems;
+  for (int g = 256; g <= 512; g *= 2)
+    if ((nvec + g - 1) / g * vec <= limit) return g;
+  return 0;
+}
+
+// Tuned on MI355X (sustained runs over rotating buffers; the resident kernel in brackets).
+// 256 threads: two workgroups per compute unit (three for rows of 6 KiB and less), 16 shards:
+//   fp16 32768 x 4096 84.0 us (90.8), 32768 x 5120 103.8 (115.0), 32768 x 6144 123.0 (133.4),
+//   65536 x 3072 128.0 (145.0), fp32 32768 x 4096 162.6 (179.1), 65536 x 2048 163.9 (185.7);
+//   8 shards are 10 to 15 % slower than 16, 32 level; three or four workgroups per compute
+//   unit 1 to 4 % slower from 8 KiB rows on.
+// 512 threads: one workgroup per compute unit, 8 shards: bf16 8192 x 12288 62.2 (67.6), fp32
+//   8192 x 8192 83.8 (91.4), fp32 16384 x 6144 125.4 (129.6); 16 and 32 shards 0.5 to 2 %
+//   slower, two workgroups per compute unit 2 to 3 %.
+// Blocks of at most 128 KiB of rows, as in RMSNorm's kernel.
+QueuePlan queue_plan(int64_t nvec, int threads) {
+  const int cus = compute_units();
+  const int64_t row_bytes = nvec * 16;
+  QueuePlan p;
+  p.threads = threads;
+  p.shards = threads == 256 ? 16 : 8;
+  const int per_cu = threads != 256 ? 1 : nvec <= 384 ? 3 : 2;
+  p.grid = cus * per_cu / p.shards * p.shards;
+  if (p.grid < p.shards) p.grid = p.shards;
+  int shift = 0;
+  while (((int64_t)2 << shift) * row_bytes <= 128 * 1024) ++shift;   // largest block of at most 128 KiB
+  p.block_shift = shift;
+  return p;
+}
+
+// Whether the automatic path takes the work-queue kernel.  It wins once a launch is long enough
+// for the compute units to drift apart (x of 64 to 96 MiB: level or up to 5 % behind the
+// resident kernel; 128 MiB: 2 to 2.5 % ahead at 8 and 16 KiB rows in 256 threads; 192 MiB: 5 to
+// 6 %; 512 MiB: 9 to 12 %).  With 512 threads, rows of 24 KiB and more are ahead from 96 MiB
+// (5.5 %), rows of up to 20 KiB only from 256 MiB (160 MiB: 0.4 to 3 % behind, 320 MiB: 2 to 3 %
+// ahead), and rows that are two chunks per thread (16 KiB in the 16-bit types) never by more
+// than 1 % and stay with the resident kernel.
+bool queue_pays(int64_t M, int64_t nvec, int dtype) {
+  const int g = queue_threads(M, nvec, dtype);
+  if (g == 0 || nvec <= kSmallRowVectors) return false;   // (one wavefront takes rows that short)
+  const int64_t bytes = M * nvec * 16;
+  if (g == 256) return bytes >= ((int64_t)(nvec <= 384 ? 192 : 128) << 20);
+  if ((nvec + g - 1) / g <= 2) return false;
+  return bytes >= ((int64_t)(nvec <= 1280 ? 256 : 96) << 20);
+}
+
+bool plan_valid(const QueuePlan& p) {
+  return (p.threads == 256 || p.threads == 512) && p.shards >= 1 && p.shards <= rms::kLnQueueMaxShards &&
+         p.grid >= p.shards && p.grid % p.shards == 0 && p.grid <= (1 << 16) && p.block_shift >= 0 &&
+         p.block_shift <= 16;
+}
+
+// Device address of this GPU's copy of `queue_counters`, looked up once per device with that
+// device current; nullptr if the lookup fails.
+unsigned* queue_base() {
+  static std::mutex mu;
+  static unsigned* base[rms::host::kSlotDevices] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= rms::host::kSlotDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(mu);
+  if (base[dev] == nullptr) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(queue_counters)) != hipSuccess) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+    base[dev] = static_cast<unsigned*>(p);
+  }
+  return base[dev];
+}
+
+// The counter block of `stream` on the current device, nullptr if the call has to do without
+// the work-queue kernel (see queue_slots.h for the streams that get none).
+unsigned* queue_counters_for(hipStream_t stream) {
+  static rms::host::StreamSlots slots;
+  unsigned* base = queue_base();
+  if (base == nullptr) return nullptr;
+  const int k = slots.block_of(stream);
+  return k < 0 ? nullptr : base + (size_t)k * kQueueSlotWords;
+}
+
 struct Args {
   const void* x;
   const void* w;
@@ -122,7 +236,18 @@ struct Args {
   int nvec;
   float eps;
   hipStream_t stream;
+  unsigned* counters;   // work-queue kernel only
+  QueuePlan plan;
 };
+
+template <int DT, int CHUNKS, int G>
+void launch_queue(const Args& a) {
+  if constexpr (CHUNKS * rms::Storage<DT>::kVec <= kResidentMaxElems) {
+    RMS_LAUNCH((rms::layernorm_queue_kernel<DT, CHUNKS, G, true>), dim3((unsigned)a.plan.grid),
+               dim3(G + rms::kLnWave), 0, a.stream, (const u32x4*)a.x, (const u32x4*)a.w, (const u32x4*)a.b,
+               (u32x4*)a.y, a.M, a.nvec, 1.0f / (float)a.N, a.eps, a.counters, a.plan.shards, a.plan.block_shift);
+  }
+}
 
 template <int DT, int CHUNKS, int G>
 void launch_row(const Args& a) {
@@ -308,8 +433,20 @@ int dispatch_unaligned(const Args& a) {
   return launched ? LAYERNORM_OK : LAYERNORM_ERR_UNSUPPORTED;
 }
 
+// The caller has checked queue_threads and that the plan is valid.
+template <int DT>
+int dispatch_queue(const Args& a) {
+  using rms::host::with_shape;
+  constexpr int kMaxChunks = (DT == rms::kFp32 ? kResidentAutoElems32 : kResidentMaxElems) / rms::Storage<DT>::kVec;
+  const int chunks = (a.nvec + a.plan.threads - 1) / a.plan.threads;
+  auto row = [&](auto g, auto c) { launch_queue<DT, decltype(c)::value, decltype(g)::value>(a); };
+  const bool launched = with_shape<256, kMaxChunks>(a.plan.threads, chunks, row) ||
+                        with_shape<512, kMaxChunks>(a.plan.threads, chunks, row);
+  return launched ? LAYERNORM_OK : LAYERNORM_ERR_UNSUPPORTED;
+}
+
 // threads == 0 means the element-wise kernel, -1 the element-addressed row kernel, -2 the
-// three-pass streaming kernel, -3 the LDS-staged kernel.
+// three-pass streaming kernel, -3 the LDS-staged kernel, -4 the work-queue kernel.
 template <int DT>
 int run_typed(const Args& a, int threads) {
   int rc = LAYERNORM_OK;
@@ -317,6 +454,7 @@ int run_typed(const Args& a, int threads) {
   else if (threads == -1) rc = dispatch_unaligned<DT>(a);
   else if (threads == -2) launch_stream<DT>(a);
   else if (threads == -3) dispatch_packed<DT>(a);
+  else if (threads == -4) rc = dispatch_queue<DT>(a);
   else rc = dispatch<DT>(a, threads);
   if (rc != LAYERNORM_OK) return rc;
   return rms::host::launch_status() == hipSuccess ? LAYERNORM_OK : LAYERNORM_ERR_LAUNCH;
@@ -327,13 +465,15 @@ int run(const void* x, const void* w, const void* b, void* y, int64_t M, int64_t
         int dtype, void* stream, int variant, int threads) {
   int rc = check_args(x, w, b, y, M, N, eps, dtype);
   if (rc != LAYERNORM_OK) return rc;
-  if (variant < -1 || variant > LAYERNORM_VARIANT_PACKED) return LAYERNORM_ERR_INVALID_ARG;
+  if (variant < -1 || variant > LAYERNORM_VARIANT_QUEUE) return LAYERNORM_ERR_INVALID_ARG;
   if (variant == -1 && max_chunks_for(threads) == 0) return LAYERNORM_ERR_INVALID_ARG;
   if (M == 0) return LAYERNORM_OK;
 
   const bool vec_ok = rows_vectorisable(x, w, b, y, N, dtype);
   const int64_t nvec = vec_ok ? N * elem_bytes(dtype) / 16 : 0;
   const bool unaligned_fits = pick_threads_unaligned(rms::host::whole_pieces(N, elem_bytes(dtype))) != 0;
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  unsigned* counters = nullptr;
   switch (variant) {
     case LAYERNORM_VARIANT_AUTO:
       threads = vec_ok ? (nvec <= kPackedAutoVectors ? -3 : pick_threads(nvec, 8, dtype))
@@ -341,6 +481,17 @@ int run(const void* x, const void* w, const void* b, void* y, int64_t M, int64_t
                        : unaligned_fits ? -1 : 0;
       if (vec_ok && threads > 0 && threads < 64 && packed_beats_lanes(nvec, threads)) threads = -3;
       if (threads == 0 && N < kStreamMaxN) threads = -2;     // too long for registers
+      // The work-queue form of the resident kernel where it pays, if this stream has counters.
+      if (threads >= 256 && queue_pays(M, nvec, dtype)) {
+        counters = queue_counters_for(hs);
+        if (counters != nullptr) threads = -4;
+      }
+      break;
+    case LAYERNORM_VARIANT_QUEUE:
+      if (!(vec_ok && queue_threads(M, nvec, dtype) != 0)) return LAYERNORM_ERR_UNSUPPORTED;
+      counters = queue_counters_for(hs);
+      if (counters == nullptr) return LAYERNORM_ERR_UNSUPPORTED;   // a stream that gets no counters
+      threads = -4;
       break;
     case LAYERNORM_VARIANT_PACKED:
       if (!packed_can(N)) return LAYERNORM_ERR_UNSUPPORTED;
@@ -374,7 +525,11 @@ int run(const void* x, const void* w, const void* b, void* y, int64_t M, int64_t
       break;
   }
 
-  Args a{x, w, b, y, M, N, (int)nvec, eps, static_cast<hipStream_t>(stream)};
+  Args a{x, w, b, y, M, N, (int)nvec, eps, hs, counters, QueuePlan{}};
+  if (threads == -4) {
+    a.plan = queue_plan(nvec, queue_threads(M, nvec, dtype));
+    if (!plan_valid(a.plan)) return LAYERNORM_ERR_UNSUPPORTED;
+  }
   switch (dtype) {
     case LAYERNORM_DTYPE_FP32: return run_typed<rms::kFp32>(a, threads);
     case LAYERNORM_DTYPE_FP16: return run_typed<rms::kFp16>(a, threads);
@@ -420,6 +575,22 @@ int64_t layernorm_unaligned_walk_grid(const void* x, const void* w, const void* 
   if (pick_threads_unaligned(rms::host::whole_pieces(N, elem_bytes(dtype))) == 0) return 0;
   int threads = 0;
   return unaligned_walk_grid(M, N, elem_bytes(dtype), &threads);
+}
+
+int layernorm_queue_plan(int64_t M, int64_t N, int dtype, int* threads, int* grid, int* shards,
+                         int* block_rows) {
+  const int eb = elem_bytes(dtype);
+  if (eb == 0 || N <= 0 || M < 0) return LAYERNORM_ERR_INVALID_ARG;
+  if ((N * eb) % 16 != 0) return LAYERNORM_ERR_UNSUPPORTED;
+  const int64_t nvec = N * eb / 16;
+  const int g = queue_threads(M, nvec, dtype);
+  if (g == 0) return LAYERNORM_ERR_UNSUPPORTED;
+  const QueuePlan p = queue_plan(nvec, g);
+  if (threads) *threads = p.threads;
+  if (grid) *grid = p.grid;
+  if (shards) *shards = p.shards;
+  if (block_rows) *block_rows = 1 << p.block_shift;
+  return queue_pays(M, nvec, dtype) ? 1 : 0;
 }
 
 int64_t layernorm_register_max_n(int dtype) {

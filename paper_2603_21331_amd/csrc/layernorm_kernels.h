@@ -382,6 +382,174 @@ layernorm_row_resident_kernel(const u32x4* x, const u32x4* __restrict__ w,
   }
 }
 
+// ---------------------------------------------------------------------------
+// Work-queue form of the resident kernel, for launches of a few hundred megabytes: the
+// resident workgroups draw their rows from counters in device memory instead of walking a
+// fixed stride, which evens out the compute units, and take them in blocks of consecutive
+// rows per XCD.  Row order and counters are those of RMSNorm's work-queue kernel: workgroup b
+// belongs to shard b % shards, the rows are cut into blocks of 2^block_shift rows, block k
+// belongs to shard k % shards; shard s owns counters[s * kLnQueueStride] (slots handed out
+// beyond the two every member takes statically) and counters[s * kLnQueueStride + 1] (members
+// that have finished); both are zero between launches (the last member of a shard to finish
+// puts them back), and launches that share counters must not overlap.  Nobody waits for
+// anybody, so the grid drains whatever the order the hardware starts it in.
+//
+// Who draws.  The compiler waits for a returning atomic where it issues it, with a count that
+// covers every load the wavefront has in flight; a wavefront that has its next row requested
+// would stall there in every step, and the workgroup behind it at the next barrier.  So the
+// workgroup has one wavefront more than the G threads that hold the row: it touches no row,
+// draws one ticket per step (for the row after next), leaves it in LDS before the step's
+// first barrier and takes part in both barriers.  The workers read it after that barrier.
+// ---------------------------------------------------------------------------
+constexpr int kLnQueueStride = 32;      // counters of neighbouring shards are 128 bytes apart
+constexpr int kLnQueueMaxShards = 32;
+
+// One step: requests row `pre` into (nxt, nxt_raw), then reduces, scales and stores row `row`
+// held in (cur, cur_raw); the extra wavefront draws.  Returns the ticket drawn in this step.
+template <int DT, int CHUNKS, int G, bool NT>
+__device__ __forceinline__ unsigned ln_queue_step(
+    const u32x4* x, u32x4* y, int64_t row, int64_t pre, int nvec, int t, int lane, int wave,
+    bool last_ok, const u32x4 (&cur)[CHUNKS], uint32_t cur_raw, u32x4 (&nxt)[CHUNKS],
+    uint32_t& nxt_raw, const float (&wf)[CHUNKS][Storage<DT>::kVec],
+    const float (&bf)[CHUNKS][Storage<DT>::kVec], float inv_n, float eps, unsigned* q,
+    float (&part_a)[G / kLnWave], float (&part_b)[G / kLnWave], unsigned& ticket) {
+  using S = Storage<DT>;
+  constexpr int VEC = S::kVec;
+  constexpr int WAVES = G / kLnWave;
+  const bool worker = t < G;
+  const int last = (CHUNKS - 1) * G + t;
+  float d[CHUNKS][VEC];
+  if (worker) {
+#pragma unroll
+    for (int c = 0; c < CHUNKS - 1; ++c) nxt[c] = load_vec<NT>(x + pre * nvec + c * G + t);
+    nxt[CHUNKS - 1] = load_vec<NT>(x + pre * nvec + (last_ok ? last : nvec - 1));
+    nxt_raw = ln_first_raw<DT>(x + pre * nvec);
+
+    const float shift = ln_first_value<DT>(cur_raw);
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int c = 0; c < CHUNKS; ++c) {
+      S::unpack(cur[c], d[c]);
+      const bool live = c < CHUNKS - 1 || last_ok;
+#pragma unroll
+      for (int k = 0; k < VEC; ++k) {
+        d[c][k] = live ? d[c][k] - shift : 0.f;
+        acc[k & 3] += d[c][k];
+      }
+    }
+    const float s1 = wave_sum((acc[0] + acc[1]) + (acc[2] + acc[3]));
+    if (lane == 0) part_a[wave] = s1;
+  } else if (lane == 0) {
+    ticket = atomicAdd(q, 1u);
+  }
+  __syncthreads();
+  const unsigned drawn = ticket;
+  if (worker) {
+    const float mean_shifted = sum_waves<WAVES>(part_a) * inv_n;
+    float sq[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int c = 0; c < CHUNKS; ++c) {
+      const bool live = c < CHUNKS - 1 || last_ok;
+#pragma unroll
+      for (int k = 0; k < VEC; ++k) {
+        d[c][k] = live ? d[c][k] - mean_shifted : 0.f;
+        sq[k & 3] = __builtin_fmaf(d[c][k], d[c][k], sq[k & 3]);
+      }
+    }
+    const float s2 = wave_sum((sq[0] + sq[1]) + (sq[2] + sq[3]));
+    if (lane == 0) part_b[wave] = s2;
+  }
+  __syncthreads();
+  if (worker) {
+    const float rstd = ln_rstd_fast(sum_waves<WAVES>(part_b), inv_n, eps);
+    const __amdgpu_buffer_rsrc_t yr = row_resource(y + row * nvec, nvec * 16);
+#pragma unroll
+    for (int c = 0; c < CHUNKS; ++c) {
+      float yf[VEC];
+#pragma unroll
+      for (int k = 0; k < VEC; ++k) yf[k] = (d[c][k] * rstd) * wf[c][k] + bf[c][k];
+      if (c < CHUNKS - 1 || last_ok) store_row_vec<NT>(yr, c * G + t, S::pack(yf));
+    }
+  }
+  return drawn;
+}
+
+template <int DT, int CHUNKS, int G, bool NT>
+__global__ void __launch_bounds__(G + kLnWave)
+layernorm_queue_kernel(const u32x4* x, const u32x4* __restrict__ w, const u32x4* __restrict__ b,
+                       u32x4* y, int64_t M, int nvec, float inv_n, float eps, unsigned* counters,
+                       int shards, int block_shift) {
+  using S = Storage<DT>;
+  constexpr int VEC = S::kVec;
+  constexpr int WAVES = G / kLnWave;
+  __shared__ __attribute__((aligned(16))) float part_a[2][WAVES];
+  __shared__ __attribute__((aligned(16))) float part_b[2][WAVES];
+  __shared__ unsigned ticket[2];
+  const int t = threadIdx.x;
+  const int lane = t & (kLnWave - 1);
+  const int wave = t / kLnWave;
+  const bool worker = t < G;
+  const int last = (CHUNKS - 1) * G + t;
+  const bool last_ok = last < nvec;
+  const u32x4 zero = {0u, 0u, 0u, 0u};
+
+  // this workgroup's shard, and how many row slots the shard has
+  const unsigned SH = (unsigned)shards;
+  const unsigned shard = blockIdx.x % SH;
+  const unsigned local = blockIdx.x / SH;
+  const unsigned members = (gridDim.x - shard + SH - 1) / SH;
+  const int64_t block_rows = (int64_t)1 << block_shift;
+  const int64_t nblocks = (M + block_rows - 1) >> block_shift;
+  const int64_t mine = nblocks > shard ? (nblocks - shard + SH - 1) / SH : 0;
+  // (only the last block can be short, and it is the last block of its shard)
+  const int64_t slots = mine * block_rows - ((nblocks - 1) % SH == shard ? nblocks * block_rows - M : 0);
+  unsigned* q = counters + shard * kLnQueueStride;
+  auto row_of = [&](int64_t i) {
+    return ((((i >> block_shift) * SH + shard)) << block_shift) + (i & (block_rows - 1));
+  };
+
+  int64_t i = local, inext = (int64_t)local + members;   // two static slots, then tickets
+  u32x4 ra[CHUNKS], rb[CHUNKS];
+  uint32_t raw_a = 0, raw_b = 0;
+  float wf[CHUNKS][VEC], bf[CHUNKS][VEC];
+  if (worker && i < slots) {
+    const int64_t row = row_of(i);
+#pragma unroll
+    for (int c = 0; c < CHUNKS - 1; ++c) ra[c] = load_vec<NT>(x + row * nvec + c * G + t);
+    ra[CHUNKS - 1] = load_vec<NT>(x + row * nvec + (last_ok ? last : nvec - 1));
+    raw_a = ln_first_raw<DT>(x + row * nvec);
+#pragma unroll
+    for (int c = 0; c < CHUNKS; ++c) {
+      const int idx = (c < CHUNKS - 1 || last_ok) ? c * G + t : nvec - 1;
+      S::unpack(w[idx], wf[c]);
+      S::unpack(b != nullptr ? b[idx] : zero, bf[c]);
+    }
+  }
+  while (i < slots) {                                       // uniform over the workgroup
+    int64_t row = row_of(i);
+    unsigned drawn = ln_queue_step<DT, CHUNKS, G, NT>(x, y, row, inext < slots ? row_of(inext) : row, nvec, t, lane,
+                                                      wave, last_ok, ra, raw_a, rb, raw_b, wf, bf, inv_n, eps, q,
+                                                      part_a[0], part_b[0], ticket[0]);
+    i = inext;
+    inext = (int64_t)2 * members + drawn;
+    if (i >= slots) break;
+    row = row_of(i);
+    drawn = ln_queue_step<DT, CHUNKS, G, NT>(x, y, row, inext < slots ? row_of(inext) : row, nvec, t, lane, wave,
+                                             last_ok, rb, raw_b, ra, raw_a, wf, bf, inv_n, eps, q, part_a[1],
+                                             part_b[1], ticket[1]);
+    i = inext;
+    inext = (int64_t)2 * members + drawn;
+  }
+  // Every member has drawn its last ticket when it gets here; the last to arrive resets.
+  if (t == G) {
+    const unsigned done = atomicAdd(&q[1], 1u);
+    if (done == members - 1) {
+      atomicExch(&q[0], 0u);
+      atomicExch(&q[1], 0u);
+    }
+  }
+}
+
 // Short rows that are not 16-byte aligned, several per workgroup, staged through LDS (see
 // packed_rows.h): L lanes per row, E elements per lane with (E - 1) * L < N <= E * L (so only a
 // lane's last element can lie past the end of its row), `tile_rows` rows (at most 16 KiB) per

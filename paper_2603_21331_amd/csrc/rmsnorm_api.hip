@@ -9,6 +9,7 @@
 #include "build_id.h"
 #include "dispatch_util.h"
 #include "launch_util.h"
+#include "queue_slots.h"
 #include "rmsnorm_kernels.h"
 
 RMS_DEFINE_BUILD_ID(rmsnorm_build_id);
@@ -22,7 +23,7 @@ RMS_DEFINE_BUILD_ID(rmsnorm_build_id);
 // passed to a kernel.
 namespace {
 constexpr int kQueueSlotWords = rms::kQueueMaxShards * rms::kQueueStride;   // 4 KiB
-constexpr int kStreamSlots = 32;
+using rms::host::kStreamSlots;
 constexpr int kStaticSlot = kStreamSlots;
 constexpr int kScratchSlots = kStreamSlots + 1;
 }  // namespace
@@ -304,35 +305,13 @@ unsigned* queue_scratch() {
 }
 
 // The counter block of `stream` on the current device for rmsnorm_fwd, nullptr if the call
-// has to do without the work-queue kernel.  Launches on one stream run one after the other, so
-// one block per stream is never shared by two running kernels; a block, once given to a
-// stream, stays with it (streams are few and long-lived; the 33rd gets none).  Two cases get
-// none: the per-thread default stream, whose one handle stands for a different stream in every
-// host thread, and a stream that is being captured into a graph, because a graph can be
-// replayed on any stream, next to anything.
+// has to do without the work-queue kernel (see queue_slots.h for the streams that get none).
 unsigned* queue_counters_for(hipStream_t stream) {
-  if (stream == hipStreamPerThread) return nullptr;
-  hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
-  if (hipStreamIsCapturing(stream, &capture) != hipSuccess) {
-    (void)hipGetLastError();
-    return nullptr;
-  }
-  if (capture != hipStreamCaptureStatusNone) return nullptr;
+  static rms::host::StreamSlots slots;
   unsigned* base = queue_scratch();
   if (base == nullptr) return nullptr;
-  constexpr int kMaxDevices = 64;
-  struct Table { hipStream_t owner[kStreamSlots]; int used; };
-  static std::mutex mu;
-  static Table tables[kMaxDevices] = {};
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
-  std::lock_guard<std::mutex> lock(mu);
-  Table& tb = tables[dev];
-  for (int k = 0; k < tb.used; ++k)
-    if (tb.owner[k] == stream) return base + (size_t)k * kQueueSlotWords;
-  if (tb.used == kStreamSlots) return nullptr;
-  tb.owner[tb.used] = stream;
-  return base + (size_t)(tb.used++) * kQueueSlotWords;
+  const int k = slots.block_of(stream);
+  return k < 0 ? nullptr : base + (size_t)k * kQueueSlotWords;
 }
 
 struct Args {

@@ -29,8 +29,10 @@ LAYERNORM_VARIANT_SUBWAVE = 4
 LAYERNORM_VARIANT_UNALIGNED = 5
 LAYERNORM_VARIANT_STREAM = 6
 LAYERNORM_VARIANT_PACKED = 7
+LAYERNORM_VARIANT_QUEUE = 8
 
-VARIANT_NAMES = {0: "auto", 1: "wave", 2: "block", 3: "generic", 4: "subwave", 5: "unaligned", 6: "stream", 7: "packed"}
+VARIANT_NAMES = {0: "auto", 1: "wave", 2: "block", 3: "generic", 4: "subwave", 5: "unaligned", 6: "stream", 7: "packed",
+                 8: "queue"}
 
 _lib = None
 
@@ -63,6 +65,9 @@ def load() -> ctypes.CDLL:
     lib.layernorm_auto_threads_per_row.restype = i32
     lib.layernorm_unaligned_walk_grid.argtypes = [vp, vp, vp, vp, i64, i64, i32]
     lib.layernorm_unaligned_walk_grid.restype = i64
+    ip = ctypes.POINTER(ctypes.c_int)
+    lib.layernorm_queue_plan.argtypes = [i64, i64, i32, ip, ip, ip, ip]
+    lib.layernorm_queue_plan.restype = i32
     lib.layernorm_register_max_n.argtypes = [i32]
     lib.layernorm_register_max_n.restype = i64
     lib.layernorm_status_string.argtypes = [i32]
@@ -156,6 +161,16 @@ def layernorm_unaligned_walk_grid(x, w, b, y) -> int:
     if rc < 0:
         _check(rc)
     return rc
+
+
+def layernorm_queue_plan(M: int, N: int, dtype: int):
+    """(auto_takes_it, threads, grid, shards, block_rows) of LAYERNORM_VARIANT_QUEUE for M x N on the
+    current device; raises if the variant cannot run such rows."""
+    out = [ctypes.c_int(0) for _ in range(4)]
+    rc = int(load().layernorm_queue_plan(int(M), int(N), int(dtype), *[ctypes.byref(o) for o in out]))
+    if rc < 0:
+        _check(rc)
+    return (rc == 1, out[0].value, out[1].value, out[2].value, out[3].value)
 
 
 def layernorm_register_max_n(dtype: int) -> int:

@@ -49,7 +49,7 @@ def test_empty_batch_unknown_variant_and_unsupported_shapes():
     W, B, Y = P + 2 * BIG, P + 3 * BIG, P + BIG
     assert lib.layernorm_fwd(None, None, None, None, 0, 16, 1e-5, 2, None) == layernorm.LAYERNORM_OK
     assert lib.layernorm_fwd_variant(P, W, B, Y, 4, 8, 1e-5, 2, None, 1000) == layernorm.LAYERNORM_ERR_INVALID_ARG
-    assert lib.layernorm_fwd_variant(P, W, B, Y, 4, 8, 1e-5, 2, None, 8) == layernorm.LAYERNORM_ERR_INVALID_ARG
+    assert lib.layernorm_fwd_variant(P, W, B, Y, 4, 8, 1e-5, 2, None, 9) == layernorm.LAYERNORM_ERR_INVALID_ARG
     # the LDS-staged kernel takes at most 1024 elements, x and y at any offsets
     for dtype in (0, 1, 2):
         assert lib.layernorm_fwd_variant(P, W, B, Y, 4, 1025, 1e-5, dtype, None, 7) == layernorm.LAYERNORM_ERR_UNSUPPORTED
@@ -110,3 +110,35 @@ def test_unaligned_walk_grid_query():
     assert q(X, W, B, Y, 2048, 32775, 1) == 256 and q(X, W, B, Y, 2048, 32776, 1) == 0
     assert q(X, W, B, Y, 8192, 0, 1) == layernorm.LAYERNORM_ERR_INVALID_ARG
     assert q(0, W, B, Y, 8192, 4097, 1) == layernorm.LAYERNORM_ERR_INVALID_ARG
+
+
+def test_queue_plan_query():
+    """Where the automatic path takes the work-queue form of the resident kernel: launches of a few
+    hundred megabytes of rows that 256 or 512 threads hold (thresholds by row length), never rows
+    of two chunks per thread in 512 threads, rows one wavefront takes, or rows that need 1024
+    threads."""
+    plan = layernorm.layernorm_queue_plan
+    FP32, FP16, BF16 = 0, 1, 2
+    MiB = 1 << 20
+    # 256 threads: 128 MiB of x from rows of 6 KiB up, 192 MiB for shorter ones
+    assert plan(16384, 4096, FP16)[:2] == (True, 256) and not plan(16383, 4096, FP16)[0]
+    assert plan(128 * MiB // (5120 * 2) + 1, 5120, FP16)[0] and not plan(128 * MiB // (5120 * 2), 5120, FP16)[0]
+    assert plan(32768, 3072, FP16)[0] and not plan(32767, 3072, FP16)[0]          # 6 KiB rows: 192 MiB
+    assert plan(8192, 4096, FP32)[:2] == (True, 256) and not plan(8191, 4096, FP32)[0]
+    # 512 threads: rows beyond 20 KiB from 96 MiB, up to 20 KiB from 256 MiB, two chunks never
+    assert plan(4096, 12288, BF16)[:2] == (True, 512) and not plan(4095, 12288, BF16)[0]
+    assert plan(13108, 10240, FP16)[0] and not plan(13107, 10240, FP16)[0]
+    assert plan(3072, 8192, FP32)[:2] == (True, 512) and not plan(3071, 8192, FP32)[0]
+    assert plan(1 << 20, 8192, BF16)[:2] == (False, 512)
+    # rows one wavefront takes can run it but never do on the automatic path
+    assert plan(1 << 22, 2048, FP16)[:2] == (False, 256)
+    # shards, blocks of at most 128 KiB of rows, grids that are whole numbers of shards
+    for M, N, dt, shards, block_rows in ((1000, 4096, FP16, 16, 16), (1000, 5120, FP16, 16, 8), (1000, 3072, FP16, 16, 16),
+                                         (1000, 12288, BF16, 8, 4), (1000, 8192, FP32, 8, 4), (1000, 512, FP32, 16, 64)):
+        _, threads, grid, s, br = plan(M, N, dt)
+        assert (s, br) == (shards, block_rows) and grid % s == 0 and grid >= s, (M, N, dt)
+    lib = layernorm.load()
+    for M, N, dt in ((4, 12296, FP16), (4, 8196, FP32), (4, 65536, BF16), (4, 4100, FP16), (0, 4096, FP16), (1 << 30, 4096, FP16)):
+        assert lib.layernorm_queue_plan(M, N, dt, None, None, None, None) == layernorm.LAYERNORM_ERR_UNSUPPORTED, (M, N, dt)
+    for M, N, dt in ((4, 0, FP16), (-1, 4096, FP16), (4, 4096, 3)):
+        assert lib.layernorm_queue_plan(M, N, dt, None, None, None, None) == layernorm.LAYERNORM_ERR_INVALID_ARG

@@ -14,7 +14,7 @@ pytestmark = pytest.mark.gpu
 
 DTYPES = [inputs.FP32, inputs.FP16, inputs.BF16]
 THREADS = (8, 16, 32, 64, 256, 512, 1024)
-MODES = (0, 1, 2, 3, 4, 5, 6, 7) + tuple(("threads", g) for g in THREADS)
+MODES = (0, 1, 2, 3, 4, 5, 6, 7, 8) + tuple(("threads", g) for g in THREADS)
 
 
 def mode_name(m):
