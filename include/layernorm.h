@@ -79,7 +79,8 @@ typedef enum {
                                       bias in registers and draw their rows from counters in
                                       device memory, in blocks of consecutive rows per XCD
                                       (see layernorm_queue_plan): 16-byte aligned rows that 256
-                                      or 512 threads hold with at most 24 elements each, fewer
+                                      or 512 threads hold with at most 32 elements of a 16-bit
+                                      type or 16 of fp32 each (N up to 16384 and 8192), fewer
                                       than 2^30 rows; what the automatic path takes for such
                                       rows in launches of a few hundred megabytes.  The counters
                                       are the library's own (a static array of 128 KiB of device
@@ -148,8 +149,8 @@ int64_t layernorm_unaligned_walk_grid(const void* x, const void* w, const void* 
  * *block_rows consecutive rows (any of the pointers may be NULL).  Returns 1 if layernorm_fwd
  * takes this kernel for such a call (on a stream that has counters), 0 if it can run but the
  * automatic path prefers another, LAYERNORM_ERR_UNSUPPORTED if it cannot run (rows that are not
- * a multiple of 16 bytes, rows the resident kernel does not take with 256 or 512 threads, 2^30
- * rows or more, M == 0), LAYERNORM_ERR_INVALID_ARG for a bad dtype, N <= 0 or M < 0.
+ * a multiple of 16 bytes, rows of more than 2048 16-byte vectors, 2^30 rows or more, M == 0),
+ * LAYERNORM_ERR_INVALID_ARG for a bad dtype, N <= 0 or M < 0.
  */
 int layernorm_queue_plan(int64_t M, int64_t N, int dtype, int* threads, int* grid, int* shards,
                          int* block_rows);

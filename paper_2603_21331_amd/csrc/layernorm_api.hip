@@ -130,6 +130,7 @@ int pick_threads_unaligned(int64_t slots) {
 // counters live.
 // ---------------------------------------------------------------------------
 constexpr int64_t kQueueMaxRows = (int64_t)1 << 30;          // tickets are 32-bit
+constexpr int kQueueWideElems = 32;    // elements of a 16-bit type per thread, weight and bias kept packed
 
 struct QueuePlan {
   int threads;       // 256 or 512 threads hold the row; the workgroup has one wavefront more
@@ -138,13 +139,14 @@ struct QueuePlan {
   int block_shift;   // rows are handed to the shards in blocks of 1 << block_shift
 };
 
-// Threads that hold a row in the work-queue kernel, 0 if it cannot take the row: the rows the
-// automatic path gives the resident kernel with 256 or 512 threads (pick_threads; with 1024 the
-// workgroup has no room for the wavefront that draws), fewer than 2^30 of them.
+// Threads that hold a row in the work-queue kernel, 0 if it cannot take the row: the smaller of
+// 256 and 512 (with 1024 the workgroup has no room for the wavefront that draws) in which a
+// thread holds at most 32 elements of a 16-bit type (beyond 24 with weight and bias kept packed,
+// see LnSlices) or 16 of fp32; fewer than 2^30 rows.
 int queue_threads(int64_t M, int64_t nvec, int dtype) {
   if (nvec < 1 || M < 1 || M >= kQueueMaxRows) return 0;
   const int vec = 16 / elem_bytes(dtype);
-  const int limit = dtype == LAYERNORM_DTYPE_FP32 ? kResidentAutoElems32 : kResidentMaxElems;
+  const int limit = dtype == LAYERNORM_DTYPE_FP32 ? kResidentAutoElems32 : kQueueWideElems;
   for (int g = 256; g <= 512; g *= 2)
     if ((nvec + g - 1) / g * vec <= limit) return g;
   return 0;
@@ -157,8 +159,8 @@ int queue_threads(int64_t M, int64_t nvec, int dtype) {
 //   8 shards are 10 to 15 % slower than 16, 32 level; three or four workgroups per compute
 //   unit 1 to 4 % slower from 8 KiB rows on.
 // 512 threads: one workgroup per compute unit, 8 shards: bf16 8192 x 12288 62.2 (67.6), fp32
-//   8192 x 8192 83.8 (91.4), fp32 16384 x 6144 125.4 (129.6); 16 and 32 shards 0.5 to 2 %
-//   slower, two workgroups per compute unit 2 to 3 %.
+//   8192 x 8192 83.8 (91.4), fp32 16384 x 6144 125.4 (129.6), bf16 8192 x 16384 86.5 (95.2 with
+//   1024 threads); 16 and 32 shards 0.5 to 2 % slower, two workgroups per compute unit 2 to 3 %.
 // Blocks of at most 128 KiB of rows, as in RMSNorm's kernel.
 QueuePlan queue_plan(int64_t nvec, int threads) {
   const int cus = compute_units();
@@ -178,16 +180,18 @@ QueuePlan queue_plan(int64_t nvec, int threads) {
 // Whether the automatic path takes the work-queue kernel.  It wins once a launch is long enough
 // for the compute units to drift apart (x of 64 to 96 MiB: level or up to 5 % behind the
 // resident kernel; 128 MiB: 2 to 2.5 % ahead at 8 and 16 KiB rows in 256 threads; 192 MiB: 5 to
-// 6 %; 512 MiB: 9 to 12 %).  With 512 threads, rows of 24 KiB and more are ahead from 96 MiB
-// (5.5 %), rows of up to 20 KiB only from 256 MiB (160 MiB: 0.4 to 3 % behind, 320 MiB: 2 to 3 %
-// ahead), and rows that are two chunks per thread (16 KiB in the 16-bit types) never by more
-// than 1 % and stay with the resident kernel.
+// 6 %; 512 MiB: 9 to 12 %).  Rows of 6 KiB and less, and the rows of 12 to 16 KiB of a 16-bit type
+// that 256 threads hold with weight and bias packed, are level at 128 MiB and ahead from 192 to
+// 256 MiB (bf16 16384 x 8192: 85.6 -> 82.9 us, 32768 x 8192: 171.2 -> 161.7; fp16 16384 x 7168:
+// 77.4 -> 74.7).  With 512 threads, rows beyond 20 KiB are ahead from 96 MiB (24 KiB rows 5.5 %;
+// bf16 rows of 32 KiB, which otherwise take 1024 threads: 2 % at 96 MiB, 9 % at 256 MiB), rows of
+// up to 20 KiB only from 256 MiB (160 MiB: 0.4 to 3 % behind, 320 MiB: 2 to 3 % ahead).
 bool queue_pays(int64_t M, int64_t nvec, int dtype) {
   const int g = queue_threads(M, nvec, dtype);
   if (g == 0 || nvec <= kSmallRowVectors) return false;   // (one wavefront takes rows that short)
   const int64_t bytes = M * nvec * 16;
-  if (g == 256) return bytes >= ((int64_t)(nvec <= 384 ? 192 : 128) << 20);
-  if ((nvec + g - 1) / g <= 2) return false;
+  const bool packed_slices = dtype != LAYERNORM_DTYPE_FP32 && nvec > 768;
+  if (g == 256) return bytes >= ((int64_t)(nvec <= 384 || packed_slices ? 192 : 128) << 20);
   return bytes >= ((int64_t)(nvec <= 1280 ? 256 : 96) << 20);
 }
 
@@ -242,8 +246,9 @@ struct Args {
 
 template <int DT, int CHUNKS, int G>
 void launch_queue(const Args& a) {
-  if constexpr (CHUNKS * rms::Storage<DT>::kVec <= kResidentMaxElems) {
-    RMS_LAUNCH((rms::layernorm_queue_kernel<DT, CHUNKS, G, true>), dim3((unsigned)a.plan.grid),
+  constexpr int kElems = CHUNKS * rms::Storage<DT>::kVec;
+  if constexpr (kElems <= kQueueWideElems) {
+    RMS_LAUNCH((rms::layernorm_queue_kernel<DT, CHUNKS, G, true, (kElems > kResidentMaxElems)>), dim3((unsigned)a.plan.grid),
                dim3(G + rms::kLnWave), 0, a.stream, (const u32x4*)a.x, (const u32x4*)a.w, (const u32x4*)a.b,
                (u32x4*)a.y, a.M, a.nvec, 1.0f / (float)a.N, a.eps, a.counters, a.plan.shards, a.plan.block_shift);
   }
@@ -437,7 +442,7 @@ int dispatch_unaligned(const Args& a) {
 template <int DT>
 int dispatch_queue(const Args& a) {
   using rms::host::with_shape;
-  constexpr int kMaxChunks = (DT == rms::kFp32 ? kResidentAutoElems32 : kResidentMaxElems) / rms::Storage<DT>::kVec;
+  constexpr int kMaxChunks = (DT == rms::kFp32 ? kResidentAutoElems32 : kQueueWideElems) / rms::Storage<DT>::kVec;
   const int chunks = (a.nvec + a.plan.threads - 1) / a.plan.threads;
   auto row = [&](auto g, auto c) { launch_queue<DT, decltype(c)::value, decltype(g)::value>(a); };
   const bool launched = with_shape<256, kMaxChunks>(a.plan.threads, chunks, row) ||

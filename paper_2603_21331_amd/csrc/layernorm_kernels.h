@@ -404,14 +404,49 @@ layernorm_row_resident_kernel(const u32x4* x, const u32x4* __restrict__ w,
 constexpr int kLnQueueStride = 32;      // counters of neighbouring shards are 128 bytes apart
 constexpr int kLnQueueMaxShards = 32;
 
+// A thread's slices of weight and bias.  Widened to fp32 once where the registers allow it
+// (up to 24 elements per thread); kept as loaded and widened again in every step beyond that
+// (32 elements of a 16-bit type: the widened form would not leave room for two row copies).
+template <int DT, int CHUNKS, bool PACKED>
+struct LnSlices;
+template <int DT, int CHUNKS>
+struct LnSlices<DT, CHUNKS, false> {
+  float w[CHUNKS][Storage<DT>::kVec], b[CHUNKS][Storage<DT>::kVec];
+  __device__ __forceinline__ void set(int c, u32x4 wv, u32x4 bv) {
+    Storage<DT>::unpack(wv, w[c]);
+    Storage<DT>::unpack(bv, b[c]);
+  }
+  __device__ __forceinline__ void step() {}
+  __device__ __forceinline__ void widen(int) {}
+  __device__ __forceinline__ float scale(int c, int k, float v) const { return v * w[c][k] + b[c][k]; }
+};
+template <int DT, int CHUNKS>
+struct LnSlices<DT, CHUNKS, true> {
+  u32x4 w[CHUNKS], b[CHUNKS];
+  float wf[Storage<DT>::kVec], bf[Storage<DT>::kVec];   // chunk c, between widen(c) and the next
+  __device__ __forceinline__ void set(int c, u32x4 wv, u32x4 bv) {
+    w[c] = wv;
+    b[c] = bv;
+  }
+  // once per step: the compiler must not carry widened values from one step to the next
+  __device__ __forceinline__ void step() {
+    forget_unpacked<CHUNKS>(w);
+    forget_unpacked<CHUNKS>(b);
+  }
+  __device__ __forceinline__ void widen(int c) {
+    Storage<DT>::unpack(w[c], wf);
+    Storage<DT>::unpack(b[c], bf);
+  }
+  __device__ __forceinline__ float scale(int, int k, float v) const { return v * wf[k] + bf[k]; }
+};
+
 // One step: requests row `pre` into (nxt, nxt_raw), then reduces, scales and stores row `row`
 // held in (cur, cur_raw); the extra wavefront draws.  Returns the ticket drawn in this step.
-template <int DT, int CHUNKS, int G, bool NT>
+template <int DT, int CHUNKS, int G, bool NT, bool PACKED>
 __device__ __forceinline__ unsigned ln_queue_step(
     const u32x4* x, u32x4* y, int64_t row, int64_t pre, int nvec, int t, int lane, int wave,
     bool last_ok, const u32x4 (&cur)[CHUNKS], uint32_t cur_raw, u32x4 (&nxt)[CHUNKS],
-    uint32_t& nxt_raw, const float (&wf)[CHUNKS][Storage<DT>::kVec],
-    const float (&bf)[CHUNKS][Storage<DT>::kVec], float inv_n, float eps, unsigned* q,
+    uint32_t& nxt_raw, LnSlices<DT, CHUNKS, PACKED>& wb, float inv_n, float eps, unsigned* q,
     float (&part_a)[G / kLnWave], float (&part_b)[G / kLnWave], unsigned& ticket) {
   using S = Storage<DT>;
   constexpr int VEC = S::kVec;
@@ -463,19 +498,21 @@ __device__ __forceinline__ unsigned ln_queue_step(
   if (worker) {
     const float rstd = ln_rstd_fast(sum_waves<WAVES>(part_b), inv_n, eps);
     const __amdgpu_buffer_rsrc_t yr = row_resource(y + row * nvec, nvec * 16);
+    wb.step();
 #pragma unroll
     for (int c = 0; c < CHUNKS; ++c) {
       float yf[VEC];
+      wb.widen(c);
 #pragma unroll
-      for (int k = 0; k < VEC; ++k) yf[k] = (d[c][k] * rstd) * wf[c][k] + bf[c][k];
+      for (int k = 0; k < VEC; ++k) yf[k] = wb.scale(c, k, d[c][k] * rstd);
       if (c < CHUNKS - 1 || last_ok) store_row_vec<NT>(yr, c * G + t, S::pack(yf));
     }
   }
   return drawn;
 }
 
-template <int DT, int CHUNKS, int G, bool NT>
-__global__ void __launch_bounds__(G + kLnWave)
+template <int DT, int CHUNKS, int G, bool NT, bool PACKED>
+__global__ void __launch_bounds__(G + kLnWave, PACKED ? 4 : 1)   // PACKED: at most 128 registers, see LnSlices
 layernorm_queue_kernel(const u32x4* x, const u32x4* __restrict__ w, const u32x4* __restrict__ b,
                        u32x4* y, int64_t M, int nvec, float inv_n, float eps, unsigned* counters,
                        int shards, int block_shift) {
@@ -511,7 +548,7 @@ layernorm_queue_kernel(const u32x4* x, const u32x4* __restrict__ w, const u32x4*
   int64_t i = local, inext = (int64_t)local + members;   // two static slots, then tickets
   u32x4 ra[CHUNKS], rb[CHUNKS];
   uint32_t raw_a = 0, raw_b = 0;
-  float wf[CHUNKS][VEC], bf[CHUNKS][VEC];
+  LnSlices<DT, CHUNKS, PACKED> wb;
   if (worker && i < slots) {
     const int64_t row = row_of(i);
 #pragma unroll
@@ -521,22 +558,21 @@ layernorm_queue_kernel(const u32x4* x, const u32x4* __restrict__ w, const u32x4*
 #pragma unroll
     for (int c = 0; c < CHUNKS; ++c) {
       const int idx = (c < CHUNKS - 1 || last_ok) ? c * G + t : nvec - 1;
-      S::unpack(w[idx], wf[c]);
-      S::unpack(b != nullptr ? b[idx] : zero, bf[c]);
+      wb.set(c, w[idx], b != nullptr ? b[idx] : zero);
     }
   }
   while (i < slots) {                                       // uniform over the workgroup
     int64_t row = row_of(i);
-    unsigned drawn = ln_queue_step<DT, CHUNKS, G, NT>(x, y, row, inext < slots ? row_of(inext) : row, nvec, t, lane,
-                                                      wave, last_ok, ra, raw_a, rb, raw_b, wf, bf, inv_n, eps, q,
-                                                      part_a[0], part_b[0], ticket[0]);
+    unsigned drawn = ln_queue_step<DT, CHUNKS, G, NT, PACKED>(x, y, row, inext < slots ? row_of(inext) : row, nvec, t,
+                                                              lane, wave, last_ok, ra, raw_a, rb, raw_b, wb, inv_n, eps,
+                                                              q, part_a[0], part_b[0], ticket[0]);
     i = inext;
     inext = (int64_t)2 * members + drawn;
     if (i >= slots) break;
     row = row_of(i);
-    drawn = ln_queue_step<DT, CHUNKS, G, NT>(x, y, row, inext < slots ? row_of(inext) : row, nvec, t, lane, wave,
-                                             last_ok, rb, raw_b, ra, raw_a, wf, bf, inv_n, eps, q, part_a[1],
-                                             part_b[1], ticket[1]);
+    drawn = ln_queue_step<DT, CHUNKS, G, NT, PACKED>(x, y, row, inext < slots ? row_of(inext) : row, nvec, t, lane,
+                                                     wave, last_ok, rb, raw_b, ra, raw_a, wb, inv_n, eps, q, part_a[1],
+                                                     part_b[1], ticket[1]);
     i = inext;
     inext = (int64_t)2 * members + drawn;
   }

@@ -114,9 +114,8 @@ def test_unaligned_walk_grid_query():
 
 def test_queue_plan_query():
     """Where the automatic path takes the work-queue form of the resident kernel: launches of a few
-    hundred megabytes of rows that 256 or 512 threads hold (thresholds by row length), never rows
-    of two chunks per thread in 512 threads, rows one wavefront takes, or rows that need 1024
-    threads."""
+    hundred megabytes of rows that 256 or 512 threads hold (thresholds by row length), never rows one
+    wavefront takes or rows of more than 2048 vectors."""
     plan = layernorm.layernorm_queue_plan
     FP32, FP16, BF16 = 0, 1, 2
     MiB = 1 << 20
@@ -125,11 +124,14 @@ def test_queue_plan_query():
     assert plan(128 * MiB // (5120 * 2) + 1, 5120, FP16)[0] and not plan(128 * MiB // (5120 * 2), 5120, FP16)[0]
     assert plan(32768, 3072, FP16)[0] and not plan(32767, 3072, FP16)[0]          # 6 KiB rows: 192 MiB
     assert plan(8192, 4096, FP32)[:2] == (True, 256) and not plan(8191, 4096, FP32)[0]
-    # 512 threads: rows beyond 20 KiB from 96 MiB, up to 20 KiB from 256 MiB, two chunks never
+    # 12 to 16 KiB rows of a 16-bit type in 256 threads (weight and bias kept packed): 192 MiB
+    assert plan(12288, 8192, BF16)[:2] == (True, 256) and not plan(12287, 8192, BF16)[0]
+    assert plan(14044, 7168, FP16)[:2] == (True, 256) and not plan(14043, 7168, FP16)[0]
+    # 512 threads: rows beyond 20 KiB from 96 MiB, up to 20 KiB from 256 MiB
     assert plan(4096, 12288, BF16)[:2] == (True, 512) and not plan(4095, 12288, BF16)[0]
     assert plan(13108, 10240, FP16)[0] and not plan(13107, 10240, FP16)[0]
     assert plan(3072, 8192, FP32)[:2] == (True, 512) and not plan(3071, 8192, FP32)[0]
-    assert plan(1 << 20, 8192, BF16)[:2] == (False, 512)
+    assert plan(3072, 16384, BF16)[:2] == (True, 512) and not plan(3071, 16384, BF16)[0]
     # rows one wavefront takes can run it but never do on the automatic path
     assert plan(1 << 22, 2048, FP16)[:2] == (False, 256)
     # shards, blocks of at most 128 KiB of rows, grids that are whole numbers of shards
@@ -138,7 +140,7 @@ def test_queue_plan_query():
         _, threads, grid, s, br = plan(M, N, dt)
         assert (s, br) == (shards, block_rows) and grid % s == 0 and grid >= s, (M, N, dt)
     lib = layernorm.load()
-    for M, N, dt in ((4, 12296, FP16), (4, 8196, FP32), (4, 65536, BF16), (4, 4100, FP16), (0, 4096, FP16), (1 << 30, 4096, FP16)):
+    for M, N, dt in ((4, 16392, FP16), (4, 8196, FP32), (4, 65536, BF16), (4, 4100, FP16), (0, 4096, FP16), (1 << 30, 4096, FP16)):
         assert lib.layernorm_queue_plan(M, N, dt, None, None, None, None) == layernorm.LAYERNORM_ERR_UNSUPPORTED, (M, N, dt)
     for M, N, dt in ((4, 0, FP16), (-1, 4096, FP16), (4, 4096, 3)):
         assert lib.layernorm_queue_plan(M, N, dt, None, None, None, None) == layernorm.LAYERNORM_ERR_INVALID_ARG

@@ -36,7 +36,11 @@ def _check(case, device, threads):
     xd = H.to_device(case["x"], dtype, device)
     wd = H.to_device(case["w"], dtype, device)
     bd = None if case["b"] is None else H.to_device(case["b"], dtype, device)
-    resident = H.to_host(layernorm.layernorm_fwd_tuned(xd, wd, bd, EPS, threads), dtype)
+    # Same threads and chunks as the resident kernel, so the same bits, except where a thread holds
+    # more than 24 elements: the resident kernel does not take those rows.
+    elems = -(-N * inputs.DTYPE_BYTES[dtype] // 16 // threads) * (16 // inputs.DTYPE_BYTES[dtype])
+    resident = H.to_host(layernorm.layernorm_fwd_tuned(xd, wd, bd, EPS, threads), dtype) if elems <= 24 else None
+    first = None
     for rep in range(2):
         H.say(f"layernorm queue {case['name']} bias={bd is not None} rep={rep}")
         whole, y = H.alloc_guarded(M, N, dtype, device)
@@ -45,7 +49,10 @@ def _check(case, device, threads):
         assert H.guards_intact(whole, M, N, dtype), f"{case['name']}: wrote outside y"
         got = H.to_host(y, dtype)
         compare.check_layernorm_parity(got, want, _scale(case, mean, rstd), dtype, f"{case['name']} [queue]")
-        assert np.array_equal(got, resident), f"{case['name']}: bits differ from the resident kernel"
+        if resident is not None:
+            assert np.array_equal(got, resident), f"{case['name']}: bits differ from the resident kernel"
+        first = got if first is None else first
+        assert np.array_equal(got, first), f"{case['name']}: bits differ from run to run"
 
 
 # (dtype, N, threads that hold the row): every chunk count of either workgroup size, exact and
@@ -57,9 +64,12 @@ SHAPES = [
     (inputs.FP16, 4096, 256),     # 512 vectors: two full chunks
     (inputs.FP16, 5120, 256),     # 640 vectors: three chunks, ragged (a shape of the paper's table)
     (inputs.BF16, 6144, 256),     # 768 vectors: three full chunks
-    (inputs.BF16, 8192, 512),     # 1024 vectors: two chunks of 512
-    (inputs.FP16, 10248, 512),    # 1281 vectors: three chunks, ragged
+    (inputs.FP16, 7168, 256),     # 896 vectors: four chunks, ragged; weight and bias stay packed
+    (inputs.BF16, 8192, 256),     # 1024 vectors: four full chunks, packed weight and bias
+    (inputs.FP16, 10248, 512),    # 1281 vectors: three chunks of 512, ragged
     (inputs.BF16, 12288, 512),    # 1536 vectors: three full chunks
+    (inputs.BF16, 14336, 512),    # 1792 vectors: four chunks, ragged, packed weight and bias
+    (inputs.FP16, 16384, 512),    # 2048 vectors: four full chunks, packed weight and bias
     (inputs.FP32, 512, 256),      # 128 vectors of fp32
     (inputs.FP32, 2048, 256),     # 512 vectors: two chunks
     (inputs.FP32, 3076, 256),     # 769 vectors: four chunks, ragged
@@ -107,7 +117,7 @@ def test_in_place_and_repeated_runs_are_bit_identical(gpu_device):
 
 
 def test_rows_the_kernel_does_not_take(gpu_device):
-    for dtype, N in ((inputs.FP16, 12296), (inputs.FP16, 4100), (inputs.FP32, 8196), (inputs.BF16, 65536)):
+    for dtype, N in ((inputs.FP16, 16392), (inputs.FP16, 4100), (inputs.FP32, 8196), (inputs.BF16, 65536)):
         case = inputs.layernorm_case(6, 1750, 4, N, dtype)
         xd, wd, bd = (H.to_device(case[k], dtype, gpu_device) for k in ("x", "w", "b"))
         with pytest.raises(layernorm.LayerNormError) as e:
@@ -115,12 +125,14 @@ def test_rows_the_kernel_does_not_take(gpu_device):
         assert e.value.status == layernorm.LAYERNORM_ERR_UNSUPPORTED, (dtype, N)
 
 
-@pytest.mark.parametrize("dtype,M,N,threads", [(inputs.FP16, 16384, 4096, 256), (inputs.BF16, 4096, 12288, 512)])
+@pytest.mark.parametrize("dtype,M,N,threads", [(inputs.FP16, 16384, 4096, 256), (inputs.BF16, 4096, 12288, 512),
+                                               (inputs.BF16, 12288, 8192, 0), (inputs.FP16, 3072, 16384, 0)])
 def test_automatic_path_takes_the_queue_for_large_launches(gpu_device, dtype, M, N, threads):
-    """128 MiB of 8 KiB rows and 96 MiB of 24 KiB rows: layernorm_fwd runs the work-queue kernel on
-    the stream's own counters (default stream, a side stream, several times in a row) with the bits
-    of the resident kernel; one row less and the plan says it does not.  Sampled rows against the
-    oracle."""
+    """128 MiB of 8 KiB rows, 96 MiB of 24 KiB rows, 192 MiB of 16 KiB rows and 96 MiB of 32 KiB rows:
+    layernorm_fwd runs the work-queue kernel on the stream's own counters (default stream, a side
+    stream, several times in a row) with the bits of the resident kernel (threads == 0: rows the
+    resident kernel does not take in that shape; the forced variant stands in); one row less and
+    the plan says it does not.  Sampled rows against the oracle."""
     code = CODES[dtype]
     assert layernorm.layernorm_queue_plan(M, N, code)[0] and not layernorm.layernorm_queue_plan(M - 1, N, code)[0]
     tdt = torch.float16 if dtype == inputs.FP16 else torch.bfloat16
@@ -128,7 +140,7 @@ def test_automatic_path_takes_the_queue_for_large_launches(gpu_device, dtype, M,
     x = (0.5 + 2.0 * torch.randn((M, N), generator=gen, device=gpu_device)).to(tdt)
     w = (1.0 + 0.1 * torch.randn(N, generator=gen, device=gpu_device)).to(tdt)
     b = (0.1 * torch.randn(N, generator=gen, device=gpu_device)).to(tdt)
-    resident = layernorm.layernorm_fwd_tuned(x, w, b, EPS, threads)
+    resident = layernorm.layernorm_fwd_tuned(x, w, b, EPS, threads) if threads else layernorm.layernorm_fwd_variant(x, w, b, EPS, Q)
     side = torch.cuda.Stream(device=gpu_device)
     torch.cuda.synchronize()
     y = torch.empty_like(x)
