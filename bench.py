@@ -218,6 +218,10 @@ def main() -> int:
                     help="with --op softmax or layernorm: instead of the paper's shape, 64 MiB of "
                          "fp16 rows of this many elements (e.g. the 197 positions of an attention "
                          "row: not 16-byte aligned, several rows per workgroup through LDS)")
+    ap.add_argument("--shape", type=int, nargs=2, metavar=("M", "N"), default=None,
+                    help="with --op layernorm: fp16 M x N of the same recipe instead of the paper's "
+                         "shape (e.g. 32768 5120, a launch large enough for the work-queue form of "
+                         "the resident kernel); `traffic` is null")
     ap.add_argument("--profile-only", action="store_true",
                     help="warm-up plus --steps launches and nothing else (for rocprofv3 runs)")
     ap.add_argument("--calib-copy", action="store_true",
@@ -508,11 +512,23 @@ def bench_layernorm(args, dev) -> int:
         which = -1
         cols = args.attention_len
         case = inputs.layernorm_case(0, 130, (64 << 20) // (2 * cols) // 8 * 8, cols, inputs.FP16)
+    elif args.shape:
+        which = -1
+        case = inputs.layernorm_case(0, 134, args.shape[0], args.shape[1], inputs.FP16)
     else:
         case = inputs.layernorm_paper_shape(which)
     M, N, eps = case["M"], case["N"], case["eps"]
     nbytes = inputs.layernorm_bytes(M, N, inputs.FP16)
+
+    def queue_takes(m, n):
+        try:
+            return layernorm.layernorm_queue_plan(m, n, layernorm.LAYERNORM_DTYPE_FP16)[0]
+        except layernorm.LayerNormError:
+            return False
+
     S = max(args.buffer_sets, 8)               # 8 x 128 MiB: well past the Infinity Cache
+    while S > 2 and S * 2 * M * N * 2 > (8 << 30):
+        S -= 1                                 # (larger shapes: at most 8 GiB of buffers)
     as_dev = lambda a: torch.from_numpy(a.view(np.int16)).to(dev).view(torch.float16)
     x0, wd, bd = as_dev(case["x"]), as_dev(case["w"]), as_dev(case["b"])
     xs = [x0] + [x0.clone() for _ in range(S - 1)]
@@ -548,6 +564,7 @@ def bench_layernorm(args, dev) -> int:
                    "storage_dtype": "fp16", "timing": "back_to_back_region",
                    "threads_per_row": args.threads_per_row
                    or layernorm.layernorm_auto_threads_per_row(N, inputs.FP16),
+                   "work_queue": bool(not args.threads_per_row and queue_takes(M, N)),
                    "buffer_sets": S, "bytes_per_step": nbytes},
         "roofline": roofline_object(nbytes, ms_per_step, durs,
                                     **(traffic_fields("layernorm") if which == 1 else {})),
