@@ -102,6 +102,22 @@ inline int64_t flat_grid(int64_t M, int64_t max_grid) {
   return ((M < max_grid ? M : max_grid) + 63) / 64 * 64;
 }
 
+// The grid of an aligned one-workgroup-per-row kernel and whether its rows go out in XCD blocks
+// of eight (flat_first_row in vec_io.h).  Measured on MI355X, blocks against rows one by one:
+// workgroups of 256 to 1024 threads on rows of 8 to 64 KiB gain 0 to 4 % (RMSNorm bf16
+// 16384 x 8192 with 512 threads 84.7 -> 82.4 us, softmax fp16 8192 x 32000 170.3 -> 163.8,
+// LayerNorm fp16 4096 x 32768 97.0 -> 94.8, rows of 8 to 16 KiB 0.1 to 1.2 %); one wavefront
+// per row loses 1 to 5 % (rows of 3 and 4 KiB), rows of 100 KiB and more lose 1.5 to 2 %, and
+// the read-only kernels (cross-entropy, row sum) lose 1 to 4 %, so those keep rows one by one.
+struct FlatRows {
+  int64_t blocks;
+  int xcd_blocks;
+};
+inline FlatRows flat_rows(int64_t M, int64_t max_grid, int threads, int64_t row_bytes) {
+  const bool in_blocks = threads >= 256 && row_bytes >= 8 * 1024 && row_bytes <= 64 * 1024;
+  return FlatRows{in_blocks ? flat_grid(M, max_grid) : (M < max_grid ? M : max_grid), in_blocks ? 1 : 0};
+}
+
 // Compute units of the current device (256 on MI355X), looked up once per device.
 inline int compute_units() {
   constexpr int kMaxDevices = 64;

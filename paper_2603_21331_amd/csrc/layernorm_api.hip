@@ -256,7 +256,6 @@ void launch_queue(const Args& a) {
 
 template <int DT, int CHUNKS, int G>
 void launch_row(const Args& a) {
-  const int64_t blocks = a.M < kMaxGrid ? a.M : kMaxGrid;
   // Rows of at most 24 elements per thread: resident workgroups, weight and bias in registers.
   // Each workgroup has one row requested ahead, so the workgroups on a compute unit decide
   // how many bytes it has in flight; about 24 KiB measured best on MI355X.  Rows of 10 KiB
@@ -272,9 +271,10 @@ void launch_row(const Args& a) {
                        (const u32x4*)a.b, (u32x4*)a.y, a.M, a.nvec, 1.0f / (float)a.N, a.eps);
     return;
   }
-  RMS_LAUNCH((rms::layernorm_row_kernel<DT, CHUNKS, G, true>), dim3((unsigned)blocks),
+  const rms::host::FlatRows rows = rms::host::flat_rows(a.M, kMaxGrid, G, (int64_t)a.nvec * 16);
+  RMS_LAUNCH((rms::layernorm_row_kernel<DT, CHUNKS, G, true>), dim3((unsigned)rows.blocks),
                      dim3(G), 0, a.stream, (const u32x4*)a.x, (const u32x4*)a.w,
-                     (const u32x4*)a.b, (u32x4*)a.y, a.M, a.nvec, (float)a.N, a.eps);
+                     (const u32x4*)a.b, (u32x4*)a.y, a.M, a.nvec, (float)a.N, a.eps, rows.xcd_blocks);
 }
 
 template <int DT, int CHUNKS, int L>

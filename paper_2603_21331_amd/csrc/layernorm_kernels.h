@@ -81,7 +81,7 @@ inline constexpr bool kLnLean = G == 1024 && DT != kFp32;
 template <int DT, int CHUNKS, int G, bool NT>
 __global__ void __launch_bounds__(G) __attribute__((amdgpu_waves_per_eu(kLnLean<DT, G> ? 8 : 4)))
 layernorm_row_kernel(const u32x4* x, const u32x4* __restrict__ w, const u32x4* __restrict__ b,
-                     u32x4* y, int64_t M, int nvec, float n, float eps) {
+                     u32x4* y, int64_t M, int nvec, float n, float eps, int xcd_blocks) {
   using S = Storage<DT>;
   constexpr int VEC = S::kVec;
   constexpr int WAVES = G / kLnWave;
@@ -98,7 +98,7 @@ layernorm_row_kernel(const u32x4* x, const u32x4* __restrict__ w, const u32x4* _
   const u32x4 zero = {0u, 0u, 0u, 0u};
   int slot = 0;
 
-  for (int64_t row = blockIdx.x; row < M; row += gridDim.x) {
+  for (int64_t row = flat_first_row(blockIdx.x, xcd_blocks); row < M; row += gridDim.x) {
     const u32x4* xr = x + row * nvec;
     u32x4* yr = y + row * nvec;
 

@@ -245,18 +245,18 @@ bool queue_can(int64_t M, int64_t nvec) {
 }
 
 // Tuned on MI355X (bf16, sustained runs over rotating buffers, 256 MiB of x per launch; one
-// workgroup per row in brackets):
+// workgroup per row, its rows in XCD blocks of eight, in brackets):
 //   rows of 16 KiB: two workgroups per compute unit, 16 shards, blocks of 8 rows (128 KiB), no
-//     prefetch: 81.9 us (84.9); grids of 1.75 and 2.25 per compute unit are 2 to 4 us slower,
-//     blocks of 4 or 16 rows 1 to 1.5 us, 8 shards 2 us;
-//   rows of 20 and 24 KiB: the same with blocks of 4 rows: 85.5 (87.3) and 84.9 (88.6);
-//   rows of 32 KiB: two per compute unit, 8 shards, blocks of 4 rows: 85.7 (90.6);
+//     prefetch: 81.8 us (82.5; 84.7 with rows one by one); grids of 1.75 and 2.25 per compute
+//     unit are 2 to 4 us slower, blocks of 4 or 16 rows 1 to 1.5 us, 8 shards 2 us;
+//   rows of 20 and 24 KiB: the same with blocks of 4 rows: 85.1 (86.5) and 84.4 (87.2);
+//   rows of 32 KiB: two per compute unit, 8 shards, blocks of 4 rows: 85.1 (87.0);
 //   rows of 40 to 64 KiB: one workgroup per compute unit, which then has to request its next
-//     row before it stores the current one, 8 shards, blocks of 2 rows: 85.7 (85.6), 86.2
-//     (87.6), 86.7 (90.7).
-// Rows of 10 to 14 KiB gain under 1 % at that size; from x of 320 MiB on they gain 1 to 3.5 %
-// (32768 rows of 10 / 12 / 14 KiB: 107.4 -> 105.7, 125.9 -> 125.0, 149.1 -> 143.8 us; fp32
-// 32768 x 3072: 128.5 -> 124.2; 65536 x 5120 bf16: 216.8 -> 210.9).  Rows of 8 KiB and less
+//     row before it stores the current one, 8 shards, blocks of 2 rows: 85.8 (85.1), 85.9
+//     (86.8), 85.9 (88.1).
+// Rows of 10 to 14 KiB are level or behind at that size; from x of 320 MiB on they are level
+// (12 KiB) or gain 1.5 to 2.5 % (10 KiB: 107.6 -> 106.1 us at 320 MiB, 173.5 -> 169.3 at 512 MiB;
+// 14 KiB: 105.1 -> 103.4 and 168.3 -> 164.9).  Rows of 8 KiB and less
 // would be one chunk per thread of the 512, and lose 4 to 20 % to one workgroup per row.
 QueuePlan queue_plan(int64_t row_bytes) {
   const int cus = compute_units();
@@ -273,8 +273,9 @@ QueuePlan queue_plan(int64_t row_bytes) {
 }
 
 // Whether the automatic path takes the work-queue kernel: it wins once the launch moves a few
-// hundred megabytes (x of 128 MiB: 1 to 3 % ahead of one workgroup per row at rows of 16 to
-// 32 KiB, level or behind at 40 and 48 KiB; x of 256 MiB: 2 to 5 % ahead, level at 40 KiB).
+// hundred megabytes (x of 128 MiB: 0.5 to 3 % ahead of one workgroup per row at rows of 16 to
+// 32 KiB, 1 to 2 % behind at 40 and 48 KiB; x of 256 MiB: 1 to 3 % ahead, level at 40 KiB; x of
+// 512 MiB: 2 to 4 % ahead).
 constexpr int64_t kQueueMinRowBytes = 16 * 1024;
 constexpr int64_t kQueueMinBytes = (int64_t)96 << 20;        // rows up to 32 KiB
 constexpr int64_t kQueueMinBytesLong = (int64_t)192 << 20;   // longer rows
@@ -329,22 +330,23 @@ struct Args {
 
 template <int DT, int CHUNKS, int G>
 void launch_row(const Args& a) {
-  const int64_t blocks = a.M < kMaxGrid ? a.M : kMaxGrid;
+  const rms::host::FlatRows rows = rms::host::flat_rows(a.M, kMaxGrid, G, (int64_t)a.nvec * 16);
+  const int64_t blocks = rows.blocks;
   // Rows that fill their chunks exactly, one row per workgroup: the instance without
   // predicates and loop bookkeeping (256 and 512 threads, where the headline shapes fall).
   if constexpr ((G == 256 || G == 512) && CHUNKS <= 8) {
-    if (a.nvec == CHUNKS * G && blocks == a.M) {
+    if (a.nvec == CHUNKS * G && a.M <= kMaxGrid) {
       RMS_LAUNCH((rms::rmsnorm_row_kernel<DT, CHUNKS, G, true, true>),
                          dim3((unsigned)blocks), dim3(G), 0, a.stream,
                          (const u32x4*)a.x, (const u32x4*)a.w, (u32x4*)a.y, a.M, a.nvec,
-                         1.0f / (float)a.N, a.eps);
+                         1.0f / (float)a.N, a.eps, rows.xcd_blocks);
       return;
     }
   }
   RMS_LAUNCH((rms::rmsnorm_row_kernel<DT, CHUNKS, G, true>),
                      dim3((unsigned)blocks), dim3(G), 0, a.stream,
                      (const u32x4*)a.x, (const u32x4*)a.w, (u32x4*)a.y, a.M, a.nvec,
-                     1.0f / (float)a.N, a.eps);
+                     1.0f / (float)a.N, a.eps, rows.xcd_blocks);
 }
 
 template <int DT, int CHUNKS, int L>

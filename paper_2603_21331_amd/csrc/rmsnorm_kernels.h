@@ -111,7 +111,7 @@ __device__ __forceinline__ u32x4 scale_vec(u32x4 xv, u32x4 wv, float rstd) {
 template <int DT, int CHUNKS, int G, bool NT, bool FLAT = false>
 __global__ void __launch_bounds__(G)
 rmsnorm_row_kernel(const u32x4* x, const u32x4* w, u32x4* y,
-                   int64_t M, int nvec, float inv_n, float eps) {
+                   int64_t M, int nvec, float inv_n, float eps, int xcd_blocks) {
   constexpr int WAVES = G / kWave;
   // When the weight chunks are fetched.  The weight is re-read by every row and misses the
   // compute unit's vector cache most of the time (the streaming row pushes it out), so its
@@ -138,7 +138,7 @@ rmsnorm_row_kernel(const u32x4* x, const u32x4* w, u32x4* y,
   const u32x4 zero = {0u, 0u, 0u, 0u};
   int slot = 0;
 
-  for (int64_t row = blockIdx.x; row < M; row += FLAT ? M : (int64_t)gridDim.x) {
+  for (int64_t row = flat_first_row(blockIdx.x, xcd_blocks); row < M; row += FLAT ? M : (int64_t)gridDim.x) {
     const u32x4* xr = x + row * nvec;
     const __amdgpu_buffer_rsrc_t yr = row_resource(y + row * nvec, nvec * 16);
 
@@ -216,8 +216,9 @@ rmsnorm_row_kernel(const u32x4* x, const u32x4* w, u32x4* y,
 // rows (128 KiB in the tuned configurations), block k belongs to shard k % shards, and the
 // members of a shard take the rows of its blocks in order: each XCD then walks contiguous
 // 128 KiB pieces of x and y instead of single rows 8 rows apart.  Measured at bf16
-// 16384 x 8192 this order alone is worth 1.5 %, and the whole form 3.5 % over one workgroup
-// per row.
+// 16384 x 8192 the whole form is 3.5 % ahead of one workgroup per row with rows handed out one
+// by one, and 1 % ahead of it with rows in XCD blocks of eight (flat_first_row), which is what
+// the flat kernel now does at this row length.
 //
 // Counters.  Shard s owns counters[s * kQueueStride] (slots handed out beyond the two that
 // every member takes statically) and counters[s * kQueueStride + 1] (members that have

@@ -106,9 +106,9 @@ struct Args {
 
 template <int DT, int CHUNKS, int G>
 void launch_row(const Args& a) {
-  const int64_t blocks = a.M < kMaxGrid ? a.M : kMaxGrid;
-  RMS_LAUNCH((rms::softmax_row_kernel<DT, CHUNKS, G, true>), dim3((unsigned)blocks),
-                     dim3(G), 0, a.stream, (const u32x4*)a.x, (u32x4*)a.y, a.M, a.nvec);
+  const rms::host::FlatRows rows = rms::host::flat_rows(a.M, kMaxGrid, G, (int64_t)a.nvec * 16);
+  RMS_LAUNCH((rms::softmax_row_kernel<DT, CHUNKS, G, true>), dim3((unsigned)rows.blocks),
+                     dim3(G), 0, a.stream, (const u32x4*)a.x, (u32x4*)a.y, a.M, a.nvec, rows.xcd_blocks);
 }
 
 template <int DT, int CHUNKS, int L>

@@ -89,7 +89,7 @@ __device__ __forceinline__ u32x4 sm_neg_inf_vec() {
 
 template <int DT, int CHUNKS, int G, bool NT>
 __global__ void __launch_bounds__(G)
-softmax_row_kernel(const u32x4* x, u32x4* y, int64_t M, int nvec) {
+softmax_row_kernel(const u32x4* x, u32x4* y, int64_t M, int nvec, int xcd_blocks) {
   using S = Storage<DT>;
   constexpr int VEC = S::kVec;
   constexpr int WAVES = G / kWaveSize;
@@ -103,7 +103,7 @@ softmax_row_kernel(const u32x4* x, u32x4* y, int64_t M, int nvec) {
   const bool last_ok = last < nvec;
   int slot = 0;
 
-  for (int64_t row = blockIdx.x; row < M; row += gridDim.x) {
+  for (int64_t row = flat_first_row(blockIdx.x, xcd_blocks); row < M; row += gridDim.x) {
     const u32x4* xr = x + row * nvec;
     u32x4* yr = y + row * nvec;
 

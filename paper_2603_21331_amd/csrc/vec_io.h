@@ -207,4 +207,10 @@ __host__ __device__ __forceinline__ int64_t xcd_block_row(unsigned block) {
   else return (int64_t)block;
 }
 
+// First row of workgroup `block` in the aligned one-workgroup-per-row kernels, whose launch code
+// decides per call whether the rows go out in XCD blocks (host::flat_rows in launch_util.h).
+__device__ __forceinline__ int64_t flat_first_row(unsigned block, int xcd_blocks) {
+  return xcd_blocks ? xcd_block_row(block) : (int64_t)block;
+}
+
 }  // namespace rms

@@ -151,6 +151,20 @@ static void check_grids() {
     const int64_t g = rms::host::flat_grid(M, 1 << 20);
     CHECK(g % 64 == 0 && g >= (M < (1 << 20) ? M : (1 << 20)) && g < M + 64 && g <= (1 << 20), "flat_grid %lld -> %lld", (long long)M, (long long)g);
   }
+  // flat_rows: XCD blocks (and then a grid of a multiple of 64) for workgroups of 256 threads and
+  // more on rows of 8 to 64 KiB only; everything else keeps one row per workgroup index.
+  for (int threads : {64, 128, 256, 512, 1024}) {
+    for (int64_t row_bytes : {16, 4096, 8176, 8192, 16384, 64000, 65536, 65552, 131072}) {
+      for (int64_t M : {1, 63, 64, 65, 8192, (1 << 20) + 77}) {
+        const rms::host::FlatRows r = rms::host::flat_rows(M, 1 << 20, threads, row_bytes);
+        const bool want = threads >= 256 && row_bytes >= 8192 && row_bytes <= 65536;
+        const int64_t capped = M < (1 << 20) ? M : (1 << 20);
+        CHECK(r.xcd_blocks == (want ? 1 : 0), "flat_rows %d threads, %lld bytes", threads, (long long)row_bytes);
+        CHECK(want ? (r.blocks % 64 == 0 && r.blocks >= capped && r.blocks < capped + 64) : r.blocks == capped,
+              "flat_rows grid %lld for %lld rows", (long long)r.blocks, (long long)M);
+      }
+    }
+  }
   for (int64_t row_bytes : {2050, 8194, 16382, 40962, 114686}) {
     for (int threads : {64, 256, 512, 1024}) {
       for (int64_t M : {1, 100, 511, 512, 1024, 1500, 3000, 8192, 16384, 100000}) {
