@@ -125,7 +125,10 @@ int layernorm_fwd_tuned(const void* x, const void* w, const void* b, void* y, in
  * such rows do not fit in registers (they take the streaming kernel); 1 if it sends them
  * through LDS several rows at a time (LAYERNORM_VARIANT_PACKED: rows of at most 64 bytes, and
  * short rows that would fill their lane group badly); a negative layernorm_status for bad
- * arguments. */
+ * arguments.  Rows of 1 to 32 KiB that are a multiple of 16 bytes but not of the 128-byte cache
+ * line are dispatched like rows that are not 16-byte aligned (the aligned kernels lose 3 to
+ * 19 % on them): LAYERNORM_VARIANT_PACKED up to 1.75 KiB (1), LAYERNORM_VARIANT_UNALIGNED beyond
+ * (its threads per row); they never take LAYERNORM_VARIANT_QUEUE on the automatic path. */
 int layernorm_auto_threads_per_row(int64_t N, int dtype);
 
 /*

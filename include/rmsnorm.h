@@ -234,6 +234,10 @@ int rmsnorm_queue_plan(int64_t M, int64_t N, int dtype, int* grid, int* shards, 
  * fill their lane group badly), a negative rmsnorm_status for a bad dtype or
  * N <= 0.  Large launches of long rows run RMSNORM_VARIANT_QUEUE with 512
  * threads per row whatever this returns (see rmsnorm_queue_plan).
+ * Rows of more than 256 bytes that are a multiple of 16 bytes but not of the
+ * 128-byte cache line are dispatched like rows that are not 16-byte aligned
+ * (the aligned kernels lose 15 to 40 % on them): RMSNORM_VARIANT_PACKED up to
+ * 2 KiB (1), RMSNORM_VARIANT_UNALIGNED beyond (its threads per row).
  */
 int rmsnorm_auto_threads_per_row(int64_t N, int dtype);
 

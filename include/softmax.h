@@ -99,7 +99,10 @@ int softmax_fwd_tuned(const void* x, void* y, int64_t M, int64_t N, int dtype, v
  * such rows do not fit in registers (they take the streaming kernel); 1 if it sends them
  * through LDS several rows at a time (SOFTMAX_VARIANT_PACKED: rows of at most 64 bytes, and
  * short rows that would fill their lane group badly); a negative softmax_status for bad
- * arguments. */
+ * arguments.  Rows of more than 256 bytes and at most 64 KiB that are a multiple of 16 bytes
+ * but not of the 128-byte cache line are dispatched like rows that are not 16-byte aligned (the
+ * aligned kernels lose 5 to 20 % on them): SOFTMAX_VARIANT_PACKED up to 1.5 KiB (1),
+ * SOFTMAX_VARIANT_UNALIGNED beyond (its threads per row). */
 int softmax_auto_threads_per_row(int64_t N, int dtype);
 
 /* Largest N the register-resident kernels accept for `dtype`; 0 for a bad dtype. */

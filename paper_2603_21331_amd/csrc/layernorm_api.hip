@@ -189,6 +189,7 @@ QueuePlan queue_plan(int64_t nvec, int threads) {
 bool queue_pays(int64_t M, int64_t nvec, int dtype) {
   const int g = queue_threads(M, nvec, dtype);
   if (g == 0 || nvec <= kSmallRowVectors) return false;   // (one wavefront takes rows that short)
+  if ((nvec * 16) % rms::kLineBytes != 0 && nvec * 16 <= 32 * 1024) return false;   // (the element-addressed kernel takes those: off_line_kernel)
   const int64_t bytes = M * nvec * 16;
   const bool packed_slices = dtype != LAYERNORM_DTYPE_FP32 && nvec > 768;
   if (g == 256) return bytes >= ((int64_t)(nvec <= 384 || packed_slices ? 192 : 128) << 20);
@@ -438,6 +439,29 @@ int dispatch_unaligned(const Args& a) {
   return launched ? LAYERNORM_OK : LAYERNORM_ERR_UNSUPPORTED;
 }
 
+// Rows that are a multiple of 16 bytes but not of the 128-byte line cost the aligned kernels 3 to
+// 19 %: every second or every eighth row starts off a line, a wavefront's 1 KiB then touches nine
+// lines instead of eight, and the last line of a row is shared with the next row, which another
+// XCD reads.  From 1 KiB on (below, the lane-group kernels are as often ahead as behind: fp16 rows of
+// 136 elements 25 % slower than through LDS, of 328 elements 6 % faster) such rows go through LDS
+// up to 1.75 KiB (fp16 60000 x 520: 29.5 -> 24.5 us, fp32 65536 x 260: 29.0 -> 24.6) and to the
+// element-addressed kernel beyond, which lays its slots out from the line a row starts in (fp16
+// 65536 x 2040 102.1 -> 95.8 us, 32768 x 3064 91.2 -> 81.9, 8192 x 12280 76.0 -> 70.4, 4096 x 8184
+// 32.2 -> 26.1, 4096 x 16376 61.3 -> 47.5, fp32 16384 x 4092 96.1 -> 87.2), up to 32 KiB: at 64 KiB
+// that kernel's four slots per thread in 1024 threads lose to the aligned one (bf16 2048 x 32760:
+// 60.6 against 53.3 us).  Returns -3, -1 or 0 (the rule does not apply).
+constexpr int64_t kLineRuleMinBytes = 1023;
+constexpr int64_t kLineRulePackedBytes = 1792;
+constexpr int64_t kLineRuleMaxBytes = 32 * 1024;
+
+int off_line_kernel(int64_t N, int dtype) {
+  const int64_t row_bytes = N * elem_bytes(dtype);
+  if (row_bytes % rms::kLineBytes == 0 || row_bytes <= kLineRuleMinBytes || row_bytes > kLineRuleMaxBytes) return 0;
+  if (row_bytes <= kLineRulePackedBytes && packed_can(N)) return -3;
+  if (pick_threads_unaligned(rms::host::whole_pieces(N, elem_bytes(dtype))) != 0) return -1;
+  return 0;
+}
+
 // The caller has checked queue_threads and that the plan is valid.
 template <int DT>
 int dispatch_queue(const Args& a) {
@@ -485,6 +509,7 @@ int run(const void* x, const void* w, const void* b, void* y, int64_t M, int64_t
                        : (packed_can(N) && !only_stores_unaligned(x, w, b, N, dtype)) ? -3
                        : unaligned_fits ? -1 : 0;
       if (vec_ok && threads > 0 && threads < 64 && packed_beats_lanes(nvec, threads)) threads = -3;
+      if (vec_ok && off_line_kernel(N, dtype) != 0) threads = off_line_kernel(N, dtype);
       if (threads == 0 && N < kStreamMaxN) threads = -2;     // too long for registers
       // The work-queue form of the resident kernel where it pays, if this stream has counters.
       if (threads >= 256 && queue_pays(M, nvec, dtype)) {
@@ -567,6 +592,10 @@ int layernorm_auto_threads_per_row(int64_t N, int dtype) {
   const int b = elem_bytes(dtype);
   if (b == 0 || N <= 0) return LAYERNORM_ERR_INVALID_ARG;
   if ((N * b) % 16 != 0) return 0;
+  // rows off the 128-byte lines (see off_line_kernel): through LDS, or the element-addressed kernel
+  const int off_line = off_line_kernel(N, dtype);
+  if (off_line == -3) return 1;
+  if (off_line == -1) return pick_threads_unaligned(rms::host::whole_pieces(N, b));
   const int64_t nvec = N * b / 16;
   const int g = pick_threads(nvec, 8, dtype);
   // the aligned rows that the automatic path sends through LDS instead (see run)

@@ -207,12 +207,37 @@ bool only_stores_unaligned(const void* x, const void* w, int64_t N, int dtype) {
   return aligned16(x) && aligned16(w) && row_bytes % 16 == 0 && row_bytes >= 1024;
 }
 
+// Rows that are a multiple of 16 bytes but not of the 128-byte line: every second or every
+// eighth row starts off a line, the 1 KiB that a wavefront of the aligned kernels loads or
+// stores then touches nine lines instead of eight, and the last line of a row is shared with the
+// next row, which another XCD reads.  Measured, such rows cost the aligned kernels 15 to 40 %
+// (fp16 65536 x 2040: 113 us where 65536 x 2048 takes 80).  The kernels written for rows that are
+// not 16-byte aligned do not care: the element-addressed kernel lays its 16-byte slots out from
+// the line a row starts in, the LDS-staged kernel moves whole tiles.  So beyond 256 bytes (below,
+// packed_beats_lanes has the measured choice) such rows go through LDS up to 2 KiB (64 MiB of
+// fp16 rows of 136 to 1000 elements: 23.3 to 24.4 us against 25.7 to 31.4) and to the
+// element-addressed kernel beyond (fp16 65536 x 2040 113.0 -> 93.7 us, 32768 x 4088
+// 107.0 -> 87.9, 16384 x 8184 105.2 -> 85.9, fp32 16384 x 4092 105.2 -> 85.4, 4096 x 8184
+// 27.5 -> 23.3, bf16 2048 x 50296 87.7 -> 71.2, fp16 1024 x 65528 60.5 -> 48.2), at every length
+// that kernel takes.  0: the rule does not apply.
+constexpr int64_t kLineRuleMinBytes = 256;
+constexpr int64_t kLineRulePackedBytes = 2048;
+
+int off_line_variant(int64_t N, int dtype) {
+  const int64_t row_bytes = N * elem_bytes(dtype);
+  if (row_bytes % rms::kLineBytes == 0 || row_bytes <= kLineRuleMinBytes) return 0;
+  if (row_bytes <= kLineRulePackedBytes && packed_can(N)) return RMSNORM_VARIANT_PACKED;
+  if (pick_threads_unaligned(slots_per_row(N, dtype))) return RMSNORM_VARIANT_UNALIGNED;
+  return 0;
+}
+
 int choose(const void* x, const void* w, const void* y, int64_t N, int dtype) {
   if (!rows_vectorisable(x, w, y, N, dtype)) {
     if (packed_can(N) && !only_stores_unaligned(x, w, N, dtype)) return RMSNORM_VARIANT_PACKED;
     if (pick_threads_unaligned(slots_per_row(N, dtype))) return RMSNORM_VARIANT_UNALIGNED;
     return N < kStreamMaxN ? RMSNORM_VARIANT_STREAM : RMSNORM_VARIANT_GENERIC;
   }
+  if (const int v = off_line_variant(N, dtype)) return v;
   // Rows of at most 64 bytes leave most of the narrowest lane group idle (one to four of its
   // eight lanes hold a vector): the LDS-staged kernel is 1.2 to 2.9 times faster there.
   if (vectors_per_row(N, dtype) <= kPackedAutoVectors) return RMSNORM_VARIANT_PACKED;
@@ -284,6 +309,7 @@ constexpr int64_t kQueueMinBytesShort = (int64_t)320 << 20;  // rows below 16 Ki
 bool queue_pays(int64_t M, int64_t nvec) {
   const int64_t row_bytes = nvec * 16;
   if (!queue_can(M, nvec)) return false;
+  if (row_bytes % rms::kLineBytes != 0) return false;   // (the element-addressed kernel takes those: off_line_variant)
   if (row_bytes < kQueueMinRowBytes) return M * row_bytes >= kQueueMinBytesShort;
   return M * row_bytes >= (row_bytes <= 32 * 1024 ? kQueueMinBytes : kQueueMinBytesLong);
 }
@@ -669,6 +695,7 @@ int rmsnorm_queue_plan(int64_t M, int64_t N, int dtype, int* grid, int* shards, 
 int rmsnorm_auto_threads_for_batch(int64_t M, int64_t N, int dtype) {
   const int g = rmsnorm_auto_threads_per_row(N, dtype);
   if (g < 256 || M < 0) return M < 0 ? RMSNORM_ERR_INVALID_ARG : g;
+  if (off_line_variant(N, dtype) != 0) return g;      // the element-addressed kernel: no batch rule
   return pick_threads_batch(vectors_per_row(N, dtype), M, dtype);
 }
 
@@ -676,6 +703,10 @@ int rmsnorm_auto_threads_per_row(int64_t N, int dtype) {
   const int b = elem_bytes(dtype);
   if (b == 0 || N <= 0) return RMSNORM_ERR_INVALID_ARG;
   if ((N * b) % 16 != 0) return 0;
+  // rows off the 128-byte lines (see off_line_variant): through LDS, or the element-addressed kernel
+  const int off_line = off_line_variant(N, dtype);
+  if (off_line == RMSNORM_VARIANT_PACKED) return 1;
+  if (off_line == RMSNORM_VARIANT_UNALIGNED) return pick_threads_unaligned(slots_per_row(N, dtype));
   const int64_t nvec = vectors_per_row(N, dtype);
   const int g = pick_threads(nvec, 8, dtype);
   // the aligned rows that the automatic path sends through LDS instead (see choose)

@@ -228,6 +228,28 @@ int dispatch_unaligned(const Args& a) {
   return launched ? SOFTMAX_OK : SOFTMAX_ERR_UNSUPPORTED;
 }
 
+// Rows that are a multiple of 16 bytes but not of the 128-byte line cost the aligned kernels 5 to
+// 20 %: every second or every eighth row starts off a line, a wavefront's 1 KiB then touches nine
+// lines instead of eight, and the last line of a row is shared with the next row, which another
+// XCD reads.  Beyond 256 bytes (below, packed_beats_lanes has the measured choice) such rows go
+// through LDS up to 1.5 KiB (64 MiB of fp16 rows of 136 to 520 elements: 22.9 to 23.7 us against
+// 26.2 to 28.8) and to the element-addressed kernel beyond, which lays its slots out from the
+// line a row starts in (fp16 65536 x 2040 101.3 -> 92.5 us, 32768 x 4088 88.1 -> 82.9, 8192 x 12280
+// 70.1 -> 64.4, 131072 x 1000 93.0 -> 84.0, 4096 x 16376 47.1 -> 44.1), up to 64 KiB: beyond, the
+// aligned kernel with 1024 threads is 6 to 14 % ahead again (bf16 2048 x 40952: 66.2 against 73.8
+// us).  Returns -3, -1 or 0 (the rule does not apply).
+constexpr int64_t kLineRuleMinBytes = 256;
+constexpr int64_t kLineRulePackedBytes = 1536;
+constexpr int64_t kLineRuleMaxBytes = 64 * 1024;
+
+int off_line_kernel(int64_t N, int dtype) {
+  const int64_t row_bytes = N * elem_bytes(dtype);
+  if (row_bytes % rms::kLineBytes == 0 || row_bytes <= kLineRuleMinBytes || row_bytes > kLineRuleMaxBytes) return 0;
+  if (row_bytes <= kLineRulePackedBytes && packed_can(N)) return -3;
+  if (pick_threads_unaligned(rms::host::whole_pieces(N, elem_bytes(dtype))) != 0) return -1;
+  return 0;
+}
+
 // threads == 0 means the element-wise kernel, -1 the element-addressed row kernel, -2 the
 // two-pass streaming kernel, -3 the LDS-staged kernel.
 template <int DT>
@@ -260,6 +282,7 @@ int run(const void* x, void* y, int64_t M, int64_t N, int dtype, void* stream, i
                        : (packed_can(N) && !only_stores_unaligned(x, N, dtype)) ? -3
                        : unaligned_fits ? -1 : 0;
       if (vec_ok && threads > 0 && threads < 64 && packed_beats_lanes(nvec, threads)) threads = -3;
+      if (vec_ok && off_line_kernel(N, dtype) != 0) threads = off_line_kernel(N, dtype);
       if (threads == 0 && N < kStreamMaxN) threads = -2;     // too long for registers
       break;
     case SOFTMAX_VARIANT_PACKED:
@@ -326,6 +349,10 @@ int softmax_auto_threads_per_row(int64_t N, int dtype) {
   const int b = elem_bytes(dtype);
   if (b == 0 || N <= 0) return SOFTMAX_ERR_INVALID_ARG;
   if ((N * b) % 16 != 0) return 0;
+  // rows off the 128-byte lines (see off_line_kernel): through LDS, or the element-addressed kernel
+  const int off_line = off_line_kernel(N, dtype);
+  if (off_line == -3) return 1;
+  if (off_line == -1) return pick_threads_unaligned(rms::host::whole_pieces(N, b));
   const int64_t nvec = N * b / 16;
   const int g = pick_threads(nvec, 8);
   // the aligned rows that the automatic path sends through LDS instead (see run)

@@ -155,14 +155,19 @@ def test_automatic_threads_per_row():
     assert auto(40, fp16) == 1 and auto(72, bf16) == 1 and auto(80, fp16) == 1 and auto(96, fp16) == 16
     assert auto(48, bf16) == 8 and auto(24, fp32) == 8
     assert auto(128, fp32) == 32
-    assert auto(200, bf16) == 32
+    assert auto(192, bf16) == 32            # 384 bytes: three whole lines
+    # rows that are a multiple of 16 bytes but not of the 128-byte line, beyond 256 bytes: through
+    # LDS up to 2 KiB (1), then the element-addressed kernel's thread counts
+    assert auto(200, bf16) == 1 and auto(136, fp16) == 1 and auto(1000, fp16) == 1 and auto(260, fp32) == 1
+    assert auto(1032, fp16) == 64 and auto(2040, bf16) == 64 and auto(4088, bf16) == 256 and auto(8184, fp16) == 256
+    assert auto(16392, bf16) == 512 and auto(131064, bf16) == 1024
     assert auto(1024, fp32) == 256 and auto(2048, fp32) == 512 and auto(1020, fp32) == 64
     assert auto(768, fp16) == 64
     assert auto(5120, fp16) == 256
-    assert auto(5632, fp16) == 256 and auto(5640, fp16) == 512
+    assert auto(5632, fp16) == 256 and auto(5696, fp16) == 512
     assert auto(13824, fp16) == 512
     assert auto(8192, fp32) == 512
-    assert auto(16384, bf16) == 512 and auto(16392, bf16) == 1024
+    assert auto(16384, bf16) == 512 and auto(16448, bf16) == 1024
     assert auto(32768, bf16) == 1024
     assert auto(65536, fp16) == 1024
     assert auto(131072, bf16) == 1024
@@ -180,7 +185,19 @@ def test_dispatch_choice_is_visible_without_a_launch():
     assert sel(P, P + 65536, P + 131072, 16, 8192, 2) == binding.RMSNORM_VARIANT_BLOCK
     assert sel(P, P + 65536, P + 131072, 16, 768, 1) == binding.RMSNORM_VARIANT_WAVE
     assert sel(P, P + 65536, P + 131072, 16, 13824, 1) == binding.RMSNORM_VARIANT_BLOCK
-    assert sel(P, P + 65536, P + 131072, 16, 2040, 2) == binding.RMSNORM_VARIANT_WAVE
+    assert sel(P, P + 65536, P + 131072, 16, 1984, 2) == binding.RMSNORM_VARIANT_WAVE
+    # 16-byte aligned rows beyond 256 bytes that are not whole 128-byte lines: through LDS up to
+    # 2 KiB, the element-addressed kernel beyond, also where the work-queue kernel would run
+    assert sel(P, P + 65536, P + 131072, 16, 2040, 2) == binding.RMSNORM_VARIANT_UNALIGNED
+    assert sel(P, P + 65536, P + 131072, 16, 200, 2) == binding.RMSNORM_VARIANT_PACKED
+    assert sel(P, P + 65536, P + 131072, 16, 1000, 1) == binding.RMSNORM_VARIANT_PACKED
+    assert sel(P, P + 65536, P + 131072, 16, 1032, 1) == binding.RMSNORM_VARIANT_UNALIGNED
+    assert sel(P, P + 65536, P + 131072, 16, 260, 0) == binding.RMSNORM_VARIANT_PACKED
+    assert sel(P, P + (1 << 22), P + (1 << 30), 16384, 8184, 2) == binding.RMSNORM_VARIANT_UNALIGNED
+    assert sel(P, P + (1 << 22), P + (1 << 30), 16384, 8192, 2) == binding.RMSNORM_VARIANT_QUEUE
+    assert lib.rmsnorm_queue_plan(16384, 8184, 2, None, None, None, None) == 0
+    assert sel(P, P + 65536, P + 131072, 16, 136, 1) == binding.RMSNORM_VARIANT_PACKED
+    assert sel(P, P + 65536, P + 131072, 16, 120, 1) == binding.RMSNORM_VARIANT_SUBWAVE   # 240 bytes: below the rule
     assert sel(P, P + 65536, P + 131072, 16, 128, 2) == binding.RMSNORM_VARIANT_SUBWAVE
     assert sel(P, P + 65536, P + 131072, 16, 48, 2) == binding.RMSNORM_VARIANT_SUBWAVE
     assert sel(P, P + 65536, P + 131072, 16, 40, 2) == binding.RMSNORM_VARIANT_PACKED   # 5 vectors on 8 lanes
@@ -262,8 +279,11 @@ def test_queue_plan_and_dispatch_threshold():
     assert binding.rmsnorm_queue_plan(6144, 8192, bf16)[0] is True
     assert binding.rmsnorm_queue_plan(32767, 5120, bf16)[0] is False
     assert binding.rmsnorm_queue_plan(32768, 5120, bf16)[0] is True
-    assert binding.rmsnorm_queue_plan(1 << 20, 4104, bf16)[0] is True
-    assert binding.rmsnorm_queue_plan(40000, 4104, bf16)[0] is False
+    assert binding.rmsnorm_queue_plan(1 << 20, 4160, bf16)[0] is True      # 8320 bytes: 65 lines
+    assert binding.rmsnorm_queue_plan(40000, 4160, bf16)[0] is False
+    # rows that are not whole 128-byte lines never: the element-addressed kernel takes those
+    assert binding.rmsnorm_queue_plan(1 << 20, 4104, bf16)[0] is False
+    assert binding.rmsnorm_queue_plan(16384, 8184, bf16)[0] is False
     lib = binding.load()
     plan = lib.rmsnorm_queue_plan
     assert plan(16, 4096, bf16, None, None, None, None) == binding.RMSNORM_ERR_UNSUPPORTED   # 512 vectors

@@ -73,7 +73,12 @@ def test_automatic_threads_per_row():
     assert auto(8, 1) == 1 and auto(32, 2) == 1 and auto(16, 0) == 1 and auto(40, 2) == 1
     assert auto(72, 2) == 1 and auto(80, 1) == 1 and auto(96, 1) == 16 and auto(48, 2) == 8
     assert auto(64, 1) == 8 and auto(128, 2) == 16 and auto(256, 1) == 16 and auto(512, 1) == 32
-    assert auto(264, 1) == 32 and auto(520, 2) == 64
+    assert auto(264, 1) == 32 and auto(576, 2) == 64
+    # rows of 1 to 32 KiB that are a multiple of 16 bytes but not of the 128-byte line: through LDS up
+    # to 1.75 KiB (1), then the element-addressed kernel's thread counts; longer ones as before
+    assert auto(520, 2) == 1 and auto(260, 0) == 1 and auto(888, 1) == 1 and auto(904, 1) == 64
+    assert auto(2056, 1) == 256 and auto(8200, 2) == 256 and auto(1028, 0) == 256 and auto(16376, 1) == 256
+    assert auto(16392, 1) == 1024
     assert auto(32, 0) == 8 and auto(64, 0) == 16 and auto(96, 0) == 16 and auto(128, 0) == 32
     assert auto(192, 0) == 32 and auto(256, 0) == 64
     # past one wavefront: the smallest workgroup whose threads hold at most 24 elements of a

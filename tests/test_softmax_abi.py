@@ -77,13 +77,19 @@ def test_automatic_threads_per_row():
     assert auto(8, 1) == 1 and auto(32, 2) == 1 and auto(16, 0) == 1 and auto(40, 2) == 1
     assert auto(72, 2) == 1 and auto(80, 1) == 1 and auto(96, 1) == 16 and auto(48, 2) == 8
     assert auto(64, 1) == 8 and auto(128, 2) == 16 and auto(256, 1) == 32 and auto(512, 1) == 64
-    assert auto(192, 1) == 16 and auto(200, 1) == 32 and auto(384, 2) == 32 and auto(392, 2) == 64
-    assert auto(96, 0) == 16 and auto(100, 0) == 32 and auto(192, 0) == 32 and auto(196, 0) == 64
+    assert auto(192, 1) == 16 and auto(256, 1) == 32 and auto(384, 2) == 32 and auto(448, 2) == 64
+    assert auto(96, 0) == 16 and auto(128, 0) == 32 and auto(192, 0) == 32 and auto(224, 0) == 64
     assert auto(2048, 2) == 64 and auto(4096, 1) == 256 and auto(5632, 1) == 256
-    assert auto(5640, 1) == 512 and auto(8192, 1) == 512 and auto(8200, 1) == 256 and auto(4096, 0) == 512
-    assert auto(16384, 2) == 256 and auto(16392, 2) == 1024 and auto(32768, 1) == 1024 and auto(65536, 2) == 1024
+    assert auto(5696, 1) == 512 and auto(8192, 1) == 512 and auto(4096, 0) == 512
+    assert auto(16384, 2) == 256 and auto(16448, 2) == 1024 and auto(32768, 1) == 1024 and auto(65536, 2) == 1024
     assert auto(65544, 2) == 0 and auto(1023, 1) == 0
-    assert auto(8192, 0) == 256 and auto(8196, 0) == 1024 and auto(32768, 0) == 1024 and auto(32772, 0) == 0
+    assert auto(8192, 0) == 256 and auto(8224, 0) == 1024 and auto(32768, 0) == 1024 and auto(32772, 0) == 0
+    # rows of 256 bytes to 64 KiB that are a multiple of 16 bytes but not of the 128-byte line: through
+    # LDS up to 1.5 KiB (1), then the element-addressed kernel's thread counts; longer ones as before
+    assert auto(200, 1) == 1 and auto(392, 2) == 1 and auto(100, 0) == 1 and auto(760, 1) == 1
+    assert auto(776, 1) == 64 and auto(2040, 1) == 64 and auto(5640, 1) == 256 and auto(8200, 1) == 256
+    assert auto(16392, 2) == 512 and auto(8196, 0) == 512 and auto(32760, 2) == 512
+    assert auto(32776, 2) == 1024 and auto(40952, 2) == 1024
     assert softmax.softmax_register_max_n(1) == 65536 and softmax.softmax_register_max_n(0) == 32768
     with pytest.raises(softmax.SoftmaxError):
         auto(0, 1)
