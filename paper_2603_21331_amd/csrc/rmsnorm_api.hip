@@ -238,6 +238,14 @@ int choose(const void* x, const void* w, const void* y, int64_t N, int dtype) {
     return N < kStreamMaxN ? RMSNORM_VARIANT_STREAM : RMSNORM_VARIANT_GENERIC;
   }
   if (const int v = off_line_variant(N, dtype)) return v;
+  // Rows of whole lines written to a y that starts off a line: it is the stores that pay for
+  // straddling (x off a line alone costs nothing measurable; y 16 bytes off: bf16 16384 x 8192
+  // 82.1 -> 94.6 us, 8192 x 4096 22.6 -> 26.7), and the element-addressed kernel, which cuts the
+  // row at the lines of x and stores element-aligned, is ahead from 2 KiB rows on (85.9 and 23.5
+  // us; 65536 x 2048: 98.4 -> 93.9; rows of 1 KiB: 71.0 against 79.5 the other way).
+  if ((reinterpret_cast<uintptr_t>(y) & (rms::kLineBytes - 1)) != 0 && N * elem_bytes(dtype) >= 2048 &&
+      pick_threads_unaligned(slots_per_row(N, dtype)))
+    return RMSNORM_VARIANT_UNALIGNED;
   // Rows of at most 64 bytes leave most of the narrowest lane group idle (one to four of its
   // eight lanes hold a vector): the LDS-staged kernel is 1.2 to 2.9 times faster there.
   if (vectors_per_row(N, dtype) <= kPackedAutoVectors) return RMSNORM_VARIANT_PACKED;
