@@ -235,7 +235,7 @@ softmax_packed_kernel(const void* x, void* y, int64_t M, int N, int tile_rows) {
   int rows = 0;
   const char* src = nullptr;
   TileCut cut = {};
-  int64_t r0 = (int64_t)blockIdx.x * tile_rows;
+  int64_t r0 = packed_first_tile(blockIdx.x, gridDim.x) * tile_rows;
   if (r0 < M) {
     cut = run_of(r0, rows, src);
     tile_request<DT, NT>(src, cut, t, regs);
