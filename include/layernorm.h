@@ -128,7 +128,8 @@ int layernorm_fwd_tuned(const void* x, const void* w, const void* b, void* y, in
  * arguments.  Rows of 1 to 32 KiB that are a multiple of 16 bytes but not of the 128-byte cache
  * line are dispatched like rows that are not 16-byte aligned (the aligned kernels lose 3 to
  * 19 % on them): LAYERNORM_VARIANT_PACKED up to 1.75 KiB (1), LAYERNORM_VARIANT_UNALIGNED beyond
- * (its threads per row); they never take LAYERNORM_VARIANT_QUEUE on the automatic path. */
+ * (its threads per row; those never take LAYERNORM_VARIANT_QUEUE on the automatic path) unless
+ * the row is a multiple of 64 bytes. */
 int layernorm_auto_threads_per_row(int64_t N, int dtype);
 
 /*

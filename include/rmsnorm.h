@@ -237,7 +237,10 @@ int rmsnorm_queue_plan(int64_t M, int64_t N, int dtype, int* grid, int* shards, 
  * Rows of more than 256 bytes that are a multiple of 16 bytes but not of the
  * 128-byte cache line are dispatched like rows that are not 16-byte aligned
  * (the aligned kernels lose 15 to 40 % on them): RMSNORM_VARIANT_PACKED up to
- * 2 KiB (1), RMSNORM_VARIANT_UNALIGNED beyond (its threads per row).
+ * 2 KiB (1), RMSNORM_VARIANT_UNALIGNED beyond (its threads per row) unless the
+ * row is a multiple of 64 bytes.  So are rows of 2 KiB and more of whole lines
+ * when y is not 64-byte aligned (RMSNORM_VARIANT_UNALIGNED; see
+ * rmsnorm_select_variant, which looks at the pointers).
  */
 int rmsnorm_auto_threads_per_row(int64_t N, int dtype);
 

@@ -227,7 +227,10 @@ int off_line_variant(int64_t N, int dtype) {
   const int64_t row_bytes = N * elem_bytes(dtype);
   if (row_bytes % rms::kLineBytes == 0 || row_bytes <= kLineRuleMinBytes) return 0;
   if (row_bytes <= kLineRulePackedBytes && packed_can(N)) return RMSNORM_VARIANT_PACKED;
-  if (pick_threads_unaligned(slots_per_row(N, dtype))) return RMSNORM_VARIANT_UNALIGNED;
+  // (rows of whole half lines keep the aligned kernels beyond that: what costs those most is their
+  // stores' write-through policy, which works on 64-byte pieces; fp16 65536 x 2080 92.4 us against
+  // 96.7 in the element-addressed kernel, 32768 x 4128 92.5 against 89.2)
+  if (row_bytes % 64 != 0 && pick_threads_unaligned(slots_per_row(N, dtype))) return RMSNORM_VARIANT_UNALIGNED;
   return 0;
 }
 
@@ -238,12 +241,13 @@ int choose(const void* x, const void* w, const void* y, int64_t N, int dtype) {
     return N < kStreamMaxN ? RMSNORM_VARIANT_STREAM : RMSNORM_VARIANT_GENERIC;
   }
   if (const int v = off_line_variant(N, dtype)) return v;
-  // Rows of whole lines written to a y that starts off a line: it is the stores that pay for
-  // straddling (x off a line alone costs nothing measurable; y 16 bytes off: bf16 16384 x 8192
-  // 82.1 -> 94.6 us, 8192 x 4096 22.6 -> 26.7), and the element-addressed kernel, which cuts the
-  // row at the lines of x and stores element-aligned, is ahead from 2 KiB rows on (85.9 and 23.5
-  // us; 65536 x 2048: 98.4 -> 93.9; rows of 1 KiB: 71.0 against 79.5 the other way).
-  if ((reinterpret_cast<uintptr_t>(y) & (rms::kLineBytes - 1)) != 0 && N * elem_bytes(dtype) >= 2048 &&
+  // Rows of whole lines written to a y that starts off the 64-byte pieces of the lines: it is the
+  // stores that pay for straddling (x off a line alone costs nothing measurable, nor does a y 64
+  // bytes off; y 16 bytes off: bf16 16384 x 8192 82.1 -> 94.6 us, 8192 x 4096 22.6 -> 26.7), and the
+  // element-addressed kernel, which cuts the row at the lines of x and stores element-aligned, is
+  // ahead from 2 KiB rows on (85.9 and 23.5 us; 65536 x 2048: 98.4 -> 93.9; rows of 1 KiB: 71.0
+  // against 79.5 the other way).
+  if ((reinterpret_cast<uintptr_t>(y) & 63u) != 0 && N * elem_bytes(dtype) >= 2048 &&
       pick_threads_unaligned(slots_per_row(N, dtype)))
     return RMSNORM_VARIANT_UNALIGNED;
   // Rows of at most 64 bytes leave most of the narrowest lane group idle (one to four of its
@@ -317,7 +321,7 @@ constexpr int64_t kQueueMinBytesShort = (int64_t)320 << 20;  // rows below 16 Ki
 bool queue_pays(int64_t M, int64_t nvec) {
   const int64_t row_bytes = nvec * 16;
   if (!queue_can(M, nvec)) return false;
-  if (row_bytes % rms::kLineBytes != 0) return false;   // (the element-addressed kernel takes those: off_line_variant)
+  if (row_bytes % 64 != 0) return false;   // (the element-addressed kernel takes those: off_line_variant)
   if (row_bytes < kQueueMinRowBytes) return M * row_bytes >= kQueueMinBytesShort;
   return M * row_bytes >= (row_bytes <= 32 * 1024 ? kQueueMinBytes : kQueueMinBytesLong);
 }

@@ -197,11 +197,17 @@ def test_dispatch_choice_is_visible_without_a_launch():
     assert sel(P, P + (1 << 22), P + (1 << 30), 16384, 8192, 2) == binding.RMSNORM_VARIANT_QUEUE
     assert lib.rmsnorm_queue_plan(16384, 8184, 2, None, None, None, None) == 0
     assert sel(P, P + 65536, P + 131072, 16, 136, 1) == binding.RMSNORM_VARIANT_PACKED
-    # whole-line rows of 2 KiB and more written to a y that starts off a line: element-addressed too
+    # whole-line rows of 2 KiB and more written to a y that starts off the 64-byte pieces of the
+    # lines: element-addressed too
     assert sel(P, P + (1 << 22), P + (1 << 30) + 16, 16384, 8192, 2) == binding.RMSNORM_VARIANT_UNALIGNED
     assert sel(P + 16, P + (1 << 22), P + (1 << 30), 16384, 8192, 2) == binding.RMSNORM_VARIANT_QUEUE
-    assert sel(P, P + (1 << 22), P + (1 << 30) + 64, 16, 1024, 2) == binding.RMSNORM_VARIANT_UNALIGNED
-    assert sel(P, P + (1 << 22), P + (1 << 30) + 64, 16, 512, 2) == binding.RMSNORM_VARIANT_WAVE
+    assert sel(P, P + (1 << 22), P + (1 << 30) + 64, 16384, 8192, 2) == binding.RMSNORM_VARIANT_QUEUE
+    assert sel(P, P + (1 << 22), P + (1 << 30) + 48, 16, 1024, 2) == binding.RMSNORM_VARIANT_UNALIGNED
+    assert sel(P, P + (1 << 22), P + (1 << 30) + 48, 16, 512, 2) == binding.RMSNORM_VARIANT_WAVE
+    # rows of whole half lines: through LDS while short, the aligned kernels beyond
+    assert sel(P, P + 65536, P + 131072, 16, 544, 1) == binding.RMSNORM_VARIANT_PACKED
+    assert sel(P, P + 65536, P + 131072, 16, 2080, 1) == binding.RMSNORM_VARIANT_BLOCK
+    assert sel(P, P + 65536, P + 131072, 16, 2072, 1) == binding.RMSNORM_VARIANT_UNALIGNED
     assert sel(P, P + 65536, P + 131072, 16, 120, 1) == binding.RMSNORM_VARIANT_SUBWAVE   # 240 bytes: below the rule
     assert sel(P, P + 65536, P + 131072, 16, 128, 2) == binding.RMSNORM_VARIANT_SUBWAVE
     assert sel(P, P + 65536, P + 131072, 16, 48, 2) == binding.RMSNORM_VARIANT_SUBWAVE

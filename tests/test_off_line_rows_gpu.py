@@ -33,6 +33,8 @@ CASES = [
     (inputs.BF16, 700, 8184, UNALIGNED, UNALIGNED, UNALIGNED),   # enough rows for the walking forms
     (inputs.FP16, 65, 16376, UNALIGNED, UNALIGNED, UNALIGNED),   # 32752 bytes
     (inputs.BF16, 33, 16392, UNALIGNED, UNALIGNED, None),        # 32784 bytes: past LayerNorm's 32 KiB
+    (inputs.FP16, 300, 544, PACKED, PACKED, PACKED),             # 1088 bytes: whole half lines, short
+    (inputs.FP16, 200, 2080, None, UNALIGNED, None),             # 4160 bytes: whole half lines; only softmax moves
     (inputs.BF16, 17, 32776, UNALIGNED, None, None),             # 65552 bytes: past softmax's 64 KiB
 ]
 RMS_VARIANT = {PACKED: binding.RMSNORM_VARIANT_PACKED, UNALIGNED: binding.RMSNORM_VARIANT_UNALIGNED}
