@@ -516,8 +516,6 @@ __global__ void __launch_bounds__(G + kLnWave, PACKED ? 4 : 1)   // PACKED: at m
 layernorm_queue_kernel(const u32x4* x, const u32x4* __restrict__ w, const u32x4* __restrict__ b,
                        u32x4* y, int64_t M, int nvec, float inv_n, float eps, unsigned* counters,
                        int shards, int block_shift) {
-  using S = Storage<DT>;
-  constexpr int VEC = S::kVec;
   constexpr int WAVES = G / kLnWave;
   __shared__ __attribute__((aligned(16))) float part_a[2][WAVES];
   __shared__ __attribute__((aligned(16))) float part_b[2][WAVES];
