@@ -100,3 +100,19 @@ def test_layernorm(gpu_device, dtype, M, N, rms, sm, ln):
     if ln:
         forced = H.to_host(layernorm.layernorm_fwd_variant(xd, wd, bd, EPS, LN_VARIANT[ln]), dtype)
         assert np.array_equal(got, forced), "the automatic path did not run the variant the rule names"
+
+
+@pytest.mark.parametrize("dtype,M,N", [(inputs.BF16, 300, 520), (inputs.FP16, 257, 1032), (inputs.FP16, 700, 8184)])
+def test_in_place(gpu_device, dtype, M, N):
+    """y == x through the automatic path on rows the rule moves: the bits of the out-of-place call."""
+    case = inputs.layernorm_case(6, 2300 + N % 97, M, N, dtype, mean=0.2, std=1.1)
+    xd, wd, bd = (H.to_device(case[k], dtype, gpu_device) for k in ("x", "w", "b"))
+    H.say(f"off-line rows in place {inputs.DTYPE_NAMES[dtype]} {M}x{N}")
+    for name, call in (("rmsnorm", lambda src, dst: binding.rmsnorm_fwd(src, wd, EPS, dst)),
+                       ("softmax", lambda src, dst: softmax.softmax_fwd(src, dst)),
+                       ("layernorm", lambda src, dst: layernorm.layernorm_fwd(src, wd, bd, EPS, dst))):
+        want = H.to_host(call(xd, torch.empty_like(xd)), dtype)
+        work = xd.clone()
+        call(work, work)
+        torch.cuda.synchronize()
+        assert np.array_equal(H.to_host(work, dtype), want), name
