@@ -3,7 +3,8 @@ path of RMSNorm, softmax and LayerNorm, against the CPU oracle element by elemen
 from 1 to 20000 (log-uniform, so that every kernel family is hit), batches of 1 to 3000 rows
 (capped so that the oracle stays fast), x, w, b and y each at its own offset of 0 to 70 elements
 from a 256-byte boundary (so rows start anywhere relative to the 16-byte boundaries and the
-128-byte lines, and y need not share x's offset), guard zones around y."""
+128-byte lines, and y need not share x's offset), guard zones around y; and a second set whose
+rows and offsets are all multiples of 16 bytes."""
 import numpy as np
 import pytest
 import torch
@@ -17,11 +18,23 @@ from paper_2603_21331_amd import binding, inputs, layernorm, softmax
 pytestmark = pytest.mark.gpu
 
 CASES = 48
+ALIGNED_CASES = 36      # cases CASES .. CASES + ALIGNED_CASES - 1, see draw
 
 
 def draw(k: int):
     rng = np.random.default_rng(7000 + k)
     dtype = [inputs.FP32, inputs.FP16, inputs.BF16][k % 3]
+    if k >= CASES:
+        # Rows and pointers that are multiples of 16 bytes, mostly not of the 128-byte line and
+        # often not of its 64-byte halves: the vector kernels can take them, and the automatic
+        # path decides by the lines which of them does.  All offsets a multiple of 16 bytes.
+        per16 = 16 // inputs.DTYPE_BYTES[dtype]
+        N = per16 * int(np.exp(rng.uniform(0.0, np.log(20000.0 / per16))))
+        M = int(min(3000, max(1, rng.integers(1, 3001)), max(1, 3_000_000 // N)))
+        offs = [per16 * int(o) for o in rng.integers(0, 9, size=4)]
+        if k % 3 == 0:
+            offs = [0, 0, 0, 0]
+        return dtype, M, N, offs
     N = int(np.exp(rng.uniform(0.0, np.log(20000.0))))
     if k % 4 == 0:
         N = max(1, N // 8 * 8 + int(rng.integers(-1, 2)))     # next to a multiple of 16 bytes
@@ -41,7 +54,7 @@ def placed(a, dtype, device, off, shape):
     return view
 
 
-@pytest.mark.parametrize("k", range(CASES))
+@pytest.mark.parametrize("k", range(CASES + ALIGNED_CASES))
 def test_random_shape_and_offsets(gpu_device, k):
     dtype, M, N, (ox, ow, ob, oy) = draw(k)
     case = inputs.layernorm_case(11, 2000 + 4 * k, M, N, dtype, 1e-5, mean=0.25, std=1.5)
