@@ -22,9 +22,11 @@
 // Same variants as the other row kernels: 8/16/32 lanes per row for rows up to
 // 1 KiB, one wavefront per row, one workgroup of 256..1024 threads per row (two
 // LDS reductions, two barriers per row) either launched per row or, for rows of
-// at most 24 elements per thread, resident with weight and bias in registers, and
-// an element-wise three-pass fallback.  Fixed reduction order, no atomics:
-// bit-identical from run to run.
+// at most 24 elements per thread, resident with weight and bias in registers
+// (walking a fixed stride, or in large launches drawing its rows from counters:
+// layernorm_queue_kernel), and an element-wise three-pass fallback.  Fixed
+// reduction order within a row, and a row's result does not depend on which
+// workgroup takes it: bit-identical from run to run.
 #pragma once
 
 #include "vec_io.h"
